@@ -1,0 +1,160 @@
+/*
+ * libcomet -- error-bounded lossy compression of convolution activations for
+ * memory-efficient CNN training (COMET), native HIP for gfx950 (MI355X).
+ *
+ * The codec is the paper's "modified cuSZ" (Sec. 3.4, Sec. 4.1): quantise the
+ * fp32 activations against an absolute error bound eb, predict every point from
+ * its neighbours (2-D Lorenzo over each H x W plane), turn the residual into an
+ * integer quantisation code, Huffman-code the codes; on decompression undo the
+ * steps and re-zero every value that lies within eb of zero.  The error-bounded
+ * mode guarantees |x - xhat| <= eb for every element (Sec. 2.2).
+ *
+ * Conventions for every entry point
+ *   - "dev" pointers are device memory on the current HIP device, owned by the
+ *     caller; "host" pointers are ordinary host memory.  Nothing is allocated
+ *     per call: all scratch lives in the comet_ctx.
+ *   - Tensors are fp32, NCHW, contiguous.  N*C*H*W must be in [1, 2^31) and
+ *     W <= 8192.
+ *   - All device work is enqueued on `stream` (a hipStream_t passed as void*;
+ *     NULL is the default stream).  A context must not be used by two calls
+ *     that can overlap in time; use one context per stream.
+ *   - Return value: COMET_OK or a negative COMET_ERR_* code.  Conditions that
+ *     are only known on the device (container too small, malformed container)
+ *     are latched in the context and reported by the next synchronising call
+ *     (comet_compress with bytes_out != NULL, or comet_sync).
+ *   - NaN / Inf / huge inputs are not errors: they are stored verbatim and come
+ *     back bit-identical.
+ */
+#ifndef COMET_H
+#define COMET_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define COMET_OK 0
+#define COMET_ERR_INVALID (-1)     /* bad argument (null pointer, zero dimension, eb or nbins out of range, ...) */
+#define COMET_ERR_CAPACITY (-2)    /* the container does not fit the caller's buffer */
+#define COMET_ERR_FORMAT (-3)      /* not a valid container / does not match the shape passed */
+#define COMET_ERR_HIP (-4)         /* a HIP runtime call failed; see comet_strerror */
+#define COMET_ERR_NOMEM (-5)       /* workspace allocation failed / context too small for the request */
+#define COMET_ERR_INTERNAL (-6)    /* a device-side safety net tripped (should not happen) */
+
+#define COMET_HEADER_BYTES 128u
+#define COMET_DEFAULT_CHUNK_SYMS 128u
+
+typedef struct comet_ctx comet_ctx;                     /* opaque; owns the device workspace */
+typedef struct { uint32_t n, c, h, w; } comet_shape;    /* NCHW */
+
+/* Header of a container, as returned by comet_peek (host copy). */
+typedef struct {
+    comet_shape shape;
+    uint32_t nbins, chunk_syms, n_chunks, n_active, max_len, n_outlier_records, n_value_records;
+    float eb;
+    uint64_t nnz;            /* number of non-zero input elements (R of Sec. 4.2 = nnz / elements) */
+    uint64_t payload_words, total_bytes;
+} comet_info;
+
+/* Create a context able to handle tensors of up to max_elems elements and
+ * max_nbins quantisation bins.  Allocates 2 bytes per element plus a few MB of
+ * device workspace on the current device.  *ctx is set on success. */
+int comet_create(comet_ctx **ctx, uint64_t max_elems, uint32_t max_nbins);
+void comet_destroy(comet_ctx *ctx);
+
+/* Symbols per Huffman chunk for subsequent comet_compress calls: 64, 128
+ * (default) or 256.  Stored in the container; the decompressor reads it there. */
+int comet_set_chunk_syms(comet_ctx *ctx, uint32_t chunk_syms);
+
+/* Worst-case container size in bytes for a shape (every element an outlier and
+ * stored verbatim); 0 if the arguments are invalid.  Realistic activations need
+ * a small fraction of it; callers that pass less rely on COMET_ERR_CAPACITY,
+ * the paper's "unexpectedly low compression ratio" case (Sec. 3.4). */
+uint64_t comet_compress_bound(comet_shape shape, uint32_t nbins, uint32_t chunk_syms);
+
+/* Compress one activation tensor right after its layer's forward pass
+ * (Sec. 3.4): dev_in (fp32, read-only) -> container at dev_out (16-byte
+ * aligned, `capacity` bytes).  eb: absolute error bound, finite, in
+ * [2^-100, 2^100].  nbins: even, in [4, 65536]; residuals outside
+ * (-nbins/2, nbins/2) are stored as outliers.
+ * bytes_out != NULL: the call synchronises `stream`, stores the container size
+ * and returns any device-side error (COMET_ERR_CAPACITY leaves the buffer
+ * contents undefined but never writes past capacity).
+ * bytes_out == NULL: fully asynchronous; the size is in the container header
+ * (comet_peek) and errors are reported by comet_sync. */
+int comet_compress(comet_ctx *ctx, const float *dev_in, comet_shape shape, float eb, uint32_t nbins,
+                   void *stream, void *dev_out, uint64_t capacity, uint64_t *bytes_out);
+
+/* Decompress a container for the backward pass (Sec. 3.4): dev_in (`bytes`
+ * bytes, 16-byte aligned) -> dev_out (fp32, shape.n*c*h*w elements).  `shape`
+ * is the shape the caller compressed; it sizes the launch and is checked on
+ * the device against the header.  Asynchronous; a malformed container is
+ * reported by comet_sync (the output is then undefined, never out of bounds). */
+int comet_decompress(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_shape shape,
+                     void *stream, float *dev_out);
+
+/* Wait for `stream` and return (then clear) the first device-side error latched
+ * in the context since the last synchronising call. */
+int comet_sync(comet_ctx *ctx, void *stream);
+
+/* Read and validate a container's header (synchronises `stream`). */
+int comet_peek(comet_ctx *ctx, const void *dev_in, uint64_t bytes, void *stream, comet_info *info);
+
+/* Adaptive error bound (Sec. 3.2, 3.3): sigma = sigma_frac * momentum_abs_mean;
+ * eb = sigma / (a * loss_grad_mean * sqrt(batch * nonzero_ratio)), evaluated in
+ * fp64 on the host, rounded to fp32, clamped to [eb_min, eb_max].  The paper's
+ * constants are a = 0.32 (Sec. 5.2) and sigma_frac = 0.01 (Sec. 3.2).
+ * loss_grad_mean == 0 or nonzero_ratio == 0 returns eb_max. */
+typedef struct { double momentum_abs_mean, loss_grad_mean, nonzero_ratio; uint32_t batch; } comet_layer_stats;
+typedef struct { double a, sigma_frac; float eb_min, eb_max; } comet_adapt_cfg;
+void comet_adapt_defaults(comet_adapt_cfg *cfg);   /* 0.32, 0.01, 2^-100, 2^100 */
+int comet_adapt_eb(const comet_layer_stats *stats, const comet_adapt_cfg *cfg /* NULL = defaults */, float *eb_out /* host */);
+
+/* ---- stage-level entry points: each runs one step of the pipeline alone so
+ * ---- that it can be compared with the reference implementation ------------ */
+
+/* Sec. 4.1 steps 1-3 fused: prequantise, Lorenzo-predict, emit codes, count the
+ * histogram and compact the outlier records.
+ * dev_codes: u16[elements]; dev_hist: u32[nbins]; dev_records: u32[2*rec_capacity]
+ * (key, payload) pairs in ascending key order, key = 2*index + type (type 0: the
+ * payload is the int32 residual of an escaped code, type 1: the fp32 bit pattern
+ * of an element stored verbatim); dev_counts: u64[3] = records, value records,
+ * non-zero inputs. */
+int comet_stage_quantize(comet_ctx *ctx, const float *dev_in, comet_shape shape, float eb, uint32_t nbins,
+                         void *stream, uint16_t *dev_codes, uint32_t *dev_hist,
+                         uint32_t *dev_records, uint64_t rec_capacity, uint64_t *dev_counts);
+
+/* Huffman code lengths (two-queue construction, leaf before internal node on
+ * equal weight, leaves ordered by (frequency, symbol)) and canonical codes.
+ * dev_hist: u32[nbins]; dev_len: u8[nbins]; dev_code: u64[nbins] (may be NULL).
+ * The context keeps the table for a following comet_stage_encode. */
+int comet_stage_codebook(comet_ctx *ctx, const uint32_t *dev_hist, uint32_t nbins, void *stream,
+                         uint8_t *dev_len, uint64_t *dev_code);
+
+/* Chunked Huffman encode with the table of the last comet_stage_codebook on
+ * this context.  dev_chunk_off: u32[ceil(n/chunk_syms)] word offset of every
+ * chunk; dev_payload: u32[payload_capacity_words]; dev_payload_words: u64[1]. */
+int comet_stage_encode(comet_ctx *ctx, const uint16_t *dev_codes, uint64_t n, uint32_t nbins, uint32_t chunk_syms,
+                       void *stream, uint32_t *dev_chunk_off, uint32_t *dev_payload,
+                       uint64_t payload_capacity_words, uint64_t *dev_payload_words);
+
+/* Chunk-parallel Huffman decode from a length table. dev_codes_out: u16[n]. */
+int comet_stage_decode(comet_ctx *ctx, const uint8_t *dev_len, uint32_t nbins,
+                       const uint32_t *dev_chunk_off, const uint32_t *dev_payload, uint64_t payload_words,
+                       uint64_t n, uint32_t chunk_syms, void *stream, uint16_t *dev_codes_out);
+
+/* Lorenzo reconstruction (plane-wise 2-D prefix sums), dequantisation, verbatim
+ * values and the re-zero filter of Sec. 3.4, from a code array and records. */
+int comet_stage_reconstruct(comet_ctx *ctx, const uint16_t *dev_codes, const uint32_t *dev_records, uint64_t n_records,
+                            comet_shape shape, uint32_t nbins, float eb, void *stream, float *dev_out);
+
+/* Text for a COMET_ERR_* code; for COMET_ERR_HIP the last HIP error string seen
+ * by this thread.  Never NULL. */
+const char *comet_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COMET_H */

@@ -1,0 +1,540 @@
+// Host side of libcomet: context / workspace, argument checks, launch geometry
+// and the extern "C" entry points declared in include/comet.h.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "../../include/comet.h"
+#include "comet_kernels.h"
+
+using namespace comet;
+
+namespace {
+
+thread_local char g_hip_msg[256] = "no HIP error recorded";
+
+int hip_fail(hipError_t e, const char *what) {
+    snprintf(g_hip_msg, sizeof(g_hip_msg), "%s: %s", what, hipGetErrorString(e));
+    return COMET_ERR_HIP;
+}
+#define HIP_TRY(expr)                                                   \
+    do {                                                                \
+        hipError_t e_ = (expr);                                         \
+        if (e_ != hipSuccess) return hip_fail(e_, #expr);               \
+    } while (0)
+
+constexpr uint64_t kMaxElems = (1ull << 31) - 1ull;
+constexpr uint32_t kMaxW = 8192;
+constexpr uint32_t kMaxBins = 65536;
+
+inline uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+
+bool valid_eb(float eb) { return std::isfinite(eb) && eb >= 0x1p-100f && eb <= 0x1p100f; }
+bool valid_nbins(uint32_t nb) { return nb >= 4u && nb <= kMaxBins && (nb & 1u) == 0u; }
+bool valid_chunk(uint32_t s) { return s == 64u || s == 128u || s == 256u; }
+
+bool shape_elems(comet_shape s, uint64_t *n) {
+    if (!s.n || !s.c || !s.h || !s.w) return false;
+    const uint64_t a = (uint64_t)s.n * s.c, b = (uint64_t)s.h * s.w;
+    if (a > kMaxElems || b > kMaxElems) return false;
+    const uint64_t t = a * b;
+    if (t > kMaxElems) return false;
+    *n = t;
+    return true;
+}
+
+uint32_t ilog2(uint32_t v) { uint32_t l = 0; while ((1u << l) < v) ++l; return l; }
+
+}  // namespace
+
+// Persistent device words followed by the per-call control block.
+struct DevState {
+    uint32_t latched;      // first-come device errors since the last synchronising call
+    uint32_t pad[3];
+    Control ctl;
+};
+
+struct comet_ctx {
+    int device = 0;
+    int num_cu = 0;
+    uint64_t max_elems = 0;
+    uint32_t max_nbins = 0;
+    uint32_t chunk_syms = COMET_DEFAULT_CHUNK_SYMS;
+    // device memory
+    DevState *state = nullptr;       // latched + Control, then histogram + descriptors (zero region)
+    uint8_t *zero_region = nullptr;  // == (uint8_t*)&state->ctl
+    uint64_t zero_cap = 0;
+    uint16_t *codes = nullptr;
+    uint64_t *enc = nullptr;
+    BookScratch book{};
+    DecodeTables tables{};
+    void *tables_blob = nullptr;
+    // pinned host
+    DevState *host_state = nullptr;
+    Header *host_hdr = nullptr;
+    // occupancy (workgroups per CU) measured once
+    int occ_quant = 1, occ_enc = 1, occ_dec0 = 1, occ_dec1 = 1;
+};
+
+namespace {
+
+struct ZeroLayout {          // sub-allocation of the zero region for one call
+    uint64_t off_hist, off_desc_q, off_desc_e, bytes;
+};
+
+ZeroLayout zero_layout(uint32_t nbins, uint64_t tiles_q, uint64_t tiles_e) {
+    ZeroLayout z;
+    uint64_t o = align_up(sizeof(Control), 256);
+    z.off_desc_q = o; o += align_up(8 * tiles_q, 256);
+    z.off_desc_e = o; o += align_up(8 * tiles_e, 256);
+    z.off_hist = o; o += align_up(4ull * nbins, 256);
+    z.bytes = o;
+    return z;
+}
+
+int status_to_error(uint32_t st) {
+    if (st & ST_INTERNAL) return COMET_ERR_INTERNAL;
+    if (st & ST_FORMAT) return COMET_ERR_FORMAT;
+    if (st & ST_CAPACITY) return COMET_ERR_CAPACITY;
+    return COMET_OK;
+}
+
+__global__ void k_latch(DevState *s) {           // fold this call's status into the persistent word
+    if (s->ctl.status) atomicOr(&s->latched, s->ctl.status);
+}
+
+struct ReconGeometry { uint32_t planes_per_unit, tile_rows, n_units, pitch, use_carry; size_t lds; };
+
+bool recon_geometry(comet_shape s, ReconGeometry *g) {
+    const uint64_t planes = (uint64_t)s.n * s.c;
+    const uint64_t P = (uint64_t)s.h * s.w;
+    g->pitch = s.w | 1u;
+    if (P <= kDecTileElems) {
+        uint64_t G = kDecTileElems / P;
+        if (G > planes) G = planes;
+        g->planes_per_unit = (uint32_t)G;
+        g->tile_rows = (uint32_t)(G * s.h);
+        g->n_units = (uint32_t)((planes + G - 1) / G);
+        g->use_carry = 0;
+    } else {
+        uint32_t R = kDecTileElems / s.w;
+        if (R < 1) R = 1;
+        if (R > s.h) R = s.h;
+        g->planes_per_unit = 1;
+        g->tile_rows = R;
+        g->n_units = (uint32_t)planes;
+        g->use_carry = 1;
+    }
+    g->lds = (size_t)g->tile_rows * g->pitch * 4u + (g->use_carry ? (size_t)s.w * 4u : 0u);
+    return g->lds <= 96u * 1024u;
+}
+
+int launch_quantize(comet_ctx *ctx, const float *x, comet_shape s, uint64_t n, float eb, uint32_t nbins,
+                    hipStream_t st, uint16_t *codes, uint32_t *hist, uint32_t *rec, uint64_t rec_cap,
+                    uint64_t *desc) {
+    QuantArgs a{};
+    a.x = x; a.n = n;
+    a.divW = make_fastdiv(s.w); a.divH = make_fastdiv(s.h);
+    a.eb = eb; a.ebx2 = 2.0f * eb; a.r = (float)(1.0 / (double)a.ebx2);
+    a.radius = (int32_t)(nbins / 2u); a.nbins = nbins;
+    a.win_n = nbins < kHistWindowMax ? nbins : kHistWindowMax;
+    a.win_lo = (nbins - a.win_n) / 2u;
+    a.n_tiles = (uint32_t)((n + kQuantTile - 1) / kQuantTile);
+    a.codes = codes; a.hist = hist; a.rec = rec; a.rec_cap = rec_cap; a.desc = desc; a.ctl = &ctx->state->ctl;
+    uint32_t grid = (uint32_t)ctx->num_cu * (uint32_t)ctx->occ_quant;
+    if (grid > a.n_tiles) grid = a.n_tiles;
+    hipLaunchKernelGGL(k_quantize, dim3(grid), dim3(kQuantBlock), a.win_n * 4u, st, a);
+    HIP_TRY(hipGetLastError());
+    return COMET_OK;
+}
+
+size_t encode_lds(uint32_t nbins, uint32_t chunk_syms, uint32_t *tbl_n) {
+    *tbl_n = nbins < kEncTableMax ? nbins : kEncTableMax;
+    return (size_t)*tbl_n * 8u + (size_t)kEncBlock * (chunk_syms + kEncPad) * 2u;
+}
+
+int launch_encode(comet_ctx *ctx, const uint16_t *codes, uint64_t n, uint32_t nbins, uint32_t chunk_syms,
+                  hipStream_t st, uint32_t *chunk_off, uint8_t *container, uint64_t capacity,
+                  uint32_t *payload, uint64_t payload_cap, uint64_t *payload_words_out, uint64_t *desc) {
+    EncodeArgs a{};
+    a.codes = codes; a.n = n; a.chunk_syms = chunk_syms; a.log2_chunk = ilog2(chunk_syms);
+    a.n_chunks = (uint32_t)((n + chunk_syms - 1) / chunk_syms);
+    a.n_tiles = (a.n_chunks + kEncBlock - 1) / kEncBlock;
+    a.enc = ctx->enc; a.nbins = nbins;
+    const size_t lds = encode_lds(nbins, chunk_syms, &a.tbl_n);
+    a.tbl_lo = (nbins - a.tbl_n) / 2u;
+    a.chunk_off = chunk_off; a.container = container; a.capacity = capacity;
+    a.payload = payload; a.payload_cap_words = payload_cap; a.payload_words_out = payload_words_out;
+    a.desc = desc; a.ctl = &ctx->state->ctl;
+    // occupancy depends on the LDS footprint, which depends on the arguments
+    int occ = 1;
+    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_encode, kEncBlock, lds));
+    if (occ < 1) occ = 1;
+    uint32_t grid = (uint32_t)ctx->num_cu * (uint32_t)occ;
+    if (grid > a.n_tiles) grid = a.n_tiles;
+    hipLaunchKernelGGL(k_encode, dim3(grid), dim3(kEncBlock), lds, st, a);
+    HIP_TRY(hipGetLastError());
+    return COMET_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int comet_create(comet_ctx **out, uint64_t max_elems, uint32_t max_nbins) {
+    if (!out || max_elems == 0 || max_elems > kMaxElems || !valid_nbins(max_nbins)) return COMET_ERR_INVALID;
+    comet_ctx *c = new (std::nothrow) comet_ctx();
+    if (!c) return COMET_ERR_NOMEM;
+    c->max_elems = max_elems;
+    c->max_nbins = max_nbins;
+    int rc = COMET_OK;
+    auto fail = [&](int code) { comet_destroy(c); return code; };
+    hipError_t e;
+    if ((e = hipGetDevice(&c->device)) != hipSuccess) return fail(hip_fail(e, "hipGetDevice"));
+    hipDeviceProp_t prop;
+    if ((e = hipGetDeviceProperties(&prop, c->device)) != hipSuccess) return fail(hip_fail(e, "hipGetDeviceProperties"));
+    c->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+
+    const uint64_t tiles_q = (max_elems + kQuantTile - 1) / kQuantTile;
+    const uint64_t tiles_e = (max_elems / 64u + kEncBlock) / kEncBlock + 1;   // smallest chunk is 64 symbols
+    const ZeroLayout z = zero_layout(kMaxBins, tiles_q, tiles_e);
+    c->zero_cap = z.bytes;
+    const uint64_t state_bytes = offsetof(DevState, ctl) + z.bytes;
+    if ((e = hipMalloc((void **)&c->state, state_bytes)) != hipSuccess) return fail(COMET_ERR_NOMEM);
+    if ((e = hipMemset(c->state, 0, state_bytes)) != hipSuccess) return fail(hip_fail(e, "hipMemset"));
+    c->zero_region = reinterpret_cast<uint8_t *>(&c->state->ctl);
+    if ((e = hipMalloc((void **)&c->codes, align_up(2 * max_elems + 64, 256))) != hipSuccess) return fail(COMET_ERR_NOMEM);
+    if ((e = hipMalloc((void **)&c->enc, 8ull * kMaxBins)) != hipSuccess) return fail(COMET_ERR_NOMEM);
+    {
+        // one blob: book scratch + decode tables
+        uint64_t o = 0;
+        const uint64_t o_keys = o; o += 8ull * kMaxBins;
+        const uint64_t o_iw = o; o += 8ull * kMaxBins;
+        const uint64_t o_lp = o; o += 4ull * kMaxBins;
+        const uint64_t o_ip = o; o += 4ull * kMaxBins;
+        const uint64_t o_limit = o; o += 8ull * 72;
+        const uint64_t o_first = o; o += 8ull * 72;
+        const uint64_t o_findex = o; o += 4ull * 72;
+        const uint64_t o_lut = o; o += 4ull * kLutSize;
+        const uint64_t o_meta = o; o += 64;
+        const uint64_t o_sorted = o; o += 2ull * kMaxBins;
+        uint8_t *blob = nullptr;
+        if ((e = hipMalloc((void **)&blob, align_up(o, 256))) != hipSuccess) return fail(COMET_ERR_NOMEM);
+        c->tables_blob = blob;
+        c->book.keys = (uint64_t *)(blob + o_keys); c->book.iw = (uint64_t *)(blob + o_iw);
+        c->book.leaf_parent = (uint32_t *)(blob + o_lp); c->book.int_parent = (uint32_t *)(blob + o_ip);
+        c->tables.limit = (uint64_t *)(blob + o_limit); c->tables.first_code = (uint64_t *)(blob + o_first);
+        c->tables.first_index = (uint32_t *)(blob + o_findex); c->tables.lut = (uint32_t *)(blob + o_lut);
+        c->tables.meta = (uint32_t *)(blob + o_meta); c->tables.sorted = (uint16_t *)(blob + o_sorted);
+    }
+    if ((e = hipHostMalloc((void **)&c->host_state, sizeof(DevState) + sizeof(Header), hipHostMallocDefault)) != hipSuccess)
+        return fail(COMET_ERR_NOMEM);
+    c->host_hdr = reinterpret_cast<Header *>(reinterpret_cast<uint8_t *>(c->host_state) + sizeof(DevState));
+
+    // kernels that need more than 64 KB of dynamic LDS must opt in
+    if ((e = hipFuncSetAttribute((const void *)k_encode, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024)) != hipSuccess)
+        return fail(hip_fail(e, "hipFuncSetAttribute(k_encode)"));
+    if ((e = hipFuncSetAttribute((const void *)k_reconstruct<0>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024)) != hipSuccess)
+        return fail(hip_fail(e, "hipFuncSetAttribute(k_reconstruct<0>)"));
+    if ((e = hipFuncSetAttribute((const void *)k_reconstruct<1>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024)) != hipSuccess)
+        return fail(hip_fail(e, "hipFuncSetAttribute(k_reconstruct<1>)"));
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&c->occ_quant, k_quantize, kQuantBlock, 4096) != hipSuccess || c->occ_quant < 1) c->occ_quant = 4;
+    (void)rc;
+    *out = c;
+    return COMET_OK;
+}
+
+void comet_destroy(comet_ctx *c) {
+    if (!c) return;
+    if (c->state) (void)hipFree(c->state);
+    if (c->codes) (void)hipFree(c->codes);
+    if (c->enc) (void)hipFree(c->enc);
+    if (c->tables_blob) (void)hipFree(c->tables_blob);
+    if (c->host_state) (void)hipHostFree(c->host_state);
+    delete c;
+}
+
+int comet_set_chunk_syms(comet_ctx *ctx, uint32_t chunk_syms) {
+    if (!ctx || !valid_chunk(chunk_syms)) return COMET_ERR_INVALID;
+    ctx->chunk_syms = chunk_syms;
+    return COMET_OK;
+}
+
+uint64_t comet_compress_bound(comet_shape s, uint32_t nbins, uint32_t chunk_syms) {
+    uint64_t n;
+    if (!shape_elems(s, &n) || !valid_nbins(nbins) || chunk_syms == 0) return 0;
+    const uint64_t n_chunks = (n + chunk_syms - 1) / chunk_syms;
+    uint64_t sz = kHeaderBytes;
+    sz = align16(sz + nbins);
+    sz = align16(sz + 4 * n_chunks);
+    sz = align16(sz + 16 * n);                          // every element both escaped and verbatim
+    sz += 4 * ((17 * n + 31) / 32 + n_chunks);         // an optimal code averages < log2(nbins) + 1 <= 17 bits
+    return sz;
+}
+
+int comet_compress(comet_ctx *ctx, const float *dev_in, comet_shape s, float eb, uint32_t nbins,
+                   void *stream, void *dev_out, uint64_t capacity, uint64_t *bytes_out) {
+    uint64_t n;
+    if (!ctx || !dev_in || !dev_out || !shape_elems(s, &n) || !valid_eb(eb) || !valid_nbins(nbins) ||
+        s.w > kMaxW || ((uintptr_t)dev_out & 15u) || ((uintptr_t)dev_in & 15u)) return COMET_ERR_INVALID;
+    if (n > ctx->max_elems || nbins > ctx->max_nbins) return COMET_ERR_NOMEM;
+    hipStream_t st = (hipStream_t)stream;
+    const uint32_t S = ctx->chunk_syms;
+    const uint64_t n_chunks = (n + S - 1) / S;
+    const uint64_t tiles_q = (n + kQuantTile - 1) / kQuantTile;
+    const uint64_t tiles_e = (n_chunks + kEncBlock - 1) / kEncBlock;
+
+    Header proto{};
+    proto.magic = kMagic; proto.version = 1; proto.N = s.n; proto.C = s.c; proto.H = s.h; proto.W = s.w;
+    proto.nbins = nbins; proto.chunk_syms = S; proto.n_chunks = (uint32_t)n_chunks;
+    const float ebx2 = 2.0f * eb;
+    const float r = (float)(1.0 / (double)ebx2);
+    memcpy(&proto.eb_bits, &eb, 4); memcpy(&proto.ebx2_bits, &ebx2, 4); memcpy(&proto.r_bits, &r, 4);
+    proto.off_len = kHeaderBytes;
+    proto.off_chunk = align16(proto.off_len + nbins);
+    proto.off_outlier = align16(proto.off_chunk + 4 * n_chunks);
+    if (proto.off_outlier > capacity) return COMET_ERR_CAPACITY;
+
+    const ZeroLayout z = zero_layout(nbins, tiles_q, tiles_e);
+    if (z.bytes > ctx->zero_cap) return COMET_ERR_NOMEM;
+    HIP_TRY(hipMemsetAsync(ctx->zero_region, 0, z.bytes, st));
+    uint32_t *hist = reinterpret_cast<uint32_t *>(ctx->zero_region + z.off_hist);
+    uint64_t *desc_q = reinterpret_cast<uint64_t *>(ctx->zero_region + z.off_desc_q);
+    uint64_t *desc_e = reinterpret_cast<uint64_t *>(ctx->zero_region + z.off_desc_e);
+    uint8_t *out = static_cast<uint8_t *>(dev_out);
+
+    int rc = launch_quantize(ctx, dev_in, s, n, eb, nbins, st, ctx->codes, hist,
+                             reinterpret_cast<uint32_t *>(out + proto.off_outlier), (capacity - proto.off_outlier) / 8u, desc_q);
+    if (rc) return rc;
+    {
+        BookArgs b{};
+        b.hist = hist; b.nbins = nbins; b.len_out = out + proto.off_len; b.code_out = nullptr; b.enc = ctx->enc;
+        b.scratch = ctx->book; b.ctl = &ctx->state->ctl; b.hdr = reinterpret_cast<Header *>(out); b.proto = proto; b.capacity = capacity;
+        hipLaunchKernelGGL(k_codebook, dim3(1), dim3(kBookBlock), 0, st, b);
+        HIP_TRY(hipGetLastError());
+    }
+    rc = launch_encode(ctx, ctx->codes, n, nbins, S, st, reinterpret_cast<uint32_t *>(out + proto.off_chunk), out, capacity,
+                       nullptr, 0, nullptr, desc_e);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_latch, dim3(1), dim3(1), 0, st, ctx->state);
+    HIP_TRY(hipGetLastError());
+    if (bytes_out) {
+        HIP_TRY(hipMemcpyAsync(ctx->host_state, ctx->state, sizeof(DevState), hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipStreamSynchronize(st));
+        const uint32_t stt = ctx->host_state->ctl.status;
+        if (stt) {
+            HIP_TRY(hipMemsetAsync(&ctx->state->latched, 0, 4, st));
+            HIP_TRY(hipStreamSynchronize(st));
+            return status_to_error(stt);
+        }
+        *bytes_out = ctx->host_state->ctl.total_bytes;
+    }
+    return COMET_OK;
+}
+
+int comet_decompress(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_shape s, void *stream, float *dev_out) {
+    uint64_t n;
+    if (!ctx || !dev_in || !dev_out || !shape_elems(s, &n) || s.w > kMaxW || ((uintptr_t)dev_in & 15u)) return COMET_ERR_INVALID;
+    if (bytes < kHeaderBytes) return COMET_ERR_FORMAT;
+    hipStream_t st = (hipStream_t)stream;
+    ReconGeometry g;
+    if (!recon_geometry(s, &g)) return COMET_ERR_INVALID;
+    HIP_TRY(hipMemsetAsync(ctx->zero_region, 0, sizeof(Control), st));
+    const uint8_t *in = static_cast<const uint8_t *>(dev_in);
+    {
+        TablesArgs t{};
+        t.len = in + kHeaderBytes; t.nbins = 0; t.t = ctx->tables; t.keys = ctx->book.keys; t.ctl = &ctx->state->ctl;
+        t.hdr = reinterpret_cast<const Header *>(in);
+        t.expect.N = s.n; t.expect.C = s.c; t.expect.H = s.h; t.expect.W = s.w; t.bytes = bytes;
+        hipLaunchKernelGGL(k_decode_tables, dim3(1), dim3(kBookBlock), 0, st, t);
+        HIP_TRY(hipGetLastError());
+    }
+    ReconArgs a{};
+    a.container = in; a.t = ctx->tables; a.n = n; a.planes = s.n * s.c; a.H = s.h; a.W = s.w; a.divW = make_fastdiv(s.w);
+    a.planes_per_unit = g.planes_per_unit; a.tile_rows = g.tile_rows; a.n_units = g.n_units; a.pitch = g.pitch; a.use_carry = g.use_carry;
+    a.out = dev_out; a.ctl = &ctx->state->ctl;
+    uint32_t grid = g.n_units;
+    const uint32_t cap = (uint32_t)ctx->num_cu * 32u;
+    if (grid > cap) grid = cap;
+    hipLaunchKernelGGL(k_reconstruct<0>, dim3(grid), dim3(kDecBlock), g.lds, st, a);
+    HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(k_latch, dim3(1), dim3(1), 0, st, ctx->state);
+    HIP_TRY(hipGetLastError());
+    return COMET_OK;
+}
+
+int comet_sync(comet_ctx *ctx, void *stream) {
+    if (!ctx) return COMET_ERR_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(hipMemcpyAsync(ctx->host_state, ctx->state, sizeof(DevState), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    const uint32_t latched = ctx->host_state->latched;
+    if (latched) {
+        HIP_TRY(hipMemsetAsync(&ctx->state->latched, 0, 4, st));
+        HIP_TRY(hipStreamSynchronize(st));
+    }
+    return status_to_error(latched);
+}
+
+int comet_peek(comet_ctx *ctx, const void *dev_in, uint64_t bytes, void *stream, comet_info *info) {
+    if (!ctx || !dev_in || !info) return COMET_ERR_INVALID;
+    if (bytes < kHeaderBytes) return COMET_ERR_FORMAT;
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(hipMemcpyAsync(ctx->host_hdr, dev_in, sizeof(Header), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    const Header &h = *ctx->host_hdr;
+    comet_shape s{h.N, h.C, h.H, h.W};
+    uint64_t n;
+    if (h.magic != kMagic || h.version != 1 || h.status != 0 || !shape_elems(s, &n) || !valid_nbins(h.nbins) ||
+        h.chunk_syms == 0 || h.total_bytes > bytes || h.total_bytes != h.off_payload + 4 * h.payload_words) return COMET_ERR_FORMAT;
+    info->shape = s; info->nbins = h.nbins; info->chunk_syms = h.chunk_syms; info->n_chunks = h.n_chunks;
+    info->n_active = h.n_active; info->max_len = h.max_len; info->n_outlier_records = h.n_rec; info->n_value_records = h.n_vrec;
+    memcpy(&info->eb, &h.eb_bits, 4);
+    info->nnz = h.nnz; info->payload_words = h.payload_words; info->total_bytes = h.total_bytes;
+    return COMET_OK;
+}
+
+void comet_adapt_defaults(comet_adapt_cfg *cfg) {
+    if (!cfg) return;
+    cfg->a = 0.32; cfg->sigma_frac = 0.01; cfg->eb_min = 0x1p-100f; cfg->eb_max = 0x1p100f;
+}
+
+int comet_adapt_eb(const comet_layer_stats *s, const comet_adapt_cfg *cfg_in, float *eb_out) {
+    if (!s || !eb_out) return COMET_ERR_INVALID;
+    comet_adapt_cfg cfg;
+    if (cfg_in) cfg = *cfg_in; else comet_adapt_defaults(&cfg);
+    if (!std::isfinite(s->momentum_abs_mean) || !std::isfinite(s->loss_grad_mean) || !std::isfinite(s->nonzero_ratio) ||
+        !std::isfinite(cfg.a) || !std::isfinite(cfg.sigma_frac)) return COMET_ERR_INVALID;
+    if (s->momentum_abs_mean < 0.0 || s->loss_grad_mean < 0.0 || s->nonzero_ratio < 0.0 || s->nonzero_ratio > 1.0 ||
+        s->batch == 0 || !(cfg.a > 0.0) || !(cfg.sigma_frac > 0.0) || !(cfg.eb_min > 0.0f) || !(cfg.eb_max >= cfg.eb_min)) return COMET_ERR_INVALID;
+    if (s->loss_grad_mean == 0.0 || s->nonzero_ratio == 0.0) { *eb_out = cfg.eb_max; return COMET_OK; }
+    const double sigma = cfg.sigma_frac * s->momentum_abs_mean;                                 // Sec. 3.2
+    const double eb = sigma / (cfg.a * s->loss_grad_mean * std::sqrt((double)s->batch * s->nonzero_ratio));   // Sec. 3.3
+    float e = (float)eb;
+    if (!(e >= cfg.eb_min)) e = cfg.eb_min;
+    if (e > cfg.eb_max) e = cfg.eb_max;
+    *eb_out = e;
+    return COMET_OK;
+}
+
+// ---------------------------------------------------------------------------
+// stage-level entry points
+// ---------------------------------------------------------------------------
+
+int comet_stage_quantize(comet_ctx *ctx, const float *dev_in, comet_shape s, float eb, uint32_t nbins, void *stream,
+                         uint16_t *dev_codes, uint32_t *dev_hist, uint32_t *dev_records, uint64_t rec_capacity,
+                         uint64_t *dev_counts) {
+    uint64_t n;
+    if (!ctx || !dev_in || !dev_codes || !dev_hist || !dev_counts || (rec_capacity && !dev_records) ||
+        !shape_elems(s, &n) || !valid_eb(eb) || !valid_nbins(nbins) || s.w > kMaxW || ((uintptr_t)dev_in & 15u) ||
+        ((uintptr_t)dev_codes & 7u) || ((uintptr_t)dev_records & 7u)) return COMET_ERR_INVALID;
+    if (n > ctx->max_elems) return COMET_ERR_NOMEM;
+    hipStream_t st = (hipStream_t)stream;
+    const uint64_t tiles_q = (n + kQuantTile - 1) / kQuantTile;
+    const ZeroLayout z = zero_layout(4, tiles_q, 1);
+    if (z.bytes > ctx->zero_cap) return COMET_ERR_NOMEM;
+    HIP_TRY(hipMemsetAsync(ctx->zero_region, 0, z.bytes, st));
+    HIP_TRY(hipMemsetAsync(dev_hist, 0, 4ull * nbins, st));
+    uint64_t *desc_q = reinterpret_cast<uint64_t *>(ctx->zero_region + z.off_desc_q);
+    int rc = launch_quantize(ctx, dev_in, s, n, eb, nbins, st, dev_codes, dev_hist, dev_records, rec_capacity, desc_q);
+    if (rc) return rc;
+    HIP_TRY(hipMemcpyAsync(dev_counts, &ctx->state->ctl.n_rec, 24, hipMemcpyDeviceToDevice, st));
+    hipLaunchKernelGGL(k_latch, dim3(1), dim3(1), 0, st, ctx->state);
+    HIP_TRY(hipGetLastError());
+    return COMET_OK;
+}
+
+int comet_stage_codebook(comet_ctx *ctx, const uint32_t *dev_hist, uint32_t nbins, void *stream, uint8_t *dev_len, uint64_t *dev_code) {
+    if (!ctx || !dev_hist || !dev_len || nbins == 0 || nbins > kMaxBins) return COMET_ERR_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(hipMemsetAsync(ctx->zero_region, 0, sizeof(Control), st));
+    BookArgs b{};
+    b.hist = dev_hist; b.nbins = nbins; b.len_out = dev_len; b.code_out = dev_code; b.enc = ctx->enc;
+    b.scratch = ctx->book; b.ctl = &ctx->state->ctl; b.hdr = nullptr; b.capacity = 0;
+    hipLaunchKernelGGL(k_codebook, dim3(1), dim3(kBookBlock), 0, st, b);
+    HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(k_latch, dim3(1), dim3(1), 0, st, ctx->state);
+    HIP_TRY(hipGetLastError());
+    return COMET_OK;
+}
+
+int comet_stage_encode(comet_ctx *ctx, const uint16_t *dev_codes, uint64_t n, uint32_t nbins, uint32_t chunk_syms, void *stream,
+                       uint32_t *dev_chunk_off, uint32_t *dev_payload, uint64_t payload_capacity_words, uint64_t *dev_payload_words) {
+    if (!ctx || !dev_codes || !dev_chunk_off || !dev_payload_words || (payload_capacity_words && !dev_payload) ||
+        n == 0 || n > kMaxElems || nbins == 0 || nbins > kMaxBins || !valid_chunk(chunk_syms) || ((uintptr_t)dev_codes & 15u)) return COMET_ERR_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    const uint64_t n_chunks = (n + chunk_syms - 1) / chunk_syms;
+    const uint64_t tiles_e = (n_chunks + kEncBlock - 1) / kEncBlock;
+    const ZeroLayout z = zero_layout(4, 1, tiles_e);
+    if (z.bytes > ctx->zero_cap) return COMET_ERR_NOMEM;
+    HIP_TRY(hipMemsetAsync(ctx->zero_region, 0, z.bytes, st));
+    uint64_t *desc_e = reinterpret_cast<uint64_t *>(ctx->zero_region + z.off_desc_e);
+    int rc = launch_encode(ctx, dev_codes, n, nbins, chunk_syms, st, dev_chunk_off, nullptr, 0, dev_payload, payload_capacity_words,
+                           dev_payload_words, desc_e);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_latch, dim3(1), dim3(1), 0, st, ctx->state);
+    HIP_TRY(hipGetLastError());
+    return COMET_OK;
+}
+
+int comet_stage_decode(comet_ctx *ctx, const uint8_t *dev_len, uint32_t nbins, const uint32_t *dev_chunk_off, const uint32_t *dev_payload,
+                       uint64_t payload_words, uint64_t n, uint32_t chunk_syms, void *stream, uint16_t *dev_codes_out) {
+    if (!ctx || !dev_len || !dev_chunk_off || !dev_codes_out || (payload_words && !dev_payload) || n == 0 || n > kMaxElems ||
+        nbins == 0 || nbins > kMaxBins || chunk_syms == 0) return COMET_ERR_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(hipMemsetAsync(ctx->zero_region, 0, sizeof(Control), st));
+    TablesArgs t{};
+    t.len = dev_len; t.nbins = nbins; t.t = ctx->tables; t.keys = ctx->book.keys; t.ctl = &ctx->state->ctl; t.hdr = nullptr;
+    hipLaunchKernelGGL(k_decode_tables, dim3(1), dim3(kBookBlock), 0, st, t);
+    HIP_TRY(hipGetLastError());
+    ReconArgs a{};
+    a.chunk_off = dev_chunk_off; a.payload = dev_payload; a.payload_words = payload_words; a.chunk_syms = chunk_syms;
+    a.n_chunks = (uint32_t)((n + chunk_syms - 1) / chunk_syms); a.t = ctx->tables; a.n = n; a.codes_out = dev_codes_out; a.ctl = &ctx->state->ctl;
+    uint32_t grid = (a.n_chunks + kDecBlock - 1) / kDecBlock;
+    const uint32_t cap = (uint32_t)ctx->num_cu * 32u;
+    if (grid > cap) grid = cap;
+    hipLaunchKernelGGL(k_decode_only, dim3(grid), dim3(kDecBlock), 0, st, a);
+    HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(k_latch, dim3(1), dim3(1), 0, st, ctx->state);
+    HIP_TRY(hipGetLastError());
+    return COMET_OK;
+}
+
+int comet_stage_reconstruct(comet_ctx *ctx, const uint16_t *dev_codes, const uint32_t *dev_records, uint64_t n_records, comet_shape s,
+                            uint32_t nbins, float eb, void *stream, float *dev_out) {
+    uint64_t n;
+    if (!ctx || !dev_codes || !dev_out || (n_records && !dev_records) || !shape_elems(s, &n) || !valid_nbins(nbins) || !valid_eb(eb) ||
+        s.w > kMaxW) return COMET_ERR_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    ReconGeometry g;
+    if (!recon_geometry(s, &g)) return COMET_ERR_INVALID;
+    ReconArgs a{};
+    a.codes_in = dev_codes; a.rec = dev_records; a.n_rec = n_records; a.n = n; a.planes = s.n * s.c; a.H = s.h; a.W = s.w;
+    a.divW = make_fastdiv(s.w); a.radius = (int32_t)(nbins / 2u); a.eb = eb; a.ebx2 = 2.0f * eb;
+    a.planes_per_unit = g.planes_per_unit; a.tile_rows = g.tile_rows; a.n_units = g.n_units; a.pitch = g.pitch; a.use_carry = g.use_carry;
+    a.out = dev_out; a.ctl = &ctx->state->ctl; a.chunk_syms = 1;
+    uint32_t grid = g.n_units;
+    const uint32_t cap = (uint32_t)ctx->num_cu * 32u;
+    if (grid > cap) grid = cap;
+    hipLaunchKernelGGL(k_reconstruct<1>, dim3(grid), dim3(kDecBlock), g.lds, st, a);
+    HIP_TRY(hipGetLastError());
+    return COMET_OK;
+}
+
+const char *comet_strerror(int code) {
+    switch (code) {
+        case COMET_OK: return "ok";
+        case COMET_ERR_INVALID: return "invalid argument";
+        case COMET_ERR_CAPACITY: return "container does not fit the output buffer";
+        case COMET_ERR_FORMAT: return "malformed container or shape mismatch";
+        case COMET_ERR_HIP: return g_hip_msg;
+        case COMET_ERR_NOMEM: return "out of memory, or request larger than the context was created for";
+        case COMET_ERR_INTERNAL: return "device-side consistency check failed";
+        default: return "unknown error code";
+    }
+}
+
+}  // extern "C"

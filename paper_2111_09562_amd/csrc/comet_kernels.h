@@ -1,0 +1,141 @@
+// Kernel argument blocks and launch constants shared by the host API and the
+// kernel translation units.
+#pragma once
+#include "comet_dev.h"
+
+namespace comet {
+
+// ---- quantise (prequantise + Lorenzo + codes + histogram + records) ----------
+constexpr int kQuantBlock = 256;
+constexpr int kQuantTile = 4096;           // elements per tile: 256 lanes x 4 iterations x float4
+constexpr uint32_t kHistWindowMax = 8192;  // LDS-private histogram bins per workgroup
+
+struct QuantArgs {
+    const float *x;
+    uint64_t n;
+    FastDiv divW, divH;        // plane width / height
+    float r, ebx2, eb;
+    int32_t radius;
+    uint32_t nbins;
+    uint32_t win_lo, win_n;    // histogram bins [win_lo, win_lo + win_n) are counted in LDS
+    uint32_t n_tiles;
+    uint16_t *codes;
+    uint32_t *hist;            // u32[nbins], zeroed
+    uint32_t *rec;             // (key, payload) pairs
+    uint64_t rec_cap;          // capacity in records
+    uint64_t *desc;            // chained-scan descriptors, one per tile, zeroed
+    Control *ctl;
+};
+__global__ void k_quantize(QuantArgs a);
+
+// ---- codebook -----------------------------------------------------------------
+constexpr int kBookBlock = 1024;
+constexpr uint32_t kBookLdsSyms = 2048;    // alphabets up to this size are built entirely in LDS
+
+struct BookScratch {                        // global scratch for large alphabets (>= 65536 entries each)
+    uint64_t *keys;        // sort keys
+    uint64_t *iw;          // internal-node weights
+    uint32_t *leaf_parent;
+    uint32_t *int_parent;
+};
+
+struct BookArgs {
+    const uint32_t *hist;
+    uint32_t nbins;
+    uint8_t *len_out;          // u8[nbins]
+    uint64_t *code_out;        // u64[nbins] or null (stage output)
+    uint64_t *enc;             // u64[nbins]: (code << 6) | len, 0 for unused symbols
+    BookScratch scratch;
+    Control *ctl;
+    // container finalisation (null header = stage call)
+    Header *hdr;
+    Header proto;              // host-filled fields
+    uint64_t capacity;
+};
+__global__ void k_codebook(BookArgs a);
+
+// ---- encode -------------------------------------------------------------------
+constexpr int kEncBlock = 256;             // one chunk per lane
+constexpr uint32_t kEncTableMax = 2048;    // table entries cached in LDS
+constexpr uint32_t kEncPad = 8;            // u16 padding per staged chunk (keeps 16-byte LDS reads conflict-free)
+
+struct EncodeArgs {
+    const uint16_t *codes;
+    uint64_t n;
+    uint32_t chunk_syms, log2_chunk;
+    uint32_t n_chunks, n_tiles;
+    const uint64_t *enc;
+    uint32_t nbins;
+    uint32_t tbl_lo, tbl_n;    // table entries [tbl_lo, tbl_lo + tbl_n) are cached in LDS
+    uint32_t *chunk_off;
+    uint8_t *container;        // product path: payload position comes from ctl->off_payload
+    uint64_t capacity;
+    uint32_t *payload;         // stage path: explicit payload buffer
+    uint64_t payload_cap_words;
+    uint64_t *payload_words_out;   // stage path
+    uint64_t *desc;
+    Control *ctl;
+};
+__global__ void k_encode(EncodeArgs a);
+
+// ---- decode tables ------------------------------------------------------------
+constexpr int kLutBits = 11;
+constexpr uint32_t kLutSize = 1u << kLutBits;
+
+struct DecodeTables {          // all in the workspace (global memory)
+    uint32_t *lut;             // kLutSize entries: (symbol << 8) | length, 0 = longer than kLutBits
+    uint64_t *limit;           // [65]: left-aligned exclusive upper bound of the codes of each length
+    uint64_t *first_code;      // [65]
+    uint32_t *first_index;     // [65]: position of the first symbol of each length in `sorted`
+    uint16_t *sorted;          // symbols in canonical (length, symbol) order
+    uint32_t *meta;            // [0] max_len, [1] n_active, [2] min_len
+};
+
+struct TablesArgs {
+    const uint8_t *len;        // u8[nbins]
+    uint32_t nbins;
+    DecodeTables t;
+    uint64_t *keys;            // sort scratch (global), >= 65536 entries
+    Control *ctl;
+    // container validation (null = stage call)
+    const Header *hdr;
+    Header expect;             // shape the caller passed
+    uint64_t bytes;
+};
+__global__ void k_decode_tables(TablesArgs a);
+
+// ---- decode + reconstruct -----------------------------------------------------
+constexpr int kDecBlock = 64;
+constexpr uint32_t kDecTileElems = 8192;   // elements per strip held in LDS
+
+struct ReconArgs {
+    // source: a container (product) or explicit arrays (stage calls)
+    const uint8_t *container;
+    const uint16_t *codes_in;      // stage reconstruct: codes come from memory
+    const uint32_t *chunk_off;
+    const uint32_t *payload;
+    uint64_t payload_words;
+    const uint32_t *rec;
+    uint64_t n_rec;
+    uint32_t chunk_syms, log2_chunk, n_chunks;
+    DecodeTables t;
+    uint64_t n;
+    uint32_t planes, H, W;
+    FastDiv divW;
+    int32_t radius;
+    float eb, ebx2;
+    // strip geometry
+    uint32_t planes_per_unit;      // >= 1 when a unit is a group of whole planes
+    uint32_t rows_per_strip;       // rows of one strip when a plane is cut into strips
+    uint32_t n_units;
+    uint32_t pitch;                // LDS row pitch (odd)
+    uint32_t tile_rows;            // rows held in LDS
+    uint32_t use_carry;            // 1 if planes are cut into strips (column carry in LDS)
+    float *out;
+    uint16_t *codes_out;           // stage decode: write codes instead of reconstructing
+    Control *ctl;
+};
+template <int MODE> __global__ void k_reconstruct(ReconArgs a);   // 0 container, 1 codes from memory
+__global__ void k_decode_only(ReconArgs a);
+
+}  // namespace comet
