@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the COMET activation codec on one MI355X.
+
+A step = one pass of the whole hot path over the ResNet-50-shaped activation set
+(batch 64, five fp32 post-BN-ReLU tensors, 590.9 MB): compress every layer in
+forward order, keep the five containers, decompress them in reverse order.
+Inputs are resident in HBM before the timed region; all ten calls are enqueued
+asynchronously on one stream and the region ends with a synchronisation.
+
+Prints ONE JSON line: round-trip throughput in GB/s of fp32 input, the roofline
+figures of the dominant kernel (per-kernel durations from HIP events recorded by
+the library on its own stream) and the CPU oracle timed on the same data.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--batch", type=int, default=64, help="batch of the activation set (64 = the metric's workload)")
+    ap.add_argument("--chunk-syms", type=int, default=128)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--per-layer", action="store_true", help="also print a per-layer table to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the codec shards with zero exchange (every GPU compresses its own batch "
+              "shard), so --gpus above 1 is not run here.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2111_09562_amd import comet, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    layers = synth.config1(args.batch)
+    t0 = time.time()
+    xs_host = [synth.make(e) for e in layers]
+    gen_s = time.time() - t0
+    xs = [torch.from_numpy(x).cuda() for x in xs_host]
+    n_total = sum(x.numel() for x in xs)
+    in_bytes = 4 * n_total
+
+    ctx = comet.Context(max_elems=max(x.numel() for x in xs), max_nbins=1024)
+    ctx.comet_set_chunk_syms(args.chunk_syms)
+    # containers: 60 % of the input is ample for these tensors; a low ratio would raise COMET_ERR_CAPACITY
+    conts = [torch.empty(int(x.numel() * 4 * 0.6) // 16 * 16, dtype=torch.uint8, device="cuda") for x in xs]
+    outs = [torch.empty_like(x) for x in xs]
+    stream = torch.cuda.current_stream()
+
+    def compress_all():
+        for x, e, c in zip(xs, layers, conts):
+            ctx.comet_compress(x, e["eb"], e["nbins"], c, stream=stream, sync=False)
+
+    def decompress_all():
+        for x, c, o in reversed(list(zip(xs, conts, outs))):
+            ctx.comet_decompress(c, c.numel(), x.shape, o, stream=stream)
+
+    def step():
+        compress_all()
+        decompress_all()
+
+    for _ in range(args.warmup):
+        step()
+    ctx.comet_sync(stream)
+    sizes = [int(ctx.comet_peek(c, c.numel()).total_bytes) for c in conts]
+
+    # ---- the timed region: exactly K steps ----
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ctx.comet_sync(stream)
+    ms_per_step = dt / args.steps * 1e3
+    value = in_bytes / (dt / args.steps) / 1e9
+
+    # compress-only and decompress-only rates (same launch configuration)
+    def timed(fn):
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / args.steps
+    tc = timed(compress_all)
+    td = timed(decompress_all)
+    ctx.comet_sync(stream)
+
+    # ---- per-kernel durations: the same K steps again with the library's event brackets on ----
+    ctx.comet_profile_enable(True)
+    ctx.comet_profile_reset()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    kern = {}
+    for kid, name in enumerate(comet.KERNEL_NAMES):
+        launches, ms = ctx.comet_profile_read(kid)
+        kern[name] = dict(launches=launches, total_ms=ms, avg_us=(ms / launches * 1e3 if launches else 0.0))
+    ctx.comet_profile_enable(False)
+
+    cont_bytes = sum(sizes)
+    b = cont_bytes / n_total                       # container bytes per element
+    # algorithmic bytes per element of each streaming kernel
+    alg = {"k_quantize": 4.0 + 2.0, "k_encode": 2.0 + b, "k_reconstruct": b + 4.0}
+    dom = max(alg.keys(), key=lambda k: kern[k]["total_ms"])
+    launches = kern[dom]["launches"]
+    # every launch of a kernel handles one layer; the five layers differ in size, so
+    # "per launch" is the mean over the set: bytes of the set / 5 per mean launch time
+    alg_bytes_per_launch = alg[dom] * n_total / len(xs)
+    avg_s = kern[dom]["total_ms"] / launches / 1e3
+    achieved = alg_bytes_per_launch / avg_s / 1e9
+    roofline = dict(bound="hbm", kernel=dom, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
+                    avg_launch_us=round(avg_s * 1e6, 2), launches=launches,
+                    alg_bytes_per_elem=round(alg[dom], 4),
+                    note="avg over the five layers of the set; events recorded by the library on its stream in a "
+                         "second pass of K steps (the timed region itself runs without event brackets)")
+    # path-level roofline: two-pass compress (8+b) and fused decompress (b+4) bytes per element
+    path = dict(compress_GBps=round(in_bytes / tc / 1e9, 1), decompress_GBps=round(in_bytes / td / 1e9, 1),
+                compress_frac_hbm=round((8.0 + b) * n_total / tc / 1e9 / HBM_PEAK_GBS, 4),
+                decompress_frac_hbm=round((b + 4.0) * n_total / td / 1e9 / HBM_PEAK_GBS, 4),
+                roundtrip_frac_hbm=round((12.0 + 2 * b) * n_total / (dt / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
+                ratio=round(in_bytes / cont_bytes, 3),
+                per_layer_ratio=[round(4 * x.numel() / s, 3) for x, s in zip(xs, sizes)],
+                kernels={k: dict(launches=v["launches"], avg_us=round(v["avg_us"], 2)) for k, v in kern.items()})
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import comet_oracle as oracle
+        t0 = time.perf_counter()
+        bufs = [oracle.compress(x, e["eb"], e["nbins"], args.chunk_syms) for x, e in zip(xs_host, layers)]
+        t1 = time.perf_counter()
+        for bf in reversed(bufs):
+            oracle.decompress(bf)
+        t2 = time.perf_counter()
+        cpu = dict(value=round(in_bytes / (t2 - t0) / 1e9, 4), unit="GB/s", cores=1, kind="oracle",
+                   sample=f"the whole set once ({in_bytes / 1e6:.1f} MB): compress {t1 - t0:.1f} s, decompress {t2 - t1:.1f} s",
+                   compress_GBps=round(in_bytes / (t1 - t0) / 1e9, 4), decompress_GBps=round(in_bytes / (t2 - t1) / 1e9, 4))
+        assert [len(bf) for bf in bufs] == sizes, "GPU and oracle container sizes differ"
+
+    if args.per_layer:
+        for e, x, s in zip(layers, xs, sizes):
+            print(f"  {tuple(x.shape)} eb={e['eb']} nbins={e['nbins']}: {4 * x.numel()} B -> {s} B (x{4 * x.numel() / s:.2f})", file=sys.stderr)
+        print(f"  generation {gen_s:.1f} s", file=sys.stderr)
+
+    line = dict(metric="compress+decompress GB/s (fp32 in)", value=round(value, 2), unit="GB/s", n_gpus=1,
+                steps=args.steps, warmup=args.warmup, ms_per_step=round(ms_per_step, 4), higher_is_better=True,
+                scaling="weak", vs_baseline=None, dtype="f32", data="synthetic",
+                config=dict(workload=f"ResNet-50-shaped activation set, batch {args.batch}: compress 5 layers forward, "
+                                     f"decompress reverse; eb per layer {[e['eb'] for e in layers]}, 1024 bins, "
+                                     f"chunk {args.chunk_syms}", elements=n_total, input_bytes=in_bytes),
+                roofline=roofline, cpu_baseline=cpu, path=path)
+    print(json.dumps(line))
+    ctx.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

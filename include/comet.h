@@ -150,6 +150,23 @@ int comet_stage_decode(comet_ctx *ctx, const uint8_t *dev_len, uint32_t nbins,
 int comet_stage_reconstruct(comet_ctx *ctx, const uint16_t *dev_codes, const uint32_t *dev_records, uint64_t n_records,
                             comet_shape shape, uint32_t nbins, float eb, void *stream, float *dev_out);
 
+/* ---- per-kernel timing, for benchmarks ---------------------------------------
+ * When enabled, every kernel the context launches is bracketed by two HIP events
+ * recorded on the call's stream.  comet_profile_read waits for those events and
+ * returns, for kernel `kernel_id`, the number of launches since the last
+ * comet_profile_reset and their summed duration in milliseconds.  Kernel ids:
+ * 0 quantize, 1 codebook, 2 encode, 3 decode tables, 4 decode+reconstruct.
+ * At most 16384 launches are kept between resets; further ones are not timed. */
+#define COMET_KERNEL_QUANTIZE 0
+#define COMET_KERNEL_CODEBOOK 1
+#define COMET_KERNEL_ENCODE 2
+#define COMET_KERNEL_TABLES 3
+#define COMET_KERNEL_RECONSTRUCT 4
+#define COMET_KERNEL_COUNT 5
+int comet_profile_enable(comet_ctx *ctx, int enable);
+int comet_profile_reset(comet_ctx *ctx);
+int comet_profile_read(comet_ctx *ctx, uint32_t kernel_id, uint32_t *launches /* host */, double *total_ms /* host */);
+
 /* Text for a COMET_ERR_* code; for COMET_ERR_HIP the last HIP error string seen
  * by this thread.  Never NULL. */
 const char *comet_strerror(int code);

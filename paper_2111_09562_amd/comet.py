@@ -21,8 +21,9 @@ EXPORTS = (
     "comet_create", "comet_destroy", "comet_set_chunk_syms", "comet_compress_bound", "comet_compress",
     "comet_decompress", "comet_sync", "comet_peek", "comet_adapt_defaults", "comet_adapt_eb",
     "comet_stage_quantize", "comet_stage_codebook", "comet_stage_encode", "comet_stage_decode",
-    "comet_stage_reconstruct", "comet_strerror",
+    "comet_stage_reconstruct", "comet_profile_enable", "comet_profile_reset", "comet_profile_read", "comet_strerror",
 )
+KERNEL_NAMES = ("k_quantize", "k_codebook", "k_encode", "k_decode_tables", "k_reconstruct")
 
 
 class Shape(C.Structure):
@@ -80,6 +81,9 @@ def lib():
         L.comet_stage_encode.argtypes = [vp, vp, u64, C.c_uint32, C.c_uint32, vp, vp, vp, u64, vp]
         L.comet_stage_decode.argtypes = [vp, vp, C.c_uint32, vp, vp, u64, u64, C.c_uint32, vp, vp]
         L.comet_stage_reconstruct.argtypes = [vp, vp, vp, u64, Shape, C.c_uint32, C.c_float, vp, vp]
+        L.comet_profile_enable.argtypes = [vp, C.c_int]
+        L.comet_profile_reset.argtypes = [vp]
+        L.comet_profile_read.argtypes = [vp, C.c_uint32, C.POINTER(C.c_uint32), C.POINTER(C.c_double)]
         L.comet_strerror.argtypes = [C.c_int]
         L.comet_strerror.restype = C.c_char_p
         for name in EXPORTS:
@@ -183,6 +187,18 @@ class Context:
         info = Info()
         _chk(lib().comet_peek(self._h, _ptr(container), int(nbytes), _stream(stream), C.byref(info)), "comet_peek")
         return info
+
+    def comet_profile_enable(self, enable: bool) -> None:
+        _chk(lib().comet_profile_enable(self._h, 1 if enable else 0), "comet_profile_enable")
+
+    def comet_profile_reset(self) -> None:
+        _chk(lib().comet_profile_reset(self._h), "comet_profile_reset")
+
+    def comet_profile_read(self, kernel_id: int):
+        """(launches, total milliseconds) of one kernel since the last reset."""
+        n, ms = C.c_uint32(), C.c_double()
+        _chk(lib().comet_profile_read(self._h, kernel_id, C.byref(n), C.byref(ms)), "comet_profile_read")
+        return int(n.value), float(ms.value)
 
     # ---- stage-level entry points -------------------------------------------------
     def comet_stage_quantize(self, x, eb: float, nbins: int, codes, hist, records, counts, stream=None) -> None:

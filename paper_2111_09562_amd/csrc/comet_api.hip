@@ -6,6 +6,7 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "../../include/comet.h"
 #include "comet_kernels.h"
@@ -76,7 +77,12 @@ struct comet_ctx {
     DevState *host_state = nullptr;
     Header *host_hdr = nullptr;
     // occupancy (workgroups per CU) measured once
-    int occ_quant = 1, occ_enc = 1, occ_dec0 = 1, occ_dec1 = 1;
+    int occ_quant = 1;
+    // optional per-kernel timing
+    struct Timed { uint32_t id; hipEvent_t a, b; };
+    bool profiling = false;
+    std::vector<Timed> pool;      // pre-created event pairs
+    size_t used = 0;
 };
 
 namespace {
@@ -105,6 +111,19 @@ int status_to_error(uint32_t st) {
 __global__ void k_latch(DevState *s) {           // fold this call's status into the persistent word
     if (s->ctl.status) atomicOr(&s->latched, s->ctl.status);
 }
+
+// Brackets a kernel launch with two events when profiling is on.
+struct TimedScope {
+    comet_ctx *c; hipStream_t st; comet_ctx::Timed *t = nullptr;
+    TimedScope(comet_ctx *ctx, hipStream_t s, uint32_t id) : c(ctx), st(s) {
+        if (c->profiling && c->used < c->pool.size()) {
+            t = &c->pool[c->used++];
+            t->id = id;
+            (void)hipEventRecord(t->a, st);
+        }
+    }
+    ~TimedScope() { if (t) (void)hipEventRecord(t->b, st); }
+};
 
 struct ReconGeometry { uint32_t planes_per_unit, tile_rows, n_units, pitch, use_carry; size_t lds; };
 
@@ -146,7 +165,10 @@ int launch_quantize(comet_ctx *ctx, const float *x, comet_shape s, uint64_t n, f
     a.codes = codes; a.hist = hist; a.rec = rec; a.rec_cap = rec_cap; a.desc = desc; a.ctl = &ctx->state->ctl;
     uint32_t grid = (uint32_t)ctx->num_cu * (uint32_t)ctx->occ_quant;
     if (grid > a.n_tiles) grid = a.n_tiles;
-    hipLaunchKernelGGL(k_quantize, dim3(grid), dim3(kQuantBlock), a.win_n * 4u, st, a);
+    {
+        TimedScope ts(ctx, st, COMET_KERNEL_QUANTIZE);
+        hipLaunchKernelGGL(k_quantize, dim3(grid), dim3(kQuantBlock), a.win_n * 4u, st, a);
+    }
     HIP_TRY(hipGetLastError());
     return COMET_OK;
 }
@@ -175,7 +197,10 @@ int launch_encode(comet_ctx *ctx, const uint16_t *codes, uint64_t n, uint32_t nb
     if (occ < 1) occ = 1;
     uint32_t grid = (uint32_t)ctx->num_cu * (uint32_t)occ;
     if (grid > a.n_tiles) grid = a.n_tiles;
-    hipLaunchKernelGGL(k_encode, dim3(grid), dim3(kEncBlock), lds, st, a);
+    {
+        TimedScope ts(ctx, st, COMET_KERNEL_ENCODE);
+        hipLaunchKernelGGL(k_encode, dim3(grid), dim3(kEncBlock), lds, st, a);
+    }
     HIP_TRY(hipGetLastError());
     return COMET_OK;
 }
@@ -254,6 +279,7 @@ void comet_destroy(comet_ctx *c) {
     if (c->enc) (void)hipFree(c->enc);
     if (c->tables_blob) (void)hipFree(c->tables_blob);
     if (c->host_state) (void)hipHostFree(c->host_state);
+    for (auto &t : c->pool) { (void)hipEventDestroy(t.a); (void)hipEventDestroy(t.b); }
     delete c;
 }
 
@@ -313,7 +339,10 @@ int comet_compress(comet_ctx *ctx, const float *dev_in, comet_shape s, float eb,
         BookArgs b{};
         b.hist = hist; b.nbins = nbins; b.len_out = out + proto.off_len; b.code_out = nullptr; b.enc = ctx->enc;
         b.scratch = ctx->book; b.ctl = &ctx->state->ctl; b.hdr = reinterpret_cast<Header *>(out); b.proto = proto; b.capacity = capacity;
-        hipLaunchKernelGGL(k_codebook, dim3(1), dim3(kBookBlock), 0, st, b);
+        {
+            TimedScope ts(ctx, st, COMET_KERNEL_CODEBOOK);
+            hipLaunchKernelGGL(k_codebook, dim3(1), dim3(kBookBlock), 0, st, b);
+        }
         HIP_TRY(hipGetLastError());
     }
     rc = launch_encode(ctx, ctx->codes, n, nbins, S, st, reinterpret_cast<uint32_t *>(out + proto.off_chunk), out, capacity,
@@ -349,7 +378,10 @@ int comet_decompress(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_s
         t.len = in + kHeaderBytes; t.nbins = 0; t.t = ctx->tables; t.keys = ctx->book.keys; t.ctl = &ctx->state->ctl;
         t.hdr = reinterpret_cast<const Header *>(in);
         t.expect.N = s.n; t.expect.C = s.c; t.expect.H = s.h; t.expect.W = s.w; t.bytes = bytes;
-        hipLaunchKernelGGL(k_decode_tables, dim3(1), dim3(kBookBlock), 0, st, t);
+        {
+            TimedScope ts(ctx, st, COMET_KERNEL_TABLES);
+            hipLaunchKernelGGL(k_decode_tables, dim3(1), dim3(kBookBlock), 0, st, t);
+        }
         HIP_TRY(hipGetLastError());
     }
     ReconArgs a{};
@@ -359,7 +391,10 @@ int comet_decompress(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_s
     uint32_t grid = g.n_units;
     const uint32_t cap = (uint32_t)ctx->num_cu * 32u;
     if (grid > cap) grid = cap;
-    hipLaunchKernelGGL(k_reconstruct<0>, dim3(grid), dim3(kDecBlock), g.lds, st, a);
+    {
+        TimedScope ts(ctx, st, COMET_KERNEL_RECONSTRUCT);
+        hipLaunchKernelGGL(k_reconstruct<0>, dim3(grid), dim3(kDecBlock), g.lds, st, a);
+    }
     HIP_TRY(hipGetLastError());
     hipLaunchKernelGGL(k_latch, dim3(1), dim3(1), 0, st, ctx->state);
     HIP_TRY(hipGetLastError());
@@ -521,6 +556,45 @@ int comet_stage_reconstruct(comet_ctx *ctx, const uint16_t *dev_codes, const uin
     if (grid > cap) grid = cap;
     hipLaunchKernelGGL(k_reconstruct<1>, dim3(grid), dim3(kDecBlock), g.lds, st, a);
     HIP_TRY(hipGetLastError());
+    return COMET_OK;
+}
+
+int comet_profile_enable(comet_ctx *ctx, int enable) {
+    if (!ctx) return COMET_ERR_INVALID;
+    if (enable && ctx->pool.empty()) {
+        ctx->pool.reserve(16384);
+        for (int i = 0; i < 16384; ++i) {
+            comet_ctx::Timed t{};
+            HIP_TRY(hipEventCreate(&t.a));
+            HIP_TRY(hipEventCreate(&t.b));
+            ctx->pool.push_back(t);
+        }
+    }
+    ctx->profiling = enable != 0;
+    return COMET_OK;
+}
+
+int comet_profile_reset(comet_ctx *ctx) {
+    if (!ctx) return COMET_ERR_INVALID;
+    ctx->used = 0;
+    return COMET_OK;
+}
+
+int comet_profile_read(comet_ctx *ctx, uint32_t kernel_id, uint32_t *launches, double *total_ms) {
+    if (!ctx || !launches || !total_ms || kernel_id >= COMET_KERNEL_COUNT) return COMET_ERR_INVALID;
+    uint32_t cnt = 0;
+    double sum = 0.0;
+    for (size_t i = 0; i < ctx->used; ++i) {
+        const comet_ctx::Timed &t = ctx->pool[i];
+        if (t.id != kernel_id) continue;
+        HIP_TRY(hipEventSynchronize(t.b));
+        float ms = 0.0f;
+        HIP_TRY(hipEventElapsedTime(&ms, t.a, t.b));
+        sum += ms;
+        ++cnt;
+    }
+    *launches = cnt;
+    *total_ms = sum;
     return COMET_OK;
 }
 
