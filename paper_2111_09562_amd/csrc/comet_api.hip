@@ -266,6 +266,14 @@ int comet_create(comet_ctx **out, uint64_t max_elems, uint32_t max_nbins) {
         return fail(hip_fail(e, "hipFuncSetAttribute(k_reconstruct<0>)"));
     if ((e = hipFuncSetAttribute((const void *)k_reconstruct<1>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024)) != hipSuccess)
         return fail(hip_fail(e, "hipFuncSetAttribute(k_reconstruct<1>)"));
+    {
+        const int lds = (int)((size_t)kDsWaves * (kDsTileEntries / 2u + kDsStageWords) * 4u);
+        const void *fns[] = {(const void *)k_decode_scan<1, 0>, (const void *)k_decode_scan<1, 1>, (const void *)k_decode_scan<1, 2>,
+                             (const void *)k_decode_scan<2, 2>, (const void *)k_decode_scan<4, 2>, (const void *)k_decode_scan<8, 2>};
+        for (const void *fn : fns)
+            if ((e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess)
+                return fail(hip_fail(e, "hipFuncSetAttribute(k_decode_scan)"));
+    }
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&c->occ_quant, k_quantize, kQuantBlock, 4096) != hipSuccess || c->occ_quant < 1) c->occ_quant = 4;
     (void)rc;
     *out = c;
@@ -384,14 +392,36 @@ int comet_decompress(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_s
         }
         HIP_TRY(hipGetLastError());
     }
-    ReconArgs a{};
-    a.container = in; a.t = ctx->tables; a.n = n; a.planes = s.n * s.c; a.H = s.h; a.W = s.w; a.divW = make_fastdiv(s.w);
-    a.planes_per_unit = g.planes_per_unit; a.tile_rows = g.tile_rows; a.n_units = g.n_units; a.pitch = g.pitch; a.use_carry = g.use_carry;
-    a.out = dev_out; a.ctl = &ctx->state->ctl;
-    uint32_t grid = g.n_units;
-    const uint32_t cap = (uint32_t)ctx->num_cu * 32u;
-    if (grid > cap) grid = cap;
-    {
+    if (s.w <= kDsMaxW) {
+        // fast path: one wavefront per strip, geometry derived on the device from the header
+        DsArgs d{};
+        d.container = in; d.t = ctx->tables; d.n = n; d.planes = s.n * s.c; d.H = s.h; d.W = s.w; d.divW = make_fastdiv(s.w);
+        d.out = dev_out; d.ctl = &ctx->state->ctl;
+        const size_t lds = (size_t)kDsWaves * (kDsTileEntries / 2u + kDsStageWords) * 4u;
+        // grid: about one wavefront per unit (estimated with the context's chunk size), a few per CU at most
+        const uint64_t emax = (uint64_t)(kDsTileEntries / (ctx->chunk_syms + 2u) - 1u) * ctx->chunk_syms;
+        const uint64_t P = (uint64_t)s.h * s.w;
+        const uint64_t units = (P <= emax) ? ((uint64_t)d.planes + emax / P - 1) / (emax / P) : d.planes;
+        uint64_t grid = (units + kDsWaves - 1) / kDsWaves;
+        const uint64_t cap = (uint64_t)ctx->num_cu * 16u;
+        if (grid > cap) grid = cap;
+        if (grid < 1) grid = 1;
+        TimedScope ts(ctx, st, COMET_KERNEL_RECONSTRUCT);
+        const dim3 g3((uint32_t)grid), b3(kDsBlock);
+        if (s.w <= 16u) hipLaunchKernelGGL((k_decode_scan<1, 0>), g3, b3, lds, st, d);
+        else if (s.w <= 32u) hipLaunchKernelGGL((k_decode_scan<1, 1>), g3, b3, lds, st, d);
+        else if (s.w <= 64u) hipLaunchKernelGGL((k_decode_scan<1, 2>), g3, b3, lds, st, d);
+        else if (s.w <= 128u) hipLaunchKernelGGL((k_decode_scan<2, 2>), g3, b3, lds, st, d);
+        else if (s.w <= 256u) hipLaunchKernelGGL((k_decode_scan<4, 2>), g3, b3, lds, st, d);
+        else hipLaunchKernelGGL((k_decode_scan<8, 2>), g3, b3, lds, st, d);
+    } else {
+        ReconArgs a{};
+        a.container = in; a.t = ctx->tables; a.n = n; a.planes = s.n * s.c; a.H = s.h; a.W = s.w; a.divW = make_fastdiv(s.w);
+        a.planes_per_unit = g.planes_per_unit; a.tile_rows = g.tile_rows; a.n_units = g.n_units; a.pitch = g.pitch; a.use_carry = g.use_carry;
+        a.out = dev_out; a.ctl = &ctx->state->ctl;
+        uint32_t grid = g.n_units;
+        const uint32_t cap = (uint32_t)ctx->num_cu * 32u;
+        if (grid > cap) grid = cap;
         TimedScope ts(ctx, st, COMET_KERNEL_RECONSTRUCT);
         hipLaunchKernelGGL(k_reconstruct<0>, dim3(grid), dim3(kDecBlock), g.lds, st, a);
     }
@@ -597,6 +627,13 @@ int comet_profile_read(comet_ctx *ctx, uint32_t kernel_id, uint32_t *launches, d
     *total_ms = sum;
     return COMET_OK;
 }
+
+#ifdef COMET_DEBUG_TIMING
+int comet_debug_read(comet_ctx *ctx, uint64_t *out32) {
+    if (hipMemcpy(out32, ctx->state->ctl.dbg, sizeof(uint64_t) * 32, hipMemcpyDeviceToHost) != hipSuccess) return COMET_ERR_HIP;
+    return COMET_OK;
+}
+#endif
 
 const char *comet_strerror(int code) {
     switch (code) {

@@ -83,7 +83,8 @@ constexpr int kLutBits = 11;
 constexpr uint32_t kLutSize = 1u << kLutBits;
 
 struct DecodeTables {          // all in the workspace (global memory)
-    uint32_t *lut;             // kLutSize entries: (symbol << 8) | length, 0 = longer than kLutBits
+    uint32_t *lut;             // kLutSize entries: (residual << 8) | length with residual = symbol - radius
+                               // (-32768 for the escape symbol 0); 0 = code longer than kLutBits
     uint64_t *limit;           // [65]: left-aligned exclusive upper bound of the codes of each length
     uint64_t *first_code;      // [65]
     uint32_t *first_index;     // [65]: position of the first symbol of each length in `sorted`
@@ -137,5 +138,24 @@ struct ReconArgs {
 };
 template <int MODE> __global__ void k_reconstruct(ReconArgs a);   // 0 container, 1 codes from memory
 __global__ void k_decode_only(ReconArgs a);
+
+// ---- decode + reconstruct, fast path (planes up to 512 columns) ----------------
+constexpr int kDsWaves = 4;                           // wavefronts per workgroup, each on its own strip
+constexpr int kDsBlock = kDsWaves * kWave;
+constexpr uint32_t kDsTileEntries = 64u * 66u;        // int16 residuals per wavefront: 64 chunks of 64 + 2 padding
+constexpr uint32_t kDsStageWords = 1536u;             // Huffman words (later: escape records) per wavefront
+constexpr uint32_t kDsMaxW = 512u;
+constexpr uint32_t kDsTailEntries = 1024u;           // residuals of long codes kept in LDS
+
+struct DsArgs {
+    const uint8_t *container;
+    DecodeTables t;
+    uint64_t n;
+    uint32_t planes, H, W;
+    FastDiv divW;
+    float *out;
+    Control *ctl;
+};
+template <int NSEG, int MODE> __global__ void k_decode_scan(DsArgs a);   // NSEG = ceil(W / 64) rounded up to 1, 2, 4, 8
 
 }  // namespace comet

@@ -33,6 +33,44 @@ __device__ void bitonic_sort(uint64_t *keys, uint32_t n2) {
     }
 }
 
+// Ascending bitonic sort of one key per lane over the first n2 (power of two,
+// <= blockDim) lanes of the workgroup; keys stay in registers, partners closer
+// than a wavefront are reached by shuffles, the others through LDS.
+__device__ inline uint64_t bitonic_sort_regs(uint64_t key, uint64_t *s_x, uint32_t n2) {
+    const uint32_t i = threadIdx.x;
+    for (uint32_t k = 2; k <= n2; k <<= 1) {
+        for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+            uint64_t other;
+            if (j < (uint32_t)kWave) other = __shfl_xor(key, (int)j, kWave);
+            else {
+                s_x[i] = key;
+                __syncthreads();
+                other = s_x[i ^ j];
+                __syncthreads();
+            }
+            const bool keep_min = ((i & k) == 0) == ((i & j) == 0);
+            const uint64_t lo = key < other ? key : other, hi = key < other ? other : key;
+            key = keep_min ? lo : hi;
+        }
+    }
+    return key;
+}
+
+// arr[begin, end) is non-decreasing in (arr[i] >> shift); number of entries <= t
+// (or < t when strict).  Gallops from the front: the answer is usually small.
+__device__ inline uint32_t count_below(const uint64_t *arr, uint32_t begin, uint32_t end, uint64_t t, int shift, bool strict) {
+    const uint32_t n = end - begin;
+    uint32_t pos = 0, step = 1;
+    auto ok = [&](uint32_t idx) { const uint64_t w = arr[begin + idx] >> shift; return strict ? (w < t) : (w <= t); };
+    while (pos + step <= n && ok(pos + step - 1)) { pos += step; step <<= 1; }
+    uint32_t lo = pos, hi = (pos + step - 1 < n) ? pos + step - 1 : n;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (ok(mid)) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
 __device__ inline uint32_t next_pow2(uint32_t v) {
     uint32_t p = 1;
     while (p < v) p <<= 1;
@@ -72,69 +110,130 @@ __device__ bool canonical_first_codes(const uint32_t *cnt, uint32_t n_active, ui
 
 }  // namespace
 
-__global__ __launch_bounds__(kBookBlock) void k_codebook(BookArgs a) {
-    __shared__ uint64_t s_keys[kBookLdsSyms];
-    __shared__ uint64_t s_iw[kBookLdsSyms];
-    __shared__ uint32_t s_lp[kBookLdsSyms];
-    __shared__ uint32_t s_ip[kBookLdsSyms];
-    __shared__ uint32_t s_part[kBookBlock / kWave];
-    __shared__ uint32_t s_cnt[65];
-    __shared__ uint64_t s_first[65];
-    __shared__ uint32_t s_findex[65];
-    __shared__ uint32_t s_maxlen;
 
+// The merge rounds.  NT lanes take part (a whole workgroup, or one wavefront when
+// the arrays are in LDS and the rounds are short); `sync` is the barrier that
+// matches NT.
+//
+// State: leaves [li, m) and internal nodes [ii, ni) not yet merged.  With t the sum
+// of the two smallest heads, every new node weighs at least t, so every waiting item
+// of weight <= t is merged before any node created now: those items, taken in merged
+// order (leaf before node on equal weight) and paired consecutively, are exactly the
+// next steps of the sequential two-queue construction.  An odd item out waits for the
+// next round.  iw[0, m) must be zero on entry.
+// Same count, by one whole wavefront probing 64 consecutive entries per step
+// (the entries are sorted, so the lanes that pass form a prefix).
+__device__ inline uint32_t count_below_wave(const uint64_t *arr, uint32_t begin, uint32_t end, uint64_t t, int shift) {
+    uint32_t cnt = 0;
+    const uint32_t lane = (uint32_t)lane_id();
+    while (true) {
+        const uint32_t idx = begin + cnt + lane;
+        const bool ok = idx < end && (arr[idx] >> shift) <= t;
+        const uint64_t mask = __ballot(ok);
+        const uint32_t c = (~mask == 0ull) ? 64u : (uint32_t)(__ffsll((unsigned long long)~mask) - 1);
+        cnt += c;
+        if (c < 64u) break;
+    }
+    return cnt;
+}
+
+template <bool WAVE, typename Sync>
+__device__ inline void huffman_rounds(const uint64_t *keys, uint64_t *iw, uint32_t *leaf_parent, uint32_t *int_parent,
+                                      uint32_t m, uint32_t lane, uint32_t nlanes, Sync sync) {
+    uint32_t li = 0, ii = 0, ni = 0;
+    while ((m - li) + (ni - ii) > 1u) {
+        const uint64_t inf = ~0ull;
+        const uint64_t a0 = li < m ? keys[li] >> 16 : inf, a1 = li + 1 < m ? keys[li + 1] >> 16 : inf;
+        const uint64_t b0 = ii < ni ? iw[ii] : inf, b1 = ii + 1 < ni ? iw[ii + 1] : inf;
+        uint64_t s0, s1;
+        if (a0 <= b0) { s0 = a0; s1 = (a1 <= b0) ? a1 : b0; }
+        else { s0 = b0; s1 = (a0 <= b1) ? a0 : b1; }
+        const uint64_t t = s0 + s1;
+        uint32_t nl = WAVE ? count_below_wave(keys, li, m, t, 16) : count_below(keys, li, m, t, 16, false);
+        uint32_t nn = WAVE ? count_below_wave(iw, ii, ni, t, 0) : count_below(iw, ii, ni, t, 0, false);
+        if ((nl + nn) & 1u) {
+            const uint64_t la = nl ? keys[li + nl - 1] >> 16 : 0, lb = nn ? iw[ii + nn - 1] : 0;
+            if (nn && (!nl || la <= lb)) --nn; else --nl;
+        }
+        for (uint32_t idx = lane; idx < nl + nn; idx += nlanes) {
+            uint64_t w;
+            uint32_t rank;
+            if (idx < nl) {
+                w = keys[li + idx] >> 16;
+                rank = idx + count_below(iw, ii, ii + nn, w, 0, true);
+                leaf_parent[li + idx] = ni + (rank >> 1);
+            } else {
+                const uint32_t b = idx - nl;
+                w = iw[ii + b];
+                rank = b + count_below(keys, li, li + nl, w, 16, false);
+                int_parent[ii + b] = ni + (rank >> 1);
+            }
+            atomicAdd(reinterpret_cast<unsigned long long *>(&iw[ni + (rank >> 1)]), (unsigned long long)w);
+        }
+        sync();
+        li += nl; ii += nn; ni += (nl + nn) >> 1;
+    }
+}
+
+// Everything between the histogram and the tables, on storage that is either LDS
+// (LDS == true: the pointers are the workgroup's own __shared__ arrays, so the
+// compiler emits ds_* instructions) or global scratch for large alphabets.
+template <bool LDS>
+__device__ inline void codebook_body(const BookArgs &a, uint32_t m, uint64_t *keys, uint64_t *iw, uint32_t *leaf_parent,
+                                     uint32_t *int_parent, uint64_t *s_x, uint32_t *s_part, uint32_t *s_cnt,
+                                     uint64_t *s_first, uint32_t *s_findex, uint32_t *s_maxlen) {
     const uint32_t tid = threadIdx.x;
     const uint32_t nbins = a.nbins;
-    const bool in_lds = nbins <= kBookLdsSyms;
-    uint64_t *keys = in_lds ? s_keys : a.scratch.keys;
-    uint64_t *iw = in_lds ? s_iw : a.scratch.iw;
-    uint32_t *leaf_parent = in_lds ? s_lp : a.scratch.leaf_parent;
-    uint32_t *int_parent = in_lds ? s_ip : a.scratch.int_parent;
-
-    if (tid < 65) s_cnt[tid] = 0;
-    if (tid == 0) s_maxlen = 0;
-
+    COMET_DBG(a.ctl, 1);
     // ---- 1. compact the active symbols into sort keys (frequency << 16 | symbol) ----
-    uint32_t m = 0;
-    for (uint32_t base = 0; base < nbins; base += kBookBlock) {
-        const uint32_t s = base + tid;
-        const uint32_t f = (s < nbins) ? a.hist[s] : 0u;
-        uint32_t tot;
-        const uint32_t pos = block_excl_scan<uint32_t, kBookBlock / kWave>(f ? 1u : 0u, s_part, tot);
-        if (f) keys[m + pos] = ((uint64_t)f << 16) | s;
-        else if (s < nbins) {           // unused symbol: length 0 everywhere
-            a.len_out[s] = 0;
-            a.enc[s] = 0;
-            if (a.code_out) a.code_out[s] = 0;
+    {
+        uint32_t done = 0;
+        for (uint32_t base = 0; base < nbins; base += kBookBlock) {
+            const uint32_t s = base + tid;
+            const uint32_t f = (s < nbins) ? a.hist[s] : 0u;
+            uint32_t tot;
+            const uint32_t pos = block_excl_scan<uint32_t, kBookBlock / kWave>(f ? 1u : 0u, s_part, tot);
+            if (f) keys[done + pos] = ((uint64_t)f << 16) | s;
+            else if (s < nbins) {           // unused symbol: length 0 everywhere
+                a.len_out[s] = 0;
+                a.enc[s] = 0;
+                if (a.code_out) a.code_out[s] = 0;
+            }
+            done += tot;
         }
-        m += tot;
     }
     const uint32_t m2 = next_pow2(m > 1 ? m : 2);
     for (uint32_t i = m + tid; i < m2; i += kBookBlock) keys[i] = ~0ull;
+    for (uint32_t i = tid; i < m; i += kBookBlock) iw[i] = 0;
     __syncthreads();
 
+    COMET_DBG(a.ctl, 2);
     // ---- 2. leaves in (frequency, symbol) order ----
-    bitonic_sort(keys, m2);
+    const bool reg_sort = LDS && m2 <= (uint32_t)kBookBlock;
+    if (reg_sort) {
+        uint64_t key = tid < m2 ? keys[tid] : ~0ull;
+        key = bitonic_sort_regs(key, s_x, m2);
+        if (tid < m2) keys[tid] = key;
+        __syncthreads();
+    } else {
+        bitonic_sort(keys, m2);
+    }
 
-    // ---- 3. two-queue merge (one lane; m-1 dependent steps) ----
-    if (m >= 2 && tid == 0) {
-        uint32_t li = 0, ii = 0, ni = 0;
-        for (uint32_t step = 0; step + 1 < m; ++step) {
-            uint64_t sum = 0;
-#pragma unroll
-            for (int pick = 0; pick < 2; ++pick) {
-                bool take_leaf;
-                const uint64_t lw = (li < m) ? (keys[li] >> 16) : ~0ull;
-                if (li < m && ii < ni) take_leaf = (lw <= iw[ii]);
-                else take_leaf = (li < m);
-                if (take_leaf) { sum += lw; leaf_parent[li] = ni; ++li; }
-                else { sum += iw[ii]; int_parent[ii] = ni; ++ii; }
-            }
-            iw[ni++] = sum;
+    COMET_DBG(a.ctl, 3);
+    // ---- 3. two-queue merge in rounds ----
+    if (m >= 2) {
+        if (LDS) {
+            // one wavefront: rounds are short, and a wavefront needs no workgroup barrier
+            if (tid < (uint32_t)kWave)
+                huffman_rounds<true>(keys, iw, leaf_parent, int_parent, m, tid, (uint32_t)kWave,
+                               [] { __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup"); __builtin_amdgcn_wave_barrier(); });
+        } else {
+            huffman_rounds<false>(keys, iw, leaf_parent, int_parent, m, tid, (uint32_t)kBookBlock, [] { __syncthreads(); });
         }
     }
     __syncthreads();
 
+    COMET_DBG(a.ctl, 4);
     // ---- 4. depth of every leaf: walk to the root (node m-2) ----
     for (uint32_t i = tid; i < m; i += kBookBlock) {
         const uint32_t sym = (uint32_t)(keys[i] & 0xffffu);
@@ -146,12 +245,20 @@ __global__ __launch_bounds__(kBookBlock) void k_codebook(BookArgs a) {
         }
         keys[i] = ((uint64_t)depth << 16) | sym;     // re-keyed for the canonical order
         atomicAdd(&s_cnt[depth > 64 ? 64 : depth], 1u);
-        atomicMax(&s_maxlen, depth);
+        atomicMax(s_maxlen, depth);
     }
     __syncthreads();
 
+    COMET_DBG(a.ctl, 5);
     // ---- 5. canonical order (length, symbol) ----
-    bitonic_sort(keys, m2);
+    if (reg_sort) {
+        uint64_t key = tid < m2 ? keys[tid] : ~0ull;
+        key = bitonic_sort_regs(key, s_x, m2);
+        if (tid < m2) keys[tid] = key;
+        __syncthreads();
+    } else {
+        bitonic_sort(keys, m2);
+    }
     if (tid == 0) {
         uint32_t mx, mn;
         const bool ok = (m == 0) || canonical_first_codes(s_cnt, m, s_first, s_findex, &mx, &mn);
@@ -159,6 +266,7 @@ __global__ __launch_bounds__(kBookBlock) void k_codebook(BookArgs a) {
     }
     __syncthreads();
 
+    COMET_DBG(a.ctl, 6);
     // ---- 6. codes and tables ----
     for (uint32_t p = tid; p < m; p += kBookBlock) {
         const uint32_t L = (uint32_t)(keys[p] >> 16);
@@ -168,7 +276,38 @@ __global__ __launch_bounds__(kBookBlock) void k_codebook(BookArgs a) {
         a.enc[sym] = (code << 6) | (uint64_t)(L & 63u);
         if (a.code_out) a.code_out[sym] = code;
     }
+}
 
+__global__ __launch_bounds__(kBookBlock) void k_codebook(BookArgs a) {
+    __shared__ uint64_t s_keys[kBookLdsSyms];
+    __shared__ uint64_t s_iw[kBookLdsSyms];
+    __shared__ uint32_t s_lp[kBookLdsSyms];
+    __shared__ uint32_t s_ip[kBookLdsSyms];
+    __shared__ uint64_t s_x[kBookBlock];
+    __shared__ uint32_t s_part[kBookBlock / kWave];
+    __shared__ uint32_t s_cnt[65];
+    __shared__ uint64_t s_first[65];
+    __shared__ uint32_t s_findex[65];
+    __shared__ uint32_t s_maxlen;
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t nbins = a.nbins;
+    COMET_DBG(a.ctl, 0);
+    if (tid < 65) s_cnt[tid] = 0;
+    if (tid == 0) s_maxlen = 0;
+
+    uint32_t m = 0;
+    for (uint32_t base = 0; base < nbins; base += kBookBlock) {
+        const uint32_t s = base + tid;
+        m += __syncthreads_count((s < nbins) && a.hist[s] != 0u);
+    }
+    if (m <= kBookLdsSyms)
+        codebook_body<true>(a, m, s_keys, s_iw, s_lp, s_ip, s_x, s_part, s_cnt, s_first, s_findex, &s_maxlen);
+    else
+        codebook_body<false>(a, m, a.scratch.keys, a.scratch.iw, a.scratch.leaf_parent, a.scratch.int_parent, s_x, s_part,
+                             s_cnt, s_first, s_findex, &s_maxlen);
+
+    COMET_DBG(a.ctl, 7);
     // ---- 7. container layout ----
     if (tid == 0) {
         a.ctl->n_active = m;
@@ -195,6 +334,7 @@ __global__ __launch_bounds__(kBookBlock) void k_codebook(BookArgs a) {
                 for (uint64_t o = h.off_outlier + 8ull * a.ctl->n_rec; o < h.off_payload; ++o) base[o] = 0;
         }
     }
+    COMET_DBG(a.ctl, 8);
 }
 
 // ---------------------------------------------------------------------------
@@ -209,6 +349,8 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
     __shared__ uint64_t s_limit[65];
     __shared__ uint32_t s_findex[65];
     __shared__ uint32_t s_ok, s_maxlen, s_nbins;
+    __shared__ uint64_t s_dkeys[kBookBlock];
+    __shared__ uint64_t s_dx[kBookBlock];
 
     const uint32_t tid = threadIdx.x;
     if (tid == 0) {
@@ -245,19 +387,27 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
         return;
     }
     const uint32_t nbins = s_nbins;
-    uint64_t *keys = a.keys;
 
     // symbols with a code, keyed (length << 16 | symbol)
     uint32_t m = 0;
-    bool bad = false;
     for (uint32_t base = 0; base < nbins; base += kBookBlock) {
         const uint32_t s = base + tid;
-        const uint32_t L = (s < nbins) ? a.len[s] : 0u;
-        if (L > 57u) bad = true;
-        uint32_t tot;
-        const uint32_t pos = block_excl_scan<uint32_t, kBookBlock / kWave>(L ? 1u : 0u, s_part, tot);
-        if (L) { keys[m + pos] = ((uint64_t)L << 16) | s; atomicAdd(&s_cnt[L > 64u ? 64u : L], 1u); }
-        m += tot;
+        m += __syncthreads_count((s < nbins) && a.len[s] != 0);
+    }
+    const bool small = m <= (uint32_t)kBookBlock;
+    uint64_t *keys = small ? s_dkeys : a.keys;
+    bool bad = false;
+    {
+        uint32_t done = 0;
+        for (uint32_t base = 0; base < nbins; base += kBookBlock) {
+            const uint32_t s = base + tid;
+            const uint32_t L = (s < nbins) ? a.len[s] : 0u;
+            if (L > 57u) bad = true;
+            uint32_t tot;
+            const uint32_t pos = block_excl_scan<uint32_t, kBookBlock / kWave>(L ? 1u : 0u, s_part, tot);
+            if (L) { keys[done + pos] = ((uint64_t)L << 16) | s; atomicAdd(&s_cnt[L > 64u ? 64u : L], 1u); }
+            done += tot;
+        }
     }
     const uint32_t m2 = next_pow2(m > 1 ? m : 2);
     for (uint32_t i = m + tid; i < m2; i += kBookBlock) keys[i] = ~0ull;
@@ -265,7 +415,15 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
         if (tid == 0) atomicOr(&a.ctl->status, (uint32_t)ST_FORMAT);
         return;
     }
-    bitonic_sort(keys, m2);
+    if (small) {
+        uint64_t key = tid < m2 ? keys[tid] : ~0ull;
+        key = bitonic_sort_regs(key, s_dx, m2);
+        __syncthreads();
+        if (tid < m2) keys[tid] = key;
+        __syncthreads();
+    } else {
+        bitonic_sort(keys, m2);
+    }
     if (tid == 0) {
         uint32_t mx, mn;
         const bool ok = canonical_first_codes(s_cnt, m, s_first, s_findex, &mx, &mn);
@@ -292,8 +450,9 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
         return;
     }
     for (uint32_t p = tid; p < m; p += kBookBlock) a.t.sorted[p] = (uint16_t)(keys[p] & 0xffffu);
-    // look-up table on the next kLutBits bits
+    // look-up table on the next kLutBits bits; entries carry the residual, not the symbol
     const uint32_t mx = s_maxlen;
+    const int32_t radius = (int32_t)(nbins / 2u);
     for (uint32_t e = tid; e < kLutSize; e += kBookBlock) {
         const uint64_t v = (uint64_t)e << (64 - kLutBits);
         uint32_t entry = 0;
@@ -303,12 +462,14 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
                 uint64_t off = (v >> (64u - L)) - s_first[L];
                 if (off >= s_cnt[L]) off = s_cnt[L] - 1u;      // only reachable with an invalid stream
                 const uint32_t sym = (uint32_t)(keys[s_findex[L] + off] & 0xffffu);
-                entry = (sym << 8) | L;
+                const int32_t d = sym ? (int32_t)sym - radius : -32768;
+                entry = ((uint32_t)d << 8) | L;
                 break;
             }
         }
         a.t.lut[e] = entry;
     }
+    if (tid == 0) a.t.meta[3] = (uint32_t)radius;
 }
 
 }  // namespace comet

@@ -46,13 +46,17 @@ struct LdsTables {
     const uint32_t *findex;
     const uint16_t *sorted;
     uint32_t max_len, n_active;
+    int32_t radius;
 };
 
 __device__ inline uint32_t decode_symbol(BitReader &br, const LdsTables &t) {
     const uint32_t e = t.lut[br.buf >> (64 - kLutBits)];
     uint32_t L, sym;
-    if (e) { L = e & 0xffu; sym = e >> 8; }
-    else {
+    if (e) {
+        L = e & 0xffu;
+        const int32_t d = (int32_t)e >> 8;                  // the table holds residuals
+        sym = (d == -32768) ? 0u : (uint32_t)(d + t.radius);
+    } else {
         const uint64_t win = br.buf | ((uint64_t)br.nw >> (br.nb - 32u));
         L = kLutBits + 1;
         while (L < t.max_len && win >= t.limit[L]) ++L;
@@ -70,7 +74,7 @@ __device__ inline void load_tables(const DecodeTables &g, uint32_t *s_lut, uint6
     for (uint32_t i = threadIdx.x; i < kLutSize; i += blockDim.x) s_lut[i] = g.lut[i];
     for (uint32_t i = threadIdx.x; i < 65u; i += blockDim.x) { s_limit[i] = g.limit[i]; s_first[i] = g.first_code[i]; s_findex[i] = g.first_index[i]; }
     t.lut = s_lut; t.limit = s_limit; t.first = s_first; t.findex = s_findex; t.sorted = g.sorted;
-    t.max_len = g.meta[0]; t.n_active = g.meta[1];
+    t.max_len = g.meta[0]; t.n_active = g.meta[1]; t.radius = (int32_t)g.meta[3];
 }
 
 // first record index whose key is >= target; all 64 lanes of one wavefront take

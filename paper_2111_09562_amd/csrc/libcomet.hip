@@ -4,4 +4,5 @@
 #include "k_codebook.hip"
 #include "k_encode.hip"
 #include "k_reconstruct.hip"
+#include "k_decompress.hip"
 #include "comet_api.hip"
