@@ -112,6 +112,16 @@ __global__ void k_latch(DevState *s) {           // fold this call's status into
     if (s->ctl.status) atomicOr(&s->latched, s->ctl.status);
 }
 
+// Last kernel of a compression: payload size and status go into the container header.
+__global__ void k_seal(DevState *s, Header *h) {
+    const uint64_t total = s->ctl.off_payload + 4ull * s->ctl.payload_words;
+    h->payload_words = s->ctl.payload_words;
+    h->total_bytes = total;
+    h->status = s->ctl.status ? 1u : 0u;
+    s->ctl.total_bytes = total;
+    if (s->ctl.status) atomicOr(&s->latched, s->ctl.status);
+}
+
 // Brackets a kernel launch with two events when profiling is on.
 struct TimedScope {
     comet_ctx *c; hipStream_t st; comet_ctx::Timed *t = nullptr;
@@ -151,6 +161,10 @@ bool recon_geometry(comet_shape s, ReconGeometry *g) {
     return g->lds <= 96u * 1024u;
 }
 
+// segments of the encode kernel: (chunks per segment, number of segments)
+void encode_geometry(const comet_ctx *ctx, uint64_t n_chunks, uint32_t *seg_chunks, uint32_t *n_seg);
+uint32_t quantize_segments(const comet_ctx *ctx, uint64_t n_tiles);
+
 int launch_quantize(comet_ctx *ctx, const float *x, comet_shape s, uint64_t n, float eb, uint32_t nbins,
                     hipStream_t st, uint16_t *codes, uint32_t *hist, uint32_t *rec, uint64_t rec_cap,
                     uint64_t *desc) {
@@ -163,46 +177,75 @@ int launch_quantize(comet_ctx *ctx, const float *x, comet_shape s, uint64_t n, f
     a.win_lo = (nbins - a.win_n) / 2u;
     a.n_tiles = (uint32_t)((n + kQuantTile - 1) / kQuantTile);
     a.codes = codes; a.hist = hist; a.rec = rec; a.rec_cap = rec_cap; a.desc = desc; a.ctl = &ctx->state->ctl;
-    uint32_t grid = (uint32_t)ctx->num_cu * (uint32_t)ctx->occ_quant;
-    if (grid > a.n_tiles) grid = a.n_tiles;
+    // one segment of consecutive tiles per workgroup, about as many workgroups as fit the chip at once
+    const uint32_t grid = quantize_segments(ctx, a.n_tiles);
+    a.tiles_per_seg = (a.n_tiles + grid - 1) / grid;
+    a.rec_lds = kQuantRecLds;
+    const size_t lds = (size_t)a.win_n * 4u + (size_t)kQuantRecLds * 8u;
     {
         TimedScope ts(ctx, st, COMET_KERNEL_QUANTIZE);
-        hipLaunchKernelGGL(k_quantize, dim3(grid), dim3(kQuantBlock), a.win_n * 4u, st, a);
+        if (a.win_n == nbins) hipLaunchKernelGGL(k_quantize<true>, dim3(grid), dim3(kQuantBlock), lds, st, a);
+        else hipLaunchKernelGGL(k_quantize<false>, dim3(grid), dim3(kQuantBlock), lds, st, a);
     }
     HIP_TRY(hipGetLastError());
     return COMET_OK;
-}
-
-size_t encode_lds(uint32_t nbins, uint32_t chunk_syms, uint32_t *tbl_n) {
-    *tbl_n = nbins < kEncTableMax ? nbins : kEncTableMax;
-    return (size_t)*tbl_n * 8u + (size_t)kEncBlock * (chunk_syms + kEncPad) * 2u;
 }
 
 int launch_encode(comet_ctx *ctx, const uint16_t *codes, uint64_t n, uint32_t nbins, uint32_t chunk_syms,
                   hipStream_t st, uint32_t *chunk_off, uint8_t *container, uint64_t capacity,
                   uint32_t *payload, uint64_t payload_cap, uint64_t *payload_words_out, uint64_t *desc) {
     EncodeArgs a{};
-    a.codes = codes; a.n = n; a.chunk_syms = chunk_syms; a.log2_chunk = ilog2(chunk_syms);
+    a.codes = codes; a.n = n; a.chunk_syms = chunk_syms;
     a.n_chunks = (uint32_t)((n + chunk_syms - 1) / chunk_syms);
-    a.n_tiles = (a.n_chunks + kEncBlock - 1) / kEncBlock;
     a.enc = ctx->enc; a.nbins = nbins;
-    const size_t lds = encode_lds(nbins, chunk_syms, &a.tbl_n);
+    a.tbl_n = nbins < kEncTableMax ? nbins : kEncTableMax;
     a.tbl_lo = (nbins - a.tbl_n) / 2u;
+    uint32_t seg, grid;
+    encode_geometry(ctx, a.n_chunks, &seg, &grid);
+    a.seg_chunks = seg;
+    const size_t lds_count = (size_t)a.tbl_n * 8u + (size_t)seg * 4u;
+    const size_t lds_pack = (size_t)a.tbl_n * 8u + (size_t)(kEncBlock / kWave) * kEncBufWords * 4u;
     a.chunk_off = chunk_off; a.container = container; a.capacity = capacity;
     a.payload = payload; a.payload_cap_words = payload_cap; a.payload_words_out = payload_words_out;
     a.desc = desc; a.ctl = &ctx->state->ctl;
-    // occupancy depends on the LDS footprint, which depends on the arguments
-    int occ = 1;
-    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_encode, kEncBlock, lds));
-    if (occ < 1) occ = 1;
-    uint32_t grid = (uint32_t)ctx->num_cu * (uint32_t)occ;
-    if (grid > a.n_tiles) grid = a.n_tiles;
+    const bool full = (a.tbl_n == nbins);
+#define COMET_LAUNCH_ENC(S)                                                                                            \
+    do {                                                                                                               \
+        if (full) {                                                                                                    \
+            hipLaunchKernelGGL((k_encode_count<S, true>), dim3(grid), dim3(kEncBlock), lds_count, st, a);              \
+            hipLaunchKernelGGL((k_encode_pack<S, true>), dim3(grid), dim3(kEncBlock), lds_pack, st, a);                \
+        } else {                                                                                                       \
+            hipLaunchKernelGGL((k_encode_count<S, false>), dim3(grid), dim3(kEncBlock), lds_count, st, a);             \
+            hipLaunchKernelGGL((k_encode_pack<S, false>), dim3(grid), dim3(kEncBlock), lds_pack, st, a);               \
+        }                                                                                                              \
+    } while (0)
     {
         TimedScope ts(ctx, st, COMET_KERNEL_ENCODE);
-        hipLaunchKernelGGL(k_encode, dim3(grid), dim3(kEncBlock), lds, st, a);
+        if (chunk_syms == 64u) COMET_LAUNCH_ENC(64);
+        else if (chunk_syms == 128u) COMET_LAUNCH_ENC(128);
+        else COMET_LAUNCH_ENC(256);
     }
+#undef COMET_LAUNCH_ENC
     HIP_TRY(hipGetLastError());
     return COMET_OK;
+}
+
+void encode_geometry(const comet_ctx *ctx, uint64_t n_chunks, uint32_t *seg_chunks, uint32_t *n_seg) {
+    // one segment of consecutive chunks per workgroup: about as many segments as workgroups fit the chip
+    const uint64_t want = (uint64_t)ctx->num_cu * 8u;
+    uint64_t seg = (n_chunks + want - 1) / want;
+    seg = (seg + 3u) & ~(uint64_t)3u;
+    if (seg < 4u) seg = 4u;
+    if (seg > kEncSegChunksMax) seg = kEncSegChunksMax;
+    *seg_chunks = (uint32_t)seg;
+    *n_seg = (uint32_t)((n_chunks + seg - 1) / seg);
+}
+
+uint32_t quantize_segments(const comet_ctx *ctx, uint64_t n_tiles) {
+    uint64_t grid = (uint64_t)ctx->num_cu * (uint64_t)ctx->occ_quant;
+    if (grid > n_tiles) grid = n_tiles;
+    const uint64_t per = (n_tiles + grid - 1) / grid;
+    return (uint32_t)((n_tiles + per - 1) / per);
 }
 
 }  // namespace
@@ -223,8 +266,9 @@ int comet_create(comet_ctx **out, uint64_t max_elems, uint32_t max_nbins) {
     if ((e = hipGetDeviceProperties(&prop, c->device)) != hipSuccess) return fail(hip_fail(e, "hipGetDeviceProperties"));
     c->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
 
-    const uint64_t tiles_q = (max_elems + kQuantTile - 1) / kQuantTile;
-    const uint64_t tiles_e = (max_elems / 64u + kEncBlock) / kEncBlock + 1;   // smallest chunk is 64 symbols
+    // scan descriptors: one per segment of the quantise / encode kernels (worst case over chunk sizes)
+    const uint64_t tiles_q = (uint64_t)c->num_cu * 16u + 16u;
+    const uint64_t tiles_e = (uint64_t)c->num_cu * 8u + max_elems / 64u / kEncSegChunksMax + 16u;
     const ZeroLayout z = zero_layout(kMaxBins, tiles_q, tiles_e);
     c->zero_cap = z.bytes;
     const uint64_t state_bytes = offsetof(DevState, ctl) + z.bytes;
@@ -260,8 +304,6 @@ int comet_create(comet_ctx **out, uint64_t max_elems, uint32_t max_nbins) {
     c->host_hdr = reinterpret_cast<Header *>(reinterpret_cast<uint8_t *>(c->host_state) + sizeof(DevState));
 
     // kernels that need more than 64 KB of dynamic LDS must opt in
-    if ((e = hipFuncSetAttribute((const void *)k_encode, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024)) != hipSuccess)
-        return fail(hip_fail(e, "hipFuncSetAttribute(k_encode)"));
     if ((e = hipFuncSetAttribute((const void *)k_reconstruct<0>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024)) != hipSuccess)
         return fail(hip_fail(e, "hipFuncSetAttribute(k_reconstruct<0>)"));
     if ((e = hipFuncSetAttribute((const void *)k_reconstruct<1>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024)) != hipSuccess)
@@ -274,7 +316,7 @@ int comet_create(comet_ctx **out, uint64_t max_elems, uint32_t max_nbins) {
             if ((e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess)
                 return fail(hip_fail(e, "hipFuncSetAttribute(k_decode_scan)"));
     }
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&c->occ_quant, k_quantize, kQuantBlock, 4096) != hipSuccess || c->occ_quant < 1) c->occ_quant = 4;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&c->occ_quant, k_quantize<true>, kQuantBlock, 4096 + kQuantRecLds * 8) != hipSuccess || c->occ_quant < 1) c->occ_quant = 4;
     (void)rc;
     *out = c;
     return COMET_OK;
@@ -318,8 +360,10 @@ int comet_compress(comet_ctx *ctx, const float *dev_in, comet_shape s, float eb,
     hipStream_t st = (hipStream_t)stream;
     const uint32_t S = ctx->chunk_syms;
     const uint64_t n_chunks = (n + S - 1) / S;
-    const uint64_t tiles_q = (n + kQuantTile - 1) / kQuantTile;
-    const uint64_t tiles_e = (n_chunks + kEncBlock - 1) / kEncBlock;
+    uint32_t e_seg, e_grid;
+    encode_geometry(ctx, n_chunks, &e_seg, &e_grid);
+    const uint64_t tiles_q = quantize_segments(ctx, (n + kQuantTile - 1) / kQuantTile);
+    const uint64_t tiles_e = e_grid;
 
     Header proto{};
     proto.magic = kMagic; proto.version = 1; proto.N = s.n; proto.C = s.c; proto.H = s.h; proto.W = s.w;
@@ -356,7 +400,7 @@ int comet_compress(comet_ctx *ctx, const float *dev_in, comet_shape s, float eb,
     rc = launch_encode(ctx, ctx->codes, n, nbins, S, st, reinterpret_cast<uint32_t *>(out + proto.off_chunk), out, capacity,
                        nullptr, 0, nullptr, desc_e);
     if (rc) return rc;
-    hipLaunchKernelGGL(k_latch, dim3(1), dim3(1), 0, st, ctx->state);
+    hipLaunchKernelGGL(k_seal, dim3(1), dim3(1), 0, st, ctx->state, reinterpret_cast<Header *>(out));
     HIP_TRY(hipGetLastError());
     if (bytes_out) {
         HIP_TRY(hipMemcpyAsync(ctx->host_state, ctx->state, sizeof(DevState), hipMemcpyDeviceToHost, st));
@@ -498,7 +542,7 @@ int comet_stage_quantize(comet_ctx *ctx, const float *dev_in, comet_shape s, flo
         ((uintptr_t)dev_codes & 7u) || ((uintptr_t)dev_records & 7u)) return COMET_ERR_INVALID;
     if (n > ctx->max_elems) return COMET_ERR_NOMEM;
     hipStream_t st = (hipStream_t)stream;
-    const uint64_t tiles_q = (n + kQuantTile - 1) / kQuantTile;
+    const uint64_t tiles_q = quantize_segments(ctx, (n + kQuantTile - 1) / kQuantTile);
     const ZeroLayout z = zero_layout(4, tiles_q, 1);
     if (z.bytes > ctx->zero_cap) return COMET_ERR_NOMEM;
     HIP_TRY(hipMemsetAsync(ctx->zero_region, 0, z.bytes, st));
@@ -532,7 +576,9 @@ int comet_stage_encode(comet_ctx *ctx, const uint16_t *dev_codes, uint64_t n, ui
         n == 0 || n > kMaxElems || nbins == 0 || nbins > kMaxBins || !valid_chunk(chunk_syms) || ((uintptr_t)dev_codes & 15u)) return COMET_ERR_INVALID;
     hipStream_t st = (hipStream_t)stream;
     const uint64_t n_chunks = (n + chunk_syms - 1) / chunk_syms;
-    const uint64_t tiles_e = (n_chunks + kEncBlock - 1) / kEncBlock;
+    uint32_t e_seg, e_grid;
+    encode_geometry(ctx, n_chunks, &e_seg, &e_grid);
+    const uint64_t tiles_e = e_grid;
     const ZeroLayout z = zero_layout(4, 1, tiles_e);
     if (z.bytes > ctx->zero_cap) return COMET_ERR_NOMEM;
     HIP_TRY(hipMemsetAsync(ctx->zero_region, 0, z.bytes, st));

@@ -53,6 +53,14 @@ struct Control {
 #define COMET_ACC(ctl, i) do {} while (0)
 #endif
 
+// Orders the LDS accesses of the lanes of one wavefront (writes before, reads after).  Only the
+// LDS counter is waited for: a fence over all address spaces would also wait for every global
+// load and store in flight, which turns a streaming loop into one memory round trip per step.
+__device__ inline void wave_lds_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup", "local");
+    __builtin_amdgcn_wave_barrier();
+}
+
 __host__ __device__ inline uint64_t align16(uint64_t v) { return (v + 15u) & ~(uint64_t)15u; }
 
 // ---------------------------------------------------------------------------

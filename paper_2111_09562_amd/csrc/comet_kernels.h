@@ -19,14 +19,17 @@ struct QuantArgs {
     uint32_t nbins;
     uint32_t win_lo, win_n;    // histogram bins [win_lo, win_lo + win_n) are counted in LDS
     uint32_t n_tiles;
+    uint32_t tiles_per_seg;    // consecutive tiles per workgroup (one segment each)
+    uint32_t rec_lds;          // records the LDS buffer of a workgroup can hold
     uint16_t *codes;
     uint32_t *hist;            // u32[nbins], zeroed
     uint32_t *rec;             // (key, payload) pairs
     uint64_t rec_cap;          // capacity in records
-    uint64_t *desc;            // chained-scan descriptors, one per tile, zeroed
+    uint64_t *desc;            // chained-scan descriptors, one per segment, zeroed
     Control *ctl;
 };
-__global__ void k_quantize(QuantArgs a);
+constexpr uint32_t kQuantRecLds = 3072;   // outlier records buffered in LDS per workgroup (24 KB)
+template <bool FULLWIN> __global__ void k_quantize(QuantArgs a);   // FULLWIN: every bin is in the LDS window
 
 // ---- codebook -----------------------------------------------------------------
 constexpr int kBookBlock = 1024;
@@ -55,15 +58,16 @@ struct BookArgs {
 __global__ void k_codebook(BookArgs a);
 
 // ---- encode -------------------------------------------------------------------
-constexpr int kEncBlock = 256;             // one chunk per lane
+constexpr int kEncBlock = 256;             // four wavefronts, each encodes 256 symbols per step cooperatively
 constexpr uint32_t kEncTableMax = 2048;    // table entries cached in LDS
-constexpr uint32_t kEncPad = 8;            // u16 padding per staged chunk (keeps 16-byte LDS reads conflict-free)
+constexpr uint32_t kEncSegChunksMax = 4096;   // chunks per workgroup segment (their word counts live in LDS)
 
 struct EncodeArgs {
     const uint16_t *codes;
     uint64_t n;
-    uint32_t chunk_syms, log2_chunk;
-    uint32_t n_chunks, n_tiles;
+    uint32_t chunk_syms;       // 64, 128 or 256
+    uint32_t n_chunks;
+    uint32_t seg_chunks;       // chunks per segment (one segment per workgroup)
     const uint64_t *enc;
     uint32_t nbins;
     uint32_t tbl_lo, tbl_n;    // table entries [tbl_lo, tbl_lo + tbl_n) are cached in LDS
@@ -73,10 +77,15 @@ struct EncodeArgs {
     uint32_t *payload;         // stage path: explicit payload buffer
     uint64_t payload_cap_words;
     uint64_t *payload_words_out;   // stage path
-    uint64_t *desc;
+    uint64_t *desc;            // words of every segment (written by the count kernel, read by the pack kernel)
     Control *ctl;
 };
-__global__ void k_encode(EncodeArgs a);
+constexpr uint32_t kEncUnroll = 4;         // steps of 256 symbols a wavefront handles per iteration
+constexpr uint32_t kEncStepWordsMax = 468; // 256 code words of up to 58 bits, in 32-bit words, plus slack
+constexpr uint32_t kEncBufWords = 640;     // assembly buffer of a wavefront (ordinary code books fill a fraction of it)
+// S: symbols per chunk (64, 128, 256); FULLTBL: the whole encode table is in LDS
+template <int S, bool FULLTBL> __global__ void k_encode_count(EncodeArgs a);
+template <int S, bool FULLTBL> __global__ void k_encode_pack(EncodeArgs a);
 
 // ---- decode tables ------------------------------------------------------------
 constexpr int kLutBits = 11;

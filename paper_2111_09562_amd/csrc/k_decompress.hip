@@ -251,8 +251,7 @@ __global__ __launch_bounds__(kDsBlock) void k_decode_scan(DsArgs a) {
             const uint32_t n_words = w_end - w_begin;
             const uint32_t n_stage = n_words < kDsStageWords ? n_words : kDsStageWords;
             for (uint32_t i = lane; i < n_stage; i += kWave) stage[i] = payload[w_begin + i];
-            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
-            __builtin_amdgcn_wave_barrier();
+            wave_lds_fence();
             COMET_ACC(a.ctl, 12);
 
             // ---- 2. decode, one lane per chunk ----
@@ -269,8 +268,7 @@ __global__ __launch_bounds__(kDsBlock) void k_decode_scan(DsArgs a) {
                     else decode_chunk(payload + w_begin, last, w0, nsym, t, dst);           // too many for LDS: read them in place
                 }
             }
-            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
-            __builtin_amdgcn_wave_barrier();
+            wave_lds_fence();
             COMET_ACC(a.ctl, 13);
 
             // ---- 3. the strip's escaped residuals, compacted into LDS (reuses the stage) ----
@@ -298,8 +296,7 @@ __global__ __launch_bounds__(kDsBlock) void k_decode_scan(DsArgs a) {
                 }
                 rpos = r_end;
                 if (n_esc > kDsStageWords / 2u) esc_in_lds = false;
-                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
-                __builtin_amdgcn_wave_barrier();
+                wave_lds_fence();
             }
             COMET_ACC(a.ctl, 14);
 
@@ -375,7 +372,8 @@ __global__ __launch_bounds__(kDsBlock) void k_decode_scan(DsArgs a) {
 
             // ---- 5. verbatim values overwrite what was just stored ----
             if (has_verbatim) {
-                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "agent");      // the lattice values must have landed first
+                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");  // the lattice values of this wavefront must have landed first
+                // (workgroup scope waits for the stores; a wider scope would also write back and invalidate the L2)
                 for (uint32_t k = r_begin + lane; k < r_end; k += kWave) {
                     const uint32_t key = rec[2 * (size_t)k];
                     if (key & 1u) {
@@ -386,8 +384,7 @@ __global__ __launch_bounds__(kDsBlock) void k_decode_scan(DsArgs a) {
                     }
                 }
             }
-            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
-            __builtin_amdgcn_wave_barrier();
+            wave_lds_fence();
             COMET_ACC(a.ctl, 16);
         }
     }

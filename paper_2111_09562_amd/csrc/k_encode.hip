@@ -1,15 +1,24 @@
 // Chunked Huffman encode (COMET Sec. 4.1, last step of the modified cuSZ
-// pipeline).  One lane encodes one chunk of chunk_syms consecutive codes; a
-// workgroup of 256 lanes takes tiles of 256 chunks by ticket.
-//   stage : the tile's codes are copied global -> LDS with coalesced 16-byte
-//           loads, every chunk padded by 8 codes so that the per-lane 16-byte
-//           LDS reads that follow hit distinct banks;
-//   pass A: each lane sums the code lengths of its chunk -> 32-bit words;
-//   scan  : workgroup scan of the word counts + chained scan over tiles gives
-//           every chunk its word offset in the payload (deterministic layout);
-//   pass B: each lane packs its codes most-significant-bit first through a
-//           64-bit buffer and writes whole 32-bit words; the last word of a chunk
-//           is zero padded.
+// pipeline), wavefront-cooperative.  A wavefront takes 256 consecutive codes per
+// step, four per lane (one 8-byte load), so a chunk of 64 / 128 / 256 symbols is
+// a group of 16 / 32 / 64 adjacent lanes.  Every lane looks up (code word, length)
+// for its four codes; a DPP prefix sum of the lengths inside the lane group gives
+// the bit position of each code word inside its chunk; the lanes OR their pieces
+// into the chunk's words in LDS (most significant bit first); the words of the
+// step's chunks, contiguous in the payload, leave with one coalesced store.
+// No per-lane serial chain, coalesced input and output, 2 KB of LDS per wavefront.
+//
+// Placement is deterministic and needs no spinning: two kernels over the same
+// segmentation of the chunks (one workgroup per segment).
+//   k_encode_count: word count of every chunk (lengths only); per segment the
+//                   exclusive scan of its counts -> chunk_off (segment-relative)
+//                   and the segment's total.
+//   k_encode_pack : a segment's base is the sum of the totals of the segments in
+//                   front of it; chunk_off becomes absolute; the chunks are
+//                   encoded and written at their final place.
+// Neither kernel fences or counts finished workgroups: a device-scope release writes back and
+// invalidates the L2 of the issuing XCD, which costs far more than the kernel boundary that
+// orders these two kernels and the one that seals the container header.
 // The encode table ((code << 6) | length per symbol) is cached in LDS for the
 // bins around the centre; other symbols are looked up in global memory.
 #include "comet_kernels.h"
@@ -18,39 +27,140 @@ namespace comet {
 
 namespace {
 
+// FULL: the whole table is in LDS.  Keeping global loads out of that variant matters: a load
+// inside the loop would make every iteration wait for the stores of the previous one.
+template <bool FULL>
 struct TableView {
     const uint64_t *lds;
     const uint64_t *glob;
-    uint32_t lo, n;
+    uint32_t lo, n, nbins;
     __device__ inline uint64_t full(uint32_t code) const {
+        if (code >= nbins) code = 0;                     // cannot happen for codes made by the quantise kernel
+        if (FULL) return lds[code];
         const uint32_t i = code - lo;
         return (i < n) ? lds[i] : glob[code];
     }
-    __device__ inline uint32_t length(uint32_t code) const {
-        const uint32_t i = code - lo;
-        return (uint32_t)((i < n) ? reinterpret_cast<const uint32_t *>(lds)[2 * i] : (uint32_t)glob[code]) & 63u;
-    }
 };
+
+// inclusive prefix sum inside groups of LPC = 16, 32 or 64 adjacent lanes (DPP, no LDS)
+template <int LPC>
+__device__ inline uint32_t group_incl_scan(uint32_t v) {
+    int32_t x = (int32_t)v;
+    x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xf, 0xf, true);    // row_shr:1
+    x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xf, 0xf, true);    // row_shr:2
+    x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xf, 0xf, true);    // row_shr:4
+    x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xf, 0xf, true);    // row_shr:8
+    if (LPC >= 32) x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1, 3
+    if (LPC >= 64) x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2, 3
+    return (uint32_t)x;
+}
+
+// Four consecutive codes of this lane (symbols i0 .. i0+3) as two packed words; 0xffff marks
+// "past the end" (no code has that value: the alphabet has at most 65535 usable bins + escape 0,
+// and an out-of-range value is treated like any other invalid code by the caller).
+__device__ inline uint2 load4(const uint16_t *codes, uint64_t i0, uint64_t n) {
+    if (i0 + 4u <= n) return *reinterpret_cast<const uint2 *>(codes + i0);
+    uint32_t c[4];
+#pragma unroll
+    for (uint32_t j = 0; j < 4; ++j) c[j] = (i0 + j < n) ? (uint32_t)codes[i0 + j] : 0u;
+    return make_uint2(c[0] | (c[1] << 16), c[2] | (c[3] << 16));
+}
+__device__ inline uint32_t code_of(uint2 v, int j) {
+    const uint32_t w = (j < 2) ? v.x : v.y;
+    return (j & 1) ? (w >> 16) : (w & 0xffffu);
+}
+
+#ifdef COMET_DEBUG_TIMING
+#define ENC_DBG(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) a.ctl->dbg[i] = wall_clock64(); \
+                        if (threadIdx.x == 0 && blockIdx.x == gridDim.x - 1) a.ctl->dbg[16 + (i)] = wall_clock64(); } while (0)
+#else
+#define ENC_DBG(i) do {} while (0)
+#endif
 
 }  // namespace
 
-__global__ __launch_bounds__(kEncBlock) void k_encode(EncodeArgs a) {
+// ---------------------------------------------------------------------------
+template <int S, bool FULLTBL>
+__global__ __launch_bounds__(kEncBlock) void k_encode_count(EncodeArgs a) {
+    constexpr int LPC = S / 4;                       // lanes per chunk
+    constexpr int CPS = 256 / S;                     // chunks per wavefront step
     extern __shared__ uint64_t s_dyn_enc[];
-    uint64_t *s_tbl = s_dyn_enc;
-    uint16_t *s_stage = reinterpret_cast<uint16_t *>(s_dyn_enc + a.tbl_n);
-    __shared__ uint32_t s_tile;
-    __shared__ uint64_t s_base;
-    __shared__ uint32_t s_part[kEncBlock / kWave];
+    uint64_t *s_tbl = s_dyn_enc;                                           // a.tbl_n entries
+    uint32_t *s_cnt = reinterpret_cast<uint32_t *>(s_dyn_enc + a.tbl_n);   // a.seg_chunks word counts
+    __shared__ uint32_t s_part32[kEncBlock / kWave];
 
-    const int tid = threadIdx.x;
-    const int lane = lane_id();
-    const int wave = tid / kWave;
-    const uint32_t S = a.chunk_syms;
-    const uint32_t pitch = S + kEncPad;                 // u16 units
-    const uint32_t nbins = a.nbins;
-
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = (uint32_t)lane_id();
+    const uint32_t wave = tid / kWave;
+    ENC_DBG(0);
     for (uint32_t i = tid; i < a.tbl_n; i += kEncBlock) s_tbl[i] = a.enc[a.tbl_lo + i];
-    TableView tbl{s_tbl, a.enc, a.tbl_lo, a.tbl_n};
+    TableView<FULLTBL> tbl{s_tbl, a.enc, a.tbl_lo, a.tbl_n, a.nbins};
+    __syncthreads();
+    ENC_DBG(1);
+
+    const uint32_t seg = blockIdx.x;
+    const uint32_t c_lo = seg * a.seg_chunks;
+    const uint32_t c_hi = (c_lo + a.seg_chunks < a.n_chunks) ? c_lo + a.seg_chunks : a.n_chunks;
+    const uint32_t nc = c_hi - c_lo;                 // seg_chunks is a multiple of the chunks per step
+    const uint32_t steps = (nc + CPS - 1u) / CPS;
+    const uint32_t g = lane / LPC;                   // my chunk inside a step
+
+    // kEncUnroll steps per iteration, their loads issued together
+    for (uint32_t st0 = wave * kEncUnroll; st0 < steps; st0 += (kEncBlock / kWave) * kEncUnroll) {
+        uint2 v[kEncUnroll];
+#pragma unroll
+        for (uint32_t u = 0; u < kEncUnroll; ++u)
+            v[u] = (st0 + u < steps) ? load4(a.codes, (uint64_t)(c_lo + (st0 + u) * CPS) * S + lane * 4u, a.n) : make_uint2(0, 0);
+#pragma unroll
+        for (uint32_t u = 0; u < kEncUnroll; ++u) {
+            if (st0 + u >= steps) break;
+            const uint32_t c0 = c_lo + (st0 + u) * CPS;
+            const uint64_t i0 = (uint64_t)c0 * S + lane * 4u;
+            uint32_t bits = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t L = (uint32_t)tbl.full(code_of(v[u], j)) & 63u;
+                bits += (i0 + j < a.n) ? L : 0u;
+            }
+            const uint32_t incl = group_incl_scan<LPC>(bits);
+            if ((lane % LPC) == LPC - 1 && c0 + g < c_hi) s_cnt[c0 + g - c_lo] = (incl + 31u) >> 5;
+        }
+    }
+    __syncthreads();
+    ENC_DBG(2);
+
+    // counts -> segment-relative exclusive offsets, kEncBlock consecutive chunks at a time
+    uint32_t running = 0;
+    for (uint32_t base = 0; base < nc; base += kEncBlock) {
+        const uint32_t idx = base + tid;
+        const uint32_t cnt = (idx < nc) ? s_cnt[idx] : 0u;
+        uint32_t tot;
+        const uint32_t ex = block_excl_scan<uint32_t, kEncBlock / kWave>(cnt, s_part32, tot);
+        if (idx < nc) a.chunk_off[c_lo + idx] = running + ex;
+        running += tot;
+    }
+    if (tid == 0) a.desc[seg] = running;             // words of this segment
+    ENC_DBG(3);
+}
+
+// ---------------------------------------------------------------------------
+template <int S, bool FULLTBL>
+__global__ __launch_bounds__(kEncBlock) void k_encode_pack(EncodeArgs a) {
+    constexpr int LPC = S / 4;
+    constexpr int CPS = 256 / S;
+    extern __shared__ uint64_t s_dyn_enc[];
+    uint64_t *s_tbl = s_dyn_enc;                                           // a.tbl_n entries
+    uint32_t *s_buf = reinterpret_cast<uint32_t *>(s_dyn_enc + a.tbl_n);   // one assembly buffer per wavefront
+    __shared__ uint64_t s_part64[kEncBlock / kWave];
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = (uint32_t)lane_id();
+    const uint32_t wave = tid / kWave;
+    ENC_DBG(4);
+    for (uint32_t i = tid; i < a.tbl_n; i += kEncBlock) s_tbl[i] = a.enc[a.tbl_lo + i];
+    TableView<FULLTBL> tbl{s_tbl, a.enc, a.tbl_lo, a.tbl_n, a.nbins};
+    uint32_t *buf = s_buf + wave * kEncBufWords;
+    for (uint32_t i = lane; i < kEncBufWords; i += kWave) buf[i] = 0;
 
     uint32_t *payload;
     uint64_t cap_words;
@@ -63,129 +173,126 @@ __global__ __launch_bounds__(kEncBlock) void k_encode(EncodeArgs a) {
         cap_words = a.payload_cap_words;
     }
 
-    if (tid == 0) s_tile = atomicAdd(&a.ctl->ticket_e, 1u);
-    __syncthreads();
-    uint32_t tile = s_tile;
-    uint16_t *my_wave_stage = s_stage + (uint32_t)wave * kWave * pitch;
-    const uint16_t *my_stage = my_wave_stage + (uint32_t)lane * pitch;
+    const uint32_t seg = blockIdx.x;
+    const uint32_t c_lo = seg * a.seg_chunks;
+    const uint32_t c_hi = (c_lo + a.seg_chunks < a.n_chunks) ? c_lo + a.seg_chunks : a.n_chunks;
+    const uint32_t nc = c_hi - c_lo;
+    const uint32_t steps = (nc + CPS - 1u) / CPS;
+    const uint32_t g = lane / LPC;
 
-    while (tile < a.n_tiles) {
-        uint32_t next_tile = 0;
-        if (tid == 0) next_tile = atomicAdd(&a.ctl->ticket_e, 1u);
+    // words of all segments in front of mine
+    uint64_t sum = 0;
+    for (uint32_t idx = tid; idx < seg; idx += kEncBlock) sum += a.desc[idx];
+    uint64_t base;
+    (void)block_excl_scan<uint64_t, kEncBlock / kWave>(sum, s_part64, base);
+    bool overflow = false;
+    if (seg + 1u == gridDim.x && tid == 0) {
+        const uint64_t pw = base + a.desc[seg];
+        a.ctl->payload_words = pw;                    // the container header is sealed by the kernel that follows
+        if (a.payload_words_out) *a.payload_words_out = pw;
+        if (pw > 0xffffffffull) overflow = true;      // chunk offsets are 32-bit word indices
+    }
+    __syncthreads();                                  // table and buffers ready
+    ENC_DBG(5);
 
-        // ---- stage this wavefront's 64 chunks ----
-        const uint64_t chunk0 = (uint64_t)tile * kEncBlock + (uint64_t)wave * kWave;
-        const uint64_t sym_base = chunk0 * S;
-        const uint32_t pieces = 8u * S;                  // 16-byte pieces per wavefront (64 * S / 8)
-        for (uint32_t p = lane; p < pieces; p += kWave) {
-            const uint64_t sym0 = sym_base + 8ull * p;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (sym0 + 8u <= a.n) v = *reinterpret_cast<const uint4 *>(a.codes + sym0);
-            else if (sym0 < a.n) {
-                uint32_t w[4] = {0, 0, 0, 0};
-                for (uint32_t j = 0; j < 8u && sym0 + j < a.n; ++j) w[j >> 1] |= (uint32_t)a.codes[sym0 + j] << (16u * (j & 1u));
-                v = make_uint4(w[0], w[1], w[2], w[3]);
-            }
-            const uint32_t cl = (8u * p) >> a.log2_chunk;
-            const uint32_t within = (8u * p) & (S - 1u);
-            *reinterpret_cast<uint4 *>(my_wave_stage + cl * pitch + within) = v;
-        }
-        __syncthreads();
-
-        // ---- pass A: bits of my chunk ----
-        const uint64_t c = chunk0 + lane;
-        uint32_t nsym = 0;
-        if (c * S < a.n) { const uint64_t rem = a.n - c * S; nsym = rem < S ? (uint32_t)rem : S; }
-        uint32_t bits = 0;
-        for (uint32_t k = 0; k < S; k += 8) {
-            const uint4 v = *reinterpret_cast<const uint4 *>(my_stage + k);
-            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    // A wavefront handles kEncUnroll steps per iteration: their words are contiguous in the
+    // payload, so they are assembled side by side in the buffer and leave together.  The codes and
+    // the offset of an iteration are fetched one iteration ahead, before the stores of the current
+    // one are issued: memory operations retire in order, so a load issued after a store could not
+    // be consumed before that store has completed.
+    auto fetch = [&](uint32_t st0, uint2 (&v)[kEncUnroll], uint32_t &off) {
 #pragma unroll
-            for (uint32_t j = 0; j < 8; ++j) {
-                uint32_t code = (w[j >> 1] >> (16u * (j & 1u))) & 0xffffu;
-                if (code >= nbins) code = 0;
-                const uint32_t L = tbl.length(code);
-                bits += (k + j < nsym) ? L : 0u;
-            }
+        for (uint32_t u = 0; u < kEncUnroll; ++u)
+            v[u] = (st0 + u < steps) ? load4(a.codes, (uint64_t)(c_lo + (st0 + u) * CPS) * S + lane * 4u, a.n) : make_uint2(0, 0);
+        off = a.chunk_off[c_lo + st0 * CPS];
+    };
+    auto flush = [&](uint64_t off0, uint32_t n_words) {
+        wave_lds_fence();
+        for (uint32_t k = lane; k < n_words; k += kWave) {
+            const uint32_t word = buf[k];
+            buf[k] = 0;
+            if (off0 + k < cap_words) payload[off0 + k] = word;
+            else overflow = true;
         }
-        const uint32_t words = (bits + 31u) / 32u;
-        uint32_t tile_words;
-        const uint32_t excl = block_excl_scan<uint32_t, kEncBlock / kWave>(words, s_part, tile_words);
-        if (wave == 0) {
-            const uint64_t base = chained_scan_wave(a.desc, tile, tile_words, &a.ctl->status);
-            if (lane == 0) {
-                s_base = base;
-                if (tile + 1 == a.n_tiles) a.ctl->payload_words = base + tile_words;
-            }
-        }
-        __syncthreads();
-        const uint64_t off = s_base + excl;
-        if (c < a.n_chunks) {
-            if (off > 0xffffffffull) atomicOr(&a.ctl->status, (uint32_t)ST_CAPACITY);
-            a.chunk_off[c] = (uint32_t)off;
-        }
-
-        // ---- pass B: pack and write ----
-        if (nsym) {
-            uint64_t buf = 0;
-            uint32_t nb = 0;
-            uint64_t wpos = off;
-            bool overflow = false;
-            auto emit = [&](uint32_t word) {
-                if (wpos < cap_words) payload[wpos] = word;
-                else overflow = true;
-                ++wpos;
-            };
-            auto put = [&](uint64_t bitsv, uint32_t L) {   // 1 <= L <= 32, nb <= 31
-                buf |= bitsv << (64u - nb - L);
-                nb += L;
-                if (nb >= 32u) { emit((uint32_t)(buf >> 32)); buf <<= 32; nb -= 32u; }
-            };
-            for (uint32_t k = 0; k < S; k += 8) {
-                const uint4 v = *reinterpret_cast<const uint4 *>(my_stage + k);
-                const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        wave_lds_fence();
+    };
+    constexpr uint32_t kStride = (kEncBlock / kWave) * kEncUnroll;
+    uint32_t st0 = wave * kEncUnroll;
+    uint2 v_next[kEncUnroll];
+    uint32_t off_next = 0;
+    if (st0 < steps) fetch(st0, v_next, off_next);
+    for (; st0 < steps; st0 += kStride) {
+        uint2 v[kEncUnroll];
 #pragma unroll
-                for (uint32_t j = 0; j < 8; ++j) {
-                    if (k + j < nsym) {
-                        uint32_t code = (w[j >> 1] >> (16u * (j & 1u))) & 0xffffu;
-                        if (code >= nbins) code = 0;
-                        const uint64_t e = tbl.full(code);
-                        const uint32_t L = (uint32_t)(e & 63u);
-                        const uint64_t cw = e >> 6;
-                        if (L > 32u) { put(cw >> 32, L - 32u); put(cw & 0xffffffffull, 32u); }
-                        else if (L) put(cw, L);
-                    }
+        for (uint32_t u = 0; u < kEncUnroll; ++u) v[u] = v_next[u];
+        uint64_t off0 = base + off_next;
+        if (st0 + kStride < steps) fetch(st0 + kStride, v_next, off_next);
+        uint32_t wpos = 0;                           // words assembled in the buffer so far
+#pragma unroll
+        for (uint32_t u = 0; u < kEncUnroll; ++u) {
+            if (st0 + u >= steps) break;
+            const uint64_t i0 = (uint64_t)(c_lo + (st0 + u) * CPS) * S + lane * 4u;
+            uint64_t cw[4];
+            uint32_t len[4], bits = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint64_t e = tbl.full(code_of(v[u], j));
+                len[j] = (i0 + j < a.n) ? (uint32_t)(e & 63u) : 0u;
+                cw[j] = e >> 6;
+                bits += len[j];
+            }
+            const uint32_t incl = group_incl_scan<LPC>(bits);
+            // words of every chunk of the step, and where each chunk's words start inside the buffer
+            uint32_t wbase = 0, total_words = 0;
+#pragma unroll
+            for (int k = 0; k < CPS; ++k) {
+                const uint32_t wk = ((uint32_t)__builtin_amdgcn_readlane((int)incl, k * LPC + LPC - 1) + 31u) >> 5;
+                if ((uint32_t)k == g) wbase = total_words;
+                total_words += wk;
+            }
+            if (wpos + total_words + 4u > kEncBufWords) {       // only with very long code words
+                flush(off0, wpos);
+                off0 += wpos;
+                wpos = 0;
+            }
+            uint32_t p = (wpos + wbase) * 32u + incl - bits;   // bit position of my first code word inside the buffer
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t L = len[j];
+                if (L) {
+                    // the code word, left-aligned in 64 bits, then moved to bit p of the word stream
+                    const uint64_t t = cw[j] << (64u - L);
+                    const uint32_t sh = p & 31u, w = p >> 5;
+                    const uint64_t hi = t >> sh;
+                    atomicOr(&buf[w], (uint32_t)(hi >> 32));
+                    const uint32_t mid = (uint32_t)hi;
+                    if (mid) atomicOr(&buf[w + 1], mid);
+                    if (L + sh > 64u) atomicOr(&buf[w + 2], (uint32_t)((t << (64u - sh)) >> 32));   // codes longer than 32 bits only
                 }
+                p += L;
             }
-            if (nb) emit((uint32_t)(buf >> 32));
-            if (overflow) atomicOr(&a.ctl->status, (uint32_t)ST_CAPACITY);
+            wpos += total_words;
         }
-
-        if (tid == 0) s_tile = next_tile;
-        __syncthreads();
-        tile = s_tile;
+        flush(off0, wpos);
     }
-
-    // ---- the last workgroup to finish seals the container ----
-    __threadfence();
+    // chunk offsets become absolute (every wavefront has consumed the relative ones of its steps
+    // only after this barrier)
     __syncthreads();
-    if (tid == 0) {
-        const uint32_t prev = atomicAdd(&a.ctl->done_e, 1u);
-        if (prev == gridDim.x - 1u) {
-            __threadfence();
-            const uint64_t pw = __hip_atomic_load(&a.ctl->payload_words, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const uint32_t st = __hip_atomic_load(&a.ctl->status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (a.container) {
-                Header *h = reinterpret_cast<Header *>(a.container);
-                const uint64_t total = a.ctl->off_payload + 4ull * pw;
-                h->payload_words = pw;
-                h->total_bytes = total;
-                h->status = st ? 1u : 0u;
-                a.ctl->total_bytes = total;
-            }
-            if (a.payload_words_out) *a.payload_words_out = pw;
-        }
-    }
+    ENC_DBG(6);
+    for (uint32_t idx = tid; idx < nc; idx += kEncBlock) a.chunk_off[c_lo + idx] = (uint32_t)(base + a.chunk_off[c_lo + idx]);
+    if (overflow) atomicOr(&a.ctl->status, (uint32_t)ST_CAPACITY);
+
+    ENC_DBG(7);
 }
+
+#define COMET_INST_ENC(S)                                                  \
+    template __global__ void k_encode_count<S, true>(EncodeArgs);          \
+    template __global__ void k_encode_count<S, false>(EncodeArgs);         \
+    template __global__ void k_encode_pack<S, true>(EncodeArgs);           \
+    template __global__ void k_encode_pack<S, false>(EncodeArgs);
+COMET_INST_ENC(64)
+COMET_INST_ENC(128)
+COMET_INST_ENC(256)
+#undef COMET_INST_ENC
 
 }  // namespace comet
