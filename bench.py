@@ -5,7 +5,8 @@ A step = one pass of the whole hot path over the ResNet-50-shaped activation set
 (batch 64, five fp32 post-BN-ReLU tensors, 590.9 MB): compress every layer in
 forward order, keep the five containers, decompress them in reverse order.
 Inputs are resident in HBM before the timed region; all ten calls are enqueued
-asynchronously on one stream and the region ends with a synchronisation.
+asynchronously (the layers are dealt to --streams contexts, each on a stream of
+its own) and the region ends with a device synchronisation.
 
 Prints ONE JSON line: round-trip throughput in GB/s of fp32 input, the roofline
 figures of the dominant kernel (per-kernel durations from HIP events recorded by
@@ -32,7 +33,10 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--batch", type=int, default=64, help="batch of the activation set (64 = the metric's workload)")
-    ap.add_argument("--chunk-syms", type=int, default=128)
+    ap.add_argument("--chunk-syms", type=int, default=64)
+    ap.add_argument("--streams", type=int, default=2,
+                    help="contexts (each on its own stream) the layers are dealt to; the single-workgroup kernels of "
+                         "one layer then overlap the streaming kernels of another")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer table to stderr")
     args = ap.parse_args()
@@ -56,20 +60,28 @@ def main() -> int:
     n_total = sum(x.numel() for x in xs)
     in_bytes = 4 * n_total
 
-    ctx = comet.Context(max_elems=max(x.numel() for x in xs), max_nbins=1024)
-    ctx.comet_set_chunk_syms(args.chunk_syms)
+    n_ctx = max(1, min(args.streams, len(xs)))
+    ctxs = [comet.Context(max_elems=max(x.numel() for x in xs), max_nbins=1024) for _ in range(n_ctx)]
+    for c in ctxs:
+        c.comet_set_chunk_syms(args.chunk_syms)
+    # context 0 runs on torch's current stream, the others on streams of their own (default priority)
+    streams = [torch.cuda.current_stream()] + [torch.cuda.Stream() for _ in range(n_ctx - 1)]
+    owner = [i % n_ctx for i in range(len(xs))]            # layer -> context / stream
     # containers: 60 % of the input is ample for these tensors; a low ratio would raise COMET_ERR_CAPACITY
     conts = [torch.empty(int(x.numel() * 4 * 0.6) // 16 * 16, dtype=torch.uint8, device="cuda") for x in xs]
     outs = [torch.empty_like(x) for x in xs]
-    stream = torch.cuda.current_stream()
 
     def compress_all():
-        for x, e, c in zip(xs, layers, conts):
-            ctx.comet_compress(x, e["eb"], e["nbins"], c, stream=stream, sync=False)
+        for i, (x, e, c) in enumerate(zip(xs, layers, conts)):
+            ctxs[owner[i]].comet_compress(x, e["eb"], e["nbins"], c, stream=streams[owner[i]], sync=False)
 
     def decompress_all():
-        for x, c, o in reversed(list(zip(xs, conts, outs))):
-            ctx.comet_decompress(c, c.numel(), x.shape, o, stream=stream)
+        for i in reversed(range(len(xs))):
+            ctxs[owner[i]].comet_decompress(conts[i], conts[i].numel(), xs[i].shape, outs[i], stream=streams[owner[i]])
+
+    def sync_all():
+        for c, st in zip(ctxs, streams):
+            c.comet_sync(st)
 
     def step():
         compress_all()
@@ -77,8 +89,8 @@ def main() -> int:
 
     for _ in range(args.warmup):
         step()
-    ctx.comet_sync(stream)
-    sizes = [int(ctx.comet_peek(c, c.numel()).total_bytes) for c in conts]
+    sync_all()
+    sizes = [int(ctxs[0].comet_peek(c, c.numel()).total_bytes) for c in conts]
 
     # ---- the timed region: exactly K steps ----
     torch.cuda.synchronize()
@@ -87,7 +99,7 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    ctx.comet_sync(stream)
+    sync_all()                                     # raises if any call of the region reported an error
     ms_per_step = dt / args.steps * 1e3
     value = in_bytes / (dt / args.steps) / 1e9
 
@@ -101,19 +113,25 @@ def main() -> int:
         return (time.perf_counter() - t) / args.steps
     tc = timed(compress_all)
     td = timed(decompress_all)
-    ctx.comet_sync(stream)
+    sync_all()
 
     # ---- per-kernel durations: the same K steps again with the library's event brackets on ----
-    ctx.comet_profile_enable(True)
-    ctx.comet_profile_reset()
+    for c in ctxs:
+        c.comet_profile_enable(True)
+        c.comet_profile_reset()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     kern = {}
     for kid, name in enumerate(comet.KERNEL_NAMES):
-        launches, ms = ctx.comet_profile_read(kid)
+        launches, ms = 0, 0.0
+        for c in ctxs:
+            l, m = c.comet_profile_read(kid)
+            launches += l
+            ms += m
         kern[name] = dict(launches=launches, total_ms=ms, avg_us=(ms / launches * 1e3 if launches else 0.0))
-    ctx.comet_profile_enable(False)
+    for c in ctxs:
+        c.comet_profile_enable(False)
 
     cont_bytes = sum(sizes)
     b = cont_bytes / n_total                       # container bytes per element
@@ -165,10 +183,12 @@ def main() -> int:
                 scaling="weak", vs_baseline=None, dtype="f32", data="synthetic",
                 config=dict(workload=f"ResNet-50-shaped activation set, batch {args.batch}: compress 5 layers forward, "
                                      f"decompress reverse; eb per layer {[e['eb'] for e in layers]}, 1024 bins, "
-                                     f"chunk {args.chunk_syms}", elements=n_total, input_bytes=in_bytes),
+                                     f"chunk {args.chunk_syms}; layers dealt to {n_ctx} contexts/streams", elements=n_total,
+                            input_bytes=in_bytes),
                 roofline=roofline, cpu_baseline=cpu, path=path)
     print(json.dumps(line))
-    ctx.close()
+    for c in ctxs:
+        c.close()
     return 0
 
 

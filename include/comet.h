@@ -155,14 +155,17 @@ int comet_stage_reconstruct(comet_ctx *ctx, const uint16_t *dev_codes, const uin
  * recorded on the call's stream.  comet_profile_read waits for those events and
  * returns, for kernel `kernel_id`, the number of launches since the last
  * comet_profile_reset and their summed duration in milliseconds.  Kernel ids:
- * 0 quantize, 1 codebook, 2 encode, 3 decode tables, 4 decode+reconstruct.
+ * 0 quantize, 1 codebook, 2 encode (count + pack), 3 decode tables,
+ * 4 reconstruct (scans + store; for planes wider than 512 columns the fused
+ * decode + reconstruct kernel), 5 Huffman decode.
  * At most 16384 launches are kept between resets; further ones are not timed. */
 #define COMET_KERNEL_QUANTIZE 0
 #define COMET_KERNEL_CODEBOOK 1
 #define COMET_KERNEL_ENCODE 2
 #define COMET_KERNEL_TABLES 3
 #define COMET_KERNEL_RECONSTRUCT 4
-#define COMET_KERNEL_COUNT 5
+#define COMET_KERNEL_DECODE 5
+#define COMET_KERNEL_COUNT 6
 int comet_profile_enable(comet_ctx *ctx, int enable);
 int comet_profile_reset(comet_ctx *ctx);
 int comet_profile_read(comet_ctx *ctx, uint32_t kernel_id, uint32_t *launches /* host */, double *total_ms /* host */);

@@ -23,7 +23,7 @@ EXPORTS = (
     "comet_stage_quantize", "comet_stage_codebook", "comet_stage_encode", "comet_stage_decode",
     "comet_stage_reconstruct", "comet_profile_enable", "comet_profile_reset", "comet_profile_read", "comet_strerror",
 )
-KERNEL_NAMES = ("k_quantize", "k_codebook", "k_encode", "k_decode_tables", "k_reconstruct")
+KERNEL_NAMES = ("k_quantize", "k_codebook", "k_encode", "k_decode_tables", "k_reconstruct", "k_decode")
 
 
 class Shape(C.Structure):

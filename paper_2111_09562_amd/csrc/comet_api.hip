@@ -308,14 +308,6 @@ int comet_create(comet_ctx **out, uint64_t max_elems, uint32_t max_nbins) {
         return fail(hip_fail(e, "hipFuncSetAttribute(k_reconstruct<0>)"));
     if ((e = hipFuncSetAttribute((const void *)k_reconstruct<1>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024)) != hipSuccess)
         return fail(hip_fail(e, "hipFuncSetAttribute(k_reconstruct<1>)"));
-    {
-        const int lds = (int)((size_t)kDsWaves * (kDsTileEntries / 2u + kDsStageWords) * 4u);
-        const void *fns[] = {(const void *)k_decode_scan<1, 0>, (const void *)k_decode_scan<1, 1>, (const void *)k_decode_scan<1, 2>,
-                             (const void *)k_decode_scan<2, 2>, (const void *)k_decode_scan<4, 2>, (const void *)k_decode_scan<8, 2>};
-        for (const void *fn : fns)
-            if ((e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds)) != hipSuccess)
-                return fail(hip_fail(e, "hipFuncSetAttribute(k_decode_scan)"));
-    }
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&c->occ_quant, k_quantize<true>, kQuantBlock, 4096 + kQuantRecLds * 8) != hipSuccess || c->occ_quant < 1) c->occ_quant = 4;
     (void)rc;
     *out = c;
@@ -436,28 +428,42 @@ int comet_decompress(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_s
         }
         HIP_TRY(hipGetLastError());
     }
-    if (s.w <= kDsMaxW) {
-        // fast path: one wavefront per strip, geometry derived on the device from the header
+    // lanes of a wavefront side by side in one row of the scan kernel (planes x columns)
+    const uint32_t ppi = s.w <= 16u ? 4u * (16u / s.w) : (s.w <= 32u ? 2u : 1u);
+    if (s.w <= kDsMaxW && (uint64_t)ppi * s.h * s.w < (1ull << 28)) {
+        // fast path: Huffman decode into int16 residuals (the code buffer of the context doubles as
+        // the work buffer), then scans and stores
         DsArgs d{};
         d.container = in; d.t = ctx->tables; d.n = n; d.planes = s.n * s.c; d.H = s.h; d.W = s.w; d.divW = make_fastdiv(s.w);
-        d.out = dev_out; d.ctl = &ctx->state->ctl;
-        const size_t lds = (size_t)kDsWaves * (kDsTileEntries / 2u + kDsStageWords) * 4u;
-        // grid: about one wavefront per unit (estimated with the context's chunk size), a few per CU at most
-        const uint64_t emax = (uint64_t)(kDsTileEntries / (ctx->chunk_syms + 2u) - 1u) * ctx->chunk_syms;
+        d.resid = reinterpret_cast<int16_t *>(ctx->codes); d.out = dev_out; d.ctl = &ctx->state->ctl;
+        {
+            // groups of 64 chunks, one per wavefront at a time; the same number of groups for every
+            // wavefront of a grid that is resident at once (estimated with the context's chunk size)
+            const uint64_t groups = (n + (uint64_t)ctx->chunk_syms * kWave - 1) / ((uint64_t)ctx->chunk_syms * kWave);
+            const uint64_t resident = (uint64_t)ctx->num_cu * 4u * kDsWaves;
+            const uint64_t per_wave = (groups + resident - 1) / resident;
+            const uint64_t waves = (groups + per_wave - 1) / per_wave;
+            const uint32_t grid = (uint32_t)((waves + kDsWaves - 1) / kDsWaves);
+            TimedScope ts(ctx, st, COMET_KERNEL_DECODE);
+            hipLaunchKernelGGL(k_decode_chunks, dim3(grid), dim3(kDsBlock), (size_t)kDsWaves * kDsStageWords * 4u, st, d);
+        }
+        HIP_TRY(hipGetLastError());
         const uint64_t P = (uint64_t)s.h * s.w;
-        const uint64_t units = (P <= emax) ? ((uint64_t)d.planes + emax / P - 1) / (emax / P) : d.planes;
+        uint64_t G = 1;
+        if (s.w <= 32u) { const uint64_t fit = kScanStripElems / (ppi * P); G = ppi * (fit ? fit : 1u); }
+        const uint64_t units = ((uint64_t)d.planes + G - 1) / G;
         uint64_t grid = (units + kDsWaves - 1) / kDsWaves;
-        const uint64_t cap = (uint64_t)ctx->num_cu * 16u;
+        const uint64_t cap = (uint64_t)ctx->num_cu * 8u;
         if (grid > cap) grid = cap;
-        if (grid < 1) grid = 1;
+        const size_t lds = (size_t)kDsWaves * kScanListWords * 4u;
         TimedScope ts(ctx, st, COMET_KERNEL_RECONSTRUCT);
         const dim3 g3((uint32_t)grid), b3(kDsBlock);
-        if (s.w <= 16u) hipLaunchKernelGGL((k_decode_scan<1, 0>), g3, b3, lds, st, d);
-        else if (s.w <= 32u) hipLaunchKernelGGL((k_decode_scan<1, 1>), g3, b3, lds, st, d);
-        else if (s.w <= 64u) hipLaunchKernelGGL((k_decode_scan<1, 2>), g3, b3, lds, st, d);
-        else if (s.w <= 128u) hipLaunchKernelGGL((k_decode_scan<2, 2>), g3, b3, lds, st, d);
-        else if (s.w <= 256u) hipLaunchKernelGGL((k_decode_scan<4, 2>), g3, b3, lds, st, d);
-        else hipLaunchKernelGGL((k_decode_scan<8, 2>), g3, b3, lds, st, d);
+        if (s.w <= 16u) hipLaunchKernelGGL((k_scan_store<1, 0>), g3, b3, lds, st, d);
+        else if (s.w <= 32u) hipLaunchKernelGGL((k_scan_store<1, 1>), g3, b3, lds, st, d);
+        else if (s.w <= 64u) hipLaunchKernelGGL((k_scan_store<1, 2>), g3, b3, lds, st, d);
+        else if (s.w <= 128u) hipLaunchKernelGGL((k_scan_store<2, 2>), g3, b3, lds, st, d);
+        else if (s.w <= 256u) hipLaunchKernelGGL((k_scan_store<4, 2>), g3, b3, lds, st, d);
+        else hipLaunchKernelGGL((k_scan_store<8, 2>), g3, b3, lds, st, d);
     } else {
         ReconArgs a{};
         a.container = in; a.t = ctx->tables; a.n = n; a.planes = s.n * s.c; a.H = s.h; a.W = s.w; a.divW = make_fastdiv(s.w);

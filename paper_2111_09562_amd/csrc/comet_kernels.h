@@ -148,13 +148,14 @@ struct ReconArgs {
 template <int MODE> __global__ void k_reconstruct(ReconArgs a);   // 0 container, 1 codes from memory
 __global__ void k_decode_only(ReconArgs a);
 
-// ---- decode + reconstruct, fast path (planes up to 512 columns) ----------------
-constexpr int kDsWaves = 4;                           // wavefronts per workgroup, each on its own strip
+// ---- decode + reconstruct, fast path (planes up to 512 columns): two kernels ------
+constexpr int kDsWaves = 4;                           // wavefronts per workgroup, each working on its own
 constexpr int kDsBlock = kDsWaves * kWave;
-constexpr uint32_t kDsTileEntries = 64u * 66u;        // int16 residuals per wavefront: 64 chunks of 64 + 2 padding
-constexpr uint32_t kDsStageWords = 1536u;             // Huffman words (later: escape records) per wavefront
+constexpr uint32_t kDsStageWords = 1536u;             // decode: Huffman words of 64 chunks per wavefront (LDS)
 constexpr uint32_t kDsMaxW = 512u;
-constexpr uint32_t kDsTailEntries = 1024u;           // residuals of long codes kept in LDS
+constexpr uint32_t kDsTailEntries = 1024u;            // decode: residuals of long codes kept in LDS
+constexpr uint32_t kScanListWords = 1024u;            // scan: escape list of a strip per wavefront (pairs) (LDS)
+constexpr uint32_t kScanStripElems = 4096u;           // scan: elements per strip (unit of the escape list)
 
 struct DsArgs {
     const uint8_t *container;
@@ -162,9 +163,11 @@ struct DsArgs {
     uint64_t n;
     uint32_t planes, H, W;
     FastDiv divW;
+    int16_t *resid;            // work buffer: one int16 residual per element (-32768 = escaped)
     float *out;
     Control *ctl;
 };
-template <int NSEG, int MODE> __global__ void k_decode_scan(DsArgs a);   // NSEG = ceil(W / 64) rounded up to 1, 2, 4, 8
+__global__ void k_decode_chunks(DsArgs a);
+template <int NSEG, int MODE> __global__ void k_scan_store(DsArgs a);   // NSEG = ceil(W / 64) rounded up to 1, 2, 4, 8
 
 }  // namespace comet

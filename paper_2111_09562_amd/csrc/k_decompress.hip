@@ -1,21 +1,26 @@
-// Fused decompression, fast path (COMET Sec. 3.4 / Sec. 4.1 run backwards) for
-// planes up to 512 columns wide: chunk-parallel Huffman decode -> Lorenzo
-// reconstruction -> dequantise -> verbatim values -> re-zero filter -> store.
+// Decompression, fast path (COMET Sec. 3.4 / Sec. 4.1 run backwards) for planes
+// up to 512 columns wide, as two streaming kernels:
 //
-// Every wavefront works on its own: it takes a unit (a group of whole planes, or
-// one plane cut into strips of rows), and for every strip
-//   1. copies the strip's Huffman words global -> LDS with coalesced loads;
-//   2. decodes: one lane per chunk, a 64-bit bit buffer per lane refilled from
-//      LDS (two words of look-ahead so that no load sits on the critical path),
-//      an 11-bit look-up table whose entries already hold the residual
-//      (code - radius); residuals go to an int16 tile in LDS, every chunk padded
-//      by one dword so that the 64 lanes hit 64 different banks;
-//   3. scans: lanes become columns.  Row by row the wavefront reads 64 residuals,
-//      forms the row prefix with a DPP scan (no LDS, no barrier), adds it to the
-//      per-column running sum held in a register (the column prefix), multiplies
-//      by 2*eb, applies the re-zero filter and stores fp32.
-// Escaped residuals (code 0) sit in the tile as -32768 and are replaced, in
-// element order, from the strip's outlier records (copied to LDS once per strip).
+//   k_decode_chunks: chunk-parallel Huffman decode.  A wavefront takes 64
+//     consecutive chunks, copies their words global -> LDS with coalesced loads and
+//     decodes one chunk per lane: a 64-bit bit buffer per lane refilled from LDS
+//     (two words of look-ahead so that no load sits on the critical path) and an
+//     11-bit look-up table whose entries already hold the residual (code - radius).
+//     Eight residuals are packed into 16 bytes and stored as int16 into a work
+//     buffer.  The kernel needs about 9 KB of LDS per wavefront, so four
+//     wavefronts per SIMD hide the latency of the serial decode chain.
+//
+//   k_scan_store: Lorenzo reconstruction -> dequantise -> verbatim values ->
+//     re-zero filter -> store.  Lanes are columns.  Row by row a wavefront reads 64
+//     residuals (buffer loads, several rows in flight), forms the row prefix with a
+//     DPP scan (no LDS, no barrier), adds it to the per-column running sum held in
+//     a register (the column prefix), multiplies by 2*eb, applies the re-zero
+//     filter and stores fp32.  Loads and stores use buffer addressing: a lane that
+//     has no element gets an out-of-range offset, which the hardware ignores, so
+//     the loop has no divergent branches and the compiler can count the memory
+//     operations in flight instead of draining them.
+// Escaped residuals (code 0) sit in the work buffer as -32768 and are replaced, in
+// element order, from the outlier records (copied to LDS once per strip).
 #include <type_traits>
 
 #include "comet_kernels.h"
@@ -51,18 +56,24 @@ __device__ inline int32_t decode_long(uint64_t win, const DsTables &t, uint32_t 
     return sym ? (int32_t)sym - t.radius : kEscape;
 }
 
-// Decode `nsym` symbols of one chunk into dst[0..nsym).  Words are read from
-// words[min(i, last)]; the chunk starts at word index w0.
-// Bit buffer: `buf` holds the next bits left-aligned with more than 32 of them
-// valid; nw0 / nw1 are the two words after it.  Everything in the loop is
-// branch-free except the wavefront-uniform test for a long code.
-__device__ inline void decode_chunk(const uint32_t *words, uint32_t last, uint32_t w0, uint32_t nsym, const DsTables &t, int16_t *dst) {
-    auto word = [&](uint32_t i) -> uint32_t { return words[i < last ? i : last]; };
-    uint64_t buf = ((uint64_t)word(w0) << 32) | word(w0 + 1);
-    uint32_t nb = 64;
-    uint32_t nw0 = word(w0 + 2), nw1 = word(w0 + 3);
-    uint32_t wp = w0 + 3;                       // index of nw1
-    for (uint32_t k = 0; k < nsym; ++k) {
+// Bit buffer of one lane: `buf` holds the next bits left-aligned with more than
+// 32 of them valid; nw0 / nw1 are the two words after it.  Words are read from
+// words[min(i, last)].  Everything in next() is branch-free except the
+// wavefront-uniform test for a long code.
+struct BitBuf {
+    const uint32_t *words;
+    uint32_t last;
+    uint64_t buf;
+    uint32_t nb, nw0, nw1, wp;
+    __device__ inline uint32_t word(uint32_t i) const { return words[i < last ? i : last]; }
+    __device__ inline void open(const uint32_t *w, uint32_t last_, uint32_t w0) {
+        words = w; last = last_;
+        buf = ((uint64_t)word(w0) << 32) | word(w0 + 1);
+        nb = 64;
+        nw0 = word(w0 + 2); nw1 = word(w0 + 3);
+        wp = w0 + 3;                            // index of nw1
+    }
+    __device__ inline int32_t next(const DsTables &t) {
         const uint32_t e = t.lut[(uint32_t)(buf >> (64 - kLutBits))];
         uint32_t L = e & 0xffu;
         int32_t d = (int32_t)e >> 8;
@@ -79,7 +90,6 @@ __device__ inline void decode_chunk(const uint32_t *words, uint32_t last, uint32
                 }
             }
         }
-        dst[k] = (int16_t)d;
         buf <<= L;
         nb -= L;
         // refill: below 33 valid bits the next word moves in
@@ -90,7 +100,31 @@ __device__ inline void decode_chunk(const uint32_t *words, uint32_t last, uint32
         nw0 = need ? nw1 : nw0;
         wp += need ? 1u : 0u;
         nw1 = word(wp);
+        return d;
     }
+};
+
+// Decode the first `nsym` symbols of one chunk into dst[0 .. nsym) (int16).  When the chunk size
+// is a multiple of eight (dst is then 16-byte aligned) the residuals leave as 16-byte stores.
+__device__ inline void decode_chunk(const uint32_t *words, uint32_t last, uint32_t w0, uint32_t S, uint32_t nsym, const DsTables &t, int16_t *dst) {
+    BitBuf bb;
+    bb.open(words, last, w0);
+    uint32_t k = 0;
+    if ((S & 7u) == 0u) {
+        uint4 *dst16 = reinterpret_cast<uint4 *>(dst);
+        for (uint32_t k8 = 0; k8 < nsym / 8u; ++k8) {
+            uint32_t pk[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t d0 = (uint32_t)bb.next(t) & 0xffffu;
+                const uint32_t d1 = (uint32_t)bb.next(t);
+                pk[j] = (d1 << 16) | d0;
+            }
+            dst16[k8] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+        }
+        k = nsym & ~7u;
+    }
+    for (; k < nsym; ++k) dst[k] = (int16_t)bb.next(t);     // chunk sizes that are no multiple of eight; the tensor's last chunk
 }
 
 // ---- DPP: value of another lane of the same 16-lane row (0 where there is none) ----
@@ -135,14 +169,16 @@ __device__ inline uint32_t rec_lower_bound(const uint32_t *rec, uint32_t lo, uin
     return lo;
 }
 
+// buffer descriptor over [p, p + bytes): accesses at offsets >= bytes are dropped (loads give 0)
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
+}
+
 }  // namespace
 
-// NSEG: 64-column segments per row.  MODE (how the lanes of a wavefront map to columns):
-// 0: W <= 16, 16/W planes side by side in every 16-lane row; 1: W <= 32, one plane per 32-lane
-// half; 2: one plane, columns = lanes.
-template <int NSEG, int MODE>
-__global__ __launch_bounds__(kDsBlock) void k_decode_scan(DsArgs a) {
-    extern __shared__ uint32_t s_dyn_ds[];
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kDsBlock) void k_decode_chunks(DsArgs a) {
+    extern __shared__ uint32_t s_dyn_ds[];                  // kDsWaves x kDsStageWords: the words of 64 chunks per wavefront
     __shared__ uint32_t s_lut[kLutSize];
     __shared__ uint64_t s_limit[65];
     __shared__ uint64_t s_first[65];
@@ -153,18 +189,14 @@ __global__ __launch_bounds__(kDsBlock) void k_decode_scan(DsArgs a) {
 
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = (uint32_t)lane_id();
-    const uint32_t wave = tid / kWave;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / kWave));
 
     const Header *hdr = reinterpret_cast<const Header *>(a.container);
     const uint32_t *chunk_off = reinterpret_cast<const uint32_t *>(a.container + hdr->off_chunk);
-    const uint32_t *rec = reinterpret_cast<const uint32_t *>(a.container + hdr->off_outlier);
     const uint32_t *payload = reinterpret_cast<const uint32_t *>(a.container + hdr->off_payload);
     const uint32_t payload_words = (uint32_t)hdr->payload_words;
-    const uint32_t n_rec = hdr->n_rec;
     const uint32_t S = hdr->chunk_syms;
     const uint32_t n_chunks = hdr->n_chunks;
-    const float eb = __uint_as_float(hdr->eb_bits);
-    const float ebx2 = __uint_as_float(hdr->ebx2_bits);
 
     for (uint32_t i = tid; i < kLutSize; i += kDsBlock) s_lut[i] = a.t.lut[i];
     for (uint32_t i = tid; i < 65u; i += kDsBlock) { s_limit[i] = a.t.limit[i]; s_first[i] = a.t.first_code[i]; s_findex[i] = a.t.first_index[i]; }
@@ -181,25 +213,65 @@ __global__ __launch_bounds__(kDsBlock) void k_decode_scan(DsArgs a) {
     }
     __syncthreads();
 
-    // per-wavefront LDS: residual tile (int16), then the word stage / escape list
-    uint32_t *my = s_dyn_ds + wave * (kDsTileEntries / 2u + kDsStageWords);
-    int16_t *tile = reinterpret_cast<int16_t *>(my);
-    uint32_t *stage = my + kDsTileEntries / 2u;
+    uint32_t *stage = s_dyn_ds + wave * kDsStageWords;
+    const uint32_t n_groups = (n_chunks + kWave - 1u) / kWave;
+    for (uint32_t grp = blockIdx.x * kDsWaves + wave; grp < n_groups; grp += gridDim.x * kDsWaves) {
+        const uint32_t c_lo = grp * kWave;
+        const uint32_t c_hi = (n_chunks - c_lo < (uint32_t)kWave) ? n_chunks : c_lo + kWave;
+        const uint32_t c = c_lo + lane;
 
-    // ---- geometry (depends on the chunk size, which only the header knows) ----
+        // ---- the group's words: one round trip for the offsets, one for the words ----
+        uint32_t my_off = 0;
+        if (c < c_hi) my_off = chunk_off[c];
+        uint32_t w_end = (c_hi < n_chunks) ? chunk_off[c_hi] : payload_words;
+        uint32_t w_begin = (uint32_t)__builtin_amdgcn_readfirstlane((int)my_off);
+        if (w_end > payload_words) w_end = payload_words;
+        if (w_begin > w_end) w_begin = w_end;
+        const uint32_t n_words = w_end - w_begin;
+        const bool all_staged = n_words <= kDsStageWords;
+        if (all_staged) {
+            for (uint32_t i = lane; i < n_words; i += kWave) stage[i] = payload[w_begin + i];
+        }
+        wave_lds_fence();
+
+        // ---- decode, one lane per chunk ----
+        if (c < c_hi && n_words) {
+            uint32_t w0 = (my_off < w_begin) ? 0u : my_off - w_begin;
+            const uint64_t s0 = (uint64_t)c * S;
+            const uint32_t nsym = (a.n - s0 < (uint64_t)S) ? (uint32_t)(a.n - s0) : S;
+            int16_t *dst = a.resid + s0;
+            if (all_staged) decode_chunk(stage, n_words - 1u, w0, S, nsym, t, dst);          // words in LDS
+            else decode_chunk(payload + w_begin, n_words - 1u, w0, S, nsym, t, dst);         // too many for LDS: read them in place
+        }
+        wave_lds_fence();
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// NSEG: 64-column segments per row.  MODE (how the lanes of a wavefront map to columns):
+// 0: W <= 16, 16/W planes side by side in every 16-lane row; 1: W <= 32, one plane per 32-lane
+// half; 2: one plane, columns = lanes.
+template <int NSEG, int MODE>
+__global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
+    extern __shared__ uint32_t s_dyn_ds[];                  // kDsWaves x kScanListWords: escape list of a wavefront's strip
+
+    if (a.ctl->status & ST_FORMAT) return;
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = (uint32_t)lane_id();
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / kWave));
+
+    const Header *hdr = reinterpret_cast<const Header *>(a.container);
+    const uint32_t *rec = reinterpret_cast<const uint32_t *>(a.container + hdr->off_outlier);
+    const uint32_t n_rec = hdr->n_rec;
+    const float eb = __uint_as_float(hdr->eb_bits);
+    const float ebx2 = __uint_as_float(hdr->ebx2_bits);
+    uint32_t *list = s_dyn_ds + wave * kScanListWords;       // pairs (element offset inside the strip, residual)
+    constexpr uint32_t kListCap = kScanListWords / 2u;
+
+    // ---- geometry ----
     const uint32_t W = a.W, H = a.H, P = H * W;
-    const uint32_t n = (uint32_t)a.n;
-    const uint32_t pitch = S + 2u;                               // tile entries per chunk
-    const bool pow2 = (S & (S - 1u)) == 0u;
-    const uint32_t log2S = pow2 ? (uint32_t)(31 - __clz((int)S)) : 0u;
-    const uint32_t cps = kDsTileEntries / pitch;                 // chunks that fit the tile
-    const uint32_t emax = cps >= 2u ? (cps - 1u) * S : 0u;       // elements per strip, whatever its alignment
-    if (emax < W) { if (tid == 0) atomicOr(&a.ctl->status, (uint32_t)ST_FORMAT); return; }
-    const bool group_mode = P <= emax;
-    const uint32_t G = group_mode ? emax / P : 1u;               // planes per unit
-    const uint32_t R = group_mode ? H : emax / W;                // rows per strip
-    const uint32_t n_units = group_mode ? (a.planes + G - 1u) / G : a.planes;
-
+    constexpr bool group_mode = MODE != 2;                    // small planes: groups of whole planes; else one plane in strips of rows
     // lanes -> (plane slot, column).  W <= 16: 16/W slots per 16-lane row; W <= 32: one slot per
     // 32-lane half; wider: one slot, NSEG segments of 64 columns.
     uint32_t ppi = 1, slot = 0, wl = lane;
@@ -216,62 +288,35 @@ __global__ __launch_bounds__(kDsBlock) void k_decode_scan(DsArgs a) {
         lane_on = lane < W;
     }
     const uint64_t lt_mask = (1ull << lane) - 1ull;
+    uint32_t G = 1;                                           // planes per unit
+    if (group_mode) {
+        const uint32_t fit = kScanStripElems / (ppi * P);     // passes of ppi planes in about kScanStripElems elements
+        G = ppi * (fit ? fit : 1u);
+    }
+    const uint32_t R = group_mode ? H : (kScanStripElems / W ? kScanStripElems / W : 1u);   // rows per strip
+    const uint32_t n_units = (a.planes + G - 1u) / G;
 
-    const uint32_t gw = blockIdx.x * kDsWaves + wave;
-    const uint32_t n_gw = gridDim.x * kDsWaves;
+    // rows handled per batch of loads: about eight row segments in flight per batch, two batches
+    constexpr uint32_t U = NSEG >= 8 ? 1u : 8u / NSEG;
 
-    COMET_ACC_DECL;
-    for (uint32_t unit = gw; unit < n_units; unit += n_gw) {
-        COMET_ACC(a.ctl, 10);
-        const uint32_t p0 = group_mode ? unit * G : unit;
-        const uint32_t planes_here = group_mode ? ((a.planes - p0 < G) ? a.planes - p0 : G) : 1u;
+    for (uint32_t unit = blockIdx.x * kDsWaves + wave; unit < n_units; unit += gridDim.x * kDsWaves) {
+        const uint32_t p0 = unit * G;
+        const uint32_t planes_here = (a.planes - p0 < G) ? a.planes - p0 : G;
         const uint32_t e_unit = p0 * P;
         uint32_t rpos = 0;
         if (n_rec) rpos = rec_lower_bound(rec, 0, n_rec, 2u * e_unit, lane);
         int32_t q[NSEG];
 #pragma unroll
         for (int s = 0; s < NSEG; ++s) q[s] = 0;
-        COMET_ACC(a.ctl, 11);
 
         for (uint32_t row0 = 0; row0 < H; row0 += R) {
             const uint32_t rows = (H - row0 < R) ? H - row0 : R;
             const uint32_t e0 = e_unit + row0 * W;
             const uint32_t e1 = group_mode ? e_unit + planes_here * P : e0 + rows * W;
-            const uint32_t c_lo = e0 / S;
-            uint32_t c_hi = (e1 - 1u) / S + 1u;
-            if (c_hi > n_chunks) c_hi = n_chunks;
+            const __amdgpu_buffer_rsrc_t r_in = make_rsrc(a.resid + e0, (e1 - e0) * 2u);
+            const __amdgpu_buffer_rsrc_t r_out = make_rsrc(a.out + e0, (e1 - e0) * 4u);
 
-            // ---- 1. stage the strip's words (one round trip for the offsets, one for the words) ----
-            uint32_t my_off = 0;                                  // word offset of chunk c_lo + lane
-            if (c_lo + lane < c_hi) my_off = chunk_off[c_lo + lane];
-            uint32_t w_end = (c_hi < n_chunks) ? chunk_off[c_hi] : payload_words;
-            uint32_t w_begin = (uint32_t)__builtin_amdgcn_readfirstlane((int)my_off);
-            if (w_end > payload_words) w_end = payload_words;
-            if (w_begin > w_end) w_begin = w_end;
-            const uint32_t n_words = w_end - w_begin;
-            const uint32_t n_stage = n_words < kDsStageWords ? n_words : kDsStageWords;
-            for (uint32_t i = lane; i < n_stage; i += kWave) stage[i] = payload[w_begin + i];
-            wave_lds_fence();
-            COMET_ACC(a.ctl, 12);
-
-            // ---- 2. decode, one lane per chunk ----
-            const bool all_staged = n_words <= kDsStageWords;
-            const uint32_t last = n_words ? n_words - 1u : 0u;
-            if (n_words) {
-                for (uint32_t c = c_lo + lane; c < c_hi; c += kWave) {
-                    uint32_t w0 = (c == c_lo + lane) ? my_off : chunk_off[c];
-                    w0 = (w0 < w_begin) ? 0u : w0 - w_begin;
-                    const uint32_t s0 = c * S;
-                    const uint32_t nsym = (n - s0 < S) ? n - s0 : S;
-                    int16_t *dst = tile + (c - c_lo) * pitch;
-                    if (all_staged) decode_chunk(stage, last, w0, nsym, t, dst);            // words in LDS
-                    else decode_chunk(payload + w_begin, last, w0, nsym, t, dst);           // too many for LDS: read them in place
-                }
-            }
-            wave_lds_fence();
-            COMET_ACC(a.ctl, 13);
-
-            // ---- 3. the strip's escaped residuals, compacted into LDS (reuses the stage) ----
+            // ---- the strip's escaped residuals, compacted into LDS ----
             const uint32_t r_begin = rpos;
             uint32_t r_end = rpos;
             uint32_t n_esc = 0;          // type-0 records of the strip
@@ -280,7 +325,6 @@ __global__ __launch_bounds__(kDsBlock) void k_decode_scan(DsArgs a) {
                 const uint32_t span = 2u * (e1 - e0);             // at most two records per element
                 const uint32_t hi = (n_rec - rpos < span) ? n_rec : rpos + span;
                 r_end = rec_lower_bound(rec, rpos, hi, 2u * e1, lane);
-                uint32_t *list = stage;  // pairs (element offset from e0, value)
                 for (uint32_t base = r_begin; base < r_end; base += kWave) {
                     const uint32_t k = base + lane;
                     uint32_t key = 1u, val = 0;
@@ -290,23 +334,21 @@ __global__ __launch_bounds__(kDsBlock) void k_decode_scan(DsArgs a) {
                     if (__ballot(k < r_end && (key & 1u))) has_verbatim = true;
                     if (esc) {
                         const uint32_t pos = n_esc + (uint32_t)__popcll(esc_mask & lt_mask);
-                        if (pos < kDsStageWords / 2u) { list[2 * pos] = (key >> 1) - e0; list[2 * pos + 1] = val; }
+                        if (pos < kListCap) { list[2 * pos] = (key >> 1) - e0; list[2 * pos + 1] = val; }
                     }
                     n_esc += (uint32_t)__popcll(esc_mask);
                 }
                 rpos = r_end;
-                if (n_esc > kDsStageWords / 2u) esc_in_lds = false;
+                if (n_esc > kListCap) esc_in_lds = false;
                 wave_lds_fence();
             }
-            COMET_ACC(a.ctl, 14);
 
-            // ---- 4. scans + dequantise + store; lanes are columns ----
-            const uint32_t tile_e0 = c_lo * S;                   // element held by tile entry 0
+            // ---- scans + dequantise + store; lanes are columns ----
             const uint32_t passes = group_mode ? (planes_here + ppi - 1u) / ppi : 1u;
             for (uint32_t pass = 0; pass < passes; ++pass) {
                 const uint32_t pl = pass * ppi + slot;           // plane inside the unit
                 const bool slot_on = lane_on && pl < planes_here;
-                const uint32_t e_row0 = group_mode ? e_unit + pl * P : e0;   // first element of my plane's first row here
+                const uint32_t rel0 = group_mode ? pl * P : 0u;  // my plane's first element here, relative to e0
                 if (group_mode) {
 #pragma unroll
                     for (int s = 0; s < NSEG; ++s) q[s] = 0;
@@ -314,66 +356,93 @@ __global__ __launch_bounds__(kDsBlock) void k_decode_scan(DsArgs a) {
                 // my cursor into the escape list: first entry at or after my plane's first element
                 uint32_t cur = 0;
                 if (n_esc && group_mode && esc_in_lds) {
-                    const uint32_t target = slot_on ? e_row0 - e0 : 0xffffffffu;
+                    const uint32_t target = slot_on ? rel0 : 0xffffffffu;
                     uint32_t lo = 0, hi = n_esc;
-                    while (lo < hi) { const uint32_t mid = (lo + hi) >> 1; if (stage[2 * mid] < target) lo = mid + 1; else hi = mid; }
+                    while (lo < hi) { const uint32_t mid = (lo + hi) >> 1; if (list[2 * mid] < target) lo = mid + 1; else hi = mid; }
                     cur = lo;
                 }
-                // The row loop exists twice: the usual one touches no global memory besides its
-                // stores (so the compiler never has to wait for them), the other one looks escaped
+                // element offsets (relative to e0) of my columns in row 0; 0x3fffffff for "no element":
+                // times 2 or 4 it still lies beyond every strip, so the access is dropped
+                uint32_t col[NSEG];
+#pragma unroll
+                for (int s = 0; s < NSEG; ++s) {
+                    const uint32_t w = wl + (uint32_t)s * kWave;
+                    col[s] = (slot_on && w < W) ? rel0 + w : 0x3fffffffu;
+                }
+                auto fetch = [&](uint32_t h, int32_t (&d)[U][NSEG]) {
+#pragma unroll
+                    for (uint32_t u = 0; u < U; ++u) {
+                        const uint32_t roff = (h + u < rows) ? (h + u) * W : 0x3fffffffu;    // wavefront-uniform
+#pragma unroll
+                        for (int s = 0; s < NSEG; ++s) {
+                            uint32_t off = col[s] + roff;
+                            off = off > 0x3fffffffu ? 0x3fffffffu : off;
+                            d[u][s] = (int32_t)(int16_t)__builtin_amdgcn_raw_buffer_load_b16(r_in, (int)(off * 2u), 0, 0);
+                        }
+                    }
+                };
+                // The row loop exists twice: the usual one touches no memory besides the strip
+                // (so the compiler never has to drain the stores), the other one looks escaped
                 // residuals up in the container when their list did not fit LDS.
-                auto row_loop = [&](auto slow_tag, auto pow2_tag) {
+                auto rows_of = [&](auto slow_tag, uint32_t h, int32_t (&dd)[U][NSEG]) {
                     constexpr bool SLOW = decltype(slow_tag)::value;
-                    constexpr bool POW2 = decltype(pow2_tag)::value;
-                    for (uint32_t h = 0; h < rows; ++h) {
+#pragma unroll
+                    for (uint32_t u = 0; u < U; ++u) {
+                        const uint32_t roff = (h + u < rows) ? (h + u) * W : 0x3fffffffu;
                         int32_t carry = 0;
 #pragma unroll
                         for (int s = 0; s < NSEG; ++s) {
-                            const uint32_t w = wl + (uint32_t)s * kWave;
-                            const bool on = slot_on && w < W;
-                            const uint32_t e = e_row0 + h * W + w;
-                            const uint32_t ce = e - tile_e0;
-                            const uint32_t entry = POW2 ? ce + ((ce >> log2S) << 1) : ce + 2u * (ce / S);
-                            int32_t d = on ? (int32_t)tile[entry] : 0;
+                            uint32_t off = col[s] + roff;
+                            off = off > 0x3fffffffu ? 0x3fffffffu : off;
+                            int32_t d = dd[u][s];
                             const bool is_esc = d == kEscape;
                             const uint64_t any_esc = __ballot(is_esc);
                             if (any_esc) {                            // wavefront-uniform
                                 const uint64_t m = any_esc & slot_mask;
                                 if (is_esc) {
                                     if (SLOW) {
-                                        const uint32_t key = 2u * e;
+                                        const uint32_t key = 2u * (e0 + off);
                                         uint32_t lo = r_begin, hi = r_end;
                                         while (lo < hi) { const uint32_t mid = (lo + hi) >> 1; if (rec[2 * (size_t)mid] < key) lo = mid + 1; else hi = mid; }
                                         d = (lo < r_end && rec[2 * (size_t)lo] == key) ? (int32_t)rec[2 * (size_t)lo + 1] : 0;
                                     } else {
                                         uint32_t pos = cur + (uint32_t)__popcll(m & lt_mask);
-                                        if (pos >= kDsStageWords / 2u) pos = kDsStageWords / 2u - 1u;   // corrupt container only
-                                        d = n_esc ? (int32_t)stage[2 * pos + 1] : 0;
+                                        if (pos >= kListCap) pos = kListCap - 1u;   // corrupt container only
+                                        d = n_esc ? (int32_t)list[2 * pos + 1] : 0;
                                     }
                                 }
                                 cur += (uint32_t)__popcll(m);
                             }
-                            int32_t rp;
-                            rp = run_scan<MODE>(d, wl, W);
+                            int32_t rp = run_scan<MODE>(d, wl, W);
                             rp = (int32_t)((uint32_t)rp + (uint32_t)carry);
                             if (NSEG > 1) carry = __builtin_amdgcn_readlane(rp, 63);
                             q[s] = (int32_t)((uint32_t)q[s] + (uint32_t)rp);
                             float v = (float)q[s] * ebx2;
                             if (fabsf(v) <= eb) v = 0.0f;
-                            if (on) a.out[e] = v;
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r_out, (int)(off * 4u), 0, 0);
                         }
                     }
                 };
-                if (!esc_in_lds) row_loop(std::true_type{}, std::false_type{});
-                else if (pow2) row_loop(std::false_type{}, std::true_type{});
-                else row_loop(std::false_type{}, std::false_type{});
+                auto row_loop = [&](auto slow_tag) {
+                    // two batches of rows alternate: the loads of one are in flight while the other is scanned
+                    int32_t da[U][NSEG], db[U][NSEG];
+                    fetch(0, da);
+                    for (uint32_t h = 0; h < rows; h += 2u * U) {
+                        fetch(h + U, db);
+                        rows_of(slow_tag, h, da);
+                        fetch(h + 2u * U, da);
+                        rows_of(slow_tag, h + U, db);
+                    }
+                };
+                if (!esc_in_lds) row_loop(std::true_type{});
+                else row_loop(std::false_type{});
             }
-            COMET_ACC(a.ctl, 15);
 
-            // ---- 5. verbatim values overwrite what was just stored ----
+            // ---- verbatim values overwrite what was just stored ----
             if (has_verbatim) {
-                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");  // the lattice values of this wavefront must have landed first
-                // (workgroup scope waits for the stores; a wider scope would also write back and invalidate the L2)
+                // the lattice values of this wavefront must have landed first (workgroup scope waits for
+                // the stores; a wider scope would also write back and invalidate the L2)
+                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
                 for (uint32_t k = r_begin + lane; k < r_end; k += kWave) {
                     const uint32_t key = rec[2 * (size_t)k];
                     if (key & 1u) {
@@ -385,16 +454,15 @@ __global__ __launch_bounds__(kDsBlock) void k_decode_scan(DsArgs a) {
                 }
             }
             wave_lds_fence();
-            COMET_ACC(a.ctl, 16);
         }
     }
 }
 
-template __global__ void k_decode_scan<1, 0>(DsArgs);
-template __global__ void k_decode_scan<1, 1>(DsArgs);
-template __global__ void k_decode_scan<1, 2>(DsArgs);
-template __global__ void k_decode_scan<2, 2>(DsArgs);
-template __global__ void k_decode_scan<4, 2>(DsArgs);
-template __global__ void k_decode_scan<8, 2>(DsArgs);
+template __global__ void k_scan_store<1, 0>(DsArgs);
+template __global__ void k_scan_store<1, 1>(DsArgs);
+template __global__ void k_scan_store<1, 2>(DsArgs);
+template __global__ void k_scan_store<2, 2>(DsArgs);
+template __global__ void k_scan_store<4, 2>(DsArgs);
+template __global__ void k_scan_store<8, 2>(DsArgs);
 
 }  // namespace comet
