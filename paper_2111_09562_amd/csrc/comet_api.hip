@@ -69,6 +69,9 @@ struct comet_ctx {
     uint8_t *zero_region = nullptr;  // == (uint8_t*)&state->ctl
     uint64_t zero_cap = 0;
     uint16_t *codes = nullptr;
+    uint32_t *rec_stage = nullptr;   // row-walking quantise kernel: staging area of every run's outlier records
+    uint32_t *run_count = nullptr;   //   and per run: record count, non-zero inputs, verbatim records
+    uint64_t max_runs = 0;
     uint64_t *enc = nullptr;
     BookScratch book{};
     DecodeTables tables{};
@@ -163,7 +166,11 @@ bool recon_geometry(comet_shape s, ReconGeometry *g) {
 
 // segments of the encode kernel: (chunks per segment, number of segments)
 void encode_geometry(const comet_ctx *ctx, uint64_t n_chunks, uint32_t *seg_chunks, uint32_t *n_seg);
-uint32_t quantize_segments(const comet_ctx *ctx, uint64_t n_tiles);
+// Work split of the quantise kernel.  rows: the row-walking kernel (planes up to kQuantRowsMaxW
+// columns) with `grid` workgroups of four wavefronts, each wavefront on rows_per_wave consecutive
+// rows; otherwise the flat-tile kernel with `grid` segments of tiles.
+struct QuantGeom { bool rows; uint32_t grid, rows_per_wave, rows_per_step; };
+QuantGeom quantize_geometry(const comet_ctx *ctx, comet_shape s, uint64_t n);
 
 int launch_quantize(comet_ctx *ctx, const float *x, comet_shape s, uint64_t n, float eb, uint32_t nbins,
                     hipStream_t st, uint16_t *codes, uint32_t *hist, uint32_t *rec, uint64_t rec_cap,
@@ -177,12 +184,36 @@ int launch_quantize(comet_ctx *ctx, const float *x, comet_shape s, uint64_t n, f
     a.win_lo = (nbins - a.win_n) / 2u;
     a.n_tiles = (uint32_t)((n + kQuantTile - 1) / kQuantTile);
     a.codes = codes; a.hist = hist; a.rec = rec; a.rec_cap = rec_cap; a.desc = desc; a.ctl = &ctx->state->ctl;
-    // one segment of consecutive tiles per workgroup, about as many workgroups as fit the chip at once
-    const uint32_t grid = quantize_segments(ctx, a.n_tiles);
-    a.tiles_per_seg = (a.n_tiles + grid - 1) / grid;
-    a.rec_lds = kQuantRecLds;
-    const size_t lds = (size_t)a.win_n * 4u + (size_t)kQuantRecLds * 8u;
-    {
+    const QuantGeom g = quantize_geometry(ctx, s, n);
+    const uint32_t grid = g.grid;
+    if (g.rows) {
+        a.rows_total = (uint32_t)((uint64_t)s.n * s.c * s.h);
+        a.rows_per_wave = g.rows_per_wave;
+        a.rows_per_step = g.rows_per_step;
+        if ((uint64_t)grid * (kQuantBlock / kWave) > ctx->max_runs) return COMET_ERR_INTERNAL;
+        a.stage = ctx->rec_stage;
+        a.run_count = ctx->run_count;
+        a.hist_shift = a.win_n <= 2048u ? 2u : 0u;            // four copies while they fit 32 KB
+        const size_t lds = (((size_t)a.win_n << a.hist_shift) + kQuantBlock) * 4u;
+        const bool full = a.win_n == nbins;
+        TimedScope ts(ctx, st, COMET_KERNEL_QUANTIZE);
+#define COMET_LAUNCH_QR(NSEG, MULTI)                                                                                   \
+        do {                                                                                                           \
+            if (full) hipLaunchKernelGGL((k_quantize_rows<NSEG, MULTI, true>), dim3(grid), dim3(kQuantBlock), lds, st, a);   \
+            else hipLaunchKernelGGL((k_quantize_rows<NSEG, MULTI, false>), dim3(grid), dim3(kQuantBlock), lds, st, a);       \
+            hipLaunchKernelGGL((k_gather_records<NSEG, MULTI>), dim3(grid), dim3(kQuantBlock), 0, st, a);              \
+        } while (0)
+        if (s.w <= 32u) COMET_LAUNCH_QR(1, true);
+        else if (s.w <= 64u) COMET_LAUNCH_QR(1, false);
+        else if (s.w <= 128u) COMET_LAUNCH_QR(2, false);
+        else if (s.w <= 256u) COMET_LAUNCH_QR(4, false);
+        else COMET_LAUNCH_QR(8, false);
+#undef COMET_LAUNCH_QR
+    } else {
+        // one segment of consecutive tiles per workgroup, about as many workgroups as fit the chip at once
+        a.tiles_per_seg = (a.n_tiles + grid - 1) / grid;
+        a.rec_lds = kQuantRecLds;
+        const size_t lds = (size_t)a.win_n * 4u + (size_t)kQuantRecLds * 8u;
         TimedScope ts(ctx, st, COMET_KERNEL_QUANTIZE);
         if (a.win_n == nbins) hipLaunchKernelGGL(k_quantize<true>, dim3(grid), dim3(kQuantBlock), lds, st, a);
         else hipLaunchKernelGGL(k_quantize<false>, dim3(grid), dim3(kQuantBlock), lds, st, a);
@@ -241,11 +272,33 @@ void encode_geometry(const comet_ctx *ctx, uint64_t n_chunks, uint32_t *seg_chun
     *n_seg = (uint32_t)((n_chunks + seg - 1) / seg);
 }
 
-uint32_t quantize_segments(const comet_ctx *ctx, uint64_t n_tiles) {
+QuantGeom quantize_geometry(const comet_ctx *ctx, comet_shape s, uint64_t n) {
+    QuantGeom g{};
+    if (s.w <= kQuantRowsMaxW) {
+        g.rows = true;
+        const uint64_t rows_total = (uint64_t)s.n * s.c * s.h;
+        const uint32_t K = s.w <= 32u ? (uint32_t)kWave / s.w : 1u;
+        g.rows_per_step = K;
+        // a few wavefronts per SIMD, but runs of at least 8192 elements (every run re-reads one row)
+        const uint64_t want = (uint64_t)ctx->num_cu * 4u * kQuantRunsPerSimd;
+        uint64_t per = (rows_total + want - 1) / want;
+        const uint64_t min_rows = (8192u + s.w - 1u) / s.w;
+        if (per < min_rows) per = min_rows;
+        per = (per + K - 1) / K * K;
+        if (per > rows_total) per = (rows_total + K - 1) / K * K;
+        // a run must stay below 2^28 elements (buffer offsets): cannot be exceeded, rows_total * w < 2^31 and
+        // the run count is in the thousands unless the tensor itself is small
+        const uint64_t waves = (rows_total + per - 1) / per;
+        g.rows_per_wave = (uint32_t)per;
+        g.grid = (uint32_t)((waves + (kQuantBlock / kWave) - 1) / (kQuantBlock / kWave));
+        return g;
+    }
+    const uint64_t n_tiles = (n + kQuantTile - 1) / kQuantTile;
     uint64_t grid = (uint64_t)ctx->num_cu * (uint64_t)ctx->occ_quant;
     if (grid > n_tiles) grid = n_tiles;
     const uint64_t per = (n_tiles + grid - 1) / grid;
-    return (uint32_t)((n_tiles + per - 1) / per);
+    g.grid = (uint32_t)((n_tiles + per - 1) / per);
+    return g;
 }
 
 }  // namespace
@@ -277,6 +330,9 @@ int comet_create(comet_ctx **out, uint64_t max_elems, uint32_t max_nbins) {
     c->zero_region = reinterpret_cast<uint8_t *>(&c->state->ctl);
     if ((e = hipMalloc((void **)&c->codes, align_up(2 * max_elems + 64, 256))) != hipSuccess) return fail(COMET_ERR_NOMEM);
     if ((e = hipMalloc((void **)&c->enc, 8ull * kMaxBins)) != hipSuccess) return fail(COMET_ERR_NOMEM);
+    c->max_runs = (uint64_t)c->num_cu * 4u * kQuantRunsPerSimd + 8u;
+    if ((e = hipMalloc((void **)&c->rec_stage, c->max_runs * kQuantRecRun * 8ull)) != hipSuccess) return fail(COMET_ERR_NOMEM);
+    if ((e = hipMalloc((void **)&c->run_count, 3ull * c->max_runs * 4ull)) != hipSuccess) return fail(COMET_ERR_NOMEM);
     {
         // one blob: book scratch + decode tables
         uint64_t o = 0;
@@ -318,6 +374,8 @@ void comet_destroy(comet_ctx *c) {
     if (!c) return;
     if (c->state) (void)hipFree(c->state);
     if (c->codes) (void)hipFree(c->codes);
+    if (c->rec_stage) (void)hipFree(c->rec_stage);
+    if (c->run_count) (void)hipFree(c->run_count);
     if (c->enc) (void)hipFree(c->enc);
     if (c->tables_blob) (void)hipFree(c->tables_blob);
     if (c->host_state) (void)hipHostFree(c->host_state);
@@ -354,7 +412,7 @@ int comet_compress(comet_ctx *ctx, const float *dev_in, comet_shape s, float eb,
     const uint64_t n_chunks = (n + S - 1) / S;
     uint32_t e_seg, e_grid;
     encode_geometry(ctx, n_chunks, &e_seg, &e_grid);
-    const uint64_t tiles_q = quantize_segments(ctx, (n + kQuantTile - 1) / kQuantTile);
+    const uint64_t tiles_q = quantize_geometry(ctx, s, n).grid;
     const uint64_t tiles_e = e_grid;
 
     Header proto{};
@@ -548,7 +606,7 @@ int comet_stage_quantize(comet_ctx *ctx, const float *dev_in, comet_shape s, flo
         ((uintptr_t)dev_codes & 7u) || ((uintptr_t)dev_records & 7u)) return COMET_ERR_INVALID;
     if (n > ctx->max_elems) return COMET_ERR_NOMEM;
     hipStream_t st = (hipStream_t)stream;
-    const uint64_t tiles_q = quantize_segments(ctx, (n + kQuantTile - 1) / kQuantTile);
+    const uint64_t tiles_q = quantize_geometry(ctx, s, n).grid;
     const ZeroLayout z = zero_layout(4, tiles_q, 1);
     if (z.bytes > ctx->zero_cap) return COMET_ERR_NOMEM;
     HIP_TRY(hipMemsetAsync(ctx->zero_region, 0, z.bytes, st));

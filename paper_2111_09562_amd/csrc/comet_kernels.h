@@ -21,6 +21,12 @@ struct QuantArgs {
     uint32_t n_tiles;
     uint32_t tiles_per_seg;    // consecutive tiles per workgroup (one segment each)
     uint32_t rec_lds;          // records the LDS buffer of a workgroup can hold
+    uint32_t rows_total;       // row-walking kernel: planes * H rows of W elements
+    uint32_t rows_per_wave;    //   consecutive rows per wavefront (a multiple of rows_per_step)
+    uint32_t rows_per_step;    //   rows a wavefront covers per step (64 / W for W <= 32, else 1)
+    uint32_t hist_shift;       //   log2 of the copies of the LDS histogram window (lane & (copies - 1) picks one)
+    uint32_t *stage;           //   staging area: kQuantRecRun (key, payload) pairs per run
+    uint32_t *run_count;       //   three arrays of one entry per run: records, non-zero inputs, verbatim records
     uint16_t *codes;
     uint32_t *hist;            // u32[nbins], zeroed
     uint32_t *rec;             // (key, payload) pairs
@@ -29,7 +35,12 @@ struct QuantArgs {
     Control *ctl;
 };
 constexpr uint32_t kQuantRecLds = 3072;   // outlier records buffered in LDS per workgroup (24 KB)
-template <bool FULLWIN> __global__ void k_quantize(QuantArgs a);   // FULLWIN: every bin is in the LDS window
+template <bool FULLWIN> __global__ void k_quantize(QuantArgs a);   // flat tiles, any plane width; FULLWIN: every bin is in the LDS window
+constexpr uint32_t kQuantRowsMaxW = 512;  // widest plane of the row-walking kernel
+constexpr uint32_t kQuantRecRun = 768;    // outlier records staged per run (one run of rows per wavefront)
+constexpr uint32_t kQuantRunsPerSimd = 5; // runs the launch aims at, per SIMD
+template <int NSEG, bool MULTI, bool FULLWIN> __global__ void k_quantize_rows(QuantArgs a);
+template <int NSEG, bool MULTI> __global__ void k_gather_records(QuantArgs a);
 
 // ---- codebook -----------------------------------------------------------------
 constexpr int kBookBlock = 1024;

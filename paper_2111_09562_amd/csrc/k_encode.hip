@@ -70,7 +70,7 @@ __device__ inline uint32_t code_of(uint2 v, int j) {
     return (j & 1) ? (w >> 16) : (w & 0xffffu);
 }
 
-#ifdef COMET_DEBUG_TIMING
+#ifdef COMET_DEBUG_ENC
 #define ENC_DBG(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) a.ctl->dbg[i] = wall_clock64(); \
                         if (threadIdx.x == 0 && blockIdx.x == gridDim.x - 1) a.ctl->dbg[16 + (i)] = wall_clock64(); } while (0)
 #else

@@ -1,0 +1,400 @@
+// Quantise kernels for planes up to 512 columns wide: prequantisation, 2-D Lorenzo
+// prediction, quantisation codes, histogram and outlier records in one sweep over
+// the input (COMET Sec. 4.1, first three steps of the modified cuSZ pipeline;
+// Sec. 2.2 for the bound).
+//
+// The tensor is a matrix of planes*H rows of W floats.  A wavefront owns a run of
+// consecutive rows and walks down it with lanes = columns, so every element is
+// loaded and prequantised exactly once:
+//   left neighbour      = the lane to the left (one DPP shift),
+//   row above           = what the same lane held one step earlier (a register),
+//   residual d          = rd - rd_above with rd = q - q_left (the row difference),
+// and there is no index arithmetic per element.  Planes of at most 32 columns are
+// walked K = 64 / W rows at a time (lane = k*W + w, the row above comes from lane
+// - W through one cross-lane permute), so the 64 lanes still cover 64 consecutive
+// elements.  Loads and stores use buffer addressing: lanes without an element get
+// an out-of-range offset, which the hardware ignores, so the loop is free of
+// divergent branches and several steps of loads are kept in flight.
+// The error-bound check is a cheap fp32 filter that falls back to the exact fp64
+// comparison only for elements within a few ulp of the bound.
+//
+// Outlier records (escapes and verbatim values) must end up in the container in
+// element order.  k_quantize_rows appends them, in order, to a staging area of
+// its run and leaves the count; k_gather_records, a second small kernel, adds up
+// the counts of the runs in front of a run and moves its records to their final
+// place (a run with more records than its staging area holds is swept again, this
+// time writing in place).  Nothing waits for anything inside a kernel.
+#include <type_traits>
+
+#include "comet_kernels.h"
+
+namespace comet {
+
+namespace {
+
+__device__ inline bool needs_verbatim_rows(float x, int32_t q, float r, float ebx2, float eb) {
+    const float t = x * r;
+    if (!(fabsf(t) < 16777216.0f)) return true;
+    const float y = (float)q * ebx2;
+    return !(fabs((double)x - (double)y) <= (double)eb);
+}
+
+// value of the lane to the left (lane 0 receives 0).  Callers combine the result with additions
+// only: a subtraction whose shifted operand the compiler folds into the instruction came out with
+// its operands exchanged on gfx950.
+__device__ inline int32_t lane_left(int32_t v) {
+    return __builtin_amdgcn_update_dpp(0, v, 0x138, 0xf, 0xf, true);   // wave_shr:1
+}
+
+__device__ inline __amdgpu_buffer_rsrc_t rows_rsrc(const void *p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
+}
+
+constexpr uint32_t kOob = 0x80000000u;      // byte offset beyond every run
+
+struct SweepCounts {
+    uint32_t nnz_lane = 0;      // per lane: non-zero inputs
+    uint32_t oow_lane = 0;      // per lane: codes counted straight into the global histogram
+    uint32_t vrec = 0;          // wavefront-uniform: verbatim records
+};
+
+// One sweep of a wavefront over rows [row_lo, row_hi).  PASS 0: everything (codes, histogram,
+// counters), records into rec_dst[0 .. rec_cap) (the rest is only counted); PASS 1: records only,
+// and a record that does not fit raises ST_CAPACITY.  Returns the number of records of the run.
+// NSEG: 64-column segments per row (1, 2, 4, 8); MULTI: W <= 32, K rows per step (NSEG == 1);
+// FULLWIN: every histogram bin is in the LDS window.
+template <int NSEG, bool MULTI, bool FULLWIN, int PASS>
+__device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint32_t row_hi, uint32_t lane, uint32_t *s_hist,
+                                      uint32_t hist_dummy, uint2 *rec_dst, uint64_t rec_cap, SweepCounts &cnt) {
+    const uint32_t W = a.divW.d, H = a.divH.d;
+    const int32_t radius = a.radius;
+    const uint32_t code_span = a.nbins - 1u;        // residual + radius - 1 must be below this
+    // an fp32 error above eb_lo needs the exact comparison (the fp32 subtraction is within one rounding)
+    const float eb_lo = a.eb * (1.0f - 0x1p-20f);
+    const uint64_t lt_mask = (1ull << lane) - 1ull;
+    const uint32_t hist_sub = lane & ((1u << a.hist_shift) - 1u);   // my copy of the histogram window
+
+    const uint32_t e_lo = row_lo * W;
+    const uint32_t n_el = (row_hi - row_lo) * W;
+    const __amdgpu_buffer_rsrc_t r_x = rows_rsrc(a.x + e_lo, n_el * 4u);
+    const __amdgpu_buffer_rsrc_t r_c = rows_rsrc(a.codes + e_lo, n_el * 2u);
+    const uint32_t K = MULTI ? a.rows_per_step : 1u;
+    const uint32_t stride = MULTI ? K * W : W;                  // elements per step
+    const uint32_t n_steps = (row_hi - row_lo + K - 1u) / K;
+    uint32_t cur = 0;                                           // records so far (uniform)
+
+    // lanes -> columns
+    uint32_t col[NSEG];                                         // element offset inside a step, kOob / 4 if none
+    uint32_t w0 = lane;                                         // MULTI: my column
+    bool first_col = false;                                     // MULTI: I am column 0 of my row
+    bool top_rows = false;                                      // MULTI: my row is the first one of a step
+    uint32_t h_lane = 0;                                        // MULTI: my row inside its plane
+    if (MULTI) {
+        const uint32_t kr = fdiv(lane, a.divW);
+        w0 = lane - kr * W;
+        col[0] = (kr < K) ? lane : kOob / 4u;
+        first_col = w0 == 0u;
+        top_rows = lane < W;
+        const uint32_t r0 = row_lo + kr;
+        h_lane = r0 - fdiv(r0, a.divH) * H;
+    } else {
+#pragma unroll
+        for (int s = 0; s < NSEG; ++s) col[s] = ((uint32_t)s * kWave + lane < W) ? (uint32_t)s * kWave + lane : kOob / 4u;
+    }
+    uint32_t h_row = row_lo - fdiv(row_lo, a.divH) * H;        // !MULTI: row of the current step inside its plane (uniform)
+    const uint32_t k_mod = MULTI ? K - fdiv(K, a.divH) * H : 0u;
+
+    // row differences of the row just above the run (only used if that row is in the same plane)
+    int32_t prev_rd[NSEG];
+#pragma unroll
+    for (int s = 0; s < NSEG; ++s) prev_rd[s] = 0;
+    if (row_lo > 0) {
+        const float *above = a.x + (size_t)(e_lo - W);
+#pragma unroll
+        for (int s = 0; s < NSEG; ++s) {
+            const uint32_t w = MULTI ? w0 : (uint32_t)s * kWave + lane;
+            const bool on = MULTI ? top_rows : (w < W);
+            const float xa = on ? above[w] : 0.0f;
+            const float xl = (on && w > 0) ? above[w - 1u] : 0.0f;
+            const float ta = xa * a.r, tl = xl * a.r;
+            const int32_t qa = (fabsf(ta) < 16777216.0f) ? (int32_t)rintf(ta) : 0;
+            const int32_t ql = (fabsf(tl) < 16777216.0f) ? (int32_t)rintf(tl) : 0;
+            prev_rd[s] = (w > 0) ? qa - ql : qa;
+        }
+    }
+
+    constexpr uint32_t U = NSEG >= 8 ? 1u : 8u / NSEG;          // steps per batch of loads
+    // FULL batches (every row of the batch inside the run) put the uniform part of the address
+    // into the scalar offset of the buffer instruction and know a lane's validity up front;
+    // the few steps at the end of a run go through the general form.
+    bool col_ok[NSEG];
+#pragma unroll
+    for (int s = 0; s < NSEG; ++s) col_ok[s] = col[s] != kOob / 4u;
+    auto fetch = [&](auto full_tag, uint32_t t0, uint32_t t_max, float (&xb)[U][NSEG]) {
+        constexpr bool FULL = decltype(full_tag)::value;
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u) {
+            const uint32_t t = (FULL && t0 + u > t_max) ? t_max : t0 + u;   // FULL: never beyond the last full step
+            const uint32_t soff = t * stride;                              // uniform
+#pragma unroll
+            for (int s = 0; s < NSEG; ++s) {
+                if (FULL) xb[u][s] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r_x, (int)(col[s] * 4u), (int)(soff * 4u), 0));
+                else xb[u][s] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r_x, (int)((col[s] + soff) * 4u), 0, 0));
+            }
+        }
+    };
+    auto steps_of = [&](auto full_tag, uint32_t t0, float (&xb)[U][NSEG]) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        int32_t dsave[U][NSEG];                                 // residuals of the batch, for the record pass
+        uint64_t flag_esc = 0, flag_susp = 0;                   // lanes that escaped / failed the fp32 bound filter anywhere in the batch
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u) {
+            const uint32_t soff = (t0 + u) * stride;
+            int32_t carry_q = 0;                                // last column of the previous segment (uniform)
+            const uint32_t hmask = h_row ? ~0u : 0u;            // !MULTI: "has a row above"
+#pragma unroll
+            for (int s = 0; s < NSEG; ++s) {
+                const bool valid = FULL ? col_ok[s] : (col[s] + soff < n_el);
+                const float x = xb[u][s];
+                const float t = x * a.r;
+                const float qf = (fabsf(t) < 16777216.0f) ? rintf(t) : 0.0f;
+                const int32_t q = (int32_t)qf;
+                int32_t nql = lane_left(-q);                    // minus the left neighbour
+                int32_t rd, up;
+                if (MULTI) {
+                    rd = first_col ? q : q + nql;
+                    const int32_t below = __builtin_amdgcn_ds_bpermute((int)((lane - W) * 4u), rd);
+                    up = top_rows ? prev_rd[0] : below;
+                    up = h_lane ? up : 0;
+                    prev_rd[0] = __builtin_amdgcn_ds_bpermute((int)((lane + (K - 1u) * W) * 4u), rd);
+                    h_lane += k_mod;
+                    h_lane -= (h_lane >= H) ? H : 0u;
+                } else {
+                    if (s > 0) nql = (lane == 0u) ? -carry_q : nql;
+                    if (NSEG > 1) carry_q = __builtin_amdgcn_readlane(q, 63);
+                    rd = q + nql;
+                    up = (int32_t)((uint32_t)prev_rd[s] & hmask);
+                    prev_rd[s] = rd;
+                }
+                const int32_t d = (int32_t)((uint32_t)rd - (uint32_t)up);
+                const uint32_t c = (uint32_t)d + (uint32_t)radius;
+                const bool inrange = (c - 1u) < code_span;
+                const uint32_t code = inrange ? c : 0u;
+                // error-bound filter: |x - y| in fp32 is within one rounding of the exact error
+                const float err = fabsf(x - qf * a.ebx2);
+                const bool suspicious = !(err <= eb_lo);        // also true for NaN / Inf / huge inputs
+                dsave[u][s] = d;
+                flag_esc |= __ballot(valid && !inrange);
+                flag_susp |= __ballot(valid && suspicious);
+                if (PASS == 0) {
+                    cnt.nnz_lane += (x != 0.0f) ? 1u : 0u;      // lanes without an element hold 0
+                    // Histogram: no divergent branch (switching the execution mask costs more than the
+                    // atomic).  Lanes that count nothing add to a word of their own; the centre bin is
+                    // not counted here, it is what is left of the workgroup's elements.  The window is
+                    // replicated: lanes that meet in one bin mostly use different copies.
+                    const bool count = valid && code != (uint32_t)radius;
+                    if (FULLWIN) {
+                        atomicAdd(&s_hist[count ? (code << a.hist_shift) + hist_sub : hist_dummy], 1u);
+                    } else {
+                        const uint32_t bin = code - a.win_lo;
+                        const bool inwin = bin < a.win_n;
+                        atomicAdd(&s_hist[(count && inwin) ? (bin << a.hist_shift) + hist_sub : hist_dummy], 1u);
+                        if (count && !inwin) { atomicAdd(&a.hist[code], 1u); ++cnt.oow_lane; }
+                    }
+                    if (FULL) __builtin_amdgcn_raw_buffer_store_b16((unsigned short)code, r_c, (int)(col[s] * 2u), (int)(soff * 2u), 0);
+                    else __builtin_amdgcn_raw_buffer_store_b16((unsigned short)code, r_c, (int)((col[s] + soff) * 2u), 0, 0);
+                }
+            }
+            if (!MULTI) { ++h_row; h_row = (h_row == H) ? 0u : h_row; }
+        }
+        // ---- outlier records (rare): escapes and verbatim values, in element order ----
+        // One wavefront-uniform test per batch; the batch is walked again only if some lane raised a flag.
+        if ((flag_esc | flag_susp) != 0ull) {
+            const bool any_susp = flag_susp != 0ull;            // uniform: verbatim candidates are much rarer than escapes
+#pragma unroll
+            for (uint32_t u = 0; u < U; ++u) {
+                const uint32_t soff = (t0 + u) * stride;
+#pragma unroll
+                for (int s = 0; s < NSEG; ++s) {
+                    const bool valid = FULL ? col_ok[s] : (col[s] + soff < n_el);
+                    const float x = xb[u][s];
+                    const int32_t d = dsave[u][s];
+                    const bool esc = valid && !(((uint32_t)d + (uint32_t)radius - 1u) < code_span);
+                    bool verb = false;
+                    if (any_susp) {
+                        const float t = x * a.r;
+                        const int32_t q = (fabsf(t) < 16777216.0f) ? (int32_t)rintf(t) : 0;
+                        const bool suspicious = !(fabsf(x - (float)q * a.ebx2) <= eb_lo);
+                        if (valid && suspicious) verb = needs_verbatim_rows(x, q, a.r, a.ebx2, a.eb);
+                    }
+                    const uint64_t em = __ballot(esc), vm = any_susp ? __ballot(verb) : 0ull;
+                    if ((em | vm) == 0ull) continue;             // wavefront-uniform
+                    uint32_t pos = cur + __builtin_amdgcn_mbcnt_hi((uint32_t)(em >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)em, 0u));
+                    if (vm) pos += __builtin_amdgcn_mbcnt_hi((uint32_t)(vm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)vm, 0u));
+                    const uint32_t e = e_lo + col[s] + soff;
+                    if (esc) {
+                        if (pos < rec_cap) rec_dst[pos] = make_uint2(2u * e, (uint32_t)d);
+                        else if (PASS == 1) atomicOr(&a.ctl->status, (uint32_t)ST_CAPACITY);
+                        ++pos;
+                    }
+                    if (verb) {
+                        if (pos < rec_cap) rec_dst[pos] = make_uint2(2u * e + 1u, __float_as_uint(x));
+                        else if (PASS == 1) atomicOr(&a.ctl->status, (uint32_t)ST_CAPACITY);
+                    }
+                    cur += (uint32_t)__popcll(em) + (uint32_t)__popcll(vm);
+                    if (PASS == 0) cnt.vrec += (uint32_t)__popcll(vm);
+                }
+            }
+        }
+    };
+    // Two batches of steps alternate: the loads of one are in flight while the other is worked on.
+    float xa[U][NSEG], xb[U][NSEG];
+    const std::true_type full{};
+    const std::false_type general{};
+    const uint32_t n_full = n_steps / (2u * U) * (2u * U);      // steps covered by full double batches
+    uint32_t t0 = 0;
+    if (n_full) {
+        const uint32_t t_max = n_full - 1u;
+        fetch(full, 0, t_max, xa);
+        for (; t0 < n_full; t0 += 2u * U) {
+            fetch(full, t0 + U, t_max, xb);
+            steps_of(full, t0, xa);
+            fetch(full, t0 + 2u * U, t_max, xa);                // the last round re-reads the last step, unused
+            steps_of(full, t0 + U, xb);
+        }
+    }
+    for (; t0 < n_steps; t0 += U) {                              // fewer than two batches left
+        fetch(general, t0, 0, xa);
+        steps_of(general, t0, xa);
+    }
+    return cur;
+}
+
+// rows [lo, hi) of run `run`
+__device__ inline void run_rows(const QuantArgs &a, uint32_t run, uint32_t *lo, uint32_t *hi) {
+    const uint64_t r0 = (uint64_t)run * a.rows_per_wave;
+    if (r0 >= a.rows_total) { *lo = 0; *hi = 0; return; }
+    *lo = (uint32_t)r0;
+    *hi = (a.rows_total - *lo < a.rows_per_wave) ? a.rows_total : *lo + a.rows_per_wave;
+}
+
+}  // namespace
+
+// One run per wavefront, kQuantBlock / 64 runs per workgroup.
+template <int NSEG, bool MULTI, bool FULLWIN>
+__global__ __launch_bounds__(kQuantBlock) void k_quantize_rows(QuantArgs a) {
+    extern __shared__ uint32_t s_dyn_qr[];          // histogram window: a.win_n bins, 1 << a.hist_shift copies of each;
+                                                    // then one word per thread for the lanes that count nothing
+    constexpr int kWaves = kQuantBlock / kWave;
+    uint32_t *s_hist = s_dyn_qr;
+    __shared__ uint64_t s_part64[kWaves];
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = (uint32_t)lane_id();
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / kWave));
+    for (uint32_t i = tid; i < (a.win_n << a.hist_shift); i += kQuantBlock) s_hist[i] = 0;
+    __syncthreads();
+
+    const uint32_t run = blockIdx.x * kWaves + wave;
+    uint32_t row_lo, row_hi;
+    run_rows(a, run, &row_lo, &row_hi);
+    SweepCounts cnt;
+    uint32_t my_records = 0;
+    if (row_hi > row_lo)
+        my_records = sweep_rows<NSEG, MULTI, FULLWIN, 0>(a, row_lo, row_hi, lane, s_hist, (a.win_n << a.hist_shift) + tid,
+                                                          reinterpret_cast<uint2 *>(a.stage) + (size_t)run * kQuantRecRun, kQuantRecRun, cnt);
+    // per-run results: record count, non-zero inputs, verbatim records (summed up by the gather kernel;
+    // thousands of atomics on one counter would cost more than the sweep)
+    const uint32_t nnz_wave = wave_sum<uint32_t>(cnt.nnz_lane);
+    if (lane == 0) {
+        const uint32_t n_runs = gridDim.x * kWaves;
+        a.run_count[run] = my_records;
+        a.run_count[n_runs + run] = nnz_wave;
+        a.run_count[2u * n_runs + run] = cnt.vrec;
+    }
+
+    // ---- flush the private histogram ----
+    // centre bin = elements of the workgroup - everything counted elsewhere
+    __syncthreads();
+    uint64_t counted = FULLWIN ? 0ull : (uint64_t)cnt.oow_lane;
+    for (uint32_t i = tid; i < a.win_n; i += kQuantBlock) {
+        uint32_t v = 0;
+        for (uint32_t k = 0; k < (1u << a.hist_shift); ++k) v += s_hist[(i << a.hist_shift) + k];
+        counted += v;
+        if (v) atomicAdd(&a.hist[a.win_lo + i], v);
+    }
+    uint64_t total;
+    (void)block_excl_scan<uint64_t, kWaves>(counted, s_part64, total);
+    if (tid == 0) {
+        const uint64_t r0 = (uint64_t)blockIdx.x * kWaves * a.rows_per_wave;
+        uint64_t r1 = r0 + (uint64_t)kWaves * a.rows_per_wave;
+        if (r1 > a.rows_total) r1 = a.rows_total;
+        const uint64_t elems = (r1 > r0) ? (r1 - r0) * a.divW.d : 0ull;
+        if (elems > total) atomicAdd(&a.hist[a.radius], (uint32_t)(elems - total));
+    }
+}
+
+// Moves the staged records of every run to their final, ordered place; same grid as k_quantize_rows.
+template <int NSEG, bool MULTI>
+__global__ __launch_bounds__(kQuantBlock) void k_gather_records(QuantArgs a) {
+    constexpr int kWaves = kQuantBlock / kWave;
+    __shared__ uint64_t s_part64[kWaves];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = (uint32_t)lane_id();
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / kWave));
+    const uint32_t n_runs = gridDim.x * kWaves;
+    const uint32_t run0 = blockIdx.x * kWaves;
+
+    // records of all runs in front of this workgroup's first run
+    uint64_t sum = 0;
+    for (uint32_t i = tid; i < run0; i += kQuantBlock) sum += a.run_count[i];
+    uint64_t base;
+    (void)block_excl_scan<uint64_t, kWaves>(sum, s_part64, base);
+    uint32_t mine = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const uint32_t c = a.run_count[run0 + w];
+        if ((uint32_t)w < wave) base += c;
+        if ((uint32_t)w == wave) mine = c;
+    }
+    if (blockIdx.x + 1u == gridDim.x) {
+        // the last workgroup also totals the counters of all runs
+        if (tid == kQuantBlock - 1) a.ctl->n_rec = base + mine;     // last run: base covers all runs before it
+        uint64_t nnz = 0, vrec = 0;
+        for (uint32_t i = tid; i < n_runs; i += kQuantBlock) { nnz += a.run_count[n_runs + i]; vrec += a.run_count[2u * n_runs + i]; }
+        uint64_t nnz_total, vrec_total;
+        (void)block_excl_scan<uint64_t, kWaves>(nnz, s_part64, nnz_total);
+        (void)block_excl_scan<uint64_t, kWaves>(vrec, s_part64, vrec_total);
+        if (tid == 0) { a.ctl->nnz = nnz_total; a.ctl->n_vrec = vrec_total; }
+    }
+    if (!mine) return;
+    const uint32_t run = run0 + wave;
+    uint2 *dst = reinterpret_cast<uint2 *>(a.rec) + base;
+    const uint64_t room = (base < a.rec_cap) ? a.rec_cap - base : 0ull;
+    if (mine <= kQuantRecRun) {
+        const uint2 *src = reinterpret_cast<const uint2 *>(a.stage) + (size_t)run * kQuantRecRun;
+        for (uint32_t i = lane; i < mine; i += kWave) {
+            if (i < room) dst[i] = src[i];
+            else atomicOr(&a.ctl->status, (uint32_t)ST_CAPACITY);
+        }
+    } else {
+        // more outliers than the staging area of a run holds: derive them again, in place
+        uint32_t row_lo, row_hi;
+        run_rows(a, run, &row_lo, &row_hi);
+        SweepCounts unused;
+        (void)sweep_rows<NSEG, MULTI, true, 1>(a, row_lo, row_hi, lane, nullptr, 0, dst, room, unused);
+    }
+}
+
+#define COMET_INST_QR(NSEG, MULTI)                                                   \
+    template __global__ void k_quantize_rows<NSEG, MULTI, true>(QuantArgs);          \
+    template __global__ void k_quantize_rows<NSEG, MULTI, false>(QuantArgs);         \
+    template __global__ void k_gather_records<NSEG, MULTI>(QuantArgs);
+COMET_INST_QR(1, true)
+COMET_INST_QR(1, false)
+COMET_INST_QR(2, false)
+COMET_INST_QR(4, false)
+COMET_INST_QR(8, false)
+#undef COMET_INST_QR
+
+}  // namespace comet
