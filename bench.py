@@ -25,6 +25,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+# HBM bytes per mean launch of a kernel, from the rocprofv3 counter runs summarised under profiles/
+# (FETCH_SIZE + WRITE_SIZE, scaled by the same counters on a plain copy of known size); filled in by hand
+# from those summaries, None where no counter run covers the kernel
+TRAFFIC = {}
 
 
 def main() -> int:
@@ -34,11 +38,12 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--batch", type=int, default=64, help="batch of the activation set (64 = the metric's workload)")
     ap.add_argument("--chunk-syms", type=int, default=64)
-    ap.add_argument("--streams", type=int, default=2,
+    ap.add_argument("--streams", type=int, default=5,
                     help="contexts (each on its own stream) the layers are dealt to; the single-workgroup kernels of "
                          "one layer then overlap the streaming kernels of another")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer table to stderr")
+    ap.add_argument("--no-split", action="store_true", help="skip the compress-only and decompress-only passes")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the codec shards with zero exchange (every GPU compresses its own batch "
@@ -104,18 +109,22 @@ def main() -> int:
     value = in_bytes / (dt / args.steps) / 1e9
 
     # compress-only and decompress-only rates (same launch configuration)
-    def timed(fn):
-        torch.cuda.synchronize()
-        t = time.perf_counter()
-        for _ in range(args.steps):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t) / args.steps
-    tc = timed(compress_all)
-    td = timed(decompress_all)
-    sync_all()
+    tc = td = None
+    if not args.no_split:
+        def timed(fn):
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(args.steps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t) / args.steps
+        tc = timed(compress_all)
+        td = timed(decompress_all)
+        sync_all()
 
-    # ---- per-kernel durations: the same K steps again with the library's event brackets on ----
+    # ---- per-kernel durations: K more steps of the same kind, this time with the library bracketing every
+    # launch with two HIP events on the launch's stream (the brackets cost about a tenth of the throughput
+    # when several streams are in use, so the timed region above runs without them) ----
     for c in ctxs:
         c.comet_profile_enable(True)
         c.comet_profile_reset()
@@ -135,8 +144,11 @@ def main() -> int:
 
     cont_bytes = sum(sizes)
     b = cont_bytes / n_total                       # container bytes per element
-    # algorithmic bytes per element of each streaming kernel
-    alg = {"k_quantize": 4.0 + 2.0, "k_encode": 2.0 + b, "k_reconstruct": b + 4.0}
+    # algorithmic bytes per element of each streaming kernel (what its interface makes it read + write):
+    # quantise: fp32 in, u16 code out; encode: codes in (count pass), codes in and container out (pack pass);
+    # decode: container in, int16 residual out; scan + store: int16 in, fp32 out
+    alg = {"k_quantize_rows": 4.0 + 2.0, "k_encode_count": 2.0, "k_encode_pack": 2.0 + b, "k_decode_chunks": b + 2.0,
+           "k_scan_store": 2.0 + 4.0}
     dom = max(alg.keys(), key=lambda k: kern[k]["total_ms"])
     launches = kern[dom]["launches"]
     # every launch of a kernel handles one layer; the five layers differ in size, so
@@ -145,19 +157,26 @@ def main() -> int:
     avg_s = kern[dom]["total_ms"] / launches / 1e3
     achieved = alg_bytes_per_launch / avg_s / 1e9
     roofline = dict(bound="hbm", kernel=dom, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
+                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=TRAFFIC.get(dom),
                     avg_launch_us=round(avg_s * 1e6, 2), launches=launches,
                     alg_bytes_per_elem=round(alg[dom], 4),
-                    note="avg over the five layers of the set; events recorded by the library on its stream in a "
-                         "second pass of K steps (the timed region itself runs without event brackets)")
-    # path-level roofline: two-pass compress (8+b) and fused decompress (b+4) bytes per element
-    path = dict(compress_GBps=round(in_bytes / tc / 1e9, 1), decompress_GBps=round(in_bytes / td / 1e9, 1),
-                compress_frac_hbm=round((8.0 + b) * n_total / tc / 1e9 / HBM_PEAK_GBS, 4),
-                decompress_frac_hbm=round((b + 4.0) * n_total / td / 1e9 / HBM_PEAK_GBS, 4),
-                roundtrip_frac_hbm=round((12.0 + 2 * b) * n_total / (dt / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
-                ratio=round(in_bytes / cont_bytes, 3),
+                    note="mean over the five layers of the set; durations from HIP events recorded by the library on "
+                         "the stream of each launch, in a pass of K more identical steps right after the timed region "
+                         "(which runs without the brackets); with several streams a kernel shares the chip with the kernels of other "
+                         "layers, which lengthens its own duration; traffic = HBM bytes per mean launch from "
+                         "rocprofv3 FETCH_SIZE + WRITE_SIZE (profiles/), null if not collected")
+    # path-level figures: bytes the kernels of a path must move per element (compress: 6 + 4 + b, decompress:
+    # b + 2 + 6) and the smallest any codec could move (4 + b each way)
+    step_s = dt / args.steps
+    path = dict(ratio=round(in_bytes / cont_bytes, 3),
                 per_layer_ratio=[round(4 * x.numel() / s, 3) for x, s in zip(xs, sizes)],
+                roundtrip_frac_hbm_kernel_bytes=round((18.0 + 2 * b) * n_total / step_s / 1e9 / HBM_PEAK_GBS, 4),
+                roundtrip_frac_hbm_min_bytes=round((8.0 + 2 * b) * n_total / step_s / 1e9 / HBM_PEAK_GBS, 4),
                 kernels={k: dict(launches=v["launches"], avg_us=round(v["avg_us"], 2)) for k, v in kern.items()})
+    if tc is not None:
+        path.update(compress_GBps=round(in_bytes / tc / 1e9, 1), decompress_GBps=round(in_bytes / td / 1e9, 1),
+                    compress_frac_hbm_kernel_bytes=round((10.0 + b) * n_total / tc / 1e9 / HBM_PEAK_GBS, 4),
+                    decompress_frac_hbm_kernel_bytes=round((8.0 + b) * n_total / td / 1e9 / HBM_PEAK_GBS, 4))
 
     cpu = None
     if not args.no_cpu_baseline:

@@ -44,7 +44,7 @@ extern "C" {
 #define COMET_ERR_INTERNAL (-6)    /* a device-side safety net tripped (should not happen) */
 
 #define COMET_HEADER_BYTES 128u
-#define COMET_DEFAULT_CHUNK_SYMS 128u
+#define COMET_DEFAULT_CHUNK_SYMS 64u
 
 typedef struct comet_ctx comet_ctx;                     /* opaque; owns the device workspace */
 typedef struct { uint32_t n, c, h, w; } comet_shape;    /* NCHW */
@@ -64,8 +64,8 @@ typedef struct {
 int comet_create(comet_ctx **ctx, uint64_t max_elems, uint32_t max_nbins);
 void comet_destroy(comet_ctx *ctx);
 
-/* Symbols per Huffman chunk for subsequent comet_compress calls: 64, 128
- * (default) or 256.  Stored in the container; the decompressor reads it there. */
+/* Symbols per Huffman chunk for subsequent comet_compress calls: 64 (default),
+ * 128 or 256.  Stored in the container; the decompressor reads it there. */
 int comet_set_chunk_syms(comet_ctx *ctx, uint32_t chunk_syms);
 
 /* Worst-case container size in bytes for a shape (every element an outlier and
@@ -155,9 +155,10 @@ int comet_stage_reconstruct(comet_ctx *ctx, const uint16_t *dev_codes, const uin
  * recorded on the call's stream.  comet_profile_read waits for those events and
  * returns, for kernel `kernel_id`, the number of launches since the last
  * comet_profile_reset and their summed duration in milliseconds.  Kernel ids:
- * 0 quantize, 1 codebook, 2 encode (count + pack), 3 decode tables,
+ * 0 quantize (sweep), 1 codebook, 2 encode (pack pass), 3 decode tables,
  * 4 reconstruct (scans + store; for planes wider than 512 columns the fused
- * decode + reconstruct kernel), 5 Huffman decode.
+ * decode + reconstruct kernel), 5 Huffman decode, 6 gather of the outlier
+ * records, 7 encode (count pass).
  * At most 16384 launches are kept between resets; further ones are not timed. */
 #define COMET_KERNEL_QUANTIZE 0
 #define COMET_KERNEL_CODEBOOK 1
@@ -165,7 +166,9 @@ int comet_stage_reconstruct(comet_ctx *ctx, const uint16_t *dev_codes, const uin
 #define COMET_KERNEL_TABLES 3
 #define COMET_KERNEL_RECONSTRUCT 4
 #define COMET_KERNEL_DECODE 5
-#define COMET_KERNEL_COUNT 6
+#define COMET_KERNEL_GATHER 6
+#define COMET_KERNEL_ENCODE_COUNT 7
+#define COMET_KERNEL_COUNT 8
 int comet_profile_enable(comet_ctx *ctx, int enable);
 int comet_profile_reset(comet_ctx *ctx);
 int comet_profile_read(comet_ctx *ctx, uint32_t kernel_id, uint32_t *launches /* host */, double *total_ms /* host */);

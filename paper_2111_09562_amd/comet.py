@@ -15,7 +15,7 @@ LIB_PATH = os.environ.get("COMET_LIB", os.path.join(_HERE, "libcomet.so"))   # C
 
 OK, ERR_INVALID, ERR_CAPACITY, ERR_FORMAT, ERR_HIP, ERR_NOMEM, ERR_INTERNAL = 0, -1, -2, -3, -4, -5, -6
 HEADER_BYTES = 128
-DEFAULT_CHUNK_SYMS = 128
+DEFAULT_CHUNK_SYMS = 64
 
 EXPORTS = (
     "comet_create", "comet_destroy", "comet_set_chunk_syms", "comet_compress_bound", "comet_compress",
@@ -23,7 +23,8 @@ EXPORTS = (
     "comet_stage_quantize", "comet_stage_codebook", "comet_stage_encode", "comet_stage_decode",
     "comet_stage_reconstruct", "comet_profile_enable", "comet_profile_reset", "comet_profile_read", "comet_strerror",
 )
-KERNEL_NAMES = ("k_quantize", "k_codebook", "k_encode", "k_decode_tables", "k_reconstruct", "k_decode")
+KERNEL_NAMES = ("k_quantize_rows", "k_codebook", "k_encode_pack", "k_decode_tables", "k_scan_store", "k_decode_chunks",
+                "k_gather_records", "k_encode_count")
 
 
 class Shape(C.Structure):

@@ -196,11 +196,14 @@ int launch_quantize(comet_ctx *ctx, const float *x, comet_shape s, uint64_t n, f
         a.hist_shift = a.win_n <= 2048u ? 2u : 0u;            // four copies while they fit 32 KB
         const size_t lds = (((size_t)a.win_n << a.hist_shift) + kQuantBlock) * 4u;
         const bool full = a.win_n == nbins;
-        TimedScope ts(ctx, st, COMET_KERNEL_QUANTIZE);
 #define COMET_LAUNCH_QR(NSEG, MULTI)                                                                                   \
         do {                                                                                                           \
-            if (full) hipLaunchKernelGGL((k_quantize_rows<NSEG, MULTI, true>), dim3(grid), dim3(kQuantBlock), lds, st, a);   \
-            else hipLaunchKernelGGL((k_quantize_rows<NSEG, MULTI, false>), dim3(grid), dim3(kQuantBlock), lds, st, a);       \
+            {                                                                                                          \
+                TimedScope ts(ctx, st, COMET_KERNEL_QUANTIZE);                                                         \
+                if (full) hipLaunchKernelGGL((k_quantize_rows<NSEG, MULTI, true>), dim3(grid), dim3(kQuantBlock), lds, st, a);   \
+                else hipLaunchKernelGGL((k_quantize_rows<NSEG, MULTI, false>), dim3(grid), dim3(kQuantBlock), lds, st, a);       \
+            }                                                                                                          \
+            TimedScope ts(ctx, st, COMET_KERNEL_GATHER);                                                               \
             hipLaunchKernelGGL((k_gather_records<NSEG, MULTI>), dim3(grid), dim3(kQuantBlock), 0, st, a);              \
         } while (0)
         if (s.w <= 32u) COMET_LAUNCH_QR(1, true);
@@ -242,20 +245,18 @@ int launch_encode(comet_ctx *ctx, const uint16_t *codes, uint64_t n, uint32_t nb
     const bool full = (a.tbl_n == nbins);
 #define COMET_LAUNCH_ENC(S)                                                                                            \
     do {                                                                                                               \
-        if (full) {                                                                                                    \
-            hipLaunchKernelGGL((k_encode_count<S, true>), dim3(grid), dim3(kEncBlock), lds_count, st, a);              \
-            hipLaunchKernelGGL((k_encode_pack<S, true>), dim3(grid), dim3(kEncBlock), lds_pack, st, a);                \
-        } else {                                                                                                       \
-            hipLaunchKernelGGL((k_encode_count<S, false>), dim3(grid), dim3(kEncBlock), lds_count, st, a);             \
-            hipLaunchKernelGGL((k_encode_pack<S, false>), dim3(grid), dim3(kEncBlock), lds_pack, st, a);               \
+        {                                                                                                              \
+            TimedScope ts(ctx, st, COMET_KERNEL_ENCODE_COUNT);                                                         \
+            if (full) hipLaunchKernelGGL((k_encode_count<S, true>), dim3(grid), dim3(kEncBlock), lds_count, st, a);    \
+            else hipLaunchKernelGGL((k_encode_count<S, false>), dim3(grid), dim3(kEncBlock), lds_count, st, a);        \
         }                                                                                                              \
+        TimedScope ts(ctx, st, COMET_KERNEL_ENCODE);                                                                   \
+        if (full) hipLaunchKernelGGL((k_encode_pack<S, true>), dim3(grid), dim3(kEncBlock), lds_pack, st, a);          \
+        else hipLaunchKernelGGL((k_encode_pack<S, false>), dim3(grid), dim3(kEncBlock), lds_pack, st, a);              \
     } while (0)
-    {
-        TimedScope ts(ctx, st, COMET_KERNEL_ENCODE);
-        if (chunk_syms == 64u) COMET_LAUNCH_ENC(64);
-        else if (chunk_syms == 128u) COMET_LAUNCH_ENC(128);
-        else COMET_LAUNCH_ENC(256);
-    }
+    if (chunk_syms == 64u) COMET_LAUNCH_ENC(64);
+    else if (chunk_syms == 128u) COMET_LAUNCH_ENC(128);
+    else COMET_LAUNCH_ENC(256);
 #undef COMET_LAUNCH_ENC
     HIP_TRY(hipGetLastError());
     return COMET_OK;
