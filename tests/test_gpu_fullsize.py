@@ -1,0 +1,191 @@
+"""GPU parity at the full sizes of the benchmark configurations, through the C ABI.
+
+Configs 1-3 are small enough for the CPU oracle to process whole (seconds per
+tensor), so containers and decompressed values are compared bit for bit.
+Config 1 runs in the launch configuration `bench.py` times: five contexts on
+five streams, every call asynchronous, chunks of 64 symbols.
+Config 4 (two tensors of 411 M elements) is checked on what the oracle can
+compute plane by plane -- the decompressed value of an element depends only on
+that element (prequantised value, verbatim flag, re-zero filter) -- plus
+properties that hold at any size, alone and with the two streams overlapped.
+"""
+import numpy as np
+import pytest
+
+from paper_2111_09562_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def comet():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2111_09562_amd import comet as libcomet
+    libcomet.lib()
+    return libcomet
+
+
+def _check_layer(oracle, x, entry, chunk, cont, out):
+    """Container bytes and decompressed bits against the oracle."""
+    want = oracle.compress(x, entry["eb"], entry["nbins"], chunk)
+    info_bytes = want.size
+    got = cont[:info_bytes].cpu().numpy()
+    assert np.array_equal(got, want), f"container differs for {entry['shape']}"
+    want_x = oracle.decompress(want).ravel()
+    got_x = out.cpu().numpy().ravel()
+    assert np.array_equal(got_x.view(np.uint32), want_x.view(np.uint32)), f"values differ for {entry['shape']}"
+    finite = np.isfinite(x.ravel())
+    err = np.abs(got_x.astype(np.float64)[finite] - x.ravel().astype(np.float64)[finite]).max()
+    assert err <= np.float64(np.float32(entry["eb"]))
+    return info_bytes
+
+
+def test_config1_full_size_in_bench_configuration(comet, oracle):
+    layers = synth.config1(64)
+    xs_host = [synth.make(e) for e in layers]
+    xs = [torch.from_numpy(x).cuda() for x in xs_host]
+    n_ctx = len(layers)
+    ctxs = [comet.Context(max_elems=max(x.numel() for x in xs), max_nbins=1024) for _ in range(n_ctx)]
+    for c in ctxs:
+        c.comet_set_chunk_syms(64)
+    streams = [torch.cuda.current_stream()] + [torch.cuda.Stream() for _ in range(n_ctx - 1)]
+    conts = [torch.empty(int(x.numel() * 4 * 0.6) // 16 * 16, dtype=torch.uint8, device="cuda") for x in xs]
+    outs = [torch.empty_like(x) for x in xs]
+    torch.cuda.synchronize()
+    for rep in range(2):                                      # a second step reuses every workspace
+        for i, (x, e, c) in enumerate(zip(xs, layers, conts)):
+            ctxs[i].comet_compress(x, e["eb"], e["nbins"], c, stream=streams[i], sync=False)
+        for i in reversed(range(len(xs))):
+            ctxs[i].comet_decompress(conts[i], conts[i].numel(), xs[i].shape, outs[i], stream=streams[i])
+    for c, st in zip(ctxs, streams):
+        c.comet_sync(st)
+    total = 0
+    for x, e, c, o, ctx in zip(xs_host, layers, conts, outs, ctxs):
+        used = int(ctx.comet_peek(c, c.numel()).total_bytes)
+        assert used == _check_layer(oracle, x, e, 64, c, o)
+        total += used
+    assert 3.5 < sum(x.nbytes for x in xs_host) / total < 5.0   # the set compresses about 4.1x
+    for c in ctxs:
+        c.close()
+
+
+def test_config2_full_size(comet, oracle):
+    layers = synth.config2(32)
+    ctx = comet.Context(max_elems=max(int(np.prod(e["shape"])) for e in layers), max_nbins=4096)
+    for e in layers:
+        x = synth.make(e)
+        xd = torch.from_numpy(x).cuda()
+        cont = torch.empty(x.nbytes // 2 // 16 * 16, dtype=torch.uint8, device="cuda")
+        out = torch.empty_like(xd)
+        used = ctx.comet_compress(xd, e["eb"], e["nbins"], cont)
+        ctx.comet_decompress(cont, used, x.shape, out)
+        ctx.comet_sync()
+        assert used == _check_layer(oracle, x, e, 64, cont, out)
+        del xd, cont, out
+    ctx.close()
+
+
+def test_config3_eb_sweep_and_adaptive_bound(comet, oracle):
+    entries = synth.config3(64)
+    x = synth.make(entries[0])
+    xd = torch.from_numpy(x).cuda()
+    ctx = comet.Context(max_elems=x.size, max_nbins=65536)
+    cont = torch.empty(x.nbytes, dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(xd)
+    ratios = []
+    for e in entries:
+        used = ctx.comet_compress(xd, e["eb"], e["nbins"], cont)
+        ctx.comet_decompress(cont, used, x.shape, out)
+        ctx.comet_sync()
+        assert used == _check_layer(oracle, x, e, 64, cont, out)
+        ratios.append(x.nbytes / used)
+        info = ctx.comet_peek(cont, used)
+        assert info.nnz == np.count_nonzero(x)
+    assert all(b > a for a, b in zip(ratios, ratios[1:])), ratios     # a looser bound compresses better
+    # the stress cell: eb = 1e-4 with 1024 bins makes most residuals outliers; if the container outgrows a
+    # buffer of the input's size the call must report it, otherwise the bytes must still match
+    stress = dict(entries[0], eb=1e-4, nbins=1024)
+    want = oracle.compress(x, stress["eb"], stress["nbins"], 64)
+    if want.size > cont.numel():
+        with pytest.raises(comet.CometError) as ei:
+            ctx.comet_compress(xd, stress["eb"], stress["nbins"], cont)
+        assert ei.value.code == comet.ERR_CAPACITY
+    else:
+        used = ctx.comet_compress(xd, stress["eb"], stress["nbins"], cont)
+        assert used == want.size and np.array_equal(cont[:used].cpu().numpy(), want)
+    # adaptive error bound (Sec. 3.2-3.3) fed with seeded synthetic layer statistics and the measured R
+    rng = np.random.default_rng(3)
+    R = np.count_nonzero(x) / x.size
+    for _ in range(16):
+        M, L = float(rng.uniform(1e-4, 1e-1)), float(rng.uniform(1e-6, 1e-2))
+        got = comet.comet_adapt_eb(M, L, R, 64)
+        assert got == oracle.adapt_eb(M, L, R, 64)
+        assert got == np.float32(0.01 * M / (0.32 * L * np.sqrt(64 * R)))
+    ctx.close()
+
+
+def _expected_values(oracle, x_plane, eb):
+    """What decompression must return for these elements: depends on each element alone."""
+    q, vflag, _ = oracle.prequant(x_plane, eb)
+    y = (q.astype(np.float32) * np.float32(2.0 * np.float32(eb))).astype(np.float32)
+    y = np.where(vflag.astype(bool), x_plane.ravel(), y)
+    y = np.where(np.abs(y) <= np.float32(eb), np.float32(0.0), y)
+    return y.astype(np.float32)
+
+
+def test_config4_two_streams(comet, oracle):
+    entries = synth.config4()
+    eb, nbins = entries[0]["eb"], entries[0]["nbins"]
+    shape = entries[0]["shape"]
+    n = int(np.prod(shape))
+    ctxs = [comet.Context(max_elems=n, max_nbins=nbins) for _ in range(2)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    xs_host = [synth.make(e) for e in entries]
+    xs = [torch.from_numpy(x).cuda() for x in xs_host]
+    conts = [torch.empty(n * 4 // 16 * 16, dtype=torch.uint8, device="cuda") for _ in xs]
+    outs = [torch.empty_like(x) for x in xs]
+    torch.cuda.synchronize()
+
+    # each alone
+    used = []
+    for i in range(2):
+        ctxs[i].comet_compress(xs[i], eb, nbins, conts[i], stream=streams[i], sync=False)
+        ctxs[i].comet_decompress(conts[i], conts[i].numel(), shape, outs[i], stream=streams[i])
+        ctxs[i].comet_sync(streams[i])
+        used.append(int(ctxs[i].comet_peek(conts[i], conts[i].numel(), stream=streams[i]).total_bytes))
+    alone_cont = [c[:u].clone() for c, u in zip(conts, used)]
+    alone_out = [o.clone() for o in outs]
+
+    P = shape[2] * shape[3]
+    rng = np.random.default_rng(17)
+    for i in range(2):
+        x, o = xs[i], outs[i]
+        # the bound on every element, on the device
+        assert float((o - x).abs().max()) <= float(np.float32(eb))
+        info = ctxs[i].comet_peek(conts[i], used[i])
+        assert info.nnz == int(torch.count_nonzero(x))
+        assert tuple(getattr(info.shape, k) for k in "nchw") == tuple(shape)
+        assert info.n_chunks == (n + 63) // 64 and info.chunk_syms == 64
+        assert 1.5 < 4.0 * n / used[i] < 6.0
+        # sampled planes, bit for bit against the oracle's element-wise arithmetic
+        planes = rng.choice(shape[0] * shape[1], size=24, replace=False)
+        for p in planes:
+            want = _expected_values(oracle, xs_host[i].reshape(-1, P)[p], eb)
+            got = o.view(-1, P)[int(p)].cpu().numpy()
+            assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), f"tensor {i} plane {p}"
+
+    # overlapped: stream 0 compresses tensor 0 again while stream 1 decompresses tensor 1's container
+    outs[1].zero_()
+    conts[0].zero_()
+    torch.cuda.synchronize()
+    ctxs[0].comet_compress(xs[0], eb, nbins, conts[0], stream=streams[0], sync=False)
+    ctxs[1].comet_decompress(conts[1], used[1], shape, outs[1], stream=streams[1])
+    ctxs[0].comet_sync(streams[0])
+    ctxs[1].comet_sync(streams[1])
+    assert torch.equal(conts[0][:used[0]], alone_cont[0])
+    assert torch.equal(outs[1].view(torch.int32), alone_out[1].view(torch.int32))
+    for c in ctxs:
+        c.close()
