@@ -44,6 +44,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer table to stderr")
     ap.add_argument("--no-split", action="store_true", help="skip the compress-only and decompress-only passes")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="first run one plain device-to-device copy of the largest layer (a kernel of known traffic "
+                         "that hardware-counter runs are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the codec shards with zero exchange (every GPU compresses its own batch "
@@ -64,6 +67,13 @@ def main() -> int:
     xs = [torch.from_numpy(x).cuda() for x in xs_host]
     n_total = sum(x.numel() for x in xs)
     in_bytes = 4 * n_total
+
+    if args.copy_probe:
+        probe = torch.empty_like(xs[0])
+        probe.copy_(xs[0])
+        torch.cuda.synchronize()
+        print(f"copy probe: {xs[0].numel() * 4} bytes read, {xs[0].numel() * 4} bytes written", file=sys.stderr)
+        del probe
 
     n_ctx = max(1, min(args.streams, len(xs)))
     ctxs = [comet.Context(max_elems=max(x.numel() for x in xs), max_nbins=1024) for _ in range(n_ctx)]

@@ -56,61 +56,73 @@ __device__ inline int32_t decode_long(uint64_t win, const DsTables &t, uint32_t 
     return sym ? (int32_t)sym - t.radius : kEscape;
 }
 
-// Bit buffer of one lane: `buf` holds the next bits left-aligned with more than
-// 32 of them valid; nw0 / nw1 are the two words after it.  Words are read from
-// words[min(i, last)].  Everything in next() is branch-free except the
-// wavefront-uniform test for a long code.
+// Bit reader of one lane: two words of the stream plus a bit position inside the
+// first one, and one word of look-ahead so that no load sits on the critical
+// path.  Words are read from words[min(i, last)].  Everything in next() is
+// branch-free except the wavefront-uniform test for a long code.
 struct BitBuf {
     const uint32_t *words;
     uint32_t last;
-    uint64_t buf;
-    uint32_t nb, nw0, nw1, wp;
+    uint32_t hi, lo, nw;        // the word being consumed, the next one, the one after (look-ahead)
+    uint32_t pos, wp;           // bits of `hi` already consumed (0 .. 31); index of `nw`
     __device__ inline uint32_t word(uint32_t i) const { return words[i < last ? i : last]; }
     __device__ inline void open(const uint32_t *w, uint32_t last_, uint32_t w0) {
         words = w; last = last_;
-        buf = ((uint64_t)word(w0) << 32) | word(w0 + 1);
-        nb = 64;
-        nw0 = word(w0 + 2); nw1 = word(w0 + 3);
-        wp = w0 + 3;                            // index of nw1
+        hi = word(w0); lo = word(w0 + 1); nw = word(w0 + 2);
+        pos = 0;
+        wp = w0 + 2;
     }
     __device__ inline int32_t next(const DsTables &t) {
-        const uint32_t e = t.lut[(uint32_t)(buf >> (64 - kLutBits))];
+        const uint64_t both = (((uint64_t)hi << 32) | lo) << pos;          // the next 64 - pos bits, left-aligned
+        const uint32_t e = t.lut[(uint32_t)(both >> (64 - kLutBits))];
         uint32_t L = e & 0xffu;
         int32_t d = (int32_t)e >> 8;
         if (__builtin_expect(__ballot(e == 0u) != 0ull, 0)) {   // some lane met a code longer than the table: rare
             if (e == 0u) {
-                const uint64_t win = buf | ((uint64_t)nw0 >> (nb - 32u));
+                const uint64_t win = both | (pos ? (uint64_t)nw >> (32u - pos) : 0ull);
                 d = decode_long(win, t, &L);
-                if (L >= nb) {                  // the code runs into the look-ahead word: consume it here
-                    const uint32_t extra = L - nb;
-                    buf = ((uint64_t)nw0 << 32) << extra;
-                    nb = 32u - extra;
-                    nw0 = nw1; ++wp; nw1 = word(wp);
-                    L = 0;
+                if (pos + L >= 64u) {            // the code runs into the look-ahead word: move one word on here
+                    hi = lo; lo = nw; ++wp; nw = word(wp);
+                    pos -= 32u;
                 }
             }
         }
-        buf <<= L;
-        nb -= L;
-        // refill: below 33 valid bits the next word moves in
-        const bool need = nb <= 32u;
-        const uint64_t add = (uint64_t)nw0 << ((32u - nb) & 31u);
-        buf |= need ? add : 0ull;
-        nb += need ? 32u : 0u;
-        nw0 = need ? nw1 : nw0;
+        pos += L;
+        // a word is used up: the next ones move in (a look-up-table code is at most kLutBits long)
+        const bool need = pos >= 32u;
+        hi = need ? lo : hi;
+        lo = need ? nw : lo;
+        pos &= 31u;
         wp += need ? 1u : 0u;
-        nw1 = word(wp);
+        nw = word(wp);
         return d;
     }
 };
 
-// Decode the first `nsym` symbols of one chunk into dst[0 .. nsym) (int16).  When the chunk size
-// is a multiple of eight (dst is then 16-byte aligned) the residuals leave as 16-byte stores.
+// Decode the first `nsym` symbols of one chunk into dst[0 .. nsym) (int16).  Chunk sizes that are a
+// multiple of 32 (dst is then 64-byte aligned) collect 32 residuals in registers and write a whole
+// 64-byte sector with four back-to-back 16-byte stores: every lane keeps a line of its own open, far
+// more lines than the L2 holds, and 16-byte stores spread over time reached HBM as partial
+// sectors (3.4 times the bytes).  Other multiples of eight leave as single 16-byte stores.
 __device__ inline void decode_chunk(const uint32_t *words, uint32_t last, uint32_t w0, uint32_t S, uint32_t nsym, const DsTables &t, int16_t *dst) {
     BitBuf bb;
     bb.open(words, last, w0);
     uint32_t k = 0;
-    if ((S & 7u) == 0u) {
+    if ((S & 31u) == 0u) {
+        uint4 *dst16 = reinterpret_cast<uint4 *>(dst);
+        for (uint32_t k32 = 0; k32 < nsym / 32u; ++k32) {
+            uint32_t pk[16];                 // indexed by a wavefront-uniform counter: stays in registers
+#pragma unroll 4
+            for (int j = 0; j < 16; ++j) {
+                const uint32_t d0 = (uint32_t)bb.next(t) & 0xffffu;
+                const uint32_t d1 = (uint32_t)bb.next(t);
+                pk[j] = (d1 << 16) | d0;
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) dst16[k32 * 4u + j] = make_uint4(pk[4 * j], pk[4 * j + 1], pk[4 * j + 2], pk[4 * j + 3]);
+        }
+        k = nsym & ~31u;
+    } else if ((S & 7u) == 0u) {
         uint4 *dst16 = reinterpret_cast<uint4 *>(dst);
         for (uint32_t k8 = 0; k8 < nsym / 8u; ++k8) {
             uint32_t pk[4];

@@ -182,7 +182,16 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_pack(EncodeArgs a) {
 
     // words of all segments in front of mine
     uint64_t sum = 0;
-    for (uint32_t idx = tid; idx < seg; idx += kEncBlock) sum += a.desc[idx];
+    for (uint32_t i0 = 0; i0 < seg; i0 += 8u * kEncBlock) {              // eight loads in flight per thread
+        uint64_t v[8];
+#pragma unroll
+        for (uint32_t j = 0; j < 8; ++j) {
+            const uint32_t idx = i0 + j * kEncBlock + tid;
+            v[j] = (idx < seg) ? a.desc[idx] : 0ull;
+        }
+#pragma unroll
+        for (uint32_t j = 0; j < 8; ++j) sum += v[j];
+    }
     uint64_t base;
     (void)block_excl_scan<uint64_t, kEncBlock / kWave>(sum, s_part64, base);
     bool overflow = false;

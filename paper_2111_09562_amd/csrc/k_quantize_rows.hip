@@ -347,7 +347,16 @@ __global__ __launch_bounds__(kQuantBlock) void k_gather_records(QuantArgs a) {
 
     // records of all runs in front of this workgroup's first run
     uint64_t sum = 0;
-    for (uint32_t i = tid; i < run0; i += kQuantBlock) sum += a.run_count[i];
+    for (uint32_t i0 = 0; i0 < run0; i0 += 8u * kQuantBlock) {          // eight loads in flight per thread
+        uint32_t v[8];
+#pragma unroll
+        for (uint32_t j = 0; j < 8; ++j) {
+            const uint32_t i = i0 + j * kQuantBlock + tid;
+            v[j] = (i < run0) ? a.run_count[i] : 0u;
+        }
+#pragma unroll
+        for (uint32_t j = 0; j < 8; ++j) sum += v[j];
+    }
     uint64_t base;
     (void)block_excl_scan<uint64_t, kWaves>(sum, s_part64, base);
     uint32_t mine = 0;
