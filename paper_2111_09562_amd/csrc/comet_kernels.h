@@ -38,6 +38,7 @@ constexpr uint32_t kQuantRecLds = 3072;   // outlier records buffered in LDS per
 template <bool FULLWIN> __global__ void k_quantize(QuantArgs a);   // flat tiles, any plane width; FULLWIN: every bin is in the LDS window
 constexpr uint32_t kQuantRowsMaxW = 512;  // widest plane of the row-walking kernel
 constexpr uint32_t kQuantRecRun = 768;    // outlier records staged per run (one run of rows per wavefront)
+constexpr uint32_t kQuantRecLds2 = 256;   // records a wavefront buffers in LDS before it writes them to the staging area in bulk
 constexpr uint32_t kQuantRunsPerSimd = 5; // runs the launch aims at, per SIMD
 template <int NSEG, bool MULTI, bool FULLWIN> __global__ void k_quantize_rows(QuantArgs a);
 template <int NSEG, bool MULTI> __global__ void k_gather_records(QuantArgs a);

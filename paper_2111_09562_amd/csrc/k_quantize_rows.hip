@@ -65,7 +65,7 @@ struct SweepCounts {
 // FULLWIN: every histogram bin is in the LDS window.
 template <int NSEG, bool MULTI, bool FULLWIN, int PASS>
 __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint32_t row_hi, uint32_t lane, uint32_t *s_hist,
-                                      uint32_t hist_dummy, uint2 *rec_dst, uint64_t rec_cap, SweepCounts &cnt) {
+                                      uint32_t hist_dummy, uint2 *s_buf, uint2 *rec_dst, uint64_t rec_cap, SweepCounts &cnt) {
     const uint32_t W = a.divW.d, H = a.divH.d;
     const int32_t radius = a.radius;
     const uint32_t code_span = a.nbins - 1u;        // residual + radius - 1 must be below this
@@ -142,6 +142,17 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
                 else xb[u][s] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r_x, (int)((col[s] + soff) * 4u), 0, 0));
             }
         }
+    };
+    uint32_t buffered = 0;                                       // records waiting in s_buf (uniform)
+    auto flush_records = [&]() {                                 // s_buf[0 .. buffered) -> rec_dst[cur ...), coalesced
+        wave_lds_fence();
+        for (uint32_t i = lane; i < buffered; i += kWave) {
+            if (cur + i < rec_cap) rec_dst[cur + i] = s_buf[i];
+            else if (PASS == 1) atomicOr(&a.ctl->status, (uint32_t)ST_CAPACITY);
+        }
+        wave_lds_fence();
+        cur += buffered;
+        buffered = 0;
     };
     auto steps_of = [&](auto full_tag, uint32_t t0, float (&xb)[U][NSEG]) {
         constexpr bool FULL = decltype(full_tag)::value;
@@ -229,20 +240,17 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
                     }
                     const uint64_t em = __ballot(esc), vm = any_susp ? __ballot(verb) : 0ull;
                     if ((em | vm) == 0ull) continue;             // wavefront-uniform
-                    uint32_t pos = cur + __builtin_amdgcn_mbcnt_hi((uint32_t)(em >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)em, 0u));
+                    // Records go to a small LDS buffer first and leave in bulk: a global store here, in a
+                    // branch the compiler cannot count, would make every later wait for the prefetched
+                    // loads a wait for all stores.
+                    uint32_t pos = buffered + __builtin_amdgcn_mbcnt_hi((uint32_t)(em >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)em, 0u));
                     if (vm) pos += __builtin_amdgcn_mbcnt_hi((uint32_t)(vm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)vm, 0u));
                     const uint32_t e = e_lo + col[s] + soff;
-                    if (esc) {
-                        if (pos < rec_cap) rec_dst[pos] = make_uint2(2u * e, (uint32_t)d);
-                        else if (PASS == 1) atomicOr(&a.ctl->status, (uint32_t)ST_CAPACITY);
-                        ++pos;
-                    }
-                    if (verb) {
-                        if (pos < rec_cap) rec_dst[pos] = make_uint2(2u * e + 1u, __float_as_uint(x));
-                        else if (PASS == 1) atomicOr(&a.ctl->status, (uint32_t)ST_CAPACITY);
-                    }
-                    cur += (uint32_t)__popcll(em) + (uint32_t)__popcll(vm);
+                    if (esc) s_buf[pos++] = make_uint2(2u * e, (uint32_t)d);
+                    if (verb) s_buf[pos] = make_uint2(2u * e + 1u, __float_as_uint(x));
+                    buffered += (uint32_t)__popcll(em) + (uint32_t)__popcll(vm);
                     if (PASS == 0) cnt.vrec += (uint32_t)__popcll(vm);
+                    if (buffered > kQuantRecLds2 - 2u * kWave) flush_records();
                 }
             }
         }
@@ -267,6 +275,7 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
         fetch(general, t0, 0, xa);
         steps_of(general, t0, xa);
     }
+    flush_records();
     return cur;
 }
 
@@ -288,6 +297,7 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize_rows(QuantArgs a) {
     constexpr int kWaves = kQuantBlock / kWave;
     uint32_t *s_hist = s_dyn_qr;
     __shared__ uint64_t s_part64[kWaves];
+    __shared__ uint2 s_recbuf[kWaves][kQuantRecLds2];   // outlier records of a wavefront on their way to the staging area
 
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = (uint32_t)lane_id();
@@ -301,7 +311,7 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize_rows(QuantArgs a) {
     SweepCounts cnt;
     uint32_t my_records = 0;
     if (row_hi > row_lo)
-        my_records = sweep_rows<NSEG, MULTI, FULLWIN, 0>(a, row_lo, row_hi, lane, s_hist, (a.win_n << a.hist_shift) + tid,
+        my_records = sweep_rows<NSEG, MULTI, FULLWIN, 0>(a, row_lo, row_hi, lane, s_hist, (a.win_n << a.hist_shift) + tid, s_recbuf[wave],
                                                           reinterpret_cast<uint2 *>(a.stage) + (size_t)run * kQuantRecRun, kQuantRecRun, cnt);
     // per-run results: record count, non-zero inputs, verbatim records (summed up by the gather kernel;
     // thousands of atomics on one counter would cost more than the sweep)
@@ -339,6 +349,7 @@ template <int NSEG, bool MULTI>
 __global__ __launch_bounds__(kQuantBlock) void k_gather_records(QuantArgs a) {
     constexpr int kWaves = kQuantBlock / kWave;
     __shared__ uint64_t s_part64[kWaves];
+    __shared__ uint2 s_recbuf[kWaves][kQuantRecLds2];
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = (uint32_t)lane_id();
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / kWave));
@@ -391,7 +402,7 @@ __global__ __launch_bounds__(kQuantBlock) void k_gather_records(QuantArgs a) {
         uint32_t row_lo, row_hi;
         run_rows(a, run, &row_lo, &row_hi);
         SweepCounts unused;
-        (void)sweep_rows<NSEG, MULTI, true, 1>(a, row_lo, row_hi, lane, nullptr, 0, dst, room, unused);
+        (void)sweep_rows<NSEG, MULTI, true, 1>(a, row_lo, row_hi, lane, nullptr, 0, s_recbuf[wave], dst, room, unused);
     }
 }
 
