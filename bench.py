@@ -28,7 +28,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per mean launch of a kernel, from the rocprofv3 counter runs summarised under profiles/
 # (FETCH_SIZE + WRITE_SIZE, scaled by the same counters on a plain copy of known size); filled in by hand
 # from those summaries, None where no counter run covers the kernel
-TRAFFIC = {}
+TRAFFIC = {"k_quantize_rows": 184728541, "k_encode_count": 61132167, "k_encode_pack": 87320299,
+           "k_decode_chunks": 110566240, "k_scan_store": 203546909}
 
 
 def main() -> int:
@@ -132,15 +133,21 @@ def main() -> int:
         td = timed(decompress_all)
         sync_all()
 
-    # ---- per-kernel durations: K more steps of the same kind, this time with the library bracketing every
-    # launch with two HIP events on the launch's stream (the brackets cost about a tenth of the throughput
-    # when several streams are in use, so the timed region above runs without them) ----
+    # ---- per-kernel durations: K more steps with the library bracketing every launch with two HIP events on
+    # the launch's stream.  This pass runs one call at a time (a synchronisation after each), so that a
+    # kernel has the chip to itself and its duration says something about the kernel; the timed region above
+    # runs without brackets and with the layers overlapped ----
     for c in ctxs:
         c.comet_profile_enable(True)
         c.comet_profile_reset()
     for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
+        for i, (x, e, c) in enumerate(zip(xs, layers, conts)):
+            ctxs[owner[i]].comet_compress(x, e["eb"], e["nbins"], c, stream=streams[owner[i]], sync=False)
+            torch.cuda.synchronize()
+        for i in reversed(range(len(xs))):
+            ctxs[owner[i]].comet_decompress(conts[i], conts[i].numel(), xs[i].shape, outs[i], stream=streams[owner[i]])
+            torch.cuda.synchronize()
+    sync_all()
     kern = {}
     for kid, name in enumerate(comet.KERNEL_NAMES):
         launches, ms = 0, 0.0
@@ -171,10 +178,11 @@ def main() -> int:
                     avg_launch_us=round(avg_s * 1e6, 2), launches=launches,
                     alg_bytes_per_elem=round(alg[dom], 4),
                     note="mean over the five layers of the set; durations from HIP events recorded by the library on "
-                         "the stream of each launch, in a pass of K more identical steps right after the timed region "
-                         "(which runs without the brackets); with several streams a kernel shares the chip with the kernels of other "
-                         "layers, which lengthens its own duration; traffic = HBM bytes per mean launch from "
-                         "rocprofv3 FETCH_SIZE + WRITE_SIZE (profiles/), null if not collected")
+                         "the stream of each launch, in a pass of K more steps after the timed region in which the "
+                         "calls run one at a time (in the timed region the layers overlap on several streams and a "
+                         "kernel shares the chip, so its duration there measures the mix, not the kernel); traffic = "
+                         "HBM bytes per mean launch from rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by a copy of known "
+                         "size (profiles/hbm_traffic_resnet50_set_batch64.txt)")
     # path-level figures: bytes the kernels of a path must move per element (compress: 6 + 4 + b, decompress:
     # b + 2 + 6) and the smallest any codec could move (4 + b each way)
     step_s = dt / args.steps
