@@ -345,6 +345,7 @@ int comet_create(comet_ctx **out, uint64_t max_elems, uint32_t max_nbins) {
         const uint64_t o_first = o; o += 8ull * 72;
         const uint64_t o_findex = o; o += 4ull * 72;
         const uint64_t o_lut = o; o += 4ull * kLutSize;
+        const uint64_t o_lut16 = o; o += 2ull * kLut16Size;
         const uint64_t o_meta = o; o += 64;
         const uint64_t o_sorted = o; o += 2ull * kMaxBins;
         uint8_t *blob = nullptr;
@@ -355,6 +356,7 @@ int comet_create(comet_ctx **out, uint64_t max_elems, uint32_t max_nbins) {
         c->tables.limit = (uint64_t *)(blob + o_limit); c->tables.first_code = (uint64_t *)(blob + o_first);
         c->tables.first_index = (uint32_t *)(blob + o_findex); c->tables.lut = (uint32_t *)(blob + o_lut);
         c->tables.meta = (uint32_t *)(blob + o_meta); c->tables.sorted = (uint16_t *)(blob + o_sorted);
+        c->tables.lut16 = (uint16_t *)(blob + o_lut16);
     }
     if ((e = hipHostMalloc((void **)&c->host_state, sizeof(DevState) + sizeof(Header), hipHostMallocDefault)) != hipSuccess)
         return fail(COMET_ERR_NOMEM);

@@ -102,15 +102,24 @@ template <int S, bool FULLTBL> __global__ void k_encode_pack(EncodeArgs a);
 // ---- decode tables ------------------------------------------------------------
 constexpr int kLutBits = 11;
 constexpr uint32_t kLutSize = 1u << kLutBits;
+// Alphabets of at most kLut16MaxBins bins (residuals fit 12 signed bits) also get a compact table on
+// the next 12 bits: same 8 KB of LDS, half as many codes too long for it.
+constexpr int kLut16Bits = 12;
+constexpr uint32_t kLut16Size = 1u << kLut16Bits;
+constexpr uint32_t kLut16MaxBins = 4096;
+constexpr int32_t kLut16Escape = -2048;    // residual value that stands for the escape symbol in the compact table
 
 struct DecodeTables {          // all in the workspace (global memory)
     uint32_t *lut;             // kLutSize entries: (residual << 8) | length with residual = symbol - radius
-                               // (-32768 for the escape symbol 0); 0 = code longer than kLutBits
+                               // (-32768 for the escape symbol 0); length 0 = code longer than kLutBits, the
+                               // residual field then holds the shortest length a code with this prefix can have
     uint64_t *limit;           // [65]: left-aligned exclusive upper bound of the codes of each length
     uint64_t *first_code;      // [65]
     uint32_t *first_index;     // [65]: position of the first symbol of each length in `sorted`
+    uint16_t *lut16;           // kLut16Size entries: (residual << 4) | length, residual in 12 signed bits (kLut16Escape for
+                               // the escape symbol); length 0 = longer code, the residual field is the shortest length
     uint16_t *sorted;          // symbols in canonical (length, symbol) order
-    uint32_t *meta;            // [0] max_len, [1] n_active, [2] min_len
+    uint32_t *meta;            // [0] max_len, [1] n_active, [2] min_len, [3] radius, [4] 1 if lut16 is valid
 };
 
 struct TablesArgs {

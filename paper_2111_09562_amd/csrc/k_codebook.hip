@@ -467,9 +467,41 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
                 break;
             }
         }
+        if (entry == 0) {
+            // no code of at most kLutBits bits starts here: length byte 0, and in the residual field the
+            // shortest length a code with this prefix can have (where the decoder's search starts)
+            uint32_t L = (uint32_t)kLutBits + 1u;
+            while (L < mx && v >= s_limit[L]) ++L;
+            entry = L << 8;
+        }
         a.t.lut[e] = entry;
     }
-    if (tid == 0) a.t.meta[3] = (uint32_t)radius;
+    // the compact table on the next kLut16Bits bits, for alphabets whose residuals fit 12 signed bits
+    const bool compact = nbins <= kLut16MaxBins;
+    if (compact) {
+        for (uint32_t e = tid; e < kLut16Size; e += kBookBlock) {
+            const uint64_t v = (uint64_t)e << (64 - kLut16Bits);
+            uint32_t entry = 0;
+            const uint32_t top = mx < (uint32_t)kLut16Bits ? mx : (uint32_t)kLut16Bits;
+            for (uint32_t L = 1; L <= top; ++L) {
+                if (s_cnt[L] && (v < s_limit[L] || L == mx)) {
+                    uint64_t off = (v >> (64u - L)) - s_first[L];
+                    if (off >= s_cnt[L]) off = s_cnt[L] - 1u;      // only reachable with an invalid stream
+                    const uint32_t sym = (uint32_t)(keys[s_findex[L] + off] & 0xffffu);
+                    const int32_t d = sym ? (int32_t)sym - radius : kLut16Escape;
+                    entry = (((uint32_t)d & 0xfffu) << 4) | L;
+                    break;
+                }
+            }
+            if (entry == 0) {
+                uint32_t L = (uint32_t)kLut16Bits + 1u;
+                while (L < mx && v >= s_limit[L]) ++L;
+                entry = L << 4;
+            }
+            a.t.lut16[e] = (uint16_t)entry;
+        }
+    }
+    if (tid == 0) { a.t.meta[3] = (uint32_t)radius; a.t.meta[4] = compact ? 1u : 0u; }
 }
 
 }  // namespace comet

@@ -32,7 +32,7 @@ namespace {
 constexpr int32_t kEscape = -32768;
 
 struct DsTables {
-    const uint32_t *lut;        // LDS
+    const uint32_t *lut;        // LDS: the 11-bit table (u32 entries) or the compact 12-bit one (u16 entries)
     const uint64_t *limit, *first;
     const uint32_t *findex;
     const uint16_t *sorted;     // global: symbols in canonical order
@@ -40,11 +40,13 @@ struct DsTables {
     uint32_t tail0, tail_n;
     uint32_t max_len, n_active;
     int32_t radius;
+    int32_t escape;             // residual value that stands for the escape symbol in the work buffer
 };
 
-// Codes longer than the look-up table: canonical search by length.
-__device__ inline int32_t decode_long(uint64_t win, const DsTables &t, uint32_t *len_out) {
-    uint32_t L = kLutBits + 1;
+// Codes longer than the look-up table: canonical search by length, from the shortest length the
+// table entry says this prefix can have.
+__device__ inline int32_t decode_long(uint64_t win, uint32_t start, uint32_t lut_bits, const DsTables &t, uint32_t *len_out) {
+    uint32_t L = start > lut_bits ? start : lut_bits + 1u;
     while (L < t.max_len && win >= t.limit[L]) ++L;
     if (L > 57u) L = 57u;
     uint64_t idx = t.findex[L] + ((win >> (64u - L)) - t.first[L]);
@@ -53,14 +55,18 @@ __device__ inline int32_t decode_long(uint64_t win, const DsTables &t, uint32_t 
     const uint32_t ti = (uint32_t)idx - t.tail0;
     if (ti < t.tail_n) return (int32_t)t.tail[ti];
     const uint32_t sym = t.sorted[idx];                      // very large alphabets only
-    return sym ? (int32_t)sym - t.radius : kEscape;
+    return sym ? (int32_t)sym - t.radius : t.escape;
 }
 
 // Bit reader of one lane: two words of the stream plus a bit position inside the
 // first one, and one word of look-ahead so that no load sits on the critical
-// path.  Words are read from words[min(i, last)].  Everything in next() is
-// branch-free except the wavefront-uniform test for a long code.
+// path.  Words are read from words[min(i, last)].  Everything is branch-free
+// except the wavefront-uniform test for a code longer than the look-up table.
+// C16: the compact table (12 bits, u16 entries (residual << 4) | length), else the
+// general one (11 bits, u32 entries (residual << 8) | length).
+template <bool C16>
 struct BitBuf {
+    static constexpr int kBits = C16 ? kLut16Bits : kLutBits;
     const uint32_t *words;
     uint32_t last;
     uint32_t hi, lo, nw;        // the word being consumed, the next one, the one after (look-ahead)
@@ -72,15 +78,23 @@ struct BitBuf {
         pos = 0;
         wp = w0 + 2;
     }
+    static __device__ inline uint32_t look(const DsTables &t, uint64_t window) {
+        const uint32_t idx = (uint32_t)(window >> (64 - kBits));
+        return C16 ? (uint32_t)reinterpret_cast<const uint16_t *>(t.lut)[idx] : t.lut[idx];
+    }
+    static __device__ inline uint32_t len_of(uint32_t e) { return C16 ? (e & 0xfu) : (e & 0xffu); }
+    static __device__ inline int32_t resid_of(uint32_t e) { return C16 ? ((int32_t)(e << 16) >> 20) : ((int32_t)e >> 8); }
+    static __device__ inline uint32_t hint_of(uint32_t e) { return C16 ? (e >> 4) : (e >> 8); }
+
     __device__ inline int32_t next(const DsTables &t) {
         const uint64_t both = (((uint64_t)hi << 32) | lo) << pos;          // the next 64 - pos bits, left-aligned
-        const uint32_t e = t.lut[(uint32_t)(both >> (64 - kLutBits))];
-        uint32_t L = e & 0xffu;
-        int32_t d = (int32_t)e >> 8;
-        if (__builtin_expect(__ballot(e == 0u) != 0ull, 0)) {   // some lane met a code longer than the table: rare
-            if (e == 0u) {
+        const uint32_t e = look(t, both);
+        uint32_t L = len_of(e);
+        int32_t d = resid_of(e);
+        if (__builtin_expect(__ballot(L == 0u) != 0ull, 0)) {   // some lane met a code longer than the table: rare
+            if (L == 0u) {
                 const uint64_t win = both | (pos ? (uint64_t)nw >> (32u - pos) : 0ull);
-                d = decode_long(win, t, &L);
+                d = decode_long(win, hint_of(e), (uint32_t)kBits, t, &L);
                 if (pos + L >= 64u) {            // the code runs into the look-ahead word: move one word on here
                     hi = lo; lo = nw; ++wp; nw = word(wp);
                     pos -= 32u;
@@ -88,7 +102,7 @@ struct BitBuf {
             }
         }
         pos += L;
-        // a word is used up: the next ones move in (a look-up-table code is at most kLutBits long)
+        // a word is used up: the next ones move in (a look-up-table code is at most kBits long)
         const bool need = pos >= 32u;
         hi = need ? lo : hi;
         lo = need ? nw : lo;
@@ -97,6 +111,30 @@ struct BitBuf {
         nw = word(wp);
         return d;
     }
+    // Two symbols packed as (second << 16) | (first & 0xffff).  Two look-up-table codes take at most
+    // 24 bits, so after the first one there are still at least kBits valid bits in the two words and
+    // the words move on only once per pair.  If either code is longer than the table
+    // (wavefront-uniform test) the pair is decoded again one symbol at a time.
+    __device__ inline uint32_t next_pair(const DsTables &t) {
+        const uint64_t both = ((uint64_t)hi << 32) | lo;
+        const uint32_t e0 = look(t, both << pos);
+        const uint32_t p1 = pos + len_of(e0);
+        const uint32_t e1 = look(t, both << p1);
+        if (__builtin_expect(__ballot(len_of(e0) == 0u || len_of(e1) == 0u) != 0ull, 0)) {
+            const uint32_t d0 = (uint32_t)next(t) & 0xffffu;
+            const uint32_t d1 = (uint32_t)next(t);
+            return (d1 << 16) | d0;
+        }
+        const uint32_t p2 = p1 + len_of(e1);
+        const bool need = p2 >= 32u;
+        hi = need ? lo : hi;
+        lo = need ? nw : lo;
+        pos = p2 & 31u;
+        wp += need ? 1u : 0u;
+        nw = word(wp);
+        if (C16) return ((uint32_t)resid_of(e1) << 16) | ((uint32_t)resid_of(e0) & 0xffffu);
+        return __builtin_amdgcn_perm(e1, e0, 0x06050201u);      // bytes 1, 2 of each entry: the two residuals
+    }
 };
 
 // Decode the first `nsym` symbols of one chunk into dst[0 .. nsym) (int16).  Chunk sizes that are a
@@ -104,8 +142,9 @@ struct BitBuf {
 // 64-byte sector with four back-to-back 16-byte stores: every lane keeps a line of its own open, far
 // more lines than the L2 holds, and 16-byte stores spread over time reached HBM as partial
 // sectors (3.4 times the bytes).  Other multiples of eight leave as single 16-byte stores.
+template <bool C16>
 __device__ inline void decode_chunk(const uint32_t *words, uint32_t last, uint32_t w0, uint32_t S, uint32_t nsym, const DsTables &t, int16_t *dst) {
-    BitBuf bb;
+    BitBuf<C16> bb;
     bb.open(words, last, w0);
     uint32_t k = 0;
     if ((S & 31u) == 0u) {
@@ -113,11 +152,7 @@ __device__ inline void decode_chunk(const uint32_t *words, uint32_t last, uint32
         for (uint32_t k32 = 0; k32 < nsym / 32u; ++k32) {
             uint32_t pk[16];                 // indexed by a wavefront-uniform counter: stays in registers
 #pragma unroll 4
-            for (int j = 0; j < 16; ++j) {
-                const uint32_t d0 = (uint32_t)bb.next(t) & 0xffffu;
-                const uint32_t d1 = (uint32_t)bb.next(t);
-                pk[j] = (d1 << 16) | d0;
-            }
+            for (int j = 0; j < 16; ++j) pk[j] = bb.next_pair(t);
 #pragma unroll
             for (int j = 0; j < 4; ++j) dst16[k32 * 4u + j] = make_uint4(pk[4 * j], pk[4 * j + 1], pk[4 * j + 2], pk[4 * j + 3]);
         }
@@ -127,11 +162,7 @@ __device__ inline void decode_chunk(const uint32_t *words, uint32_t last, uint32
         for (uint32_t k8 = 0; k8 < nsym / 8u; ++k8) {
             uint32_t pk[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint32_t d0 = (uint32_t)bb.next(t) & 0xffffu;
-                const uint32_t d1 = (uint32_t)bb.next(t);
-                pk[j] = (d1 << 16) | d0;
-            }
+            for (int j = 0; j < 4; ++j) pk[j] = bb.next_pair(t);
             dst16[k8] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
         }
         k = nsym & ~7u;
@@ -210,18 +241,24 @@ __global__ __launch_bounds__(kDsBlock) void k_decode_chunks(DsArgs a) {
     const uint32_t S = hdr->chunk_syms;
     const uint32_t n_chunks = hdr->n_chunks;
 
-    for (uint32_t i = tid; i < kLutSize; i += kDsBlock) s_lut[i] = a.t.lut[i];
+    const bool c16 = a.t.meta[4] != 0u;                     // the compact table exists: use it
+    {
+        const uint32_t *src = c16 ? reinterpret_cast<const uint32_t *>(a.t.lut16) : a.t.lut;   // either is kLutSize dwords
+        for (uint32_t i = tid; i < kLutSize; i += kDsBlock) s_lut[i] = src[i];
+    }
     for (uint32_t i = tid; i < 65u; i += kDsBlock) { s_limit[i] = a.t.limit[i]; s_first[i] = a.t.first_code[i]; s_findex[i] = a.t.first_index[i]; }
     DsTables t;
     t.lut = s_lut; t.limit = s_limit; t.first = s_first; t.findex = s_findex; t.sorted = a.t.sorted;
     t.max_len = a.t.meta[0]; t.n_active = a.t.meta[1]; t.radius = (int32_t)(hdr->nbins / 2u);
     // residuals of the symbols whose codes are longer than the look-up table, in canonical order
     t.tail = s_tail;
-    t.tail0 = (t.max_len > (uint32_t)kLutBits) ? a.t.first_index[kLutBits + 1] : t.n_active;
+    const uint32_t lut_bits = c16 ? (uint32_t)kLut16Bits : (uint32_t)kLutBits;
+    t.escape = c16 ? kLut16Escape : kEscape;
+    t.tail0 = (t.max_len > lut_bits) ? a.t.first_index[lut_bits + 1u] : t.n_active;
     t.tail_n = t.n_active - t.tail0 < kDsTailEntries ? t.n_active - t.tail0 : kDsTailEntries;
     for (uint32_t i = tid; i < t.tail_n; i += kDsBlock) {
         const uint32_t sym = a.t.sorted[t.tail0 + i];
-        s_tail[i] = (int16_t)(sym ? (int32_t)sym - t.radius : kEscape);
+        s_tail[i] = (int16_t)(sym ? (int32_t)sym - t.radius : t.escape);
     }
     __syncthreads();
 
@@ -252,8 +289,13 @@ __global__ __launch_bounds__(kDsBlock) void k_decode_chunks(DsArgs a) {
             const uint64_t s0 = (uint64_t)c * S;
             const uint32_t nsym = (a.n - s0 < (uint64_t)S) ? (uint32_t)(a.n - s0) : S;
             int16_t *dst = a.resid + s0;
-            if (all_staged) decode_chunk(stage, n_words - 1u, w0, S, nsym, t, dst);          // words in LDS
-            else decode_chunk(payload + w_begin, n_words - 1u, w0, S, nsym, t, dst);         // too many for LDS: read them in place
+            if (c16) {
+                if (all_staged) decode_chunk<true>(stage, n_words - 1u, w0, S, nsym, t, dst);          // words in LDS
+                else decode_chunk<true>(payload + w_begin, n_words - 1u, w0, S, nsym, t, dst);         // too many for LDS: read them in place
+            } else {
+                if (all_staged) decode_chunk<false>(stage, n_words - 1u, w0, S, nsym, t, dst);
+                else decode_chunk<false>(payload + w_begin, n_words - 1u, w0, S, nsym, t, dst);
+            }
         }
         wave_lds_fence();
     }
@@ -278,6 +320,7 @@ __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
     const uint32_t n_rec = hdr->n_rec;
     const float eb = __uint_as_float(hdr->eb_bits);
     const float ebx2 = __uint_as_float(hdr->ebx2_bits);
+    const int32_t esc_marker = a.t.meta[4] ? kLut16Escape : kEscape;   // what the decode kernel wrote for escaped residuals
     uint32_t *list = s_dyn_ds + wave * kScanListWords;       // pairs (element offset inside the strip, residual)
     constexpr uint32_t kListCap = kScanListWords / 2u;
 
@@ -407,7 +450,7 @@ __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
                             uint32_t off = col[s] + roff;
                             off = off > 0x3fffffffu ? 0x3fffffffu : off;
                             int32_t d = dd[u][s];
-                            const bool is_esc = d == kEscape;
+                            const bool is_esc = d == esc_marker;
                             const uint64_t any_esc = __ballot(is_esc);
                             if (any_esc) {                            // wavefront-uniform
                                 const uint64_t m = any_esc & slot_mask;

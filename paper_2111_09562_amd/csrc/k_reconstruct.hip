@@ -52,13 +52,14 @@ struct LdsTables {
 __device__ inline uint32_t decode_symbol(BitReader &br, const LdsTables &t) {
     const uint32_t e = t.lut[br.buf >> (64 - kLutBits)];
     uint32_t L, sym;
-    if (e) {
+    if (e & 0xffu) {
         L = e & 0xffu;
         const int32_t d = (int32_t)e >> 8;                  // the table holds residuals
         sym = (d == -32768) ? 0u : (uint32_t)(d + t.radius);
     } else {
         const uint64_t win = br.buf | ((uint64_t)br.nw >> (br.nb - 32u));
-        L = kLutBits + 1;
+        L = e >> 8;                                         // the shortest length this prefix can have
+        if (L <= (uint32_t)kLutBits) L = kLutBits + 1;
         while (L < t.max_len && win >= t.limit[L]) ++L;
         if (L > 57u) L = 57u;
         uint64_t idx = t.findex[L] + ((win >> (64u - L)) - t.first[L]);
