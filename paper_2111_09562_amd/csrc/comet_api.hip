@@ -478,20 +478,22 @@ int comet_decompress(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_s
     if (!recon_geometry(s, &g)) return COMET_ERR_INVALID;
     HIP_TRY(hipMemsetAsync(ctx->zero_region, 0, sizeof(Control), st));
     const uint8_t *in = static_cast<const uint8_t *>(dev_in);
+    // lanes of a wavefront side by side in one row of the scan kernel (planes x columns)
+    const uint32_t ppi = s.w <= 16u ? 4u * (16u / s.w) : (s.w <= 32u ? 2u : 1u);
+    const bool fast_path = s.w <= kDsMaxW && (uint64_t)ppi * s.h * s.w < (1ull << 28);
     {
         TablesArgs t{};
         t.len = in + kHeaderBytes; t.nbins = 0; t.t = ctx->tables; t.keys = ctx->book.keys; t.ctl = &ctx->state->ctl;
         t.hdr = reinterpret_cast<const Header *>(in);
         t.expect.N = s.n; t.expect.C = s.c; t.expect.H = s.h; t.expect.W = s.w; t.bytes = bytes;
+        t.compact_only = fast_path ? 1u : 0u;
         {
             TimedScope ts(ctx, st, COMET_KERNEL_TABLES);
             hipLaunchKernelGGL(k_decode_tables, dim3(1), dim3(kBookBlock), 0, st, t);
         }
         HIP_TRY(hipGetLastError());
     }
-    // lanes of a wavefront side by side in one row of the scan kernel (planes x columns)
-    const uint32_t ppi = s.w <= 16u ? 4u * (16u / s.w) : (s.w <= 32u ? 2u : 1u);
-    if (s.w <= kDsMaxW && (uint64_t)ppi * s.h * s.w < (1ull << 28)) {
+    if (fast_path) {
         // fast path: Huffman decode into int16 residuals (the code buffer of the context doubles as
         // the work buffer), then scans and stores
         DsArgs d{};

@@ -61,6 +61,10 @@ __device__ inline void wave_lds_fence() {
     __builtin_amdgcn_wave_barrier();
 }
 
+// Lanes of the wavefront for which `p` holds.  (The HIP __ballot takes an int: its bool -> int -> compare
+// round trip costs two extra vector instructions per call.)
+__device__ inline uint64_t wave_ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
+
 __host__ __device__ inline uint64_t align16(uint64_t v) { return (v + 15u) & ~(uint64_t)15u; }
 
 // ---------------------------------------------------------------------------

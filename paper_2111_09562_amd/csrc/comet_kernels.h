@@ -127,6 +127,8 @@ struct TablesArgs {
     uint32_t nbins;
     DecodeTables t;
     uint64_t *keys;            // sort scratch (global), >= 65536 entries
+    uint32_t compact_only;     // 1: the caller decodes with k_decode_chunks, which uses the compact table whenever it
+                               //    exists, so the general table need not be filled in that case
     Control *ctl;
     // container validation (null = stage call)
     const Header *hdr;

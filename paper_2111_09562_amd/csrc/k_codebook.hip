@@ -453,7 +453,8 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
     // look-up table on the next kLutBits bits; entries carry the residual, not the symbol
     const uint32_t mx = s_maxlen;
     const int32_t radius = (int32_t)(nbins / 2u);
-    for (uint32_t e = tid; e < kLutSize; e += kBookBlock) {
+    const bool compact = nbins <= kLut16MaxBins;
+    for (uint32_t e = tid; e < ((compact && a.compact_only) ? 0u : kLutSize); e += kBookBlock) {
         const uint64_t v = (uint64_t)e << (64 - kLutBits);
         uint32_t entry = 0;
         const uint32_t top = mx < (uint32_t)kLutBits ? mx : (uint32_t)kLutBits;
@@ -477,7 +478,6 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
         a.t.lut[e] = entry;
     }
     // the compact table on the next kLut16Bits bits, for alphabets whose residuals fit 12 signed bits
-    const bool compact = nbins <= kLut16MaxBins;
     if (compact) {
         for (uint32_t e = tid; e < kLut16Size; e += kBookBlock) {
             const uint64_t v = (uint64_t)e << (64 - kLut16Bits);

@@ -91,7 +91,7 @@ struct BitBuf {
         const uint32_t e = look(t, both);
         uint32_t L = len_of(e);
         int32_t d = resid_of(e);
-        if (__builtin_expect(__ballot(L == 0u) != 0ull, 0)) {   // some lane met a code longer than the table: rare
+        if (__builtin_expect(wave_ballot(L == 0u) != 0ull, 0)) {   // some lane met a code longer than the table: rare
             if (L == 0u) {
                 const uint64_t win = both | (pos ? (uint64_t)nw >> (32u - pos) : 0ull);
                 d = decode_long(win, hint_of(e), (uint32_t)kBits, t, &L);
@@ -120,7 +120,7 @@ struct BitBuf {
         const uint32_t e0 = look(t, both << pos);
         const uint32_t p1 = pos + len_of(e0);
         const uint32_t e1 = look(t, both << p1);
-        if (__builtin_expect(__ballot(len_of(e0) == 0u || len_of(e1) == 0u) != 0ull, 0)) {
+        if (__builtin_expect(wave_ballot(len_of(e0) == 0u || len_of(e1) == 0u) != 0ull, 0)) {
             const uint32_t d0 = (uint32_t)next(t) & 0xffffu;
             const uint32_t d1 = (uint32_t)next(t);
             return (d1 << 16) | d0;
@@ -204,7 +204,7 @@ __device__ inline uint32_t rec_lower_bound(const uint32_t *rec, uint32_t lo, uin
         const uint32_t step = (hi - lo + 64u) / 65u;
         const uint32_t p = lo + (lane + 1u) * step - 1u;
         const bool less = (p < hi) ? (rec[2 * (size_t)p] < target) : false;
-        const uint32_t c = (uint32_t)__popcll(__ballot(less));
+        const uint32_t c = (uint32_t)__popcll(wave_ballot(less));
         const uint32_t pc = lo + (c + 1u) * step - 1u;
         hi = (c < (uint32_t)kWave && pc < hi) ? pc : hi;
         lo = lo + c * step;
@@ -385,8 +385,8 @@ __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
                     uint32_t key = 1u, val = 0;
                     if (k < r_end) { key = rec[2 * (size_t)k]; val = rec[2 * (size_t)k + 1]; }
                     const bool esc = k < r_end && !(key & 1u);
-                    const uint64_t esc_mask = __ballot(esc);
-                    if (__ballot(k < r_end && (key & 1u))) has_verbatim = true;
+                    const uint64_t esc_mask = wave_ballot(esc);
+                    if (wave_ballot(k < r_end && (key & 1u))) has_verbatim = true;
                     if (esc) {
                         const uint32_t pos = n_esc + (uint32_t)__popcll(esc_mask & lt_mask);
                         if (pos < kListCap) { list[2 * pos] = (key >> 1) - e0; list[2 * pos + 1] = val; }
@@ -451,7 +451,7 @@ __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
                             off = off > 0x3fffffffu ? 0x3fffffffu : off;
                             int32_t d = dd[u][s];
                             const bool is_esc = d == esc_marker;
-                            const uint64_t any_esc = __ballot(is_esc);
+                            const uint64_t any_esc = wave_ballot(is_esc);
                             if (any_esc) {                            // wavefront-uniform
                                 const uint64_t m = any_esc & slot_mask;
                                 if (is_esc) {

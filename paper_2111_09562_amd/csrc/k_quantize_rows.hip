@@ -195,8 +195,8 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
                 const float err = fabsf(x - qf * a.ebx2);
                 const bool suspicious = !(err <= eb_lo);        // also true for NaN / Inf / huge inputs
                 dsave[u][s] = d;
-                flag_esc |= __ballot(valid && !inrange);
-                flag_susp |= __ballot(valid && suspicious);
+                flag_esc |= wave_ballot(valid && !inrange);
+                flag_susp |= wave_ballot(valid && suspicious);
                 if (PASS == 0) {
                     cnt.nnz_lane += (x != 0.0f) ? 1u : 0u;      // lanes without an element hold 0
                     // Histogram: no divergent branch (switching the execution mask costs more than the
@@ -238,7 +238,7 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
                         const bool suspicious = !(fabsf(x - (float)q * a.ebx2) <= eb_lo);
                         if (valid && suspicious) verb = needs_verbatim_rows(x, q, a.r, a.ebx2, a.eb);
                     }
-                    const uint64_t em = __ballot(esc), vm = any_susp ? __ballot(verb) : 0ull;
+                    const uint64_t em = wave_ballot(esc), vm = any_susp ? wave_ballot(verb) : 0ull;
                     if ((em | vm) == 0ull) continue;             // wavefront-uniform
                     // Records go to a small LDS buffer first and leave in bulk: a global store here, in a
                     // branch the compiler cannot count, would make every later wait for the prefetched
