@@ -28,8 +28,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per mean launch of a kernel, from the rocprofv3 counter runs summarised under profiles/
 # (FETCH_SIZE + WRITE_SIZE, scaled by the same counters on a plain copy of known size); filled in by hand
 # from those summaries, None where no counter run covers the kernel
-TRAFFIC = {"k_quantize_rows": 184728541, "k_encode_count": 61132167, "k_encode_pack": 87320299,
-           "k_decode_chunks": 110566240, "k_scan_store": 203546909}
+TRAFFIC = {"k_quantize_rows": 184717386, "k_encode_count": 61144691, "k_encode_pack": 87332120,
+           "k_decode_chunks": 104454575, "k_scan_store": 203526995}
 
 
 def main() -> int:

@@ -3,12 +3,16 @@
 //
 //   k_decode_chunks: chunk-parallel Huffman decode.  A wavefront takes 64
 //     consecutive chunks, copies their words global -> LDS with coalesced loads and
-//     decodes one chunk per lane: a 64-bit bit buffer per lane refilled from LDS
-//     (two words of look-ahead so that no load sits on the critical path) and an
-//     11-bit look-up table whose entries already hold the residual (code - radius).
-//     Eight residuals are packed into 16 bytes and stored as int16 into a work
-//     buffer.  The kernel needs about 9 KB of LDS per wavefront, so four
-//     wavefronts per SIMD hide the latency of the serial decode chain.
+//     decodes one chunk per lane: two words of the stream and a bit position per
+//     lane, one word of look-ahead from LDS so that no load sits on the critical
+//     path, and a look-up table whose entries already hold the residual (code -
+//     radius): 12 bits and 16-bit entries for alphabets up to 4096 bins, else 11
+//     bits and 32-bit entries (8 KB of LDS either way).  Symbols are decoded in
+//     pairs (one refill per pair); codes longer than the table take a
+//     wavefront-uniform slow path that starts its search at the length the table
+//     entry gives.  32 residuals are collected in registers and leave as int16
+//     in four back-to-back 16-byte stores.  The kernel needs about 9 KB of LDS per
+//     wavefront, so four wavefronts per SIMD share the issue slots.
 //
 //   k_scan_store: Lorenzo reconstruction -> dequantise -> verbatim values ->
 //     re-zero filter -> store.  Lanes are columns.  Row by row a wavefront reads 64

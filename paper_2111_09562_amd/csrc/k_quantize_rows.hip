@@ -20,7 +20,8 @@
 //
 // Outlier records (escapes and verbatim values) must end up in the container in
 // element order.  k_quantize_rows appends them, in order, to a staging area of
-// its run and leaves the count; k_gather_records, a second small kernel, adds up
+// its run (through a small LDS buffer, so that the main loop holds no global store
+// the compiler cannot count) and leaves the count; k_gather_records, a second small kernel, adds up
 // the counts of the runs in front of a run and moves its records to their final
 // place (a run with more records than its staging area holds is swept again, this
 // time writing in place).  Nothing waits for anything inside a kernel.
