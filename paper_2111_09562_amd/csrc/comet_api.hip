@@ -91,15 +91,24 @@ struct comet_ctx {
 namespace {
 
 struct ZeroLayout {          // sub-allocation of the zero region for one call
-    uint64_t off_hist, off_desc_q, off_desc_e, bytes;
+    uint64_t off_hist, off_parts, off_desc_q, off_desc_e, bytes;
 };
 
-ZeroLayout zero_layout(uint32_t nbins, uint64_t tiles_q, uint64_t tiles_e) {
+// partial histograms of the row-walking quantise kernel for an alphabet of nbins
+uint32_t hist_copies(uint32_t nbins) {
+    const uint32_t c = kQuantHistPartsWords / (nbins ? nbins : 1u);
+    return c < 1u ? 1u : (c > kQuantHistCopiesMax ? kQuantHistCopiesMax : c);
+}
+
+// nbins_hist: entries of the histogram itself (0 if the caller brings its own), nbins_parts: alphabet
+// the partial histograms are for (0: none)
+ZeroLayout zero_layout(uint32_t nbins_hist, uint32_t nbins_parts, uint64_t tiles_q, uint64_t tiles_e) {
     ZeroLayout z;
     uint64_t o = align_up(sizeof(Control), 256);
     z.off_desc_q = o; o += align_up(8 * tiles_q, 256);
     z.off_desc_e = o; o += align_up(8 * tiles_e, 256);
-    z.off_hist = o; o += align_up(4ull * nbins, 256);
+    z.off_hist = o; o += align_up(4ull * nbins_hist, 256);
+    z.off_parts = o; o += align_up(4ull * nbins_parts * hist_copies(nbins_parts), 256);
     z.bytes = o;
     return z;
 }
@@ -169,11 +178,12 @@ void encode_geometry(const comet_ctx *ctx, uint64_t n_chunks, uint32_t *seg_chun
 // Work split of the quantise kernel.  rows: the row-walking kernel (planes up to kQuantRowsMaxW
 // columns) with `grid` workgroups of four wavefronts, each wavefront on rows_per_wave consecutive
 // rows; otherwise the flat-tile kernel with `grid` segments of tiles.
-struct QuantGeom { bool rows; uint32_t grid, rows_per_wave, rows_per_step; };
-QuantGeom quantize_geometry(const comet_ctx *ctx, comet_shape s, uint64_t n);
+// vec: columns per lane of the row-walking kernel (2 if W is even and the input is 8-byte aligned).
+struct QuantGeom { bool rows; uint32_t grid, rows_per_wave, rows_per_step, vec; };
+QuantGeom quantize_geometry(const comet_ctx *ctx, comet_shape s, uint64_t n, const float *x);
 
 int launch_quantize(comet_ctx *ctx, const float *x, comet_shape s, uint64_t n, float eb, uint32_t nbins,
-                    hipStream_t st, uint16_t *codes, uint32_t *hist, uint32_t *rec, uint64_t rec_cap,
+                    hipStream_t st, uint16_t *codes, uint32_t *hist, uint32_t *hist_parts, uint32_t *rec, uint64_t rec_cap,
                     uint64_t *desc) {
     QuantArgs a{};
     a.x = x; a.n = n;
@@ -184,7 +194,7 @@ int launch_quantize(comet_ctx *ctx, const float *x, comet_shape s, uint64_t n, f
     a.win_lo = (nbins - a.win_n) / 2u;
     a.n_tiles = (uint32_t)((n + kQuantTile - 1) / kQuantTile);
     a.codes = codes; a.hist = hist; a.rec = rec; a.rec_cap = rec_cap; a.desc = desc; a.ctl = &ctx->state->ctl;
-    const QuantGeom g = quantize_geometry(ctx, s, n);
+    const QuantGeom g = quantize_geometry(ctx, s, n, x);
     const uint32_t grid = g.grid;
     if (g.rows) {
         a.rows_total = (uint32_t)((uint64_t)s.n * s.c * s.h);
@@ -193,24 +203,34 @@ int launch_quantize(comet_ctx *ctx, const float *x, comet_shape s, uint64_t n, f
         if ((uint64_t)grid * (kQuantBlock / kWave) > ctx->max_runs) return COMET_ERR_INTERNAL;
         a.stage = ctx->rec_stage;
         a.run_count = ctx->run_count;
+        a.hist_parts = hist_parts;
+        a.hist_copies = hist_copies(nbins);
         a.hist_shift = a.win_n <= 2048u ? 2u : 0u;            // four copies while they fit 32 KB
         const size_t lds = (((size_t)a.win_n << a.hist_shift) + kQuantBlock) * 4u;
         const bool full = a.win_n == nbins;
-#define COMET_LAUNCH_QR(NSEG, MULTI)                                                                                   \
+#define COMET_LAUNCH_QR(VEC, NSEG, MULTI)                                                                              \
         do {                                                                                                           \
             {                                                                                                          \
                 TimedScope ts(ctx, st, COMET_KERNEL_QUANTIZE);                                                         \
-                if (full) hipLaunchKernelGGL((k_quantize_rows<NSEG, MULTI, true>), dim3(grid), dim3(kQuantBlock), lds, st, a);   \
-                else hipLaunchKernelGGL((k_quantize_rows<NSEG, MULTI, false>), dim3(grid), dim3(kQuantBlock), lds, st, a);       \
+                if (full) hipLaunchKernelGGL((k_quantize_rows<VEC, NSEG, MULTI, true>), dim3(grid), dim3(kQuantBlock), lds, st, a);   \
+                else hipLaunchKernelGGL((k_quantize_rows<VEC, NSEG, MULTI, false>), dim3(grid), dim3(kQuantBlock), lds, st, a);       \
             }                                                                                                          \
             TimedScope ts(ctx, st, COMET_KERNEL_GATHER);                                                               \
-            hipLaunchKernelGGL((k_gather_records<NSEG, MULTI>), dim3(grid), dim3(kQuantBlock), 0, st, a);              \
+            hipLaunchKernelGGL((k_gather_records<VEC, NSEG, MULTI>), dim3(grid), dim3(kQuantBlock), 0, st, a);         \
         } while (0)
-        if (s.w <= 32u) COMET_LAUNCH_QR(1, true);
-        else if (s.w <= 64u) COMET_LAUNCH_QR(1, false);
-        else if (s.w <= 128u) COMET_LAUNCH_QR(2, false);
-        else if (s.w <= 256u) COMET_LAUNCH_QR(4, false);
-        else COMET_LAUNCH_QR(8, false);
+        const uint32_t lanes_per_row = s.w / g.vec;
+        if (g.vec == 2u) {
+            if (lanes_per_row <= 32u) COMET_LAUNCH_QR(2, 1, true);
+            else if (lanes_per_row <= 64u) COMET_LAUNCH_QR(2, 1, false);
+            else if (lanes_per_row <= 128u) COMET_LAUNCH_QR(2, 2, false);
+            else COMET_LAUNCH_QR(2, 4, false);
+        } else {
+            if (lanes_per_row <= 32u) COMET_LAUNCH_QR(1, 1, true);
+            else if (lanes_per_row <= 64u) COMET_LAUNCH_QR(1, 1, false);
+            else if (lanes_per_row <= 128u) COMET_LAUNCH_QR(1, 2, false);
+            else if (lanes_per_row <= 256u) COMET_LAUNCH_QR(1, 4, false);
+            else COMET_LAUNCH_QR(1, 8, false);
+        }
 #undef COMET_LAUNCH_QR
     } else {
         // one segment of consecutive tiles per workgroup, about as many workgroups as fit the chip at once
@@ -237,8 +257,8 @@ int launch_encode(comet_ctx *ctx, const uint16_t *codes, uint64_t n, uint32_t nb
     uint32_t seg, grid;
     encode_geometry(ctx, a.n_chunks, &seg, &grid);
     a.seg_chunks = seg;
-    const size_t lds_count = (size_t)a.tbl_n * 8u + (size_t)seg * 4u;
-    const size_t lds_pack = (size_t)a.tbl_n * 8u + (size_t)(kEncBlock / kWave) * kEncBufWords * 4u;
+    const size_t lds_count = ((size_t)a.tbl_n + 1u) * 8u + (size_t)seg * 4u;       // table, a zero entry, word counts
+    const size_t lds_pack = ((size_t)a.tbl_n + 1u) * 8u + (size_t)(kEncBlock / kWave) * kEncBufWords * 4u;
     a.chunk_off = chunk_off; a.container = container; a.capacity = capacity;
     a.payload = payload; a.payload_cap_words = payload_cap; a.payload_words_out = payload_words_out;
     a.desc = desc; a.ctl = &ctx->state->ctl;
@@ -273,12 +293,16 @@ void encode_geometry(const comet_ctx *ctx, uint64_t n_chunks, uint32_t *seg_chun
     *n_seg = (uint32_t)((n_chunks + seg - 1) / seg);
 }
 
-QuantGeom quantize_geometry(const comet_ctx *ctx, comet_shape s, uint64_t n) {
+QuantGeom quantize_geometry(const comet_ctx *ctx, comet_shape s, uint64_t n, const float *x) {
     QuantGeom g{};
+    g.vec = 1;
     if (s.w <= kQuantRowsMaxW) {
         g.rows = true;
         const uint64_t rows_total = (uint64_t)s.n * s.c * s.h;
-        const uint32_t K = s.w <= 32u ? (uint32_t)kWave / s.w : 1u;
+        // two columns per lane: every row then starts at an even element, so pairs are 8-byte aligned
+        if ((s.w & 1u) == 0u && ((uintptr_t)x & 7u) == 0u) g.vec = 2;
+        const uint32_t lanes_per_row = s.w / g.vec;
+        const uint32_t K = lanes_per_row <= 32u ? (uint32_t)kWave / lanes_per_row : 1u;
         g.rows_per_step = K;
         // a few wavefronts per SIMD, but runs of at least 8192 elements (every run re-reads one row)
         const uint64_t want = (uint64_t)ctx->num_cu * 4u * kQuantRunsPerSimd;
@@ -323,8 +347,8 @@ int comet_create(comet_ctx **out, uint64_t max_elems, uint32_t max_nbins) {
     // scan descriptors: one per segment of the quantise / encode kernels (worst case over chunk sizes)
     const uint64_t tiles_q = (uint64_t)c->num_cu * 16u + 16u;
     const uint64_t tiles_e = (uint64_t)c->num_cu * 8u + max_elems / 64u / kEncSegChunksMax + 16u;
-    const ZeroLayout z = zero_layout(kMaxBins, tiles_q, tiles_e);
-    c->zero_cap = z.bytes;
+    const ZeroLayout z = zero_layout(kMaxBins, kMaxBins, tiles_q, tiles_e);   // the partial histograms take 256 KB whatever the alphabet
+    c->zero_cap = z.bytes + 4ull * kQuantHistPartsWords;
     const uint64_t state_bytes = offsetof(DevState, ctl) + z.bytes;
     if ((e = hipMalloc((void **)&c->state, state_bytes)) != hipSuccess) return fail(COMET_ERR_NOMEM);
     if ((e = hipMemset(c->state, 0, state_bytes)) != hipSuccess) return fail(hip_fail(e, "hipMemset"));
@@ -415,7 +439,7 @@ int comet_compress(comet_ctx *ctx, const float *dev_in, comet_shape s, float eb,
     const uint64_t n_chunks = (n + S - 1) / S;
     uint32_t e_seg, e_grid;
     encode_geometry(ctx, n_chunks, &e_seg, &e_grid);
-    const uint64_t tiles_q = quantize_geometry(ctx, s, n).grid;
+    const uint64_t tiles_q = quantize_geometry(ctx, s, n, dev_in).grid;
     const uint64_t tiles_e = e_grid;
 
     Header proto{};
@@ -429,15 +453,16 @@ int comet_compress(comet_ctx *ctx, const float *dev_in, comet_shape s, float eb,
     proto.off_outlier = align16(proto.off_chunk + 4 * n_chunks);
     if (proto.off_outlier > capacity) return COMET_ERR_CAPACITY;
 
-    const ZeroLayout z = zero_layout(nbins, tiles_q, tiles_e);
+    const ZeroLayout z = zero_layout(nbins, nbins, tiles_q, tiles_e);
     if (z.bytes > ctx->zero_cap) return COMET_ERR_NOMEM;
     HIP_TRY(hipMemsetAsync(ctx->zero_region, 0, z.bytes, st));
     uint32_t *hist = reinterpret_cast<uint32_t *>(ctx->zero_region + z.off_hist);
+    uint32_t *hist_parts = reinterpret_cast<uint32_t *>(ctx->zero_region + z.off_parts);
     uint64_t *desc_q = reinterpret_cast<uint64_t *>(ctx->zero_region + z.off_desc_q);
     uint64_t *desc_e = reinterpret_cast<uint64_t *>(ctx->zero_region + z.off_desc_e);
     uint8_t *out = static_cast<uint8_t *>(dev_out);
 
-    int rc = launch_quantize(ctx, dev_in, s, n, eb, nbins, st, ctx->codes, hist,
+    int rc = launch_quantize(ctx, dev_in, s, n, eb, nbins, st, ctx->codes, hist, hist_parts,
                              reinterpret_cast<uint32_t *>(out + proto.off_outlier), (capacity - proto.off_outlier) / 8u, desc_q);
     if (rc) return rc;
     {
@@ -611,13 +636,14 @@ int comet_stage_quantize(comet_ctx *ctx, const float *dev_in, comet_shape s, flo
         ((uintptr_t)dev_codes & 7u) || ((uintptr_t)dev_records & 7u)) return COMET_ERR_INVALID;
     if (n > ctx->max_elems) return COMET_ERR_NOMEM;
     hipStream_t st = (hipStream_t)stream;
-    const uint64_t tiles_q = quantize_geometry(ctx, s, n).grid;
-    const ZeroLayout z = zero_layout(4, tiles_q, 1);
+    const uint64_t tiles_q = quantize_geometry(ctx, s, n, dev_in).grid;
+    const ZeroLayout z = zero_layout(0, nbins, tiles_q, 1);
     if (z.bytes > ctx->zero_cap) return COMET_ERR_NOMEM;
     HIP_TRY(hipMemsetAsync(ctx->zero_region, 0, z.bytes, st));
     HIP_TRY(hipMemsetAsync(dev_hist, 0, 4ull * nbins, st));
     uint64_t *desc_q = reinterpret_cast<uint64_t *>(ctx->zero_region + z.off_desc_q);
-    int rc = launch_quantize(ctx, dev_in, s, n, eb, nbins, st, dev_codes, dev_hist, dev_records, rec_capacity, desc_q);
+    uint32_t *hist_parts = reinterpret_cast<uint32_t *>(ctx->zero_region + z.off_parts);
+    int rc = launch_quantize(ctx, dev_in, s, n, eb, nbins, st, dev_codes, dev_hist, hist_parts, dev_records, rec_capacity, desc_q);
     if (rc) return rc;
     HIP_TRY(hipMemcpyAsync(dev_counts, &ctx->state->ctl.n_rec, 24, hipMemcpyDeviceToDevice, st));
     hipLaunchKernelGGL(k_latch, dim3(1), dim3(1), 0, st, ctx->state);
@@ -648,7 +674,7 @@ int comet_stage_encode(comet_ctx *ctx, const uint16_t *dev_codes, uint64_t n, ui
     uint32_t e_seg, e_grid;
     encode_geometry(ctx, n_chunks, &e_seg, &e_grid);
     const uint64_t tiles_e = e_grid;
-    const ZeroLayout z = zero_layout(4, 1, tiles_e);
+    const ZeroLayout z = zero_layout(0, 0, 1, tiles_e);
     if (z.bytes > ctx->zero_cap) return COMET_ERR_NOMEM;
     HIP_TRY(hipMemsetAsync(ctx->zero_region, 0, z.bytes, st));
     uint64_t *desc_e = reinterpret_cast<uint64_t *>(ctx->zero_region + z.off_desc_e);

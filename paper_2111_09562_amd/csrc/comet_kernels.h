@@ -23,10 +23,12 @@ struct QuantArgs {
     uint32_t rec_lds;          // records the LDS buffer of a workgroup can hold
     uint32_t rows_total;       // row-walking kernel: planes * H rows of W elements
     uint32_t rows_per_wave;    //   consecutive rows per wavefront (a multiple of rows_per_step)
-    uint32_t rows_per_step;    //   rows a wavefront covers per step (64 / W for W <= 32, else 1)
+    uint32_t rows_per_step;    //   rows a wavefront covers per step (64 / lanes per row if a row takes at most 32 lanes, else 1)
     uint32_t hist_shift;       //   log2 of the copies of the LDS histogram window (lane & (copies - 1) picks one)
     uint32_t *stage;           //   staging area: kQuantRecRun (key, payload) pairs per run
     uint32_t *run_count;       //   three arrays of one entry per run: records, non-zero inputs, verbatim records
+    uint32_t *hist_parts;      //   hist_copies partial histograms of nbins entries, zeroed: workgroup b adds to copy b % hist_copies
+    uint32_t hist_copies;      //   (k_gather_records adds them up into hist)
     uint16_t *codes;
     uint32_t *hist;            // u32[nbins], zeroed
     uint32_t *rec;             // (key, payload) pairs
@@ -40,8 +42,12 @@ constexpr uint32_t kQuantRowsMaxW = 512;  // widest plane of the row-walking ker
 constexpr uint32_t kQuantRecRun = 768;    // outlier records staged per run (one run of rows per wavefront)
 constexpr uint32_t kQuantRecLds2 = 256;   // records a wavefront buffers in LDS before it writes them to the staging area in bulk
 constexpr uint32_t kQuantRunsPerSimd = 5; // runs the launch aims at, per SIMD
-template <int NSEG, bool MULTI, bool FULLWIN> __global__ void k_quantize_rows(QuantArgs a);
-template <int NSEG, bool MULTI> __global__ void k_gather_records(QuantArgs a);
+constexpr uint32_t kQuantHistCopiesMax = 32;        // partial histograms the workgroups spread their flushes over
+constexpr uint32_t kQuantHistPartsWords = 65536;    // all copies together have at most this many entries
+// VEC adjacent columns per lane (2 needs an even W and 8-byte aligned input), NSEG segments of 64 lanes per row,
+// MULTI: several rows per step
+template <int VEC, int NSEG, bool MULTI, bool FULLWIN> __global__ void k_quantize_rows(QuantArgs a);
+template <int VEC, int NSEG, bool MULTI> __global__ void k_gather_records(QuantArgs a);
 
 // ---- codebook -----------------------------------------------------------------
 constexpr int kBookBlock = 1024;

@@ -34,11 +34,18 @@ struct TableView {
     const uint64_t *lds;
     const uint64_t *glob;
     uint32_t lo, n, nbins;
+    // A code outside the alphabet cannot come from the quantise kernel; it reads the zero entry
+    // that follows the cached part (length 0: the symbol contributes no bits).
     __device__ inline uint64_t full(uint32_t code) const {
-        if (code >= nbins) code = 0;                     // cannot happen for codes made by the quantise kernel
-        if (FULL) return lds[code];
+        if (FULL) return lds[code < nbins ? code : nbins];
+        if (code >= nbins) return 0ull;
         const uint32_t i = code - lo;
         return (i < n) ? lds[i] : glob[code];
+    }
+    // length only
+    __device__ inline uint32_t length(uint32_t code) const {
+        if (FULL) return reinterpret_cast<const uint32_t *>(lds)[2u * (code < nbins ? code : nbins)] & 63u;
+        return (uint32_t)full(code) & 63u;
     }
 };
 
@@ -65,6 +72,23 @@ __device__ inline uint2 load4(const uint16_t *codes, uint64_t i0, uint64_t n) {
     for (uint32_t j = 0; j < 4; ++j) c[j] = (i0 + j < n) ? (uint32_t)codes[i0 + j] : 0u;
     return make_uint2(c[0] | (c[1] << 16), c[2] | (c[3] << 16));
 }
+// The codes of kEncUnroll consecutive steps (256 symbols each) from step st0 of the segment that
+// starts at chunk c_lo.  All arguments but `lane` are wavefront-uniform: the usual case, every step
+// inside the segment and the tensor, is one branch and kEncUnroll plain loads.
+template <int S>
+__device__ inline void fetch_steps(const uint16_t *codes, uint64_t n, uint32_t c_lo, uint32_t st0, uint32_t steps, uint32_t lane,
+                                   uint2 (&v)[kEncUnroll]) {
+    const uint64_t e0 = (uint64_t)c_lo * S + (uint64_t)st0 * 256u;
+    if (st0 + kEncUnroll <= steps && e0 + 256u * kEncUnroll <= n) {
+        const uint2 *src = reinterpret_cast<const uint2 *>(codes + e0) + lane;
+#pragma unroll
+        for (uint32_t u = 0; u < kEncUnroll; ++u) v[u] = src[u * kWave];
+    } else {
+#pragma unroll
+        for (uint32_t u = 0; u < kEncUnroll; ++u)
+            v[u] = (st0 + u < steps) ? load4(codes, e0 + u * 256u + lane * 4u, n) : make_uint2(0, 0);
+    }
+}
 __device__ inline uint32_t code_of(uint2 v, int j) {
     const uint32_t w = (j < 2) ? v.x : v.y;
     return (j & 1) ? (w >> 16) : (w & 0xffffu);
@@ -85,15 +109,15 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_count(EncodeArgs a) {
     constexpr int LPC = S / 4;                       // lanes per chunk
     constexpr int CPS = 256 / S;                     // chunks per wavefront step
     extern __shared__ uint64_t s_dyn_enc[];
-    uint64_t *s_tbl = s_dyn_enc;                                           // a.tbl_n entries
-    uint32_t *s_cnt = reinterpret_cast<uint32_t *>(s_dyn_enc + a.tbl_n);   // a.seg_chunks word counts
+    uint64_t *s_tbl = s_dyn_enc;                                                // a.tbl_n entries and a zero entry
+    uint32_t *s_cnt = reinterpret_cast<uint32_t *>(s_dyn_enc + a.tbl_n + 1u);   // a.seg_chunks word counts
     __shared__ uint32_t s_part32[kEncBlock / kWave];
 
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = (uint32_t)lane_id();
-    const uint32_t wave = tid / kWave;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / kWave));   // a scalar: what derives from it stays scalar
     ENC_DBG(0);
-    for (uint32_t i = tid; i < a.tbl_n; i += kEncBlock) s_tbl[i] = a.enc[a.tbl_lo + i];
+    for (uint32_t i = tid; i <= a.tbl_n; i += kEncBlock) s_tbl[i] = (i < a.tbl_n) ? a.enc[a.tbl_lo + i] : 0ull;
     TableView<FULLTBL> tbl{s_tbl, a.enc, a.tbl_lo, a.tbl_n, a.nbins};
     __syncthreads();
     ENC_DBG(1);
@@ -108,19 +132,20 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_count(EncodeArgs a) {
     // kEncUnroll steps per iteration, their loads issued together
     for (uint32_t st0 = wave * kEncUnroll; st0 < steps; st0 += (kEncBlock / kWave) * kEncUnroll) {
         uint2 v[kEncUnroll];
-#pragma unroll
-        for (uint32_t u = 0; u < kEncUnroll; ++u)
-            v[u] = (st0 + u < steps) ? load4(a.codes, (uint64_t)(c_lo + (st0 + u) * CPS) * S + lane * 4u, a.n) : make_uint2(0, 0);
+        fetch_steps<S>(a.codes, a.n, c_lo, st0, steps, lane, v);
 #pragma unroll
         for (uint32_t u = 0; u < kEncUnroll; ++u) {
             if (st0 + u >= steps) break;
             const uint32_t c0 = c_lo + (st0 + u) * CPS;
-            const uint64_t i0 = (uint64_t)c0 * S + lane * 4u;
+            const uint64_t e0 = (uint64_t)c0 * S;                           // first symbol of the step (uniform)
             uint32_t bits = 0;
+            if (e0 + 256u <= a.n) {                                         // every symbol of the step exists (uniform)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint32_t L = (uint32_t)tbl.full(code_of(v[u], j)) & 63u;
-                bits += (i0 + j < a.n) ? L : 0u;
+                for (int j = 0; j < 4; ++j) bits += tbl.length(code_of(v[u], j));
+            } else {
+                const uint32_t left = (a.n > e0) ? (uint32_t)(a.n - e0) : 0u;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) bits += (lane * 4u + (uint32_t)j < left) ? tbl.length(code_of(v[u], j)) : 0u;
             }
             const uint32_t incl = group_incl_scan<LPC>(bits);
             if ((lane % LPC) == LPC - 1 && c0 + g < c_hi) s_cnt[c0 + g - c_lo] = (incl + 31u) >> 5;
@@ -149,15 +174,15 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_pack(EncodeArgs a) {
     constexpr int LPC = S / 4;
     constexpr int CPS = 256 / S;
     extern __shared__ uint64_t s_dyn_enc[];
-    uint64_t *s_tbl = s_dyn_enc;                                           // a.tbl_n entries
-    uint32_t *s_buf = reinterpret_cast<uint32_t *>(s_dyn_enc + a.tbl_n);   // one assembly buffer per wavefront
+    uint64_t *s_tbl = s_dyn_enc;                                                // a.tbl_n entries and a zero entry
+    uint32_t *s_buf = reinterpret_cast<uint32_t *>(s_dyn_enc + a.tbl_n + 1u);   // one assembly buffer per wavefront
     __shared__ uint64_t s_part64[kEncBlock / kWave];
 
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = (uint32_t)lane_id();
-    const uint32_t wave = tid / kWave;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / kWave));   // a scalar: what derives from it stays scalar
     ENC_DBG(4);
-    for (uint32_t i = tid; i < a.tbl_n; i += kEncBlock) s_tbl[i] = a.enc[a.tbl_lo + i];
+    for (uint32_t i = tid; i <= a.tbl_n; i += kEncBlock) s_tbl[i] = (i < a.tbl_n) ? a.enc[a.tbl_lo + i] : 0ull;
     TableView<FULLTBL> tbl{s_tbl, a.enc, a.tbl_lo, a.tbl_n, a.nbins};
     uint32_t *buf = s_buf + wave * kEncBufWords;
     for (uint32_t i = lane; i < kEncBufWords; i += kWave) buf[i] = 0;
@@ -210,9 +235,7 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_pack(EncodeArgs a) {
     // one are issued: memory operations retire in order, so a load issued after a store could not
     // be consumed before that store has completed.
     auto fetch = [&](uint32_t st0, uint2 (&v)[kEncUnroll], uint32_t &off) {
-#pragma unroll
-        for (uint32_t u = 0; u < kEncUnroll; ++u)
-            v[u] = (st0 + u < steps) ? load4(a.codes, (uint64_t)(c_lo + (st0 + u) * CPS) * S + lane * 4u, a.n) : make_uint2(0, 0);
+        fetch_steps<S>(a.codes, a.n, c_lo, st0, steps, lane, v);
         off = a.chunk_off[c_lo + st0 * CPS];
     };
     auto flush = [&](uint64_t off0, uint32_t n_words) {
@@ -240,15 +263,19 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_pack(EncodeArgs a) {
 #pragma unroll
         for (uint32_t u = 0; u < kEncUnroll; ++u) {
             if (st0 + u >= steps) break;
-            const uint64_t i0 = (uint64_t)(c_lo + (st0 + u) * CPS) * S + lane * 4u;
+            const uint64_t e0 = (uint64_t)(c_lo + (st0 + u) * CPS) * S;    // first symbol of the step (uniform)
+            const uint32_t left = (e0 + 256u <= a.n) ? 256u : ((a.n > e0) ? (uint32_t)(a.n - e0) : 0u);
             uint64_t cw[4];
             uint32_t len[4], bits = 0;
+            uint64_t acc = 0;                                // my code words one after the other (if they fit 64 bits)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const uint64_t e = tbl.full(code_of(v[u], j));
-                len[j] = (i0 + j < a.n) ? (uint32_t)(e & 63u) : 0u;
+                uint64_t e = tbl.full(code_of(v[u], j));
+                if (left < 256u) e = (lane * 4u + (uint32_t)j < left) ? e : 0ull;   // uniform test; only the last step of the tensor
+                len[j] = (uint32_t)e & 63u;
                 cw[j] = e >> 6;
                 bits += len[j];
+                acc = (acc << len[j]) | cw[j];
             }
             const uint32_t incl = group_incl_scan<LPC>(bits);
             // words of every chunk of the step, and where each chunk's words start inside the buffer
@@ -265,20 +292,26 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_pack(EncodeArgs a) {
                 wpos = 0;
             }
             uint32_t p = (wpos + wbase) * 32u + incl - bits;   // bit position of my first code word inside the buffer
+            // A bit string of L <= 64 bits, left-aligned in t, goes to bit p of the word stream: at most
+            // three words.  The second OR is unconditional (a branch around it costs more than an OR of
+            // zero; the buffer has spare words behind the step), the third is rare.
+            auto place = [&](uint64_t t, uint32_t L, uint32_t at) {
+                const uint32_t sh = at & 31u, w = at >> 5;
+                const uint64_t hi = t >> sh;
+                atomicOr(&buf[w], (uint32_t)(hi >> 32));
+                atomicOr(&buf[w + 1], (uint32_t)hi);
+                if (L + sh > 64u) atomicOr(&buf[w + 2], (uint32_t)((t << (64u - sh)) >> 32));
+            };
+            if (bits <= 64u) {
+                // the usual case: my four code words as one string (a shift by 64 - 0 leaves zero bits: nothing is set)
+                place(bits ? acc << (64u - bits) : 0ull, bits, p);
+            } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint32_t L = len[j];
-                if (L) {
-                    // the code word, left-aligned in 64 bits, then moved to bit p of the word stream
-                    const uint64_t t = cw[j] << (64u - L);
-                    const uint32_t sh = p & 31u, w = p >> 5;
-                    const uint64_t hi = t >> sh;
-                    atomicOr(&buf[w], (uint32_t)(hi >> 32));
-                    const uint32_t mid = (uint32_t)hi;
-                    if (mid) atomicOr(&buf[w + 1], mid);
-                    if (L + sh > 64u) atomicOr(&buf[w + 2], (uint32_t)((t << (64u - sh)) >> 32));   // codes longer than 32 bits only
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t L = len[j];
+                    if (L) place(cw[j] << (64u - L), L, p);
+                    p += L;
                 }
-                p += L;
             }
             wpos += total_words;
         }

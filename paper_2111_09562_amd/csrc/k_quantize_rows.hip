@@ -52,6 +52,7 @@ __device__ inline __amdgpu_buffer_rsrc_t rows_rsrc(const void *p, uint32_t bytes
 }
 
 constexpr uint32_t kOob = 0x80000000u;      // byte offset beyond every run
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 struct SweepCounts {
     uint32_t nnz_lane = 0;      // per lane: non-zero inputs
@@ -62,17 +63,19 @@ struct SweepCounts {
 // One sweep of a wavefront over rows [row_lo, row_hi).  PASS 0: everything (codes, histogram,
 // counters), records into rec_dst[0 .. rec_cap) (the rest is only counted); PASS 1: records only,
 // and a record that does not fit raises ST_CAPACITY.  Returns the number of records of the run.
-// NSEG: 64-column segments per row (1, 2, 4, 8); MULTI: W <= 32, K rows per step (NSEG == 1);
-// FULLWIN: every histogram bin is in the LDS window.
-template <int NSEG, bool MULTI, bool FULLWIN, int PASS>
+// VEC: adjacent columns per lane (1, or 2 for even W: one 8-byte load, one packed code store and
+// one cross-lane shift per pair); NSEG: segments of 64 lanes per row (1, 2, 4, 8); MULTI: a row
+// takes at most 32 lanes, K rows per step (NSEG == 1); FULLWIN: every histogram bin is in the LDS
+// window.
+template <int VEC, int NSEG, bool MULTI, bool FULLWIN, int PASS>
 __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint32_t row_hi, uint32_t lane, uint32_t *s_hist,
                                       uint32_t hist_dummy, uint2 *s_buf, uint2 *rec_dst, uint64_t rec_cap, SweepCounts &cnt) {
     const uint32_t W = a.divW.d, H = a.divH.d;
+    const uint32_t LPR = W / (uint32_t)VEC;         // lanes per row
     const int32_t radius = a.radius;
     const uint32_t code_span = a.nbins - 1u;        // residual + radius - 1 must be below this
     // an fp32 error above eb_lo needs the exact comparison (the fp32 subtraction is within one rounding)
     const float eb_lo = a.eb * (1.0f - 0x1p-20f);
-    const uint64_t lt_mask = (1ull << lane) - 1ull;
     const uint32_t hist_sub = lane & ((1u << a.hist_shift) - 1u);   // my copy of the histogram window
 
     const uint32_t e_lo = row_lo * W;
@@ -85,53 +88,64 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
     uint32_t cur = 0;                                           // records so far (uniform)
 
     // lanes -> columns
-    uint32_t col[NSEG];                                         // element offset inside a step, kOob / 4 if none
-    uint32_t w0 = lane;                                         // MULTI: my column
-    bool first_col = false;                                     // MULTI: I am column 0 of my row
+    uint32_t col[NSEG];                                         // element offset of my first column inside a step, kOob / 4 if none
+    uint32_t w0 = lane * VEC;                                   // MULTI: my first column
+    bool first_col = false;                                     // MULTI: I hold column 0 of my row
     bool top_rows = false;                                      // MULTI: my row is the first one of a step
     uint32_t h_lane = 0;                                        // MULTI: my row inside its plane
     if (MULTI) {
-        const uint32_t kr = fdiv(lane, a.divW);
-        w0 = lane - kr * W;
-        col[0] = (kr < K) ? lane : kOob / 4u;
+        const uint32_t kr = fdiv(lane * VEC, a.divW);
+        w0 = lane * VEC - kr * W;
+        col[0] = (kr < K) ? lane * VEC : kOob / 4u;
         first_col = w0 == 0u;
-        top_rows = lane < W;
+        top_rows = lane < LPR;
         const uint32_t r0 = row_lo + kr;
         h_lane = r0 - fdiv(r0, a.divH) * H;
     } else {
 #pragma unroll
-        for (int s = 0; s < NSEG; ++s) col[s] = ((uint32_t)s * kWave + lane < W) ? (uint32_t)s * kWave + lane : kOob / 4u;
+        for (int s = 0; s < NSEG; ++s) {
+            const uint32_t c = ((uint32_t)s * kWave + lane) * VEC;
+            col[s] = (c < W) ? c : kOob / 4u;
+        }
     }
     uint32_t h_row = row_lo - fdiv(row_lo, a.divH) * H;        // !MULTI: row of the current step inside its plane (uniform)
     const uint32_t k_mod = MULTI ? K - fdiv(K, a.divH) * H : 0u;
 
     // row differences of the row just above the run (only used if that row is in the same plane)
-    int32_t prev_rd[NSEG];
+    int32_t prev_rd[NSEG][VEC];
 #pragma unroll
-    for (int s = 0; s < NSEG; ++s) prev_rd[s] = 0;
+    for (int s = 0; s < NSEG; ++s)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) prev_rd[s][v] = 0;
     if (row_lo > 0) {
         const float *above = a.x + (size_t)(e_lo - W);
 #pragma unroll
         for (int s = 0; s < NSEG; ++s) {
-            const uint32_t w = MULTI ? w0 : (uint32_t)s * kWave + lane;
-            const bool on = MULTI ? top_rows : (w < W);
-            const float xa = on ? above[w] : 0.0f;
-            const float xl = (on && w > 0) ? above[w - 1u] : 0.0f;
-            const float ta = xa * a.r, tl = xl * a.r;
-            const int32_t qa = (fabsf(ta) < 16777216.0f) ? (int32_t)rintf(ta) : 0;
-            const int32_t ql = (fabsf(tl) < 16777216.0f) ? (int32_t)rintf(tl) : 0;
-            prev_rd[s] = (w > 0) ? qa - ql : qa;
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                const uint32_t w = (MULTI ? w0 : ((uint32_t)s * kWave + lane) * VEC) + (uint32_t)v;
+                const bool on = MULTI ? top_rows : (w < W);
+                const float xa = on ? above[w] : 0.0f;
+                const float xl = (on && w > 0) ? above[w - 1u] : 0.0f;
+                const float ta = xa * a.r, tl = xl * a.r;
+                const int32_t qa = (fabsf(ta) < 16777216.0f) ? (int32_t)rintf(ta) : 0;
+                const int32_t ql = (fabsf(tl) < 16777216.0f) ? (int32_t)rintf(tl) : 0;
+                prev_rd[s][v] = (w > 0) ? qa - ql : qa;
+            }
         }
     }
 
-    constexpr uint32_t U = NSEG >= 8 ? 1u : 8u / NSEG;          // steps per batch of loads
+    constexpr uint32_t U = NSEG * VEC >= 8 ? 1u : 8u / (NSEG * VEC);   // steps per batch of loads
     // FULL batches (every row of the batch inside the run) put the uniform part of the address
     // into the scalar offset of the buffer instruction and know a lane's validity up front;
     // the few steps at the end of a run go through the general form.
     bool col_ok[NSEG];
 #pragma unroll
     for (int s = 0; s < NSEG; ++s) col_ok[s] = col[s] != kOob / 4u;
-    auto fetch = [&](auto full_tag, uint32_t t0, uint32_t t_max, float (&xb)[U][NSEG]) {
+    uint64_t ok_mask[NSEG];
+#pragma unroll
+    for (int s = 0; s < NSEG; ++s) ok_mask[s] = wave_ballot(col_ok[s]);
+    auto fetch = [&](auto full_tag, uint32_t t0, uint32_t t_max, float (&xb)[U][NSEG][VEC]) {
         constexpr bool FULL = decltype(full_tag)::value;
 #pragma unroll
         for (uint32_t u = 0; u < U; ++u) {
@@ -139,8 +153,15 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
             const uint32_t soff = t * stride;                              // uniform
 #pragma unroll
             for (int s = 0; s < NSEG; ++s) {
-                if (FULL) xb[u][s] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r_x, (int)(col[s] * 4u), (int)(soff * 4u), 0));
-                else xb[u][s] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r_x, (int)((col[s] + soff) * 4u), 0, 0));
+                const int voff = FULL ? (int)(col[s] * 4u) : (int)((col[s] + soff) * 4u);
+                const int sof = FULL ? (int)(soff * 4u) : 0;
+                if (VEC == 2) {
+                    const u32x2 r = __builtin_amdgcn_raw_buffer_load_b64(r_x, voff, sof, 0);
+                    xb[u][s][0] = __uint_as_float(r.x);
+                    xb[u][s][VEC - 1] = __uint_as_float(r.y);
+                } else {
+                    xb[u][s][0] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r_x, voff, sof, 0));
+                }
             }
         }
     };
@@ -155,9 +176,9 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
         cur += buffered;
         buffered = 0;
     };
-    auto steps_of = [&](auto full_tag, uint32_t t0, float (&xb)[U][NSEG]) {
+    auto steps_of = [&](auto full_tag, uint32_t t0, float (&xb)[U][NSEG][VEC]) {
         constexpr bool FULL = decltype(full_tag)::value;
-        int32_t dsave[U][NSEG];                                 // residuals of the batch, for the record pass
+        int32_t dsave[U][NSEG][VEC];                            // residuals of the batch, for the record pass
         uint64_t flag_esc = 0, flag_susp = 0;                   // lanes that escaped / failed the fp32 bound filter anywhere in the batch
 #pragma unroll
         for (uint32_t u = 0; u < U; ++u) {
@@ -167,54 +188,81 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
 #pragma unroll
             for (int s = 0; s < NSEG; ++s) {
                 const bool valid = FULL ? col_ok[s] : (col[s] + soff < n_el);
-                const float x = xb[u][s];
-                const float t = x * a.r;
-                const float qf = (fabsf(t) < 16777216.0f) ? rintf(t) : 0.0f;
-                const int32_t q = (int32_t)qf;
-                int32_t nql = lane_left(-q);                    // minus the left neighbour
-                int32_t rd, up;
+                float x[VEC], qf[VEC];
+                int32_t q[VEC], rd[VEC], up[VEC];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    x[v] = xb[u][s][v];
+                    const float t = x[v] * a.r;
+                    qf[v] = (fabsf(t) < 16777216.0f) ? rintf(t) : 0.0f;
+                    q[v] = (int32_t)qf[v];
+                }
+                int32_t nql = lane_left(-q[VEC - 1]);           // minus the left neighbour of my first column
                 if (MULTI) {
-                    rd = first_col ? q : q + nql;
-                    const int32_t below = __builtin_amdgcn_ds_bpermute((int)((lane - W) * 4u), rd);
-                    up = top_rows ? prev_rd[0] : below;
-                    up = h_lane ? up : 0;
-                    prev_rd[0] = __builtin_amdgcn_ds_bpermute((int)((lane + (K - 1u) * W) * 4u), rd);
+                    rd[0] = first_col ? q[0] : q[0] + nql;
+                } else {
+                    if (s > 0) nql = (lane == 0u) ? -carry_q : nql;
+                    if (NSEG > 1) carry_q = __builtin_amdgcn_readlane(q[VEC - 1], 63);
+                    rd[0] = q[0] + nql;
+                }
+#pragma unroll
+                for (int v = 1; v < VEC; ++v) rd[v] = q[v] - q[v - 1];
+                if (MULTI) {
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) {
+                        const int32_t below = __builtin_amdgcn_ds_bpermute((int)((lane - LPR) * 4u), rd[v]);
+                        const int32_t upv = top_rows ? prev_rd[0][v] : below;
+                        up[v] = h_lane ? upv : 0;
+                        prev_rd[0][v] = __builtin_amdgcn_ds_bpermute((int)((lane + (K - 1u) * LPR) * 4u), rd[v]);
+                    }
                     h_lane += k_mod;
                     h_lane -= (h_lane >= H) ? H : 0u;
                 } else {
-                    if (s > 0) nql = (lane == 0u) ? -carry_q : nql;
-                    if (NSEG > 1) carry_q = __builtin_amdgcn_readlane(q, 63);
-                    rd = q + nql;
-                    up = (int32_t)((uint32_t)prev_rd[s] & hmask);
-                    prev_rd[s] = rd;
-                }
-                const int32_t d = (int32_t)((uint32_t)rd - (uint32_t)up);
-                const uint32_t c = (uint32_t)d + (uint32_t)radius;
-                const bool inrange = (c - 1u) < code_span;
-                const uint32_t code = inrange ? c : 0u;
-                // error-bound filter: |x - y| in fp32 is within one rounding of the exact error
-                const float err = fabsf(x - qf * a.ebx2);
-                const bool suspicious = !(err <= eb_lo);        // also true for NaN / Inf / huge inputs
-                dsave[u][s] = d;
-                flag_esc |= wave_ballot(valid && !inrange);
-                flag_susp |= wave_ballot(valid && suspicious);
-                if (PASS == 0) {
-                    cnt.nnz_lane += (x != 0.0f) ? 1u : 0u;      // lanes without an element hold 0
-                    // Histogram: no divergent branch (switching the execution mask costs more than the
-                    // atomic).  Lanes that count nothing add to a word of their own; the centre bin is
-                    // not counted here, it is what is left of the workgroup's elements.  The window is
-                    // replicated: lanes that meet in one bin mostly use different copies.
-                    const bool count = valid && code != (uint32_t)radius;
-                    if (FULLWIN) {
-                        atomicAdd(&s_hist[count ? (code << a.hist_shift) + hist_sub : hist_dummy], 1u);
-                    } else {
-                        const uint32_t bin = code - a.win_lo;
-                        const bool inwin = bin < a.win_n;
-                        atomicAdd(&s_hist[(count && inwin) ? (bin << a.hist_shift) + hist_sub : hist_dummy], 1u);
-                        if (count && !inwin) { atomicAdd(&a.hist[code], 1u); ++cnt.oow_lane; }
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) {
+                        up[v] = (int32_t)((uint32_t)prev_rd[s][v] & hmask);
+                        prev_rd[s][v] = rd[v];
                     }
-                    if (FULL) __builtin_amdgcn_raw_buffer_store_b16((unsigned short)code, r_c, (int)(col[s] * 2u), (int)(soff * 2u), 0);
-                    else __builtin_amdgcn_raw_buffer_store_b16((unsigned short)code, r_c, (int)((col[s] + soff) * 2u), 0, 0);
+                }
+                // wavefront masks straight from the comparisons (scalar registers, no per-lane flags)
+                const uint64_t vmask = FULL ? ok_mask[s] : wave_ballot(valid);
+                uint64_t out_mask = 0ull, susp_mask = 0ull;
+                uint32_t code[VEC];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    const int32_t d = (int32_t)((uint32_t)rd[v] - (uint32_t)up[v]);
+                    const uint32_t c = (uint32_t)d + (uint32_t)radius;
+                    const bool inrange = (c - 1u) < code_span;
+                    code[v] = inrange ? c : 0u;
+                    // error-bound filter: |x - y| in fp32 is within one rounding of the exact error
+                    const float err = fabsf(x[v] - qf[v] * a.ebx2);
+                    susp_mask |= wave_ballot(!(err <= eb_lo));  // also true for NaN / Inf / huge inputs
+                    out_mask |= wave_ballot(!inrange);
+                    dsave[u][s][v] = d;
+                    if (PASS == 0) {
+                        cnt.nnz_lane += (x[v] != 0.0f) ? 1u : 0u;   // lanes without an element hold 0
+                        // Histogram: no divergent branch (switching the execution mask costs more than the
+                        // atomic).  Lanes that count nothing add to a word of their own; the centre bin is
+                        // not counted here, it is what is left of the workgroup's elements.  The window is
+                        // replicated: lanes that meet in one bin mostly use different copies.
+                        const bool count = valid && code[v] != (uint32_t)radius;
+                        if (FULLWIN) {
+                            atomicAdd(&s_hist[count ? (code[v] << a.hist_shift) + hist_sub : hist_dummy], 1u);
+                        } else {
+                            const uint32_t bin = code[v] - a.win_lo;
+                            const bool inwin = bin < a.win_n;
+                            atomicAdd(&s_hist[(count && inwin) ? (bin << a.hist_shift) + hist_sub : hist_dummy], 1u);
+                            if (count && !inwin) { atomicAdd(&a.hist[code[v]], 1u); ++cnt.oow_lane; }
+                        }
+                    }
+                }
+                flag_esc |= out_mask & vmask;
+                flag_susp |= susp_mask & vmask;
+                if (PASS == 0) {
+                    const int voff = FULL ? (int)(col[s] * 2u) : (int)((col[s] + soff) * 2u);
+                    const int sof = FULL ? (int)(soff * 2u) : 0;
+                    if (VEC == 2) __builtin_amdgcn_raw_buffer_store_b32(code[0] | (code[VEC - 1] << 16), r_c, voff, sof, 0);
+                    else __builtin_amdgcn_raw_buffer_store_b16((unsigned short)code[0], r_c, voff, sof, 0);
                 }
             }
             if (!MULTI) { ++h_row; h_row = (h_row == H) ? 0u : h_row; }
@@ -229,35 +277,50 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
 #pragma unroll
                 for (int s = 0; s < NSEG; ++s) {
                     const bool valid = FULL ? col_ok[s] : (col[s] + soff < n_el);
-                    const float x = xb[u][s];
-                    const int32_t d = dsave[u][s];
-                    const bool esc = valid && !(((uint32_t)d + (uint32_t)radius - 1u) < code_span);
-                    bool verb = false;
-                    if (any_susp) {
-                        const float t = x * a.r;
-                        const int32_t q = (fabsf(t) < 16777216.0f) ? (int32_t)rintf(t) : 0;
-                        const bool suspicious = !(fabsf(x - (float)q * a.ebx2) <= eb_lo);
-                        if (valid && suspicious) verb = needs_verbatim_rows(x, q, a.r, a.ebx2, a.eb);
+                    bool esc[VEC], verb[VEC];
+                    uint64_t em[VEC], vm[VEC], any = 0ull;
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) {
+                        const float x = xb[u][s][v];
+                        esc[v] = valid && !(((uint32_t)dsave[u][s][v] + (uint32_t)radius - 1u) < code_span);
+                        verb[v] = false;
+                        if (any_susp) {
+                            const float t = x * a.r;
+                            const int32_t q = (fabsf(t) < 16777216.0f) ? (int32_t)rintf(t) : 0;
+                            const bool suspicious = !(fabsf(x - (float)q * a.ebx2) <= eb_lo);
+                            if (valid && suspicious) verb[v] = needs_verbatim_rows(x, q, a.r, a.ebx2, a.eb);
+                        }
+                        em[v] = wave_ballot(esc[v]);
+                        vm[v] = any_susp ? wave_ballot(verb[v]) : 0ull;
+                        any |= em[v] | vm[v];
                     }
-                    const uint64_t em = wave_ballot(esc), vm = any_susp ? wave_ballot(verb) : 0ull;
-                    if ((em | vm) == 0ull) continue;             // wavefront-uniform
+                    if (any == 0ull) continue;                   // wavefront-uniform
                     // Records go to a small LDS buffer first and leave in bulk: a global store here, in a
                     // branch the compiler cannot count, would make every later wait for the prefetched
-                    // loads a wait for all stores.
-                    uint32_t pos = buffered + __builtin_amdgcn_mbcnt_hi((uint32_t)(em >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)em, 0u));
-                    if (vm) pos += __builtin_amdgcn_mbcnt_hi((uint32_t)(vm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)vm, 0u));
+                    // loads a wait for all stores.  Order: lanes, then a lane's columns, escape before verbatim.
+                    uint32_t add = 0, before = 0;                // records of this slot (uniform); those of the lanes below me
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) {
+                        add += (uint32_t)__popcll(em[v]) + (uint32_t)__popcll(vm[v]);
+                        before += __builtin_amdgcn_mbcnt_hi((uint32_t)(em[v] >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)em[v], 0u));
+                        if (vm[v]) before += __builtin_amdgcn_mbcnt_hi((uint32_t)(vm[v] >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)vm[v], 0u));
+                        if (PASS == 0) cnt.vrec += (uint32_t)__popcll(vm[v]);
+                    }
+                    if (buffered + add > kQuantRecLds2) flush_records();
+                    uint32_t pos = buffered + before;
                     const uint32_t e = e_lo + col[s] + soff;
-                    if (esc) s_buf[pos++] = make_uint2(2u * e, (uint32_t)d);
-                    if (verb) s_buf[pos] = make_uint2(2u * e + 1u, __float_as_uint(x));
-                    buffered += (uint32_t)__popcll(em) + (uint32_t)__popcll(vm);
-                    if (PASS == 0) cnt.vrec += (uint32_t)__popcll(vm);
-                    if (buffered > kQuantRecLds2 - 2u * kWave) flush_records();
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) {
+                        if (esc[v]) s_buf[pos++] = make_uint2(2u * (e + (uint32_t)v), (uint32_t)dsave[u][s][v]);
+                        if (verb[v]) s_buf[pos++] = make_uint2(2u * (e + (uint32_t)v) + 1u, __float_as_uint(xb[u][s][v]));
+                    }
+                    buffered += add;
                 }
             }
         }
     };
     // Two batches of steps alternate: the loads of one are in flight while the other is worked on.
-    float xa[U][NSEG], xb[U][NSEG];
+    float xa[U][NSEG][VEC], xb[U][NSEG][VEC];
     const std::true_type full{};
     const std::false_type general{};
     const uint32_t n_full = n_steps / (2u * U) * (2u * U);      // steps covered by full double batches
@@ -291,7 +354,7 @@ __device__ inline void run_rows(const QuantArgs &a, uint32_t run, uint32_t *lo, 
 }  // namespace
 
 // One run per wavefront, kQuantBlock / 64 runs per workgroup.
-template <int NSEG, bool MULTI, bool FULLWIN>
+template <int VEC, int NSEG, bool MULTI, bool FULLWIN>
 __global__ __launch_bounds__(kQuantBlock) void k_quantize_rows(QuantArgs a) {
     extern __shared__ uint32_t s_dyn_qr[];          // histogram window: a.win_n bins, 1 << a.hist_shift copies of each;
                                                     // then one word per thread for the lanes that count nothing
@@ -312,7 +375,7 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize_rows(QuantArgs a) {
     SweepCounts cnt;
     uint32_t my_records = 0;
     if (row_hi > row_lo)
-        my_records = sweep_rows<NSEG, MULTI, FULLWIN, 0>(a, row_lo, row_hi, lane, s_hist, (a.win_n << a.hist_shift) + tid, s_recbuf[wave],
+        my_records = sweep_rows<VEC, NSEG, MULTI, FULLWIN, 0>(a, row_lo, row_hi, lane, s_hist, (a.win_n << a.hist_shift) + tid, s_recbuf[wave],
                                                           reinterpret_cast<uint2 *>(a.stage) + (size_t)run * kQuantRecRun, kQuantRecRun, cnt);
     // per-run results: record count, non-zero inputs, verbatim records (summed up by the gather kernel;
     // thousands of atomics on one counter would cost more than the sweep)
@@ -325,14 +388,18 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize_rows(QuantArgs a) {
     }
 
     // ---- flush the private histogram ----
+    // Into one of several partial histograms: the occupied bins are a few cache lines, and thousands
+    // of workgroups adding to the same lines would queue up behind each other for longer than the
+    // sweep takes.  k_gather_records adds the copies up.
     // centre bin = elements of the workgroup - everything counted elsewhere
     __syncthreads();
+    uint32_t *part = a.hist_parts + (size_t)(blockIdx.x % a.hist_copies) * a.nbins;
     uint64_t counted = FULLWIN ? 0ull : (uint64_t)cnt.oow_lane;
     for (uint32_t i = tid; i < a.win_n; i += kQuantBlock) {
         uint32_t v = 0;
         for (uint32_t k = 0; k < (1u << a.hist_shift); ++k) v += s_hist[(i << a.hist_shift) + k];
         counted += v;
-        if (v) atomicAdd(&a.hist[a.win_lo + i], v);
+        if (v) atomicAdd(&part[a.win_lo + i], v);
     }
     uint64_t total;
     (void)block_excl_scan<uint64_t, kWaves>(counted, s_part64, total);
@@ -341,12 +408,12 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize_rows(QuantArgs a) {
         uint64_t r1 = r0 + (uint64_t)kWaves * a.rows_per_wave;
         if (r1 > a.rows_total) r1 = a.rows_total;
         const uint64_t elems = (r1 > r0) ? (r1 - r0) * a.divW.d : 0ull;
-        if (elems > total) atomicAdd(&a.hist[a.radius], (uint32_t)(elems - total));
+        if (elems > total) atomicAdd(&part[a.radius], (uint32_t)(elems - total));
     }
 }
 
 // Moves the staged records of every run to their final, ordered place; same grid as k_quantize_rows.
-template <int NSEG, bool MULTI>
+template <int VEC, int NSEG, bool MULTI>
 __global__ __launch_bounds__(kQuantBlock) void k_gather_records(QuantArgs a) {
     constexpr int kWaves = kQuantBlock / kWave;
     __shared__ uint64_t s_part64[kWaves];
@@ -356,6 +423,14 @@ __global__ __launch_bounds__(kQuantBlock) void k_gather_records(QuantArgs a) {
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / kWave));
     const uint32_t n_runs = gridDim.x * kWaves;
     const uint32_t run0 = blockIdx.x * kWaves;
+
+    // histogram: one thread per bin adds up the partial histograms (codes outside the LDS window of
+    // the quantise kernel were counted in hist directly)
+    for (uint32_t b = blockIdx.x * kQuantBlock + tid; b < a.nbins; b += gridDim.x * kQuantBlock) {
+        uint32_t v = 0;
+        for (uint32_t c = 0; c < a.hist_copies; ++c) v += a.hist_parts[(size_t)c * a.nbins + b];
+        if (v) a.hist[b] += v;
+    }
 
     // records of all runs in front of this workgroup's first run
     uint64_t sum = 0;
@@ -403,19 +478,23 @@ __global__ __launch_bounds__(kQuantBlock) void k_gather_records(QuantArgs a) {
         uint32_t row_lo, row_hi;
         run_rows(a, run, &row_lo, &row_hi);
         SweepCounts unused;
-        (void)sweep_rows<NSEG, MULTI, true, 1>(a, row_lo, row_hi, lane, nullptr, 0, s_recbuf[wave], dst, room, unused);
+        (void)sweep_rows<VEC, NSEG, MULTI, true, 1>(a, row_lo, row_hi, lane, nullptr, 0, s_recbuf[wave], dst, room, unused);
     }
 }
 
-#define COMET_INST_QR(NSEG, MULTI)                                                   \
-    template __global__ void k_quantize_rows<NSEG, MULTI, true>(QuantArgs);          \
-    template __global__ void k_quantize_rows<NSEG, MULTI, false>(QuantArgs);         \
-    template __global__ void k_gather_records<NSEG, MULTI>(QuantArgs);
-COMET_INST_QR(1, true)
-COMET_INST_QR(1, false)
-COMET_INST_QR(2, false)
-COMET_INST_QR(4, false)
-COMET_INST_QR(8, false)
+#define COMET_INST_QR(VEC, NSEG, MULTI)                                                   \
+    template __global__ void k_quantize_rows<VEC, NSEG, MULTI, true>(QuantArgs);          \
+    template __global__ void k_quantize_rows<VEC, NSEG, MULTI, false>(QuantArgs);         \
+    template __global__ void k_gather_records<VEC, NSEG, MULTI>(QuantArgs);
+COMET_INST_QR(1, 1, true)
+COMET_INST_QR(1, 1, false)
+COMET_INST_QR(1, 2, false)
+COMET_INST_QR(1, 4, false)
+COMET_INST_QR(1, 8, false)
+COMET_INST_QR(2, 1, true)
+COMET_INST_QR(2, 1, false)
+COMET_INST_QR(2, 2, false)
+COMET_INST_QR(2, 4, false)
 #undef COMET_INST_QR
 
 }  // namespace comet
