@@ -304,10 +304,10 @@ QuantGeom quantize_geometry(const comet_ctx *ctx, comet_shape s, uint64_t n, con
         const uint32_t lanes_per_row = s.w / g.vec;
         const uint32_t K = lanes_per_row <= 32u ? (uint32_t)kWave / lanes_per_row : 1u;
         g.rows_per_step = K;
-        // a few wavefronts per SIMD, but runs of at least 8192 elements (every run re-reads one row)
+        // a few wavefronts per SIMD, but runs of at least 2048 elements (every run re-reads one row)
         const uint64_t want = (uint64_t)ctx->num_cu * 4u * kQuantRunsPerSimd;
         uint64_t per = (rows_total + want - 1) / want;
-        const uint64_t min_rows = (8192u + s.w - 1u) / s.w;
+        const uint64_t min_rows = (2048u + s.w - 1u) / s.w;
         if (per < min_rows) per = min_rows;
         per = (per + K - 1) / K * K;
         if (per > rows_total) per = (rows_total + K - 1) / K * K;
@@ -536,9 +536,17 @@ int comet_decompress(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_s
             hipLaunchKernelGGL(k_decode_chunks, dim3(grid), dim3(kDsBlock), (size_t)kDsWaves * kDsStageWords * 4u, st, d);
         }
         HIP_TRY(hipGetLastError());
+        // small planes: a unit of work is a group of whole planes, `passes` times the planes that sit side by
+        // side in a wavefront: about kScanStripElems elements, fewer if that leaves the chip short of wavefronts
         const uint64_t P = (uint64_t)s.h * s.w;
         uint64_t G = 1;
-        if (s.w <= 32u) { const uint64_t fit = kScanStripElems / (ppi * P); G = ppi * (fit ? fit : 1u); }
+        if (s.w <= 32u) {
+            uint64_t passes = kScanStripElems / (ppi * P);
+            const uint64_t spread = (uint64_t)d.planes / ((uint64_t)ppi * ctx->num_cu * 32u);
+            if (passes > spread) passes = spread;
+            G = ppi * (passes ? passes : 1u);
+        }
+        d.group_planes = (uint32_t)G;
         const uint64_t units = ((uint64_t)d.planes + G - 1) / G;
         uint64_t grid = (units + kDsWaves - 1) / kDsWaves;
         const uint64_t cap = (uint64_t)ctx->num_cu * 8u;

@@ -191,6 +191,7 @@ struct DsArgs {
     DecodeTables t;
     uint64_t n;
     uint32_t planes, H, W;
+    uint32_t group_planes;     // scan kernel, planes of at most 32 columns: whole planes per unit of work (a multiple of the planes side by side in a wavefront)
     FastDiv divW;
     int16_t *resid;            // work buffer: one int16 residual per element (-32768 = escaped)
     float *out;

@@ -347,11 +347,7 @@ __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
         lane_on = lane < W;
     }
     const uint64_t lt_mask = (1ull << lane) - 1ull;
-    uint32_t G = 1;                                           // planes per unit
-    if (group_mode) {
-        const uint32_t fit = kScanStripElems / (ppi * P);     // passes of ppi planes in about kScanStripElems elements
-        G = ppi * (fit ? fit : 1u);
-    }
+    const uint32_t G = group_mode ? a.group_planes : 1u;      // planes per unit
     const uint32_t R = group_mode ? H : (kScanStripElems / W ? kScanStripElems / W : 1u);   // rows per strip
     const uint32_t n_units = (a.planes + G - 1u) / G;
 

@@ -361,6 +361,7 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize_rows(QuantArgs a) {
     constexpr int kWaves = kQuantBlock / kWave;
     uint32_t *s_hist = s_dyn_qr;
     __shared__ uint64_t s_part64[kWaves];
+    __shared__ uint32_t s_tot[kWaves][3];
     __shared__ uint2 s_recbuf[kWaves][kQuantRecLds2];   // outlier records of a wavefront on their way to the staging area
 
     const uint32_t tid = threadIdx.x;
@@ -377,14 +378,12 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize_rows(QuantArgs a) {
     if (row_hi > row_lo)
         my_records = sweep_rows<VEC, NSEG, MULTI, FULLWIN, 0>(a, row_lo, row_hi, lane, s_hist, (a.win_n << a.hist_shift) + tid, s_recbuf[wave],
                                                           reinterpret_cast<uint2 *>(a.stage) + (size_t)run * kQuantRecRun, kQuantRecRun, cnt);
-    // per-run results: record count, non-zero inputs, verbatim records (summed up by the gather kernel;
-    // thousands of atomics on one counter would cost more than the sweep)
+    // results: record count per run; records, non-zero inputs and verbatim records per workgroup (summed
+    // up by the gather kernel; thousands of atomics on one counter would cost more than the sweep)
     const uint32_t nnz_wave = wave_sum<uint32_t>(cnt.nnz_lane);
     if (lane == 0) {
-        const uint32_t n_runs = gridDim.x * kWaves;
         a.run_count[run] = my_records;
-        a.run_count[n_runs + run] = nnz_wave;
-        a.run_count[2u * n_runs + run] = cnt.vrec;
+        s_tot[wave][0] = my_records; s_tot[wave][1] = nnz_wave; s_tot[wave][2] = cnt.vrec;
     }
 
     // ---- flush the private histogram ----
@@ -393,6 +392,12 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize_rows(QuantArgs a) {
     // sweep takes.  k_gather_records adds the copies up.
     // centre bin = elements of the workgroup - everything counted elsewhere
     __syncthreads();
+    if (tid < 3u) {
+        uint32_t t = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) t += s_tot[w][tid];
+        a.run_count[gridDim.x * kWaves + tid * gridDim.x + blockIdx.x] = t;   // three arrays of one entry per workgroup
+    }
     uint32_t *part = a.hist_parts + (size_t)(blockIdx.x % a.hist_copies) * a.nbins;
     uint64_t counted = FULLWIN ? 0ull : (uint64_t)cnt.oow_lane;
     for (uint32_t i = tid; i < a.win_n; i += kQuantBlock) {
@@ -428,24 +433,36 @@ __global__ __launch_bounds__(kQuantBlock) void k_gather_records(QuantArgs a) {
     // the quantise kernel were counted in hist directly)
     for (uint32_t b = blockIdx.x * kQuantBlock + tid; b < a.nbins; b += gridDim.x * kQuantBlock) {
         uint32_t v = 0;
-        for (uint32_t c = 0; c < a.hist_copies; ++c) v += a.hist_parts[(size_t)c * a.nbins + b];
+        for (uint32_t c0 = 0; c0 < a.hist_copies; c0 += 8u) {               // eight loads in flight
+            uint32_t p[8];
+#pragma unroll
+            for (uint32_t j = 0; j < 8; ++j) p[j] = (c0 + j < a.hist_copies) ? a.hist_parts[(size_t)(c0 + j) * a.nbins + b] : 0u;
+#pragma unroll
+            for (uint32_t j = 0; j < 8; ++j) v += p[j];
+        }
         if (v) a.hist[b] += v;
     }
 
-    // records of all runs in front of this workgroup's first run
-    uint64_t sum = 0;
-    for (uint32_t i0 = 0; i0 < run0; i0 += 8u * kQuantBlock) {          // eight loads in flight per thread
-        uint32_t v[8];
+    // sum of the per-workgroup counters wg[0 .. count) over the workgroup, eight loads in flight per thread
+    auto total_of = [&](const uint32_t *wg, uint32_t count) {
+        uint64_t sum = 0;
+        for (uint32_t i0 = 0; i0 < count; i0 += 8u * kQuantBlock) {
+            uint32_t v[8];
 #pragma unroll
-        for (uint32_t j = 0; j < 8; ++j) {
-            const uint32_t i = i0 + j * kQuantBlock + tid;
-            v[j] = (i < run0) ? a.run_count[i] : 0u;
+            for (uint32_t j = 0; j < 8; ++j) {
+                const uint32_t i = i0 + j * kQuantBlock + tid;
+                v[j] = (i < count) ? wg[i] : 0u;
+            }
+#pragma unroll
+            for (uint32_t j = 0; j < 8; ++j) sum += v[j];
         }
-#pragma unroll
-        for (uint32_t j = 0; j < 8; ++j) sum += v[j];
-    }
-    uint64_t base;
-    (void)block_excl_scan<uint64_t, kWaves>(sum, s_part64, base);
+        uint64_t total;
+        (void)block_excl_scan<uint64_t, kWaves>(sum, s_part64, total);
+        return total;
+    };
+    const uint32_t *wg_rec = a.run_count + n_runs, *wg_nnz = wg_rec + gridDim.x, *wg_vrec = wg_nnz + gridDim.x;
+    // records of all workgroups in front of mine
+    uint64_t base = total_of(wg_rec, blockIdx.x);
     uint32_t mine = 0;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) {
@@ -453,14 +470,11 @@ __global__ __launch_bounds__(kQuantBlock) void k_gather_records(QuantArgs a) {
         if ((uint32_t)w < wave) base += c;
         if ((uint32_t)w == wave) mine = c;
     }
-    if (blockIdx.x + 1u == gridDim.x) {
-        // the last workgroup also totals the counters of all runs
-        if (tid == kQuantBlock - 1) a.ctl->n_rec = base + mine;     // last run: base covers all runs before it
-        uint64_t nnz = 0, vrec = 0;
-        for (uint32_t i = tid; i < n_runs; i += kQuantBlock) { nnz += a.run_count[n_runs + i]; vrec += a.run_count[2u * n_runs + i]; }
-        uint64_t nnz_total, vrec_total;
-        (void)block_excl_scan<uint64_t, kWaves>(nnz, s_part64, nnz_total);
-        (void)block_excl_scan<uint64_t, kWaves>(vrec, s_part64, vrec_total);
+    if (blockIdx.x + 1u == gridDim.x && tid == kQuantBlock - 1) a.ctl->n_rec = base + mine;   // last run: base covers all runs before it
+    if (blockIdx.x == 0) {
+        // the first workgroup (nothing in front of it) totals the other counters
+        const uint64_t nnz_total = total_of(wg_nnz, gridDim.x);
+        const uint64_t vrec_total = total_of(wg_vrec, gridDim.x);
         if (tid == 0) { a.ctl->nnz = nnz_total; a.ctl->n_vrec = vrec_total; }
     }
     if (!mine) return;
