@@ -279,6 +279,9 @@ __device__ inline void codebook_body(const BookArgs &a, uint32_t m, uint64_t *ke
 }
 
 __global__ __launch_bounds__(kBookBlock) void k_codebook(BookArgs a) {
+    // One workgroup on the critical path of its stream, often next to the streaming kernels of
+    // other streams: its wavefronts go first whenever they are ready to issue.
+    __builtin_amdgcn_s_setprio(3);
     __shared__ uint64_t s_keys[kBookLdsSyms];
     __shared__ uint64_t s_iw[kBookLdsSyms];
     __shared__ uint32_t s_lp[kBookLdsSyms];
@@ -343,6 +346,7 @@ __global__ __launch_bounds__(kBookBlock) void k_codebook(BookArgs a) {
 // the reconstruct kernel do nothing.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
+    __builtin_amdgcn_s_setprio(3);                  // as k_codebook: a single workgroup others wait for
     __shared__ uint32_t s_part[kBookBlock / kWave];
     __shared__ uint32_t s_cnt[65];
     __shared__ uint64_t s_first[65];

@@ -62,9 +62,8 @@ __device__ inline uint32_t group_incl_scan(uint32_t v) {
     return (uint32_t)x;
 }
 
-// Four consecutive codes of this lane (symbols i0 .. i0+3) as two packed words; 0xffff marks
-// "past the end" (no code has that value: the alphabet has at most 65535 usable bins + escape 0,
-// and an out-of-range value is treated like any other invalid code by the caller).
+// Four consecutive codes of this lane (symbols i0 .. i0+3) as two packed words, 0 past the end
+// (the caller masks those positions: every 16-bit value can be a code of the largest alphabet).
 __device__ inline uint2 load4(const uint16_t *codes, uint64_t i0, uint64_t n) {
     if (i0 + 4u <= n) return *reinterpret_cast<const uint2 *>(codes + i0);
     uint32_t c[4];
@@ -271,7 +270,10 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_pack(EncodeArgs a) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 uint64_t e = tbl.full(code_of(v[u], j));
-                if (left < 256u) e = (lane * 4u + (uint32_t)j < left) ? e : 0ull;   // uniform test; only the last step of the tensor
+                if (__builtin_expect(left < 256u, 0)) {      // wavefront-uniform; only the last step of the tensor
+                    asm volatile("" ::: "memory");           // keep this a branch: as selects it would cost every step
+                    e = (lane * 4u + (uint32_t)j < left) ? e : 0ull;
+                }
                 len[j] = (uint32_t)e & 63u;
                 cw[j] = e >> 6;
                 bits += len[j];
