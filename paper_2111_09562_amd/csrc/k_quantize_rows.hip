@@ -178,8 +178,6 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
     };
     auto steps_of = [&](auto full_tag, uint32_t t0, float (&xb)[U][NSEG][VEC]) {
         constexpr bool FULL = decltype(full_tag)::value;
-        int32_t dsave[U][NSEG][VEC];                            // residuals of the batch, for the record pass
-        uint64_t flag_esc = 0, flag_susp = 0;                   // lanes that escaped / failed the fp32 bound filter anywhere in the batch
 #pragma unroll
         for (uint32_t u = 0; u < U; ++u) {
             const uint32_t soff = (t0 + u) * stride;
@@ -189,7 +187,7 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
             for (int s = 0; s < NSEG; ++s) {
                 const bool valid = FULL ? col_ok[s] : (col[s] + soff < n_el);
                 float x[VEC], qf[VEC];
-                int32_t q[VEC], rd[VEC], up[VEC];
+                int32_t q[VEC], rd[VEC], up[VEC], d[VEC];
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) {
                     x[v] = xb[u][s][v];
@@ -226,19 +224,21 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
                 }
                 // wavefront masks straight from the comparisons (scalar registers, no per-lane flags)
                 const uint64_t vmask = FULL ? ok_mask[s] : wave_ballot(valid);
-                uint64_t out_mask = 0ull, susp_mask = 0ull;
+                uint64_t em[VEC], sm[VEC], any_rec = 0ull;      // lanes with an escape / lanes that failed the fp32 bound filter
+                bool inr[VEC], susp[VEC];
                 uint32_t code[VEC];
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) {
-                    const int32_t d = (int32_t)((uint32_t)rd[v] - (uint32_t)up[v]);
-                    const uint32_t c = (uint32_t)d + (uint32_t)radius;
-                    const bool inrange = (c - 1u) < code_span;
-                    code[v] = inrange ? c : 0u;
+                    d[v] = (int32_t)((uint32_t)rd[v] - (uint32_t)up[v]);
+                    const uint32_t c = (uint32_t)d[v] + (uint32_t)radius;
+                    inr[v] = (c - 1u) < code_span;
+                    code[v] = inr[v] ? c : 0u;
                     // error-bound filter: |x - y| in fp32 is within one rounding of the exact error
                     const float err = fabsf(x[v] - qf[v] * a.ebx2);
-                    susp_mask |= wave_ballot(!(err <= eb_lo));  // also true for NaN / Inf / huge inputs
-                    out_mask |= wave_ballot(!inrange);
-                    dsave[u][s][v] = d;
+                    susp[v] = !(err <= eb_lo);                  // also true for NaN / Inf / huge inputs
+                    em[v] = wave_ballot(!inr[v]) & vmask;
+                    sm[v] = wave_ballot(susp[v]) & vmask;
+                    any_rec |= em[v] | sm[v];
                     if (PASS == 0) {
                         cnt.nnz_lane += (x[v] != 0.0f) ? 1u : 0u;   // lanes without an element hold 0
                         // Histogram: no divergent branch (switching the execution mask costs more than the
@@ -256,48 +256,28 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
                         }
                     }
                 }
-                flag_esc |= out_mask & vmask;
-                flag_susp |= susp_mask & vmask;
                 if (PASS == 0) {
                     const int voff = FULL ? (int)(col[s] * 2u) : (int)((col[s] + soff) * 2u);
                     const int sof = FULL ? (int)(soff * 2u) : 0;
                     if (VEC == 2) __builtin_amdgcn_raw_buffer_store_b32(code[0] | (code[VEC - 1] << 16), r_c, voff, sof, 0);
                     else __builtin_amdgcn_raw_buffer_store_b16((unsigned short)code[0], r_c, voff, sof, 0);
                 }
-            }
-            if (!MULTI) { ++h_row; h_row = (h_row == H) ? 0u : h_row; }
-        }
-        // ---- outlier records (rare): escapes and verbatim values, in element order ----
-        // One wavefront-uniform test per batch; the batch is walked again only if some lane raised a flag.
-        if ((flag_esc | flag_susp) != 0ull) {
-            const bool any_susp = flag_susp != 0ull;            // uniform: verbatim candidates are much rarer than escapes
+                // ---- outlier records: escapes and verbatim values, in element order (lanes, then a lane's
+                // columns, escape before verbatim).  One wavefront-uniform test per slot.  They go to a small LDS
+                // buffer and leave in bulk, so that the loop holds no global store outside this branch. ----
+                if (any_rec != 0ull) {
+                    uint64_t vm[VEC];
+                    bool verb[VEC];
+                    uint64_t any_s = 0ull;
 #pragma unroll
-            for (uint32_t u = 0; u < U; ++u) {
-                const uint32_t soff = (t0 + u) * stride;
+                    for (int v = 0; v < VEC; ++v) { vm[v] = 0ull; verb[v] = false; any_s |= sm[v]; }
+                    if (any_s != 0ull) {                         // much rarer than escapes: the exact comparison
 #pragma unroll
-                for (int s = 0; s < NSEG; ++s) {
-                    const bool valid = FULL ? col_ok[s] : (col[s] + soff < n_el);
-                    bool esc[VEC], verb[VEC];
-                    uint64_t em[VEC], vm[VEC], any = 0ull;
-#pragma unroll
-                    for (int v = 0; v < VEC; ++v) {
-                        const float x = xb[u][s][v];
-                        esc[v] = valid && !(((uint32_t)dsave[u][s][v] + (uint32_t)radius - 1u) < code_span);
-                        verb[v] = false;
-                        if (any_susp) {
-                            const float t = x * a.r;
-                            const int32_t q = (fabsf(t) < 16777216.0f) ? (int32_t)rintf(t) : 0;
-                            const bool suspicious = !(fabsf(x - (float)q * a.ebx2) <= eb_lo);
-                            if (valid && suspicious) verb[v] = needs_verbatim_rows(x, q, a.r, a.ebx2, a.eb);
+                        for (int v = 0; v < VEC; ++v) {
+                            if (valid && susp[v]) verb[v] = needs_verbatim_rows(x[v], q[v], a.r, a.ebx2, a.eb);
+                            vm[v] = wave_ballot(verb[v]);
                         }
-                        em[v] = wave_ballot(esc[v]);
-                        vm[v] = any_susp ? wave_ballot(verb[v]) : 0ull;
-                        any |= em[v] | vm[v];
                     }
-                    if (any == 0ull) continue;                   // wavefront-uniform
-                    // Records go to a small LDS buffer first and leave in bulk: a global store here, in a
-                    // branch the compiler cannot count, would make every later wait for the prefetched
-                    // loads a wait for all stores.  Order: lanes, then a lane's columns, escape before verbatim.
                     uint32_t add = 0, before = 0;                // records of this slot (uniform); those of the lanes below me
 #pragma unroll
                     for (int v = 0; v < VEC; ++v) {
@@ -306,17 +286,20 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
                         if (vm[v]) before += __builtin_amdgcn_mbcnt_hi((uint32_t)(vm[v] >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)vm[v], 0u));
                         if (PASS == 0) cnt.vrec += (uint32_t)__popcll(vm[v]);
                     }
-                    if (buffered + add > kQuantRecLds2) flush_records();
-                    uint32_t pos = buffered + before;
-                    const uint32_t e = e_lo + col[s] + soff;
+                    if (add) {
+                        if (buffered + add > kQuantRecLds2) flush_records();
+                        uint32_t pos = buffered + before;
+                        const uint32_t e = e_lo + col[s] + soff;
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v) {
-                        if (esc[v]) s_buf[pos++] = make_uint2(2u * (e + (uint32_t)v), (uint32_t)dsave[u][s][v]);
-                        if (verb[v]) s_buf[pos++] = make_uint2(2u * (e + (uint32_t)v) + 1u, __float_as_uint(xb[u][s][v]));
+                        for (int v = 0; v < VEC; ++v) {
+                            if (valid && !inr[v]) s_buf[pos++] = make_uint2(2u * (e + (uint32_t)v), (uint32_t)d[v]);
+                            if (verb[v]) s_buf[pos++] = make_uint2(2u * (e + (uint32_t)v) + 1u, __float_as_uint(x[v]));
+                        }
+                        buffered += add;
                     }
-                    buffered += add;
                 }
             }
+            if (!MULTI) { ++h_row; h_row = (h_row == H) ? 0u : h_row; }
         }
     };
     // Two batches of steps alternate: the loads of one are in flight while the other is worked on.
