@@ -229,6 +229,37 @@ def test_decompress_oracle_container(comet, ctx, oracle, shape, kind, eb, nbins,
     assert err.max() <= np.float64(np.float32(eb))
 
 
+# Plane widths on both sides of every boundary between the lane mappings of the quantise and the
+# scan kernels (one or two columns per lane; several rows per step up to 32 lanes per row; 1, 2, 4, 8
+# segments of 64 lanes), odd and even, with heights that leave a ragged last step and last strip.
+WIDTHS = [2, 8, 15, 16, 18, 31, 32, 33, 34, 62, 63, 64, 65, 66, 99, 126, 128, 129, 130, 201, 254, 256, 257, 258, 300, 333, 510, 511, 512]
+
+
+@pytest.mark.parametrize("w", WIDTHS)
+def test_widths_compress_and_decompress(comet, ctx, oracle, w):
+    """Container bytes and decompressed bits for one width of every lane mapping, with escapes (a
+    small alphabet at a tight bound), verbatim values and negative zero among the inputs."""
+    h = 11 if w > 64 else 37
+    shape = (2, 3, h, w)
+    x = synth.relu_blur(shape, seed=500 + w, blur=3, shift=-0.2)
+    flat = x.ravel()
+    flat[5 % flat.size] = np.inf
+    flat[flat.size // 2] = -np.inf
+    flat[flat.size - 1] = np.nan
+    flat[flat.size // 3] = -0.0
+    flat[flat.size // 5] = 3.0e9                              # beyond the prequantisation range: stored verbatim
+    for eb, nbins, chunk in [(1e-2, 1024, 64), (2e-3, 16, 128)]:
+        want = oracle.compress(x, eb, nbins, chunk)
+        out, used = gpu_compress(ctx, comet, x, eb, nbins, chunk)
+        assert used == want.size
+        assert np.array_equal(out[:used].cpu().numpy(), want), f"container differs, w={w} eb={eb}"
+        want_x = oracle.decompress(want).ravel()
+        y = torch.empty(x.size, dtype=torch.float32, device="cuda")
+        ctx.comet_decompress(out, used, x.shape, y)
+        ctx.comet_sync()
+        assert np.array_equal(y.cpu().numpy().view(np.uint32), want_x.view(np.uint32)), f"values differ, w={w} eb={eb}"
+
+
 def test_roundtrip_config0_and_determinism(comet, ctx, oracle):
     e = synth.config0()[0]
     x = synth.make(e)
