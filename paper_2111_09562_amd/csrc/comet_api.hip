@@ -120,6 +120,13 @@ int status_to_error(uint32_t st) {
     return COMET_OK;
 }
 
+// Clears the zero region of a call (control block, descriptors, histograms): one launch, and a plain
+// kernel rather than a memset node for callers that capture the call in a graph.  n16: 16-byte words.
+__global__ __launch_bounds__(256) void k_clear(uint4 *p, uint32_t n16) {
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    if (i < n16) p[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
 __global__ void k_latch(DevState *s) {           // fold this call's status into the persistent word
     if (s->ctl.status) atomicOr(&s->latched, s->ctl.status);
 }
@@ -455,7 +462,11 @@ int comet_compress(comet_ctx *ctx, const float *dev_in, comet_shape s, float eb,
 
     const ZeroLayout z = zero_layout(nbins, nbins, tiles_q, tiles_e);
     if (z.bytes > ctx->zero_cap) return COMET_ERR_NOMEM;
-    HIP_TRY(hipMemsetAsync(ctx->zero_region, 0, z.bytes, st));
+    {
+        const uint32_t n16 = (uint32_t)(z.bytes / 16u);      // the layout is made of 256-byte pieces
+        hipLaunchKernelGGL(k_clear, dim3((n16 + 255u) / 256u), dim3(256), 0, st, reinterpret_cast<uint4 *>(ctx->zero_region), n16);
+        HIP_TRY(hipGetLastError());
+    }
     uint32_t *hist = reinterpret_cast<uint32_t *>(ctx->zero_region + z.off_hist);
     uint32_t *hist_parts = reinterpret_cast<uint32_t *>(ctx->zero_region + z.off_parts);
     uint64_t *desc_q = reinterpret_cast<uint64_t *>(ctx->zero_region + z.off_desc_q);
@@ -501,7 +512,6 @@ int comet_decompress(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_s
     hipStream_t st = (hipStream_t)stream;
     ReconGeometry g;
     if (!recon_geometry(s, &g)) return COMET_ERR_INVALID;
-    HIP_TRY(hipMemsetAsync(ctx->zero_region, 0, sizeof(Control), st));
     const uint8_t *in = static_cast<const uint8_t *>(dev_in);
     // lanes of a wavefront side by side in one row of the scan kernel (planes x columns)
     const uint32_t ppi = s.w <= 16u ? 4u * (16u / s.w) : (s.w <= 32u ? 2u : 1u);
@@ -512,6 +522,9 @@ int comet_decompress(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_s
         t.hdr = reinterpret_cast<const Header *>(in);
         t.expect.N = s.n; t.expect.C = s.c; t.expect.H = s.h; t.expect.W = s.w; t.bytes = bytes;
         t.compact_only = fast_path ? 1u : 0u;
+        // the only kernel of a decompression that raises status bits: it clears the call's control block itself
+        // and latches what it raises, so the call needs neither a fill before nor a kernel after
+        t.reset_ctl = 1u; t.latched = &ctx->state->latched;
         {
             TimedScope ts(ctx, st, COMET_KERNEL_TABLES);
             hipLaunchKernelGGL(k_decode_tables, dim3(1), dim3(kBookBlock), 0, st, t);
@@ -571,8 +584,6 @@ int comet_decompress(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_s
         TimedScope ts(ctx, st, COMET_KERNEL_RECONSTRUCT);
         hipLaunchKernelGGL(k_reconstruct<0>, dim3(grid), dim3(kDecBlock), g.lds, st, a);
     }
-    HIP_TRY(hipGetLastError());
-    hipLaunchKernelGGL(k_latch, dim3(1), dim3(1), 0, st, ctx->state);
     HIP_TRY(hipGetLastError());
     return COMET_OK;
 }

@@ -136,6 +136,8 @@ struct TablesArgs {
     uint32_t compact_only;     // 1: the caller decodes with k_decode_chunks, which uses the compact table whenever it
                                //    exists, so the general table need not be filled in that case
     Control *ctl;
+    uint32_t reset_ctl;        // 1: this kernel is the first of its call and clears *ctl itself (no separate fill before it)
+    uint32_t *latched;         // if set, a status bit raised here also goes into this persistent word (no separate kernel after the call)
     // container validation (null = stage call)
     const Header *hdr;
     Header expect;             // shape the caller passed

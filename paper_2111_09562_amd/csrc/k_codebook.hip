@@ -357,6 +357,11 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
     __shared__ uint64_t s_dx[kBookBlock];
 
     const uint32_t tid = threadIdx.x;
+    if (a.reset_ctl && tid < sizeof(Control) / 4u) reinterpret_cast<uint32_t *>(a.ctl)[tid] = 0u;   // before the first barrier: nothing has raised a bit yet
+    auto raise_format = [&]() {
+        atomicOr(&a.ctl->status, (uint32_t)ST_FORMAT);
+        if (a.latched) atomicOr(a.latched, (uint32_t)ST_FORMAT);
+    };
     if (tid == 0) {
         uint32_t ok = 1;
         s_nbins = a.nbins;
@@ -387,7 +392,7 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
     if (tid < 65) s_cnt[tid] = 0;
     __syncthreads();
     if (!s_ok) {
-        if (tid == 0) atomicOr(&a.ctl->status, (uint32_t)ST_FORMAT);
+        if (tid == 0) raise_format();
         return;
     }
     const uint32_t nbins = s_nbins;
@@ -416,7 +421,7 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
     const uint32_t m2 = next_pow2(m > 1 ? m : 2);
     for (uint32_t i = m + tid; i < m2; i += kBookBlock) keys[i] = ~0ull;
     if (__syncthreads_or(bad ? 1 : 0) || m == 0) {
-        if (tid == 0) atomicOr(&a.ctl->status, (uint32_t)ST_FORMAT);
+        if (tid == 0) raise_format();
         return;
     }
     if (small) {
@@ -450,7 +455,7 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
     }
     __syncthreads();
     if (!s_ok) {
-        if (tid == 0) atomicOr(&a.ctl->status, (uint32_t)ST_FORMAT);
+        if (tid == 0) raise_format();
         return;
     }
     for (uint32_t p = tid; p < m; p += kBookBlock) a.t.sorted[p] = (uint16_t)(keys[p] & 0xffffu);
