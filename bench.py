@@ -28,8 +28,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per mean launch of a kernel, from the rocprofv3 counter runs summarised under profiles/
 # (FETCH_SIZE + WRITE_SIZE, scaled by the same counters on a plain copy of known size); filled in by hand
 # from those summaries, None where no counter run covers the kernel
-TRAFFIC = {"k_quantize_rows": 184717386, "k_encode_count": 61144691, "k_encode_pack": 87332120,
-           "k_decode_chunks": 104454575, "k_scan_store": 203526995}
+TRAFFIC = {"k_quantize_rows": 185738189, "k_encode_count": 61157375, "k_encode_pack": 88011701,
+           "k_decode_chunks": 104833435, "k_scan_store": 204364594}
 
 
 def main() -> int:
@@ -190,7 +190,10 @@ def main() -> int:
                 per_layer_ratio=[round(4 * x.numel() / s, 3) for x, s in zip(xs, sizes)],
                 roundtrip_frac_hbm_kernel_bytes=round((18.0 + 2 * b) * n_total / step_s / 1e9 / HBM_PEAK_GBS, 4),
                 roundtrip_frac_hbm_min_bytes=round((8.0 + 2 * b) * n_total / step_s / 1e9 / HBM_PEAK_GBS, 4),
-                kernels={k: dict(launches=v["launches"], avg_us=round(v["avg_us"], 2)) for k, v in kern.items()})
+                kernels={k: dict(launches=v["launches"], avg_us=round(v["avg_us"], 2)) for k, v in kern.items()},
+                # the same roofline arithmetic for every streaming kernel (mean launch, algorithmic bytes / duration)
+                kernel_frac_hbm={k: round(alg[k] * n_total / len(xs) / (kern[k]["total_ms"] / kern[k]["launches"] / 1e3) / 1e9
+                                          / HBM_PEAK_GBS, 4) for k in alg if kern[k]["launches"]})
     if tc is not None:
         path.update(compress_GBps=round(in_bytes / tc / 1e9, 1), decompress_GBps=round(in_bytes / td / 1e9, 1),
                     compress_frac_hbm_kernel_bytes=round((10.0 + b) * n_total / tc / 1e9 / HBM_PEAK_GBS, 4),
