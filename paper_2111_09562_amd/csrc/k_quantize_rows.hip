@@ -4,27 +4,30 @@
 // Sec. 2.2 for the bound).
 //
 // The tensor is a matrix of planes*H rows of W floats.  A wavefront owns a run of
-// consecutive rows and walks down it with lanes = columns, so every element is
-// loaded and prequantised exactly once:
+// consecutive rows and walks down it with lanes = columns (two adjacent columns per
+// lane if W is even: one 8-byte load and one packed store of two codes), so every
+// element is loaded and prequantised exactly once:
 //   left neighbour      = the lane to the left (one DPP shift),
 //   row above           = what the same lane held one step earlier (a register),
 //   residual d          = rd - rd_above with rd = q - q_left (the row difference),
-// and there is no index arithmetic per element.  Planes of at most 32 columns are
-// walked K = 64 / W rows at a time (lane = k*W + w, the row above comes from lane
-// - W through one cross-lane permute), so the 64 lanes still cover 64 consecutive
-// elements.  Loads and stores use buffer addressing: lanes without an element get
-// an out-of-range offset, which the hardware ignores, so the loop is free of
-// divergent branches and several steps of loads are kept in flight.
+// and there is no index arithmetic per element.  Rows that take at most 32 lanes are
+// walked K = 64 / lanes-per-row at a time (the row above then comes from the lanes of
+// the row before through one cross-lane permute), so the 64 lanes still cover
+// consecutive elements.  Loads and stores use buffer addressing: lanes without an
+// element get an out-of-range offset, which the hardware ignores, so the loop is
+// free of divergent branches and several steps of loads are kept in flight.
 // The error-bound check is a cheap fp32 filter that falls back to the exact fp64
 // comparison only for elements within a few ulp of the bound.
 //
 // Outlier records (escapes and verbatim values) must end up in the container in
 // element order.  k_quantize_rows appends them, in order, to a staging area of
 // its run (through a small LDS buffer, so that the main loop holds no global store
-// the compiler cannot count) and leaves the count; k_gather_records, a second small kernel, adds up
-// the counts of the runs in front of a run and moves its records to their final
+// the compiler cannot count) and leaves the count; k_gather_records, a second small
+// kernel, adds up the counts in front of a run and moves its records to their final
 // place (a run with more records than its staging area holds is swept again, this
-// time writing in place).  Nothing waits for anything inside a kernel.
+// time writing in place).  The histogram goes the same way: LDS windows are added
+// to one of several partial histograms, which k_gather_records adds up.  Nothing
+// waits for anything inside a kernel.
 #include <type_traits>
 
 #include "comet_kernels.h"
