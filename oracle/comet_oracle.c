@@ -501,12 +501,50 @@ uint64_t oracle_compress_bound(uint32_t N, uint32_t C, uint32_t H, uint32_t W,
     return sz;
 }
 
-int oracle_compress(const float *x, uint32_t N, uint32_t C, uint32_t H, uint32_t W,
-                    float eb, uint32_t nbins, uint32_t chunk_syms,
-                    uint8_t *out, uint64_t capacity, uint64_t *used) {
+/*
+ * A length table a caller brings along (codebook reuse, below) must describe a
+ * code the decoder accepts: lengths 1..57, and either one active symbol of
+ * length 1 or a complete prefix code (Kraft sum exactly 1).
+ */
+static int valid_given_lengths(const uint8_t *len, uint32_t nbins) {
+    uint64_t kraft = 0;                      /* in units of 2^-57 */
+    uint32_t active = 0;
+    for (uint32_t s = 0; s < nbins; ++s) {
+        if (!len[s]) continue;
+        if (len[s] > 57u) return 0;
+        ++active;
+        kraft += 1ull << (57u - len[s]);
+        if (kraft > (1ull << 57)) return 0;
+    }
+    if (active == 0) return 0;
+    if (active == 1) return kraft == (1ull << 56);          /* one symbol: one bit per occurrence */
+    return kraft == (1ull << 57);
+}
+
+/*
+ * given == NULL: the pipeline of the paper (Sec. 4.1): the code book is built
+ * from the histogram of this tensor.
+ * given != NULL: code book reuse.  The paper refreshes its per-layer statistics
+ * only every W iterations because they change slowly (Sec. 3.1); the same holds
+ * for a layer's histogram, so a caller may keep the length table of an earlier
+ * compression of the layer.  Steps 1-2 are unchanged; a quantisation code that
+ * has no code word in the given table is treated exactly like a residual outside
+ * the alphabet: it becomes the escape symbol 0 and its residual goes to the
+ * outlier records.  If an escape is needed and the table has no code word for
+ * the escape symbol either (the earlier tensor had none), the table cannot
+ * represent this tensor: ORC_ERR_INVALID, and the caller compresses in full.
+ * Steps 3-4 are skipped; canonical codes, encoding and the
+ * container follow from the given lengths, which are stored in the container as
+ * usual, so the decoder needs no change and the reconstruction is the one the
+ * full pipeline gives.
+ */
+static int compress_impl(const float *x, uint32_t N, uint32_t C, uint32_t H, uint32_t W,
+                         float eb, uint32_t nbins, uint32_t chunk_syms, const uint8_t *given,
+                         uint8_t *out, uint64_t capacity, uint64_t *used) {
     uint64_t n;
     if (!x || !out || !used || !valid_eb(eb) || !valid_nbins(nbins) || chunk_syms == 0 ||
         !shape_elems(N, C, H, W, &n)) return ORC_ERR_INVALID;
+    if (given && !valid_given_lengths(given, nbins)) return ORC_ERR_INVALID;
     float ebx2, r;
     oracle_constants(eb, &ebx2, &r);
     uint64_t n_chunks = (n + chunk_syms - 1u) / chunk_syms;
@@ -523,8 +561,16 @@ int oracle_compress(const float *x, uint32_t N, uint32_t C, uint32_t H, uint32_t
     uint64_t nnz = 0;
     if ((rc = oracle_prequant(x, n, eb, q, vflag, &nnz)) != ORC_OK) goto done;
     if ((rc = oracle_predict_code(q, N, C, H, W, nbins, codes, delta)) != ORC_OK) goto done;
-    if ((rc = oracle_histogram(codes, n, nbins, freq)) != ORC_OK) goto done;
-    if ((rc = oracle_code_lengths(freq, nbins, len)) != ORC_OK) goto done;
+    if (given) {
+        memcpy(len, given, nbins);
+        for (uint64_t i = 0; i < n; ++i) {
+            if (len[codes[i]] == 0) codes[i] = 0;             /* no code word: escape */
+            if (codes[i] == 0 && len[0] == 0) { rc = ORC_ERR_INVALID; goto done; }
+        }
+    } else {
+        if ((rc = oracle_histogram(codes, n, nbins, freq)) != ORC_OK) goto done;
+        if ((rc = oracle_code_lengths(freq, nbins, len)) != ORC_OK) goto done;
+    }
     if ((rc = oracle_canonical_codes(len, nbins, code)) != ORC_OK) goto done;
 
     uint64_t n_rec = 0, n_vrec = 0;
@@ -566,6 +612,20 @@ int oracle_compress(const float *x, uint32_t N, uint32_t C, uint32_t H, uint32_t
 done:
     free(q); free(delta); free(vflag); free(codes); free(freq); free(len); free(code); free(chunk_off);
     return rc;
+}
+
+int oracle_compress(const float *x, uint32_t N, uint32_t C, uint32_t H, uint32_t W,
+                    float eb, uint32_t nbins, uint32_t chunk_syms,
+                    uint8_t *out, uint64_t capacity, uint64_t *used) {
+    return compress_impl(x, N, C, H, W, eb, nbins, chunk_syms, NULL, out, capacity, used);
+}
+
+/* Compression with the length table of an earlier compression (see compress_impl). */
+int oracle_compress_with_lengths(const float *x, uint32_t N, uint32_t C, uint32_t H, uint32_t W,
+                                 float eb, uint32_t nbins, uint32_t chunk_syms, const uint8_t *given_len,
+                                 uint8_t *out, uint64_t capacity, uint64_t *used) {
+    if (!given_len) return ORC_ERR_INVALID;
+    return compress_impl(x, N, C, H, W, eb, nbins, chunk_syms, given_len, out, capacity, used);
 }
 
 int oracle_decompress(const uint8_t *in, uint64_t bytes, float *out, uint64_t out_cap_elems,

@@ -54,11 +54,12 @@ def lib():
         L.oracle_compress_bound.argtypes = [C.c_uint32] * 6
         L.oracle_compress_bound.restype = C.c_uint64
         L.oracle_compress.argtypes = [f32p] + [C.c_uint32] * 4 + [C.c_float, C.c_uint32, C.c_uint32, u8p, C.c_uint64, u64p]
+        L.oracle_compress_with_lengths.argtypes = [f32p] + [C.c_uint32] * 4 + [C.c_float, C.c_uint32, C.c_uint32, u8p, u8p, C.c_uint64, u64p]
         L.oracle_decompress.argtypes = [u8p, C.c_uint64, f32p, C.c_uint64, u32p]
         L.oracle_adapt_eb.argtypes = [C.c_double, C.c_double, C.c_double, C.c_uint32, C.c_double, C.c_double, C.c_float, C.c_float, f32p]
         for name in ("oracle_prequant", "oracle_predict_code", "oracle_histogram", "oracle_code_lengths",
                      "oracle_canonical_codes", "oracle_encode", "oracle_decode", "oracle_reconstruct",
-                     "oracle_compress", "oracle_decompress", "oracle_adapt_eb"):
+                     "oracle_compress", "oracle_compress_with_lengths", "oracle_decompress", "oracle_adapt_eb"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -195,6 +196,24 @@ def compress(x, eb: float, nbins: int, chunk_syms: int, capacity: int | None = N
             continue
         _chk(rc, "oracle_compress")
         return out[: int(used.value)].copy()
+
+
+def compress_with_lengths(x, eb: float, nbins: int, chunk_syms: int, given_len) -> np.ndarray:
+    """Compression that reuses a length table (a code without a code word in it becomes an escape)."""
+    x = _c(x, np.float32)
+    assert x.ndim == 4
+    n_, c_, h_, w_ = x.shape
+    given = _c(given_len, np.uint8)
+    assert given.size == nbins
+    capacity = compress_bound(x.shape, nbins, chunk_syms)
+    if capacity == 0:
+        raise OracleError(ERR_INVALID, "oracle_compress_bound")
+    out = np.empty(capacity, np.uint8)
+    used = C.c_uint64()
+    rc = lib().oracle_compress_with_lengths(_p(x, C.c_float), n_, c_, h_, w_, C.c_float(eb), nbins, chunk_syms,
+                                            _p(given, C.c_uint8), _p(out, C.c_uint8), capacity, C.byref(used))
+    _chk(rc, "oracle_compress_with_lengths")
+    return out[: int(used.value)].copy()
 
 
 def decompress(container) -> np.ndarray:

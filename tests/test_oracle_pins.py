@@ -507,6 +507,77 @@ def test_capacity_and_format_errors(oracle):
             oracle.compress(x, 1e-2, nb, 128)
 
 
+# --------------------------------------------------------------------------
+# code book reuse (compression with the length table of an earlier compression)
+# --------------------------------------------------------------------------
+
+def _lengths_of(oracle, x, eb, nbins):
+    q, _, _ = oracle.prequant(x, eb)
+    codes, _ = oracle.predict_code(q, x.shape, nbins)
+    return np.asarray(oracle.code_lengths(oracle.histogram(codes, nbins)), np.uint8)
+
+
+def test_reuse_hand_case(oracle):
+    """By hand: 2 eb = 1, so q = x; one row, so d = q - q_left = [0, 1, 0, -1] and the codes are d + 4 =
+    [4, 5, 4, 3].  The given table has code words for the symbols 0 (escape), 4 and 5 only, so the 3
+    becomes an escape with the record (2 * 3, -1).  Canonical codes by (length, symbol): 4 -> 0, 0 -> 10,
+    5 -> 11; the chunk reads 0 11 0 10, left-aligned in one word."""
+    x = np.array([0.0, 1.0, 1.0, 0.0], np.float32).reshape(1, 1, 1, 4)
+    given = np.zeros(8, np.uint8)
+    given[0], given[4], given[5] = 2, 1, 2
+    buf = oracle.compress_with_lengths(x, 0.5, 8, 64, given)
+    c = oracle.parse_container(buf)
+    assert list(c["len"]) == list(given)
+    assert list(c["chunk_off"]) == [0]
+    assert [int(w) for w in c["payload"]] == [0b011010 << 26]
+    assert [tuple(int(v) for v in r) for r in c["records"]] == [(6, 0xFFFFFFFF)]
+    assert np.array_equal(oracle.decompress(buf), x)
+
+
+@pytest.mark.parametrize("eb,nbins,chunk", [(1e-2, 1024, 64), (2e-3, 64, 128)])
+def test_reuse_with_own_lengths_is_the_full_pipeline(oracle, eb, nbins, chunk):
+    x = synth.relu_blur((2, 3, 19, 23), seed=31, blur=3, shift=-0.2)
+    want = oracle.compress(x, eb, nbins, chunk)
+    got = oracle.compress_with_lengths(x, eb, nbins, chunk, _lengths_of(oracle, x, eb, nbins))
+    assert np.array_equal(got, want)
+
+
+def test_reuse_with_a_stale_table_reconstructs_the_same_values(oracle):
+    """The entropy coder is lossless: whatever complete table is used, the values that come back are
+    those of the full pipeline (and so obey the bound); only the size changes."""
+    eb, nbins = 5e-3, 256
+    x_old = synth.relu_blur((2, 4, 17, 21), seed=41, blur=3, shift=-0.2)
+    x_new = synth.relu_blur((2, 4, 17, 21), seed=42, blur=2, shift=0.1) * np.float32(1.7)
+    stale = _lengths_of(oracle, x_old, eb, nbins)
+    own = oracle.compress(x_new, eb, nbins, 64)
+    reused = oracle.compress_with_lengths(x_new, eb, nbins, 64, stale)
+    a, b = oracle.decompress(own), oracle.decompress(reused)
+    assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    assert np.abs(b.astype(np.float64) - x_new.astype(np.float64)).max() <= np.float64(np.float32(eb))
+    assert reused.size >= own.size - 8 * 64                  # an optimal table of its own is never much worse
+    # symbols the stale table does not know became escapes: more records than before
+    q, _, _ = oracle.prequant(x_new, eb)
+    codes, _ = oracle.predict_code(q, x_new.shape, nbins)
+    unknown = int(np.count_nonzero((stale[codes] == 0) & (codes != 0)))
+    assert unknown > 0
+    assert oracle.parse_container(reused)["n_records"] == oracle.parse_container(own)["n_records"] + unknown
+
+
+def test_reuse_rejects_tables_the_decoder_would_reject(oracle):
+    x = synth.relu_blur((1, 2, 9, 9), seed=5)
+    incomplete = np.zeros(64, np.uint8); incomplete[0], incomplete[32] = 2, 1       # Kraft sum 3/4
+    over = np.zeros(64, np.uint8); over[0], over[31], over[32] = 1, 1, 1            # Kraft sum 3/2
+    too_long = np.zeros(64, np.uint8); too_long[0], too_long[32] = 1, 58
+    no_escape = np.zeros(64, np.uint8); no_escape[32], no_escape[33] = 1, 1         # a valid code, but x needs more symbols
+    for bad in (incomplete, over, too_long, no_escape, np.zeros(64, np.uint8)):
+        with pytest.raises(oracle.OracleError) as ei:
+            oracle.compress_with_lengths(x, 1e-2, 64, 64, bad)
+        assert ei.value.code == oracle.ERR_INVALID
+    single = np.zeros(64, np.uint8); single[0] = 1                                  # everything escapes
+    buf = oracle.compress_with_lengths(x, 1e-2, 64, 64, single)
+    assert np.array_equal(oracle.decompress(buf).view(np.uint32), oracle.decompress(oracle.compress(x, 1e-2, 64, 64)).view(np.uint32))
+
+
 def test_expansion_case_fits_bound(oracle):
     """White noise at a tight bound with few bins escapes almost everywhere: the
     container grows past the input, and must still fit the stated worst case."""
