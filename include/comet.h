@@ -42,6 +42,8 @@ extern "C" {
 #define COMET_ERR_HIP (-4)         /* a HIP runtime call failed; see comet_strerror */
 #define COMET_ERR_NOMEM (-5)       /* workspace allocation failed / context too small for the request */
 #define COMET_ERR_INTERNAL (-6)    /* a device-side safety net tripped (should not happen) */
+#define COMET_ERR_CODEBOOK (-7)    /* comet_compress_with_codebook: the length table is no complete prefix code, or the
+                                      tensor needs an escape and the table has no code word for the escape symbol */
 
 #define COMET_HEADER_BYTES 128u
 #define COMET_DEFAULT_CHUNK_SYMS 64u
@@ -86,6 +88,24 @@ uint64_t comet_compress_bound(comet_shape shape, uint32_t nbins, uint32_t chunk_
  * (comet_peek) and errors are reported by comet_sync. */
 int comet_compress(comet_ctx *ctx, const float *dev_in, comet_shape shape, float eb, uint32_t nbins,
                    void *stream, void *dev_out, uint64_t capacity, uint64_t *bytes_out);
+
+/* Compress with the code book of an earlier compression of the same layer.  COMET refreshes a
+ * layer's statistics only every W iterations because they change slowly (Sec. 3.1); the same holds
+ * for the layer's histogram, so the histogram and the Huffman construction (Sec. 4.1) can be skipped
+ * between refreshes.  dev_len: device pointer to u8[nbins] code lengths (the length section of an
+ * earlier container of the same nbins starts COMET_HEADER_BYTES into it); it must stay valid and
+ * unchanged until the call has completed and may lie inside another container, not inside dev_out.
+ * The lengths must form a complete prefix code (or one symbol of length 1), none above 57.  A
+ * quantisation code without a code word in the table is stored like a residual outside the
+ * alphabet (escape symbol + outlier record); the container carries the table, so it decompresses
+ * with comet_decompress to exactly the values comet_compress would give.  Everything else as
+ * comet_compress.  Limits: nbins <= 8192 and planes of at most 512 columns (COMET_ERR_INVALID
+ * otherwise).  A table that is no such code, or that lacks a code word for the escape symbol when
+ * the tensor needs one, raises COMET_ERR_CODEBOOK (device-side: returned here if bytes_out is
+ * given, else by comet_sync); the caller then compresses in full. */
+int comet_compress_with_codebook(comet_ctx *ctx, const float *dev_in, comet_shape shape, float eb, uint32_t nbins,
+                                 const uint8_t *dev_len, void *stream, void *dev_out, uint64_t capacity,
+                                 uint64_t *bytes_out);
 
 /* Decompress a container for the backward pass (Sec. 3.4): dev_in (`bytes`
  * bytes, 16-byte aligned) -> dev_out (fp32, shape.n*c*h*w elements).  `shape`

@@ -13,12 +13,12 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("COMET_LIB", os.path.join(_HERE, "libcomet.so"))   # COMET_LIB: use another build of the library
 
-OK, ERR_INVALID, ERR_CAPACITY, ERR_FORMAT, ERR_HIP, ERR_NOMEM, ERR_INTERNAL = 0, -1, -2, -3, -4, -5, -6
+OK, ERR_INVALID, ERR_CAPACITY, ERR_FORMAT, ERR_HIP, ERR_NOMEM, ERR_INTERNAL, ERR_CODEBOOK = 0, -1, -2, -3, -4, -5, -6, -7
 HEADER_BYTES = 128
 DEFAULT_CHUNK_SYMS = 64
 
 EXPORTS = (
-    "comet_create", "comet_destroy", "comet_set_chunk_syms", "comet_compress_bound", "comet_compress",
+    "comet_create", "comet_destroy", "comet_set_chunk_syms", "comet_compress_bound", "comet_compress", "comet_compress_with_codebook",
     "comet_decompress", "comet_sync", "comet_peek", "comet_adapt_defaults", "comet_adapt_eb",
     "comet_stage_quantize", "comet_stage_codebook", "comet_stage_encode", "comet_stage_decode",
     "comet_stage_reconstruct", "comet_profile_enable", "comet_profile_reset", "comet_profile_read", "comet_strerror",
@@ -71,6 +71,7 @@ def lib():
         L.comet_compress_bound.argtypes = [Shape, C.c_uint32, C.c_uint32]
         L.comet_compress_bound.restype = u64
         L.comet_compress.argtypes = [vp, vp, Shape, C.c_float, C.c_uint32, vp, vp, u64, C.POINTER(u64)]
+        L.comet_compress_with_codebook.argtypes = [vp, vp, Shape, C.c_float, C.c_uint32, vp, vp, vp, u64, C.POINTER(u64)]
         L.comet_decompress.argtypes = [vp, vp, u64, Shape, vp, vp]
         L.comet_sync.argtypes = [vp, vp]
         L.comet_peek.argtypes = [vp, vp, u64, vp, C.POINTER(Info)]
@@ -175,6 +176,18 @@ class Context:
         rc = lib().comet_compress(self._h, _ptr(x), _shape(x.shape), C.c_float(eb), nbins, _stream(stream), _ptr(out),
                                   out.numel() * out.element_size(), C.byref(used) if sync else None)
         _chk(rc, "comet_compress")
+        return int(used.value) if sync else None
+
+    def comet_compress_with_codebook(self, x, eb: float, nbins: int, dev_len, out, stream=None, sync: bool = True):
+        """As comet_compress, with the code lengths of an earlier compression: dev_len is a uint8 device tensor of
+        nbins entries (e.g. ``earlier_container[HEADER_BYTES:HEADER_BYTES + nbins]``)."""
+        assert x.dim() == 4 and str(x.dtype) == "torch.float32"
+        assert str(dev_len.dtype) == "torch.uint8" and dev_len.numel() == nbins and dev_len.is_contiguous()
+        used = C.c_uint64()
+        rc = lib().comet_compress_with_codebook(self._h, _ptr(x), _shape(x.shape), C.c_float(eb), nbins, _ptr(dev_len),
+                                                _stream(stream), _ptr(out), out.numel() * out.element_size(),
+                                                C.byref(used) if sync else None)
+        _chk(rc, "comet_compress_with_codebook")
         return int(used.value) if sync else None
 
     def comet_decompress(self, container, nbytes: int, shape, out, stream=None) -> None:

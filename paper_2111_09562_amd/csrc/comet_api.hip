@@ -115,6 +115,7 @@ ZeroLayout zero_layout(uint32_t nbins_hist, uint32_t nbins_parts, uint64_t tiles
 
 int status_to_error(uint32_t st) {
     if (st & ST_INTERNAL) return COMET_ERR_INTERNAL;
+    if (st & ST_CODEBOOK) return COMET_ERR_CODEBOOK;
     if (st & ST_FORMAT) return COMET_ERR_FORMAT;
     if (st & ST_CAPACITY) return COMET_ERR_CAPACITY;
     return COMET_OK;
@@ -189,9 +190,10 @@ void encode_geometry(const comet_ctx *ctx, uint64_t n_chunks, uint32_t *seg_chun
 struct QuantGeom { bool rows; uint32_t grid, rows_per_wave, rows_per_step, vec; };
 QuantGeom quantize_geometry(const comet_ctx *ctx, comet_shape s, uint64_t n, const float *x);
 
+// reuse_len: code book reuse (device u8[nbins], row-walking kernel only); else null
 int launch_quantize(comet_ctx *ctx, const float *x, comet_shape s, uint64_t n, float eb, uint32_t nbins,
                     hipStream_t st, uint16_t *codes, uint32_t *hist, uint32_t *hist_parts, uint32_t *rec, uint64_t rec_cap,
-                    uint64_t *desc) {
+                    uint64_t *desc, const uint8_t *reuse_len = nullptr) {
     QuantArgs a{};
     a.x = x; a.n = n;
     a.divW = make_fastdiv(s.w); a.divH = make_fastdiv(s.h);
@@ -219,12 +221,16 @@ int launch_quantize(comet_ctx *ctx, const float *x, comet_shape s, uint64_t n, f
         do {                                                                                                           \
             {                                                                                                          \
                 TimedScope ts(ctx, st, COMET_KERNEL_QUANTIZE);                                                         \
-                if (full) hipLaunchKernelGGL((k_quantize_rows<VEC, NSEG, MULTI, true>), dim3(grid), dim3(kQuantBlock), lds, st, a);   \
-                else hipLaunchKernelGGL((k_quantize_rows<VEC, NSEG, MULTI, false>), dim3(grid), dim3(kQuantBlock), lds, st, a);       \
+                if (reuse_len) hipLaunchKernelGGL((k_quantize_rows<VEC, NSEG, MULTI, true, true>), dim3(grid), dim3(kQuantBlock), lds_reuse, st, a); \
+                else if (full) hipLaunchKernelGGL((k_quantize_rows<VEC, NSEG, MULTI, true, false>), dim3(grid), dim3(kQuantBlock), lds, st, a);   \
+                else hipLaunchKernelGGL((k_quantize_rows<VEC, NSEG, MULTI, false, false>), dim3(grid), dim3(kQuantBlock), lds, st, a);       \
             }                                                                                                          \
             TimedScope ts(ctx, st, COMET_KERNEL_GATHER);                                                               \
-            hipLaunchKernelGGL((k_gather_records<VEC, NSEG, MULTI>), dim3(grid), dim3(kQuantBlock), 0, st, a);         \
+            if (reuse_len) hipLaunchKernelGGL((k_gather_records<VEC, NSEG, MULTI, true>), dim3(grid), dim3(kQuantBlock), lds_reuse, st, a); \
+            else hipLaunchKernelGGL((k_gather_records<VEC, NSEG, MULTI, false>), dim3(grid), dim3(kQuantBlock), 0, st, a); \
         } while (0)
+        a.reuse_len = reuse_len;
+        const size_t lds_reuse = ((size_t)nbins + 3u) & ~(size_t)3u;    // the given length table, one byte per bin
         const uint32_t lanes_per_row = s.w / g.vec;
         if (g.vec == 2u) {
             if (lanes_per_row <= 32u) COMET_LAUNCH_QR(2, 1, true);
@@ -240,6 +246,7 @@ int launch_quantize(comet_ctx *ctx, const float *x, comet_shape s, uint64_t n, f
         }
 #undef COMET_LAUNCH_QR
     } else {
+        if (reuse_len) return COMET_ERR_INVALID;          // the flat-tile kernel has no code book reuse
         // one segment of consecutive tiles per workgroup, about as many workgroups as fit the chip at once
         a.tiles_per_seg = (a.n_tiles + grid - 1) / grid;
         a.rec_lds = kQuantRecLds;
@@ -435,8 +442,26 @@ uint64_t comet_compress_bound(comet_shape s, uint32_t nbins, uint32_t chunk_syms
     return sz;
 }
 
+namespace {
+int compress_impl(comet_ctx *ctx, const float *dev_in, comet_shape s, float eb, uint32_t nbins, const uint8_t *dev_len,
+                  void *stream, void *dev_out, uint64_t capacity, uint64_t *bytes_out);
+}
+
 int comet_compress(comet_ctx *ctx, const float *dev_in, comet_shape s, float eb, uint32_t nbins,
                    void *stream, void *dev_out, uint64_t capacity, uint64_t *bytes_out) {
+    return compress_impl(ctx, dev_in, s, eb, nbins, nullptr, stream, dev_out, capacity, bytes_out);
+}
+
+int comet_compress_with_codebook(comet_ctx *ctx, const float *dev_in, comet_shape s, float eb, uint32_t nbins,
+                                 const uint8_t *dev_len, void *stream, void *dev_out, uint64_t capacity,
+                                 uint64_t *bytes_out) {
+    if (!dev_len || nbins > kQuantReuseMaxBins || s.w > kQuantRowsMaxW) return COMET_ERR_INVALID;
+    return compress_impl(ctx, dev_in, s, eb, nbins, dev_len, stream, dev_out, capacity, bytes_out);
+}
+
+namespace {
+int compress_impl(comet_ctx *ctx, const float *dev_in, comet_shape s, float eb, uint32_t nbins, const uint8_t *dev_len,
+                  void *stream, void *dev_out, uint64_t capacity, uint64_t *bytes_out) {
     uint64_t n;
     if (!ctx || !dev_in || !dev_out || !shape_elems(s, &n) || !valid_eb(eb) || !valid_nbins(nbins) ||
         s.w > kMaxW || ((uintptr_t)dev_out & 15u) || ((uintptr_t)dev_in & 15u)) return COMET_ERR_INVALID;
@@ -474,11 +499,11 @@ int comet_compress(comet_ctx *ctx, const float *dev_in, comet_shape s, float eb,
     uint8_t *out = static_cast<uint8_t *>(dev_out);
 
     int rc = launch_quantize(ctx, dev_in, s, n, eb, nbins, st, ctx->codes, hist, hist_parts,
-                             reinterpret_cast<uint32_t *>(out + proto.off_outlier), (capacity - proto.off_outlier) / 8u, desc_q);
+                             reinterpret_cast<uint32_t *>(out + proto.off_outlier), (capacity - proto.off_outlier) / 8u, desc_q, dev_len);
     if (rc) return rc;
     {
         BookArgs b{};
-        b.hist = hist; b.nbins = nbins; b.len_out = out + proto.off_len; b.code_out = nullptr; b.enc = ctx->enc;
+        b.hist = hist; b.given_len = dev_len; b.nbins = nbins; b.len_out = out + proto.off_len; b.code_out = nullptr; b.enc = ctx->enc;
         b.scratch = ctx->book; b.ctl = &ctx->state->ctl; b.hdr = reinterpret_cast<Header *>(out); b.proto = proto; b.capacity = capacity;
         {
             TimedScope ts(ctx, st, COMET_KERNEL_CODEBOOK);
@@ -504,6 +529,7 @@ int comet_compress(comet_ctx *ctx, const float *dev_in, comet_shape s, float eb,
     }
     return COMET_OK;
 }
+}  // namespace
 
 int comet_decompress(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_shape s, void *stream, float *dev_out) {
     uint64_t n;
@@ -804,6 +830,7 @@ const char *comet_strerror(int code) {
         case COMET_ERR_HIP: return g_hip_msg;
         case COMET_ERR_NOMEM: return "out of memory, or request larger than the context was created for";
         case COMET_ERR_INTERNAL: return "device-side consistency check failed";
+        case COMET_ERR_CODEBOOK: return "the given code lengths are no complete prefix code, or lack a code word for an escape the tensor needs";
         default: return "unknown error code";
     }
 }

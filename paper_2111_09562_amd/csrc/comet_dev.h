@@ -12,7 +12,7 @@ constexpr uint32_t kHeaderBytes = 128u;
 constexpr int kWave = 64;                   // CDNA wavefront width
 
 // device-side status bits, latched in Control::status
-enum : uint32_t { ST_CAPACITY = 1u, ST_FORMAT = 2u, ST_INTERNAL = 4u };
+enum : uint32_t { ST_CAPACITY = 1u, ST_FORMAT = 2u, ST_INTERNAL = 4u, ST_CODEBOOK = 8u };
 
 // Container header.  Field order is the on-disk order (little-endian).
 struct Header {

@@ -27,6 +27,7 @@ struct QuantArgs {
     uint32_t hist_shift;       //   log2 of the copies of the LDS histogram window (lane & (copies - 1) picks one)
     uint32_t *stage;           //   staging area: kQuantRecRun (key, payload) pairs per run
     uint32_t *run_count;       //   three arrays of one entry per run: records, non-zero inputs, verbatim records
+    const uint8_t *reuse_len;  //   code book reuse (REUSE kernels): u8[nbins] code lengths; a code of length 0 becomes an escape; no histogram
     uint32_t *hist_parts;      //   hist_copies partial histograms of nbins entries, zeroed: workgroup b adds to copy b % hist_copies
     uint32_t hist_copies;      //   (k_gather_records adds them up into hist)
     uint16_t *codes;
@@ -46,8 +47,10 @@ constexpr uint32_t kQuantHistCopiesMax = 32;        // partial histograms the wo
 constexpr uint32_t kQuantHistPartsWords = 65536;    // all copies together have at most this many entries
 // VEC adjacent columns per lane (2 needs an even W and 8-byte aligned input), NSEG segments of 64 lanes per row,
 // MULTI: several rows per step
-template <int VEC, int NSEG, bool MULTI, bool FULLWIN> __global__ void k_quantize_rows(QuantArgs a);
-template <int VEC, int NSEG, bool MULTI> __global__ void k_gather_records(QuantArgs a);
+// REUSE: code book reuse: escapes follow the given length table, no histogram (FULLWIN is then true and unused)
+template <int VEC, int NSEG, bool MULTI, bool FULLWIN, bool REUSE = false> __global__ void k_quantize_rows(QuantArgs a);
+template <int VEC, int NSEG, bool MULTI, bool REUSE = false> __global__ void k_gather_records(QuantArgs a);
+constexpr uint32_t kQuantReuseMaxBins = 8192;   // largest alphabet whose length table the REUSE kernels keep in LDS
 
 // ---- codebook -----------------------------------------------------------------
 constexpr int kBookBlock = 1024;
@@ -62,6 +65,7 @@ struct BookScratch {                        // global scratch for large alphabet
 
 struct BookArgs {
     const uint32_t *hist;
+    const uint8_t *given_len;  // code book reuse: take these lengths instead of building them from hist (which is then unused)
     uint32_t nbins;
     uint8_t *len_out;          // u8[nbins]
     uint64_t *code_out;        // u64[nbins] or null (stage output)

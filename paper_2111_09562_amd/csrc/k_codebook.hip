@@ -186,11 +186,14 @@ __device__ inline void codebook_body(const BookArgs &a, uint32_t m, uint64_t *ke
     const uint32_t nbins = a.nbins;
     COMET_DBG(a.ctl, 1);
     // ---- 1. compact the active symbols into sort keys (frequency << 16 | symbol) ----
+    // (code book reuse: the given length takes the place of the frequency, so the keys are already
+    // those of step 5 and steps 2-4 are skipped)
+    const bool given = a.given_len != nullptr;
     {
         uint32_t done = 0;
         for (uint32_t base = 0; base < nbins; base += kBookBlock) {
             const uint32_t s = base + tid;
-            const uint32_t f = (s < nbins) ? a.hist[s] : 0u;
+            const uint32_t f = (s < nbins) ? (given ? (uint32_t)a.given_len[s] : a.hist[s]) : 0u;
             uint32_t tot;
             const uint32_t pos = block_excl_scan<uint32_t, kBookBlock / kWave>(f ? 1u : 0u, s_part, tot);
             if (f) keys[done + pos] = ((uint64_t)f << 16) | s;
@@ -208,8 +211,18 @@ __device__ inline void codebook_body(const BookArgs &a, uint32_t m, uint64_t *ke
     __syncthreads();
 
     COMET_DBG(a.ctl, 2);
-    // ---- 2. leaves in (frequency, symbol) order ----
     const bool reg_sort = LDS && m2 <= (uint32_t)kBookBlock;
+    if (given) {
+        // lengths per symbol are known: count them; a length the container cannot hold spoils the count
+        // of length 64, which the completeness test below then rejects
+        for (uint32_t i = tid; i < m; i += kBookBlock) {
+            const uint32_t depth = (uint32_t)(keys[i] >> 16);
+            atomicAdd(&s_cnt[depth > 57 ? 64 : depth], 1u);
+            atomicMax(s_maxlen, depth);
+        }
+        __syncthreads();
+    } else {
+    // ---- 2. leaves in (frequency, symbol) order ----
     if (reg_sort) {
         uint64_t key = tid < m2 ? keys[tid] : ~0ull;
         key = bitonic_sort_regs(key, s_x, m2);
@@ -248,6 +261,7 @@ __device__ inline void codebook_body(const BookArgs &a, uint32_t m, uint64_t *ke
         atomicMax(s_maxlen, depth);
     }
     __syncthreads();
+    }   // !given
 
     COMET_DBG(a.ctl, 5);
     // ---- 5. canonical order (length, symbol) ----
@@ -261,8 +275,8 @@ __device__ inline void codebook_body(const BookArgs &a, uint32_t m, uint64_t *ke
     }
     if (tid == 0) {
         uint32_t mx, mn;
-        const bool ok = (m == 0) || canonical_first_codes(s_cnt, m, s_first, s_findex, &mx, &mn);
-        if (!ok) atomicOr(&a.ctl->status, (uint32_t)ST_INTERNAL);
+        const bool ok = (m == 0 && !given) || (m != 0 && canonical_first_codes(s_cnt, m, s_first, s_findex, &mx, &mn));
+        if (!ok) atomicOr(&a.ctl->status, given ? (uint32_t)ST_CODEBOOK : (uint32_t)ST_INTERNAL);   // a given table must be a complete code
     }
     __syncthreads();
 
@@ -302,7 +316,7 @@ __global__ __launch_bounds__(kBookBlock) void k_codebook(BookArgs a) {
     uint32_t m = 0;
     for (uint32_t base = 0; base < nbins; base += kBookBlock) {
         const uint32_t s = base + tid;
-        m += __syncthreads_count((s < nbins) && a.hist[s] != 0u);
+        m += __syncthreads_count((s < nbins) && (a.given_len ? a.given_len[s] != 0 : a.hist[s] != 0u));
     }
     if (m <= kBookLdsSyms)
         codebook_body<true>(a, m, s_keys, s_iw, s_lp, s_ip, s_x, s_part, s_cnt, s_first, s_findex, &s_maxlen);

@@ -70,9 +70,13 @@ struct SweepCounts {
 // one cross-lane shift per pair); NSEG: segments of 64 lanes per row (1, 2, 4, 8); MULTI: a row
 // takes at most 32 lanes, K rows per step (NSEG == 1); FULLWIN: every histogram bin is in the LDS
 // window.
-template <int VEC, int NSEG, bool MULTI, bool FULLWIN, int PASS>
+// REUSE: code book reuse.  s_len (LDS, u8[nbins]) holds the code lengths the caller brought; a code
+// whose length is 0 becomes an escape, there is no histogram, and an escape that the table has no
+// code word for raises ST_CODEBOOK.
+template <int VEC, int NSEG, bool MULTI, bool FULLWIN, int PASS, bool REUSE = false>
 __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint32_t row_hi, uint32_t lane, uint32_t *s_hist,
-                                      uint32_t hist_dummy, uint2 *s_buf, uint2 *rec_dst, uint64_t rec_cap, SweepCounts &cnt) {
+                                      uint32_t hist_dummy, uint2 *s_buf, uint2 *rec_dst, uint64_t rec_cap, SweepCounts &cnt,
+                                      const uint8_t *s_len = nullptr) {
     const uint32_t W = a.divW.d, H = a.divH.d;
     const uint32_t LPR = W / (uint32_t)VEC;         // lanes per row
     const int32_t radius = a.radius;
@@ -235,6 +239,7 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
                     d[v] = (int32_t)((uint32_t)rd[v] - (uint32_t)up[v]);
                     const uint32_t c = (uint32_t)d[v] + (uint32_t)radius;
                     inr[v] = (c - 1u) < code_span;
+                    if (REUSE) inr[v] = inr[v] && s_len[inr[v] ? c : 0u] != 0;    // no code word in the given table: an escape
                     code[v] = inr[v] ? c : 0u;
                     // error-bound filter: |x - y| in fp32 is within one rounding of the exact error
                     const float err = fabsf(x[v] - qf[v] * a.ebx2);
@@ -242,8 +247,8 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
                     em[v] = wave_ballot(!inr[v]) & vmask;
                     sm[v] = wave_ballot(susp[v]) & vmask;
                     any_rec |= em[v] | sm[v];
-                    if (PASS == 0) {
-                        cnt.nnz_lane += (x[v] != 0.0f) ? 1u : 0u;   // lanes without an element hold 0
+                    if (PASS == 0) cnt.nnz_lane += (x[v] != 0.0f) ? 1u : 0u;   // lanes without an element hold 0
+                    if (PASS == 0 && !REUSE) {
                         // Histogram: no divergent branch (switching the execution mask costs more than the
                         // atomic).  Lanes that count nothing add to a word of their own; the centre bin is
                         // not counted here, it is what is left of the workgroup's elements.  The window is
@@ -269,6 +274,12 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
                 // columns, escape before verbatim).  One wavefront-uniform test per slot.  They go to a small LDS
                 // buffer and leave in bulk, so that the loop holds no global store outside this branch. ----
                 if (any_rec != 0ull) {
+                    if (REUSE && PASS == 0) {                    // an escape, and the table has no code word for it
+                        uint64_t any_e = 0ull;
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) any_e |= em[v];
+                        if (any_e != 0ull && s_len[0] == 0 && lane == 0) atomicOr(&a.ctl->status, (uint32_t)ST_CODEBOOK);
+                    }
                     uint64_t vm[VEC];
                     bool verb[VEC];
                     uint64_t any_s = 0ull;
@@ -340,10 +351,11 @@ __device__ inline void run_rows(const QuantArgs &a, uint32_t run, uint32_t *lo, 
 }  // namespace
 
 // One run per wavefront, kQuantBlock / 64 runs per workgroup.
-template <int VEC, int NSEG, bool MULTI, bool FULLWIN>
+template <int VEC, int NSEG, bool MULTI, bool FULLWIN, bool REUSE>
 __global__ __launch_bounds__(kQuantBlock) void k_quantize_rows(QuantArgs a) {
     extern __shared__ uint32_t s_dyn_qr[];          // histogram window: a.win_n bins, 1 << a.hist_shift copies of each;
                                                     // then one word per thread for the lanes that count nothing
+                                                    // (REUSE: the given length table instead, u8[nbins])
     constexpr int kWaves = kQuantBlock / kWave;
     uint32_t *s_hist = s_dyn_qr;
     __shared__ uint64_t s_part64[kWaves];
@@ -353,7 +365,12 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize_rows(QuantArgs a) {
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = (uint32_t)lane_id();
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / kWave));
-    for (uint32_t i = tid; i < (a.win_n << a.hist_shift); i += kQuantBlock) s_hist[i] = 0;
+    uint8_t *s_len = reinterpret_cast<uint8_t *>(s_dyn_qr);
+    if (REUSE) {
+        for (uint32_t i = tid; i < a.nbins; i += kQuantBlock) s_len[i] = a.reuse_len[i];
+    } else {
+        for (uint32_t i = tid; i < (a.win_n << a.hist_shift); i += kQuantBlock) s_hist[i] = 0;
+    }
     __syncthreads();
 
     const uint32_t run = blockIdx.x * kWaves + wave;
@@ -362,8 +379,8 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize_rows(QuantArgs a) {
     SweepCounts cnt;
     uint32_t my_records = 0;
     if (row_hi > row_lo)
-        my_records = sweep_rows<VEC, NSEG, MULTI, FULLWIN, 0>(a, row_lo, row_hi, lane, s_hist, (a.win_n << a.hist_shift) + tid, s_recbuf[wave],
-                                                          reinterpret_cast<uint2 *>(a.stage) + (size_t)run * kQuantRecRun, kQuantRecRun, cnt);
+        my_records = sweep_rows<VEC, NSEG, MULTI, FULLWIN, 0, REUSE>(a, row_lo, row_hi, lane, s_hist, (a.win_n << a.hist_shift) + tid, s_recbuf[wave],
+                                                                 reinterpret_cast<uint2 *>(a.stage) + (size_t)run * kQuantRecRun, kQuantRecRun, cnt, s_len);
     // results: record count per run; records, non-zero inputs and verbatim records per workgroup (summed
     // up by the gather kernel; thousands of atomics on one counter would cost more than the sweep)
     const uint32_t nnz_wave = wave_sum<uint32_t>(cnt.nnz_lane);
@@ -384,6 +401,7 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize_rows(QuantArgs a) {
         for (int w = 0; w < kWaves; ++w) t += s_tot[w][tid];
         a.run_count[gridDim.x * kWaves + tid * gridDim.x + blockIdx.x] = t;   // three arrays of one entry per workgroup
     }
+    if (REUSE) return;                              // no histogram (uniform: every thread has passed the barrier above)
     uint32_t *part = a.hist_parts + (size_t)(blockIdx.x % a.hist_copies) * a.nbins;
     uint64_t counted = FULLWIN ? 0ull : (uint64_t)cnt.oow_lane;
     for (uint32_t i = tid; i < a.win_n; i += kQuantBlock) {
@@ -404,9 +422,10 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize_rows(QuantArgs a) {
 }
 
 // Moves the staged records of every run to their final, ordered place; same grid as k_quantize_rows.
-template <int VEC, int NSEG, bool MULTI>
+template <int VEC, int NSEG, bool MULTI, bool REUSE>
 __global__ __launch_bounds__(kQuantBlock) void k_gather_records(QuantArgs a) {
     constexpr int kWaves = kQuantBlock / kWave;
+    extern __shared__ uint32_t s_dyn_gr[];          // REUSE: the given length table, u8[nbins] (for runs that are swept again)
     __shared__ uint64_t s_part64[kWaves];
     __shared__ uint2 s_recbuf[kWaves][kQuantRecLds2];
     const uint32_t tid = threadIdx.x;
@@ -415,9 +434,14 @@ __global__ __launch_bounds__(kQuantBlock) void k_gather_records(QuantArgs a) {
     const uint32_t n_runs = gridDim.x * kWaves;
     const uint32_t run0 = blockIdx.x * kWaves;
 
+    uint8_t *s_len = reinterpret_cast<uint8_t *>(s_dyn_gr);
+    if (REUSE) {
+        for (uint32_t i = tid; i < a.nbins; i += kQuantBlock) s_len[i] = a.reuse_len[i];
+        __syncthreads();
+    }
     // histogram: one thread per bin adds up the partial histograms (codes outside the LDS window of
     // the quantise kernel were counted in hist directly)
-    for (uint32_t b = blockIdx.x * kQuantBlock + tid; b < a.nbins; b += gridDim.x * kQuantBlock) {
+    for (uint32_t b = blockIdx.x * kQuantBlock + tid; !REUSE && b < a.nbins; b += gridDim.x * kQuantBlock) {
         uint32_t v = 0;
         for (uint32_t c0 = 0; c0 < a.hist_copies; c0 += 8u) {               // eight loads in flight
             uint32_t p[8];
@@ -478,14 +502,16 @@ __global__ __launch_bounds__(kQuantBlock) void k_gather_records(QuantArgs a) {
         uint32_t row_lo, row_hi;
         run_rows(a, run, &row_lo, &row_hi);
         SweepCounts unused;
-        (void)sweep_rows<VEC, NSEG, MULTI, true, 1>(a, row_lo, row_hi, lane, nullptr, 0, s_recbuf[wave], dst, room, unused);
+        (void)sweep_rows<VEC, NSEG, MULTI, true, 1, REUSE>(a, row_lo, row_hi, lane, nullptr, 0, s_recbuf[wave], dst, room, unused, s_len);
     }
 }
 
-#define COMET_INST_QR(VEC, NSEG, MULTI)                                                   \
-    template __global__ void k_quantize_rows<VEC, NSEG, MULTI, true>(QuantArgs);          \
-    template __global__ void k_quantize_rows<VEC, NSEG, MULTI, false>(QuantArgs);         \
-    template __global__ void k_gather_records<VEC, NSEG, MULTI>(QuantArgs);
+#define COMET_INST_QR(VEC, NSEG, MULTI)                                                          \
+    template __global__ void k_quantize_rows<VEC, NSEG, MULTI, true, false>(QuantArgs);          \
+    template __global__ void k_quantize_rows<VEC, NSEG, MULTI, false, false>(QuantArgs);         \
+    template __global__ void k_quantize_rows<VEC, NSEG, MULTI, true, true>(QuantArgs);           \
+    template __global__ void k_gather_records<VEC, NSEG, MULTI, false>(QuantArgs);               \
+    template __global__ void k_gather_records<VEC, NSEG, MULTI, true>(QuantArgs);
 COMET_INST_QR(1, 1, true)
 COMET_INST_QR(1, 1, false)
 COMET_INST_QR(1, 2, false)

@@ -260,6 +260,84 @@ def test_widths_compress_and_decompress(comet, ctx, oracle, w):
         assert np.array_equal(y.cpu().numpy().view(np.uint32), want_x.view(np.uint32)), f"values differ, w={w} eb={eb}"
 
 
+# --------------------------------------------------------------------------
+# code book reuse
+# --------------------------------------------------------------------------
+
+def _reuse_case(comet, ctx, oracle, x_old, x_new, eb, nbins, chunk):
+    """Compress x_new with the length table of x_old's container on both sides and compare."""
+    ctx.comet_set_chunk_syms(chunk)
+    first, used_first = gpu_compress(ctx, comet, x_old, eb, nbins, chunk)
+    table = first[comet.HEADER_BYTES: comet.HEADER_BYTES + nbins]              # on the device, inside the older container
+    out = torch.empty(comet.comet_compress_bound(x_new.shape, nbins, chunk), dtype=torch.uint8, device="cuda")
+    try:
+        want = oracle.compress_with_lengths(x_new, eb, nbins, chunk, table.cpu().numpy())
+    except oracle.OracleError as e:
+        assert e.code == oracle.ERR_INVALID                       # an escape is needed and the table has no code word for it
+        with pytest.raises(comet.CometError) as ei:
+            ctx.comet_compress_with_codebook(dev(x_new), eb, nbins, table, out)
+        assert ei.value.code == comet.ERR_CODEBOOK
+        return None
+    used = ctx.comet_compress_with_codebook(dev(x_new), eb, nbins, table, out)
+    assert used == want.size
+    assert np.array_equal(out[:used].cpu().numpy(), want)
+    y = torch.empty(x_new.size, dtype=torch.float32, device="cuda")
+    ctx.comet_decompress(out, used, x_new.shape, y)
+    ctx.comet_sync()
+    assert np.array_equal(y.cpu().numpy().view(np.uint32), oracle.decompress(want).ravel().view(np.uint32))
+    return used
+
+
+@pytest.mark.parametrize("w", [7, 14, 28, 56, 63, 112, 200, 224, 333, 512])
+@pytest.mark.parametrize("eb,nbins,chunk", [(1e-2, 1024, 64), (2e-3, 64, 128), (1e-3, 4096, 256)])
+def test_compress_with_codebook_stale_table(comet, ctx, oracle, w, eb, nbins, chunk):
+    h = 9 if w > 64 else 31
+    x_old = synth.relu_blur((2, 3, h, w), seed=700 + w, blur=3, shift=-0.2)
+    x_new = synth.relu_blur((2, 3, h, w), seed=800 + w, blur=2, shift=0.0) * np.float32(1.5)
+    x_new.ravel()[3] = np.inf                                     # a verbatim value
+    x_new.ravel()[11] = -900.0                                    # residuals far outside the alphabet: escapes
+    x_old.ravel()[5] = 1000.0                                     # ... and in the older tensor, so that its table has a code word for them
+    assert _reuse_case(comet, ctx, oracle, x_old, x_new, eb, nbins, chunk) is not None
+
+
+def test_compress_with_codebook_own_table_is_compress(comet, ctx, oracle):
+    x = synth.relu_blur((2, 8, 56, 56), seed=91, blur=3, shift=-0.2)
+    a, used_a = gpu_compress(ctx, comet, x, 1e-2, 1024, 64)
+    table = a[comet.HEADER_BYTES: comet.HEADER_BYTES + 1024]
+    b = torch.empty_like(a)
+    used_b = ctx.comet_compress_with_codebook(dev(x), 1e-2, 1024, table, b)
+    assert used_b == used_a and torch.equal(a[:used_a], b[:used_b])
+
+
+def test_compress_with_codebook_errors(comet, ctx, oracle):
+    x = synth.relu_blur((1, 2, 20, 20), seed=92)
+    out = torch.empty(comet.comet_compress_bound(x.shape, 64, 64), dtype=torch.uint8, device="cuda")
+    ctx.comet_set_chunk_syms(64)
+    # smooth older tensor without any escape, newer one with outliers: no code word for the escape it needs
+    smooth = np.full((1, 2, 20, 20), 0.25, np.float32)
+    rough = x.copy(); rough.ravel()[7] = 50.0
+    assert _reuse_case(comet, ctx, oracle, smooth, rough, 1e-2, 64, 64) is None
+    for bad in ([2, 1] + [0] * 62, [1, 1, 1] + [0] * 61, [0] * 64, [1, 58] + [0] * 62):      # incomplete, over-full, empty, too long
+        t = dev(np.array(bad, np.uint8))
+        with pytest.raises(comet.CometError) as ei:
+            ctx.comet_compress_with_codebook(dev(x), 1e-2, 64, t, out)
+        assert ei.value.code == comet.ERR_CODEBOOK
+        with pytest.raises(oracle.OracleError):
+            oracle.compress_with_lengths(x, 1e-2, 64, 64, np.array(bad, np.uint8))
+    # the context still works afterwards
+    used = ctx.comet_compress(dev(x), 1e-2, 64, out)
+    assert np.array_equal(out[:used].cpu().numpy(), oracle.compress(x, 1e-2, 64, 64))
+    # limits of the entry point: alphabet and plane width
+    big = torch.zeros(16384, dtype=torch.uint8, device="cuda")
+    with pytest.raises(comet.CometError) as ei:
+        ctx.comet_compress_with_codebook(dev(x), 1e-2, 16384, big, torch.empty(1 << 20, dtype=torch.uint8, device="cuda"))
+    assert ei.value.code == comet.ERR_INVALID
+    wide = np.zeros((1, 1, 2, 600), np.float32)
+    with pytest.raises(comet.CometError) as ei:
+        ctx.comet_compress_with_codebook(dev(wide), 1e-2, 64, dev(np.array([1, 1] + [0] * 62, np.uint8)), out)
+    assert ei.value.code == comet.ERR_INVALID
+
+
 def test_roundtrip_config0_and_determinism(comet, ctx, oracle):
     e = synth.config0()[0]
     x = synth.make(e)
