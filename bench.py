@@ -120,7 +120,7 @@ def main() -> int:
     value = in_bytes / (dt / args.steps) / 1e9
 
     # compress-only and decompress-only rates (same launch configuration)
-    tc = td = None
+    tc = td = tr = None
     if not args.no_split:
         def timed(fn):
             torch.cuda.synchronize()
@@ -132,6 +132,18 @@ def main() -> int:
         tc = timed(compress_all)
         td = timed(decompress_all)
         sync_all()
+        # code book reuse: the same compression with the length tables of the containers just written (copied out,
+        # a table may not lie inside the buffer that is being written); same tensors, so the containers must not change
+        tables = [c[comet.HEADER_BYTES: comet.HEADER_BYTES + e["nbins"]].clone() for c, e in zip(conts, layers)]
+
+        def compress_reuse_all():
+            for i, (x, e, c) in enumerate(zip(xs, layers, conts)):
+                ctxs[owner[i]].comet_compress_with_codebook(x, e["eb"], e["nbins"], tables[i], c, stream=streams[owner[i]], sync=False)
+        compress_reuse_all()
+        sync_all()
+        tr = timed(compress_reuse_all)
+        sync_all()
+        assert [int(ctxs[0].comet_peek(c, c.numel()).total_bytes) for c in conts] == sizes, "code book reuse changed a container"
 
     # ---- per-kernel durations: K more steps with the library bracketing every launch with two HIP events on
     # the launch's stream.  This pass runs one call at a time (a synchronisation after each), so that a
@@ -196,6 +208,7 @@ def main() -> int:
                                           / HBM_PEAK_GBS, 4) for k in alg if kern[k]["launches"]})
     if tc is not None:
         path.update(compress_GBps=round(in_bytes / tc / 1e9, 1), decompress_GBps=round(in_bytes / td / 1e9, 1),
+                    compress_with_codebook_GBps=round(in_bytes / tr / 1e9, 1),
                     compress_frac_hbm_kernel_bytes=round((10.0 + b) * n_total / tc / 1e9 / HBM_PEAK_GBS, 4),
                     decompress_frac_hbm_kernel_bytes=round((8.0 + b) * n_total / td / 1e9 / HBM_PEAK_GBS, 4))
 
