@@ -72,6 +72,46 @@ def test_config1_full_size_in_bench_configuration(comet, oracle):
         c.close()
 
 
+def test_codebook_reuse_full_size(comet, oracle):
+    """Code book reuse at the benchmark's sizes.  With a tensor's own table the container must be the one
+    comet_compress writes, byte for byte (that one is checked against the oracle above); with the table of a
+    different tensor of the layer the values that come back must be the same and the size close (or the call
+    reports that the older table has no code word for the escapes the newer tensor needs).  The last case is
+    a tensor twice the size of the largest layer."""
+    layers = synth.config1(64)
+    cases = [(synth.make(e), e["eb"], e["nbins"]) for e in layers]
+    big = dict(layers[0]); big["shape"] = (64, 64, 160, 160)                  # 104.9 M elements
+    cases.append((synth.make(big), big["eb"], big["nbins"]))
+    ctx = comet.Context(max_elems=max(x.size for x, _, _ in cases), max_nbins=1024)
+    ctx.comet_set_chunk_syms(64)
+    for x, eb, nbins in cases:
+        xd = torch.from_numpy(x).cuda()
+        a = torch.empty(int(x.size * 4 * 0.6) // 16 * 16, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        used_a = ctx.comet_compress(xd, eb, nbins, a)
+        table = a[comet.HEADER_BYTES: comet.HEADER_BYTES + nbins].clone()
+        used_b = ctx.comet_compress_with_codebook(xd, eb, nbins, table, b)
+        assert used_b == used_a and torch.equal(a[:used_a], b[:used_b]), f"own table, {x.shape}"
+        # another tensor of the same kind (the batch reversed and scaled a little): stale table
+        xs = torch.flip(xd, dims=[0]) * 1.1
+        ya, yb = torch.empty_like(xs), torch.empty_like(xs)
+        used_c = ctx.comet_compress(xs, eb, nbins, a)
+        ctx.comet_decompress(a, used_c, xs.shape, ya)
+        try:
+            used_d = ctx.comet_compress_with_codebook(xs, eb, nbins, table, b)
+        except comet.CometError as e:
+            # new symbols, and the older tensor had no escape, so its table has no code word for one
+            assert e.code == comet.ERR_CODEBOOK and int(table[0]) == 0, f"stale table, {x.shape}"
+        else:
+            assert int(table[0]) != 0 or used_d > 0
+            ctx.comet_decompress(b, used_d, xs.shape, yb)
+            ctx.comet_sync()
+            assert torch.equal(ya.view(torch.int32), yb.view(torch.int32)), f"stale table, {x.shape}"
+            assert used_d >= used_c - 4096 and used_d < 1.1 * used_c
+        del xd, xs, ya, yb, a, b
+    ctx.close()
+
+
 def test_config2_full_size(comet, oracle):
     layers = synth.config2(32)
     ctx = comet.Context(max_elems=max(int(np.prod(e["shape"])) for e in layers), max_nbins=4096)
