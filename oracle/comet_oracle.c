@@ -696,3 +696,60 @@ int oracle_adapt_eb(double momentum_abs_mean, double loss_grad_mean, double nonz
     *eb_out = e;
     return ORC_OK;
 }
+
+/* ------------------------------------------------------------------------- */
+/* Controller glue (Sec. 3.1): a semi-online statistic and the active factor  */
+/* ------------------------------------------------------------------------- */
+/*
+ * "Average value of the momentum" and "average gradient of the loss" (Sec. 3.1)
+ * are taken as means of absolute values (a signed mean of either is about zero
+ * and would give a zero error bound): sum of |x[i]| in fp64, in index order,
+ * divided by n.
+ */
+int oracle_abs_mean(const float *x, uint64_t n, double *mean_out) {
+    if (!x || !mean_out || n == 0) return ORC_ERR_INVALID;
+    double sum = 0.0;
+    for (uint64_t i = 0; i < n; ++i) sum += fabs((double)x[i]);
+    *mean_out = sum / (double)n;
+    return ORC_OK;
+}
+
+/*
+ * Active factor W (Sec. 3.1): the semi-online parameters are collected, and the
+ * error bounds re-estimated, every W iterations; W starts at its default (1000).
+ * After a re-estimation the largest change of a layer's bound since the
+ * previous one is looked at, as a ratio >= 1 in either direction: above 2, W
+ * is halved (never below 1); otherwise the bounds have settled and W returns to
+ * its default.  state[0] = default, state[1] = W, state[2] = iterations since
+ * the last collection.
+ */
+int oracle_controller_init(uint32_t *state, uint32_t w_default) {
+    if (!state) return ORC_ERR_INVALID;
+    state[0] = w_default ? w_default : 1000u;
+    state[1] = state[0];
+    state[2] = 0;
+    return ORC_OK;
+}
+
+/* One iteration has passed; *collect = 1 in every W-th one. */
+int oracle_controller_tick(uint32_t *state, int *collect) {
+    if (!state || !collect || state[1] == 0) return ORC_ERR_INVALID;
+    state[2] += 1u;
+    *collect = 0;
+    if (state[2] >= state[1]) { state[2] = 0; *collect = 1; }
+    return ORC_OK;
+}
+
+int oracle_controller_update(uint32_t *state, const float *eb_old, const float *eb_new, uint32_t n_layers) {
+    if (!state || !eb_old || !eb_new || n_layers == 0 || state[1] == 0) return ORC_ERR_INVALID;
+    double worst = 1.0;
+    for (uint32_t l = 0; l < n_layers; ++l) {
+        double a = (double)eb_old[l], b = (double)eb_new[l];
+        if (!(a > 0.0) || !(b > 0.0) || !isfinite(a) || !isfinite(b)) return ORC_ERR_INVALID;
+        double ratio = a > b ? a / b : b / a;
+        if (ratio > worst) worst = ratio;
+    }
+    if (worst > 2.0) state[1] = state[1] > 1u ? state[1] / 2u : 1u;
+    else state[1] = state[0];
+    return ORC_OK;
+}

@@ -57,9 +57,14 @@ def lib():
         L.oracle_compress_with_lengths.argtypes = [f32p] + [C.c_uint32] * 4 + [C.c_float, C.c_uint32, C.c_uint32, u8p, u8p, C.c_uint64, u64p]
         L.oracle_decompress.argtypes = [u8p, C.c_uint64, f32p, C.c_uint64, u32p]
         L.oracle_adapt_eb.argtypes = [C.c_double, C.c_double, C.c_double, C.c_uint32, C.c_double, C.c_double, C.c_float, C.c_float, f32p]
+        L.oracle_abs_mean.argtypes = [f32p, C.c_uint64, C.POINTER(C.c_double)]
+        L.oracle_controller_init.argtypes = [u32p, C.c_uint32]
+        L.oracle_controller_tick.argtypes = [u32p, C.POINTER(C.c_int)]
+        L.oracle_controller_update.argtypes = [u32p, f32p, f32p, C.c_uint32]
         for name in ("oracle_prequant", "oracle_predict_code", "oracle_histogram", "oracle_code_lengths",
                      "oracle_canonical_codes", "oracle_encode", "oracle_decode", "oracle_reconstruct",
-                     "oracle_compress", "oracle_compress_with_lengths", "oracle_decompress", "oracle_adapt_eb"):
+                     "oracle_compress", "oracle_compress_with_lengths", "oracle_decompress", "oracle_adapt_eb",
+                     "oracle_abs_mean", "oracle_controller_init", "oracle_controller_tick", "oracle_controller_update"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -236,6 +241,36 @@ def adapt_eb(momentum_abs_mean, loss_grad_mean, nonzero_ratio, batch, a=0.32, si
     _chk(lib().oracle_adapt_eb(momentum_abs_mean, loss_grad_mean, nonzero_ratio, batch, a, sigma_frac,
                                C.c_float(eb_min), C.c_float(eb_max), C.byref(out)), "oracle_adapt_eb")
     return np.float32(out.value)
+
+
+def abs_mean(x) -> float:
+    x = _c(x, np.float32).ravel()
+    out = C.c_double()
+    _chk(lib().oracle_abs_mean(_p(x, C.c_float), x.size, C.byref(out)), "oracle_abs_mean")
+    return out.value
+
+
+class Controller:
+    """The active factor W (state kept in three uint32, as the C functions see it)."""
+
+    def __init__(self, w_default: int = 0):
+        self.state = np.zeros(3, np.uint32)
+        _chk(lib().oracle_controller_init(_p(self.state, C.c_uint32), w_default), "oracle_controller_init")
+
+    @property
+    def w(self) -> int:
+        return int(self.state[1])
+
+    def tick(self) -> bool:
+        c = C.c_int()
+        _chk(lib().oracle_controller_tick(_p(self.state, C.c_uint32), C.byref(c)), "oracle_controller_tick")
+        return bool(c.value)
+
+    def update(self, eb_old, eb_new) -> int:
+        a, b = _c(eb_old, np.float32).ravel(), _c(eb_new, np.float32).ravel()
+        assert a.size == b.size
+        _chk(lib().oracle_controller_update(_p(self.state, C.c_uint32), _p(a, C.c_float), _p(b, C.c_float), a.size), "oracle_controller_update")
+        return self.w
 
 
 # ---------------------------------------------------------------------------

@@ -620,6 +620,39 @@ def test_adapt_eb_closed_form(oracle):
 # the input generator (not part of the method, but the workloads rest on it)
 # --------------------------------------------------------------------------
 
+def test_abs_mean_closed_forms(oracle):
+    n = 10_001
+    assert oracle.abs_mean(np.full(n, -0.75, np.float32)) == 0.75
+    ramp = np.arange(-5000, 5001, dtype=np.float32)                   # |k| for k = -5000 .. 5000: sum = 5000 * 5001
+    assert oracle.abs_mean(ramp) == 5000.0 * 5001.0 / n
+    x = synth.relu_blur((2, 3, 17, 19), seed=3) - np.float32(0.1)
+    assert abs(oracle.abs_mean(x) - float(np.abs(x.astype(np.float64)).mean())) <= 1e-15
+    assert oracle.abs_mean(np.array([np.inf, 1.0], np.float32)) == np.inf
+    with pytest.raises(oracle.OracleError):
+        oracle.abs_mean(np.zeros(0, np.float32))
+
+
+def test_controller_hand_trace(oracle):
+    """W = 8 by default.  Collections fall on iterations 8, 16; a change above 2x halves W (4, 2, 1, 1), a
+    quiet check brings it back to 8."""
+    c = oracle.Controller(8)
+    hits = [i for i in range(1, 25) if c.tick()]
+    assert hits == [8, 16, 24] and c.w == 8
+    eb = np.array([1e-2, 1e-3, 5e-2], np.float32)
+    assert c.update(eb, eb * np.float32(1.9)) == 8                    # 1.9x: settled
+    assert c.update(eb, eb * np.array([1.0, 2.5, 1.0], np.float32)) == 4
+    assert c.update(eb, eb * np.array([0.3, 1.0, 1.0], np.float32)) == 2   # a drop by more than 2x counts as well
+    hits = [i for i in range(1, 9) if c.tick()]
+    assert hits == [2, 4, 6, 8]
+    assert c.update(eb, eb * np.float32(4.0)) == 1
+    assert c.update(eb, eb * np.float32(4.0)) == 1                    # never below one
+    assert c.update(eb, eb * np.float32(2.0)) == 8                    # exactly 2x does not exceed it
+    assert oracle.Controller().w == 1000
+    for bad in (np.array([0.0], np.float32), np.array([np.nan], np.float32), np.array([-1.0], np.float32)):
+        with pytest.raises(oracle.OracleError):
+            c.update(bad, np.array([1.0], np.float32))
+
+
 def test_synth_recipe_statistics():
     x = synth.make(synth.config0()[0])
     assert x.shape == (8, 64, 56, 56) and x.dtype == np.float32
