@@ -132,6 +132,25 @@ typedef struct { double a, sigma_frac; float eb_min, eb_max; } comet_adapt_cfg;
 void comet_adapt_defaults(comet_adapt_cfg *cfg);   /* 0.32, 0.01, 2^-100, 2^100 */
 int comet_adapt_eb(const comet_layer_stats *stats, const comet_adapt_cfg *cfg /* NULL = defaults */, float *eb_out /* host */);
 
+/* Semi-online statistic for comet_layer_stats (Sec. 3.1: the average of the momentum, the average
+ * gradient of the loss; taken as means of absolute values): mean of |dev_in[i]| over n fp32 values
+ * on the device, accumulated in fp64 by a fixed tree (the same result on every call).  Synchronises
+ * `stream`; *mean_out is host memory.  Non-finite inputs give a non-finite mean.  The fraction of
+ * non-zero activations comes with every compression (comet_info.nnz). */
+int comet_abs_mean(comet_ctx *ctx, const float *dev_in, uint64_t n, void *stream, double *mean_out);
+
+/* Active factor W (Sec. 3.1), a host-side counter: statistics are collected and the error bounds
+ * re-estimated every W iterations, W = 1000 by default; after a re-estimation, if the bound of any
+ * layer changed by more than 2x (in either direction) since the previous one, W is halved (not below
+ * 1), else it returns to its default. */
+typedef struct { uint32_t w_default, w, since; } comet_controller;
+int comet_controller_init(comet_controller *c, uint32_t w_default /* 0 = 1000 */);
+/* One training iteration has passed; *collect = 1 in every W-th call. */
+int comet_controller_tick(comet_controller *c, int *collect);
+/* After a re-estimation: eb_old / eb_new are host arrays of the n_layers bounds before and after
+ * (all finite and > 0, else COMET_ERR_INVALID). */
+int comet_controller_update(comet_controller *c, const float *eb_old, const float *eb_new, uint32_t n_layers);
+
 /* ---- stage-level entry points: each runs one step of the pipeline alone so
  * ---- that it can be compared with the reference implementation ------------ */
 

@@ -19,7 +19,8 @@ DEFAULT_CHUNK_SYMS = 64
 
 EXPORTS = (
     "comet_create", "comet_destroy", "comet_set_chunk_syms", "comet_compress_bound", "comet_compress", "comet_compress_with_codebook",
-    "comet_decompress", "comet_sync", "comet_peek", "comet_adapt_defaults", "comet_adapt_eb",
+    "comet_decompress", "comet_sync", "comet_peek", "comet_adapt_defaults", "comet_adapt_eb", "comet_abs_mean",
+    "comet_controller_init", "comet_controller_tick", "comet_controller_update",
     "comet_stage_quantize", "comet_stage_codebook", "comet_stage_encode", "comet_stage_decode",
     "comet_stage_reconstruct", "comet_profile_enable", "comet_profile_reset", "comet_profile_read", "comet_strerror",
 )
@@ -74,6 +75,10 @@ def lib():
         L.comet_compress_with_codebook.argtypes = [vp, vp, Shape, C.c_float, C.c_uint32, vp, vp, vp, u64, C.POINTER(u64)]
         L.comet_decompress.argtypes = [vp, vp, u64, Shape, vp, vp]
         L.comet_sync.argtypes = [vp, vp]
+        L.comet_abs_mean.argtypes = [vp, vp, u64, vp, C.POINTER(C.c_double)]
+        L.comet_controller_init.argtypes = [vp, C.c_uint32]
+        L.comet_controller_tick.argtypes = [vp, C.POINTER(C.c_int)]
+        L.comet_controller_update.argtypes = [vp, vp, vp, C.c_uint32]
         L.comet_peek.argtypes = [vp, vp, u64, vp, C.POINTER(Info)]
         L.comet_adapt_defaults.argtypes = [C.POINTER(AdaptCfg)]
         L.comet_adapt_defaults.restype = None
@@ -147,6 +152,35 @@ def comet_adapt_eb(momentum_abs_mean: float, loss_grad_mean: float, nonzero_rati
     return out.value
 
 
+class ControllerState(C.Structure):
+    _fields_ = [("w_default", C.c_uint32), ("w", C.c_uint32), ("since", C.c_uint32)]
+
+
+class Controller:
+    """The active factor W of the controller (host-side counter)."""
+
+    def __init__(self, w_default: int = 0):
+        self._s = ControllerState()
+        _chk(lib().comet_controller_init(C.byref(self._s), int(w_default)), "comet_controller_init")
+
+    @property
+    def w(self) -> int:
+        return int(self._s.w)
+
+    def comet_controller_tick(self) -> bool:
+        c = C.c_int()
+        _chk(lib().comet_controller_tick(C.byref(self._s), C.byref(c)), "comet_controller_tick")
+        return bool(c.value)
+
+    def comet_controller_update(self, eb_old, eb_new) -> int:
+        n = len(eb_old)
+        assert n == len(eb_new)
+        a = (C.c_float * n)(*[float(v) for v in eb_old])
+        b = (C.c_float * n)(*[float(v) for v in eb_new])
+        _chk(lib().comet_controller_update(C.byref(self._s), a, b, n), "comet_controller_update")
+        return self.w
+
+
 class Context:
     """Owns one comet_ctx (device workspace).  One per stream."""
 
@@ -193,6 +227,13 @@ class Context:
     def comet_decompress(self, container, nbytes: int, shape, out, stream=None) -> None:
         _chk(lib().comet_decompress(self._h, _ptr(container), int(nbytes), _shape(shape), _stream(stream), _ptr(out)),
              "comet_decompress")
+
+    def comet_abs_mean(self, x, stream=None) -> float:
+        """Mean of |x| over a contiguous fp32 device tensor (synchronises the stream)."""
+        assert str(x.dtype) == "torch.float32" and x.is_contiguous()
+        out = C.c_double()
+        _chk(lib().comet_abs_mean(self._h, _ptr(x), x.numel(), _stream(stream), C.byref(out)), "comet_abs_mean")
+        return out.value
 
     def comet_sync(self, stream=None) -> None:
         _chk(lib().comet_sync(self._h, _stream(stream)), "comet_sync")

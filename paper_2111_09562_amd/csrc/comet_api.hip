@@ -80,6 +80,7 @@ struct comet_ctx {
     DevState *host_state = nullptr;
     Header *host_hdr = nullptr;
     // occupancy (workgroups per CU) measured once
+    double *stats = nullptr;      // kStatsPartialMax partial sums and, behind them, the mean
     int occ_quant = 1;
     // optional per-kernel timing
     struct Timed { uint32_t id; hipEvent_t a, b; };
@@ -369,6 +370,7 @@ int comet_create(comet_ctx **out, uint64_t max_elems, uint32_t max_nbins) {
     c->zero_region = reinterpret_cast<uint8_t *>(&c->state->ctl);
     if ((e = hipMalloc((void **)&c->codes, align_up(2 * max_elems + 64, 256))) != hipSuccess) return fail(COMET_ERR_NOMEM);
     if ((e = hipMalloc((void **)&c->enc, 8ull * kMaxBins)) != hipSuccess) return fail(COMET_ERR_NOMEM);
+    if ((e = hipMalloc((void **)&c->stats, 8ull * (kStatsPartialMax + 1u))) != hipSuccess) return fail(COMET_ERR_NOMEM);
     c->max_runs = (uint64_t)c->num_cu * 4u * kQuantRunsPerSimd + 8u;
     if ((e = hipMalloc((void **)&c->rec_stage, c->max_runs * kQuantRecRun * 8ull)) != hipSuccess) return fail(COMET_ERR_NOMEM);
     if ((e = hipMalloc((void **)&c->run_count, 3ull * c->max_runs * 4ull)) != hipSuccess) return fail(COMET_ERR_NOMEM);
@@ -415,6 +417,7 @@ void comet_destroy(comet_ctx *c) {
     if (!c) return;
     if (c->state) (void)hipFree(c->state);
     if (c->codes) (void)hipFree(c->codes);
+    if (c->stats) (void)hipFree(c->stats);
     if (c->rec_stage) (void)hipFree(c->rec_stage);
     if (c->run_count) (void)hipFree(c->run_count);
     if (c->enc) (void)hipFree(c->enc);
@@ -665,6 +668,53 @@ int comet_adapt_eb(const comet_layer_stats *s, const comet_adapt_cfg *cfg_in, fl
     if (!(e >= cfg.eb_min)) e = cfg.eb_min;
     if (e > cfg.eb_max) e = cfg.eb_max;
     *eb_out = e;
+    return COMET_OK;
+}
+
+// ---------------------------------------------------------------------------
+// controller glue (Sec. 3.1)
+// ---------------------------------------------------------------------------
+
+int comet_abs_mean(comet_ctx *ctx, const float *dev_in, uint64_t n, void *stream, double *mean_out) {
+    if (!ctx || !dev_in || !mean_out || n == 0) return COMET_ERR_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    // a slice of at least 16384 values per workgroup, a few workgroups per CU at most
+    uint64_t grid = (n + 16383u) / 16384u;
+    const uint64_t cap = (uint64_t)ctx->num_cu * 8u < kStatsPartialMax ? (uint64_t)ctx->num_cu * 8u : kStatsPartialMax;
+    if (grid > cap) grid = cap;
+    hipLaunchKernelGGL(k_abs_sum, dim3((uint32_t)grid), dim3(kStatsBlock), 0, st, dev_in, n, ctx->stats);
+    hipLaunchKernelGGL(k_abs_mean_final, dim3(1), dim3(kWave), 0, st, ctx->stats, (uint32_t)grid, n, ctx->stats + kStatsPartialMax);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipMemcpyAsync(mean_out, ctx->stats + kStatsPartialMax, 8, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    return COMET_OK;
+}
+
+int comet_controller_init(comet_controller *c, uint32_t w_default) {
+    if (!c) return COMET_ERR_INVALID;
+    c->w_default = w_default ? w_default : 1000u;
+    c->w = c->w_default;
+    c->since = 0;
+    return COMET_OK;
+}
+
+int comet_controller_tick(comet_controller *c, int *collect) {
+    if (!c || !collect || c->w == 0) return COMET_ERR_INVALID;
+    *collect = 0;
+    if (++c->since >= c->w) { c->since = 0; *collect = 1; }
+    return COMET_OK;
+}
+
+int comet_controller_update(comet_controller *c, const float *eb_old, const float *eb_new, uint32_t n_layers) {
+    if (!c || !eb_old || !eb_new || n_layers == 0 || c->w == 0) return COMET_ERR_INVALID;
+    bool moved = false;                                   // some layer's bound changed by more than 2x, up or down
+    for (uint32_t l = 0; l < n_layers; ++l) {
+        const double a = (double)eb_old[l], b = (double)eb_new[l];
+        if (!(a > 0.0) || !(b > 0.0) || !std::isfinite(a) || !std::isfinite(b)) return COMET_ERR_INVALID;
+        if (a > 2.0 * b || b > 2.0 * a) moved = true;
+    }
+    if (moved) c->w = c->w > 1u ? c->w / 2u : 1u;
+    else c->w = c->w_default;
     return COMET_OK;
 }
 

@@ -52,6 +52,12 @@ template <int VEC, int NSEG, bool MULTI, bool FULLWIN, bool REUSE = false> __glo
 template <int VEC, int NSEG, bool MULTI, bool REUSE = false> __global__ void k_gather_records(QuantArgs a);
 constexpr uint32_t kQuantReuseMaxBins = 8192;   // largest alphabet whose length table the REUSE kernels keep in LDS
 
+// ---- statistics ---------------------------------------------------------------
+constexpr int kStatsBlock = 256;
+constexpr uint32_t kStatsPartialMax = 4096;     // workgroups of k_abs_sum at most (one partial sum each)
+__global__ void k_abs_sum(const float *x, uint64_t n, double *partial);
+__global__ void k_abs_mean_final(const double *partial, uint32_t n_partial, uint64_t n, double *mean_out);
+
 // ---- codebook -----------------------------------------------------------------
 constexpr int kBookBlock = 1024;
 constexpr uint32_t kBookLdsSyms = 2048;    // alphabets up to this size are built entirely in LDS

@@ -6,4 +6,5 @@
 #include "k_encode.hip"
 #include "k_reconstruct.hip"
 #include "k_decompress.hip"
+#include "k_stats.hip"
 #include "comet_api.hip"

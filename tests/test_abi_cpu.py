@@ -44,6 +44,29 @@ def test_adapt_eb_matches_oracle(comet, oracle):
         assert ei.value.code == comet.ERR_INVALID
 
 
+def test_controller_matches_oracle(comet, oracle):
+    """The active factor W through the C ABI against the oracle's, on random histories of bounds that
+    sometimes jump (both directions), sometimes hit a factor of exactly two and mostly stay put."""
+    rng = np.random.default_rng(11)
+    for w0 in (0, 1, 7, 64):
+        a, b = comet.Controller(w0), oracle.Controller(w0)
+        assert a.w == b.w == (w0 or 1000)
+        eb = rng.uniform(1e-4, 1e-1, 5).astype(np.float32)
+        for step in range(400):
+            assert a.comet_controller_tick() == b.tick()
+            if step % 3 == 0:
+                kind = rng.integers(0, 4)
+                f = {0: rng.uniform(0.9, 1.1, 5), 1: rng.uniform(0.2, 5.0, 5), 2: np.full(5, 2.0), 3: np.full(5, 0.5)}[int(kind)]
+                new = (eb * f.astype(np.float32)).astype(np.float32)
+                assert a.comet_controller_update(eb, new) == b.update(eb, new)
+                eb = new
+    c = comet.Controller(8)
+    for bad in ([0.0], [float("nan")], [-1.0], [float("inf")]):
+        with pytest.raises(comet.CometError) as ei:
+            c.comet_controller_update(bad, [1.0])
+        assert ei.value.code == comet.ERR_INVALID
+
+
 def test_compress_bound_matches_oracle(comet, oracle):
     for shape, nb, cs in [((8, 64, 56, 56), 1024, 128), ((1, 1, 1, 1), 4, 64), ((64, 2048, 7, 7), 65536, 256)]:
         assert comet.comet_compress_bound(shape, nb, cs) == oracle.compress_bound(shape, nb, cs)

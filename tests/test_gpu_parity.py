@@ -338,6 +338,23 @@ def test_compress_with_codebook_errors(comet, ctx, oracle):
     assert ei.value.code == comet.ERR_INVALID
 
 
+def test_abs_mean(comet, ctx, oracle):
+    """The controller's statistic.  Tolerance: both sides add non-negative fp64 terms, the oracle in index
+    order, the GPU in a fixed tree; each addition is within 2^-53 relative, so the two sums differ by at
+    most about n * 2^-53 relative (1.2e-10 at a million terms); 1e-9 is asked for.  Repeated calls must
+    give the same bits."""
+    for n, seed in [(1, 1), (63, 2), (16384, 3), (1_000_003, 4)]:
+        x = (synth.relu_laplace((1, 1, 1, n), seed) - np.float32(0.05)).ravel()
+        got = ctx.comet_abs_mean(dev(x))
+        want = oracle.abs_mean(x)
+        assert abs(got - want) <= 1e-9 * want
+        assert ctx.comet_abs_mean(dev(x)) == got
+    assert ctx.comet_abs_mean(dev(np.full(4099, -0.375, np.float32))) == 0.375
+    assert ctx.comet_abs_mean(dev(np.array([1.0, -np.inf, 2.0], np.float32))) == np.inf
+    with pytest.raises(comet.CometError):
+        ctx.comet_abs_mean(torch.empty(0, dtype=torch.float32, device="cuda"))
+
+
 def test_roundtrip_config0_and_determinism(comet, ctx, oracle):
     e = synth.config0()[0]
     x = synth.make(e)
