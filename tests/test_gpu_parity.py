@@ -355,6 +355,55 @@ def test_abs_mean(comet, ctx, oracle):
         ctx.comet_abs_mean(torch.empty(0, dtype=torch.float32, device="cuda"))
 
 
+def test_saved_activation_hook_on_a_toy_conv_stack(comet, oracle):
+    """Sec. 3.4 end to end on three random conv + ReLU layers: the forward result is untouched, every
+    activation saved for backward goes through libcomet (and comes back as the oracle says it must),
+    the weight gradients move with the error bound and the containers are smaller than the tensors."""
+    from paper_2111_09562_amd.autograd import saved_activations
+    torch.manual_seed(0)
+    net = torch.nn.Sequential(
+        torch.nn.Conv2d(8, 16, 3, padding=1), torch.nn.ReLU(),
+        torch.nn.Conv2d(16, 16, 3, padding=1), torch.nn.ReLU(),
+        torch.nn.Conv2d(16, 4, 3, padding=1)).cuda()
+    x = torch.randn(8, 8, 48, 48, device="cuda")
+
+    def run(hook):
+        net.zero_grad(set_to_none=True)
+        if hook is None:
+            loss = net(x).square().mean()
+        else:
+            with hook:
+                loss = net(x).square().mean()
+        loss.backward()
+        return float(loss.detach()), [p.grad.detach().clone() for p in net.parameters()]
+
+    base_loss, base = run(None)
+    c = comet.Context(max_elems=8 * 16 * 48 * 48, max_nbins=1024)
+    c.comet_set_chunk_syms(64)
+    errs = []
+    for eb in (5e-2, 5e-3):
+        hook = saved_activations(c, eb, nbins=1024, min_elems=1 << 12)
+        loss, grads = run(hook)
+        c.comet_sync()
+        assert loss == base_loss                                         # the forward pass does not see the codec
+        assert hook.packed >= 3 and hook.unpacked >= hook.packed         # the input and the two ReLU outputs at least
+        assert hook.bytes_kept < hook.bytes_in
+        errs.append(max(float((g - b).abs().max() / b.abs().max()) for g, b in zip(grads, base)))
+    assert errs[0] < 0.2 and errs[1] < 0.5 * errs[0]
+    # white noise at a tight bound does not fit 60 % of its size: the hook keeps such a tensor as it is
+    hook = saved_activations(c, 1e-5, min_elems=1 << 12)
+    assert hook._pack(x) is x and hook.kept_raw == 1
+    c.comet_sync()
+    # what comes back for one saved tensor is what the oracle decompresses from the oracle's container
+    hook = saved_activations(c, 1e-2, min_elems=1 << 12)
+    packed = hook._pack(x)
+    back = hook._unpack(packed)
+    c.comet_sync()
+    want = oracle.decompress(oracle.compress(x.cpu().numpy(), 1e-2, 1024, 64))
+    assert np.array_equal(back.cpu().numpy().view(np.uint32), want.view(np.uint32))
+    c.close()
+
+
 def test_roundtrip_config0_and_determinism(comet, ctx, oracle):
     e = synth.config0()[0]
     x = synth.make(e)
