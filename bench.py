@@ -43,6 +43,9 @@ def main() -> int:
                     help="contexts (each on its own stream) the layers are dealt to; the single-workgroup kernels of "
                          "one layer then overlap the streaming kernels of another")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--overlap-conv", action="store_true",
+                    help="also time the step next to fp32 3x3 convolutions of the five layers on a stream of their own "
+                         "(the paper's future work: hiding the codec behind the layers' compute); adds path.overlap_with_conv")
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer table to stderr")
     ap.add_argument("--no-split", action="store_true", help="skip the compress-only and decompress-only passes")
     ap.add_argument("--copy-probe", action="store_true",
@@ -145,6 +148,38 @@ def main() -> int:
         sync_all()
         assert [int(ctxs[0].comet_peek(c, c.numel()).total_bytes) for c in conts] == sizes, "code book reuse changed a container"
 
+    # ---- optional: the codec next to convolutions (one more stream, default priority) ----
+    overlap = None
+    if args.overlap_conv:
+        import torch.nn.functional as F
+        conv_stream = torch.cuda.Stream()
+        ws = [torch.randn(x.shape[1], x.shape[1], 3, 3, device="cuda") * 0.05 for x in xs]
+
+        def convs():
+            with torch.cuda.stream(conv_stream):
+                for x, w in zip(xs, ws):
+                    F.conv2d(x, w, padding=1)
+
+        def timed_pair(f, g, reps):
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(reps):
+                if f:
+                    f()
+                if g:
+                    g()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t) / reps
+        convs(); torch.cuda.synchronize()                     # algorithm selection happens here
+        reps = max(3, args.steps // 2)
+        t_conv = timed_pair(convs, None, reps)
+        t_codec = timed_pair(None, step, reps)
+        t_both = timed_pair(convs, step, reps)
+        overlap = dict(conv_ms=round(t_conv * 1e3, 3), codec_ms=round(t_codec * 1e3, 3), both_ms=round(t_both * 1e3, 3),
+                       hidden_frac_of_codec=round((t_conv + t_codec - t_both) / t_codec, 3),
+                       note="five fp32 3x3 convolutions (C -> C, padding 1) of the layers' shapes on one stream, the codec "
+                            "step on its streams; hidden = (conv + codec - both) / codec")
+
     # ---- per-kernel durations: K more steps with the library bracketing every launch with two HIP events on
     # the launch's stream.  This pass runs one call at a time (a synchronisation after each), so that a
     # kernel has the chip to itself and its duration says something about the kernel; the timed region above
@@ -206,6 +241,8 @@ def main() -> int:
                 # the same roofline arithmetic for every streaming kernel (mean launch, algorithmic bytes / duration)
                 kernel_frac_hbm={k: round(alg[k] * n_total / len(xs) / (kern[k]["total_ms"] / kern[k]["launches"] / 1e3) / 1e9
                                           / HBM_PEAK_GBS, 4) for k in alg if kern[k]["launches"]})
+    if overlap is not None:
+        path["overlap_with_conv"] = overlap
     if tc is not None:
         path.update(compress_GBps=round(in_bytes / tc / 1e9, 1), decompress_GBps=round(in_bytes / td / 1e9, 1),
                     compress_with_codebook_GBps=round(in_bytes / tr / 1e9, 1),
