@@ -193,6 +193,7 @@ __global__ void k_decode_only(ReconArgs a);
 constexpr int kDsWaves = 4;                           // wavefronts per workgroup, each working on its own
 constexpr int kDsBlock = kDsWaves * kWave;
 constexpr uint32_t kDsStageWords = 1536u;             // decode: Huffman words of 64 chunks per wavefront (LDS)
+constexpr uint32_t kDsStageBatch = 8u;                // decode: loads in flight per lane while those words are fetched
 constexpr uint32_t kDsMaxW = 512u;
 constexpr uint32_t kDsTailEntries = 1024u;            // decode: residuals of long codes kept in LDS
 constexpr uint32_t kScanListWords = 1024u;            // scan: escape list of a strip per wavefront (pairs) (LDS)

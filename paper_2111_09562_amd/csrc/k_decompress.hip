@@ -268,24 +268,49 @@ __global__ __launch_bounds__(kDsBlock) void k_decode_chunks(DsArgs a) {
 
     uint32_t *stage = s_dyn_ds + wave * kDsStageWords;
     const uint32_t n_groups = (n_chunks + kWave - 1u) / kWave;
-    for (uint32_t grp = blockIdx.x * kDsWaves + wave; grp < n_groups; grp += gridDim.x * kDsWaves) {
+    // The offsets of a group are fetched while the group before it is decoded: what is loaded after
+    // the residual stores of a group completes only once those stores have.
+    const uint32_t grp_step = gridDim.x * kDsWaves;
+    auto offsets_of = [&](uint32_t grp, uint32_t &o_lane, uint32_t &o_end) {
+        if (grp >= n_groups) return;
+        const uint32_t c_lo = grp * kWave;
+        const uint32_t c_hi = (n_chunks - c_lo < (uint32_t)kWave) ? n_chunks : c_lo + kWave;
+        o_lane = chunk_off[c_lo + lane < c_hi ? c_lo + lane : c_lo];
+        o_end = chunk_off[c_hi < n_chunks ? c_hi : c_lo];
+    };
+    uint32_t off_lane_next = 0, off_end_next = 0;
+    offsets_of(blockIdx.x * kDsWaves + wave, off_lane_next, off_end_next);
+    for (uint32_t grp = blockIdx.x * kDsWaves + wave; grp < n_groups; grp += grp_step) {
         const uint32_t c_lo = grp * kWave;
         const uint32_t c_hi = (n_chunks - c_lo < (uint32_t)kWave) ? n_chunks : c_lo + kWave;
         const uint32_t c = c_lo + lane;
 
-        // ---- the group's words: one round trip for the offsets, one for the words ----
-        uint32_t my_off = 0;
-        if (c < c_hi) my_off = chunk_off[c];
-        uint32_t w_end = (c_hi < n_chunks) ? chunk_off[c_hi] : payload_words;
+        // ---- the group's words, kDsStageBatch loads in flight per lane (a loop of load, wait, LDS
+        // write would spend one memory round trip per 64 words, as long as the decoding itself) ----
+        const uint32_t off_lane = off_lane_next, off_end = off_end_next;
+        const uint32_t my_off = (c < c_hi) ? off_lane : 0u;
+        uint32_t w_end = (c_hi < n_chunks) ? off_end : payload_words;
         uint32_t w_begin = (uint32_t)__builtin_amdgcn_readfirstlane((int)my_off);
         if (w_end > payload_words) w_end = payload_words;
         if (w_begin > w_end) w_begin = w_end;
         const uint32_t n_words = w_end - w_begin;
         const bool all_staged = n_words <= kDsStageWords;
         if (all_staged) {
-            for (uint32_t i = lane; i < n_words; i += kWave) stage[i] = payload[w_begin + i];
+            const __amdgpu_buffer_rsrc_t r_w = make_rsrc(payload + w_begin, n_words * 4u);   // loads past the end give 0
+            for (uint32_t i0 = 0; i0 < n_words; i0 += kDsStageBatch * kWave) {
+                uint32_t v[kDsStageBatch];
+#pragma unroll
+                for (uint32_t j = 0; j < kDsStageBatch; ++j)
+                    v[j] = __builtin_amdgcn_raw_buffer_load_b32(r_w, (int)((i0 + j * kWave + lane) * 4u), 0, 0);
+#pragma unroll
+                for (uint32_t j = 0; j < kDsStageBatch; ++j) {
+                    const uint32_t i = i0 + j * kWave + lane;
+                    if (i < n_words) stage[i] = v[j];
+                }
+            }
         }
         wave_lds_fence();
+        offsets_of(grp + grp_step, off_lane_next, off_end_next);
 
         // ---- decode, one lane per chunk ----
         if (c < c_hi && n_words) {
