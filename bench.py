@@ -123,7 +123,7 @@ def main() -> int:
     value = in_bytes / (dt / args.steps) / 1e9
 
     # compress-only and decompress-only rates (same launch configuration)
-    tc = td = tr = None
+    tc = td = tr = t16 = None
     if not args.no_split:
         def timed(fn):
             torch.cuda.synchronize()
@@ -147,6 +147,20 @@ def main() -> int:
         tr = timed(compress_reuse_all)
         sync_all()
         assert [int(ctxs[0].comet_peek(c, c.numel()).total_bytes) for c in conts] == sizes, "code book reuse changed a container"
+        # 16-bit activations: the same step on the set rounded to bfloat16 (half the input and output bytes)
+        xs16 = [x.to(torch.bfloat16) for x in xs]
+        outs16 = [torch.empty_like(x) for x in xs16]
+
+        def step16():
+            for i, (x, e, c) in enumerate(zip(xs16, layers, conts)):
+                ctxs[owner[i]].comet_compress_16(x, e["eb"], e["nbins"], c, stream=streams[owner[i]], sync=False)
+            for i in reversed(range(len(xs16))):
+                ctxs[owner[i]].comet_decompress_16(conts[i], conts[i].numel(), xs16[i].shape, outs16[i], stream=streams[owner[i]])
+        step16()
+        sync_all()
+        t16 = timed(step16)
+        sync_all()
+        del xs16, outs16
 
     # ---- optional: the codec next to convolutions (one more stream, default priority) ----
     overlap = None
@@ -246,6 +260,7 @@ def main() -> int:
     if tc is not None:
         path.update(compress_GBps=round(in_bytes / tc / 1e9, 1), decompress_GBps=round(in_bytes / td / 1e9, 1),
                     compress_with_codebook_GBps=round(in_bytes / tr / 1e9, 1),
+                    bf16_roundtrip_Gelem_per_s=round(n_total / t16 / 1e9, 2), fp32_roundtrip_Gelem_per_s=round(n_total / (dt / args.steps) / 1e9, 2),
                     compress_frac_hbm_kernel_bytes=round((10.0 + b) * n_total / tc / 1e9 / HBM_PEAK_GBS, 4),
                     decompress_frac_hbm_kernel_bytes=round((8.0 + b) * n_total / td / 1e9 / HBM_PEAK_GBS, 4))
 

@@ -115,6 +115,23 @@ int comet_compress_with_codebook(comet_ctx *ctx, const float *dev_in, comet_shap
 int comet_decompress(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_shape shape,
                      void *stream, float *dev_out);
 
+/* Activations held in 16 bits (mixed-precision training; the paper trains in fp32 and this goes
+ * beyond it).  The codec itself is the fp32 one of Sec. 4.1: comet_compress_16 widens every input
+ * element to fp32 as it is loaded (exact for both types) and from there on is comet_compress, so
+ * the container is byte for byte the one comet_compress writes for the widened tensor, and either
+ * decompression reads it.  comet_decompress_16 rounds the fp32 result of comet_decompress to the
+ * 16-bit type (nearest, ties to even; after the re-zero filter), so a value differs from the
+ * input by at most eb plus half a unit in the last place of the 16-bit type; verbatim values come
+ * back exactly.  dtype: COMET_F16 (IEEE binary16) or COMET_BF16 (bfloat16); dev_in / dev_out of
+ * the 16-bit type, 16-byte aligned, device memory, owned by the caller.  Limit: planes of at most
+ * 512 columns (COMET_ERR_INVALID otherwise).  Errors, `bytes_out`, streams: as for the fp32 calls. */
+#define COMET_F16 1
+#define COMET_BF16 2
+int comet_compress_16(comet_ctx *ctx, const void *dev_in, int dtype, comet_shape shape, float eb, uint32_t nbins,
+                      void *stream, void *dev_out, uint64_t capacity, uint64_t *bytes_out);
+int comet_decompress_16(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_shape shape, int dtype,
+                        void *stream, void *dev_out);
+
 /* Wait for `stream` and return (then clear) the first device-side error latched
  * in the context since the last synchronising call. */
 int comet_sync(comet_ctx *ctx, void *stream);

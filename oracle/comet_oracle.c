@@ -753,3 +753,73 @@ int oracle_controller_update(uint32_t *state, const float *eb_old, const float *
     else state[1] = state[0];
     return ORC_OK;
 }
+
+/* ------------------------------------------------------------------------- */
+/* 16-bit activations (an extension; the paper trains in fp32).  The codec     */
+/* stays the fp32 one of Sec. 4.1: a 16-bit input is widened to fp32 (exact    */
+/* for both formats) and compressed as such; a 16-bit output is the fp32       */
+/* reconstruction rounded to the nearest value of the format, ties to even.    */
+/* Both conversions are written out from the definition of a binary            */
+/* floating-point format with p significand bits (implicit bit included) and   */
+/* exponent range [emin, emax]: binary16 p = 11, emin = -14, emax = 15;        */
+/* bfloat16 p = 8, emin = -126, emax = 127.                                    */
+/* Pins: all 65536 binary16 patterns and random / edge fp32 values against     */
+/* numpy's float16, bfloat16 against torch's CPU conversion, hand cases        */
+/* (ties, overflow to infinity, subnormals, signed zero).                      */
+/* ------------------------------------------------------------------------- */
+static int fmt_of(int kind, int *p, int *emin, int *emax) {
+    if (kind == 1) { *p = 11; *emin = -14; *emax = 15; return 1; }
+    if (kind == 2) { *p = 8; *emin = -126; *emax = 127; return 1; }
+    return 0;
+}
+
+/* value of the 16-bit pattern h */
+static float widen_one(uint16_t h, int p, int emin, int emax) {
+    const int ebits = 16 - p;                       /* 1 sign bit + ebits + (p - 1) fraction bits */
+    const uint32_t frac = h & ((1u << (p - 1)) - 1u);
+    const uint32_t ef = ((uint32_t)h >> (p - 1)) & ((1u << ebits) - 1u);
+    const double sign = (h & 0x8000u) ? -1.0 : 1.0;
+    if (ef == (1u << ebits) - 1u) return (float)(frac ? NAN : sign * INFINITY);
+    if (ef == 0) return (float)(sign * ldexp((double)frac, emin - (p - 1)));           /* subnormal or zero */
+    (void)emax;
+    return (float)(sign * ldexp((double)(frac | (1u << (p - 1))), (int)ef - (emax) - (p - 1)));  /* bias = emax */
+}
+
+/* nearest value of the format to x, ties to even, as its bit pattern */
+static uint16_t narrow_one(float x, int p, int emin, int emax) {
+    const int ebits = 16 - p;
+    const uint16_t sign = signbit(x) ? 0x8000u : 0u;
+    const uint16_t inf = (uint16_t)(((1u << ebits) - 1u) << (p - 1));
+    if (isnan(x)) return (uint16_t)(sign | inf | (1u << (p - 2)));
+    double a = fabs((double)x);
+    if (isinf(x)) return (uint16_t)(sign | inf);
+    if (a == 0.0) return sign;
+    int e;
+    (void)frexp(a, &e);                             /* a = m * 2^e, 0.5 <= m < 1: the leading bit has weight 2^(e-1) */
+    int E = e - 1;
+    if (E < emin) E = emin;                         /* subnormal range: fixed spacing */
+    const double quantum = ldexp(1.0, E - (p - 1));
+    const double v = nearbyint(a / quantum) * quantum;   /* round-to-nearest-even is the default mode; the scaling is exact */
+    if (v >= ldexp(1.0, emax + 1)) return (uint16_t)(sign | inf);
+    if (v == 0.0) return sign;
+    (void)frexp(v, &e);
+    const int E2 = e - 1;
+    if (E2 < emin) return (uint16_t)(sign | (uint16_t)(v / ldexp(1.0, emin - (p - 1))));
+    const uint32_t sig = (uint32_t)(v / ldexp(1.0, E2 - (p - 1)));      /* p bits, leading one set */
+    return (uint16_t)(sign | (uint32_t)((E2 + emax) << (p - 1)) | (sig & ((1u << (p - 1)) - 1u)));
+}
+
+/* kind: 1 binary16, 2 bfloat16 */
+int oracle_widen16(const uint16_t *in, int kind, float *out, uint64_t n) {
+    int p, emin, emax;
+    if (!in || !out || !fmt_of(kind, &p, &emin, &emax)) return ORC_ERR_INVALID;
+    for (uint64_t i = 0; i < n; ++i) out[i] = widen_one(in[i], p, emin, emax);
+    return ORC_OK;
+}
+
+int oracle_narrow16(const float *in, int kind, uint16_t *out, uint64_t n) {
+    int p, emin, emax;
+    if (!in || !out || !fmt_of(kind, &p, &emin, &emax)) return ORC_ERR_INVALID;
+    for (uint64_t i = 0; i < n; ++i) out[i] = narrow_one(in[i], p, emin, emax);
+    return ORC_OK;
+}

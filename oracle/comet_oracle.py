@@ -61,6 +61,8 @@ def lib():
         L.oracle_controller_init.argtypes = [u32p, C.c_uint32]
         L.oracle_controller_tick.argtypes = [u32p, C.POINTER(C.c_int)]
         L.oracle_controller_update.argtypes = [u32p, f32p, f32p, C.c_uint32]
+        L.oracle_widen16.argtypes = [u16p, C.c_int, f32p, C.c_uint64]
+        L.oracle_narrow16.argtypes = [f32p, C.c_int, u16p, C.c_uint64]
         for name in ("oracle_prequant", "oracle_predict_code", "oracle_histogram", "oracle_code_lengths",
                      "oracle_canonical_codes", "oracle_encode", "oracle_decode", "oracle_reconstruct",
                      "oracle_compress", "oracle_compress_with_lengths", "oracle_decompress", "oracle_adapt_eb",
@@ -233,6 +235,35 @@ def decompress(container) -> np.ndarray:
     shp = (C.c_uint32 * 4)()
     _chk(lib().oracle_decompress(_p(buf, C.c_uint8), buf.size, _p(out, C.c_float), n_elems, shp), "oracle_decompress")
     return out.reshape(tuple(int(s) for s in shp))
+
+
+F16, BF16 = 1, 2
+
+
+def widen16(bits, kind: int) -> np.ndarray:
+    """fp32 values of 16-bit patterns (uint16 array; kind F16 or BF16)."""
+    b = _c(bits, np.uint16)
+    out = np.empty(b.shape, np.float32)
+    _chk(lib().oracle_widen16(_p(b, C.c_uint16), kind, _p(out, C.c_float), b.size), "oracle_widen16")
+    return out
+
+
+def narrow16(x, kind: int) -> np.ndarray:
+    """Nearest (ties to even) 16-bit patterns of fp32 values, as uint16."""
+    v = _c(x, np.float32)
+    out = np.empty(v.shape, np.uint16)
+    _chk(lib().oracle_narrow16(_p(v, C.c_float), kind, _p(out, C.c_uint16), v.size), "oracle_narrow16")
+    return out
+
+
+def compress_16(bits, kind: int, eb: float, nbins: int, chunk_syms: int, capacity: int | None = None) -> np.ndarray:
+    """Container of a 16-bit NCHW tensor given as uint16 patterns: the fp32 codec on the widened values."""
+    return compress(widen16(bits, kind), eb, nbins, chunk_syms, capacity)
+
+
+def decompress_16(container, kind: int) -> np.ndarray:
+    """The reconstruction rounded to the 16-bit format, as uint16 patterns."""
+    return narrow16(decompress(container), kind)
 
 
 def adapt_eb(momentum_abs_mean, loss_grad_mean, nonzero_ratio, batch, a=0.32, sigma_frac=0.01,

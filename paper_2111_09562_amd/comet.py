@@ -19,7 +19,7 @@ DEFAULT_CHUNK_SYMS = 64
 
 EXPORTS = (
     "comet_create", "comet_destroy", "comet_set_chunk_syms", "comet_compress_bound", "comet_compress", "comet_compress_with_codebook",
-    "comet_decompress", "comet_sync", "comet_peek", "comet_adapt_defaults", "comet_adapt_eb", "comet_abs_mean",
+    "comet_decompress", "comet_compress_16", "comet_decompress_16", "comet_sync", "comet_peek", "comet_adapt_defaults", "comet_adapt_eb", "comet_abs_mean",
     "comet_controller_init", "comet_controller_tick", "comet_controller_update",
     "comet_stage_quantize", "comet_stage_codebook", "comet_stage_encode", "comet_stage_decode",
     "comet_stage_reconstruct", "comet_profile_enable", "comet_profile_reset", "comet_profile_read", "comet_strerror",
@@ -74,6 +74,8 @@ def lib():
         L.comet_compress.argtypes = [vp, vp, Shape, C.c_float, C.c_uint32, vp, vp, u64, C.POINTER(u64)]
         L.comet_compress_with_codebook.argtypes = [vp, vp, Shape, C.c_float, C.c_uint32, vp, vp, vp, u64, C.POINTER(u64)]
         L.comet_decompress.argtypes = [vp, vp, u64, Shape, vp, vp]
+        L.comet_compress_16.argtypes = [vp, vp, C.c_int, Shape, C.c_float, C.c_uint32, vp, vp, u64, C.POINTER(u64)]
+        L.comet_decompress_16.argtypes = [vp, vp, u64, Shape, C.c_int, vp, vp]
         L.comet_sync.argtypes = [vp, vp]
         L.comet_abs_mean.argtypes = [vp, vp, u64, vp, C.POINTER(C.c_double)]
         L.comet_controller_init.argtypes = [vp, C.c_uint32]
@@ -107,6 +109,18 @@ def strerror(code: int) -> str:
 def _chk(rc: int, where: str) -> None:
     if rc != OK:
         raise CometError(rc, where)
+
+
+F16, BF16 = 1, 2
+
+
+def _dtype16(t) -> int:
+    name = str(t.dtype)
+    if name == "torch.float16":
+        return F16
+    if name == "torch.bfloat16":
+        return BF16
+    raise TypeError(f"float16 or bfloat16 tensor expected, got {name}")
 
 
 def _ptr(t):
@@ -227,6 +241,20 @@ class Context:
     def comet_decompress(self, container, nbytes: int, shape, out, stream=None) -> None:
         _chk(lib().comet_decompress(self._h, _ptr(container), int(nbytes), _shape(shape), _stream(stream), _ptr(out)),
              "comet_decompress")
+
+    def comet_compress_16(self, x, eb: float, nbins: int, out, stream=None, sync: bool = True):
+        """As comet_compress for a float16 or bfloat16 NCHW device tensor."""
+        assert x.dim() == 4
+        used = C.c_uint64()
+        rc = lib().comet_compress_16(self._h, _ptr(x), _dtype16(x), _shape(x.shape), C.c_float(eb), nbins, _stream(stream),
+                                     _ptr(out), out.numel() * out.element_size(), C.byref(used) if sync else None)
+        _chk(rc, "comet_compress_16")
+        return int(used.value) if sync else None
+
+    def comet_decompress_16(self, container, nbytes: int, shape, out, stream=None) -> None:
+        """As comet_decompress into a float16 or bfloat16 device tensor."""
+        _chk(lib().comet_decompress_16(self._h, _ptr(container), int(nbytes), _shape(shape), _dtype16(out), _stream(stream),
+                                       _ptr(out)), "comet_decompress_16")
 
     def comet_abs_mean(self, x, stream=None) -> float:
         """Mean of |x| over a contiguous fp32 device tensor (synchronises the stream)."""

@@ -189,12 +189,14 @@ void encode_geometry(const comet_ctx *ctx, uint64_t n_chunks, uint32_t *seg_chun
 // rows; otherwise the flat-tile kernel with `grid` segments of tiles.
 // vec: columns per lane of the row-walking kernel (2 if W is even and the input is 8-byte aligned).
 struct QuantGeom { bool rows; uint32_t grid, rows_per_wave, rows_per_step, vec; };
-QuantGeom quantize_geometry(const comet_ctx *ctx, comet_shape s, uint64_t n, const float *x);
+QuantGeom quantize_geometry(const comet_ctx *ctx, comet_shape s, uint64_t n, const void *x, uint32_t elem_bytes = 4);
 
 // reuse_len: code book reuse (device u8[nbins], row-walking kernel only); else null
-int launch_quantize(comet_ctx *ctx, const float *x, comet_shape s, uint64_t n, float eb, uint32_t nbins,
+// in_type: element type of x (0 fp32, COMET_F16, COMET_BF16; the 16-bit types: row-walking kernel only, no reuse)
+int launch_quantize(comet_ctx *ctx, const void *x, comet_shape s, uint64_t n, float eb, uint32_t nbins,
                     hipStream_t st, uint16_t *codes, uint32_t *hist, uint32_t *hist_parts, uint32_t *rec, uint64_t rec_cap,
-                    uint64_t *desc, const uint8_t *reuse_len = nullptr) {
+                    uint64_t *desc, const uint8_t *reuse_len = nullptr, int in_type = 0) {
+    if (in_type != 0 && (reuse_len || s.w > kQuantRowsMaxW)) return COMET_ERR_INVALID;
     QuantArgs a{};
     a.x = x; a.n = n;
     a.divW = make_fastdiv(s.w); a.divH = make_fastdiv(s.h);
@@ -204,7 +206,7 @@ int launch_quantize(comet_ctx *ctx, const float *x, comet_shape s, uint64_t n, f
     a.win_lo = (nbins - a.win_n) / 2u;
     a.n_tiles = (uint32_t)((n + kQuantTile - 1) / kQuantTile);
     a.codes = codes; a.hist = hist; a.rec = rec; a.rec_cap = rec_cap; a.desc = desc; a.ctl = &ctx->state->ctl;
-    const QuantGeom g = quantize_geometry(ctx, s, n, x);
+    const QuantGeom g = quantize_geometry(ctx, s, n, x, in_type ? 2u : 4u);
     const uint32_t grid = g.grid;
     if (g.rows) {
         a.rows_total = (uint32_t)((uint64_t)s.n * s.c * s.h);
@@ -218,17 +220,27 @@ int launch_quantize(comet_ctx *ctx, const float *x, comet_shape s, uint64_t n, f
         a.hist_shift = a.win_n <= 2048u ? 2u : 0u;            // four copies while they fit 32 KB
         const size_t lds = (((size_t)a.win_n << a.hist_shift) + kQuantBlock) * 4u;
         const bool full = a.win_n == nbins;
-#define COMET_LAUNCH_QR(VEC, NSEG, MULTI)                                                                              \
+#define COMET_LAUNCH_QR_IN(VEC, NSEG, MULTI, IN)                                                                       \
         do {                                                                                                           \
             {                                                                                                          \
                 TimedScope ts(ctx, st, COMET_KERNEL_QUANTIZE);                                                         \
-                if (reuse_len) hipLaunchKernelGGL((k_quantize_rows<VEC, NSEG, MULTI, true, true>), dim3(grid), dim3(kQuantBlock), lds_reuse, st, a); \
-                else if (full) hipLaunchKernelGGL((k_quantize_rows<VEC, NSEG, MULTI, true, false>), dim3(grid), dim3(kQuantBlock), lds, st, a);   \
-                else hipLaunchKernelGGL((k_quantize_rows<VEC, NSEG, MULTI, false, false>), dim3(grid), dim3(kQuantBlock), lds, st, a);       \
+                if (full) hipLaunchKernelGGL((k_quantize_rows<VEC, NSEG, MULTI, true, false, IN>), dim3(grid), dim3(kQuantBlock), lds, st, a);   \
+                else hipLaunchKernelGGL((k_quantize_rows<VEC, NSEG, MULTI, false, false, IN>), dim3(grid), dim3(kQuantBlock), lds, st, a);       \
             }                                                                                                          \
             TimedScope ts(ctx, st, COMET_KERNEL_GATHER);                                                               \
-            if (reuse_len) hipLaunchKernelGGL((k_gather_records<VEC, NSEG, MULTI, true>), dim3(grid), dim3(kQuantBlock), lds_reuse, st, a); \
-            else hipLaunchKernelGGL((k_gather_records<VEC, NSEG, MULTI, false>), dim3(grid), dim3(kQuantBlock), 0, st, a); \
+            hipLaunchKernelGGL((k_gather_records<VEC, NSEG, MULTI, false, IN>), dim3(grid), dim3(kQuantBlock), 0, st, a); \
+        } while (0)
+#define COMET_LAUNCH_QR(VEC, NSEG, MULTI)                                                                              \
+        do {                                                                                                           \
+            if (in_type == COMET_F16) { COMET_LAUNCH_QR_IN(VEC, NSEG, MULTI, 1); break; }                              \
+            if (in_type == COMET_BF16) { COMET_LAUNCH_QR_IN(VEC, NSEG, MULTI, 2); break; }                             \
+            if (!reuse_len) { COMET_LAUNCH_QR_IN(VEC, NSEG, MULTI, 0); break; }                                        \
+            {                                                                                                          \
+                TimedScope ts(ctx, st, COMET_KERNEL_QUANTIZE);                                                         \
+                hipLaunchKernelGGL((k_quantize_rows<VEC, NSEG, MULTI, true, true>), dim3(grid), dim3(kQuantBlock), lds_reuse, st, a); \
+            }                                                                                                          \
+            TimedScope ts(ctx, st, COMET_KERNEL_GATHER);                                                               \
+            hipLaunchKernelGGL((k_gather_records<VEC, NSEG, MULTI, true>), dim3(grid), dim3(kQuantBlock), lds_reuse, st, a); \
         } while (0)
         a.reuse_len = reuse_len;
         const size_t lds_reuse = ((size_t)nbins + 3u) & ~(size_t)3u;    // the given length table, one byte per bin
@@ -246,6 +258,7 @@ int launch_quantize(comet_ctx *ctx, const float *x, comet_shape s, uint64_t n, f
             else COMET_LAUNCH_QR(1, 8, false);
         }
 #undef COMET_LAUNCH_QR
+#undef COMET_LAUNCH_QR_IN
     } else {
         if (reuse_len) return COMET_ERR_INVALID;          // the flat-tile kernel has no code book reuse
         // one segment of consecutive tiles per workgroup, about as many workgroups as fit the chip at once
@@ -308,14 +321,14 @@ void encode_geometry(const comet_ctx *ctx, uint64_t n_chunks, uint32_t *seg_chun
     *n_seg = (uint32_t)((n_chunks + seg - 1) / seg);
 }
 
-QuantGeom quantize_geometry(const comet_ctx *ctx, comet_shape s, uint64_t n, const float *x) {
+QuantGeom quantize_geometry(const comet_ctx *ctx, comet_shape s, uint64_t n, const void *x, uint32_t elem_bytes) {
     QuantGeom g{};
     g.vec = 1;
     if (s.w <= kQuantRowsMaxW) {
         g.rows = true;
         const uint64_t rows_total = (uint64_t)s.n * s.c * s.h;
-        // two columns per lane: every row then starts at an even element, so pairs are 8-byte aligned
-        if ((s.w & 1u) == 0u && ((uintptr_t)x & 7u) == 0u) g.vec = 2;
+        // two columns per lane: every row then starts at an even element, so pairs are aligned to their size
+        if ((s.w & 1u) == 0u && ((uintptr_t)x & (2u * elem_bytes - 1u)) == 0u) g.vec = 2;
         const uint32_t lanes_per_row = s.w / g.vec;
         const uint32_t K = lanes_per_row <= 32u ? (uint32_t)kWave / lanes_per_row : 1u;
         g.rows_per_step = K;
@@ -446,24 +459,30 @@ uint64_t comet_compress_bound(comet_shape s, uint32_t nbins, uint32_t chunk_syms
 }
 
 namespace {
-int compress_impl(comet_ctx *ctx, const float *dev_in, comet_shape s, float eb, uint32_t nbins, const uint8_t *dev_len,
+int compress_impl(comet_ctx *ctx, const void *dev_in, int in_type, comet_shape s, float eb, uint32_t nbins, const uint8_t *dev_len,
                   void *stream, void *dev_out, uint64_t capacity, uint64_t *bytes_out);
 }
 
 int comet_compress(comet_ctx *ctx, const float *dev_in, comet_shape s, float eb, uint32_t nbins,
                    void *stream, void *dev_out, uint64_t capacity, uint64_t *bytes_out) {
-    return compress_impl(ctx, dev_in, s, eb, nbins, nullptr, stream, dev_out, capacity, bytes_out);
+    return compress_impl(ctx, dev_in, 0, s, eb, nbins, nullptr, stream, dev_out, capacity, bytes_out);
+}
+
+int comet_compress_16(comet_ctx *ctx, const void *dev_in, int dtype, comet_shape s, float eb, uint32_t nbins,
+                      void *stream, void *dev_out, uint64_t capacity, uint64_t *bytes_out) {
+    if ((dtype != COMET_F16 && dtype != COMET_BF16) || s.w > kQuantRowsMaxW) return COMET_ERR_INVALID;
+    return compress_impl(ctx, dev_in, dtype, s, eb, nbins, nullptr, stream, dev_out, capacity, bytes_out);
 }
 
 int comet_compress_with_codebook(comet_ctx *ctx, const float *dev_in, comet_shape s, float eb, uint32_t nbins,
                                  const uint8_t *dev_len, void *stream, void *dev_out, uint64_t capacity,
                                  uint64_t *bytes_out) {
     if (!dev_len || nbins > kQuantReuseMaxBins || s.w > kQuantRowsMaxW) return COMET_ERR_INVALID;
-    return compress_impl(ctx, dev_in, s, eb, nbins, dev_len, stream, dev_out, capacity, bytes_out);
+    return compress_impl(ctx, dev_in, 0, s, eb, nbins, dev_len, stream, dev_out, capacity, bytes_out);
 }
 
 namespace {
-int compress_impl(comet_ctx *ctx, const float *dev_in, comet_shape s, float eb, uint32_t nbins, const uint8_t *dev_len,
+int compress_impl(comet_ctx *ctx, const void *dev_in, int in_type, comet_shape s, float eb, uint32_t nbins, const uint8_t *dev_len,
                   void *stream, void *dev_out, uint64_t capacity, uint64_t *bytes_out) {
     uint64_t n;
     if (!ctx || !dev_in || !dev_out || !shape_elems(s, &n) || !valid_eb(eb) || !valid_nbins(nbins) ||
@@ -474,7 +493,7 @@ int compress_impl(comet_ctx *ctx, const float *dev_in, comet_shape s, float eb, 
     const uint64_t n_chunks = (n + S - 1) / S;
     uint32_t e_seg, e_grid;
     encode_geometry(ctx, n_chunks, &e_seg, &e_grid);
-    const uint64_t tiles_q = quantize_geometry(ctx, s, n, dev_in).grid;
+    const uint64_t tiles_q = quantize_geometry(ctx, s, n, dev_in, in_type ? 2u : 4u).grid;
     const uint64_t tiles_e = e_grid;
 
     Header proto{};
@@ -502,7 +521,7 @@ int compress_impl(comet_ctx *ctx, const float *dev_in, comet_shape s, float eb, 
     uint8_t *out = static_cast<uint8_t *>(dev_out);
 
     int rc = launch_quantize(ctx, dev_in, s, n, eb, nbins, st, ctx->codes, hist, hist_parts,
-                             reinterpret_cast<uint32_t *>(out + proto.off_outlier), (capacity - proto.off_outlier) / 8u, desc_q, dev_len);
+                             reinterpret_cast<uint32_t *>(out + proto.off_outlier), (capacity - proto.off_outlier) / 8u, desc_q, dev_len, in_type);
     if (rc) return rc;
     {
         BookArgs b{};
@@ -534,7 +553,21 @@ int compress_impl(comet_ctx *ctx, const float *dev_in, comet_shape s, float eb, 
 }
 }  // namespace
 
+namespace {
+int decompress_impl(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_shape s, void *stream, void *dev_out, int out_type);
+}
+
 int comet_decompress(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_shape s, void *stream, float *dev_out) {
+    return decompress_impl(ctx, dev_in, bytes, s, stream, dev_out, 0);
+}
+
+int comet_decompress_16(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_shape s, int dtype, void *stream, void *dev_out) {
+    if (dtype != COMET_F16 && dtype != COMET_BF16) return COMET_ERR_INVALID;
+    return decompress_impl(ctx, dev_in, bytes, s, stream, dev_out, dtype);
+}
+
+namespace {
+int decompress_impl(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_shape s, void *stream, void *dev_out, int out_type) {
     uint64_t n;
     if (!ctx || !dev_in || !dev_out || !shape_elems(s, &n) || s.w > kMaxW || ((uintptr_t)dev_in & 15u)) return COMET_ERR_INVALID;
     if (bytes < kHeaderBytes) return COMET_ERR_FORMAT;
@@ -545,6 +578,7 @@ int comet_decompress(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_s
     // lanes of a wavefront side by side in one row of the scan kernel (planes x columns)
     const uint32_t ppi = s.w <= 16u ? 4u * (16u / s.w) : (s.w <= 32u ? 2u : 1u);
     const bool fast_path = s.w <= kDsMaxW && (uint64_t)ppi * s.h * s.w < (1ull << 28);
+    if (out_type != 0 && !fast_path) return COMET_ERR_INVALID;       // 16-bit outputs: planes of at most kDsMaxW columns
     {
         TablesArgs t{};
         t.len = in + kHeaderBytes; t.nbins = 0; t.t = ctx->tables; t.keys = ctx->book.keys; t.ctl = &ctx->state->ctl;
@@ -596,17 +630,24 @@ int comet_decompress(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_s
         const size_t lds = (size_t)kDsWaves * kScanListWords * 4u;
         TimedScope ts(ctx, st, COMET_KERNEL_RECONSTRUCT);
         const dim3 g3((uint32_t)grid), b3(kDsBlock);
-        if (s.w <= 16u) hipLaunchKernelGGL((k_scan_store<1, 0>), g3, b3, lds, st, d);
-        else if (s.w <= 32u) hipLaunchKernelGGL((k_scan_store<1, 1>), g3, b3, lds, st, d);
-        else if (s.w <= 64u) hipLaunchKernelGGL((k_scan_store<1, 2>), g3, b3, lds, st, d);
-        else if (s.w <= 128u) hipLaunchKernelGGL((k_scan_store<2, 2>), g3, b3, lds, st, d);
-        else if (s.w <= 256u) hipLaunchKernelGGL((k_scan_store<4, 2>), g3, b3, lds, st, d);
-        else hipLaunchKernelGGL((k_scan_store<8, 2>), g3, b3, lds, st, d);
+#define COMET_LAUNCH_SCAN(OUT)                                                                        \
+        do {                                                                                          \
+            if (s.w <= 16u) hipLaunchKernelGGL((k_scan_store<1, 0, OUT>), g3, b3, lds, st, d);        \
+            else if (s.w <= 32u) hipLaunchKernelGGL((k_scan_store<1, 1, OUT>), g3, b3, lds, st, d);   \
+            else if (s.w <= 64u) hipLaunchKernelGGL((k_scan_store<1, 2, OUT>), g3, b3, lds, st, d);   \
+            else if (s.w <= 128u) hipLaunchKernelGGL((k_scan_store<2, 2, OUT>), g3, b3, lds, st, d);  \
+            else if (s.w <= 256u) hipLaunchKernelGGL((k_scan_store<4, 2, OUT>), g3, b3, lds, st, d);  \
+            else hipLaunchKernelGGL((k_scan_store<8, 2, OUT>), g3, b3, lds, st, d);                   \
+        } while (0)
+        if (out_type == COMET_F16) COMET_LAUNCH_SCAN(1);
+        else if (out_type == COMET_BF16) COMET_LAUNCH_SCAN(2);
+        else COMET_LAUNCH_SCAN(0);
+#undef COMET_LAUNCH_SCAN
     } else {
         ReconArgs a{};
         a.container = in; a.t = ctx->tables; a.n = n; a.planes = s.n * s.c; a.H = s.h; a.W = s.w; a.divW = make_fastdiv(s.w);
         a.planes_per_unit = g.planes_per_unit; a.tile_rows = g.tile_rows; a.n_units = g.n_units; a.pitch = g.pitch; a.use_carry = g.use_carry;
-        a.out = dev_out; a.ctl = &ctx->state->ctl;
+        a.out = static_cast<float *>(dev_out); a.ctl = &ctx->state->ctl;
         uint32_t grid = g.n_units;
         const uint32_t cap = (uint32_t)ctx->num_cu * 32u;
         if (grid > cap) grid = cap;
@@ -616,6 +657,7 @@ int comet_decompress(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_s
     HIP_TRY(hipGetLastError());
     return COMET_OK;
 }
+}  // namespace
 
 int comet_sync(comet_ctx *ctx, void *stream) {
     if (!ctx) return COMET_ERR_INVALID;

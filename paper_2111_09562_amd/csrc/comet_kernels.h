@@ -11,7 +11,7 @@ constexpr int kQuantTile = 4096;           // elements per tile: 256 lanes x 4 i
 constexpr uint32_t kHistWindowMax = 8192;  // LDS-private histogram bins per workgroup
 
 struct QuantArgs {
-    const float *x;
+    const void *x;             // fp32; the row-walking kernels also take IEEE half or bfloat16 (template parameter IN)
     uint64_t n;
     FastDiv divW, divH;        // plane width / height
     float r, ebx2, eb;
@@ -48,8 +48,10 @@ constexpr uint32_t kQuantHistPartsWords = 65536;    // all copies together have 
 // VEC adjacent columns per lane (2 needs an even W and 8-byte aligned input), NSEG segments of 64 lanes per row,
 // MULTI: several rows per step
 // REUSE: code book reuse: escapes follow the given length table, no histogram (FULLWIN is then true and unused)
-template <int VEC, int NSEG, bool MULTI, bool FULLWIN, bool REUSE = false> __global__ void k_quantize_rows(QuantArgs a);
-template <int VEC, int NSEG, bool MULTI, bool REUSE = false> __global__ void k_gather_records(QuantArgs a);
+// IN: element type of x (0 fp32, 1 IEEE half, 2 bfloat16; 16-bit inputs are widened exactly as they are loaded;
+// VEC = 2 then needs 4-byte aligned input)
+template <int VEC, int NSEG, bool MULTI, bool FULLWIN, bool REUSE = false, int IN = 0> __global__ void k_quantize_rows(QuantArgs a);
+template <int VEC, int NSEG, bool MULTI, bool REUSE = false, int IN = 0> __global__ void k_gather_records(QuantArgs a);
 constexpr uint32_t kQuantReuseMaxBins = 8192;   // largest alphabet whose length table the REUSE kernels keep in LDS
 
 // ---- statistics ---------------------------------------------------------------
@@ -207,10 +209,12 @@ struct DsArgs {
     uint32_t group_planes;     // scan kernel, planes of at most 32 columns: whole planes per unit of work (a multiple of the planes side by side in a wavefront)
     FastDiv divW;
     int16_t *resid;            // work buffer: one int16 residual per element (-32768 = escaped)
-    float *out;
+    void *out;                 // fp32, or IEEE half / bfloat16 (template parameter OUT of the scan kernel)
     Control *ctl;
 };
 __global__ void k_decode_chunks(DsArgs a);
-template <int NSEG, int MODE> __global__ void k_scan_store(DsArgs a);   // NSEG = ceil(W / 64) rounded up to 1, 2, 4, 8
+// NSEG = ceil(W / 64) rounded up to 1, 2, 4, 8; OUT: element type of the output (0 fp32, 1 IEEE half, 2 bfloat16:
+// the fp32 result rounded to nearest even)
+template <int NSEG, int MODE, int OUT = 0> __global__ void k_scan_store(DsArgs a);
 
 }  // namespace comet

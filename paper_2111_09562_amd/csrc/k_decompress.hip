@@ -216,6 +216,15 @@ __device__ inline uint32_t rec_lower_bound(const uint32_t *rec, uint32_t lo, uin
     return lo;
 }
 
+// Element type of the output: OUT = 0 fp32, 1 IEEE half, 2 bfloat16.  A 16-bit output is the fp32
+// result rounded to nearest, ties to even (NaN stays NaN).
+template <int OUT> __device__ inline uint32_t narrow16(float v) {
+    if (OUT == 1) return (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)v);
+    const uint32_t u = __float_as_uint(v);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x0040u;       // NaN: keep it one
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
 // buffer descriptor over [p, p + bytes): accesses at offsets >= bytes are dropped (loads give 0)
 __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
@@ -334,8 +343,9 @@ __global__ __launch_bounds__(kDsBlock) void k_decode_chunks(DsArgs a) {
 // NSEG: 64-column segments per row.  MODE (how the lanes of a wavefront map to columns):
 // 0: W <= 16, 16/W planes side by side in every 16-lane row; 1: W <= 32, one plane per 32-lane
 // half; 2: one plane, columns = lanes.
-template <int NSEG, int MODE>
+template <int NSEG, int MODE, int OUT>
 __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
+    constexpr uint32_t OS = OUT ? 2u : 4u;                   // bytes per output element
     extern __shared__ uint32_t s_dyn_ds[];                  // kDsWaves x kScanListWords: escape list of a wavefront's strip
 
     if (a.ctl->status & ST_FORMAT) return;
@@ -394,7 +404,7 @@ __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
             const uint32_t e0 = e_unit + row0 * W;
             const uint32_t e1 = group_mode ? e_unit + planes_here * P : e0 + rows * W;
             const __amdgpu_buffer_rsrc_t r_in = make_rsrc(a.resid + e0, (e1 - e0) * 2u);
-            const __amdgpu_buffer_rsrc_t r_out = make_rsrc(a.out + e0, (e1 - e0) * 4u);
+            const __amdgpu_buffer_rsrc_t r_out = make_rsrc(reinterpret_cast<char *>(a.out) + (size_t)e0 * OS, (e1 - e0) * OS);
 
             // ---- the strip's escaped residuals, compacted into LDS ----
             const uint32_t r_begin = rpos;
@@ -499,7 +509,8 @@ __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
                             q[s] = (int32_t)((uint32_t)q[s] + (uint32_t)rp);
                             float v = (float)q[s] * ebx2;
                             if (fabsf(v) <= eb) v = 0.0f;
-                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r_out, (int)(off * 4u), 0, 0);
+                            if (OUT == 0) __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r_out, (int)(off * 4u), 0, 0);
+                            else __builtin_amdgcn_raw_buffer_store_b16((unsigned short)narrow16<OUT>(v), r_out, (int)(off * 2u), 0, 0);
                         }
                     }
                 };
@@ -529,7 +540,10 @@ __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
                         float v = __uint_as_float(rec[2 * (size_t)k + 1]);
                         if (fabsf(v) <= eb) v = 0.0f;
                         const uint32_t e = key >> 1;
-                        if (e >= e0 && e < e1) a.out[e] = v;
+                        if (e >= e0 && e < e1) {
+                            if (OUT == 0) static_cast<float *>(a.out)[e] = v;
+                            else static_cast<unsigned short *>(a.out)[e] = (unsigned short)narrow16<OUT>(v);
+                        }
                     }
                 }
             }
@@ -538,11 +552,16 @@ __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
     }
 }
 
-template __global__ void k_scan_store<1, 0>(DsArgs);
-template __global__ void k_scan_store<1, 1>(DsArgs);
-template __global__ void k_scan_store<1, 2>(DsArgs);
-template __global__ void k_scan_store<2, 2>(DsArgs);
-template __global__ void k_scan_store<4, 2>(DsArgs);
-template __global__ void k_scan_store<8, 2>(DsArgs);
+#define COMET_INST_SCAN(OUT)                                         \
+    template __global__ void k_scan_store<1, 0, OUT>(DsArgs);        \
+    template __global__ void k_scan_store<1, 1, OUT>(DsArgs);        \
+    template __global__ void k_scan_store<1, 2, OUT>(DsArgs);        \
+    template __global__ void k_scan_store<2, 2, OUT>(DsArgs);        \
+    template __global__ void k_scan_store<4, 2, OUT>(DsArgs);        \
+    template __global__ void k_scan_store<8, 2, OUT>(DsArgs);
+COMET_INST_SCAN(0)
+COMET_INST_SCAN(1)
+COMET_INST_SCAN(2)
+#undef COMET_INST_SCAN
 
 }  // namespace comet

@@ -59,6 +59,7 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize(QuantArgs a) {
     const int wave = tid / kWave;
 
     COMET_DBG(a.ctl, 20);
+    const float *xin = static_cast<const float *>(a.x);      // this kernel takes fp32 only
     for (uint32_t i = tid; i < a.win_n; i += kQuantBlock) s_hist[i] = 0;
     // A workgroup owns one segment of consecutive tiles; segments are handed out by ticket so that
     // a segment is never started before the ones in front of it (the final offsets wait on them).
@@ -95,7 +96,7 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize(QuantArgs a) {
             const uint32_t nvalid = (n - i0 >= (uint32_t)kVec) ? (uint32_t)kVec : (n - i0);
             float xv[kVec];
 #pragma unroll
-            for (int j = 0; j < kVec; ++j) xv[j] = ((uint32_t)j < nvalid) ? a.x[i0 + j] : 0.0f;
+            for (int j = 0; j < kVec; ++j) xv[j] = ((uint32_t)j < nvalid) ? xin[i0 + j] : 0.0f;
             const uint32_t row0 = fdiv(i0, a.divW);
             uint32_t w = i0 - row0 * W;
             uint32_t h = row0 - fdiv(row0, a.divH) * H;
@@ -105,9 +106,9 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize(QuantArgs a) {
 #pragma unroll
             for (int k = 0; k < kVec + 1; ++k) {
                 const int64_t idx = (int64_t)i0 - (int64_t)W - 1 + k;
-                xu[k] = a.x[idx > 0 ? idx : 0];
+                xu[k] = xin[idx > 0 ? idx : 0];
             }
-            const float xl = a.x[i0 > 0 ? i0 - 1 : 0];
+            const float xl = xin[i0 > 0 ? i0 - 1 : 0];
             int32_t qu[kVec + 1];
 #pragma unroll
             for (int k = 0; k < kVec + 1; ++k) qu[k] = prequant(xu[k], a.r);
@@ -152,7 +153,7 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize(QuantArgs a) {
                 if (i0 + (uint32_t)j < n) {
                     const int32_t d = dres[it][j];
                     if (!(d > -radius && d < radius)) f |= 1u << j;
-                    const float x = a.x[i0 + j];
+                    const float x = xin[i0 + j];
                     if (needs_verbatim(x, prequant(x, a.r), a.r, a.ebx2, a.eb)) f |= 16u << j;
                 }
             }
@@ -179,7 +180,7 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize(QuantArgs a) {
                     if (!(f & ((type ? 16u : 1u) << j))) continue;
                     uint2 rc;
                     rc.x = 2u * (i0 + j) + (uint32_t)type;
-                    rc.y = type ? __float_as_uint(a.x[i0 + j]) : (uint32_t)dres[it][j];
+                    rc.y = type ? __float_as_uint(xin[i0 + j]) : (uint32_t)dres[it][j];
                     if (to_global) {
                         if (gbase + pos < a.rec_cap) reinterpret_cast<uint2 *>(a.rec)[gbase + pos] = rc;
                         else atomicOr(&a.ctl->status, (uint32_t)ST_CAPACITY);
@@ -204,11 +205,11 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize(QuantArgs a) {
 #pragma unroll
             for (int it = 0; it < kIter; ++it) {
                 const uint32_t i0 = start + (uint32_t)it * (kQuantBlock * kVec) + (uint32_t)tid * kVec;
-                const float4 v = *reinterpret_cast<const float4 *>(a.x + i0);
+                const float4 v = *reinterpret_cast<const float4 *>(xin + i0);
                 const float xv[kVec] = {v.x, v.y, v.z, v.w};
-                const float *up = a.x + (i0 - W - 1u);
+                const float *up = xin + (i0 - W - 1u);
                 const float xu[kVec + 1] = {up[0], up[1], up[2], up[3], up[4]};
-                const float xl = a.x[i0 - 1u];
+                const float xl = xin[i0 - 1u];
                 // position of the first element inside its plane; wj = where the row wraps inside my four
                 const uint32_t row0 = fdiv(i0, a.divW);
                 const uint32_t w0 = i0 - row0 * W;

@@ -57,6 +57,17 @@ __device__ inline __amdgpu_buffer_rsrc_t rows_rsrc(const void *p, uint32_t bytes
 constexpr uint32_t kOob = 0x80000000u;      // byte offset beyond every run
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
+// Element type of the input: IN = 0 fp32, 1 IEEE half, 2 bfloat16.  A 16-bit input is widened to
+// fp32 (exactly) as it is loaded; everything after the load is the fp32 pipeline.
+template <int IN> __device__ inline float widen16(uint32_t h) {
+    if (IN == 1) return (float)__builtin_bit_cast(_Float16, (unsigned short)h);
+    return __uint_as_float(h << 16);
+}
+template <int IN> __device__ inline float load_elem(const void *x, size_t i) {
+    if (IN == 0) return static_cast<const float *>(x)[i];
+    return widen16<IN>(static_cast<const unsigned short *>(x)[i]);
+}
+
 struct SweepCounts {
     uint32_t nnz_lane = 0;      // per lane: non-zero inputs
     uint32_t oow_lane = 0;      // per lane: codes counted straight into the global histogram
@@ -73,7 +84,7 @@ struct SweepCounts {
 // REUSE: code book reuse.  s_len (LDS, u8[nbins]) holds the code lengths the caller brought; a code
 // whose length is 0 becomes an escape, there is no histogram, and an escape that the table has no
 // code word for raises ST_CODEBOOK.
-template <int VEC, int NSEG, bool MULTI, bool FULLWIN, int PASS, bool REUSE = false>
+template <int VEC, int NSEG, bool MULTI, bool FULLWIN, int PASS, bool REUSE = false, int IN = 0>
 __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint32_t row_hi, uint32_t lane, uint32_t *s_hist,
                                       uint32_t hist_dummy, uint2 *s_buf, uint2 *rec_dst, uint64_t rec_cap, SweepCounts &cnt,
                                       const uint8_t *s_len = nullptr) {
@@ -87,7 +98,8 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
 
     const uint32_t e_lo = row_lo * W;
     const uint32_t n_el = (row_hi - row_lo) * W;
-    const __amdgpu_buffer_rsrc_t r_x = rows_rsrc(a.x + e_lo, n_el * 4u);
+    constexpr uint32_t ES = IN ? 2u : 4u;                          // bytes per input element
+    const __amdgpu_buffer_rsrc_t r_x = rows_rsrc(reinterpret_cast<const char *>(a.x) + (size_t)e_lo * ES, n_el * ES);
     const __amdgpu_buffer_rsrc_t r_c = rows_rsrc(a.codes + e_lo, n_el * 2u);
     const uint32_t K = MULTI ? a.rows_per_step : 1u;
     const uint32_t stride = MULTI ? K * W : W;                  // elements per step
@@ -125,15 +137,15 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
 #pragma unroll
         for (int v = 0; v < VEC; ++v) prev_rd[s][v] = 0;
     if (row_lo > 0) {
-        const float *above = a.x + (size_t)(e_lo - W);
+        const size_t above = (size_t)(e_lo - W);                  // first element of that row
 #pragma unroll
         for (int s = 0; s < NSEG; ++s) {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
                 const uint32_t w = (MULTI ? w0 : ((uint32_t)s * kWave + lane) * VEC) + (uint32_t)v;
                 const bool on = MULTI ? top_rows : (w < W);
-                const float xa = on ? above[w] : 0.0f;
-                const float xl = (on && w > 0) ? above[w - 1u] : 0.0f;
+                const float xa = on ? load_elem<IN>(a.x, above + w) : 0.0f;
+                const float xl = (on && w > 0) ? load_elem<IN>(a.x, above + w - 1u) : 0.0f;
                 const float ta = xa * a.r, tl = xl * a.r;
                 const int32_t qa = (fabsf(ta) < 16777216.0f) ? (int32_t)rintf(ta) : 0;
                 const int32_t ql = (fabsf(tl) < 16777216.0f) ? (int32_t)rintf(tl) : 0;
@@ -160,14 +172,20 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
             const uint32_t soff = t * stride;                              // uniform
 #pragma unroll
             for (int s = 0; s < NSEG; ++s) {
-                const int voff = FULL ? (int)(col[s] * 4u) : (int)((col[s] + soff) * 4u);
-                const int sof = FULL ? (int)(soff * 4u) : 0;
-                if (VEC == 2) {
+                const int voff = FULL ? (int)(col[s] * ES) : (int)((col[s] + soff) * ES);
+                const int sof = FULL ? (int)(soff * ES) : 0;
+                if (IN == 0 && VEC == 2) {
                     const u32x2 r = __builtin_amdgcn_raw_buffer_load_b64(r_x, voff, sof, 0);
                     xb[u][s][0] = __uint_as_float(r.x);
                     xb[u][s][VEC - 1] = __uint_as_float(r.y);
-                } else {
+                } else if (IN == 0) {
                     xb[u][s][0] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r_x, voff, sof, 0));
+                } else if (VEC == 2) {
+                    const uint32_t r = __builtin_amdgcn_raw_buffer_load_b32(r_x, voff, sof, 0);   // two 16-bit elements
+                    xb[u][s][0] = widen16<IN>(r & 0xffffu);
+                    xb[u][s][VEC - 1] = widen16<IN>(r >> 16);
+                } else {
+                    xb[u][s][0] = widen16<IN>((uint32_t)__builtin_amdgcn_raw_buffer_load_b16(r_x, voff, sof, 0));
                 }
             }
         }
@@ -351,7 +369,7 @@ __device__ inline void run_rows(const QuantArgs &a, uint32_t run, uint32_t *lo, 
 }  // namespace
 
 // One run per wavefront, kQuantBlock / 64 runs per workgroup.
-template <int VEC, int NSEG, bool MULTI, bool FULLWIN, bool REUSE>
+template <int VEC, int NSEG, bool MULTI, bool FULLWIN, bool REUSE, int IN>
 __global__ __launch_bounds__(kQuantBlock) void k_quantize_rows(QuantArgs a) {
     extern __shared__ uint32_t s_dyn_qr[];          // histogram window: a.win_n bins, 1 << a.hist_shift copies of each;
                                                     // then one word per thread for the lanes that count nothing
@@ -379,7 +397,7 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize_rows(QuantArgs a) {
     SweepCounts cnt;
     uint32_t my_records = 0;
     if (row_hi > row_lo)
-        my_records = sweep_rows<VEC, NSEG, MULTI, FULLWIN, 0, REUSE>(a, row_lo, row_hi, lane, s_hist, (a.win_n << a.hist_shift) + tid, s_recbuf[wave],
+        my_records = sweep_rows<VEC, NSEG, MULTI, FULLWIN, 0, REUSE, IN>(a, row_lo, row_hi, lane, s_hist, (a.win_n << a.hist_shift) + tid, s_recbuf[wave],
                                                                  reinterpret_cast<uint2 *>(a.stage) + (size_t)run * kQuantRecRun, kQuantRecRun, cnt, s_len);
     // results: record count per run; records, non-zero inputs and verbatim records per workgroup (summed
     // up by the gather kernel; thousands of atomics on one counter would cost more than the sweep)
@@ -422,7 +440,7 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize_rows(QuantArgs a) {
 }
 
 // Moves the staged records of every run to their final, ordered place; same grid as k_quantize_rows.
-template <int VEC, int NSEG, bool MULTI, bool REUSE>
+template <int VEC, int NSEG, bool MULTI, bool REUSE, int IN>
 __global__ __launch_bounds__(kQuantBlock) void k_gather_records(QuantArgs a) {
     constexpr int kWaves = kQuantBlock / kWave;
     extern __shared__ uint32_t s_dyn_gr[];          // REUSE: the given length table, u8[nbins] (for runs that are swept again)
@@ -502,16 +520,22 @@ __global__ __launch_bounds__(kQuantBlock) void k_gather_records(QuantArgs a) {
         uint32_t row_lo, row_hi;
         run_rows(a, run, &row_lo, &row_hi);
         SweepCounts unused;
-        (void)sweep_rows<VEC, NSEG, MULTI, true, 1, REUSE>(a, row_lo, row_hi, lane, nullptr, 0, s_recbuf[wave], dst, room, unused, s_len);
+        (void)sweep_rows<VEC, NSEG, MULTI, true, 1, REUSE, IN>(a, row_lo, row_hi, lane, nullptr, 0, s_recbuf[wave], dst, room, unused, s_len);
     }
 }
 
 #define COMET_INST_QR(VEC, NSEG, MULTI)                                                          \
-    template __global__ void k_quantize_rows<VEC, NSEG, MULTI, true, false>(QuantArgs);          \
-    template __global__ void k_quantize_rows<VEC, NSEG, MULTI, false, false>(QuantArgs);         \
-    template __global__ void k_quantize_rows<VEC, NSEG, MULTI, true, true>(QuantArgs);           \
-    template __global__ void k_gather_records<VEC, NSEG, MULTI, false>(QuantArgs);               \
-    template __global__ void k_gather_records<VEC, NSEG, MULTI, true>(QuantArgs);
+    template __global__ void k_quantize_rows<VEC, NSEG, MULTI, true, false, 0>(QuantArgs);       \
+    template __global__ void k_quantize_rows<VEC, NSEG, MULTI, false, false, 0>(QuantArgs);      \
+    template __global__ void k_quantize_rows<VEC, NSEG, MULTI, true, true, 0>(QuantArgs);        \
+    template __global__ void k_gather_records<VEC, NSEG, MULTI, false, 0>(QuantArgs);            \
+    template __global__ void k_gather_records<VEC, NSEG, MULTI, true, 0>(QuantArgs);             \
+    COMET_INST_QR16(VEC, NSEG, MULTI, 1)                                                         \
+    COMET_INST_QR16(VEC, NSEG, MULTI, 2)
+#define COMET_INST_QR16(VEC, NSEG, MULTI, IN)                                                    \
+    template __global__ void k_quantize_rows<VEC, NSEG, MULTI, true, false, IN>(QuantArgs);      \
+    template __global__ void k_quantize_rows<VEC, NSEG, MULTI, false, false, IN>(QuantArgs);     \
+    template __global__ void k_gather_records<VEC, NSEG, MULTI, false, IN>(QuantArgs);
 COMET_INST_QR(1, 1, true)
 COMET_INST_QR(1, 1, false)
 COMET_INST_QR(1, 2, false)
@@ -521,6 +545,7 @@ COMET_INST_QR(2, 1, true)
 COMET_INST_QR(2, 1, false)
 COMET_INST_QR(2, 2, false)
 COMET_INST_QR(2, 4, false)
+#undef COMET_INST_QR16
 #undef COMET_INST_QR
 
 }  // namespace comet

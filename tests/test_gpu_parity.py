@@ -261,6 +261,70 @@ def test_widths_compress_and_decompress(comet, ctx, oracle, w):
 
 
 # --------------------------------------------------------------------------
+# 16-bit activations
+# --------------------------------------------------------------------------
+def _bits16(t):
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+@pytest.mark.parametrize("w", [1, 7, 14, 28, 33, 56, 64, 66, 112, 130, 224, 257, 300, 512])
+@pytest.mark.parametrize("kind", ["float16", "bfloat16"])
+def test_16_bit_compress_and_decompress(comet, ctx, oracle, kind, w):
+    """comet_compress_16 writes the container of the widened tensor; comet_decompress_16 returns the
+    fp32 reconstruction rounded to the 16-bit type.  Bit-exact against the oracle, every lane mapping,
+    with infinities, NaN, negative zero, the largest finite values and subnormals among the inputs."""
+    tdt = getattr(torch, kind)
+    okind = oracle.F16 if kind == "float16" else oracle.BF16
+    h = 9 if w > 64 else 35
+    shape = (2, 3, h, w)
+    x32 = synth.relu_blur(shape, seed=900 + w, blur=3, shift=-0.2)
+    xt = torch.from_numpy(x32).to(tdt)
+    flat = xt.view(-1)
+    n = flat.numel()
+    flat[5 % n] = float("inf")
+    flat[n // 2] = float("-inf")
+    flat[n - 1] = float("nan")
+    flat[n // 3] = -0.0
+    flat[n // 5] = torch.finfo(tdt).max
+    flat[n // 7] = torch.finfo(tdt).tiny / 4                     # a subnormal of the 16-bit type
+    bits = _bits16(xt).reshape(shape)
+    xd = xt.cuda()
+    for eb, nbins, chunk in [(1e-2, 1024, 64), (2e-3, 16, 128), (1e-3, 4096, 256)]:
+        want = oracle.compress_16(bits, okind, eb, nbins, chunk)
+        ctx.comet_set_chunk_syms(chunk)
+        out = torch.zeros(int(want.size * 1.5) // 16 * 16 + 4096, dtype=torch.uint8, device="cuda")
+        used = ctx.comet_compress_16(xd, eb, nbins, out)
+        assert used == want.size
+        assert np.array_equal(out[:used].cpu().numpy(), want), f"container differs, {kind} w={w} eb={eb}"
+        # back in the 16-bit type ...
+        y = torch.empty(shape, dtype=tdt, device="cuda")
+        ctx.comet_decompress_16(out, used, shape, y)
+        ctx.comet_sync()
+        got, ref = _bits16(y).ravel(), oracle.decompress_16(want, okind).ravel()
+        nan = np.isnan(oracle.widen16(ref, okind))
+        assert np.array_equal(got[~nan], ref[~nan]), f"values differ, {kind} w={w} eb={eb}"
+        assert np.all(np.isnan(oracle.widen16(got[nan], okind)))
+        # ... and as fp32 (the container is an ordinary one)
+        y32 = torch.empty(shape, dtype=torch.float32, device="cuda")
+        ctx.comet_decompress(out, used, shape, y32)
+        ctx.comet_sync()
+        assert np.array_equal(y32.cpu().numpy().view(np.uint32).ravel(), oracle.decompress(want).view(np.uint32).ravel())
+    ctx.comet_set_chunk_syms(128)
+
+
+def test_16_bit_errors(comet, ctx):
+    x = torch.zeros((1, 1, 2, 513), dtype=torch.float16, device="cuda")
+    out = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(comet.CometError) as e:
+        ctx.comet_compress_16(x, 1e-2, 1024, out)                # wider than the row-walking kernels take
+    assert e.value.code == comet.ERR_INVALID
+    with pytest.raises(TypeError):
+        ctx.comet_compress_16(x.float(), 1e-2, 1024, out)
+    rc = comet.lib().comet_compress_16(ctx._h, x.data_ptr(), 3, comet._shape((1, 1, 2, 8)), 1e-2, 1024, None, out.data_ptr(), out.numel(), None)
+    assert rc == comet.ERR_INVALID                                # no such element type
+
+
+# --------------------------------------------------------------------------
 # code book reuse
 # --------------------------------------------------------------------------
 
@@ -401,6 +465,15 @@ def test_saved_activation_hook_on_a_toy_conv_stack(comet, oracle):
     c.comet_sync()
     want = oracle.decompress(oracle.compress(x.cpu().numpy(), 1e-2, 1024, 64))
     assert np.array_equal(back.cpu().numpy().view(np.uint32), want.view(np.uint32))
+    # a 16-bit activation comes back in its own type, as the oracle rounds it
+    for tdt, okind in ((torch.float16, oracle.F16), (torch.bfloat16, oracle.BF16)):
+        x16 = x.to(tdt)
+        back = hook._unpack(hook._pack(x16))
+        c.comet_sync()
+        assert back.dtype == tdt
+        bits = x16.view(torch.int16).cpu().numpy().view(np.uint16)
+        want = oracle.decompress_16(oracle.compress_16(bits, okind, 1e-2, 1024, 64), okind)
+        assert np.array_equal(back.view(torch.int16).cpu().numpy().view(np.uint16), want)
     c.close()
 
 

@@ -663,3 +663,70 @@ def test_synth_recipe_statistics():
     assert np.array_equal(x, again)
     lap = synth.relu_laplace((1, 2, 32, 32), seed=12)
     assert 0.4 < float((lap == 0).mean()) < 0.6
+
+
+# ---------------------------------------------------------------------------------------------
+# 16-bit activations: widening and rounding (an extension of the fp32 codec of Sec. 4.1)
+# ---------------------------------------------------------------------------------------------
+def _edge_floats():
+    rng = np.random.default_rng(99)
+    bits = rng.integers(0, 2**32, size=200000, dtype=np.uint64).astype(np.uint32)       # every exponent, NaNs included
+    vals = [0.0, -0.0, 1.0, -1.0, np.inf, -np.inf, np.nan, 65504.0, 65519.9, 65520.0, 65536.0, 6e-8, 5.96e-8, 2.98e-8, 2.9e-8,
+            6.1e-5, 3.3895e38, 3.4e38, 1e-40, 1e-45, 9.2e-41, 4.6e-41, 1.0 + 2.0**-11, 1.0 + 2.0**-10 + 2.0**-11,
+            1.0 + 2.0**-8, 1.0 + 2.0**-7 + 2.0**-8, 1.0 + 2.0**-8 + 2.0**-20]
+    return np.concatenate([bits.view(np.float32), np.array(vals, np.float32), rng.normal(0, 1, 50000).astype(np.float32)])
+
+
+def test_binary16_all_patterns_against_numpy(oracle):
+    bits = np.arange(65536, dtype=np.uint16)
+    got = oracle.widen16(bits, oracle.F16)
+    ref = bits.view(np.float16).astype(np.float32)                # library conversion, exact
+    assert np.array_equal(got.view(np.uint32)[~np.isnan(ref)], ref.view(np.uint32)[~np.isnan(ref)])
+    assert np.all(np.isnan(got[np.isnan(ref)]))
+    # widening then rounding gives every pattern back (NaNs stay NaN)
+    back = oracle.narrow16(got, oracle.F16)
+    ok = ~np.isnan(ref)
+    assert np.array_equal(back[ok], bits[ok]) and np.all(np.isnan(back[~ok].view(np.float16)))
+
+
+def test_round_to_binary16_against_numpy(oracle):
+    x = _edge_floats()
+    with np.errstate(over="ignore"):
+        ref = x.astype(np.float16).view(np.uint16)
+    got = oracle.narrow16(x, oracle.F16)
+    ok = ~np.isnan(x)
+    assert np.array_equal(got[ok], ref[ok])
+    assert np.all(np.isnan(got[~ok].view(np.float16)))
+
+
+def test_bfloat16_against_torch_and_hand_cases(oracle):
+    torch = pytest.importorskip("torch")
+    x = _edge_floats()
+    ref = torch.from_numpy(x.copy()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = oracle.narrow16(x, oracle.BF16)
+    ok = ~np.isnan(x)
+    assert np.array_equal(got[ok], ref[ok])
+    assert np.all(np.isnan(oracle.widen16(got[~ok], oracle.BF16)))
+    # widening = the pattern in the upper half of an fp32 word
+    bits = np.arange(65536, dtype=np.uint16)
+    wide = oracle.widen16(bits, oracle.BF16)
+    expect = (bits.astype(np.uint32) << 16).view(np.float32)
+    ok = ~np.isnan(expect)
+    assert np.array_equal(wide.view(np.uint32)[ok], expect.view(np.uint32)[ok]) and np.all(np.isnan(wide[~ok]))
+    # hand cases: 8 significand bits; ties go to the even neighbour; overflow rounds to infinity
+    hand = {1.0: 0x3F80, 1.0 + 2.0**-8: 0x3F80, 1.0 + 2.0**-8 + 2.0**-20: 0x3F81, 1.0 + 2.0**-7 + 2.0**-8: 0x3F82,
+            -0.0: 0x8000, 3.4e38: 0x7F80, 3.3895e38: 0x7F7F, float("inf"): 0x7F80, -2.5: 0xC020}
+    for v, b in hand.items():
+        assert int(oracle.narrow16(np.array([v], np.float32), oracle.BF16)[0]) == b, (v, hex(b))
+
+
+def test_16_bit_codec_is_the_fp32_codec_on_widened_values(oracle):
+    rng = np.random.default_rng(5)
+    x16 = rng.normal(0, 1, (2, 3, 9, 10)).astype(np.float16)
+    cont = oracle.compress_16(x16.view(np.uint16), oracle.F16, 1e-2, 256, 64)
+    assert bytes(cont) == bytes(oracle.compress(x16.astype(np.float32), 1e-2, 256, 64))
+    xh = oracle.widen16(oracle.decompress_16(cont, oracle.F16), oracle.F16)
+    # error bound plus half a unit in the last place of the 16-bit value
+    err = np.abs(xh.astype(np.float64) - x16.astype(np.float64))
+    ulp = np.spacing(np.abs(xh).astype(np.float16)).astype(np.float64)
+    assert np.all(err <= 1e-2 * (1 + 1e-6) + 0.5 * ulp)
