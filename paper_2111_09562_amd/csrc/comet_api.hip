@@ -575,8 +575,12 @@ int decompress_impl(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_sh
     ReconGeometry g;
     if (!recon_geometry(s, &g)) return COMET_ERR_INVALID;
     const uint8_t *in = static_cast<const uint8_t *>(dev_in);
-    // lanes of a wavefront side by side in one row of the scan kernel (planes x columns)
-    const uint32_t ppi = s.w <= 16u ? 4u * (16u / s.w) : (s.w <= 32u ? 2u : 1u);
+    // scan kernel: two adjacent columns per lane if every pair is aligned in the output; a row then takes
+    // lpr lanes, and ppi planes lie side by side in a wavefront
+    const uint32_t out_elem = out_type ? 2u : 4u;
+    const uint32_t vec = ((s.w & 1u) == 0u && ((uintptr_t)dev_out & (2u * out_elem - 1u)) == 0u) ? 2u : 1u;
+    const uint32_t lpr = s.w / vec;
+    const uint32_t ppi = lpr <= 16u ? 4u * (16u / lpr) : (lpr <= 32u ? 2u : 1u);
     const bool fast_path = s.w <= kDsMaxW && (uint64_t)ppi * s.h * s.w < (1ull << 28);
     if (out_type != 0 && !fast_path) return COMET_ERR_INVALID;       // 16-bit outputs: planes of at most kDsMaxW columns
     {
@@ -598,7 +602,7 @@ int decompress_impl(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_sh
         // fast path: Huffman decode into int16 residuals (the code buffer of the context doubles as
         // the work buffer), then scans and stores
         DsArgs d{};
-        d.container = in; d.t = ctx->tables; d.n = n; d.planes = s.n * s.c; d.H = s.h; d.W = s.w; d.divW = make_fastdiv(s.w);
+        d.container = in; d.t = ctx->tables; d.n = n; d.planes = s.n * s.c; d.H = s.h; d.W = s.w; d.divW = make_fastdiv(s.w); d.divL = make_fastdiv(lpr);
         d.resid = reinterpret_cast<int16_t *>(ctx->codes); d.out = dev_out; d.ctl = &ctx->state->ctl;
         {
             // groups of 64 chunks, one per wavefront at a time; the same number of groups for every
@@ -616,7 +620,7 @@ int decompress_impl(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_sh
         // side in a wavefront: about kScanStripElems elements, fewer if that leaves the chip short of wavefronts
         const uint64_t P = (uint64_t)s.h * s.w;
         uint64_t G = 1;
-        if (s.w <= 32u) {
+        if (lpr <= 32u) {
             uint64_t passes = kScanStripElems / (ppi * P);
             const uint64_t spread = (uint64_t)d.planes / ((uint64_t)ppi * ctx->num_cu * 32u);
             if (passes > spread) passes = spread;
@@ -630,14 +634,22 @@ int decompress_impl(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_sh
         const size_t lds = (size_t)kDsWaves * kScanListWords * 4u;
         TimedScope ts(ctx, st, COMET_KERNEL_RECONSTRUCT);
         const dim3 g3((uint32_t)grid), b3(kDsBlock);
-#define COMET_LAUNCH_SCAN(OUT)                                                                        \
-        do {                                                                                          \
-            if (s.w <= 16u) hipLaunchKernelGGL((k_scan_store<1, 0, OUT>), g3, b3, lds, st, d);        \
-            else if (s.w <= 32u) hipLaunchKernelGGL((k_scan_store<1, 1, OUT>), g3, b3, lds, st, d);   \
-            else if (s.w <= 64u) hipLaunchKernelGGL((k_scan_store<1, 2, OUT>), g3, b3, lds, st, d);   \
-            else if (s.w <= 128u) hipLaunchKernelGGL((k_scan_store<2, 2, OUT>), g3, b3, lds, st, d);  \
-            else if (s.w <= 256u) hipLaunchKernelGGL((k_scan_store<4, 2, OUT>), g3, b3, lds, st, d);  \
-            else hipLaunchKernelGGL((k_scan_store<8, 2, OUT>), g3, b3, lds, st, d);                   \
+#define COMET_LAUNCH_SCAN(OUT)                                                                           \
+        do {                                                                                             \
+            if (vec == 2u) {                                                                             \
+                if (lpr <= 16u) hipLaunchKernelGGL((k_scan_store<1, 0, OUT, 2>), g3, b3, lds, st, d);    \
+                else if (lpr <= 32u) hipLaunchKernelGGL((k_scan_store<1, 1, OUT, 2>), g3, b3, lds, st, d); \
+                else if (lpr <= 64u) hipLaunchKernelGGL((k_scan_store<1, 2, OUT, 2>), g3, b3, lds, st, d); \
+                else if (lpr <= 128u) hipLaunchKernelGGL((k_scan_store<2, 2, OUT, 2>), g3, b3, lds, st, d); \
+                else hipLaunchKernelGGL((k_scan_store<4, 2, OUT, 2>), g3, b3, lds, st, d);               \
+            } else {                                                                                     \
+                if (lpr <= 16u) hipLaunchKernelGGL((k_scan_store<1, 0, OUT, 1>), g3, b3, lds, st, d);    \
+                else if (lpr <= 32u) hipLaunchKernelGGL((k_scan_store<1, 1, OUT, 1>), g3, b3, lds, st, d); \
+                else if (lpr <= 64u) hipLaunchKernelGGL((k_scan_store<1, 2, OUT, 1>), g3, b3, lds, st, d); \
+                else if (lpr <= 128u) hipLaunchKernelGGL((k_scan_store<2, 2, OUT, 1>), g3, b3, lds, st, d); \
+                else if (lpr <= 256u) hipLaunchKernelGGL((k_scan_store<4, 2, OUT, 1>), g3, b3, lds, st, d); \
+                else hipLaunchKernelGGL((k_scan_store<8, 2, OUT, 1>), g3, b3, lds, st, d);               \
+            }                                                                                            \
         } while (0)
         if (out_type == COMET_F16) COMET_LAUNCH_SCAN(1);
         else if (out_type == COMET_BF16) COMET_LAUNCH_SCAN(2);

@@ -208,13 +208,15 @@ struct DsArgs {
     uint32_t planes, H, W;
     uint32_t group_planes;     // scan kernel, planes of at most 32 columns: whole planes per unit of work (a multiple of the planes side by side in a wavefront)
     FastDiv divW;
+    FastDiv divL;              // scan kernel: lanes per row (W / columns per lane)
     int16_t *resid;            // work buffer: one int16 residual per element (-32768 = escaped)
     void *out;                 // fp32, or IEEE half / bfloat16 (template parameter OUT of the scan kernel)
     Control *ctl;
 };
 __global__ void k_decode_chunks(DsArgs a);
-// NSEG = ceil(W / 64) rounded up to 1, 2, 4, 8; OUT: element type of the output (0 fp32, 1 IEEE half, 2 bfloat16:
+// NSEG = ceil(lanes per row / 64) rounded up to 1, 2, 4, 8; OUT: element type of the output (0 fp32, 1 IEEE half, 2 bfloat16:
 // the fp32 result rounded to nearest even)
-template <int NSEG, int MODE, int OUT = 0> __global__ void k_scan_store(DsArgs a);
+// VEC: adjacent columns per lane (2: even W, output aligned to two elements); the lane mapping follows W / VEC
+template <int NSEG, int MODE, int OUT = 0, int VEC = 1> __global__ void k_scan_store(DsArgs a);
 
 }  // namespace comet

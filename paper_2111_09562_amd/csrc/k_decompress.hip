@@ -34,6 +34,7 @@ namespace comet {
 namespace {
 
 constexpr int32_t kEscape = -32768;
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
 struct DsTables {
     const uint32_t *lut;        // LDS: the 11-bit table (u32 entries) or the compact 12-bit one (u16 entries)
@@ -340,10 +341,12 @@ __global__ __launch_bounds__(kDsBlock) void k_decode_chunks(DsArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// NSEG: 64-column segments per row.  MODE (how the lanes of a wavefront map to columns):
-// 0: W <= 16, 16/W planes side by side in every 16-lane row; 1: W <= 32, one plane per 32-lane
-// half; 2: one plane, columns = lanes.
-template <int NSEG, int MODE, int OUT>
+// VEC: adjacent columns per lane (2 needs an even W and an output aligned to two elements: one load
+// and one store per pair, half the memory instructions).  A row takes L = W / VEC lanes.
+// NSEG: 64-lane segments per row.  MODE (how the lanes of a wavefront map to rows):
+// 0: L <= 16, 16/L planes side by side in every 16-lane row; 1: L <= 32, one plane per 32-lane
+// half; 2: one plane, NSEG segments.
+template <int NSEG, int MODE, int OUT, int VEC>
 __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
     constexpr uint32_t OS = OUT ? 2u : 4u;                   // bytes per output element
     extern __shared__ uint32_t s_dyn_ds[];                  // kDsWaves x kScanListWords: escape list of a wavefront's strip
@@ -365,21 +368,22 @@ __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
 
     // ---- geometry ----
     const uint32_t W = a.W, H = a.H, P = H * W;
+    const uint32_t L = W / (uint32_t)VEC;                     // lanes per row
     constexpr bool group_mode = MODE != 2;                    // small planes: groups of whole planes; else one plane in strips of rows
-    // lanes -> (plane slot, column).  W <= 16: 16/W slots per 16-lane row; W <= 32: one slot per
-    // 32-lane half; wider: one slot, NSEG segments of 64 columns.
+    // lanes -> (plane slot, position in the row).  L <= 16: 16/L slots per 16-lane row; L <= 32: one
+    // slot per 32-lane half; wider: one slot, NSEG segments of 64 lanes.
     uint32_t ppi = 1, slot = 0, wl = lane;
     bool lane_on = true;
     uint64_t slot_mask = ~0ull;
     if (MODE == 0) {
-        const uint32_t spr = 16u / W, r = lane & 15u, sir = fdiv(r, a.divW);
-        wl = r - sir * W; lane_on = sir < spr; slot = (lane >> 4) * spr + sir; ppi = 4u * spr;
-        slot_mask = ((1ull << W) - 1ull) << ((lane & ~15u) + sir * W);
+        const uint32_t spr = 16u / L, r = lane & 15u, sir = fdiv(r, a.divL);
+        wl = r - sir * L; lane_on = sir < spr; slot = (lane >> 4) * spr + sir; ppi = 4u * spr;
+        slot_mask = ((1ull << L) - 1ull) << ((lane & ~15u) + sir * L);
     } else if (MODE == 1) {
-        wl = lane & 31u; lane_on = wl < W; slot = lane >> 5; ppi = 2u;
-        slot_mask = ((1ull << W) - 1ull) << (lane & 32u);
+        wl = lane & 31u; lane_on = wl < L; slot = lane >> 5; ppi = 2u;
+        slot_mask = ((1ull << L) - 1ull) << (lane & 32u);
     } else if (NSEG == 1) {
-        lane_on = lane < W;
+        lane_on = lane < L;
     }
     const uint64_t lt_mask = (1ull << lane) - 1ull;
     const uint32_t G = group_mode ? a.group_planes : 1u;      // planes per unit
@@ -395,9 +399,11 @@ __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
         const uint32_t e_unit = p0 * P;
         uint32_t rpos = 0;
         if (n_rec) rpos = rec_lower_bound(rec, 0, n_rec, 2u * e_unit, lane);
-        int32_t q[NSEG];
+        int32_t q[NSEG][VEC];                               // running column sums
 #pragma unroll
-        for (int s = 0; s < NSEG; ++s) q[s] = 0;
+        for (int s = 0; s < NSEG; ++s)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) q[s][v] = 0;
 
         for (uint32_t row0 = 0; row0 < H; row0 += R) {
             const uint32_t rows = (H - row0 < R) ? H - row0 : R;
@@ -441,7 +447,9 @@ __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
                 const uint32_t rel0 = group_mode ? pl * P : 0u;  // my plane's first element here, relative to e0
                 if (group_mode) {
 #pragma unroll
-                    for (int s = 0; s < NSEG; ++s) q[s] = 0;
+                    for (int s = 0; s < NSEG; ++s)
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) q[s][v] = 0;
                 }
                 // my cursor into the escape list: first entry at or after my plane's first element
                 uint32_t cur = 0;
@@ -451,15 +459,15 @@ __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
                     while (lo < hi) { const uint32_t mid = (lo + hi) >> 1; if (list[2 * mid] < target) lo = mid + 1; else hi = mid; }
                     cur = lo;
                 }
-                // element offsets (relative to e0) of my columns in row 0; 0x3fffffff for "no element":
+                // element offsets (relative to e0) of my first column in row 0; 0x3fffffff for "no element":
                 // times 2 or 4 it still lies beyond every strip, so the access is dropped
                 uint32_t col[NSEG];
 #pragma unroll
                 for (int s = 0; s < NSEG; ++s) {
                     const uint32_t w = wl + (uint32_t)s * kWave;
-                    col[s] = (slot_on && w < W) ? rel0 + w : 0x3fffffffu;
+                    col[s] = (slot_on && w < L) ? rel0 + w * (uint32_t)VEC : 0x3fffffffu;
                 }
-                auto fetch = [&](uint32_t h, int32_t (&d)[U][NSEG]) {
+                auto fetch = [&](uint32_t h, int32_t (&d)[U][NSEG][VEC]) {
 #pragma unroll
                     for (uint32_t u = 0; u < U; ++u) {
                         const uint32_t roff = (h + u < rows) ? (h + u) * W : 0x3fffffffu;    // wavefront-uniform
@@ -467,14 +475,20 @@ __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
                         for (int s = 0; s < NSEG; ++s) {
                             uint32_t off = col[s] + roff;
                             off = off > 0x3fffffffu ? 0x3fffffffu : off;
-                            d[u][s] = (int32_t)(int16_t)__builtin_amdgcn_raw_buffer_load_b16(r_in, (int)(off * 2u), 0, 0);
+                            if (VEC == 2) {
+                                const uint32_t two = __builtin_amdgcn_raw_buffer_load_b32(r_in, (int)(off * 2u), 0, 0);
+                                d[u][s][0] = (int32_t)(int16_t)(two & 0xffffu);
+                                d[u][s][VEC - 1] = (int32_t)two >> 16;
+                            } else {
+                                d[u][s][0] = (int32_t)(int16_t)__builtin_amdgcn_raw_buffer_load_b16(r_in, (int)(off * 2u), 0, 0);
+                            }
                         }
                     }
                 };
                 // The row loop exists twice: the usual one touches no memory besides the strip
                 // (so the compiler never has to drain the stores), the other one looks escaped
                 // residuals up in the container when their list did not fit LDS.
-                auto rows_of = [&](auto slow_tag, uint32_t h, int32_t (&dd)[U][NSEG]) {
+                auto rows_of = [&](auto slow_tag, uint32_t h, int32_t (&dd)[U][NSEG][VEC]) {
                     constexpr bool SLOW = decltype(slow_tag)::value;
 #pragma unroll
                     for (uint32_t u = 0; u < U; ++u) {
@@ -484,39 +498,78 @@ __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
                         for (int s = 0; s < NSEG; ++s) {
                             uint32_t off = col[s] + roff;
                             off = off > 0x3fffffffu ? 0x3fffffffu : off;
-                            int32_t d = dd[u][s];
-                            const bool is_esc = d == esc_marker;
-                            const uint64_t any_esc = wave_ballot(is_esc);
+                            int32_t d[VEC];
+                            bool is_esc[VEC];
+                            uint64_t em[VEC], any_esc = 0ull;
+#pragma unroll
+                            for (int v = 0; v < VEC; ++v) {
+                                d[v] = dd[u][s][v];
+                                is_esc[v] = d[v] == esc_marker;
+                                em[v] = wave_ballot(is_esc[v]);
+                                any_esc |= em[v];
+                            }
                             if (any_esc) {                            // wavefront-uniform
-                                const uint64_t m = any_esc & slot_mask;
-                                if (is_esc) {
-                                    if (SLOW) {
-                                        const uint32_t key = 2u * (e0 + off);
-                                        uint32_t lo = r_begin, hi = r_end;
-                                        while (lo < hi) { const uint32_t mid = (lo + hi) >> 1; if (rec[2 * (size_t)mid] < key) lo = mid + 1; else hi = mid; }
-                                        d = (lo < r_end && rec[2 * (size_t)lo] == key) ? (int32_t)rec[2 * (size_t)lo + 1] : 0;
-                                    } else {
-                                        uint32_t pos = cur + (uint32_t)__popcll(m & lt_mask);
-                                        if (pos >= kListCap) pos = kListCap - 1u;   // corrupt container only
-                                        d = n_esc ? (int32_t)list[2 * pos + 1] : 0;
+                                // escapes of my plane in element order: lanes, then a lane's columns
+                                uint32_t before = 0, all = 0;
+#pragma unroll
+                                for (int v = 0; v < VEC; ++v) {
+                                    const uint64_t m = em[v] & slot_mask;
+                                    before += (uint32_t)__popcll(m & lt_mask);
+                                    all += (uint32_t)__popcll(m);
+                                }
+                                uint32_t pos = cur + before;
+#pragma unroll
+                                for (int v = 0; v < VEC; ++v) {
+                                    if (is_esc[v]) {
+                                        if (SLOW) {
+                                            const uint32_t key = 2u * (e0 + off + (uint32_t)v);
+                                            uint32_t lo = r_begin, hi = r_end;
+                                            while (lo < hi) { const uint32_t mid = (lo + hi) >> 1; if (rec[2 * (size_t)mid] < key) lo = mid + 1; else hi = mid; }
+                                            d[v] = (lo < r_end && rec[2 * (size_t)lo] == key) ? (int32_t)rec[2 * (size_t)lo + 1] : 0;
+                                        } else {
+                                            const uint32_t at = pos < kListCap ? pos : kListCap - 1u;   // beyond: corrupt container only
+                                            d[v] = n_esc ? (int32_t)list[2 * at + 1] : 0;
+                                        }
+                                        ++pos;
                                     }
                                 }
-                                cur += (uint32_t)__popcll(m);
+                                cur += all;
                             }
-                            int32_t rp = run_scan<MODE>(d, wl, W);
-                            rp = (int32_t)((uint32_t)rp + (uint32_t)carry);
-                            if (NSEG > 1) carry = __builtin_amdgcn_readlane(rp, 63);
-                            q[s] = (int32_t)((uint32_t)q[s] + (uint32_t)rp);
-                            float v = (float)q[s] * ebx2;
-                            if (fabsf(v) <= eb) v = 0.0f;
-                            if (OUT == 0) __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r_out, (int)(off * 4u), 0, 0);
-                            else __builtin_amdgcn_raw_buffer_store_b16((unsigned short)narrow16<OUT>(v), r_out, (int)(off * 2u), 0, 0);
+                            // row prefix: the lane's own columns, then a scan of the lanes' sums
+                            int32_t mine = d[0];
+#pragma unroll
+                            for (int v = 1; v < VEC; ++v) mine = (int32_t)((uint32_t)mine + (uint32_t)d[v]);
+                            int32_t incl = run_scan<MODE>(mine, wl, L);
+                            incl = (int32_t)((uint32_t)incl + (uint32_t)carry);
+                            if (NSEG > 1) carry = __builtin_amdgcn_readlane(incl, 63);
+                            int32_t rp[VEC];
+                            rp[VEC - 1] = incl;
+#pragma unroll
+                            for (int v = VEC - 2; v >= 0; --v) rp[v] = (int32_t)((uint32_t)rp[v + 1] - (uint32_t)d[v + 1]);
+                            float val[VEC];
+#pragma unroll
+                            for (int v = 0; v < VEC; ++v) {
+                                q[s][v] = (int32_t)((uint32_t)q[s][v] + (uint32_t)rp[v]);
+                                val[v] = (float)q[s][v] * ebx2;
+                                if (fabsf(val[v]) <= eb) val[v] = 0.0f;
+                            }
+                            if (OUT == 0 && VEC == 2) {
+                                u32x2_t two;
+                                two.x = __float_as_uint(val[0]); two.y = __float_as_uint(val[VEC - 1]);
+                                __builtin_amdgcn_raw_buffer_store_b64(two, r_out, (int)(off * 4u), 0, 0);
+                            } else if (OUT == 0) {
+                                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val[0]), r_out, (int)(off * 4u), 0, 0);
+                            } else if (VEC == 2) {
+                                __builtin_amdgcn_raw_buffer_store_b32(narrow16<OUT>(val[0]) | (narrow16<OUT>(val[VEC - 1]) << 16), r_out, (int)(off * 2u), 0, 0);
+                            } else {
+                                __builtin_amdgcn_raw_buffer_store_b16((unsigned short)narrow16<OUT>(val[0]), r_out, (int)(off * 2u), 0, 0);
+                            }
                         }
                     }
                 };
                 auto row_loop = [&](auto slow_tag) {
                     // two batches of rows alternate: the loads of one are in flight while the other is scanned
-                    int32_t da[U][NSEG], db[U][NSEG];
+                    int32_t da[U][NSEG][VEC], db[U][NSEG][VEC];
                     fetch(0, da);
                     for (uint32_t h = 0; h < rows; h += 2u * U) {
                         fetch(h + U, db);
@@ -552,13 +605,18 @@ __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
     }
 }
 
-#define COMET_INST_SCAN(OUT)                                         \
-    template __global__ void k_scan_store<1, 0, OUT>(DsArgs);        \
-    template __global__ void k_scan_store<1, 1, OUT>(DsArgs);        \
-    template __global__ void k_scan_store<1, 2, OUT>(DsArgs);        \
-    template __global__ void k_scan_store<2, 2, OUT>(DsArgs);        \
-    template __global__ void k_scan_store<4, 2, OUT>(DsArgs);        \
-    template __global__ void k_scan_store<8, 2, OUT>(DsArgs);
+#define COMET_INST_SCAN(OUT)                                            \
+    template __global__ void k_scan_store<1, 0, OUT, 1>(DsArgs);        \
+    template __global__ void k_scan_store<1, 1, OUT, 1>(DsArgs);        \
+    template __global__ void k_scan_store<1, 2, OUT, 1>(DsArgs);        \
+    template __global__ void k_scan_store<2, 2, OUT, 1>(DsArgs);        \
+    template __global__ void k_scan_store<4, 2, OUT, 1>(DsArgs);        \
+    template __global__ void k_scan_store<8, 2, OUT, 1>(DsArgs);        \
+    template __global__ void k_scan_store<1, 0, OUT, 2>(DsArgs);        \
+    template __global__ void k_scan_store<1, 1, OUT, 2>(DsArgs);        \
+    template __global__ void k_scan_store<1, 2, OUT, 2>(DsArgs);        \
+    template __global__ void k_scan_store<2, 2, OUT, 2>(DsArgs);        \
+    template __global__ void k_scan_store<4, 2, OUT, 2>(DsArgs);
 COMET_INST_SCAN(0)
 COMET_INST_SCAN(1)
 COMET_INST_SCAN(2)
