@@ -262,7 +262,27 @@ def main() -> int:
                     compress_with_codebook_GBps=round(in_bytes / tr / 1e9, 1),
                     bf16_roundtrip_Gelem_per_s=round(n_total / t16 / 1e9, 2), fp32_roundtrip_Gelem_per_s=round(n_total / (dt / args.steps) / 1e9, 2),
                     compress_frac_hbm_kernel_bytes=round((10.0 + b) * n_total / tc / 1e9 / HBM_PEAK_GBS, 4),
-                    decompress_frac_hbm_kernel_bytes=round((8.0 + b) * n_total / td / 1e9 / HBM_PEAK_GBS, 4))
+                    decompress_frac_hbm_kernel_bytes=round((8.0 + b) * n_total / td / 1e9 / HBM_PEAK_GBS, 4),
+                    # floors of the method itself: two passes over the data to compress (8 + b bytes per element),
+                    # a fused decode + reconstruction to decompress (b + 4), and what a codec with a known code book
+                    # could reach (4 + b)
+                    compress_frac_hbm_two_pass_floor=round((8.0 + b) * n_total / tc / 1e9 / HBM_PEAK_GBS, 4),
+                    decompress_frac_hbm_fused_floor=round((4.0 + b) * n_total / td / 1e9 / HBM_PEAK_GBS, 4),
+                    compress_frac_hbm_ideal_floor=round((4.0 + b) * n_total / tc / 1e9 / HBM_PEAK_GBS, 4))
+        # what a plain device-to-device copy of the largest layer reaches in this run (read + write bytes)
+        big = max(range(len(xs)), key=lambda i: xs[i].numel())
+
+        def copy_big():
+            outs[big].copy_(xs[big])
+        copy_big()
+        t_copy = timed(copy_big)
+        copy_gbs = 8.0 * xs[big].numel() / t_copy / 1e9
+        path.update(copy_ceiling_GBps=round(copy_gbs, 1),
+                    roundtrip_frac_copy_ceiling_kernel_bytes=round((18.0 + 2 * b) * n_total / step_s / 1e9 / copy_gbs, 4),
+                    roundtrip_frac_copy_ceiling_min_bytes=round((8.0 + 2 * b) * n_total / step_s / 1e9 / copy_gbs, 4))
+    prop = torch.cuda.get_device_properties(0)
+    path["device"] = dict(name=prop.name, compute_units=prop.multi_processor_count, memory_GB=round(prop.total_memory / 2**30, 1),
+                          l2_MB_per_xcd=round(getattr(prop, "L2_cache_size", 0) / 2**20, 1))
 
     cpu = None
     if not args.no_cpu_baseline:
