@@ -28,8 +28,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per mean launch of a kernel, from the rocprofv3 counter runs summarised under profiles/
 # (FETCH_SIZE + WRITE_SIZE, scaled by the same counters on a plain copy of known size); filled in by hand
 # from those summaries, None where no counter run covers the kernel
-TRAFFIC = {"k_quantize_rows": 185733148, "k_encode_count": 61157629, "k_encode_pack": 88006750,
-           "k_decode_chunks": 103159584, "k_scan_store": 204335514}
+TRAFFIC = {"k_quantize_rows": 185741670, "k_encode_count": 61147458, "k_encode_pack": 87997985,
+           "k_decode_chunks": 103334462, "k_scan_store": 199320649}
 
 
 def main() -> int:
