@@ -390,8 +390,9 @@ __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
     const uint32_t R = group_mode ? H : (kScanStripElems / W ? kScanStripElems / W : 1u);   // rows per strip
     const uint32_t n_units = (a.planes + G - 1u) / G;
 
-    // rows handled per batch of loads: about eight row segments in flight per batch, two batches
-    constexpr uint32_t U = NSEG >= 8 ? 1u : 8u / NSEG;
+    // rows handled per batch of loads: four row segments in flight per batch, two batches (eight were
+    // slower on every layer: more registers, fewer wavefronts)
+    constexpr uint32_t U = NSEG >= 4 ? 1u : 4u / NSEG;
 
     for (uint32_t unit = blockIdx.x * kDsWaves + wave; unit < n_units; unit += gridDim.x * kDsWaves) {
         const uint32_t p0 = unit * G;
