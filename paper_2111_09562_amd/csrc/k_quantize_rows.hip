@@ -154,7 +154,7 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
         }
     }
 
-    constexpr uint32_t U = NSEG * VEC >= 8 ? 1u : 8u / (NSEG * VEC);   // steps per batch of loads
+    constexpr uint32_t U = NSEG * VEC >= 4 ? 1u : 4u / (NSEG * VEC);   // steps per batch of loads (eight values per lane and batch were slower)
     // FULL batches (every row of the batch inside the run) put the uniform part of the address
     // into the scalar offset of the buffer instruction and know a lane's validity up front;
     // the few steps at the end of a run go through the general form.
