@@ -312,6 +312,28 @@ def test_16_bit_compress_and_decompress(comet, ctx, oracle, kind, w):
     ctx.comet_set_chunk_syms(128)
 
 
+def test_decompress_into_an_output_that_is_not_pair_aligned(comet, ctx, oracle):
+    """Even widths take two columns per lane only if every pair of outputs is aligned; an output that
+    starts one element into an allocation goes the one-column way and gives the same bits."""
+    shape = (2, 3, 20, 56)
+    x = synth.relu_blur(shape, seed=77, blur=3, shift=-0.2)
+    want = oracle.compress(x, 1e-2, 1024, 64)
+    ref = oracle.decompress(want).ravel()
+    cont = dev(np.concatenate([want, np.zeros((-want.size) % 16, np.uint8)]))
+    n = x.size
+    y = torch.empty(n + 1, dtype=torch.float32, device="cuda")[1:]
+    assert y.data_ptr() % 8 == 4
+    ctx.comet_decompress(cont, want.size, shape, y)
+    ctx.comet_sync()
+    assert np.array_equal(y.cpu().numpy().view(np.uint32), ref.view(np.uint32))
+    for tdt, okind in ((torch.float16, oracle.F16), (torch.bfloat16, oracle.BF16)):
+        y16 = torch.empty(n + 1, dtype=tdt, device="cuda")[1:]
+        assert y16.data_ptr() % 4 == 2
+        ctx.comet_decompress_16(cont, want.size, shape, y16)
+        ctx.comet_sync()
+        assert np.array_equal(y16.view(torch.int16).cpu().numpy().view(np.uint16), oracle.narrow16(ref, okind))
+
+
 def test_16_bit_errors(comet, ctx):
     x = torch.zeros((1, 1, 2, 513), dtype=torch.float16, device="cuda")
     out = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
