@@ -2,7 +2,8 @@
 // up to 512 columns wide, as two streaming kernels:
 //
 //   k_decode_chunks: chunk-parallel Huffman decode.  A wavefront takes 64
-//     consecutive chunks, copies their words global -> LDS with coalesced loads and
+//     consecutive chunks, copies their words global -> LDS with coalesced loads (several
+//     in flight; the chunk offsets are fetched one group ahead) and
 //     decodes one chunk per lane: two words of the stream and a bit position per
 //     lane, one word of look-ahead from LDS so that no load sits on the critical
 //     path, and a look-up table whose entries already hold the residual (code -
@@ -15,11 +16,12 @@
 //     wavefront, so four wavefronts per SIMD share the issue slots.
 //
 //   k_scan_store: Lorenzo reconstruction -> dequantise -> verbatim values ->
-//     re-zero filter -> store.  Lanes are columns.  Row by row a wavefront reads 64
-//     residuals (buffer loads, several rows in flight), forms the row prefix with a
+//     re-zero filter -> store.  Lanes are columns (pairs of adjacent columns for even
+//     widths: one load and one store per pair).  Row by row a wavefront reads 64
+//     residuals or pairs (buffer loads, several rows in flight), forms the row prefix with a
 //     DPP scan (no LDS, no barrier), adds it to the per-column running sum held in
 //     a register (the column prefix), multiplies by 2*eb, applies the re-zero
-//     filter and stores fp32.  Loads and stores use buffer addressing: a lane that
+//     filter and stores fp32 (or rounds to a 16-bit type).  Loads and stores use buffer addressing: a lane that
 //     has no element gets an out-of-range offset, which the hardware ignores, so
 //     the loop has no divergent branches and the compiler can count the memory
 //     operations in flight instead of draining them.

@@ -18,6 +18,8 @@
 // free of divergent branches and several steps of loads are kept in flight.
 // The error-bound check is a cheap fp32 filter that falls back to the exact fp64
 // comparison only for elements within a few ulp of the bound.
+// The input may also be IEEE half or bfloat16: an element is widened to fp32 (exactly)
+// as it is loaded, and everything after the load is the fp32 pipeline.
 //
 // Outlier records (escapes and verbatim values) must end up in the container in
 // element order.  k_quantize_rows appends them, in order, to a staging area of
