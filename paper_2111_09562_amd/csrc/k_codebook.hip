@@ -137,40 +137,87 @@ __device__ inline uint32_t count_below_wave(const uint64_t *arr, uint32_t begin,
     return cnt;
 }
 
+// One round, control part: how many leaves (nl) and internal nodes (nn) are merged now.  Uniform
+// over the callers; WAVE: the counts are taken by a whole wavefront probing 64 entries per step.
+template <bool WAVE>
+__device__ inline void round_control(const uint64_t *keys, const uint64_t *iw, uint32_t m, uint32_t li, uint32_t ii, uint32_t ni,
+                                     uint32_t *nl_out, uint32_t *nn_out) {
+    const uint64_t inf = ~0ull;
+    const uint64_t a0 = li < m ? keys[li] >> 16 : inf, a1 = li + 1 < m ? keys[li + 1] >> 16 : inf;
+    const uint64_t b0 = ii < ni ? iw[ii] : inf, b1 = ii + 1 < ni ? iw[ii + 1] : inf;
+    uint64_t s0, s1;
+    if (a0 <= b0) { s0 = a0; s1 = (a1 <= b0) ? a1 : b0; }
+    else { s0 = b0; s1 = (a0 <= b1) ? a0 : b1; }
+    const uint64_t t = s0 + s1;
+    uint32_t nl = WAVE ? count_below_wave(keys, li, m, t, 16) : count_below(keys, li, m, t, 16, false);
+    uint32_t nn = WAVE ? count_below_wave(iw, ii, ni, t, 0) : count_below(iw, ii, ni, t, 0, false);
+    if ((nl + nn) & 1u) {
+        const uint64_t la = nl ? keys[li + nl - 1] >> 16 : 0, lb = nn ? iw[ii + nn - 1] : 0;
+        if (nn && (!nl || la <= lb)) --nn; else --nl;
+    }
+    *nl_out = nl; *nn_out = nn;
+}
+
+// One round, the items: lane `lane` of `nlanes` takes every nlanes-th of the nl + nn items.
+__device__ inline void round_items(const uint64_t *keys, uint64_t *iw, uint32_t *leaf_parent, uint32_t *int_parent,
+                                   uint32_t li, uint32_t ii, uint32_t ni, uint32_t nl, uint32_t nn, uint32_t lane, uint32_t nlanes) {
+    for (uint32_t idx = lane; idx < nl + nn; idx += nlanes) {
+        uint64_t w;
+        uint32_t rank;
+        if (idx < nl) {
+            w = keys[li + idx] >> 16;
+            rank = idx + count_below(iw, ii, ii + nn, w, 0, true);
+            leaf_parent[li + idx] = ni + (rank >> 1);
+        } else {
+            const uint32_t b = idx - nl;
+            w = iw[ii + b];
+            rank = b + count_below(keys, li, li + nl, w, 16, false);
+            int_parent[ii + b] = ni + (rank >> 1);
+        }
+        atomicAdd(reinterpret_cast<unsigned long long *>(&iw[ni + (rank >> 1)]), (unsigned long long)w);
+    }
+}
+
 template <bool WAVE, typename Sync>
 __device__ inline void huffman_rounds(const uint64_t *keys, uint64_t *iw, uint32_t *leaf_parent, uint32_t *int_parent,
                                       uint32_t m, uint32_t lane, uint32_t nlanes, Sync sync) {
     uint32_t li = 0, ii = 0, ni = 0;
     while ((m - li) + (ni - ii) > 1u) {
-        const uint64_t inf = ~0ull;
-        const uint64_t a0 = li < m ? keys[li] >> 16 : inf, a1 = li + 1 < m ? keys[li + 1] >> 16 : inf;
-        const uint64_t b0 = ii < ni ? iw[ii] : inf, b1 = ii + 1 < ni ? iw[ii + 1] : inf;
-        uint64_t s0, s1;
-        if (a0 <= b0) { s0 = a0; s1 = (a1 <= b0) ? a1 : b0; }
-        else { s0 = b0; s1 = (a0 <= b1) ? a0 : b1; }
-        const uint64_t t = s0 + s1;
-        uint32_t nl = WAVE ? count_below_wave(keys, li, m, t, 16) : count_below(keys, li, m, t, 16, false);
-        uint32_t nn = WAVE ? count_below_wave(iw, ii, ni, t, 0) : count_below(iw, ii, ni, t, 0, false);
-        if ((nl + nn) & 1u) {
-            const uint64_t la = nl ? keys[li + nl - 1] >> 16 : 0, lb = nn ? iw[ii + nn - 1] : 0;
-            if (nn && (!nl || la <= lb)) --nn; else --nl;
-        }
-        for (uint32_t idx = lane; idx < nl + nn; idx += nlanes) {
-            uint64_t w;
-            uint32_t rank;
-            if (idx < nl) {
-                w = keys[li + idx] >> 16;
-                rank = idx + count_below(iw, ii, ii + nn, w, 0, true);
-                leaf_parent[li + idx] = ni + (rank >> 1);
-            } else {
-                const uint32_t b = idx - nl;
-                w = iw[ii + b];
-                rank = b + count_below(keys, li, li + nl, w, 16, false);
-                int_parent[ii + b] = ni + (rank >> 1);
-            }
-            atomicAdd(reinterpret_cast<unsigned long long *>(&iw[ni + (rank >> 1)]), (unsigned long long)w);
-        }
+        uint32_t nl, nn;
+        round_control<WAVE>(keys, iw, m, li, ii, ni, &nl, &nn);
+        round_items(keys, iw, leaf_parent, int_parent, li, ii, ni, nl, nn, lane, nlanes);
         sync();
+        li += nl; ii += nn; ni += (nl + nn) >> 1;
+    }
+}
+
+// The same rounds for arrays in LDS, by the whole workgroup: the first wavefront runs the rounds of
+// at most 64 items alone (they need no workgroup barrier), a round with more items is shared by all
+// wavefronts (every wavefront works out the round's counts for itself).  state: three words of LDS.
+__device__ inline void huffman_rounds_lds(const uint64_t *keys, uint64_t *iw, uint32_t *leaf_parent, uint32_t *int_parent,
+                                          uint32_t m, uint32_t tid, uint32_t nthreads, uint32_t *state) {
+    uint32_t li = 0, ii = 0, ni = 0;
+    const uint32_t lane = tid & (uint32_t)(kWave - 1);
+    while (true) {
+        if (tid < (uint32_t)kWave) {
+            while ((m - li) + (ni - ii) > 1u) {
+                uint32_t nl, nn;
+                round_control<true>(keys, iw, m, li, ii, ni, &nl, &nn);
+                if (nl + nn > (uint32_t)kWave) break;            // a large round: everybody's
+                round_items(keys, iw, leaf_parent, int_parent, li, ii, ni, nl, nn, lane, (uint32_t)kWave);
+                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+                __builtin_amdgcn_wave_barrier();
+                li += nl; ii += nn; ni += (nl + nn) >> 1;
+            }
+            if (lane == 0) { state[0] = li; state[1] = ii; state[2] = ni; }
+        }
+        __syncthreads();
+        li = state[0]; ii = state[1]; ni = state[2];
+        if ((m - li) + (ni - ii) <= 1u) break;
+        uint32_t nl, nn;
+        round_control<true>(keys, iw, m, li, ii, ni, &nl, &nn);
+        round_items(keys, iw, leaf_parent, int_parent, li, ii, ni, nl, nn, tid, nthreads);
+        __syncthreads();
         li += nl; ii += nn; ni += (nl + nn) >> 1;
     }
 }
@@ -236,10 +283,7 @@ __device__ inline void codebook_body(const BookArgs &a, uint32_t m, uint64_t *ke
     // ---- 3. two-queue merge in rounds ----
     if (m >= 2) {
         if (LDS) {
-            // one wavefront: rounds are short, and a wavefront needs no workgroup barrier
-            if (tid < (uint32_t)kWave)
-                huffman_rounds<true>(keys, iw, leaf_parent, int_parent, m, tid, (uint32_t)kWave,
-                               [] { __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup"); __builtin_amdgcn_wave_barrier(); });
+            huffman_rounds_lds(keys, iw, leaf_parent, int_parent, m, tid, (uint32_t)kBookBlock, s_part);
         } else {
             huffman_rounds<false>(keys, iw, leaf_parent, int_parent, m, tid, (uint32_t)kBookBlock, [] { __syncthreads(); });
         }
