@@ -191,20 +191,70 @@ __device__ inline void huffman_rounds(const uint64_t *keys, uint64_t *iw, uint32
     }
 }
 
-// The same rounds for arrays in LDS, by the whole workgroup: the first wavefront runs the rounds of
-// at most 64 items alone (they need no workgroup barrier), a round with more items is shared by all
-// wavefronts (every wavefront works out the round's counts for itself).  state: three words of LDS.
+__device__ inline uint64_t lane_value64(uint64_t v, uint32_t src) {      // src: wavefront-uniform
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, (int)src);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), (int)src);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// The same rounds for arrays in LDS, by the whole workgroup.  The first wavefront runs the rounds of
+// fewer than 64 leaves and 64 nodes alone and in registers: lane l holds the l-th waiting leaf and
+// the l-th waiting node, the counts of a round are two ballots (the queues are sorted, so the
+// items merged now are a prefix of each), and an item's rank among the items of the other queue is
+// counted in a loop over the shorter of the two (one broadcast and one comparison per step)
+// instead of a binary search in LDS per item.  A round with more items is shared by all
+// wavefronts through the general routines (every wavefront works out the round's counts for
+// itself).  state: three words of LDS.
 __device__ inline void huffman_rounds_lds(const uint64_t *keys, uint64_t *iw, uint32_t *leaf_parent, uint32_t *int_parent,
                                           uint32_t m, uint32_t tid, uint32_t nthreads, uint32_t *state) {
     uint32_t li = 0, ii = 0, ni = 0;
     const uint32_t lane = tid & (uint32_t)(kWave - 1);
+    const uint64_t inf = ~0ull;
     while (true) {
         if (tid < (uint32_t)kWave) {
             while ((m - li) + (ni - ii) > 1u) {
-                uint32_t nl, nn;
-                round_control<true>(keys, iw, m, li, ii, ni, &nl, &nn);
-                if (nl + nn > (uint32_t)kWave) break;            // a large round: everybody's
-                round_items(keys, iw, leaf_parent, int_parent, li, ii, ni, nl, nn, lane, (uint32_t)kWave);
+                const uint64_t A = li + lane < m ? keys[li + lane] >> 16 : inf;      // waiting leaves
+                const uint64_t B = ii + lane < ni ? iw[ii + lane] : inf;             // waiting nodes
+                const uint64_t a0 = lane_value64(A, 0), a1 = lane_value64(A, 1), b0 = lane_value64(B, 0), b1 = lane_value64(B, 1);
+                uint64_t s0, s1;
+                if (a0 <= b0) { s0 = a0; s1 = (a1 <= b0) ? a1 : b0; }
+                else { s0 = b0; s1 = (a0 <= b1) ? a0 : b1; }
+                const uint64_t t = s0 + s1;
+                uint32_t nl = (uint32_t)__popcll(wave_ballot(A != inf && A <= t));
+                uint32_t nn = (uint32_t)__popcll(wave_ballot(B != inf && B <= t));
+                if (nl == (uint32_t)kWave || nn == (uint32_t)kWave) break;   // there may be more beyond the window: everybody's round
+                if ((nl + nn) & 1u) {
+                    const uint64_t la = nl ? lane_value64(A, nl - 1u) : 0, lb = nn ? lane_value64(B, nn - 1u) : 0;
+                    if (nn && (!nl || la <= lb)) --nn; else --nl;
+                }
+                // ranks in the other queue: my leaf counts the merged nodes lighter than it, my node the merged
+                // leaves not heavier than it
+                uint32_t before_leaf = 0, before_node = 0;
+                if (nn <= nl) {
+                    for (uint32_t k = 0; k < nn; ++k) {
+                        const uint64_t bk = lane_value64(B, k);
+                        before_leaf += (bk < A) ? 1u : 0u;
+                        const uint32_t c = (uint32_t)__popcll(wave_ballot(lane < nl && A <= bk));
+                        before_node = (lane == k) ? c : before_node;
+                    }
+                } else {
+                    for (uint32_t k = 0; k < nl; ++k) {
+                        const uint64_t ak = lane_value64(A, k);
+                        before_node += (ak <= B) ? 1u : 0u;
+                        const uint32_t c = (uint32_t)__popcll(wave_ballot(lane < nn && B < ak));
+                        before_leaf = (lane == k) ? c : before_leaf;
+                    }
+                }
+                if (lane < nl) {
+                    const uint32_t parent = ni + ((lane + before_leaf) >> 1);
+                    leaf_parent[li + lane] = parent;
+                    atomicAdd(reinterpret_cast<unsigned long long *>(&iw[parent]), (unsigned long long)A);
+                }
+                if (lane < nn) {
+                    const uint32_t parent = ni + ((lane + before_node) >> 1);
+                    int_parent[ii + lane] = parent;
+                    atomicAdd(reinterpret_cast<unsigned long long *>(&iw[parent]), (unsigned long long)B);
+                }
                 __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
                 __builtin_amdgcn_wave_barrier();
                 li += nl; ii += nn; ni += (nl + nn) >> 1;
