@@ -77,32 +77,46 @@ __device__ inline uint32_t next_pow2(uint32_t v) {
     return p;
 }
 
-// Canonical first codes per length from the per-length symbol counts; returns
-// false if the lengths are not a complete prefix code (or a single 1-bit code).
-__device__ bool canonical_first_codes(const uint32_t *cnt, uint32_t n_active, uint64_t *first_code,
-                                      uint32_t *first_index, uint32_t *max_len_out, uint32_t *min_len_out) {
-    uint64_t c = 0;
-    uint32_t idx = 0, max_len = 0, min_len = 0;
-    bool ok = true;
-    for (uint32_t L = 1; L <= 64; ++L) {
-        c <<= 1;                       // first code of length L = (first of L-1 + count of L-1) * 2
-        first_code[L] = c;
-        first_index[L] = idx;
-        if (cnt[L]) {
-            if (!min_len) min_len = L;
-            max_len = L;
-            if (L < 64 && c + cnt[L] > (1ull << L)) ok = false;
-            c += cnt[L];
-            idx += cnt[L];
-        }
+__device__ inline uint64_t lane_value64_any(uint64_t v, uint32_t src) {      // src: wavefront-uniform
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, (int)src);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), (int)src);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// Canonical first codes per length from the per-length symbol counts (cnt[1 .. 64]; 64 stands for
+// every length the container cannot hold); returns false if the lengths are not a complete prefix
+// code (or a single 1-bit code).  By one whole wavefront: every lane of it must call, the results
+// are wavefront-uniform.  The first code of length L is (first code of L-1 + count of L-1) * 2,
+// i.e. the sum over k < L of cnt[k] * 2^(L-k): lane L holds the count of length L and the first
+// codes are an exclusive scan of the counts in units of 2^-57.  A table is a valid code exactly
+// if no length above 57 is used, the Kraft sum does not exceed one, and it equals one unless the
+// code has a single symbol (of length 1).
+__device__ inline bool canonical_first_codes_wave(const uint32_t *cnt, uint32_t n_active, uint64_t *first_code,
+                                                  uint32_t *first_index, uint32_t *max_len_out, uint32_t *min_len_out) {
+    const uint32_t L = (uint32_t)lane_id();                  // lane 0 stands for no length; length 64 is looked at apart
+    const uint32_t c = L ? cnt[L] : 0u;
+    const uint32_t c64 = cnt[64];
+    const uint64_t used = wave_ballot(c != 0u);
+    // a count above 2^L alone breaks the Kraft inequality (and would overflow the sum below)
+    const bool too_many = L && L < 17u && c > (1u << L);
+    const bool too_long = (L > 57u && c != 0u);
+    const bool broken = wave_ballot(too_many || too_long) != 0ull || c64 != 0u;
+    const uint64_t term = (L && L <= 57u && !too_many) ? (uint64_t)c << (57u - L) : 0ull;
+    const uint64_t incl = wave_incl_scan<uint64_t>(term);
+    const uint32_t idx_incl = wave_incl_scan<uint32_t>(c);
+    const uint64_t excl = incl - term;
+    if (L) {
+        first_code[L] = (L <= 57u) ? excl >> (57u - L) : excl << (L - 57u);
+        first_index[L] = idx_incl - c;
     }
-    if (idx != n_active || max_len == 0 || max_len > 57) ok = false;
-    if (ok && n_active > 1) {
-        // completeness: one past the last code of the longest length is 2^max_len
-        uint64_t end = first_code[max_len] + cnt[max_len];
-        if (end != (1ull << max_len)) ok = false;
-    }
-    if (ok && n_active == 1 && max_len != 1) ok = false;
+    const uint64_t kraft = lane_value64_any(incl, 63);       // in units of 2^-57
+    const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)idx_incl, 63);
+    if (L == 0u) { first_code[64] = lane_value64_any(excl, 63) << 7; first_index[64] = total; }   // (length 64 is never valid)
+    const uint32_t max_len = c64 ? 64u : (used ? 63u - (uint32_t)__builtin_clzll(used) : 0u);
+    const uint32_t min_len = used ? (uint32_t)__builtin_ctzll(used) : (c64 ? 64u : 0u);
+    bool ok = !broken && total + c64 == n_active && max_len != 0u && max_len <= 57u && kraft <= (1ull << 57);
+    if (ok && n_active > 1u && kraft != (1ull << 57)) ok = false;
+    if (ok && n_active == 1u && max_len != 1u) ok = false;
     *max_len_out = max_len;
     *min_len_out = min_len;
     return ok;
@@ -191,11 +205,7 @@ __device__ inline void huffman_rounds(const uint64_t *keys, uint64_t *iw, uint32
     }
 }
 
-__device__ inline uint64_t lane_value64(uint64_t v, uint32_t src) {      // src: wavefront-uniform
-    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, (int)src);
-    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), (int)src);
-    return ((uint64_t)hi << 32) | lo;
-}
+__device__ inline uint64_t lane_value64(uint64_t v, uint32_t src) { return lane_value64_any(v, src); }
 
 // The same rounds for arrays in LDS, by the whole workgroup.  The first wavefront runs the rounds of
 // fewer than 64 leaves and 64 nodes alone and in registers: lane l holds the l-th waiting leaf and
@@ -367,10 +377,10 @@ __device__ inline void codebook_body(const BookArgs &a, uint32_t m, uint64_t *ke
     } else {
         bitonic_sort(keys, m2);
     }
-    if (tid == 0) {
+    if (tid < (uint32_t)kWave) {
         uint32_t mx, mn;
-        const bool ok = (m == 0 && !given) || (m != 0 && canonical_first_codes(s_cnt, m, s_first, s_findex, &mx, &mn));
-        if (!ok) atomicOr(&a.ctl->status, given ? (uint32_t)ST_CODEBOOK : (uint32_t)ST_INTERNAL);   // a given table must be a complete code
+        const bool ok = (m == 0 && !given) || (m != 0 && canonical_first_codes_wave(s_cnt, m, s_first, s_findex, &mx, &mn));
+        if (!ok && tid == 0) atomicOr(&a.ctl->status, given ? (uint32_t)ST_CODEBOOK : (uint32_t)ST_INTERNAL);   // a given table must be a complete code
     }
     __syncthreads();
 
@@ -541,24 +551,25 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
     } else {
         bitonic_sort(keys, m2);
     }
-    if (tid == 0) {
+    if (tid < (uint32_t)kWave) {
         uint32_t mx, mn;
-        const bool ok = canonical_first_codes(s_cnt, m, s_first, s_findex, &mx, &mn);
-        s_maxlen = mx;
-        s_ok = ok ? 1u : 0u;
+        const bool ok = canonical_first_codes_wave(s_cnt, m, s_first, s_findex, &mx, &mn);
+        if (tid == 0) { s_maxlen = mx; s_ok = ok ? 1u : 0u; }
         if (ok) {
-            for (uint32_t L = 1; L <= 64; ++L) {
-                // exclusive upper bound, left-aligned; the longest length closes the code space
-                uint64_t lim = 0;
-                if (L < mx) lim = (s_first[L] + s_cnt[L]) << (64u - L);
-                else lim = ~0ull;
-                s_limit[L] = lim;
-                a.t.limit[L] = lim;
-                a.t.first_code[L] = s_first[L];
-                a.t.first_index[L] = s_findex[L];
+            wave_lds_fence();                                // the first codes of the other lengths
+            const uint32_t L = tid ? tid : 64u;              // one length per lane
+            // exclusive upper bound, left-aligned; the longest length closes the code space
+            uint64_t lim = 0;
+            if (L < mx) lim = (s_first[L] + s_cnt[L]) << (64u - L);
+            else lim = ~0ull;
+            s_limit[L] = lim;
+            a.t.limit[L] = lim;
+            a.t.first_code[L] = s_first[L];
+            a.t.first_index[L] = s_findex[L];
+            if (tid == 0) {
+                a.t.limit[0] = 0; a.t.first_code[0] = 0; a.t.first_index[0] = 0;
+                a.t.meta[0] = mx; a.t.meta[1] = m; a.t.meta[2] = mn;
             }
-            a.t.limit[0] = 0; a.t.first_code[0] = 0; a.t.first_index[0] = 0;
-            a.t.meta[0] = mx; a.t.meta[1] = m; a.t.meta[2] = mn;
         }
     }
     __syncthreads();
