@@ -471,8 +471,9 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
     __shared__ uint64_t s_limit[65];
     __shared__ uint32_t s_findex[65];
     __shared__ uint32_t s_ok, s_maxlen, s_nbins;
-    __shared__ uint64_t s_dkeys[kBookBlock];
-    __shared__ uint64_t s_dx[kBookBlock];
+    __shared__ uint16_t s_sorted[kBookBlock * 2];                   // symbols in canonical order (alphabets up to this size)
+    __shared__ uint32_t s_wc[(kBookBlock / kWave) * 64];            // symbols per (wavefront, length) of the current 1024 symbols
+    __shared__ uint32_t s_run[65];                                  // symbols per length in front of them
 
     const uint32_t tid = threadIdx.x;
     if (a.reset_ctl && tid < sizeof(Control) / 4u) reinterpret_cast<uint32_t *>(a.ctl)[tid] = 0u;   // before the first barrier: nothing has raised a bit yet
@@ -515,41 +516,19 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
     }
     const uint32_t nbins = s_nbins;
 
-    // symbols with a code, keyed (length << 16 | symbol)
+    // ---- symbols per length ----
     uint32_t m = 0;
+    bool bad = false;
     for (uint32_t base = 0; base < nbins; base += kBookBlock) {
         const uint32_t s = base + tid;
-        m += __syncthreads_count((s < nbins) && a.len[s] != 0);
+        const uint32_t L = (s < nbins) ? a.len[s] : 0u;
+        if (L > 57u) bad = true;
+        if (L) atomicAdd(&s_cnt[L > 64u ? 64u : L], 1u);
+        m += __syncthreads_count(L != 0u);
     }
-    const bool small = m <= (uint32_t)kBookBlock;
-    uint64_t *keys = small ? s_dkeys : a.keys;
-    bool bad = false;
-    {
-        uint32_t done = 0;
-        for (uint32_t base = 0; base < nbins; base += kBookBlock) {
-            const uint32_t s = base + tid;
-            const uint32_t L = (s < nbins) ? a.len[s] : 0u;
-            if (L > 57u) bad = true;
-            uint32_t tot;
-            const uint32_t pos = block_excl_scan<uint32_t, kBookBlock / kWave>(L ? 1u : 0u, s_part, tot);
-            if (L) { keys[done + pos] = ((uint64_t)L << 16) | s; atomicAdd(&s_cnt[L > 64u ? 64u : L], 1u); }
-            done += tot;
-        }
-    }
-    const uint32_t m2 = next_pow2(m > 1 ? m : 2);
-    for (uint32_t i = m + tid; i < m2; i += kBookBlock) keys[i] = ~0ull;
     if (__syncthreads_or(bad ? 1 : 0) || m == 0) {
         if (tid == 0) raise_format();
         return;
-    }
-    if (small) {
-        uint64_t key = tid < m2 ? keys[tid] : ~0ull;
-        key = bitonic_sort_regs(key, s_dx, m2);
-        __syncthreads();
-        if (tid < m2) keys[tid] = key;
-        __syncthreads();
-    } else {
-        bitonic_sort(keys, m2);
     }
     if (tid < (uint32_t)kWave) {
         uint32_t mx, mn;
@@ -577,7 +556,49 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
         if (tid == 0) raise_format();
         return;
     }
-    for (uint32_t p = tid; p < m; p += kBookBlock) a.t.sorted[p] = (uint16_t)(keys[p] & 0xffffu);
+    // ---- canonical order: by length, then by symbol.  The symbols are visited in increasing order,
+    // so the place of a symbol is the first index of its length plus the number of smaller symbols of
+    // the same length: a counting sort (per wavefront the lanes of one length are found with a ballot
+    // per length that occurs, then a prefix over the wavefronts in front). ----
+    const bool small = m <= (uint32_t)kBookBlock * 2u;
+    uint16_t *sorted = small ? s_sorted : a.t.sorted;
+    {
+        const uint32_t lane = tid & (uint32_t)(kWave - 1), wave = tid / (uint32_t)kWave;
+        constexpr uint32_t kWaves = kBookBlock / kWave;
+        for (uint32_t i = tid; i < 65u; i += kBookBlock) s_run[i] = 0;
+        for (uint32_t base = 0; base < nbins; base += kBookBlock) {
+            for (uint32_t i = tid; i < kWaves * 64u; i += kBookBlock) s_wc[i] = 0;
+            __syncthreads();
+            const uint32_t s = base + tid;
+            const uint32_t L = (s < nbins) ? a.len[s] : 0u;  // 1 .. 57 here
+            uint32_t in_wave = 0;
+            uint64_t todo = wave_ballot(L != 0u);
+            while (todo) {                                   // one step per length that occurs in the wavefront
+                const uint32_t Lc = (uint32_t)__builtin_amdgcn_readlane((int)L, __builtin_ctzll(todo));
+                const uint64_t same = wave_ballot(L == Lc);
+                if (L == Lc) in_wave = (uint32_t)__popcll(same & ((1ull << lane) - 1ull));
+                if (lane == 0) s_wc[wave * 64u + Lc] = (uint32_t)__popcll(same);
+                todo &= ~same;
+            }
+            __syncthreads();
+            if (L) {
+                uint32_t before = s_run[L];
+                for (uint32_t w = 0; w < wave; ++w) before += s_wc[w * 64u + L];
+                sorted[s_findex[L] + before + in_wave] = (uint16_t)s;
+            }
+            __syncthreads();
+            if (tid < 64u && tid) {                          // symbols of each length so far
+                uint32_t add = 0;
+                for (uint32_t w = 0; w < kWaves; ++w) add += s_wc[w * 64u + tid];
+                s_run[tid] += add;
+            }
+            __syncthreads();                                 // the counts are cleared for the next 1024 symbols
+        }
+    }
+    if (small) {
+        for (uint32_t p = tid; p < m; p += kBookBlock) a.t.sorted[p] = sorted[p];
+    }
+
     // look-up table on the next kLutBits bits; entries carry the residual, not the symbol
     const uint32_t mx = s_maxlen;
     const int32_t radius = (int32_t)(nbins / 2u);
@@ -590,7 +611,7 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
             if (s_cnt[L] && (v < s_limit[L] || L == mx)) {
                 uint64_t off = (v >> (64u - L)) - s_first[L];
                 if (off >= s_cnt[L]) off = s_cnt[L] - 1u;      // only reachable with an invalid stream
-                const uint32_t sym = (uint32_t)(keys[s_findex[L] + off] & 0xffffu);
+                const uint32_t sym = sorted[s_findex[L] + off];
                 const int32_t d = sym ? (int32_t)sym - radius : -32768;
                 entry = ((uint32_t)d << 8) | L;
                 break;
@@ -615,7 +636,7 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
                 if (s_cnt[L] && (v < s_limit[L] || L == mx)) {
                     uint64_t off = (v >> (64u - L)) - s_first[L];
                     if (off >= s_cnt[L]) off = s_cnt[L] - 1u;      // only reachable with an invalid stream
-                    const uint32_t sym = (uint32_t)(keys[s_findex[L] + off] & 0xffffu);
+                    const uint32_t sym = sorted[s_findex[L] + off];
                     const int32_t d = sym ? (int32_t)sym - radius : kLut16Escape;
                     entry = (((uint32_t)d & 0xfffu) << 4) | L;
                     break;
