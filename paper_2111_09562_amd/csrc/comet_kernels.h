@@ -63,6 +63,7 @@ __global__ void k_abs_mean_final(const double *partial, uint32_t n_partial, uint
 // ---- codebook -----------------------------------------------------------------
 constexpr int kBookBlock = 1024;
 constexpr uint32_t kBookLdsSyms = 2048;    // alphabets up to this size are built entirely in LDS
+constexpr uint32_t kBookBySymbolMax = 8192; // nbins up to which the code lengths also fit LDS by symbol (one byte each)
 
 struct BookScratch {                        // global scratch for large alphabets (>= 65536 entries each)
     uint64_t *keys;        // sort keys

@@ -288,7 +288,7 @@ __device__ inline void huffman_rounds_lds(const uint64_t *keys, uint64_t *iw, ui
 template <bool LDS>
 __device__ inline void codebook_body(const BookArgs &a, uint32_t m, uint64_t *keys, uint64_t *iw, uint32_t *leaf_parent,
                                      uint32_t *int_parent, uint64_t *s_x, uint32_t *s_part, uint32_t *s_cnt,
-                                     uint64_t *s_first, uint32_t *s_findex, uint32_t *s_maxlen) {
+                                     uint64_t *s_first, uint32_t *s_findex, uint32_t *s_maxlen, uint32_t *s_wc) {
     const uint32_t tid = threadIdx.x;
     const uint32_t nbins = a.nbins;
     COMET_DBG(a.ctl, 1);
@@ -319,13 +319,22 @@ __device__ inline void codebook_body(const BookArgs &a, uint32_t m, uint64_t *ke
 
     COMET_DBG(a.ctl, 2);
     const bool reg_sort = LDS && m2 <= (uint32_t)kBookBlock;
+    // Canonical order without a second sort: the lengths are scattered into a by-symbol table (in the
+    // sort's exchange buffer, free after step 2) and the symbols are then visited in increasing order.
+    const bool by_symbol = LDS && nbins <= (uint32_t)kBookBySymbolMax;
+    uint8_t *s_depth = reinterpret_cast<uint8_t *>(s_x);
     if (given) {
         // lengths per symbol are known: count them; a length the container cannot hold spoils the count
         // of length 64, which the completeness test below then rejects
+        if (by_symbol) {
+            for (uint32_t i = tid; i < nbins; i += kBookBlock) s_depth[i] = 0;
+            __syncthreads();
+        }
         for (uint32_t i = tid; i < m; i += kBookBlock) {
             const uint32_t depth = (uint32_t)(keys[i] >> 16);
             atomicAdd(&s_cnt[depth > 57 ? 64 : depth], 1u);
             atomicMax(s_maxlen, depth);
+            if (by_symbol) s_depth[(uint32_t)(keys[i] & 0xffffu)] = (uint8_t)(depth > 57 ? 64 : depth);
         }
         __syncthreads();
     } else {
@@ -351,6 +360,10 @@ __device__ inline void codebook_body(const BookArgs &a, uint32_t m, uint64_t *ke
     __syncthreads();
 
     COMET_DBG(a.ctl, 4);
+    if (by_symbol) {
+        for (uint32_t i = tid; i < nbins; i += kBookBlock) s_depth[i] = 0;
+        __syncthreads();
+    }
     // ---- 4. depth of every leaf: walk to the root (node m-2) ----
     for (uint32_t i = tid; i < m; i += kBookBlock) {
         const uint32_t sym = (uint32_t)(keys[i] & 0xffffu);
@@ -363,36 +376,81 @@ __device__ inline void codebook_body(const BookArgs &a, uint32_t m, uint64_t *ke
         keys[i] = ((uint64_t)depth << 16) | sym;     // re-keyed for the canonical order
         atomicAdd(&s_cnt[depth > 64 ? 64 : depth], 1u);
         atomicMax(s_maxlen, depth);
+        if (by_symbol) s_depth[sym] = (uint8_t)(depth > 64 ? 64 : depth);
     }
     __syncthreads();
     }   // !given
 
     COMET_DBG(a.ctl, 5);
     // ---- 5. canonical order (length, symbol) ----
-    if (reg_sort) {
-        uint64_t key = tid < m2 ? keys[tid] : ~0ull;
-        key = bitonic_sort_regs(key, s_x, m2);
-        if (tid < m2) keys[tid] = key;
-        __syncthreads();
-    } else {
-        bitonic_sort(keys, m2);
+    if (!by_symbol) {
+        if (reg_sort) {
+            uint64_t key = tid < m2 ? keys[tid] : ~0ull;
+            key = bitonic_sort_regs(key, s_x, m2);
+            if (tid < m2) keys[tid] = key;
+            __syncthreads();
+        } else {
+            bitonic_sort(keys, m2);
+        }
     }
+    bool ok = true;
     if (tid < (uint32_t)kWave) {
         uint32_t mx, mn;
-        const bool ok = (m == 0 && !given) || (m != 0 && canonical_first_codes_wave(s_cnt, m, s_first, s_findex, &mx, &mn));
+        ok = (m == 0 && !given) || (m != 0 && canonical_first_codes_wave(s_cnt, m, s_first, s_findex, &mx, &mn));
         if (!ok && tid == 0) atomicOr(&a.ctl->status, given ? (uint32_t)ST_CODEBOOK : (uint32_t)ST_INTERNAL);   // a given table must be a complete code
     }
-    __syncthreads();
+    ok = __syncthreads_and(ok ? 1 : 0) != 0;
 
     COMET_DBG(a.ctl, 6);
     // ---- 6. codes and tables ----
-    for (uint32_t p = tid; p < m; p += kBookBlock) {
-        const uint32_t L = (uint32_t)(keys[p] >> 16);
-        const uint32_t sym = (uint32_t)(keys[p] & 0xffffu);
-        const uint64_t code = s_first[L > 64 ? 64 : L] + (p - s_findex[L > 64 ? 64 : L]);
-        a.len_out[sym] = (uint8_t)L;
-        a.enc[sym] = (code << 6) | (uint64_t)(L & 63u);
-        if (a.code_out) a.code_out[sym] = code;
+    if (!by_symbol) {
+        for (uint32_t p = tid; p < m; p += kBookBlock) {
+            const uint32_t L = (uint32_t)(keys[p] >> 16);
+            const uint32_t sym = (uint32_t)(keys[p] & 0xffffu);
+            const uint64_t code = s_first[L > 64 ? 64 : L] + (p - s_findex[L > 64 ? 64 : L]);
+            a.len_out[sym] = (uint8_t)L;
+            a.enc[sym] = (code << 6) | (uint64_t)(L & 63u);
+            if (a.code_out) a.code_out[sym] = code;
+        }
+        return;
+    }
+    // The symbols in increasing order: the code of a symbol is the first code of its length plus the
+    // number of smaller symbols of the same length (per wavefront the lanes of one length are found
+    // with a ballot per length that occurs, then a prefix over the wavefronts in front).
+    const uint32_t lane = tid & (uint32_t)(kWave - 1), wave = tid / (uint32_t)kWave;
+    constexpr uint32_t kWaves = kBookBlock / kWave;
+    uint32_t *s_run = s_wc + kWaves * 64u;                   // symbols per length in front of the current 1024 symbols
+    for (uint32_t i = tid; i < 65u; i += kBookBlock) s_run[i] = 0;
+    for (uint32_t base = 0; base < nbins; base += kBookBlock) {
+        for (uint32_t i = tid; i < kWaves * 64u; i += kBookBlock) s_wc[i] = 0;
+        __syncthreads();
+        const uint32_t sym = base + tid;
+        const uint32_t L = (sym < nbins) ? s_depth[sym] : 0u;
+        uint32_t in_wave = 0;
+        uint64_t todo = wave_ballot(L != 0u);
+        while (todo) {                                       // one step per length that occurs in the wavefront
+            const uint32_t Lc = (uint32_t)__builtin_amdgcn_readlane((int)L, __builtin_ctzll(todo));
+            const uint64_t same = wave_ballot(L == Lc);
+            if (L == Lc) in_wave = (uint32_t)__popcll(same & ((1ull << lane) - 1ull));
+            if (lane == 0) s_wc[wave * 64u + (Lc & 63u)] = (uint32_t)__popcll(same);
+            todo &= ~same;
+        }
+        __syncthreads();
+        if (L) {
+            uint32_t before = s_run[L & 63u];
+            for (uint32_t w = 0; w < wave; ++w) before += s_wc[w * 64u + (L & 63u)];
+            const uint64_t code = s_first[L] + before + in_wave;
+            a.len_out[sym] = (uint8_t)L;
+            a.enc[sym] = (code << 6) | (uint64_t)(L & 63u);
+            if (a.code_out) a.code_out[sym] = code;
+        }
+        __syncthreads();
+        if (tid < 64u) {
+            uint32_t add = 0;
+            for (uint32_t w = 0; w < kWaves; ++w) add += s_wc[w * 64u + tid];
+            s_run[tid] += add;
+        }
+        __syncthreads();                                     // the counts are cleared for the next 1024 symbols
     }
 }
 
@@ -410,6 +468,7 @@ __global__ __launch_bounds__(kBookBlock) void k_codebook(BookArgs a) {
     __shared__ uint64_t s_first[65];
     __shared__ uint32_t s_findex[65];
     __shared__ uint32_t s_maxlen;
+    __shared__ uint32_t s_wc[(kBookBlock / kWave) * 64 + 65];      // canonical order: symbols per (wavefront, length), and per length so far
 
     const uint32_t tid = threadIdx.x;
     const uint32_t nbins = a.nbins;
@@ -423,10 +482,10 @@ __global__ __launch_bounds__(kBookBlock) void k_codebook(BookArgs a) {
         m += __syncthreads_count((s < nbins) && (a.given_len ? a.given_len[s] != 0 : a.hist[s] != 0u));
     }
     if (m <= kBookLdsSyms)
-        codebook_body<true>(a, m, s_keys, s_iw, s_lp, s_ip, s_x, s_part, s_cnt, s_first, s_findex, &s_maxlen);
+        codebook_body<true>(a, m, s_keys, s_iw, s_lp, s_ip, s_x, s_part, s_cnt, s_first, s_findex, &s_maxlen, s_wc);
     else
         codebook_body<false>(a, m, a.scratch.keys, a.scratch.iw, a.scratch.leaf_parent, a.scratch.int_parent, s_x, s_part,
-                             s_cnt, s_first, s_findex, &s_maxlen);
+                             s_cnt, s_first, s_findex, &s_maxlen, s_wc);
 
     COMET_DBG(a.ctl, 7);
     // ---- 7. container layout ----
