@@ -208,11 +208,10 @@ __device__ inline void huffman_rounds(const uint64_t *keys, uint64_t *iw, uint32
 __device__ inline uint64_t lane_value64(uint64_t v, uint32_t src) { return lane_value64_any(v, src); }
 
 // The same rounds for arrays in LDS, by the whole workgroup.  The first wavefront runs the rounds of
-// fewer than 64 leaves and 64 nodes alone and in registers: lane l holds the l-th waiting leaf and
-// the l-th waiting node, the counts of a round are two ballots (the queues are sorted, so the
-// items merged now are a prefix of each), and an item's rank among the items of the other queue is
-// counted in a loop over the shorter of the two (one broadcast and one comparison per step)
-// instead of a binary search in LDS per item.  A round with more items is shared by all
+// at most 64 items alone and in registers: lane l holds the l-th waiting leaf and the l-th waiting
+// node, the counts of a round are two ballots (the queues are sorted, so the items merged now are
+// a prefix of each), and the merged order of the items comes from a short counting loop or from
+// one bitonic merge across the lanes instead of a binary search in LDS per item.  A round with more items is shared by all
 // wavefronts through the general routines (every wavefront works out the round's counts for
 // itself).  state: three words of LDS.
 __device__ inline void huffman_rounds_lds(const uint64_t *keys, uint64_t *iw, uint32_t *leaf_parent, uint32_t *int_parent,
@@ -237,33 +236,63 @@ __device__ inline void huffman_rounds_lds(const uint64_t *keys, uint64_t *iw, ui
                     const uint64_t la = nl ? lane_value64(A, nl - 1u) : 0, lb = nn ? lane_value64(B, nn - 1u) : 0;
                     if (nn && (!nl || la <= lb)) --nn; else --nl;
                 }
-                // ranks in the other queue: my leaf counts the merged nodes lighter than it, my node the merged
-                // leaves not heavier than it
-                uint32_t before_leaf = 0, before_node = 0;
-                if (nn <= nl) {
-                    for (uint32_t k = 0; k < nn; ++k) {
-                        const uint64_t bk = lane_value64(B, k);
-                        before_leaf += (bk < A) ? 1u : 0u;
-                        const uint32_t c = (uint32_t)__popcll(wave_ballot(lane < nl && A <= bk));
-                        before_node = (lane == k) ? c : before_node;
+                if (nl + nn > (uint32_t)kWave) break;        // more items than lanes: everybody's round
+                if ((nl < nn ? nl : nn) <= 8u) {
+                    // A short queue: an item's rank in the other queue is counted in a loop over the shorter
+                    // one (one broadcast and one comparison per step): my leaf counts the merged nodes lighter
+                    // than it, my node the merged leaves not heavier than it.
+                    uint32_t before_leaf = 0, before_node = 0;
+                    if (nn <= nl) {
+                        for (uint32_t k = 0; k < nn; ++k) {
+                            const uint64_t bk = lane_value64(B, k);
+                            before_leaf += (bk < A) ? 1u : 0u;
+                            const uint32_t c = (uint32_t)__popcll(wave_ballot(lane < nl && A <= bk));
+                            before_node = (lane == k) ? c : before_node;
+                        }
+                    } else {
+                        for (uint32_t k = 0; k < nl; ++k) {
+                            const uint64_t ak = lane_value64(A, k);
+                            before_node += (ak <= B) ? 1u : 0u;
+                            const uint32_t c = (uint32_t)__popcll(wave_ballot(lane < nn && B < ak));
+                            before_leaf = (lane == k) ? c : before_leaf;
+                        }
+                    }
+                    if (lane < nl) {
+                        const uint32_t parent = ni + ((lane + before_leaf) >> 1);
+                        leaf_parent[li + lane] = parent;
+                        atomicAdd(reinterpret_cast<unsigned long long *>(&iw[parent]), (unsigned long long)A);
+                    }
+                    if (lane < nn) {
+                        const uint32_t parent = ni + ((lane + before_node) >> 1);
+                        int_parent[ii + lane] = parent;
+                        atomicAdd(reinterpret_cast<unsigned long long *>(&iw[parent]), (unsigned long long)B);
                     }
                 } else {
-                    for (uint32_t k = 0; k < nl; ++k) {
-                        const uint64_t ak = lane_value64(A, k);
-                        before_node += (ak <= B) ? 1u : 0u;
-                        const uint32_t c = (uint32_t)__popcll(wave_ballot(lane < nn && B < ak));
-                        before_leaf = (lane == k) ? c : before_leaf;
+                    // Merged order of the round's items: the leaves ascending from lane 0, the nodes descending
+                    // from lane 63 and infinity between them are a bitonic sequence, which six compare-exchange
+                    // steps sort.  Key = (weight, node after leaf, position in its queue): the order of the
+                    // sequential construction, and no two keys are equal (weights stay below 2^57: at most
+                    // 65536 counts of 32 bits).
+                    const uint64_t Brev = __shfl(B, (int)(kWave - 1u - lane), kWave);
+                    uint64_t key = inf;
+                    if (lane < nl) key = (A << 7) | lane;
+                    else if ((uint32_t)kWave - 1u - lane < nn) key = (Brev << 7) | 64u | ((uint32_t)kWave - 1u - lane);
+#pragma unroll
+                    for (uint32_t j = kWave / 2; j > 0; j >>= 1) {
+                        const uint64_t other = __shfl_xor(key, (int)j, kWave);
+                        const uint64_t lo = key < other ? key : other, hi = key < other ? other : key;
+                        key = (lane & j) ? hi : lo;
                     }
-                }
-                if (lane < nl) {
-                    const uint32_t parent = ni + ((lane + before_leaf) >> 1);
-                    leaf_parent[li + lane] = parent;
-                    atomicAdd(reinterpret_cast<unsigned long long *>(&iw[parent]), (unsigned long long)A);
-                }
-                if (lane < nn) {
-                    const uint32_t parent = ni + ((lane + before_node) >> 1);
-                    int_parent[ii + lane] = parent;
-                    atomicAdd(reinterpret_cast<unsigned long long *>(&iw[parent]), (unsigned long long)B);
+                    // lane r now holds the item of rank r: items 2j and 2j+1 become node ni + j
+                    const uint64_t w = key >> 7;
+                    const uint64_t w_next = __shfl_xor(w, 1, kWave);
+                    if (lane < nl + nn) {
+                        const uint32_t parent = ni + (lane >> 1);
+                        const uint32_t pos = (uint32_t)key & 63u;
+                        if (key & 64u) int_parent[ii + pos] = parent;
+                        else leaf_parent[li + pos] = parent;
+                        if ((lane & 1u) == 0u) iw[parent] = w + w_next;
+                    }
                 }
                 __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
                 __builtin_amdgcn_wave_barrier();
