@@ -553,7 +553,6 @@ __global__ __launch_bounds__(kBookBlock) void k_codebook(BookArgs a) {
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
     __builtin_amdgcn_s_setprio(3);                  // as k_codebook: a single workgroup others wait for
-    __shared__ uint32_t s_part[kBookBlock / kWave];
     __shared__ uint32_t s_cnt[65];
     __shared__ uint64_t s_first[65];
     __shared__ uint64_t s_limit[65];

@@ -56,7 +56,6 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize(QuantArgs a) {
 
     const int tid = threadIdx.x;
     const int lane = lane_id();
-    const int wave = tid / kWave;
 
     COMET_DBG(a.ctl, 20);
     const float *xin = static_cast<const float *>(a.x);      // this kernel takes fp32 only
