@@ -501,11 +501,14 @@ __global__ __launch_bounds__(kQuantBlock) void k_gather_records(QuantArgs a) {
         if ((uint32_t)w == wave) mine = c;
     }
     if (blockIdx.x + 1u == gridDim.x && tid == kQuantBlock - 1) a.ctl->n_rec = base + mine;   // last run: base covers all runs before it
+    // two of the first workgroups (little in front of them) total the other counters, one each
     if (blockIdx.x == 0) {
-        // the first workgroup (nothing in front of it) totals the other counters
         const uint64_t nnz_total = total_of(wg_nnz, gridDim.x);
+        if (tid == 0) a.ctl->nnz = nnz_total;
+    }
+    if (blockIdx.x == (gridDim.x > 1u ? 1u : 0u)) {
         const uint64_t vrec_total = total_of(wg_vrec, gridDim.x);
-        if (tid == 0) { a.ctl->nnz = nnz_total; a.ctl->n_vrec = vrec_total; }
+        if (tid == 0) a.ctl->n_vrec = vrec_total;
     }
     if (!mine) return;
     const uint32_t run = run0 + wave;
