@@ -117,6 +117,46 @@ def test_stage_codebook(comet, ctx, oracle, name):
     assert np.array_equal(codes.cpu().numpy().view(np.uint64), want_code)
 
 
+def test_stage_codebook_sweep(comet, ctx, oracle):
+    """Code lengths and canonical codes over many alphabets: every size around the limits of the
+    merge rounds (one wavefront in registers, the workgroup, global scratch) and of the counting
+    order (by-symbol table up to 8192 bins), weight distributions with few and with many ties,
+    counts up to 2^32 - 1."""
+    rng = np.random.default_rng(2024)
+    cases = []
+    for nb in (16, 1024, 2048, 4096, 8192, 16384):
+        for m in (2, 3, 31, 63, 64, 65, 127, 129, 700, 1024, 2047, 2048, 2049, 3000):
+            if m > nb:
+                continue
+            for kind in ("zipf", "flat", "expo", "huge"):
+                if rng.random() < 0.45 and m not in (64, 65, 2048, 2049):
+                    continue
+                h = np.zeros(nb, np.uint64)
+                act = rng.choice(nb, m, replace=False)
+                if kind == "zipf":
+                    w = np.floor(1e6 / (1 + rng.permutation(m)) ** 1.3) + 1
+                elif kind == "flat":
+                    w = rng.integers(1, 4, m)
+                elif kind == "expo":
+                    w = np.floor(np.exp(rng.uniform(0, 20, m))) + 1
+                else:
+                    w = rng.integers(2 ** 31, 2 ** 32 - 1, m)
+                h[act] = w
+                cases.append((nb, m, kind, h.astype(np.uint32)))
+    assert len(cases) > 60
+    for nb, m, kind, h in cases:
+        want_len = oracle.code_lengths(h)
+        if want_len.max() > 57:
+            continue                                            # the container cannot hold such a code (both sides refuse it)
+        want_code = oracle.canonical_codes(want_len)
+        lens = torch.empty(nb, dtype=torch.uint8, device="cuda")
+        codes = torch.empty(nb, dtype=torch.int64, device="cuda")
+        ctx.comet_stage_codebook(dev(h.view(np.int32)), nb, lens, codes)
+        ctx.comet_sync()
+        assert np.array_equal(lens.cpu().numpy(), want_len), (nb, m, kind)
+        assert np.array_equal(codes.cpu().numpy().view(np.uint64), want_code), (nb, m, kind)
+
+
 @pytest.mark.parametrize("chunk_syms", [64, 128, 256])
 @pytest.mark.parametrize("n,nbins,conc", [(100_003, 1024, 0.05), (1, 16, 1.0), (64 * 256 * 3 + 5, 64, 0.5), (33_000, 65536, 0.001)])
 def test_stage_encode_decode(comet, ctx, oracle, chunk_syms, n, nbins, conc):
