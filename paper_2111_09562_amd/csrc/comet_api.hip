@@ -133,16 +133,6 @@ __global__ void k_latch(DevState *s) {           // fold this call's status into
     if (s->ctl.status) atomicOr(&s->latched, s->ctl.status);
 }
 
-// Last kernel of a compression: payload size and status go into the container header.
-__global__ void k_seal(DevState *s, Header *h) {
-    const uint64_t total = s->ctl.off_payload + 4ull * s->ctl.payload_words;
-    h->payload_words = s->ctl.payload_words;
-    h->total_bytes = total;
-    h->status = s->ctl.status ? 1u : 0u;
-    s->ctl.total_bytes = total;
-    if (s->ctl.status) atomicOr(&s->latched, s->ctl.status);
-}
-
 // Brackets a kernel launch with two events when profiling is on.
 struct TimedScope {
     comet_ctx *c; hipStream_t st; comet_ctx::Timed *t = nullptr;
@@ -290,6 +280,7 @@ int launch_encode(comet_ctx *ctx, const uint16_t *codes, uint64_t n, uint32_t nb
     a.chunk_off = chunk_off; a.container = container; a.capacity = capacity;
     a.payload = payload; a.payload_cap_words = payload_cap; a.payload_words_out = payload_words_out;
     a.desc = desc; a.ctl = &ctx->state->ctl;
+    a.latched = container ? &ctx->state->latched : nullptr;
     const bool full = (a.tbl_n == nbins);
 #define COMET_LAUNCH_ENC(S)                                                                                            \
     do {                                                                                                               \
@@ -536,8 +527,6 @@ int compress_impl(comet_ctx *ctx, const void *dev_in, int in_type, comet_shape s
     rc = launch_encode(ctx, ctx->codes, n, nbins, S, st, reinterpret_cast<uint32_t *>(out + proto.off_chunk), out, capacity,
                        nullptr, 0, nullptr, desc_e);
     if (rc) return rc;
-    hipLaunchKernelGGL(k_seal, dim3(1), dim3(1), 0, st, ctx->state, reinterpret_cast<Header *>(out));
-    HIP_TRY(hipGetLastError());
     if (bytes_out) {
         HIP_TRY(hipMemcpyAsync(ctx->host_state, ctx->state, sizeof(DevState), hipMemcpyDeviceToHost, st));
         HIP_TRY(hipStreamSynchronize(st));

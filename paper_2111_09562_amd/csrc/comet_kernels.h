@@ -110,6 +110,7 @@ struct EncodeArgs {
     uint64_t *payload_words_out;   // stage path
     uint64_t *desc;            // words of every segment (written by the count kernel, read by the pack kernel)
     Control *ctl;
+    uint32_t *latched;         // product path: the context's persistent status word (the pack kernel seals the header); else null
 };
 constexpr uint32_t kEncUnroll = 4;         // steps of 256 symbols a wavefront handles per iteration
 constexpr uint32_t kEncStepWordsMax = 468; // 256 code words of up to 58 bits, in 32-bit words, plus slack

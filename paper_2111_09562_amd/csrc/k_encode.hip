@@ -18,7 +18,8 @@
 //                   encoded and written at their final place.
 // Neither kernel fences or counts finished workgroups: a device-scope release writes back and
 // invalidates the L2 of the issuing XCD, which costs far more than the kernel boundary that
-// orders these two kernels and the one that seals the container header.
+// orders these two kernels.  The last segment's workgroup of the pack kernel seals the container
+// header: the payload size it computes decides everything the header still lacks.
 // The encode table ((code << 6) | length per symbol) is cached in LDS for the
 // bins around the centre; other symbols are looked up in global memory.
 #include "comet_kernels.h"
@@ -221,9 +222,23 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_pack(EncodeArgs a) {
     bool overflow = false;
     if (seg + 1u == gridDim.x && tid == 0) {
         const uint64_t pw = base + a.desc[seg];
-        a.ctl->payload_words = pw;                    // the container header is sealed by the kernel that follows
+        a.ctl->payload_words = pw;
         if (a.payload_words_out) *a.payload_words_out = pw;
         if (pw > 0xffffffffull) overflow = true;      // chunk offsets are 32-bit word indices
+        if (a.container && a.latched) {
+            // The thread that knows the payload size also seals the container header (no kernel of its
+            // own for that): the only bit this kernel can raise is the capacity bit, and whether any
+            // workgroup raises it follows from the size.
+            Header *h = reinterpret_cast<Header *>(a.container);
+            const uint64_t total = a.ctl->off_payload + 4ull * pw;
+            uint32_t stt = a.ctl->status;             // what the kernels before this one raised
+            if (overflow || total > a.capacity) stt |= (uint32_t)ST_CAPACITY;
+            h->payload_words = pw;
+            h->total_bytes = total;
+            h->status = stt ? 1u : 0u;
+            a.ctl->total_bytes = total;
+            if (stt) atomicOr(a.latched, stt);        // folded into the context's persistent word
+        }
     }
     __syncthreads();                                  // table and buffers ready
     ENC_DBG(5);
