@@ -28,8 +28,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per mean launch of a kernel, from the rocprofv3 counter runs summarised under profiles/
 # (FETCH_SIZE + WRITE_SIZE, scaled by the same counters on a plain copy of known size); filled in by hand
 # from those summaries, None where no counter run covers the kernel
-TRAFFIC = {"k_quantize_rows": 185593884, "k_encode_count": 61157279, "k_encode_pack": 88065877,
-           "k_decode_chunks": 103104033, "k_scan_store": 201215643}
+TRAFFIC = {"k_quantize_rows": 185594479, "k_encode_count": 61144341, "k_encode_pack": 87444836,
+           "k_decode_chunks": 103274120, "k_scan_store": 201241676}
 
 
 def main() -> int:
