@@ -539,6 +539,43 @@ def test_saved_activation_hook_on_a_toy_conv_stack(comet, oracle):
     c.close()
 
 
+def test_calls_can_be_captured_in_a_graph(comet, oracle):
+    """The asynchronous calls issue kernels only (no memset, no synchronisation), so a stream capture
+    records them.  The graph is replayed several times on new inputs, with eager work between the
+    replays, and every replay is compared with the oracle."""
+    shape = (4, 16, 56, 56)
+    c = comet.Context(int(np.prod(shape)), 1024)
+    c.comet_set_chunk_syms(64)
+    x = torch.empty(shape, dtype=torch.float32, device="cuda")
+    cont = torch.zeros(int(x.numel() * 4 * 0.8) // 16 * 16, dtype=torch.uint8, device="cuda")
+    y = torch.empty_like(x)
+    inputs = [synth.relu_blur(shape, seed=s, blur=3, shift=-0.2) for s in (1, 2, 3)]
+    x.copy_(torch.from_numpy(inputs[0]))
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        c.comet_compress(x, 1e-2, 1024, cont, stream=st, sync=False)           # warm-up outside the capture
+        c.comet_decompress(cont, cont.numel(), shape, y, stream=st)
+        c.comet_sync(st)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=st):
+            c.comet_compress(x, 1e-2, 1024, cont, stream=torch.cuda.current_stream(), sync=False)
+            c.comet_decompress(cont, cont.numel(), shape, y, stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for xn in inputs + inputs[:1]:
+        x.copy_(torch.from_numpy(xn))
+        cont.zero_()
+        y.zero_()
+        float((x * 2).sum())                                                   # eager work between the replays
+        g.replay()
+        torch.cuda.synchronize()
+        want = oracle.compress(xn, 1e-2, 1024, 64)
+        used = int(c.comet_peek(cont, cont.numel()).total_bytes)
+        assert used == want.size and np.array_equal(cont[:used].cpu().numpy(), want)
+        assert np.array_equal(y.cpu().numpy().view(np.uint32), oracle.decompress(want).view(np.uint32))
+    c.comet_sync()
+    c.close()
+
+
 def test_roundtrip_config0_and_determinism(comet, ctx, oracle):
     e = synth.config0()[0]
     x = synth.make(e)
