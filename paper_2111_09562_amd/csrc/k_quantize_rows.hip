@@ -462,15 +462,13 @@ __global__ __launch_bounds__(kQuantBlock) void k_gather_records(QuantArgs a) {
     // histogram: one thread per bin adds up the partial histograms (codes outside the LDS window of
     // the quantise kernel were counted in hist directly)
     for (uint32_t b = blockIdx.x * kQuantBlock + tid; !REUSE && b < a.nbins; b += gridDim.x * kQuantBlock) {
-        uint32_t v = 0;
-        for (uint32_t c0 = 0; c0 < a.hist_copies; c0 += 8u) {               // eight loads in flight
-            uint32_t p[8];
+        uint32_t v = a.hist[b];                                             // (codes outside the LDS window)
+        uint32_t p[kQuantHistCopiesMax];                                    // every copy in flight at once: one round trip
 #pragma unroll
-            for (uint32_t j = 0; j < 8; ++j) p[j] = (c0 + j < a.hist_copies) ? a.hist_parts[(size_t)(c0 + j) * a.nbins + b] : 0u;
+        for (uint32_t j = 0; j < kQuantHistCopiesMax; ++j) p[j] = (j < a.hist_copies) ? a.hist_parts[(size_t)j * a.nbins + b] : 0u;
 #pragma unroll
-            for (uint32_t j = 0; j < 8; ++j) v += p[j];
-        }
-        if (v) a.hist[b] += v;
+        for (uint32_t j = 0; j < kQuantHistCopiesMax; ++j) v += p[j];
+        a.hist[b] = v;
     }
 
     // sum of the per-workgroup counters wg[0 .. count) over the workgroup, eight loads in flight per thread
