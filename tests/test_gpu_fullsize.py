@@ -72,6 +72,36 @@ def test_config1_full_size_in_bench_configuration(comet, oracle):
         c.close()
 
 
+def test_config1_full_size_bfloat16(comet, oracle):
+    """The benchmark set rounded to bfloat16 through comet_compress_16 / comet_decompress_16, five
+    contexts on five streams as `bench.py` runs it: containers and 16-bit outputs bit for bit."""
+    layers = synth.config1(64)
+    xs16 = [torch.from_numpy(synth.make(e)).to(torch.bfloat16) for e in layers]
+    bits = [x.view(torch.int16).numpy().view(np.uint16) for x in xs16]
+    xs = [x.cuda() for x in xs16]
+    n_ctx = len(layers)
+    ctxs = [comet.Context(max_elems=max(x.numel() for x in xs), max_nbins=1024) for _ in range(n_ctx)]
+    for c in ctxs:
+        c.comet_set_chunk_syms(64)
+    streams = [torch.cuda.current_stream()] + [torch.cuda.Stream() for _ in range(n_ctx - 1)]
+    conts = [torch.empty(int(x.numel() * 4 * 0.6) // 16 * 16, dtype=torch.uint8, device="cuda") for x in xs]
+    outs = [torch.empty_like(x) for x in xs]
+    torch.cuda.synchronize()
+    for i, (x, e, c) in enumerate(zip(xs, layers, conts)):
+        ctxs[i].comet_compress_16(x, e["eb"], e["nbins"], c, stream=streams[i], sync=False)
+    for i in reversed(range(n_ctx)):
+        ctxs[i].comet_decompress_16(conts[i], conts[i].numel(), xs[i].shape, outs[i], stream=streams[i])
+    for c, st in zip(ctxs, streams):
+        c.comet_sync(st)
+    for b, e, cont, out in zip(bits, layers, conts, outs):
+        want = oracle.compress_16(b, oracle.BF16, e["eb"], e["nbins"], 64)
+        assert np.array_equal(cont[:want.size].cpu().numpy(), want), f"container differs for {e['shape']}"
+        got = out.view(torch.int16).cpu().numpy().view(np.uint16)
+        assert np.array_equal(got, oracle.decompress_16(want, oracle.BF16)), f"values differ for {e['shape']}"
+    for c in ctxs:
+        c.close()
+
+
 def test_codebook_reuse_full_size(comet, oracle):
     """Code book reuse at the benchmark's sizes.  With a tensor's own table the container must be the one
     comet_compress writes, byte for byte (that one is checked against the oracle above); with the table of a
