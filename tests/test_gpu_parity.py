@@ -193,6 +193,36 @@ def test_stage_encode_decode(comet, ctx, oracle, chunk_syms, n, nbins, conc):
     assert np.array_equal(out.cpu().numpy().view(np.uint16), codes)
 
 
+def test_stage_decode_large_alphabet(comet, ctx, oracle):
+    """Tens of thousands of active symbols: the canonical order of the decode tables is built over
+    several blocks of symbols and kept in global memory, and most codes are longer than the
+    look-up table."""
+    rng = np.random.default_rng(77)
+    nbins, n, chunk_syms = 65536, 300_000, 128
+    active = rng.choice(nbins, 20_000, replace=False)
+    codes = active[rng.integers(0, active.size, n)].astype(np.uint16)
+    codes[:5000] = active[0]                                   # one frequent symbol: code lengths spread out
+    hist = oracle.histogram(codes, nbins)
+    ln = oracle.code_lengths(hist)
+    cw = oracle.canonical_codes(ln)
+    want_off, want_payload = oracle.encode(codes, nbins, chunk_syms, ln, cw)
+    out = torch.empty(n, dtype=torch.int16, device="cuda")
+    ctx.comet_stage_decode(dev(ln), nbins, dev(want_off.view(np.int32)), dev(want_payload.view(np.int32)),
+                           want_payload.size, n, chunk_syms, out)
+    ctx.comet_sync()
+    assert np.array_equal(out.cpu().numpy().view(np.uint16), codes)
+    # and through the whole path: a tensor whose residuals spread over a 65536-bin alphabet
+    x = (rng.normal(0, 40.0, (2, 3, 64, 96))).astype(np.float32)
+    want = oracle.compress(x, 1e-3, 65536, 64)
+    assert oracle.parse_container(want)["n_active"] > 2048
+    out_c, used = gpu_compress(ctx, comet, x, 1e-3, 65536, 64)
+    assert used == want.size and np.array_equal(out_c[:used].cpu().numpy(), want)
+    y = torch.empty(x.size, dtype=torch.float32, device="cuda")
+    ctx.comet_decompress(out_c, used, x.shape, y)
+    ctx.comet_sync()
+    assert np.array_equal(y.cpu().numpy().view(np.uint32), oracle.decompress(want).ravel().view(np.uint32))
+
+
 def test_stage_decode_long_codes(comet, ctx, oracle):
     fib = [1, 1]
     while len(fib) < 47:
