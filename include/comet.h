@@ -122,9 +122,11 @@ int comet_decompress(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_s
  * decompression reads it.  comet_decompress_16 rounds the fp32 result of comet_decompress to the
  * 16-bit type (nearest, ties to even; after the re-zero filter), so a value differs from the
  * input by at most eb plus half a unit in the last place of the 16-bit type; verbatim values come
- * back exactly.  dtype: COMET_F16 (IEEE binary16) or COMET_BF16 (bfloat16); dev_in / dev_out of
- * the 16-bit type, 16-byte aligned, device memory, owned by the caller.  Limit: planes of at most
- * 512 columns (COMET_ERR_INVALID otherwise).  Errors, `bytes_out`, streams: as for the fp32 calls. */
+ * back exactly.  dtype: COMET_F16 (IEEE binary16) or COMET_BF16 (bfloat16); the tensor is device
+ * memory of the 16-bit type, owned by the caller (input of comet_compress_16: 16-byte aligned, as
+ * for comet_compress; output of comet_decompress_16: any element-aligned address).  Limit: planes
+ * of at most 512 columns (COMET_ERR_INVALID otherwise).  Errors, `bytes_out`, streams: as for the
+ * fp32 calls. */
 #define COMET_F16 1
 #define COMET_BF16 2
 int comet_compress_16(comet_ctx *ctx, const void *dev_in, int dtype, comet_shape shape, float eb, uint32_t nbins,
