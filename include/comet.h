@@ -82,8 +82,10 @@ uint64_t comet_compress_bound(comet_shape shape, uint32_t nbins, uint32_t chunk_
  * [2^-100, 2^100].  nbins: even, in [4, 65536]; residuals outside
  * (-nbins/2, nbins/2) are stored as outliers.
  * bytes_out != NULL: the call synchronises `stream`, stores the container size
- * and returns any device-side error (COMET_ERR_CAPACITY leaves the buffer
- * contents undefined but never writes past capacity).
+ * and returns any device-side error of this call (COMET_ERR_CAPACITY leaves the
+ * buffer contents undefined but never writes past capacity) or, if this call
+ * raised none, the first one that earlier asynchronous calls on this context
+ * have latched (*bytes_out is then still this call's valid size).
  * bytes_out == NULL: fully asynchronous; the size is in the container header
  * (comet_peek) and errors are reported by comet_sync. */
 int comet_compress(comet_ctx *ctx, const float *dev_in, comet_shape shape, float eb, uint32_t nbins,

@@ -176,6 +176,11 @@ int oracle_histogram(const uint16_t *codes, uint64_t n, uint32_t nbins, uint32_t
  *     when a leaf and an internal node weigh the same, and appends their sum;
  *   - the length of a symbol is the depth of its leaf.
  * One active symbol gets length 1.  Symbols with freq 0 get length 0.
+ * Reading for the longest code (the paper gives none): 57 bits, the longest code
+ * word that shares a 64-bit table entry with its 6-bit length; a histogram whose
+ * tree is deeper is refused.  A leaf at depth d needs a total count of at least
+ * Fibonacci(d + 2), and Fibonacci(60) > 2^40, so no tensor of fewer than 2^31
+ * elements gets there; only a hand-made histogram can.
  */
 typedef struct { uint64_t f; uint32_t s; } orc_leaf;
 
@@ -227,7 +232,7 @@ int oracle_code_lengths(const uint32_t *freq, uint32_t nbins, uint8_t *len) {
         for (uint32_t j = ni - 1; j-- > 0;) int_depth[j] = int_depth[int_parent[j]] + 1u;
         for (uint32_t i = 0; i < m; ++i) {
             uint32_t dpt = int_depth[leaf_parent[i]] + 1u;
-            if (dpt > 64u) { rc = ORC_ERR_INVALID; break; }
+            if (dpt > 57u) { rc = ORC_ERR_INVALID; break; }
             len[leaf[i].s] = (uint8_t)dpt;
         }
     }

@@ -11,7 +11,7 @@ import ctypes as C
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("COMET_LIB", os.path.join(_HERE, "libcomet.so"))   # COMET_LIB: use another build of the library
+LIB_PATH = os.path.join(_HERE, "libcomet.so")
 
 OK, ERR_INVALID, ERR_CAPACITY, ERR_FORMAT, ERR_HIP, ERR_NOMEM, ERR_INTERNAL, ERR_CODEBOOK = 0, -1, -2, -3, -4, -5, -6, -7
 HEADER_BYTES = 128

@@ -367,7 +367,7 @@ int comet_create(comet_ctx **out, uint64_t max_elems, uint32_t max_nbins) {
     const uint64_t tiles_q = (uint64_t)c->num_cu * 16u + 16u;
     const uint64_t tiles_e = (uint64_t)c->num_cu * 8u + max_elems / 64u / kEncSegChunksMax + 16u;
     const ZeroLayout z = zero_layout(kMaxBins, kMaxBins, tiles_q, tiles_e);   // the partial histograms take 256 KB whatever the alphabet
-    c->zero_cap = z.bytes + 4ull * kQuantHistPartsWords;
+    c->zero_cap = z.bytes;
     const uint64_t state_bytes = offsetof(DevState, ctl) + z.bytes;
     if ((e = hipMalloc((void **)&c->state, state_bytes)) != hipSuccess) return fail(COMET_ERR_NOMEM);
     if ((e = hipMemset(c->state, 0, state_bytes)) != hipSuccess) return fail(hip_fail(e, "hipMemset"));
@@ -530,13 +530,15 @@ int compress_impl(comet_ctx *ctx, const void *dev_in, int in_type, comet_shape s
     if (bytes_out) {
         HIP_TRY(hipMemcpyAsync(ctx->host_state, ctx->state, sizeof(DevState), hipMemcpyDeviceToHost, st));
         HIP_TRY(hipStreamSynchronize(st));
-        const uint32_t stt = ctx->host_state->ctl.status;
+        // this call's own bits, and whatever earlier asynchronous calls on this context have latched
+        const uint32_t own = ctx->host_state->ctl.status;
+        const uint32_t stt = own | ctx->host_state->latched;
+        if (!own) *bytes_out = ctx->host_state->ctl.total_bytes;
         if (stt) {
             HIP_TRY(hipMemsetAsync(&ctx->state->latched, 0, 4, st));
             HIP_TRY(hipStreamSynchronize(st));
             return status_to_error(stt);
         }
-        *bytes_out = ctx->host_state->ctl.total_bytes;
     }
     return COMET_OK;
 }
@@ -560,6 +562,7 @@ int decompress_impl(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_sh
     uint64_t n;
     if (!ctx || !dev_in || !dev_out || !shape_elems(s, &n) || s.w > kMaxW || ((uintptr_t)dev_in & 15u)) return COMET_ERR_INVALID;
     if (bytes < kHeaderBytes) return COMET_ERR_FORMAT;
+    if (n > ctx->max_elems) return COMET_ERR_NOMEM;        // the work buffer holds one residual per element of the context's size
     hipStream_t st = (hipStream_t)stream;
     ReconGeometry g;
     if (!recon_geometry(s, &g)) return COMET_ERR_INVALID;
@@ -906,13 +909,6 @@ int comet_profile_read(comet_ctx *ctx, uint32_t kernel_id, uint32_t *launches, d
     *total_ms = sum;
     return COMET_OK;
 }
-
-#ifdef COMET_DEBUG_TIMING
-int comet_debug_read(comet_ctx *ctx, uint64_t *out32) {
-    if (hipMemcpy(out32, ctx->state->ctl.dbg, sizeof(uint64_t) * 32, hipMemcpyDeviceToHost) != hipSuccess) return COMET_ERR_HIP;
-    return COMET_OK;
-}
-#endif
 
 const char *comet_strerror(int code) {
     switch (code) {

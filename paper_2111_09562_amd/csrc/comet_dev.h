@@ -38,20 +38,7 @@ struct Control {
     uint64_t total_bytes;
     uint32_t n_active;
     uint32_t max_len;
-#ifdef COMET_DEBUG_TIMING
-    uint64_t dbg[32];
-#endif
 };
-
-#ifdef COMET_DEBUG_TIMING
-#define COMET_DBG(ctl, i) do { if (threadIdx.x == 0 && blockIdx.x == 0) (ctl)->dbg[i] = wall_clock64(); } while (0)
-#define COMET_ACC_DECL uint64_t dbg_t0_ = wall_clock64()
-#define COMET_ACC(ctl, i) do { uint64_t now_ = wall_clock64(); if (threadIdx.x == 0 && blockIdx.x == 0) (ctl)->dbg[i] += now_ - dbg_t0_; dbg_t0_ = now_; } while (0)
-#else
-#define COMET_DBG(ctl, i) do {} while (0)
-#define COMET_ACC_DECL do {} while (0)
-#define COMET_ACC(ctl, i) do {} while (0)
-#endif
 
 // Orders the LDS accesses of the lanes of one wavefront (writes before, reads after).  Only the
 // LDS counter is waited for: a fence over all address spaces would also wait for every global

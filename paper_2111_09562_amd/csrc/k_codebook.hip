@@ -320,7 +320,6 @@ __device__ inline void codebook_body(const BookArgs &a, uint32_t m, uint64_t *ke
                                      uint64_t *s_first, uint32_t *s_findex, uint32_t *s_maxlen, uint32_t *s_wc) {
     const uint32_t tid = threadIdx.x;
     const uint32_t nbins = a.nbins;
-    COMET_DBG(a.ctl, 1);
     // ---- 1. compact the active symbols into sort keys (frequency << 16 | symbol) ----
     // (code book reuse: the given length takes the place of the frequency, so the keys are already
     // those of step 5 and steps 2-4 are skipped)
@@ -346,7 +345,6 @@ __device__ inline void codebook_body(const BookArgs &a, uint32_t m, uint64_t *ke
     for (uint32_t i = tid; i < m; i += kBookBlock) iw[i] = 0;
     __syncthreads();
 
-    COMET_DBG(a.ctl, 2);
     const bool reg_sort = LDS && m2 <= (uint32_t)kBookBlock;
     // Canonical order without a second sort: the lengths are scattered into a by-symbol table (in the
     // sort's exchange buffer, free after step 2) and the symbols are then visited in increasing order.
@@ -377,7 +375,6 @@ __device__ inline void codebook_body(const BookArgs &a, uint32_t m, uint64_t *ke
         bitonic_sort(keys, m2);
     }
 
-    COMET_DBG(a.ctl, 3);
     // ---- 3. two-queue merge in rounds ----
     if (m >= 2) {
         if (LDS) {
@@ -388,7 +385,6 @@ __device__ inline void codebook_body(const BookArgs &a, uint32_t m, uint64_t *ke
     }
     __syncthreads();
 
-    COMET_DBG(a.ctl, 4);
     if (by_symbol) {
         for (uint32_t i = tid; i < nbins; i += kBookBlock) s_depth[i] = 0;
         __syncthreads();
@@ -410,7 +406,6 @@ __device__ inline void codebook_body(const BookArgs &a, uint32_t m, uint64_t *ke
     __syncthreads();
     }   // !given
 
-    COMET_DBG(a.ctl, 5);
     // ---- 5. canonical order (length, symbol) ----
     if (!by_symbol) {
         if (reg_sort) {
@@ -430,7 +425,6 @@ __device__ inline void codebook_body(const BookArgs &a, uint32_t m, uint64_t *ke
     }
     ok = __syncthreads_and(ok ? 1 : 0) != 0;
 
-    COMET_DBG(a.ctl, 6);
     // ---- 6. codes and tables ----
     if (!by_symbol) {
         for (uint32_t p = tid; p < m; p += kBookBlock) {
@@ -501,7 +495,6 @@ __global__ __launch_bounds__(kBookBlock) void k_codebook(BookArgs a) {
 
     const uint32_t tid = threadIdx.x;
     const uint32_t nbins = a.nbins;
-    COMET_DBG(a.ctl, 0);
     if (tid < 65) s_cnt[tid] = 0;
     if (tid == 0) s_maxlen = 0;
 
@@ -516,7 +509,6 @@ __global__ __launch_bounds__(kBookBlock) void k_codebook(BookArgs a) {
         codebook_body<false>(a, m, a.scratch.keys, a.scratch.iw, a.scratch.leaf_parent, a.scratch.int_parent, s_x, s_part,
                              s_cnt, s_first, s_findex, &s_maxlen, s_wc);
 
-    COMET_DBG(a.ctl, 7);
     // ---- 7. container layout ----
     if (tid == 0) {
         a.ctl->n_active = m;
@@ -543,7 +535,6 @@ __global__ __launch_bounds__(kBookBlock) void k_codebook(BookArgs a) {
                 for (uint64_t o = h.off_outlier + 8ull * a.ctl->n_rec; o < h.off_payload; ++o) base[o] = 0;
         }
     }
-    COMET_DBG(a.ctl, 8);
 }
 
 // ---------------------------------------------------------------------------
@@ -584,6 +575,7 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
             const float eb = __uint_as_float(h.eb_bits);
             if (!(eb >= 0x1p-100f && eb <= 0x1p100f)) ok = 0;
             if (__float_as_uint(2.0f * eb) != h.ebx2_bits) ok = 0;
+            if (__float_as_uint((float)(1.0 / (double)(2.0f * eb))) != h.r_bits) ok = 0;
             if (ok) {
                 const uint64_t n_chunks = (n + h.chunk_syms - 1u) / h.chunk_syms;
                 if (h.n_chunks != n_chunks) ok = 0;

@@ -94,13 +94,6 @@ __device__ inline uint32_t code_of(uint2 v, int j) {
     return (j & 1) ? (w >> 16) : (w & 0xffffu);
 }
 
-#ifdef COMET_DEBUG_ENC
-#define ENC_DBG(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) a.ctl->dbg[i] = wall_clock64(); \
-                        if (threadIdx.x == 0 && blockIdx.x == gridDim.x - 1) a.ctl->dbg[16 + (i)] = wall_clock64(); } while (0)
-#else
-#define ENC_DBG(i) do {} while (0)
-#endif
-
 }  // namespace
 
 // ---------------------------------------------------------------------------
@@ -116,11 +109,9 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_count(EncodeArgs a) {
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = (uint32_t)lane_id();
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / kWave));   // a scalar: what derives from it stays scalar
-    ENC_DBG(0);
     for (uint32_t i = tid; i <= a.tbl_n; i += kEncBlock) s_tbl[i] = (i < a.tbl_n) ? a.enc[a.tbl_lo + i] : 0ull;
     TableView<FULLTBL> tbl{s_tbl, a.enc, a.tbl_lo, a.tbl_n, a.nbins};
     __syncthreads();
-    ENC_DBG(1);
 
     const uint32_t seg = blockIdx.x;
     const uint32_t c_lo = seg * a.seg_chunks;
@@ -152,7 +143,6 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_count(EncodeArgs a) {
         }
     }
     __syncthreads();
-    ENC_DBG(2);
 
     // counts -> segment-relative exclusive offsets, kEncBlock consecutive chunks at a time
     uint32_t running = 0;
@@ -165,7 +155,6 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_count(EncodeArgs a) {
         running += tot;
     }
     if (tid == 0) a.desc[seg] = running;             // words of this segment
-    ENC_DBG(3);
 }
 
 // ---------------------------------------------------------------------------
@@ -181,7 +170,6 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_pack(EncodeArgs a) {
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = (uint32_t)lane_id();
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / kWave));   // a scalar: what derives from it stays scalar
-    ENC_DBG(4);
     for (uint32_t i = tid; i <= a.tbl_n; i += kEncBlock) s_tbl[i] = (i < a.tbl_n) ? a.enc[a.tbl_lo + i] : 0ull;
     TableView<FULLTBL> tbl{s_tbl, a.enc, a.tbl_lo, a.tbl_n, a.nbins};
     uint32_t *buf = s_buf + wave * kEncBufWords;
@@ -241,7 +229,6 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_pack(EncodeArgs a) {
         }
     }
     __syncthreads();                                  // table and buffers ready
-    ENC_DBG(5);
 
     // A wavefront handles kEncUnroll steps per iteration: their words are contiguous in the
     // payload, so they are assembled side by side in the buffer and leave together.  The codes and
@@ -337,11 +324,9 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_pack(EncodeArgs a) {
     // chunk offsets become absolute (every wavefront has consumed the relative ones of its steps
     // only after this barrier)
     __syncthreads();
-    ENC_DBG(6);
     for (uint32_t idx = tid; idx < nc; idx += kEncBlock) a.chunk_off[c_lo + idx] = (uint32_t)(base + a.chunk_off[c_lo + idx]);
     if (overflow) atomicOr(&a.ctl->status, (uint32_t)ST_CAPACITY);
 
-    ENC_DBG(7);
 }
 
 #define COMET_INST_ENC(S)                                                  \

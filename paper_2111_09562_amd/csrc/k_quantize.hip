@@ -57,7 +57,6 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize(QuantArgs a) {
     const int tid = threadIdx.x;
     const int lane = lane_id();
 
-    COMET_DBG(a.ctl, 20);
     const float *xin = static_cast<const float *>(a.x);      // this kernel takes fp32 only
     for (uint32_t i = tid; i < a.win_n; i += kQuantBlock) s_hist[i] = 0;
     // A workgroup owns one segment of consecutive tiles; segments are handed out by ticket so that
@@ -192,7 +191,6 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize(QuantArgs a) {
         seg_records = pos_it;
     };
 
-    COMET_DBG(a.ctl, 21);
     for (uint32_t tile = tile_lo; tile < tile_hi; ++tile) {
         const uint32_t start = tile * (uint32_t)kQuantTile;
         int32_t dres[kIter][kVec];
@@ -261,7 +259,6 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize(QuantArgs a) {
         }
     }
 
-    COMET_DBG(a.ctl, 22);
     // ---- where this segment's records go: the sum of the counts of all segments in front ----
     // Every workgroup publishes its count once and adds up the counts in front of it; nobody waits
     // for anybody else's sum, only for counts, and those are published by workgroups that took their
@@ -309,7 +306,6 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize(QuantArgs a) {
         }
     }
 
-    COMET_DBG(a.ctl, 23);
     // ---- flush the private histogram and the counters ----
     {
         const uint32_t c = wave_sum<uint32_t>(centre_count);
@@ -329,7 +325,6 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize(QuantArgs a) {
     if (tid == 0 && tot) atomicAdd((unsigned long long *)&a.ctl->nnz, (unsigned long long)tot);
     (void)block_excl_scan<uint32_t, kQuantBlock / kWave>(vrec_local, s_part32, tot);
     if (tid == 0 && tot) atomicAdd((unsigned long long *)&a.ctl->n_vrec, (unsigned long long)tot);
-    COMET_DBG(a.ctl, 24);
 }
 
 template __global__ void k_quantize<true>(QuantArgs);

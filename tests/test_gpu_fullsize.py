@@ -4,11 +4,16 @@ Configs 1-3 are small enough for the CPU oracle to process whole (seconds per
 tensor), so containers and decompressed values are compared bit for bit.
 Config 1 runs in the launch configuration `bench.py` times: five contexts on
 five streams, every call asynchronous, chunks of 64 symbols.
-Config 4 (two tensors of 411 M elements) is checked on what the oracle can
-compute plane by plane -- the decompressed value of an element depends only on
-that element (prequantised value, verbatim flag, re-zero filter) -- plus
-properties that hold at any size, alone and with the two streams overlapped.
+Config 4 (two tensors of 411 M elements, 65536 bins) goes through the oracle
+whole as well (about a minute of CPU per tensor, both at once on two threads):
+container bytes and every decompressed bit, each tensor alone and with the two
+streams overlapped.  Config 3 runs its primary curve and every secondary cell
+(each error bound with 1024 and with 65536 bins).
 """
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 import pytest
 
@@ -26,6 +31,13 @@ def comet():
     from paper_2111_09562_amd import comet as libcomet
     libcomet.lib()
     return libcomet
+
+
+def _progress(request, text):
+    """One line past pytest's capture: the long tests say which step they have finished."""
+    capman = request.config.pluginmanager.getplugin("capturemanager")
+    with capman.global_and_fixture_disabled():
+        print(f"\n[{time.strftime('%H:%M:%S')}] {text}", end="", flush=True)
 
 
 def _check_layer(oracle, x, entry, chunk, cont, out):
@@ -158,7 +170,7 @@ def test_config2_full_size(comet, oracle):
     ctx.close()
 
 
-def test_config3_eb_sweep_and_adaptive_bound(comet, oracle):
+def test_config3_eb_sweep_and_adaptive_bound(comet, oracle, request):
     entries = synth.config3(64)
     x = synth.make(entries[0])
     xd = torch.from_numpy(x).cuda()
@@ -175,17 +187,26 @@ def test_config3_eb_sweep_and_adaptive_bound(comet, oracle):
         info = ctx.comet_peek(cont, used)
         assert info.nnz == np.count_nonzero(x)
     assert all(b > a for a, b in zip(ratios, ratios[1:])), ratios     # a looser bound compresses better
-    # the stress cell: eb = 1e-4 with 1024 bins makes most residuals outliers; if the container outgrows a
-    # buffer of the input's size the call must report it, otherwise the bytes must still match
-    stress = dict(entries[0], eb=1e-4, nbins=1024)
-    want = oracle.compress(x, stress["eb"], stress["nbins"], 64)
-    if want.size > cont.numel():
-        with pytest.raises(comet.CometError) as ei:
-            ctx.comet_compress(xd, stress["eb"], stress["nbins"], cont)
-        assert ei.value.code == comet.ERR_CAPACITY
-    else:
-        used = ctx.comet_compress(xd, stress["eb"], stress["nbins"], cont)
-        assert used == want.size and np.array_equal(cont[:used].cpu().numpy(), want)
+    # secondary cells: every error bound with the smallest and with the largest alphabet.  With 1024 bins at a
+    # tight bound most residuals are outliers and the container outgrows the input; a cell whose container
+    # does not fit the buffer must say so, every other one must match byte for byte and bit for bit
+    big = torch.empty(int(comet.comet_compress_bound(x.shape, 1024, 64)), dtype=torch.uint8, device="cuda")
+    for e in entries:
+        for nb in (1024, 65536):
+            if nb == e["nbins"]:
+                continue
+            cell = dict(e, nbins=nb)
+            want = oracle.compress(x, cell["eb"], nb, 64)
+            if want.size > cont.numel():
+                with pytest.raises(comet.CometError) as ei:
+                    ctx.comet_compress(xd, cell["eb"], nb, cont)
+                assert ei.value.code == comet.ERR_CAPACITY
+            used = ctx.comet_compress(xd, cell["eb"], nb, big)
+            assert used == want.size and np.array_equal(big[:used].cpu().numpy(), want), (cell["eb"], nb)
+            ctx.comet_decompress(big, used, x.shape, out)
+            ctx.comet_sync()
+            assert np.array_equal(out.cpu().numpy().ravel().view(np.uint32), oracle.decompress(want).ravel().view(np.uint32)), (cell["eb"], nb)
+            _progress(request, f"config 3 cell eb={cell['eb']:.1e} nbins={nb}: ratio {x.nbytes / used:.2f}")
     # adaptive error bound (Sec. 3.2-3.3) fed with seeded synthetic layer statistics and the measured R
     rng = np.random.default_rng(3)
     R = np.count_nonzero(x) / x.size
@@ -197,65 +218,78 @@ def test_config3_eb_sweep_and_adaptive_bound(comet, oracle):
     ctx.close()
 
 
-def _expected_values(oracle, x_plane, eb):
-    """What decompression must return for these elements: depends on each element alone."""
-    q, vflag, _ = oracle.prequant(x_plane, eb)
-    y = (q.astype(np.float32) * np.float32(2.0 * np.float32(eb))).astype(np.float32)
-    y = np.where(vflag.astype(bool), x_plane.ravel(), y)
-    y = np.where(np.abs(y) <= np.float32(eb), np.float32(0.0), y)
-    return y.astype(np.float32)
-
-
-def test_config4_two_streams(comet, oracle):
+@pytest.fixture(scope="module")
+def config4_oracle(oracle, request):
+    """Both tensors of config 4 through the oracle, whole: (input, container, decompressed values) each."""
     entries = synth.config4()
+
+    def one(e):
+        x = synth.make(e)
+        _progress(request, f"config 4 seed {e['seed']}: input generated")
+        want = oracle.compress(x, e["eb"], e["nbins"], 64)
+        _progress(request, f"config 4 seed {e['seed']}: oracle container {want.size} bytes")
+        want_x = oracle.decompress(want).ravel()
+        _progress(request, f"config 4 seed {e['seed']}: oracle decompressed")
+        return x, want, want_x
+
+    with ThreadPoolExecutor(max_workers=2) as pool:
+        return entries, list(pool.map(one, entries))
+
+
+def test_config4_two_streams(comet, oracle, config4_oracle, request):
+    entries, ref = config4_oracle
     eb, nbins = entries[0]["eb"], entries[0]["nbins"]
     shape = entries[0]["shape"]
     n = int(np.prod(shape))
     ctxs = [comet.Context(max_elems=n, max_nbins=nbins) for _ in range(2)]
     streams = [torch.cuda.Stream(), torch.cuda.Stream()]
-    xs_host = [synth.make(e) for e in entries]
-    xs = [torch.from_numpy(x).cuda() for x in xs_host]
-    conts = [torch.empty(n * 4 // 16 * 16, dtype=torch.uint8, device="cuda") for _ in xs]
+    xs = [torch.from_numpy(r[0]).cuda() for r in ref]
+    conts = [torch.zeros(n * 4 // 16 * 16, dtype=torch.uint8, device="cuda") for _ in xs]
     outs = [torch.empty_like(x) for x in xs]
     torch.cuda.synchronize()
 
+    def check(i, what):
+        x, want, want_x = ref[i]
+        info = ctxs[i].comet_peek(conts[i], conts[i].numel(), stream=streams[i])
+        assert int(info.total_bytes) == want.size, f"{what}: size of container {i}"
+        assert np.array_equal(conts[i][:want.size].cpu().numpy(), want), f"{what}: container {i} differs from the oracle's"
+        assert info.n_active > 2048 and info.nnz == np.count_nonzero(x)
+        assert 1.5 < 4.0 * n / want.size < 6.0
+
+    def check_values(i, what):
+        x, want, want_x = ref[i]
+        got = outs[i].cpu().numpy().ravel()
+        assert np.array_equal(got.view(np.uint32), want_x.view(np.uint32)), f"{what}: values of tensor {i} differ from the oracle's"
+        assert float((outs[i] - xs[i]).abs().max()) <= float(np.float32(eb))
+
     # each alone
-    used = []
     for i in range(2):
         ctxs[i].comet_compress(xs[i], eb, nbins, conts[i], stream=streams[i], sync=False)
         ctxs[i].comet_decompress(conts[i], conts[i].numel(), shape, outs[i], stream=streams[i])
         ctxs[i].comet_sync(streams[i])
-        used.append(int(ctxs[i].comet_peek(conts[i], conts[i].numel(), stream=streams[i]).total_bytes))
-    alone_cont = [c[:u].clone() for c, u in zip(conts, used)]
-    alone_out = [o.clone() for o in outs]
-
-    P = shape[2] * shape[3]
-    rng = np.random.default_rng(17)
-    for i in range(2):
-        x, o = xs[i], outs[i]
-        # the bound on every element, on the device
-        assert float((o - x).abs().max()) <= float(np.float32(eb))
-        info = ctxs[i].comet_peek(conts[i], used[i])
-        assert info.nnz == int(torch.count_nonzero(x))
-        assert tuple(getattr(info.shape, k) for k in "nchw") == tuple(shape)
-        assert info.n_chunks == (n + 63) // 64 and info.chunk_syms == 64
-        assert 1.5 < 4.0 * n / used[i] < 6.0
-        # sampled planes, bit for bit against the oracle's element-wise arithmetic
-        planes = rng.choice(shape[0] * shape[1], size=24, replace=False)
-        for p in planes:
-            want = _expected_values(oracle, xs_host[i].reshape(-1, P)[p], eb)
-            got = o.view(-1, P)[int(p)].cpu().numpy()
-            assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), f"tensor {i} plane {p}"
+        check(i, "alone")
+        check_values(i, "alone")
+        _progress(request, f"config 4 tensor {i} alone: container and values equal the oracle's")
 
     # overlapped: stream 0 compresses tensor 0 again while stream 1 decompresses tensor 1's container
     outs[1].zero_()
     conts[0].zero_()
     torch.cuda.synchronize()
     ctxs[0].comet_compress(xs[0], eb, nbins, conts[0], stream=streams[0], sync=False)
-    ctxs[1].comet_decompress(conts[1], used[1], shape, outs[1], stream=streams[1])
+    ctxs[1].comet_decompress(conts[1], ref[1][1].size, shape, outs[1], stream=streams[1])
     ctxs[0].comet_sync(streams[0])
     ctxs[1].comet_sync(streams[1])
-    assert torch.equal(conts[0][:used[0]], alone_cont[0])
-    assert torch.equal(outs[1].view(torch.int32), alone_out[1].view(torch.int32))
+    check(0, "overlapped")
+    check_values(1, "overlapped")
+    # and the other way round
+    outs[0].zero_()
+    conts[1].zero_()
+    torch.cuda.synchronize()
+    ctxs[1].comet_compress(xs[1], eb, nbins, conts[1], stream=streams[1], sync=False)
+    ctxs[0].comet_decompress(conts[0], ref[0][1].size, shape, outs[0], stream=streams[0])
+    ctxs[0].comet_sync(streams[0])
+    ctxs[1].comet_sync(streams[1])
+    check(1, "overlapped")
+    check_values(0, "overlapped")
     for c in ctxs:
         c.close()

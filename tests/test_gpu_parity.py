@@ -50,6 +50,9 @@ SHAPES = [
     ((2, 8, 56, 56), "blur"), ((3, 5, 17, 13), "blur"), ((1, 1, 1, 1), "blur"), ((4, 33, 7, 7), "blur"),
     ((1, 2, 224, 224), "blur"), ((2, 3, 5, 1), "blur"), ((1, 1, 1, 4099), "blur"), ((2, 2, 112, 112), "lap"),
     ((5, 7, 14, 14), "blur"), ((1, 3, 200, 3), "lap"),
+    # planes wider than 512 columns (flat-tile quantise kernel, fused decode + LDS-tile reconstruction): the row
+    # above and the up-left neighbour, rows that wrap inside a 16-byte load, the carry between strips of a plane
+    ((1, 2, 9, 600), "blur"), ((2, 1, 40, 1030), "blur"), ((1, 1, 3, 8192), "lap"),
 ]
 
 
@@ -146,8 +149,6 @@ def test_stage_codebook_sweep(comet, ctx, oracle):
     assert len(cases) > 60
     for nb, m, kind, h in cases:
         want_len = oracle.code_lengths(h)
-        if want_len.max() > 57:
-            continue                                            # the container cannot hold such a code (both sides refuse it)
         want_code = oracle.canonical_codes(want_len)
         lens = torch.empty(nb, dtype=torch.uint8, device="cuda")
         codes = torch.empty(nb, dtype=torch.int64, device="cuda")
@@ -155,6 +156,46 @@ def test_stage_codebook_sweep(comet, ctx, oracle):
         ctx.comet_sync()
         assert np.array_equal(lens.cpu().numpy(), want_len), (nb, m, kind)
         assert np.array_equal(codes.cpu().numpy().view(np.uint64), want_code), (nb, m, kind)
+
+
+def _deep_histogram(levels, nbins):
+    """Counts whose Huffman tree is a chain `levels` deep at its far end: Fibonacci numbers as long as they
+    fit 32 bits, then groups of equal counts that add up to the next Fibonacci number (a group merges into
+    one node before the chain reaches it)."""
+    fib = [1, 1]
+    while len(fib) < levels + 2:
+        fib.append(fib[-1] + fib[-2])
+    h = list(fib[:47])
+    for j in range(47, levels + 1):
+        k = 1
+        while fib[j] / k >= 2 ** 32 - 1:
+            k *= 2
+        h += [fib[j] // k + 1] * k
+    assert len(h) <= nbins
+    return np.array(h + [0] * (nbins - len(h)), np.uint32)
+
+
+def test_stage_codebook_longest_code(comet, ctx, oracle):
+    """The longest code word either side accepts has 57 bits.  No tensor below 2^31 elements gets there (a leaf
+    at depth d needs a total count of Fibonacci(d + 2)); a hand-made histogram does: 57 bits is built and
+    equal on both sides, anything deeper is refused by both."""
+    h = _deep_histogram(62, 8192)
+    want_len = oracle.code_lengths(h)
+    assert want_len.max() == 57
+    lens = torch.empty(h.size, dtype=torch.uint8, device="cuda")
+    codes = torch.empty(h.size, dtype=torch.int64, device="cuda")
+    ctx.comet_stage_codebook(dev(h.view(np.int32)), h.size, lens, codes)
+    ctx.comet_sync()
+    assert np.array_equal(lens.cpu().numpy(), want_len)
+    assert np.array_equal(codes.cpu().numpy().view(np.uint64), oracle.canonical_codes(want_len))
+    h = _deep_histogram(64, 16384)
+    with pytest.raises(oracle.OracleError):
+        oracle.code_lengths(h)
+    lens = torch.empty(h.size, dtype=torch.uint8, device="cuda")
+    ctx.comet_stage_codebook(dev(h.view(np.int32)), h.size, lens)
+    with pytest.raises(comet.CometError) as ei:
+        ctx.comet_sync()
+    assert ei.value.code == comet.ERR_INTERNAL
 
 
 @pytest.mark.parametrize("chunk_syms", [64, 128, 256])
@@ -659,6 +700,78 @@ def test_capacity_error_and_recovery(comet, ctx, oracle):
     # the context keeps working, and an exact-size buffer is enough
     out, used = gpu_compress(ctx, comet, x, 1e-3, 1024, 128, capacity=(want.size + 15) // 16 * 16)
     assert np.array_equal(out[:used].cpu().numpy(), want)
+
+
+def test_asynchronous_capacity_error_is_latched(comet, ctx, oracle):
+    """bytes_out == NULL: nothing is reported by the call itself; the pack kernel seals the header with a
+    non-zero status and latches the error, comet_sync returns it once, a decompression of that buffer is
+    refused, and the next synchronising compression is clean again."""
+    x = synth.relu_blur((2, 4, 56, 56), seed=93)
+    want = oracle.compress(x, 1e-3, 1024, 64)
+    ctx.comet_set_chunk_syms(64)
+    xd = dev(x)
+    small = torch.zeros(want.size // 2 // 16 * 16, dtype=torch.uint8, device="cuda")
+    guard = small.numel() - 64
+    assert ctx.comet_compress(xd, 1e-3, 1024, small[:guard], sync=False) is None
+    with pytest.raises(comet.CometError) as ei:
+        ctx.comet_sync()
+    assert ei.value.code == comet.ERR_CAPACITY
+    ctx.comet_sync()                                            # reported once
+    assert int(small[guard:].max()) == 0                        # nothing written past the capacity given
+    with pytest.raises(comet.CometError) as ei:
+        ctx.comet_peek(small, guard)                            # the header says the container is not complete
+    assert ei.value.code == comet.ERR_FORMAT
+    xh = torch.empty(x.size, dtype=torch.float32, device="cuda")
+    ctx.comet_decompress(small, guard, x.shape, xh)
+    with pytest.raises(comet.CometError) as ei:
+        ctx.comet_sync()
+    assert ei.value.code == comet.ERR_FORMAT
+    # an error latched by an asynchronous call is also returned by the next synchronising compression,
+    # which still delivers its own size
+    ctx.comet_compress(xd, 1e-3, 1024, small[:guard], sync=False)
+    big = torch.zeros((want.size + 15) // 16 * 16, dtype=torch.uint8, device="cuda")
+    used = comet.C.c_uint64()
+    rc = comet.lib().comet_compress(ctx._h, comet._ptr(xd), comet._shape(x.shape), comet.C.c_float(1e-3), 1024,
+                                    comet._stream(None), comet._ptr(big), big.numel(), comet.C.byref(used))
+    assert rc == comet.ERR_CAPACITY and used.value == want.size
+    assert np.array_equal(big[:want.size].cpu().numpy(), want)
+    ctx.comet_sync()
+
+
+def test_decompress_refuses_a_tensor_larger_than_the_context(comet, oracle):
+    """The work buffer of a context holds max_elems residuals: a larger shape is an error before any launch."""
+    small = comet.Context(max_elems=1000, max_nbins=1024)
+    x = synth.relu_blur((1, 2, 30, 30), seed=94)
+    buf = oracle.compress(x, 1e-2, 1024, 64)
+    cont = dev(np.concatenate([buf, np.zeros((-buf.size) % 16, np.uint8)]))
+    out = torch.empty(x.size, dtype=torch.float32, device="cuda")
+    with pytest.raises(comet.CometError) as ei:
+        small.comet_decompress(cont, buf.size, x.shape, out)
+    assert ei.value.code == comet.ERR_NOMEM
+    with pytest.raises(comet.CometError) as ei:
+        small.comet_compress(dev(x), 1e-2, 1024, torch.empty(1 << 16, dtype=torch.uint8, device="cuda"))
+    assert ei.value.code == comet.ERR_NOMEM
+    small.comet_sync()
+    small.close()
+
+
+def test_header_constants_are_checked(comet, ctx, oracle):
+    """A header whose reciprocal 1 / (2 eb) does not belong to its eb is refused, as the oracle refuses it."""
+    x = synth.relu_blur((1, 4, 28, 28), seed=95)
+    buf = oracle.compress(x, 1e-2, 1024, 64)
+    bad = buf.copy()
+    bad[48:52] = np.array([np.float32(49.0)], np.float32).view(np.uint8)      # r_bits (1 / 0.02 rounds to 50)
+    with pytest.raises(oracle.OracleError):
+        oracle.decompress(bad)
+    xh = torch.empty(x.size, dtype=torch.float32, device="cuda")
+    pad = np.zeros((-buf.size) % 16, np.uint8)
+    ctx.comet_decompress(dev(np.concatenate([bad, pad])), buf.size, x.shape, xh)
+    with pytest.raises(comet.CometError) as ei:
+        ctx.comet_sync()
+    assert ei.value.code == comet.ERR_FORMAT
+    ctx.comet_decompress(dev(np.concatenate([buf, pad])), buf.size, x.shape, xh)
+    ctx.comet_sync()
+    assert np.array_equal(xh.cpu().numpy().view(np.uint32), oracle.decompress(buf).ravel().view(np.uint32))
 
 
 def test_format_errors(comet, ctx, oracle):

@@ -320,6 +320,32 @@ def test_lengths_closed_forms(oracle):
     assert oracle.code_lengths(np.zeros(16, np.uint32)).tolist() == [0] * 16
 
 
+def test_lengths_longest_code(oracle):
+    """57 bits is the longest code either side builds; a deeper tree is refused.  A leaf at depth d needs a
+    total count of at least Fibonacci(d + 2), so only a hand-made histogram gets there: Fibonacci counts as
+    long as they fit 32 bits, then groups of equal counts that add up to the next Fibonacci number."""
+    fib = [1, 1]
+    while len(fib) < 70:
+        fib.append(fib[-1] + fib[-2])
+    assert fib[59] > 2 ** 31                                   # depth 58 is out of reach of a tensor of < 2^31 elements
+
+    def deep(levels, nbins):
+        h = list(fib[:47])
+        for j in range(47, levels + 1):
+            k = 1
+            while fib[j] / k >= 2 ** 32 - 1:
+                k *= 2
+            h += [fib[j] // k + 1] * k
+        return np.array(h + [0] * (nbins - len(h)), np.uint32)
+
+    h = deep(62, 8192)
+    ln = oracle.code_lengths(h)
+    assert ln.max() == 57 and _kraft(ln) == 1
+    assert int((h.astype(object) * ln.astype(object)).sum()) == _heap_huffman_cost(h)
+    with pytest.raises(oracle.OracleError):
+        oracle.code_lengths(deep(64, 16384))
+
+
 def test_lengths_tie_rule(oracle):
     # worked by hand from the two-queue rule (leaf before internal node on ties)
     assert oracle.code_lengths(np.array([1, 1, 1], np.uint32)).tolist() == [2, 2, 1]
