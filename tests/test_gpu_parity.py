@@ -610,6 +610,46 @@ def test_saved_activation_hook_on_a_toy_conv_stack(comet, oracle):
     c.close()
 
 
+def test_saved_activation_hook_asynchronous(comet, oracle):
+    """exact_size=False never waits for a compression.  A container that fits stands in for the tensor and
+    decompresses to what the oracle says; one that outgrows its buffer (white noise at a tight bound, the
+    low-ratio case of Sec. 3.4) is noticed from its header and the tensor comes back untouched -- never
+    an uninitialised buffer -- and the context is left without a latched error."""
+    from paper_2111_09562_amd.autograd import saved_activations
+    shape = (4, 8, 48, 48)
+    c = comet.Context(max_elems=int(np.prod(shape)), max_nbins=1024)
+    c.comet_set_chunk_syms(64)
+    smooth = torch.from_numpy(synth.relu_blur(shape, seed=5, blur=3, shift=-0.2)).cuda()
+    noise = torch.randn(shape, device="cuda", generator=torch.Generator("cuda").manual_seed(1))
+    hook = saved_activations(c, 1e-2, min_elems=1 << 12, exact_size=False)
+    p1 = hook._pack(smooth)
+    back = hook._unpack(p1)
+    c.comet_sync()
+    want = oracle.decompress(oracle.compress(smooth.cpu().numpy(), 1e-2, 1024, 64))
+    assert np.array_equal(back.cpu().numpy().view(np.uint32), want.view(np.uint32))
+    assert p1.raw is None and hook.packed == 1 and hook.kept_raw == 0
+    hook = saved_activations(c, 1e-5, min_elems=1 << 12, exact_size=False)
+    p2 = hook._pack(noise)
+    back = hook._unpack(p2)
+    assert back.data_ptr() == noise.data_ptr() and torch.equal(back, noise)
+    assert hook.kept_raw == 1 and hook.packed == 0 and hook.unpacked == 0
+    c.comet_sync()                                                  # nothing left latched
+    # and inside autograd: gradients through the asynchronous hook equal those through the waiting one
+    # (up to the summation order of the convolution's own backward kernels)
+    torch.manual_seed(1)
+    conv = torch.nn.Conv2d(8, 8, 3, padding=1).cuda()
+    grads = []
+    for exact in (True, False):
+        conv.zero_grad(set_to_none=True)
+        with saved_activations(c, 1e-2, min_elems=1 << 12, exact_size=exact):
+            loss = conv(torch.relu(conv(smooth))).square().mean()
+        loss.backward()
+        grads.append(conv.weight.grad.detach().clone())
+    c.comet_sync()
+    assert torch.allclose(grads[0], grads[1], rtol=1e-4, atol=1e-7)
+    c.close()
+
+
 def test_calls_can_be_captured_in_a_graph(comet, oracle):
     """The asynchronous calls issue kernels only (no memset, no synchronisation), so a stream capture
     records them.  The graph is replayed several times on new inputs, with eager work between the
