@@ -136,6 +136,20 @@ int comet_compress_16(comet_ctx *ctx, const void *dev_in, int dtype, comet_shape
 int comet_decompress_16(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_shape shape, int dtype,
                         void *stream, void *dev_out);
 
+/* comet_decompress for callers that cannot allocate device memory or hold a context: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  No comet_create is needed and
+ * the call allocates nothing: its control block, decode tables and work buffer live in a static device
+ * array inside the library (about 8.2 MiB, held by every GPU the library runs on until the process
+ * ends), which limits the tensor to COMET_STATIC_MAX_ELEMS elements (COMET_ERR_NOMEM beyond).
+ * dev_in, bytes, shape, stream, dev_out: as for comet_decompress.  dev_status: device memory, one
+ * int32 owned by the caller, or NULL; when the call's kernels have run it holds COMET_OK, or
+ * COMET_ERR_FORMAT if the container was refused (dev_out is then undefined, never out of bounds).
+ * Asynchronous, kernels only.  All calls on one GPU share the one array: calls that can overlap in
+ * time on the same GPU (two streams, two threads) race; issue them on one stream. */
+#define COMET_STATIC_MAX_ELEMS (4u << 20)
+int comet_decompress_static(const void *dev_in, uint64_t bytes, comet_shape shape, void *stream, float *dev_out,
+                            int32_t *dev_status);
+
 /* Wait for `stream` and return (then clear) the first device-side error latched
  * in the context since the last synchronising call. */
 int comet_sync(comet_ctx *ctx, void *stream);

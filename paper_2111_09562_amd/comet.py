@@ -19,7 +19,7 @@ DEFAULT_CHUNK_SYMS = 64
 
 EXPORTS = (
     "comet_create", "comet_destroy", "comet_set_chunk_syms", "comet_compress_bound", "comet_compress", "comet_compress_with_codebook",
-    "comet_decompress", "comet_compress_16", "comet_decompress_16", "comet_sync", "comet_peek", "comet_adapt_defaults", "comet_adapt_eb", "comet_abs_mean",
+    "comet_decompress", "comet_decompress_static", "comet_compress_16", "comet_decompress_16", "comet_sync", "comet_peek", "comet_adapt_defaults", "comet_adapt_eb", "comet_abs_mean",
     "comet_controller_init", "comet_controller_tick", "comet_controller_update",
     "comet_stage_quantize", "comet_stage_codebook", "comet_stage_encode", "comet_stage_decode",
     "comet_stage_reconstruct", "comet_profile_enable", "comet_profile_reset", "comet_profile_read", "comet_strerror",
@@ -74,6 +74,7 @@ def lib():
         L.comet_compress.argtypes = [vp, vp, Shape, C.c_float, C.c_uint32, vp, vp, u64, C.POINTER(u64)]
         L.comet_compress_with_codebook.argtypes = [vp, vp, Shape, C.c_float, C.c_uint32, vp, vp, vp, u64, C.POINTER(u64)]
         L.comet_decompress.argtypes = [vp, vp, u64, Shape, vp, vp]
+        L.comet_decompress_static.argtypes = [vp, u64, Shape, vp, vp, vp]
         L.comet_compress_16.argtypes = [vp, vp, C.c_int, Shape, C.c_float, C.c_uint32, vp, vp, u64, C.POINTER(u64)]
         L.comet_decompress_16.argtypes = [vp, vp, u64, Shape, C.c_int, vp, vp]
         L.comet_sync.argtypes = [vp, vp]
@@ -164,6 +165,16 @@ def comet_adapt_eb(momentum_abs_mean: float, loss_grad_mean: float, nonzero_rati
     out = C.c_float()
     _chk(lib().comet_adapt_eb(C.byref(st), C.byref(cfg), C.byref(out)), "comet_adapt_eb")
     return out.value
+
+
+STATIC_MAX_ELEMS = 4 << 20
+
+
+def comet_decompress_static(container, nbytes: int, shape, out, status=None, stream=None) -> None:
+    """comet_decompress without a context (the library's static scratch array; allocates nothing).
+    status: optional int32 device tensor of one element that receives 0 or ERR_FORMAT."""
+    _chk(lib().comet_decompress_static(_ptr(container), int(nbytes), _shape(shape), _stream(stream), _ptr(out), _ptr(status)),
+         "comet_decompress_static")
 
 
 class ControllerState(C.Structure):

@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -137,7 +138,7 @@ __global__ void k_latch(DevState *s) {           // fold this call's status into
 struct TimedScope {
     comet_ctx *c; hipStream_t st; comet_ctx::Timed *t = nullptr;
     TimedScope(comet_ctx *ctx, hipStream_t s, uint32_t id) : c(ctx), st(s) {
-        if (c->profiling && c->used < c->pool.size()) {
+        if (c && c->profiling && c->used < c->pool.size()) {
             t = &c->pool[c->used++];
             t->id = id;
             (void)hipEventRecord(t->a, st);
@@ -545,24 +546,43 @@ int compress_impl(comet_ctx *ctx, const void *dev_in, int in_type, comet_shape s
 }  // namespace
 
 namespace {
-int decompress_impl(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_shape s, void *stream, void *dev_out, int out_type);
+// What a decompression needs beyond its input and its output: the control block, the decode tables and the
+// residual work buffer, in a context's workspace or in the library's static scratch array.
+struct DecompWs {
+    DevState *state;
+    DecodeTables tables;
+    int16_t *resid;            // one int16 per element, max_elems of them
+    uint64_t max_elems;
+    int num_cu;
+    uint32_t chunk_syms;       // chunk size the launch geometry is estimated with
+    comet_ctx *prof;           // per-kernel timing, or null
+    int32_t *dev_status;       // if set, the tables kernel stores 0 or COMET_ERR_FORMAT there
+};
+int decompress_impl(const DecompWs &ws, const void *dev_in, uint64_t bytes, comet_shape s, void *stream, void *dev_out, int out_type);
+DecompWs ctx_ws(comet_ctx *ctx) {
+    DecompWs ws{};
+    ws.state = ctx->state; ws.tables = ctx->tables; ws.resid = reinterpret_cast<int16_t *>(ctx->codes);
+    ws.max_elems = ctx->max_elems; ws.num_cu = ctx->num_cu; ws.chunk_syms = ctx->chunk_syms; ws.prof = ctx; ws.dev_status = nullptr;
+    return ws;
+}
 }
 
 int comet_decompress(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_shape s, void *stream, float *dev_out) {
-    return decompress_impl(ctx, dev_in, bytes, s, stream, dev_out, 0);
+    if (!ctx) return COMET_ERR_INVALID;
+    return decompress_impl(ctx_ws(ctx), dev_in, bytes, s, stream, dev_out, 0);
 }
 
 int comet_decompress_16(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_shape s, int dtype, void *stream, void *dev_out) {
-    if (dtype != COMET_F16 && dtype != COMET_BF16) return COMET_ERR_INVALID;
-    return decompress_impl(ctx, dev_in, bytes, s, stream, dev_out, dtype);
+    if (!ctx || (dtype != COMET_F16 && dtype != COMET_BF16)) return COMET_ERR_INVALID;
+    return decompress_impl(ctx_ws(ctx), dev_in, bytes, s, stream, dev_out, dtype);
 }
 
 namespace {
-int decompress_impl(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_shape s, void *stream, void *dev_out, int out_type) {
+int decompress_impl(const DecompWs &ws, const void *dev_in, uint64_t bytes, comet_shape s, void *stream, void *dev_out, int out_type) {
     uint64_t n;
-    if (!ctx || !dev_in || !dev_out || !shape_elems(s, &n) || s.w > kMaxW || ((uintptr_t)dev_in & 15u)) return COMET_ERR_INVALID;
+    if (!dev_in || !dev_out || !shape_elems(s, &n) || s.w > kMaxW || ((uintptr_t)dev_in & 15u)) return COMET_ERR_INVALID;
     if (bytes < kHeaderBytes) return COMET_ERR_FORMAT;
-    if (n > ctx->max_elems) return COMET_ERR_NOMEM;        // the work buffer holds one residual per element of the context's size
+    if (n > ws.max_elems) return COMET_ERR_NOMEM;        // the work buffer holds one residual per element of the context's size
     hipStream_t st = (hipStream_t)stream;
     ReconGeometry g;
     if (!recon_geometry(s, &g)) return COMET_ERR_INVALID;
@@ -577,15 +597,15 @@ int decompress_impl(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_sh
     if (out_type != 0 && !fast_path) return COMET_ERR_INVALID;       // 16-bit outputs: planes of at most kDsMaxW columns
     {
         TablesArgs t{};
-        t.len = in + kHeaderBytes; t.nbins = 0; t.t = ctx->tables; t.keys = ctx->book.keys; t.ctl = &ctx->state->ctl;
+        t.len = in + kHeaderBytes; t.nbins = 0; t.t = ws.tables; t.ctl = &ws.state->ctl;
         t.hdr = reinterpret_cast<const Header *>(in);
         t.expect.N = s.n; t.expect.C = s.c; t.expect.H = s.h; t.expect.W = s.w; t.bytes = bytes;
         t.compact_only = fast_path ? 1u : 0u;
         // the only kernel of a decompression that raises status bits: it clears the call's control block itself
         // and latches what it raises, so the call needs neither a fill before nor a kernel after
-        t.reset_ctl = 1u; t.latched = &ctx->state->latched;
+        t.reset_ctl = 1u; t.latched = &ws.state->latched; t.status_out = ws.dev_status;
         {
-            TimedScope ts(ctx, st, COMET_KERNEL_TABLES);
+            TimedScope ts(ws.prof, st, COMET_KERNEL_TABLES);
             hipLaunchKernelGGL(k_decode_tables, dim3(1), dim3(kBookBlock), 0, st, t);
         }
         HIP_TRY(hipGetLastError());
@@ -594,17 +614,17 @@ int decompress_impl(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_sh
         // fast path: Huffman decode into int16 residuals (the code buffer of the context doubles as
         // the work buffer), then scans and stores
         DsArgs d{};
-        d.container = in; d.t = ctx->tables; d.n = n; d.planes = s.n * s.c; d.H = s.h; d.W = s.w; d.divW = make_fastdiv(s.w); d.divL = make_fastdiv(lpr);
-        d.resid = reinterpret_cast<int16_t *>(ctx->codes); d.out = dev_out; d.ctl = &ctx->state->ctl;
+        d.container = in; d.t = ws.tables; d.n = n; d.planes = s.n * s.c; d.H = s.h; d.W = s.w; d.divW = make_fastdiv(s.w); d.divL = make_fastdiv(lpr);
+        d.resid = ws.resid; d.out = dev_out; d.ctl = &ws.state->ctl;
         {
             // groups of 64 chunks, one per wavefront at a time; the same number of groups for every
             // wavefront of a grid that is resident at once (estimated with the context's chunk size)
-            const uint64_t groups = (n + (uint64_t)ctx->chunk_syms * kWave - 1) / ((uint64_t)ctx->chunk_syms * kWave);
-            const uint64_t resident = (uint64_t)ctx->num_cu * 4u * kDsWaves;
+            const uint64_t groups = (n + (uint64_t)ws.chunk_syms * kWave - 1) / ((uint64_t)ws.chunk_syms * kWave);
+            const uint64_t resident = (uint64_t)ws.num_cu * 4u * kDsWaves;
             const uint64_t per_wave = (groups + resident - 1) / resident;
             const uint64_t waves = (groups + per_wave - 1) / per_wave;
             const uint32_t grid = (uint32_t)((waves + kDsWaves - 1) / kDsWaves);
-            TimedScope ts(ctx, st, COMET_KERNEL_DECODE);
+            TimedScope ts(ws.prof, st, COMET_KERNEL_DECODE);
             hipLaunchKernelGGL(k_decode_chunks, dim3(grid), dim3(kDsBlock), (size_t)kDsWaves * kDsStageWords * 4u, st, d);
         }
         HIP_TRY(hipGetLastError());
@@ -614,17 +634,17 @@ int decompress_impl(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_sh
         uint64_t G = 1;
         if (lpr <= 32u) {
             uint64_t passes = kScanStripElems / (ppi * P);
-            const uint64_t spread = (uint64_t)d.planes / ((uint64_t)ppi * ctx->num_cu * 32u);
+            const uint64_t spread = (uint64_t)d.planes / ((uint64_t)ppi * ws.num_cu * 32u);
             if (passes > spread) passes = spread;
             G = ppi * (passes ? passes : 1u);
         }
         d.group_planes = (uint32_t)G;
         const uint64_t units = ((uint64_t)d.planes + G - 1) / G;
         uint64_t grid = (units + kDsWaves - 1) / kDsWaves;
-        const uint64_t cap = (uint64_t)ctx->num_cu * 8u;
+        const uint64_t cap = (uint64_t)ws.num_cu * 8u;
         if (grid > cap) grid = cap;
         const size_t lds = (size_t)kDsWaves * kScanListWords * 4u;
-        TimedScope ts(ctx, st, COMET_KERNEL_RECONSTRUCT);
+        TimedScope ts(ws.prof, st, COMET_KERNEL_RECONSTRUCT);
         const dim3 g3((uint32_t)grid), b3(kDsBlock);
 #define COMET_LAUNCH_SCAN(OUT)                                                                           \
         do {                                                                                             \
@@ -649,19 +669,97 @@ int decompress_impl(comet_ctx *ctx, const void *dev_in, uint64_t bytes, comet_sh
 #undef COMET_LAUNCH_SCAN
     } else {
         ReconArgs a{};
-        a.container = in; a.t = ctx->tables; a.n = n; a.planes = s.n * s.c; a.H = s.h; a.W = s.w; a.divW = make_fastdiv(s.w);
+        a.container = in; a.t = ws.tables; a.n = n; a.planes = s.n * s.c; a.H = s.h; a.W = s.w; a.divW = make_fastdiv(s.w);
         a.planes_per_unit = g.planes_per_unit; a.tile_rows = g.tile_rows; a.n_units = g.n_units; a.pitch = g.pitch; a.use_carry = g.use_carry;
-        a.out = static_cast<float *>(dev_out); a.ctl = &ctx->state->ctl;
+        a.out = static_cast<float *>(dev_out); a.ctl = &ws.state->ctl;
         uint32_t grid = g.n_units;
-        const uint32_t cap = (uint32_t)ctx->num_cu * 32u;
+        const uint32_t cap = (uint32_t)ws.num_cu * 32u;
         if (grid > cap) grid = cap;
-        TimedScope ts(ctx, st, COMET_KERNEL_RECONSTRUCT);
+        TimedScope ts(ws.prof, st, COMET_KERNEL_RECONSTRUCT);
         hipLaunchKernelGGL(k_reconstruct<0>, dim3(grid), dim3(kDecBlock), g.lds, st, a);
     }
     HIP_TRY(hipGetLastError());
     return COMET_OK;
 }
 }  // namespace
+
+// ---------------------------------------------------------------------------
+// decompression without a context, for callers that cannot allocate
+// ---------------------------------------------------------------------------
+namespace {
+constexpr uint64_t kStaticMaxElems = COMET_STATIC_MAX_ELEMS;
+// layout of the static scratch array: control block | decode tables | residual work buffer
+constexpr size_t kSsState = 0;
+constexpr size_t kSsLimit = 512;
+constexpr size_t kSsFirst = kSsLimit + 8 * 72;
+constexpr size_t kSsFindex = kSsFirst + 8 * 72;
+constexpr size_t kSsMeta = kSsFindex + 4 * 72 + 32;          // 16-byte aligned
+constexpr size_t kSsLut = kSsMeta + 64;
+constexpr size_t kSsLut16 = kSsLut + 4 * kLutSize;
+constexpr size_t kSsSorted = kSsLut16 + 2 * kLut16Size;
+constexpr size_t kSsResid = (kSsSorted + 2 * (size_t)kMaxBins + 255) / 256 * 256;
+constexpr size_t kSsBytes = kSsResid + 2 * (size_t)kStaticMaxElems + 256;
+static_assert(sizeof(DevState) <= kSsLimit && kSsMeta % 16 == 0 && kSsLut % 16 == 0, "scratch layout");
+constexpr int kStaticMaxDevices = 64;
+struct StaticDev { void *ptr; int num_cu; };
+StaticDev g_static_dev[kStaticMaxDevices];       // filled once per device, under the lock
+bool g_static_ready[kStaticMaxDevices];
+std::mutex g_static_lock;
+}  // namespace
+
+// Device memory of comet_decompress_static: every GPU the library runs on holds its own copy until
+// the process ends.  In host code this name is a stand-in, not a device address; the address comes
+// from hipGetSymbolAddress (static_scratch below).
+static __device__ __align__(256) unsigned char scratch[kSsBytes];
+
+namespace {
+// The current device's copy of `scratch` (looked up once per device, with that device current).
+int static_scratch(StaticDev *out) {
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kStaticMaxDevices) return COMET_ERR_INVALID;
+    std::lock_guard<std::mutex> guard(g_static_lock);
+    if (!g_static_ready[dev]) {
+        void *ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return COMET_ERR_HIP;
+        int cus = 0;
+        HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        // the kernel for planes wider than 512 columns needs more than 64 KB of dynamic LDS
+        HIP_TRY(hipFuncSetAttribute((const void *)k_reconstruct<0>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
+        g_static_dev[dev].ptr = ptr;
+        g_static_dev[dev].num_cu = cus > 0 ? cus : 256;
+        g_static_ready[dev] = true;
+    }
+    *out = g_static_dev[dev];
+    return COMET_OK;
+}
+}  // namespace
+
+int comet_decompress_static(const void *dev_in, uint64_t bytes, comet_shape s, void *stream, float *dev_out, int32_t *dev_status) {
+    uint64_t n;
+    if (!shape_elems(s, &n)) return COMET_ERR_INVALID;
+    if (n > kStaticMaxElems) return COMET_ERR_NOMEM;         // the static work buffer holds COMET_STATIC_MAX_ELEMS residuals
+    StaticDev sd{};
+    const int rc = static_scratch(&sd);
+    if (rc) return rc;
+    uint8_t *base = static_cast<uint8_t *>(sd.ptr);
+    DecompWs ws{};
+    ws.state = reinterpret_cast<DevState *>(base + kSsState);
+    ws.tables.limit = reinterpret_cast<uint64_t *>(base + kSsLimit);
+    ws.tables.first_code = reinterpret_cast<uint64_t *>(base + kSsFirst);
+    ws.tables.first_index = reinterpret_cast<uint32_t *>(base + kSsFindex);
+    ws.tables.meta = reinterpret_cast<uint32_t *>(base + kSsMeta);
+    ws.tables.lut = reinterpret_cast<uint32_t *>(base + kSsLut);
+    ws.tables.lut16 = reinterpret_cast<uint16_t *>(base + kSsLut16);
+    ws.tables.sorted = reinterpret_cast<uint16_t *>(base + kSsSorted);
+    ws.resid = reinterpret_cast<int16_t *>(base + kSsResid);
+    ws.max_elems = kStaticMaxElems; ws.num_cu = sd.num_cu; ws.chunk_syms = COMET_DEFAULT_CHUNK_SYMS;
+    ws.prof = nullptr; ws.dev_status = dev_status;
+    // Nothing in the array has to start at zero: the tables kernel clears the control block and stores
+    // the status, every table entry and residual that is read has been written by this call.
+    return decompress_impl(ws, dev_in, bytes, s, stream, dev_out, 0);
+}
 
 int comet_sync(comet_ctx *ctx, void *stream) {
     if (!ctx) return COMET_ERR_INVALID;
@@ -834,7 +932,7 @@ int comet_stage_decode(comet_ctx *ctx, const uint8_t *dev_len, uint32_t nbins, c
     hipStream_t st = (hipStream_t)stream;
     HIP_TRY(hipMemsetAsync(ctx->zero_region, 0, sizeof(Control), st));
     TablesArgs t{};
-    t.len = dev_len; t.nbins = nbins; t.t = ctx->tables; t.keys = ctx->book.keys; t.ctl = &ctx->state->ctl; t.hdr = nullptr;
+    t.len = dev_len; t.nbins = nbins; t.t = ctx->tables; t.ctl = &ctx->state->ctl; t.hdr = nullptr;
     hipLaunchKernelGGL(k_decode_tables, dim3(1), dim3(kBookBlock), 0, st, t);
     HIP_TRY(hipGetLastError());
     ReconArgs a{};

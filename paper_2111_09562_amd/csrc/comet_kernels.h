@@ -146,12 +146,12 @@ struct TablesArgs {
     const uint8_t *len;        // u8[nbins]
     uint32_t nbins;
     DecodeTables t;
-    uint64_t *keys;            // sort scratch (global), >= 65536 entries
     uint32_t compact_only;     // 1: the caller decodes with k_decode_chunks, which uses the compact table whenever it
                                //    exists, so the general table need not be filled in that case
     Control *ctl;
     uint32_t reset_ctl;        // 1: this kernel is the first of its call and clears *ctl itself (no separate fill before it)
     uint32_t *latched;         // if set, a status bit raised here also goes into this persistent word (no separate kernel after the call)
+    int32_t *status_out;       // if set: receives 0, or -3 (the library's code for a malformed container) if the header or the table is refused
     // container validation (null = stage call)
     const Header *hdr;
     Header expect;             // shape the caller passed

@@ -555,11 +555,13 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
 
     const uint32_t tid = threadIdx.x;
     if (a.reset_ctl && tid < sizeof(Control) / 4u) reinterpret_cast<uint32_t *>(a.ctl)[tid] = 0u;   // before the first barrier: nothing has raised a bit yet
-    auto raise_format = [&]() {
+    auto raise_format = [&]() {                     // thread 0 only
         atomicOr(&a.ctl->status, (uint32_t)ST_FORMAT);
         if (a.latched) atomicOr(a.latched, (uint32_t)ST_FORMAT);
+        if (a.status_out) *a.status_out = -3;
     };
     if (tid == 0) {
+        if (a.status_out) *a.status_out = 0;
         uint32_t ok = 1;
         s_nbins = a.nbins;
         if (a.hdr) {
