@@ -232,7 +232,8 @@ int comet_stage_reconstruct(comet_ctx *ctx, const uint16_t *dev_codes, const uin
  * 0 quantize (sweep), 1 codebook, 2 encode (pack pass), 3 decode tables,
  * 4 reconstruct (scans + store; for planes wider than 512 columns the fused
  * decode + reconstruct kernel), 5 Huffman decode, 6 gather of the outlier
- * records, 7 encode (count pass).
+ * records, 7 encode (count pass), 8 decompression in one kernel (Huffman decode, reconstruction and
+ * store; containers with chunks of 64 symbols and planes of at most 512 columns).
  * At most 16384 launches are kept between resets; further ones are not timed. */
 #define COMET_KERNEL_QUANTIZE 0
 #define COMET_KERNEL_CODEBOOK 1
@@ -242,7 +243,8 @@ int comet_stage_reconstruct(comet_ctx *ctx, const uint16_t *dev_codes, const uin
 #define COMET_KERNEL_DECODE 5
 #define COMET_KERNEL_GATHER 6
 #define COMET_KERNEL_ENCODE_COUNT 7
-#define COMET_KERNEL_COUNT 8
+#define COMET_KERNEL_FUSED 8
+#define COMET_KERNEL_COUNT 9
 int comet_profile_enable(comet_ctx *ctx, int enable);
 int comet_profile_reset(comet_ctx *ctx);
 int comet_profile_read(comet_ctx *ctx, uint32_t kernel_id, uint32_t *launches /* host */, double *total_ms /* host */);

@@ -25,7 +25,7 @@ EXPORTS = (
     "comet_stage_reconstruct", "comet_profile_enable", "comet_profile_reset", "comet_profile_read", "comet_strerror",
 )
 KERNEL_NAMES = ("k_quantize_rows", "k_codebook", "k_encode_pack", "k_decode_tables", "k_scan_store", "k_decode_chunks",
-                "k_gather_records", "k_encode_count")
+                "k_gather_records", "k_encode_count", "k_decode_scan")
 
 
 class Shape(C.Structure):

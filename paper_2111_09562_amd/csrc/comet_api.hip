@@ -173,6 +173,7 @@ bool recon_geometry(comet_shape s, ReconGeometry *g) {
     return g->lds <= 96u * 1024u;
 }
 
+int fused_opt_in();          // k_decode_scan: opt in to its dynamic LDS size (defined with the decompression)
 // segments of the encode kernel: (chunks per segment, number of segments)
 void encode_geometry(const comet_ctx *ctx, uint64_t n_chunks, uint32_t *seg_chunks, uint32_t *n_seg);
 // Work split of the quantise kernel.  rows: the row-walking kernel (planes up to kQuantRowsMaxW
@@ -391,6 +392,7 @@ int comet_create(comet_ctx **out, uint64_t max_elems, uint32_t max_nbins) {
         const uint64_t o_findex = o; o += 4ull * 72;
         const uint64_t o_lut = o; o += 4ull * kLutSize;
         const uint64_t o_lut16 = o; o += 2ull * kLut16Size;
+        const uint64_t o_sub16 = o; o += 2ull * kSubEntries;
         const uint64_t o_meta = o; o += 64;
         const uint64_t o_sorted = o; o += 2ull * kMaxBins;
         uint8_t *blob = nullptr;
@@ -402,6 +404,7 @@ int comet_create(comet_ctx **out, uint64_t max_elems, uint32_t max_nbins) {
         c->tables.first_index = (uint32_t *)(blob + o_findex); c->tables.lut = (uint32_t *)(blob + o_lut);
         c->tables.meta = (uint32_t *)(blob + o_meta); c->tables.sorted = (uint16_t *)(blob + o_sorted);
         c->tables.lut16 = (uint16_t *)(blob + o_lut16);
+        c->tables.sub16 = (uint16_t *)(blob + o_sub16);
     }
     if ((e = hipHostMalloc((void **)&c->host_state, sizeof(DevState) + sizeof(Header), hipHostMallocDefault)) != hipSuccess)
         return fail(COMET_ERR_NOMEM);
@@ -412,6 +415,7 @@ int comet_create(comet_ctx **out, uint64_t max_elems, uint32_t max_nbins) {
         return fail(hip_fail(e, "hipFuncSetAttribute(k_reconstruct<0>)"));
     if ((e = hipFuncSetAttribute((const void *)k_reconstruct<1>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024)) != hipSuccess)
         return fail(hip_fail(e, "hipFuncSetAttribute(k_reconstruct<1>)"));
+    if (fused_opt_in() != COMET_OK) return fail(COMET_ERR_HIP);
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&c->occ_quant, k_quantize<true>, kQuantBlock, 4096 + kQuantRecLds * 8) != hipSuccess || c->occ_quant < 1) c->occ_quant = 4;
     (void)rc;
     *out = c;
@@ -578,6 +582,66 @@ int comet_decompress_16(comet_ctx *ctx, const void *dev_in, uint64_t bytes, come
 }
 
 namespace {
+constexpr size_t kFuLdsBytes = (size_t)kFuWaves * kFuRegionWords * 4u;
+
+// instantiation of k_decode_scan for (64-lane segments per row, lane mapping, output type, columns per lane)
+const void *fused_kernel(int nseg, int mode, int out, int vec) {
+#define COMET_FU(NS, MO, OU, VE) if (nseg == NS && mode == MO && out == OU && vec == VE) return (const void *)k_decode_scan<NS, MO, OU, VE>;
+#define COMET_FU_OUT(OU)                                                                     \
+    COMET_FU(1, 0, OU, 1) COMET_FU(1, 1, OU, 1) COMET_FU(1, 2, OU, 1) COMET_FU(2, 2, OU, 1) \
+    COMET_FU(4, 2, OU, 1) COMET_FU(8, 2, OU, 1) COMET_FU(1, 0, OU, 2) COMET_FU(1, 1, OU, 2) \
+    COMET_FU(1, 2, OU, 2) COMET_FU(2, 2, OU, 2) COMET_FU(4, 2, OU, 2)
+    COMET_FU_OUT(0) COMET_FU_OUT(1) COMET_FU_OUT(2)
+#undef COMET_FU_OUT
+#undef COMET_FU
+    return nullptr;
+}
+
+// every instantiation needs more than 64 KB of dynamic LDS: opt in once per device
+int fused_opt_in() {
+    static const int nsegs[] = {1, 2, 4, 8};
+    for (int out = 0; out < 3; ++out)
+        for (int vec = 1; vec <= 2; ++vec)
+            for (int mode = 0; mode < 3; ++mode)
+                for (int ns : nsegs) {
+                    const void *fn = fused_kernel(ns, mode, out, vec);
+                    if (fn) HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFuLdsBytes));
+                }
+    return COMET_OK;
+}
+
+// Work split of k_decode_scan: units of G whole planes, one wavefront per unit at a time.  A unit costs as
+// many strips (decode phases of 64 symbols per lane) as its elements take at about 4032 per strip, and the
+// launch takes as long as its busiest wavefront: G minimises (units per wavefront) * (strips per unit).
+struct FusedGeom { uint32_t G, n_units, grid; };
+FusedGeom fused_geometry(int num_cu, comet_shape s) {
+    const uint64_t planes = (uint64_t)s.n * s.c, P = (uint64_t)s.h * s.w;
+    const uint64_t waves = (uint64_t)num_cu * kFuWaves;
+    auto strips_of = [&](uint64_t G) {                       // a unit that starts on a chunk boundary
+        uint64_t a = 0, cnt = 0;
+        const uint64_t end = G * P;
+        while (a < end) {
+            uint64_t lim = ((a >> 6) + 64u) * 64u / s.w * s.w;
+            a = lim < end ? lim : end;
+            ++cnt;
+        }
+        return cnt;
+    };
+    uint64_t g_max = 2u * ((planes + waves - 1) / waves) + 2u * (4096u / P) + 2u;
+    if (g_max > planes) g_max = planes;
+    uint64_t best_g = 1, best_cost = ~0ull;
+    for (uint64_t G = 1; G <= g_max; ++G) {
+        const uint64_t units = (planes + G - 1) / G;
+        const uint64_t cost = ((units + waves - 1) / waves) * strips_of(G);
+        if (cost < best_cost) { best_cost = cost; best_g = G; }
+    }
+    FusedGeom f;
+    f.G = (uint32_t)best_g;
+    f.n_units = (uint32_t)((planes + best_g - 1) / best_g);
+    f.grid = (uint32_t)(f.n_units < (uint64_t)num_cu ? f.n_units : (uint64_t)num_cu);
+    return f;
+}
+
 int decompress_impl(const DecompWs &ws, const void *dev_in, uint64_t bytes, comet_shape s, void *stream, void *dev_out, int out_type) {
     uint64_t n;
     if (!dev_in || !dev_out || !shape_elems(s, &n) || s.w > kMaxW || ((uintptr_t)dev_in & 15u)) return COMET_ERR_INVALID;
@@ -595,12 +659,17 @@ int decompress_impl(const DecompWs &ws, const void *dev_in, uint64_t bytes, come
     const uint32_t ppi = lpr <= 16u ? 4u * (16u / lpr) : (lpr <= 32u ? 2u : 1u);
     const bool fast_path = s.w <= kDsMaxW && (uint64_t)ppi * s.h * s.w < (1ull << 28);
     if (out_type != 0 && !fast_path) return COMET_ERR_INVALID;       // 16-bit outputs: planes of at most kDsMaxW columns
+    // Chunks of 64 symbols (what the caller's context compresses with tells what to expect) go through the
+    // single fused kernel; it leaves a container with another chunk size alone, and the kernels launched
+    // behind it, which take any chunk size, leave one with 64 alone.
+    const bool fused = fast_path && ws.chunk_syms == 64u;
     {
         TablesArgs t{};
         t.len = in + kHeaderBytes; t.nbins = 0; t.t = ws.tables; t.ctl = &ws.state->ctl;
         t.hdr = reinterpret_cast<const Header *>(in);
         t.expect.N = s.n; t.expect.C = s.c; t.expect.H = s.h; t.expect.W = s.w; t.bytes = bytes;
         t.compact_only = fast_path ? 1u : 0u;
+        t.general_unless_chunk64 = (fused && out_type == 0) ? 1u : 0u;   // the kernel behind k_decode_scan reads the general table
         // the only kernel of a decompression that raises status bits: it clears the call's control block itself
         // and latches what it raises, so the call needs neither a fill before nor a kernel after
         t.reset_ctl = 1u; t.latched = &ws.state->latched; t.status_out = ws.dev_status;
@@ -610,10 +679,37 @@ int decompress_impl(const DecompWs &ws, const void *dev_in, uint64_t bytes, come
         }
         HIP_TRY(hipGetLastError());
     }
-    if (fast_path) {
-        // fast path: Huffman decode into int16 residuals (the code buffer of the context doubles as
+    if (fused) {
+        FuArgs f{};
+        f.container = in; f.t = ws.tables; f.n = n; f.planes = s.n * s.c; f.H = s.h; f.W = s.w;
+        f.divW = make_fastdiv(s.w); f.divH = make_fastdiv(s.h); f.divL = make_fastdiv(lpr);
+        f.divSpr = make_fastdiv(lpr <= 16u ? 16u / lpr : 1u);
+        f.out = dev_out; f.ctl = &ws.state->ctl;
+        const FusedGeom fg = fused_geometry(ws.num_cu, s);
+        f.G = fg.G; f.n_units = fg.n_units;
+        const int mode = lpr <= 16u ? 0 : (lpr <= 32u ? 1 : 2);
+        const int nseg = lpr <= 64u ? 1 : (lpr <= 128u ? 2 : (lpr <= 256u ? 4 : 8));
+        const void *fn = fused_kernel(nseg, mode, out_type, (int)vec);
+        if (!fn) return COMET_ERR_INTERNAL;
+        void *kargs[] = {&f};
+        TimedScope ts(ws.prof, st, COMET_KERNEL_FUSED);
+        HIP_TRY(hipLaunchKernel(fn, dim3(fg.grid), dim3(kFuBlock), kargs, kFuLdsBytes, st));
+    }
+    if (fused && out_type == 0) {
+        // any other chunk size: the general kernel, on a small grid (it is rarely needed)
+        ReconArgs a{};
+        a.container = in; a.t = ws.tables; a.n = n; a.planes = s.n * s.c; a.H = s.h; a.W = s.w; a.divW = make_fastdiv(s.w);
+        a.planes_per_unit = g.planes_per_unit; a.tile_rows = g.tile_rows; a.n_units = g.n_units; a.pitch = g.pitch; a.use_carry = g.use_carry;
+        a.out = static_cast<float *>(dev_out); a.ctl = &ws.state->ctl; a.skip_chunk64 = 1u;
+        uint32_t grid = g.n_units;
+        const uint32_t cap = (uint32_t)ws.num_cu * 4u;
+        if (grid > cap) grid = cap;
+        hipLaunchKernelGGL(k_reconstruct<0>, dim3(grid), dim3(kDecBlock), g.lds, st, a);
+    } else if (fast_path) {
+        // Huffman decode into int16 residuals (the code buffer of the context doubles as
         // the work buffer), then scans and stores
         DsArgs d{};
+        d.skip_chunk64 = fused ? 1u : 0u;
         d.container = in; d.t = ws.tables; d.n = n; d.planes = s.n * s.c; d.H = s.h; d.W = s.w; d.divW = make_fastdiv(s.w); d.divL = make_fastdiv(lpr);
         d.resid = ws.resid; d.out = dev_out; d.ctl = &ws.state->ctl;
         {
@@ -696,7 +792,8 @@ constexpr size_t kSsFindex = kSsFirst + 8 * 72;
 constexpr size_t kSsMeta = kSsFindex + 4 * 72 + 32;          // 16-byte aligned
 constexpr size_t kSsLut = kSsMeta + 64;
 constexpr size_t kSsLut16 = kSsLut + 4 * kLutSize;
-constexpr size_t kSsSorted = kSsLut16 + 2 * kLut16Size;
+constexpr size_t kSsSub16 = kSsLut16 + 2 * kLut16Size;
+constexpr size_t kSsSorted = kSsSub16 + 2 * kSubEntries;
 constexpr size_t kSsResid = (kSsSorted + 2 * (size_t)kMaxBins + 255) / 256 * 256;
 constexpr size_t kSsBytes = kSsResid + 2 * (size_t)kStaticMaxElems + 256;
 static_assert(sizeof(DevState) <= kSsLimit && kSsMeta % 16 == 0 && kSsLut % 16 == 0, "scratch layout");
@@ -727,6 +824,10 @@ int static_scratch(StaticDev *out) {
         HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
         // the kernel for planes wider than 512 columns needs more than 64 KB of dynamic LDS
         HIP_TRY(hipFuncSetAttribute((const void *)k_reconstruct<0>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
+        {
+            const int rc = fused_opt_in();
+            if (rc) return rc;
+        }
         g_static_dev[dev].ptr = ptr;
         g_static_dev[dev].num_cu = cus > 0 ? cus : 256;
         g_static_ready[dev] = true;
@@ -752,6 +853,7 @@ int comet_decompress_static(const void *dev_in, uint64_t bytes, comet_shape s, v
     ws.tables.meta = reinterpret_cast<uint32_t *>(base + kSsMeta);
     ws.tables.lut = reinterpret_cast<uint32_t *>(base + kSsLut);
     ws.tables.lut16 = reinterpret_cast<uint16_t *>(base + kSsLut16);
+    ws.tables.sub16 = reinterpret_cast<uint16_t *>(base + kSsSub16);
     ws.tables.sorted = reinterpret_cast<uint16_t *>(base + kSsSorted);
     ws.resid = reinterpret_cast<int16_t *>(base + kSsResid);
     ws.max_elems = kStaticMaxElems; ws.num_cu = sd.num_cu; ws.chunk_syms = COMET_DEFAULT_CHUNK_SYMS;

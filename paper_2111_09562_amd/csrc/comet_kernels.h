@@ -128,6 +128,7 @@ constexpr int kLut16Bits = 12;
 constexpr uint32_t kLut16Size = 1u << kLut16Bits;
 constexpr uint32_t kLut16MaxBins = 4096;
 constexpr int32_t kLut16Escape = -2048;    // residual value that stands for the escape symbol in the compact table
+constexpr uint32_t kSubEntries = 2048;     // second level of the compact table: entries of all sub-tables together
 
 struct DecodeTables {          // all in the workspace (global memory)
     uint32_t *lut;             // kLutSize entries: (residual << 8) | length with residual = symbol - radius
@@ -137,7 +138,9 @@ struct DecodeTables {          // all in the workspace (global memory)
     uint64_t *first_code;      // [65]
     uint32_t *first_index;     // [65]: position of the first symbol of each length in `sorted`
     uint16_t *lut16;           // kLut16Size entries: (residual << 4) | length, residual in 12 signed bits (kLut16Escape for
-                               // the escape symbol); length 0 = longer code, the residual field is the shortest length
+                               // the escape symbol); length 0 = longer code: the upper 12 bits are (offset / 2) << 2 | width
+                               // code of the prefix's sub-table in sub16 (width 1, 2, 4, 6 bits), all zero if it has none
+    uint16_t *sub16;           // kSubEntries entries: (residual << 4) | (length - kLut16Bits), 0 = longer still
     uint16_t *sorted;          // symbols in canonical (length, symbol) order
     uint32_t *meta;            // [0] max_len, [1] n_active, [2] min_len, [3] radius, [4] 1 if lut16 is valid
 };
@@ -146,8 +149,9 @@ struct TablesArgs {
     const uint8_t *len;        // u8[nbins]
     uint32_t nbins;
     DecodeTables t;
-    uint32_t compact_only;     // 1: the caller decodes with k_decode_chunks, which uses the compact table whenever it
+    uint32_t compact_only;     // 1: the caller decodes with kernels that use the compact table whenever it
                                //    exists, so the general table need not be filled in that case
+    uint32_t general_unless_chunk64;   // 1: ... except for a container whose chunks are not 64 symbols (its kernel reads the general table)
     Control *ctl;
     uint32_t reset_ctl;        // 1: this kernel is the first of its call and clears *ctl itself (no separate fill before it)
     uint32_t *latched;         // if set, a status bit raised here also goes into this persistent word (no separate kernel after the call)
@@ -187,6 +191,7 @@ struct ReconArgs {
     uint32_t tile_rows;            // rows held in LDS
     uint32_t use_carry;            // 1 if planes are cut into strips (column carry in LDS)
     float *out;
+    uint32_t skip_chunk64;         // 1: do nothing for a container with chunks of 64 symbols (k_decode_scan has handled it)
     uint16_t *codes_out;           // stage decode: write codes instead of reconstructing
     Control *ctl;
 };
@@ -211,6 +216,7 @@ struct DsArgs {
     uint32_t group_planes;     // scan kernel, planes of at most 32 columns: whole planes per unit of work (a multiple of the planes side by side in a wavefront)
     FastDiv divW;
     FastDiv divL;              // scan kernel: lanes per row (W / columns per lane)
+    uint32_t skip_chunk64;     // 1: do nothing for a container with chunks of 64 symbols (k_decode_scan has handled it)
     int16_t *resid;            // work buffer: one int16 residual per element (-32768 = escaped)
     void *out;                 // fp32, or IEEE half / bfloat16 (template parameter OUT of the scan kernel)
     Control *ctl;
@@ -220,5 +226,29 @@ __global__ void k_decode_chunks(DsArgs a);
 // the fp32 result rounded to nearest even)
 // VEC: adjacent columns per lane (2: even W, output aligned to two elements); the lane mapping follows W / VEC
 template <int NSEG, int MODE, int OUT = 0, int VEC = 1> __global__ void k_scan_store(DsArgs a);
+
+// ---- decode + reconstruct in one kernel (planes up to 512 columns, chunks of 64 symbols) ----------
+constexpr int kFuWaves = 12;                          // wavefronts per workgroup, each working on its own; one workgroup per CU
+constexpr int kFuBlock = kFuWaves * kWave;
+constexpr uint32_t kFuPitch = 36u;                    // words of LDS per chunk row: 32 of residuals, 4 of padding (16-byte rows, no bank conflicts)
+constexpr uint32_t kFuStripWords = 64u * kFuPitch;    // a strip's residuals; before that, the words of its chunks
+constexpr uint32_t kFuEscEntries = 512u;              // values of a strip's escaped residuals kept in LDS
+constexpr uint32_t kFuRegionWords = kFuStripWords + kFuEscEntries;
+
+struct FuArgs {
+    const uint8_t *container;
+    DecodeTables t;
+    uint64_t n;
+    uint32_t planes, H, W;
+    uint32_t G;                // whole planes per unit of work (one wavefront walks a unit)
+    uint32_t n_units;
+    FastDiv divW, divH;
+    FastDiv divL;              // lanes per row (W / columns per lane)
+    FastDiv divSpr;            // rows of at most 16 lanes: rows side by side in 16 lanes
+    void *out;                 // fp32, or IEEE half / bfloat16 (template parameter OUT)
+    Control *ctl;
+};
+// NSEG, MODE, OUT, VEC as for k_scan_store; MODE 0 / 1 walk several consecutive rows per step
+template <int NSEG, int MODE, int OUT = 0, int VEC = 1> __global__ void k_decode_scan(FuArgs a);
 
 }  // namespace comet

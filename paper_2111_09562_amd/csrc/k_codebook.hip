@@ -548,10 +548,13 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
     __shared__ uint64_t s_first[65];
     __shared__ uint64_t s_limit[65];
     __shared__ uint32_t s_findex[65];
-    __shared__ uint32_t s_ok, s_maxlen, s_nbins;
+    __shared__ uint32_t s_ok, s_maxlen, s_nbins, s_chunk;
     __shared__ uint16_t s_sorted[kBookBlock * 2];                   // symbols in canonical order (alphabets up to this size)
     __shared__ uint32_t s_wc[(kBookBlock / kWave) * 64];            // symbols per (wavefront, length) of the current 1024 symbols
     __shared__ uint32_t s_run[65];                                  // symbols per length in front of them
+    __shared__ uint32_t s_scan[kBookBlock / kWave];
+    __shared__ uint16_t s_ent[kLut16Size];                          // first level of the compact table
+    __shared__ uint16_t s_owner[kSubEntries];                       // second level: the prefix every entry belongs to
 
     const uint32_t tid = threadIdx.x;
     if (a.reset_ctl && tid < sizeof(Control) / 4u) reinterpret_cast<uint32_t *>(a.ctl)[tid] = 0u;   // before the first barrier: nothing has raised a bit yet
@@ -564,6 +567,7 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
         if (a.status_out) *a.status_out = 0;
         uint32_t ok = 1;
         s_nbins = a.nbins;
+        s_chunk = 64u;
         if (a.hdr) {
             const Header h = *a.hdr;
             const Header &e = a.expect;
@@ -574,6 +578,7 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
             if (h.nbins < 4u || h.nbins > 65536u || (h.nbins & 1u)) ok = 0;
             s_nbins = h.nbins;
             if (h.chunk_syms == 0) ok = 0;
+            s_chunk = h.chunk_syms;
             const float eb = __uint_as_float(h.eb_bits);
             if (!(eb >= 0x1p-100f && eb <= 0x1p100f)) ok = 0;
             if (__float_as_uint(2.0f * eb) != h.ebx2_bits) ok = 0;
@@ -684,7 +689,8 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
     const uint32_t mx = s_maxlen;
     const int32_t radius = (int32_t)(nbins / 2u);
     const bool compact = nbins <= kLut16MaxBins;
-    for (uint32_t e = tid; e < ((compact && a.compact_only) ? 0u : kLutSize); e += kBookBlock) {
+    const bool skip_general = compact && a.compact_only && !(a.general_unless_chunk64 && s_chunk != 64u);
+    for (uint32_t e = tid; e < (skip_general ? 0u : kLutSize); e += kBookBlock) {
         const uint64_t v = (uint64_t)e << (64 - kLutBits);
         uint32_t entry = 0;
         const uint32_t top = mx < (uint32_t)kLutBits ? mx : (uint32_t)kLutBits;
@@ -707,9 +713,17 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
         }
         a.t.lut[e] = entry;
     }
-    // the compact table on the next kLut16Bits bits, for alphabets whose residuals fit 12 signed bits
+    // The compact table on the next kLut16Bits bits, for alphabets whose residuals fit 12 signed bits, and
+    // its second level.  A prefix of kLut16Bits bits under which longer codes lie gets a sub-table indexed by
+    // the next 1, 2, 4 or 6 bits (enough for the longest code under the prefix, 6 at most): its entries are
+    // (residual << 4) | (length - kLut16Bits), or 0 for a code that is longer still.  The first-level entry of
+    // such a prefix is ((offset / 2) << 2 | width code) << 4 with a zero length; offset 0 is never given out,
+    // so an all-zero entry means "no sub-table" (the sub-tables filled their array: search by length).
     if (compact) {
-        for (uint32_t e = tid; e < kLut16Size; e += kBookBlock) {
+        constexpr uint32_t kPer = kLut16Size / kBookBlock;          // consecutive first-level entries per thread
+        uint32_t ent[kPer], kbits[kPer], need = 0;
+        for (uint32_t j = 0; j < kPer; ++j) {
+            const uint32_t e = tid * kPer + j;
             const uint64_t v = (uint64_t)e << (64 - kLut16Bits);
             uint32_t entry = 0;
             const uint32_t top = mx < (uint32_t)kLut16Bits ? mx : (uint32_t)kLut16Bits;
@@ -723,12 +737,61 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
                     break;
                 }
             }
+            ent[j] = entry;
+            kbits[j] = 0;
             if (entry == 0) {
+                // the longest code under this prefix is the one its last bit pattern belongs to
+                const uint64_t v_hi = v | ((1ull << (64 - kLut16Bits)) - 1ull);
                 uint32_t L = (uint32_t)kLut16Bits + 1u;
-                while (L < mx && v >= s_limit[L]) ++L;
-                entry = L << 4;
+                while (L < mx && v_hi >= s_limit[L]) ++L;
+                const uint32_t k = L - (uint32_t)kLut16Bits;
+                kbits[j] = k <= 1u ? 1u : (k <= 2u ? 2u : (k <= 4u ? 4u : 6u));
+                need += 1u << kbits[j];
             }
-            a.t.lut16[e] = (uint16_t)entry;
+        }
+        uint32_t total;
+        uint32_t at = 2u + block_excl_scan<uint32_t, kBookBlock / kWave>(need, s_scan, total);
+        // first-level entries; every sub-table entry learns which prefix it belongs to
+        for (uint32_t j = 0; j < kPer; ++j) {
+            const uint32_t e = tid * kPer + j;
+            if (kbits[j]) {
+                const uint32_t kb = kbits[j], size = 1u << kb;
+                if (at + size <= kSubEntries) {
+                    const uint32_t kcode = kb == 1u ? 0u : (kb == 2u ? 1u : (kb == 4u ? 2u : 3u));
+                    ent[j] = (((at >> 1) << 2) | kcode) << 4;
+                    for (uint32_t i = 0; i < size; ++i) s_owner[at + i] = (uint16_t)e;
+                }
+                at += size;
+            }
+            s_ent[e] = (uint16_t)ent[j];
+            a.t.lut16[e] = (uint16_t)ent[j];
+        }
+        __syncthreads();
+        // the sub-table entries, one thread each
+        const uint32_t used = (2u + total < kSubEntries) ? 2u + total : kSubEntries;
+        for (uint32_t x = tid; x < used; x += kBookBlock) {
+            uint32_t entry = 0;
+            if (x >= 2u) {
+                const uint32_t e = s_owner[x] & (kLut16Size - 1u);      // (an entry past the last sub-table that fitted holds anything)
+                const uint32_t pe = s_ent[e];
+                const uint32_t kb = (0x6421u >> (((pe >> 4) & 3u) * 4u)) & 0xfu;
+                const uint32_t first = (pe >> 6) << 1;
+                if (pe != 0u && (pe & 0xfu) == 0u && x >= first && x - first < (1u << kb)) {       // (always, for an entry inside an allocated sub-table)
+                    const uint64_t v = ((uint64_t)e << (64 - kLut16Bits)) | ((uint64_t)(x - first) << (64 - kLut16Bits - kb));
+                    const uint32_t top = mx < (uint32_t)kLut16Bits + kb ? mx : (uint32_t)kLut16Bits + kb;
+                    for (uint32_t L = (uint32_t)kLut16Bits + 1u; L <= top; ++L) {
+                        if (s_cnt[L] && (v < s_limit[L] || L == mx)) {
+                            uint64_t off = (v >> (64u - L)) - s_first[L];
+                            if (off >= s_cnt[L]) off = s_cnt[L] - 1u;  // only reachable with an invalid stream
+                            const uint32_t sym = sorted[s_findex[L] + off];
+                            const int32_t d = sym ? (int32_t)sym - radius : kLut16Escape;
+                            entry = (((uint32_t)d & 0xfffu) << 4) | (L - (uint32_t)kLut16Bits);
+                            break;
+                        }
+                    }
+                }
+            }
+            a.t.sub16[x] = (uint16_t)entry;
         }
     }
     if (tid == 0) { a.t.meta[3] = (uint32_t)radius; a.t.meta[4] = compact ? 1u : 0u; }

@@ -43,6 +43,7 @@ struct DsTables {
     const uint64_t *limit, *first;
     const uint32_t *findex;
     const uint16_t *sorted;     // global: symbols in canonical order
+    const uint16_t *sub;        // LDS: second level of the compact table (sub-tables of the prefixes with longer codes), or null
     const int16_t *tail;        // LDS: residuals of the canonical indices [tail0, tail0 + tail_n), i.e. of the long codes
     uint32_t tail0, tail_n;
     uint32_t max_len, n_active;
@@ -101,7 +102,16 @@ struct BitBuf {
         if (__builtin_expect(wave_ballot(L == 0u) != 0ull, 0)) {   // some lane met a code longer than the table: rare
             if (L == 0u) {
                 const uint64_t win = both | (pos ? (uint64_t)nw >> (32u - pos) : 0ull);
-                d = decode_long(win, hint_of(e), (uint32_t)kBits, t, &L);
+                // second level: the prefix's sub-table on the next 1, 2, 4 or 6 bits; what is longer still
+                // (or has no sub-table) is searched by length
+                bool found = false;
+                const uint32_t h = e >> 4;
+                if (C16 && h != 0u) {
+                    const uint32_t kb = (0x6421u >> ((h & 3u) * 4u)) & 0xfu;
+                    const uint32_t e2 = t.sub[((h >> 2) << 1) + (uint32_t)((win << kBits) >> (64u - kb))];
+                    if (e2 & 0xfu) { L = (uint32_t)kBits + (e2 & 0xfu); d = resid_of(e2); found = true; }
+                }
+                if (!found) d = decode_long(win, C16 ? 0u : hint_of(e), (uint32_t)kBits, t, &L);
                 if (pos + L >= 64u) {            // the code runs into the look-ahead word: move one word on here
                     hi = lo; lo = nw; ++wp; nw = word(wp);
                     pos -= 32u;
@@ -243,6 +253,7 @@ __global__ __launch_bounds__(kDsBlock) void k_decode_chunks(DsArgs a) {
     __shared__ uint64_t s_first[65];
     __shared__ uint32_t s_findex[65];
     __shared__ int16_t s_tail[kDsTailEntries];
+    __shared__ uint32_t s_sub[kSubEntries / 2u];
 
     if (a.ctl->status & ST_FORMAT) return;
 
@@ -251,6 +262,7 @@ __global__ __launch_bounds__(kDsBlock) void k_decode_chunks(DsArgs a) {
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / kWave));
 
     const Header *hdr = reinterpret_cast<const Header *>(a.container);
+    if (a.skip_chunk64 && hdr->chunk_syms == 64u) return;
     const uint32_t *chunk_off = reinterpret_cast<const uint32_t *>(a.container + hdr->off_chunk);
     const uint32_t *payload = reinterpret_cast<const uint32_t *>(a.container + hdr->off_payload);
     const uint32_t payload_words = (uint32_t)hdr->payload_words;
@@ -263,7 +275,9 @@ __global__ __launch_bounds__(kDsBlock) void k_decode_chunks(DsArgs a) {
         for (uint32_t i = tid; i < kLutSize; i += kDsBlock) s_lut[i] = src[i];
     }
     for (uint32_t i = tid; i < 65u; i += kDsBlock) { s_limit[i] = a.t.limit[i]; s_first[i] = a.t.first_code[i]; s_findex[i] = a.t.first_index[i]; }
+    if (c16) for (uint32_t i = tid; i < kSubEntries / 2u; i += kDsBlock) s_sub[i] = reinterpret_cast<const uint32_t *>(a.t.sub16)[i];
     DsTables t;
+    t.sub = reinterpret_cast<const uint16_t *>(s_sub);
     t.lut = s_lut; t.limit = s_limit; t.first = s_first; t.findex = s_findex; t.sorted = a.t.sorted;
     t.max_len = a.t.meta[0]; t.n_active = a.t.meta[1]; t.radius = (int32_t)(hdr->nbins / 2u);
     // residuals of the symbols whose codes are longer than the look-up table, in canonical order
@@ -360,6 +374,7 @@ __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / kWave));
 
     const Header *hdr = reinterpret_cast<const Header *>(a.container);
+    if (a.skip_chunk64 && hdr->chunk_syms == 64u) return;
     const uint32_t *rec = reinterpret_cast<const uint32_t *>(a.container + hdr->off_outlier);
     const uint32_t n_rec = hdr->n_rec;
     const float eb = __uint_as_float(hdr->eb_bits);
@@ -607,6 +622,386 @@ __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
         }
     }
 }
+
+// ---------------------------------------------------------------------------------------------
+// Fused decompression for containers with 64-symbol chunks: Huffman decode, Lorenzo reconstruction,
+// dequantisation, verbatim values, re-zero filter and store in one kernel; residuals never leave the
+// compute unit (Sec. 3.4: "decompress ... when needed" as one pass over the container).
+//
+// A wavefront owns a unit of whole planes and walks it in strips: runs of whole rows whose elements
+// lie inside 64 consecutive chunks.  Per strip:
+//   1. the words of the strip's chunks come global -> LDS with coalesced loads;
+//   2. every lane decodes one chunk, 64 symbols, into 32 registers (pairs of int16 residuals);
+//   3. the lanes write their registers to the same LDS region, one row of kFuPitch words per chunk
+//      (the words are no longer needed: the two uses share the memory);
+//   4. the lanes turn into columns and walk the strip's rows out of LDS: row prefix by a DPP scan,
+//      column prefix in a register per column, * 2eb, store.  Rows that take at most 32 lanes are
+//      walked several at a time (slots of lanes side by side); the column prefix then also runs
+//      across the slots of a step (cross-lane permutes), and what a plane has summed up so far is
+//      handed from step to step and strip to strip through the lanes of the last row.
+// A strip need not end at a plane boundary: the column sums restart wherever a plane starts.
+// The re-zero filter needs no instruction here: a lattice value q * 2eb lies within eb of zero only
+// for q == 0, which already gives +0.0; verbatim values are filtered where they are written.
+template <int NSEG, int MODE, int OUT, int VEC>
+__global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
+    constexpr uint32_t OS = OUT ? 2u : 4u;                   // bytes per output element
+    extern __shared__ uint32_t s_dyn_ds[];                  // per wavefront: strip (kFuStripWords), escape values (kFuEscEntries)
+    __shared__ uint32_t s_lut[kLutSize];
+    __shared__ uint32_t s_sub[kSubEntries / 2u];
+    __shared__ uint64_t s_limit[65];
+    __shared__ uint64_t s_first[65];
+    __shared__ uint32_t s_findex[65];
+
+    if (a.ctl->status & ST_FORMAT) return;
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = (uint32_t)lane_id();
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / kWave));
+
+    const Header *hdr = reinterpret_cast<const Header *>(a.container);
+    if (hdr->chunk_syms != 64u) return;                     // another chunk size: the general kernel launched behind this one takes it
+    const uint32_t *chunk_off = reinterpret_cast<const uint32_t *>(a.container + hdr->off_chunk);
+    const uint32_t *payload = reinterpret_cast<const uint32_t *>(a.container + hdr->off_payload);
+    const uint32_t *rec = reinterpret_cast<const uint32_t *>(a.container + hdr->off_outlier);
+    const uint32_t payload_words = (uint32_t)hdr->payload_words;
+    const uint32_t n_chunks = hdr->n_chunks;
+    const uint32_t n_rec = hdr->n_rec;
+    const float eb = __uint_as_float(hdr->eb_bits);
+    const float ebx2 = __uint_as_float(hdr->ebx2_bits);
+
+    // ---- decode tables into LDS ----
+    const bool c16 = a.t.meta[4] != 0u;
+    {
+        const uint32_t *src = c16 ? reinterpret_cast<const uint32_t *>(a.t.lut16) : a.t.lut;
+        for (uint32_t i = tid; i < kLutSize; i += kFuBlock) s_lut[i] = src[i];
+        if (c16) for (uint32_t i = tid; i < kSubEntries / 2u; i += kFuBlock) s_sub[i] = reinterpret_cast<const uint32_t *>(a.t.sub16)[i];
+    }
+    for (uint32_t i = tid; i < 65u; i += kFuBlock) { s_limit[i] = a.t.limit[i]; s_first[i] = a.t.first_code[i]; s_findex[i] = a.t.first_index[i]; }
+    DsTables t;
+    t.lut = s_lut; t.sub = reinterpret_cast<const uint16_t *>(s_sub);
+    t.limit = s_limit; t.first = s_first; t.findex = s_findex; t.sorted = a.t.sorted;
+    t.max_len = a.t.meta[0]; t.n_active = a.t.meta[1]; t.radius = (int32_t)(hdr->nbins / 2u);
+    t.tail = nullptr; t.tail0 = 0; t.tail_n = 0;            // what neither table level resolves is rare: symbols from global memory
+    t.escape = c16 ? kLut16Escape : kEscape;
+    const int32_t esc_marker = t.escape;
+    __syncthreads();
+
+    uint32_t *strip = s_dyn_ds + wave * kFuRegionWords;
+    int32_t *esc = reinterpret_cast<int32_t *>(strip + kFuStripWords);
+
+    // ---- lanes -> columns (scan phase) ----
+    const uint32_t W = a.W, H = a.H, P = H * W;
+    const uint32_t L = W / (uint32_t)VEC;                     // lanes per row
+    uint32_t K = 1, slot = 0, wl = lane;                      // rows per step; my row inside a step; my position in the row
+    bool lane_on = true;
+    uint32_t spr = 1;
+    if (MODE == 0) {
+        spr = 16u / L;
+        const uint32_t r = lane & 15u, sir = fdiv(r, a.divL);
+        wl = r - sir * L; lane_on = sir < spr; slot = (lane >> 4) * spr + sir; K = 4u * spr;
+    } else if (MODE == 1) {
+        wl = lane & 31u; lane_on = wl < L; slot = lane >> 5; K = 2u;
+    } else if (NSEG == 1) {
+        lane_on = lane < L;
+    }
+    const uint64_t lt_mask = (1ull << lane) - 1ull;
+    // element offset of my first column inside a step; 0x1fffffff for "no element" (times 2 or 4 it still
+    // lies beyond every strip, so the access is dropped)
+    constexpr uint32_t kNoElem = 0x1fffffffu;
+    uint32_t col[NSEG];
+#pragma unroll
+    for (int s = 0; s < NSEG; ++s) {
+        const uint32_t w = wl + (uint32_t)s * kWave;
+        col[s] = (lane_on && w < L) ? slot * W + w * (uint32_t)VEC : kNoElem;
+    }
+    // MODE 0 / 1: lanes that hold my column in the slots 1, 2, 4, ... rows above mine (byte addresses for the
+    // cross-lane permute), and the lane part of the address of "my column in slot k"
+    uint32_t src_up[6];
+#pragma unroll
+    for (uint32_t lv = 0; lv < 6u; ++lv) {
+        const uint32_t dd = 1u << lv;
+        uint32_t sl = slot >= dd ? slot - dd : 0u;
+        uint32_t ln = lane;
+        if (MODE == 0) { const uint32_t rw = fdiv(sl, a.divSpr); ln = rw * 16u + (sl - rw * spr) * L + wl; }
+        if (MODE == 1) ln = sl * 32u + wl;
+        src_up[lv] = ln * 4u;
+    }
+
+    const uint32_t waves_total = gridDim.x * (uint32_t)kFuWaves;
+    for (uint32_t unit = wave * gridDim.x + blockIdx.x; unit < a.n_units; unit += waves_total) {
+        const uint32_t p0 = unit * a.G;
+        const uint32_t p1 = (a.planes - p0 < a.G) ? a.planes : p0 + a.G;
+        const uint32_t e_a = p0 * P, e_b = p1 * P;
+        uint32_t rpos = 0;
+        if (n_rec) rpos = rec_lower_bound(rec, 0, n_rec, 2u * e_a, lane);
+        int32_t q[NSEG][VEC];                               // MODE 2: running column sums; MODE 0 / 1: the plane's sums up to the last row of the step before
+#pragma unroll
+        for (int s = 0; s < NSEG; ++s)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) q[s][v] = 0;
+
+        uint32_t s_a = e_a;
+        while (s_a < e_b) {
+            // ---- the strip: whole rows from s_a on, inside chunks [c0, c0 + 64) ----
+            const uint32_t c0 = s_a >> 6;
+            const uint32_t lim = fdiv((c0 + 64u) << 6, a.divW) * W;         // end of the last whole row inside those chunks
+            const uint32_t s_b = lim < e_b ? lim : e_b;
+            const uint32_t c1 = (s_b + 63u) >> 6;                             // <= c0 + 64
+            const uint32_t rows = fdiv(s_b - s_a, a.divW);
+            const uint32_t c = c0 + lane;
+
+            // ---- 1. words of the chunks [c0, c1) -> LDS ----
+            const uint32_t off_lane = chunk_off[c < c1 ? c : c0];
+            const uint32_t off_end = chunk_off[c1 < n_chunks ? c1 : c0];
+            const uint32_t my_off = (c < c1) ? off_lane : 0u;
+            uint32_t w_end = (c1 < n_chunks) ? off_end : payload_words;
+            uint32_t w_begin = (uint32_t)__builtin_amdgcn_readfirstlane((int)my_off);
+            if (w_end > payload_words) w_end = payload_words;
+            if (w_begin > w_end) w_begin = w_end;
+            const uint32_t n_words = w_end - w_begin;
+            const bool all_staged = n_words <= kFuStripWords - 4u;             // (the reader looks up to two words ahead)
+            if (all_staged) {
+                const __amdgpu_buffer_rsrc_t r_w = make_rsrc(payload + w_begin, n_words * 4u);   // loads past the end give 0
+                for (uint32_t i0 = 0; i0 < n_words; i0 += kDsStageBatch * kWave) {
+                    uint32_t v[kDsStageBatch];
+#pragma unroll
+                    for (uint32_t j = 0; j < kDsStageBatch; ++j)
+                        v[j] = __builtin_amdgcn_raw_buffer_load_b32(r_w, (int)((i0 + j * kWave + lane) * 4u), 0, 0);
+#pragma unroll
+                    for (uint32_t j = 0; j < kDsStageBatch; ++j) {
+                        const uint32_t i = i0 + j * kWave + lane;
+                        if (i < n_words) strip[i] = v[j];
+                    }
+                }
+            }
+            wave_lds_fence();
+
+            // ---- 2. decode, one lane per chunk, into registers: eight groups of four pairs, written out
+            // one after the other (a loop over an array of groups would put the array into scratch memory) ----
+            uint4 g0, g1, g2, g3, g4, g5, g6, g7;
+            g0 = g1 = g2 = g3 = g4 = g5 = g6 = g7 = make_uint4(0u, 0u, 0u, 0u);
+            {
+                const uint32_t last = n_words ? n_words - 1u : 0u;
+                uint32_t w0 = (my_off < w_begin) ? 0u : my_off - w_begin;
+                w0 = w0 < last ? w0 : last;
+                const uint32_t *words = all_staged ? strip : payload + w_begin;
+                auto run = [&](auto c16_tag, const uint32_t *wsrc) {
+                    BitBuf<decltype(c16_tag)::value> bb;
+                    bb.open(wsrc, last, w0);
+                    auto four = [&](uint4 &g) { g.x = bb.next_pair(t); g.y = bb.next_pair(t); g.z = bb.next_pair(t); g.w = bb.next_pair(t); };
+                    four(g0); four(g1); four(g2); four(g3); four(g4); four(g5); four(g6); four(g7);
+                };
+                if (c < c1 && n_words) {
+                    if (c16) run(std::true_type{}, words); else run(std::false_type{}, words);
+                }
+            }
+            wave_lds_fence();
+
+            // ---- 3. registers -> LDS, one row of kFuPitch words per chunk ----
+            {
+                uint4 *row = reinterpret_cast<uint4 *>(strip + lane * kFuPitch);
+                row[0] = g0; row[1] = g1; row[2] = g2; row[3] = g3; row[4] = g4; row[5] = g5; row[6] = g6; row[7] = g7;
+            }
+
+            // ---- the strip's escaped residuals, their values compacted into LDS in element order ----
+            const uint32_t r_begin = rpos;
+            uint32_t r_end = rpos;
+            uint32_t n_esc = 0;
+            bool has_verbatim = false;
+            if (n_rec && rpos < n_rec) {
+                const uint32_t span = 2u * (s_b - s_a);           // at most two records per element
+                const uint32_t hi = (n_rec - rpos < span) ? n_rec : rpos + span;
+                r_end = rec_lower_bound(rec, rpos, hi, 2u * s_b, lane);
+                for (uint32_t base = r_begin; base < r_end; base += kWave) {
+                    const uint32_t k = base + lane;
+                    uint32_t key = 1u, val = 0;
+                    if (k < r_end) { key = rec[2 * (size_t)k]; val = rec[2 * (size_t)k + 1]; }
+                    const bool is_e = k < r_end && !(key & 1u);
+                    const uint64_t esc_mask = wave_ballot(is_e);
+                    if (wave_ballot(k < r_end && (key & 1u))) has_verbatim = true;
+                    if (is_e) {
+                        const uint32_t pos = n_esc + (uint32_t)__popcll(esc_mask & lt_mask);
+                        if (pos < kFuEscEntries) esc[pos] = (int32_t)val;
+                    }
+                    n_esc += (uint32_t)__popcll(esc_mask);
+                }
+                rpos = r_end;
+            }
+            const bool esc_in_lds = n_esc <= kFuEscEntries;
+            wave_lds_fence();
+
+            // ---- 4. scan the rows out of LDS ----
+            const uint32_t rel0 = s_a - (c0 << 6);               // the strip's first element inside its chunks
+            const uint32_t row0 = fdiv(s_a, a.divW);
+            const uint32_t h0 = row0 - fdiv(row0, a.divH) * H;   // row of the strip's first row inside its plane
+            const __amdgpu_buffer_rsrc_t r_out = make_rsrc(reinterpret_cast<char *>(a.out) + (size_t)s_a * OS, (s_b - s_a) * OS);
+            const uint32_t n_steps = (rows + K - 1u) / K;
+            const uint32_t step_elems = K * W;
+            uint32_t h_lane = h0 + slot;                         // my row inside its plane (MODE 0 / 1)
+            h_lane -= fdiv(h_lane, a.divH) * H;
+            const uint32_t k_mod = K - fdiv(K, a.divH) * H;
+            uint32_t h_row = h0;                                 // MODE 2: the step's row inside its plane (uniform)
+            uint32_t cur = 0;                                    // escapes consumed so far
+
+            auto scan_rows = [&](auto esc_tag) {
+                constexpr int ESC = decltype(esc_tag)::value;   // 0: the strip has no escape, 1: values in LDS, 2: too many for LDS, look them up in the container
+                for (uint32_t tstep = 0; tstep < n_steps; ++tstep) {
+                    const uint32_t e_step = tstep * step_elems;          // uniform
+                    const uint32_t rows_left = rows - tstep * K;
+                    int32_t carry = 0;
+#pragma unroll
+                    for (int s = 0; s < NSEG; ++s) {
+                        const bool on = col[s] != kNoElem && (MODE == 2 || slot < rows_left);
+                        const uint32_t off = on ? col[s] + e_step : kNoElem;              // element offset inside the strip
+                        const uint32_t rel = (on ? off : 0u) + rel0;
+                        const uint32_t lds_byte = (rel << 1) + ((rel >> 6) << 4);          // (rel / 64) * kFuPitch * 4 + (rel % 64) * 2
+                        int32_t d[VEC];
+                        if (VEC == 2) {
+                            const uint32_t two = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(strip) + lds_byte);
+                            d[0] = (int32_t)(int16_t)(two & 0xffffu);
+                            d[VEC - 1] = (int32_t)two >> 16;
+                        } else {
+                            d[0] = (int32_t)*reinterpret_cast<const int16_t *>(reinterpret_cast<const char *>(strip) + lds_byte);
+                        }
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) d[v] = on ? d[v] : 0;
+                        if (ESC) {
+                            bool is_esc[VEC];
+                            uint64_t em[VEC], any_esc = 0ull;
+#pragma unroll
+                            for (int v = 0; v < VEC; ++v) {
+                                is_esc[v] = d[v] == esc_marker;
+                                em[v] = wave_ballot(is_esc[v]);
+                                any_esc |= em[v];
+                            }
+                            if (any_esc) {                            // wavefront-uniform
+                                // escapes in element order: the lanes hold consecutive elements (slots in order,
+                                // columns in order), then a lane's own columns
+                                uint32_t before = 0, all = 0;
+#pragma unroll
+                                for (int v = 0; v < VEC; ++v) {
+                                    before += (uint32_t)__popcll(em[v] & lt_mask);
+                                    all += (uint32_t)__popcll(em[v]);
+                                }
+                                uint32_t pos = cur + before;
+#pragma unroll
+                                for (int v = 0; v < VEC; ++v) {
+                                    if (is_esc[v]) {
+                                        if (ESC == 2) {
+                                            const uint32_t key = 2u * (s_a + off + (uint32_t)v);
+                                            uint32_t lo = r_begin, hi = r_end;
+                                            while (lo < hi) { const uint32_t mid = (lo + hi) >> 1; if (rec[2 * (size_t)mid] < key) lo = mid + 1; else hi = mid; }
+                                            d[v] = (lo < r_end && rec[2 * (size_t)lo] == key) ? (int32_t)rec[2 * (size_t)lo + 1] : 0;
+                                        } else {
+                                            d[v] = esc[pos < kFuEscEntries ? pos : kFuEscEntries - 1u];   // beyond: corrupt container only
+                                        }
+                                        ++pos;
+                                    }
+                                }
+                                cur += all;
+                            }
+                        }
+                        // row prefix: the lane's own columns, then a scan over the lanes of the row
+                        int32_t mine = d[0];
+#pragma unroll
+                        for (int v = 1; v < VEC; ++v) mine = (int32_t)((uint32_t)mine + (uint32_t)d[v]);
+                        int32_t incl = run_scan<MODE>(mine, wl, L);
+                        incl = (int32_t)((uint32_t)incl + (uint32_t)carry);
+                        if (NSEG > 1) carry = __builtin_amdgcn_readlane(incl, 63);
+                        int32_t rp[VEC];
+                        rp[VEC - 1] = incl;
+#pragma unroll
+                        for (int v = VEC - 2; v >= 0; --v) rp[v] = (int32_t)((uint32_t)rp[v + 1] - (uint32_t)d[v + 1]);
+                        float val[VEC];
+                        if (MODE == 2) {
+                            const uint32_t keep = h_row ? ~0u : 0u;          // a plane starts: its column sums start over
+#pragma unroll
+                            for (int v = 0; v < VEC; ++v) {
+                                q[s][v] = (int32_t)(((uint32_t)q[s][v] & keep) + (uint32_t)rp[v]);
+                                val[v] = (float)q[s][v] * ebx2;
+                            }
+                        } else {
+                            // column prefix across the slots of the step (rows of one plane only), on top of
+                            // what the plane had summed up when the step began
+#pragma unroll
+                            for (int v = 0; v < VEC; ++v) {
+                                int32_t cs = rp[v];
+#pragma unroll
+                                for (uint32_t lv = 0; lv < (MODE == 1 ? 1u : 6u); ++lv) {
+                                    const uint32_t dd = 1u << lv;
+                                    if (MODE == 0 && dd >= K) break;                       // uniform
+                                    const int32_t up = __builtin_amdgcn_ds_bpermute((int)src_up[lv], cs);
+                                    cs = (slot >= dd && h_lane >= dd) ? (int32_t)((uint32_t)cs + (uint32_t)up) : cs;
+                                }
+                                const int32_t qq = (int32_t)((uint32_t)cs + (h_lane > slot ? (uint32_t)q[0][v] : 0u));
+                                val[v] = (float)qq * ebx2;
+                                // the last row of the step hands its sums to every slot of the next step
+                                const uint32_t ks = (rows_left < K ? rows_left : K) - 1u;   // uniform
+                                uint32_t ln;
+                                if (MODE == 1) ln = ks * 32u + wl;
+                                else { const uint32_t rw = fdiv(ks, a.divSpr); ln = rw * 16u + (ks - rw * spr) * L + wl; }
+                                q[0][v] = __builtin_amdgcn_ds_bpermute((int)(ln * 4u), qq);
+                            }
+                        }
+                        const uint32_t off_c = off > kNoElem ? kNoElem : off;
+                        if (OUT == 0 && VEC == 2) {
+                            u32x2_t two;
+                            two.x = __float_as_uint(val[0]); two.y = __float_as_uint(val[VEC - 1]);
+                            __builtin_amdgcn_raw_buffer_store_b64(two, r_out, (int)(off_c * 4u), 0, 0);
+                        } else if (OUT == 0) {
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val[0]), r_out, (int)(off_c * 4u), 0, 0);
+                        } else if (VEC == 2) {
+                            __builtin_amdgcn_raw_buffer_store_b32(narrow16<OUT>(val[0]) | (narrow16<OUT>(val[VEC - 1]) << 16), r_out, (int)(off_c * 2u), 0, 0);
+                        } else {
+                            __builtin_amdgcn_raw_buffer_store_b16((unsigned short)narrow16<OUT>(val[0]), r_out, (int)(off_c * 2u), 0, 0);
+                        }
+                    }
+                    if (MODE == 2) { ++h_row; h_row = (h_row == H) ? 0u : h_row; }
+                    else { h_lane += k_mod; h_lane -= (h_lane >= H) ? H : 0u; }
+                }
+            };
+            if (n_esc == 0u) scan_rows(std::integral_constant<int, 0>{});
+            else if (esc_in_lds) scan_rows(std::integral_constant<int, 1>{});
+            else scan_rows(std::integral_constant<int, 2>{});
+
+            // ---- verbatim values overwrite what was just stored ----
+            if (has_verbatim) {
+                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");      // the lattice values of this wavefront have landed
+                for (uint32_t k = r_begin + lane; k < r_end; k += kWave) {
+                    const uint32_t key = rec[2 * (size_t)k];
+                    if (key & 1u) {
+                        float v = __uint_as_float(rec[2 * (size_t)k + 1]);
+                        if (fabsf(v) <= eb) v = 0.0f;
+                        const uint32_t e = key >> 1;
+                        if (e >= s_a && e < s_b) {
+                            if (OUT == 0) static_cast<float *>(a.out)[e] = v;
+                            else static_cast<unsigned short *>(a.out)[e] = (unsigned short)narrow16<OUT>(v);
+                        }
+                    }
+                }
+            }
+            wave_lds_fence();
+            s_a = s_b;
+        }
+    }
+}
+
+#define COMET_INST_FUSED(OUT)                                           \
+    template __global__ void k_decode_scan<1, 0, OUT, 1>(FuArgs);       \
+    template __global__ void k_decode_scan<1, 1, OUT, 1>(FuArgs);       \
+    template __global__ void k_decode_scan<1, 2, OUT, 1>(FuArgs);       \
+    template __global__ void k_decode_scan<2, 2, OUT, 1>(FuArgs);       \
+    template __global__ void k_decode_scan<4, 2, OUT, 1>(FuArgs);       \
+    template __global__ void k_decode_scan<8, 2, OUT, 1>(FuArgs);       \
+    template __global__ void k_decode_scan<1, 0, OUT, 2>(FuArgs);       \
+    template __global__ void k_decode_scan<1, 1, OUT, 2>(FuArgs);       \
+    template __global__ void k_decode_scan<1, 2, OUT, 2>(FuArgs);       \
+    template __global__ void k_decode_scan<2, 2, OUT, 2>(FuArgs);       \
+    template __global__ void k_decode_scan<4, 2, OUT, 2>(FuArgs);
+COMET_INST_FUSED(0)
+COMET_INST_FUSED(1)
+COMET_INST_FUSED(2)
+#undef COMET_INST_FUSED
 
 #define COMET_INST_SCAN(OUT)                                            \
     template __global__ void k_scan_store<1, 0, OUT, 1>(DsArgs);        \

@@ -108,6 +108,8 @@ __global__ __launch_bounds__(kDecBlock) void k_reconstruct(ReconArgs a) {
     __shared__ uint32_t s_findex[65];
 
     if (MODE == 0 && (a.ctl->status & ST_FORMAT)) return;
+    // launched behind the kernel for chunks of 64 symbols: only containers that one has left alone
+    if (MODE == 0 && a.skip_chunk64 && reinterpret_cast<const Header *>(a.container)->chunk_syms == 64u) return;
 
     const int tid = threadIdx.x;
     int32_t *tile = s_dyn_rec;

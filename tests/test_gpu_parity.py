@@ -319,9 +319,13 @@ def test_compress_container_bytes(comet, ctx, oracle, shape, kind, eb, nbins, ch
 
 
 @pytest.mark.parametrize("shape,kind", SHAPES)
-@pytest.mark.parametrize("eb,nbins,chunk_syms", [(1e-2, 1024, 128), (1e-3, 1024, 77), (1e-4, 65536, 256), (5e-2, 4, 1000)])
-def test_decompress_oracle_container(comet, ctx, oracle, shape, kind, eb, nbins, chunk_syms):
-    """The decompressor accepts any chunk size: feed it the oracle's container."""
+@pytest.mark.parametrize("hint", [64, 128])
+@pytest.mark.parametrize("eb,nbins,chunk_syms", [(1e-2, 1024, 128), (1e-3, 1024, 77), (1e-4, 65536, 256), (5e-2, 4, 1000), (1e-3, 256, 64)])
+def test_decompress_oracle_container(comet, ctx, oracle, shape, kind, eb, nbins, chunk_syms, hint):
+    """The decompressor accepts any chunk size: feed it the oracle's container.  `hint` is the chunk size the
+    context compresses with, which picks the kernels that are launched: with 64 the single fused kernel and,
+    behind it, the general one for containers the fused kernel leaves alone; else the two-kernel path."""
+    ctx.comet_set_chunk_syms(hint)
     x = make_input(shape, kind, seed=71)
     if x.size > 100:
         x.ravel()[7] = np.inf
@@ -338,6 +342,29 @@ def test_decompress_oracle_container(comet, ctx, oracle, shape, kind, eb, nbins,
     finite = np.isfinite(x.ravel())
     err = np.abs(got.astype(np.float64)[finite] - x.ravel().astype(np.float64)[finite])
     assert err.max() <= np.float64(np.float32(eb))
+
+
+def test_which_kernels_decompress(comet, oracle):
+    """Chunks of 64 symbols and planes of at most 512 columns take the fused kernel alone; any other chunk size
+    under the same context falls to the general kernel behind it; a context set to another chunk size takes
+    the two-kernel path.  All give the oracle's values."""
+    shape = (2, 8, 56, 56)
+    x = synth.relu_blur(shape, seed=44, blur=3, shift=-0.2)
+    c = comet.Context(max_elems=x.size, max_nbins=1024)
+    c.comet_profile_enable(True)
+    FUSED, DECODE, SCAN = 8, 5, 4
+    for hint, chunk, want_launches in [(64, 64, (1, 0, 0)), (64, 100, (1, 0, 0)), (128, 64, (0, 1, 1)), (128, 128, (0, 1, 1))]:
+        buf = oracle.compress(x, 1e-2, 1024, chunk)
+        cont = dev(np.concatenate([buf, np.zeros((-buf.size) % 16, np.uint8)]))
+        out = torch.zeros(x.size, dtype=torch.float32, device="cuda")
+        c.comet_set_chunk_syms(hint)
+        c.comet_profile_reset()
+        c.comet_decompress(cont, buf.size, shape, out)
+        c.comet_sync()
+        got = tuple(c.comet_profile_read(k)[0] for k in (FUSED, DECODE, SCAN))
+        assert got == want_launches, (hint, chunk, got)
+        assert np.array_equal(out.cpu().numpy().view(np.uint32), oracle.decompress(buf).ravel().view(np.uint32)), (hint, chunk)
+    c.close()
 
 
 # Plane widths on both sides of every boundary between the lane mappings of the quantise and the
