@@ -684,11 +684,19 @@ int decompress_impl(const DecompWs &ws, const void *dev_in, uint64_t bytes, come
         f.container = in; f.t = ws.tables; f.n = n; f.planes = s.n * s.c; f.H = s.h; f.W = s.w;
         f.divW = make_fastdiv(s.w); f.divH = make_fastdiv(s.h); f.divL = make_fastdiv(lpr);
         f.divSpr = make_fastdiv(lpr <= 16u ? 16u / lpr : 1u);
+        f.divK = make_fastdiv(lpr <= 16u ? 4u * (16u / lpr) : (lpr <= 32u ? 2u : 1u));
         f.out = dev_out; f.ctl = &ws.state->ctl;
-        const FusedGeom fg = fused_geometry(ws.num_cu, s);
-        f.G = fg.G; f.n_units = fg.n_units;
         const int mode = lpr <= 16u ? 0 : (lpr <= 32u ? 1 : 2);
         const int nseg = lpr <= 64u ? 1 : (lpr <= 128u ? 2 : (lpr <= 256u ? 4 : 8));
+        // planes of at most kFuCarryW columns: one segment of planes per workgroup, its strips dealt to all its
+        // wavefronts; wider planes: units of whole planes per wavefront
+        const bool coop = nseg == 1 || (nseg == 2 && vec == 1u);
+        FusedGeom fg = fused_geometry(ws.num_cu, s);
+        if (coop) {
+            const uint64_t planes = (uint64_t)s.n * s.c;
+            fg.grid = (uint32_t)(planes < (uint64_t)ws.num_cu ? planes : (uint64_t)ws.num_cu);
+        }
+        f.G = fg.G; f.n_units = fg.n_units;
         const void *fn = fused_kernel(nseg, mode, out_type, (int)vec);
         if (!fn) return COMET_ERR_INTERNAL;
         void *kargs[] = {&f};

@@ -137,7 +137,9 @@ struct DecodeTables {          // all in the workspace (global memory)
     uint64_t *limit;           // [65]: left-aligned exclusive upper bound of the codes of each length
     uint64_t *first_code;      // [65]
     uint32_t *first_index;     // [65]: position of the first symbol of each length in `sorted`
-    uint16_t *lut16;           // kLut16Size entries: (residual << 4) | length, residual in 12 signed bits (kLut16Escape for
+    uint16_t *lut16;           // (if the alphabet is too large for the compact table: a copy of `lut`, so that the chunk decoders
+                               // always load from here; meta[4] tells which it is)
+                               // kLut16Size entries: (residual << 4) | length, residual in 12 signed bits (kLut16Escape for
                                // the escape symbol); length 0 = longer code: the upper 12 bits are (offset / 2) << 2 | width
                                // code of the prefix's sub-table in sub16 (width 1, 2, 4, 6 bits), all zero if it has none
     uint16_t *sub16;           // kSubEntries entries: (residual << 4) | (length - kLut16Bits), 0 = longer still
@@ -234,6 +236,8 @@ constexpr uint32_t kFuPitch = 36u;                    // words of LDS per chunk 
 constexpr uint32_t kFuStripWords = 64u * kFuPitch;    // a strip's residuals; before that, the words of its chunks
 constexpr uint32_t kFuEscEntries = 512u;              // values of a strip's escaped residuals kept in LDS
 constexpr uint32_t kFuRegionWords = kFuStripWords + kFuEscEntries;
+constexpr uint32_t kFuPrefetch = 20u;                 // words per lane (of a strip's chunks) loaded while the strip before is scanned
+constexpr uint32_t kFuCarryW = 128u;                  // widest plane whose strips are dealt to all wavefronts of a workgroup (column sums handed on through LDS)
 
 struct FuArgs {
     const uint8_t *container;
@@ -245,6 +249,7 @@ struct FuArgs {
     FastDiv divW, divH;
     FastDiv divL;              // lanes per row (W / columns per lane)
     FastDiv divSpr;            // rows of at most 16 lanes: rows side by side in 16 lanes
+    FastDiv divK;              // rows per step
     void *out;                 // fp32, or IEEE half / bfloat16 (template parameter OUT)
     Control *ctl;
 };

@@ -712,6 +712,7 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
             entry = L << 8;
         }
         a.t.lut[e] = entry;
+        if (!compact) reinterpret_cast<uint32_t *>(a.t.lut16)[e] = entry;    // the chunk decoders load their table from one place
     }
     // The compact table on the next kLut16Bits bits, for alphabets whose residuals fit 12 signed bits, and
     // its second level.  A prefix of kLut16Bits bits under which longer codes lie gets a sub-table indexed by

@@ -37,6 +37,7 @@ namespace {
 
 constexpr int32_t kEscape = -32768;
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x16_t __attribute__((ext_vector_type(16)));
 
 struct DsTables {
     const uint32_t *lut;        // LDS: the 11-bit table (u32 entries) or the compact 12-bit one (u16 entries)
@@ -104,13 +105,7 @@ struct BitBuf {
                 const uint64_t win = both | (pos ? (uint64_t)nw >> (32u - pos) : 0ull);
                 // second level: the prefix's sub-table on the next 1, 2, 4 or 6 bits; what is longer still
                 // (or has no sub-table) is searched by length
-                bool found = false;
-                const uint32_t h = e >> 4;
-                if (C16 && h != 0u) {
-                    const uint32_t kb = (0x6421u >> ((h & 3u) * 4u)) & 0xfu;
-                    const uint32_t e2 = t.sub[((h >> 2) << 1) + (uint32_t)((win << kBits) >> (64u - kb))];
-                    if (e2 & 0xfu) { L = (uint32_t)kBits + (e2 & 0xfu); d = resid_of(e2); found = true; }
-                }
+                const bool found = second_level(t, e, win, L, d);
                 if (!found) d = decode_long(win, C16 ? 0u : hint_of(e), (uint32_t)kBits, t, &L);
                 if (pos + L >= 64u) {            // the code runs into the look-ahead word: move one word on here
                     hi = lo; lo = nw; ++wp; nw = word(wp);
@@ -128,20 +123,33 @@ struct BitBuf {
         nw = word(wp);
         return d;
     }
+    // Second level of the compact table: the sub-table of the first-level entry `e` (a prefix under which
+    // longer codes lie), indexed by the bits that follow the prefix in `win` (64 bits of the stream from the
+    // code's first bit).  False if the prefix has no sub-table or the code is longer than its sub-table covers.
+    static __device__ inline bool second_level(const DsTables &t, uint32_t e, uint64_t win, uint32_t &L, int32_t &d) {
+        const uint32_t h = e >> 4;
+        if (!C16 || h == 0u) return false;
+        const uint32_t kb = (0x6421u >> ((h & 3u) * 4u)) & 0xfu;
+        const uint32_t e2 = t.sub[((h >> 2) << 1) + (uint32_t)((win << kBits) >> (64u - kb))];
+        if ((e2 & 0xfu) == 0u) return false;
+        L = (uint32_t)kBits + (e2 & 0xfu);
+        d = resid_of(e2);
+        return true;
+    }
+    // 64 bits of the stream from bit p (< 64) of the two words on: the look-ahead word fills the low end
+    __device__ inline uint64_t window_at(uint64_t both, uint32_t p) const {
+        return (both << p) | (p ? (((uint64_t)nw << 32) >> (64u - p)) : 0ull);
+    }
     // Two symbols packed as (second << 16) | (first & 0xffff).  Two look-up-table codes take at most
     // 24 bits, so after the first one there are still at least kBits valid bits in the two words and
-    // the words move on only once per pair.  If either code is longer than the table
-    // (wavefront-uniform test) the pair is decoded again one symbol at a time.
+    // the words move on only once per pair.  One wavefront-uniform test per pair: if either code of any
+    // lane is longer than the table the pair is finished by pair_with_long_codes.
     __device__ inline uint32_t next_pair(const DsTables &t) {
         const uint64_t both = ((uint64_t)hi << 32) | lo;
         const uint32_t e0 = look(t, both << pos);
         const uint32_t p1 = pos + len_of(e0);
         const uint32_t e1 = look(t, both << p1);
-        if (__builtin_expect(wave_ballot(len_of(e0) == 0u || len_of(e1) == 0u) != 0ull, 0)) {
-            const uint32_t d0 = (uint32_t)next(t) & 0xffffu;
-            const uint32_t d1 = (uint32_t)next(t);
-            return (d1 << 16) | d0;
-        }
+        if (__builtin_expect(wave_ballot(len_of(e0) == 0u || len_of(e1) == 0u) != 0ull, 0)) return pair_with_long_codes(t, both, e0);
         const uint32_t p2 = p1 + len_of(e1);
         const bool need = p2 >= 32u;
         hi = need ? lo : hi;
@@ -151,6 +159,36 @@ struct BitBuf {
         nw = word(wp);
         if (C16) return ((uint32_t)resid_of(e1) << 16) | ((uint32_t)resid_of(e0) & 0xffffu);
         return __builtin_amdgcn_perm(e1, e0, 0x06050201u);      // bytes 1, 2 of each entry: the two residuals
+    }
+    // The same pair when some lane has a code longer than the table.  Such a code is resolved through the
+    // second level (the lanes concerned only): up to 18 bits, so the second look-up still finds its bits in the
+    // two words, and the pair may use up two words instead of one.  Only a code beyond both levels makes the
+    // pair start over, one symbol at a time.
+    __device__ inline uint32_t pair_with_long_codes(const DsTables &t, uint64_t both, uint32_t e0) {
+        uint32_t L0 = len_of(e0);
+        int32_t d0 = resid_of(e0);
+        bool fail = false;
+        if (L0 == 0u) fail = !second_level(t, e0, window_at(both, pos), L0, d0);
+        const uint32_t p1 = pos + L0;                          // at most 31 + 18
+        const uint32_t e1 = look(t, both << p1);
+        uint32_t L1 = len_of(e1);
+        int32_t d1 = resid_of(e1);
+        if (L1 == 0u) fail = !second_level(t, e1, window_at(both, p1), L1, d1) || fail;
+        if (wave_ballot(fail) != 0ull) {
+            const uint32_t s0 = (uint32_t)next(t) & 0xffffu;
+            const uint32_t s1 = (uint32_t)next(t);
+            return (s1 << 16) | s0;
+        }
+        uint32_t p2 = p1 + L1;                                 // at most 31 + 36
+        const bool need = p2 >= 32u;
+        hi = need ? lo : hi;
+        lo = need ? nw : lo;
+        p2 -= need ? 32u : 0u;
+        wp += need ? 1u : 0u;
+        nw = word(wp);
+        if (p2 >= 32u) { hi = lo; lo = nw; p2 -= 32u; ++wp; nw = word(wp); }     // long codes may have used up a second word
+        pos = p2;
+        return ((uint32_t)d1 << 16) | ((uint32_t)d0 & 0xffffu);
     }
 };
 
@@ -271,7 +309,7 @@ __global__ __launch_bounds__(kDsBlock) void k_decode_chunks(DsArgs a) {
 
     const bool c16 = a.t.meta[4] != 0u;                     // the compact table exists: use it
     {
-        const uint32_t *src = c16 ? reinterpret_cast<const uint32_t *>(a.t.lut16) : a.t.lut;   // either is kLutSize dwords
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(a.t.lut16);     // the compact table, or a copy of the general one: kLutSize dwords
         for (uint32_t i = tid; i < kLutSize; i += kDsBlock) s_lut[i] = src[i];
     }
     for (uint32_t i = tid; i < 65u; i += kDsBlock) { s_limit[i] = a.t.limit[i]; s_first[i] = a.t.first_code[i]; s_findex[i] = a.t.first_index[i]; }
@@ -628,8 +666,8 @@ __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
 // dequantisation, verbatim values, re-zero filter and store in one kernel; residuals never leave the
 // compute unit (Sec. 3.4: "decompress ... when needed" as one pass over the container).
 //
-// A wavefront owns a unit of whole planes and walks it in strips: runs of whole rows whose elements
-// lie inside 64 consecutive chunks.  Per strip:
+// The tensor is cut into segments of whole planes and a segment into strips: runs of whole rows whose
+// elements lie inside 64 consecutive chunks (about 4032 elements).  A wavefront takes a strip:
 //   1. the words of the strip's chunks come global -> LDS with coalesced loads;
 //   2. every lane decodes one chunk, 64 symbols, into 32 registers (pairs of int16 residuals);
 //   3. the lanes write their registers to the same LDS region, one row of kFuPitch words per chunk
@@ -638,19 +676,35 @@ __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
 //      column prefix in a register per column, * 2eb, store.  Rows that take at most 32 lanes are
 //      walked several at a time (slots of lanes side by side); the column prefix then also runs
 //      across the slots of a step (cross-lane permutes), and what a plane has summed up so far is
-//      handed from step to step and strip to strip through the lanes of the last row.
+//      handed from step to step through the lanes of the last row.
 // A strip need not end at a plane boundary: the column sums restart wherever a plane starts.
+//
+// Who takes which strip.  Planes of at most 128 columns (COOP): one segment per workgroup, its strips
+// dealt to the twelve wavefronts in turn, so the work divides evenly whatever the plane size.  A strip
+// that starts inside a plane needs that plane's column sums over the rows above: every strip adds up
+// the residuals of its last (unfinished) plane column by column, which after a prefix over the
+// columns is what the strip contributes, adds what it received itself if the plane started earlier,
+// and hands the result to the next strip through LDS (a slot and two sequence numbers per wavefront).
+// That sum costs a fraction of the scan, and it is ready long before the strip's own scan is, so the
+// wavefronts of a workgroup decode and scan side by side instead of one after the other.  Wider
+// planes: a segment per wavefront (a.G planes), the sums stay in its registers.
+//
 // The re-zero filter needs no instruction here: a lattice value q * 2eb lies within eb of zero only
 // for q == 0, which already gives +0.0; verbatim values are filtered where they are written.
 template <int NSEG, int MODE, int OUT, int VEC>
 __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
     constexpr uint32_t OS = OUT ? 2u : 4u;                   // bytes per output element
+    constexpr bool COOP = NSEG == 1 || (NSEG == 2 && VEC == 1);     // planes of at most kFuCarryW columns
+    constexpr uint32_t NWG = COOP ? (uint32_t)kFuWaves : 1u;        // wavefronts that share a segment
     extern __shared__ uint32_t s_dyn_ds[];                  // per wavefront: strip (kFuStripWords), escape values (kFuEscEntries)
     __shared__ uint32_t s_lut[kLutSize];
     __shared__ uint32_t s_sub[kSubEntries / 2u];
     __shared__ uint64_t s_limit[65];
     __shared__ uint64_t s_first[65];
     __shared__ uint32_t s_findex[65];
+    __shared__ int32_t s_carry[COOP ? kFuWaves : 1][COOP ? kFuCarryW : 1];   // column sums a strip hands to the next one
+    __shared__ uint32_t s_ready[kFuWaves], s_acked[kFuWaves];               // strip number + 1 of the slot's content / of its last reader
+    __shared__ uint32_t s_cnt[(MODE != 2) ? kFuWaves : 1][64];                // MODE 0 / 1: escapes per slot of lanes
 
     if (a.ctl->status & ST_FORMAT) return;
 
@@ -669,14 +723,15 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
     const float eb = __uint_as_float(hdr->eb_bits);
     const float ebx2 = __uint_as_float(hdr->ebx2_bits);
 
-    // ---- decode tables into LDS ----
+    // ---- decode tables into LDS (every load independent of the others: one round trip) ----
     const bool c16 = a.t.meta[4] != 0u;
     {
-        const uint32_t *src = c16 ? reinterpret_cast<const uint32_t *>(a.t.lut16) : a.t.lut;
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(a.t.lut16);     // the compact table, or a copy of the general one
         for (uint32_t i = tid; i < kLutSize; i += kFuBlock) s_lut[i] = src[i];
-        if (c16) for (uint32_t i = tid; i < kSubEntries / 2u; i += kFuBlock) s_sub[i] = reinterpret_cast<const uint32_t *>(a.t.sub16)[i];
+        for (uint32_t i = tid; i < kSubEntries / 2u; i += kFuBlock) s_sub[i] = reinterpret_cast<const uint32_t *>(a.t.sub16)[i];
     }
     for (uint32_t i = tid; i < 65u; i += kFuBlock) { s_limit[i] = a.t.limit[i]; s_first[i] = a.t.first_code[i]; s_findex[i] = a.t.first_index[i]; }
+    if (tid < (uint32_t)kFuWaves) { s_ready[tid] = 0u; s_acked[tid] = 0u; }
     DsTables t;
     t.lut = s_lut; t.sub = reinterpret_cast<const uint16_t *>(s_sub);
     t.limit = s_limit; t.first = s_first; t.findex = s_findex; t.sorted = a.t.sorted;
@@ -705,113 +760,227 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
         lane_on = lane < L;
     }
     const uint64_t lt_mask = (1ull << lane) - 1ull;
-    // element offset of my first column inside a step; 0x1fffffff for "no element" (times 2 or 4 it still
-    // lies beyond every strip, so the access is dropped)
+    // kNoElem for "no element": as an element offset times 2 or 4 it lies beyond every strip, so a
+    // buffer access with it is dropped
     constexpr uint32_t kNoElem = 0x1fffffffu;
-    uint32_t col[NSEG];
+    uint32_t colw[NSEG];                                      // my first column's index in its row (kNoElem if none)
 #pragma unroll
     for (int s = 0; s < NSEG; ++s) {
         const uint32_t w = wl + (uint32_t)s * kWave;
-        col[s] = (lane_on && w < L) ? slot * W + w * (uint32_t)VEC : kNoElem;
+        const bool on = lane_on && w < L;
+        colw[s] = on ? w * (uint32_t)VEC : kNoElem;
     }
-    // MODE 0 / 1: lanes that hold my column in the slots 1, 2, 4, ... rows above mine (byte addresses for the
-    // cross-lane permute), and the lane part of the address of "my column in slot k"
-    uint32_t src_up[6];
-#pragma unroll
-    for (uint32_t lv = 0; lv < 6u; ++lv) {
-        const uint32_t dd = 1u << lv;
-        uint32_t sl = slot >= dd ? slot - dd : 0u;
-        uint32_t ln = lane;
-        if (MODE == 0) { const uint32_t rw = fdiv(sl, a.divSpr); ln = rw * 16u + (sl - rw * spr) * L + wl; }
-        if (MODE == 1) ln = sl * 32u + wl;
-        src_up[lv] = ln * 4u;
-    }
+    // next strip boundary after s (a strip = whole rows inside 64 consecutive chunks), inside a segment that ends at e_end
+    auto strip_end = [&](uint32_t s, uint32_t e_end) {
+        const uint32_t lim = fdiv(((s >> 6) + 64u) << 6, a.divW) * W;
+        return lim < e_end ? lim : e_end;
+    };
+    // first word and number of words of the chunks whose offsets the lanes hold (lane 0: the first chunk's; off_end: that of
+    // the chunk behind the last one, c_end), clamped to the payload; uniform results
+    auto words_of = [&](uint32_t off_mine, uint32_t off_end, uint32_t c_end, uint32_t &w_begin, uint32_t &n_words) {
+        uint32_t w_end = (c_end < n_chunks) ? (uint32_t)__builtin_amdgcn_readfirstlane((int)off_end) : payload_words;
+        w_begin = (uint32_t)__builtin_amdgcn_readfirstlane((int)off_mine);
+        if (w_end > payload_words) w_end = payload_words;
+        if (w_begin > w_end) w_begin = w_end;
+        n_words = w_end - w_begin;
+    };
+    // wait until *flag >= want (LDS; the writer is another wavefront of this workgroup working on an earlier strip)
+    auto wait_for = [&](const uint32_t *flag, uint32_t want) {
+        uint32_t spins = 0;
+        while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < want) {
+            __builtin_amdgcn_s_sleep(2);
+            if (++spins > (1u << 24)) { if (lane == 0) atomicOr(&a.ctl->status, (uint32_t)ST_INTERNAL); break; }   // cannot happen: turns a hang into an error
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    };
 
-    const uint32_t waves_total = gridDim.x * (uint32_t)kFuWaves;
-    for (uint32_t unit = wave * gridDim.x + blockIdx.x; unit < a.n_units; unit += waves_total) {
-        const uint32_t p0 = unit * a.G;
-        const uint32_t p1 = (a.planes - p0 < a.G) ? a.planes : p0 + a.G;
+    const uint32_t gw = COOP ? wave : 0u;                     // my place among the wavefronts of my segment
+    const uint32_t n_seg = COOP ? gridDim.x : a.n_units;
+    const uint32_t seg_planes = COOP ? (a.planes + gridDim.x - 1u) / gridDim.x : a.G;
+    const uint32_t seg_first = COOP ? blockIdx.x : wave * gridDim.x + blockIdx.x;
+    const uint32_t seg_step = COOP ? n_seg : gridDim.x * (uint32_t)kFuWaves;
+    uint32_t published = 0;                                   // COOP: strip number + 1 of my last hand-over that somebody reads
+
+    for (uint32_t seg = seg_first; seg < n_seg; seg += seg_step) {
+        const uint32_t p0 = seg * seg_planes;
+        if (p0 >= a.planes) break;
+        const uint32_t p1 = (a.planes - p0 < seg_planes) ? a.planes : p0 + seg_planes;
         const uint32_t e_a = p0 * P, e_b = p1 * P;
-        uint32_t rpos = 0;
-        if (n_rec) rpos = rec_lower_bound(rec, 0, n_rec, 2u * e_a, lane);
+        uint32_t rpos = 0;                                  // records before my current strip (only ever moves forward)
         int32_t q[NSEG][VEC];                               // MODE 2: running column sums; MODE 0 / 1: the plane's sums up to the last row of the step before
 #pragma unroll
         for (int s = 0; s < NSEG; ++s)
 #pragma unroll
             for (int v = 0; v < VEC; ++v) q[s][v] = 0;
 
+        bool pf_have = false;                               // what has been asked for ahead of time for my next strip
+        uint32_t pf_off_lane = 0, pf_off_end = 0;
+        uint32_t pf_words[kFuPrefetch];
+#pragma unroll
+        for (uint32_t jj = 0; jj < kFuPrefetch; ++jj) pf_words[jj] = 0u;
+        // my first strip: number gw of the segment
+        uint32_t j = gw;
         uint32_t s_a = e_a;
+        for (uint32_t i = 0; i < gw && s_a < e_b; ++i) s_a = strip_end(s_a, e_b);
         while (s_a < e_b) {
-            // ---- the strip: whole rows from s_a on, inside chunks [c0, c0 + 64) ----
+            const uint32_t s_b = strip_end(s_a, e_b);
             const uint32_t c0 = s_a >> 6;
-            const uint32_t lim = fdiv((c0 + 64u) << 6, a.divW) * W;         // end of the last whole row inside those chunks
-            const uint32_t s_b = lim < e_b ? lim : e_b;
             const uint32_t c1 = (s_b + 63u) >> 6;                             // <= c0 + 64
             const uint32_t rows = fdiv(s_b - s_a, a.divW);
+            const uint32_t row0 = fdiv(s_a, a.divW);
+            const uint32_t h0 = row0 - fdiv(row0, a.divH) * H;   // row of the strip's first row inside its plane
+            // the strip's last plane: it starts at row `lastseg` of the strip, or before the strip (then `fresh` is false)
+            const uint32_t h_last = (h0 + rows - 1u) - fdiv(h0 + rows - 1u, a.divH) * H;
+            const bool fresh = h_last + 1u <= rows;
+            const uint32_t lastseg = fresh ? rows - (h_last + 1u) : 0u;
+            const bool carry_in = COOP && h0 != 0u;             // (then the strip is not the first of its segment)
+            const bool hand_on = COOP && s_b < e_b && h_last + 1u != H;    // the next strip starts inside my last plane
             const uint32_t c = c0 + lane;
+            const uint32_t prev_w = (wave + (uint32_t)kFuWaves - 1u) % (uint32_t)kFuWaves;
 
-            // ---- 1. words of the chunks [c0, c1) -> LDS ----
-            const uint32_t off_lane = chunk_off[c < c1 ? c : c0];
-            const uint32_t off_end = chunk_off[c1 < n_chunks ? c1 : c0];
+            // ---- 1. words of the chunks [c0, c1) -> LDS.  The chunk offsets and the first kFuPrefetch * 64 words were
+            // asked for while the strip before this one was being worked on (pf_*). ----
+            uint32_t off_lane, off_end;
+            if (pf_have) { off_lane = pf_off_lane; off_end = pf_off_end; }
+            else { off_lane = chunk_off[c < c1 ? c : c0]; off_end = chunk_off[c1 < n_chunks ? c1 : c0]; }
             const uint32_t my_off = (c < c1) ? off_lane : 0u;
-            uint32_t w_end = (c1 < n_chunks) ? off_end : payload_words;
-            uint32_t w_begin = (uint32_t)__builtin_amdgcn_readfirstlane((int)my_off);
-            if (w_end > payload_words) w_end = payload_words;
-            if (w_begin > w_end) w_begin = w_end;
-            const uint32_t n_words = w_end - w_begin;
+            uint32_t w_begin, n_words;
+            words_of(my_off, off_end, c1, w_begin, n_words);
             const bool all_staged = n_words <= kFuStripWords - 4u;             // (the reader looks up to two words ahead)
             if (all_staged) {
                 const __amdgpu_buffer_rsrc_t r_w = make_rsrc(payload + w_begin, n_words * 4u);   // loads past the end give 0
-                for (uint32_t i0 = 0; i0 < n_words; i0 += kDsStageBatch * kWave) {
+                uint32_t i_first = 0;
+                if (pf_have) {
+#pragma unroll
+                    for (uint32_t jj = 0; jj < kFuPrefetch; ++jj) {
+                        const uint32_t i = jj * kWave + lane;
+                        if (i < n_words) strip[i] = pf_words[jj];
+                    }
+                    i_first = kFuPrefetch * kWave;
+                }
+                for (uint32_t i0 = i_first; i0 < n_words; i0 += kDsStageBatch * kWave) {
                     uint32_t v[kDsStageBatch];
 #pragma unroll
-                    for (uint32_t j = 0; j < kDsStageBatch; ++j)
-                        v[j] = __builtin_amdgcn_raw_buffer_load_b32(r_w, (int)((i0 + j * kWave + lane) * 4u), 0, 0);
+                    for (uint32_t jj = 0; jj < kDsStageBatch; ++jj)
+                        v[jj] = __builtin_amdgcn_raw_buffer_load_b32(r_w, (int)((i0 + jj * kWave + lane) * 4u), 0, 0);
 #pragma unroll
-                    for (uint32_t j = 0; j < kDsStageBatch; ++j) {
-                        const uint32_t i = i0 + j * kWave + lane;
-                        if (i < n_words) strip[i] = v[j];
+                    for (uint32_t jj = 0; jj < kDsStageBatch; ++jj) {
+                        const uint32_t i = i0 + jj * kWave + lane;
+                        if (i < n_words) strip[i] = v[jj];
+                    }
+                }
+            }
+            // my next strip (NWG strips on): its chunk offsets are asked for now
+            uint32_t n_sa = s_b;
+            for (uint32_t i = 1; i < NWG && n_sa < e_b; ++i) n_sa = strip_end(n_sa, e_b);
+            const bool n_have = n_sa < e_b;
+            const uint32_t n_sb = n_have ? strip_end(n_sa, e_b) : e_b;
+            const uint32_t n_c0 = n_sa >> 6, n_c1 = (n_sb + 63u) >> 6;
+            if (n_have) {
+                pf_off_lane = chunk_off[n_c0 + lane < n_c1 ? n_c0 + lane : n_c0];
+                pf_off_end = chunk_off[n_c1 < n_chunks ? n_c1 : n_c0];
+            }
+            // MODE 0 / 1: the strip's rows are dealt to the K slots of lanes, slot k walks rows [ra, rb) on its own
+            // (MODE 2: one slot, all rows).  ha: my first row inside its plane; my last plane starts at row
+            // `lastseg_l` of the strip, or before my rows (then fresh_l is false).
+            uint32_t rps = rows, ra = 0u, rb = rows, ha = h0, lastseg_l = lastseg;
+            bool fresh_l = fresh;
+            auto slot_rows = [&](uint32_t k, uint32_t &r0, uint32_t &r1, bool &fr, uint32_t &ls) {
+                r0 = k * rps; r0 = r0 < rows ? r0 : rows;
+                r1 = r0 + rps; r1 = r1 < rows ? r1 : rows;
+                fr = false; ls = r0;
+                if (r1 > r0) {
+                    const uint32_t x = h0 + r1 - 1u;
+                    const uint32_t hl = x - fdiv(x, a.divH) * H;
+                    fr = hl + 1u <= r1 - r0;
+                    ls = fr ? r1 - (hl + 1u) : r0;
+                }
+            };
+            if (MODE != 2) {
+                rps = fdiv(rows + K - 1u, a.divK);
+                slot_rows(slot, ra, rb, fresh_l, lastseg_l);
+                const uint32_t x = h0 + ra;
+                ha = x - fdiv(x, a.divH) * H;
+            }
+            const bool exchange = hand_on || MODE != 2;       // column sums go through the exchange area of LDS
+            // my exchange area: free once the reader of what I handed on last has taken it; cleared for the escapes' share
+            if (exchange) {
+                if (published) wait_for(&s_acked[wave], published);
+                for (uint32_t i = lane; i < kFuCarryW; i += kWave) s_carry[wave][COOP ? i : 0u] = 0;
+                if (MODE != 2) s_cnt[wave][lane] = 0u;
+            }
+            wave_lds_fence();
+
+            // ---- 2. decode, one lane per chunk, into registers: two halves of sixteen pairs, each filled by
+            // a loop over four groups of four pairs (a vector of 16 words indexed by a wavefront-uniform
+            // counter stays in registers; an array would be placed in scratch memory) ----
+            u32x16_t pa = {}, pb = {};
+            {
+                const uint32_t last = n_words ? n_words - 1u : 0u;
+                uint32_t w0 = (my_off < w_begin) ? 0u : my_off - w_begin;
+                w0 = w0 < last ? w0 : last;
+                // (one call per address space of the words, so that the reader's loads are LDS or global
+                // instructions, not generic ones)
+                auto run = [&](auto c16_tag, auto wsrc) {
+                    BitBuf<decltype(c16_tag)::value> bb;
+                    bb.open(wsrc, last, w0);
+#pragma nounroll
+                    for (uint32_t j4 = 0; j4 < 4u; ++j4) {
+#pragma unroll
+                        for (uint32_t i = 0; i < 4u; ++i) pa[4u * j4 + i] = bb.next_pair(t);
+                    }
+#pragma nounroll
+                    for (uint32_t j4 = 0; j4 < 4u; ++j4) {
+#pragma unroll
+                        for (uint32_t i = 0; i < 4u; ++i) pb[4u * j4 + i] = bb.next_pair(t);
+                    }
+                };
+                if (c < c1 && n_words) {
+                    if (all_staged) {
+                        if (c16) run(std::true_type{}, strip); else run(std::false_type{}, strip);
+                    } else {
+                        const uint32_t *gsrc = payload + w_begin;
+                        if (c16) run(std::true_type{}, gsrc); else run(std::false_type{}, gsrc);
                     }
                 }
             }
             wave_lds_fence();
 
-            // ---- 2. decode, one lane per chunk, into registers: eight groups of four pairs, written out
-            // one after the other (a loop over an array of groups would put the array into scratch memory) ----
-            uint4 g0, g1, g2, g3, g4, g5, g6, g7;
-            g0 = g1 = g2 = g3 = g4 = g5 = g6 = g7 = make_uint4(0u, 0u, 0u, 0u);
-            {
-                const uint32_t last = n_words ? n_words - 1u : 0u;
-                uint32_t w0 = (my_off < w_begin) ? 0u : my_off - w_begin;
-                w0 = w0 < last ? w0 : last;
-                const uint32_t *words = all_staged ? strip : payload + w_begin;
-                auto run = [&](auto c16_tag, const uint32_t *wsrc) {
-                    BitBuf<decltype(c16_tag)::value> bb;
-                    bb.open(wsrc, last, w0);
-                    auto four = [&](uint4 &g) { g.x = bb.next_pair(t); g.y = bb.next_pair(t); g.z = bb.next_pair(t); g.w = bb.next_pair(t); };
-                    four(g0); four(g1); four(g2); four(g3); four(g4); four(g5); four(g6); four(g7);
-                };
-                if (c < c1 && n_words) {
-                    if (c16) run(std::true_type{}, words); else run(std::false_type{}, words);
+            // the first words of my next strip: on their way while this strip is scanned
+            pf_have = false;
+            if (n_have) {
+                uint32_t nb, nn;
+                words_of((n_c0 + lane < n_c1) ? pf_off_lane : 0u, pf_off_end, n_c1, nb, nn);
+                if (nn <= kFuStripWords - 4u) {
+                    const __amdgpu_buffer_rsrc_t r_n = make_rsrc(payload + nb, nn * 4u);
+#pragma unroll
+                    for (uint32_t jj = 0; jj < kFuPrefetch; ++jj)
+                        pf_words[jj] = __builtin_amdgcn_raw_buffer_load_b32(r_n, (int)((jj * kWave + lane) * 4u), 0, 0);
                 }
+                pf_have = true;
             }
-            wave_lds_fence();
 
             // ---- 3. registers -> LDS, one row of kFuPitch words per chunk ----
             {
                 uint4 *row = reinterpret_cast<uint4 *>(strip + lane * kFuPitch);
-                row[0] = g0; row[1] = g1; row[2] = g2; row[3] = g3; row[4] = g4; row[5] = g5; row[6] = g6; row[7] = g7;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    row[i] = make_uint4(pa[4 * i], pa[4 * i + 1], pa[4 * i + 2], pa[4 * i + 3]);
+                    row[4 + i] = make_uint4(pb[4 * i], pb[4 * i + 1], pb[4 * i + 2], pb[4 * i + 3]);
+                }
             }
 
-            // ---- the strip's escaped residuals, their values compacted into LDS in element order ----
-            const uint32_t r_begin = rpos;
-            uint32_t r_end = rpos;
+            // ---- the strip's escaped residuals: their values compacted into LDS in element order; each also goes,
+            // column by column, into the exchange area of the slot whose last plane it lies in (minus the marker
+            // the residual holds); per slot they are counted, for the slot's place in the list ----
+            uint32_t r_begin = rpos, r_end = rpos;
             uint32_t n_esc = 0;
             bool has_verbatim = false;
-            if (n_rec && rpos < n_rec) {
+            if (n_rec) {
+                r_begin = rec_lower_bound(rec, rpos, n_rec, 2u * s_a, lane);
                 const uint32_t span = 2u * (s_b - s_a);           // at most two records per element
-                const uint32_t hi = (n_rec - rpos < span) ? n_rec : rpos + span;
-                r_end = rec_lower_bound(rec, rpos, hi, 2u * s_b, lane);
+                const uint32_t hi = (n_rec - r_begin < span) ? n_rec : r_begin + span;
+                r_end = rec_lower_bound(rec, r_begin, hi, 2u * s_b, lane);
                 for (uint32_t base = r_begin; base < r_end; base += kWave) {
                     const uint32_t k = base + lane;
                     uint32_t key = 1u, val = 0;
@@ -822,6 +991,23 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
                     if (is_e) {
                         const uint32_t pos = n_esc + (uint32_t)__popcll(esc_mask & lt_mask);
                         if (pos < kFuEscEntries) esc[pos] = (int32_t)val;
+                        if (exchange) {
+                            const uint32_t e = (key >> 1) - s_a;                 // inside the strip
+                            const uint32_t r = fdiv(e, a.divW);
+                            const uint32_t cw = e - r * W;
+                            uint32_t ke = 0u, ls = lastseg;
+                            if (MODE != 2) {
+                                // r / rps for small numbers: the float quotient is off by one at most
+                                ke = (uint32_t)((float)r / (float)rps);
+                                if (ke * rps > r) --ke;
+                                if ((ke + 1u) * rps <= r) ++ke;
+                                uint32_t r0, r1; bool fr;
+                                slot_rows(ke, r0, r1, fr, ls);
+                                atomicAdd(&s_cnt[wave][ke & 63u], 1u);
+                            }
+                            if (r >= ls && (MODE != 2 || hand_on))
+                                atomicAdd(&s_carry[wave][COOP ? (ke * W + cw) & (kFuCarryW - 1u) : 0u], (int32_t)(val - (uint32_t)esc_marker));
+                        }
                     }
                     n_esc += (uint32_t)__popcll(esc_mask);
                 }
@@ -829,59 +1015,212 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
             }
             const bool esc_in_lds = n_esc <= kFuEscEntries;
             wave_lds_fence();
+            uint32_t esc_base = 0;                               // escapes of the slots in front of mine
+            if (MODE != 2 && n_esc) {
+                const uint32_t mine = s_cnt[wave][lane];
+                const uint32_t incl = wave_incl_scan<uint32_t>(mine);
+                wave_lds_fence();
+                s_cnt[wave][lane] = incl - mine;
+                wave_lds_fence();
+                esc_base = s_cnt[wave][slot & 63u];
+            }
 
-            // ---- 4. scan the rows out of LDS ----
             const uint32_t rel0 = s_a - (c0 << 6);               // the strip's first element inside its chunks
-            const uint32_t row0 = fdiv(s_a, a.divW);
-            const uint32_t h0 = row0 - fdiv(row0, a.divH) * H;   // row of the strip's first row inside its plane
-            const __amdgpu_buffer_rsrc_t r_out = make_rsrc(reinterpret_cast<char *>(a.out) + (size_t)s_a * OS, (s_b - s_a) * OS);
-            const uint32_t n_steps = (rows + K - 1u) / K;
-            const uint32_t step_elems = K * W;
-            uint32_t h_lane = h0 + slot;                         // my row inside its plane (MODE 0 / 1)
-            h_lane -= fdiv(h_lane, a.divH) * H;
-            const uint32_t k_mod = K - fdiv(K, a.divH) * H;
-            uint32_t h_row = h0;                                 // MODE 2: the step's row inside its plane (uniform)
-            uint32_t cur = 0;                                    // escapes consumed so far
+            // a strip's element `off` in LDS: ((rel0 + off) / 64) * kFuPitch * 4 + ((rel0 + off) % 64) * 2 bytes
+            auto lds_of = [&](uint32_t off) { const uint32_t rel = off + rel0; return (rel << 1) + ((rel >> 6) << 4); };
+            auto lds_read = [&](uint32_t off) -> uint32_t {      // VEC == 2: two residuals; else one (sign-extended)
+                const char *p = reinterpret_cast<const char *>(strip) + lds_of(off);
+                if (VEC == 2) return *reinterpret_cast<const uint32_t *>(p);
+                return (uint32_t)(int32_t)*reinterpret_cast<const int16_t *>(p);
+            };
 
-            auto scan_rows = [&](auto esc_tag) {
-                constexpr int ESC = decltype(esc_tag)::value;   // 0: the strip has no escape, 1: values in LDS, 2: too many for LDS, look them up in the container
-                for (uint32_t tstep = 0; tstep < n_steps; ++tstep) {
-                    const uint32_t e_step = tstep * step_elems;          // uniform
-                    const uint32_t rows_left = rows - tstep * K;
+            // ---- column sums above my rows.  Every slot adds up the residuals of its last (unfinished) plane column
+            // by column (an escaped one counts as its marker; the difference is in the exchange area already), a
+            // prefix over the columns turns that into what the slot adds to the plane's column sums; a slot then
+            // collects what the slots in front of it add, back to the one its plane starts in, and what the strip
+            // itself received if the plane started before the strip; the last slot hands the sums on. ----
+            if (COOP) {
+                int32_t tcol[NSEG][VEC];
+#pragma unroll
+                for (int s = 0; s < NSEG; ++s)
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) tcol[s][v] = 0;
+                if (exchange) {
+                    int32_t dsum[NSEG][VEC];
+#pragma unroll
+                    for (int s = 0; s < NSEG; ++s)
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) dsum[s][v] = 0;
+                    const uint32_t r_first = MODE == 2 ? lastseg : 0u;       // MODE 2: uniform
+                    const uint32_t r_count = MODE == 2 ? rows - lastseg : rps;
+#pragma unroll 4
+                    for (uint32_t ts = 0; ts < r_count; ++ts) {
+                        const uint32_t r = (MODE == 2 ? r_first : ra) + ts;   // my row inside the strip
+#pragma unroll
+                        for (int s = 0; s < NSEG; ++s) {
+                            const bool on = colw[s] != kNoElem && r >= lastseg_l && r < rb;
+                            const uint32_t raw = lds_read(on ? r * W + colw[s] : 0u);
+                            if (VEC == 2) {
+                                dsum[s][0] += on ? (int32_t)(int16_t)(raw & 0xffffu) : 0;
+                                dsum[s][VEC - 1] += on ? (int32_t)raw >> 16 : 0;
+                            } else {
+                                dsum[s][0] += on ? (int32_t)raw : 0;
+                            }
+                        }
+                    }
+                    // prefix over the columns, on top of the escapes' share
                     int32_t carry = 0;
 #pragma unroll
                     for (int s = 0; s < NSEG; ++s) {
-                        const bool on = col[s] != kNoElem && (MODE == 2 || slot < rows_left);
-                        const uint32_t off = on ? col[s] + e_step : kNoElem;              // element offset inside the strip
-                        const uint32_t rel = (on ? off : 0u) + rel0;
-                        const uint32_t lds_byte = (rel << 1) + ((rel >> 6) << 4);          // (rel / 64) * kFuPitch * 4 + (rel % 64) * 2
+                        int32_t dd[VEC];
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v)
+                            dd[v] = colw[s] != kNoElem ? (int32_t)((uint32_t)dsum[s][v] + (uint32_t)s_carry[wave][COOP ? (slot * W + colw[s] + (uint32_t)v) & (kFuCarryW - 1u) : 0u]) : 0;
+                        int32_t mine = dd[0];
+#pragma unroll
+                        for (int v = 1; v < VEC; ++v) mine = (int32_t)((uint32_t)mine + (uint32_t)dd[v]);
+                        int32_t incl = run_scan<MODE>(mine, wl, L);
+                        incl = (int32_t)((uint32_t)incl + (uint32_t)carry);
+                        if (NSEG > 1) carry = __builtin_amdgcn_readlane(incl, 63);
+                        tcol[s][VEC - 1] = incl;
+#pragma unroll
+                        for (int v = VEC - 2; v >= 0; --v) tcol[s][v] = (int32_t)((uint32_t)tcol[s][v + 1] - (uint32_t)dd[v + 1]);
+                    }
+                    wave_lds_fence();                             // everybody has read the escapes' share
+                }
+                // MODE 0 / 1: the slots exchange their sums
+                int32_t acc[VEC];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) acc[v] = 0;
+                bool reached = false;                             // the slot my first row's plane starts in has been added
+                if (MODE != 2) {
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v)
+                        if (colw[0] != kNoElem) s_carry[wave][COOP ? (slot * W + colw[0] + (uint32_t)v) & (kFuCarryW - 1u) : 0u] = tcol[0][v];
+                    wave_lds_fence();
+                    for (uint32_t dd = 1; dd < K; ++dd) {         // slots in front of mine, nearest first
+                        const bool take = slot >= dd && !reached && colw[0] != kNoElem;
+                        const uint32_t kk = take ? slot - dd : 0u;
+                        uint32_t r0, r1, ls; bool fr;
+                        slot_rows(kk, r0, r1, fr, ls);
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) {
+                            const int32_t tv = s_carry[wave][COOP ? (kk * W + (take ? colw[0] : 0u) + (uint32_t)v) & (kFuCarryW - 1u) : 0u];
+                            acc[v] = take ? (int32_t)((uint32_t)acc[v] + (uint32_t)tv) : acc[v];
+                        }
+                        reached = reached || (take && fr);
+                    }
+                    wave_lds_fence();                             // all sums read: the area may take the hand-over
+                }
+                // what the strip received
+                int32_t cin[NSEG][VEC];
+#pragma unroll
+                for (int s = 0; s < NSEG; ++s)
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) cin[s][v] = 0;
+                if (carry_in) {
+                    wait_for(&s_ready[prev_w], j);                // strip j - 1 has handed over
+#pragma unroll
+                    for (int s = 0; s < NSEG; ++s)
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) cin[s][v] = colw[s] != kNoElem ? s_carry[prev_w][COOP ? (colw[s] + (uint32_t)v) & (kFuCarryW - 1u) : 0u] : 0;
+                    wave_lds_fence();
+                    if (lane == 0) __hip_atomic_store(&s_acked[prev_w], j, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
+                // the sums above my first row
+#pragma unroll
+                for (int s = 0; s < NSEG; ++s)
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) {
+                        if (MODE == 2) q[s][v] = cin[s][v];
+                        else q[s][v] = ha != 0u ? (int32_t)((uint32_t)acc[v] + (reached ? 0u : (uint32_t)cin[s][v])) : 0;
+                    }
+                if (hand_on) {
+                    const bool last_slot = MODE == 2 || (rb == rows && rb > ra);
+#pragma unroll
+                    for (int s = 0; s < NSEG; ++s)
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v)
+                            if (colw[s] != kNoElem && last_slot)
+                                s_carry[wave][COOP ? (colw[s] + (uint32_t)v) & (kFuCarryW - 1u) : 0u] = (int32_t)((uint32_t)tcol[s][v] + (fresh_l ? 0u : (uint32_t)q[s][v]));
+                    wave_lds_fence();
+                    if (lane == 0) __hip_atomic_store(&s_ready[wave], j + 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    published = j + 1u;
+                } else {
+                    published = 0u;
+                }
+            }
+
+            // ---- 4. scan the rows out of LDS ----
+            const __amdgpu_buffer_rsrc_t r_out = make_rsrc(reinterpret_cast<char *>(a.out) + (size_t)s_a * OS, (s_b - s_a) * OS);
+            const uint32_t n_steps = MODE == 2 ? rows : rps;
+            uint32_t h_row = h0;                                 // MODE 2: the step's row inside its plane (uniform)
+            uint32_t h_l = ha;                                   // MODE 0 / 1: my row inside its plane
+            uint32_t cur = esc_base;                             // my place in the list of escaped values
+            // lanes of my slot (MODE 0 / 1: the escapes of a step are taken slot by slot)
+            uint64_t slot_mask = ~0ull;
+            if (MODE == 0) slot_mask = ((1ull << L) - 1ull) << ((lane & ~15u) + (slot - (lane >> 4) * spr) * L);
+            if (MODE == 1) slot_mask = ((1ull << L) - 1ull) << (lane & 32u);
+
+            uint32_t sbase[NSEG], rbase[NSEG];                   // my first column in my first row: element of the strip (kNoElem: none) / where to read it
+#pragma unroll
+            for (int s = 0; s < NSEG; ++s) {
+                sbase[s] = colw[s] != kNoElem ? ra * W + colw[s] : kNoElem;
+                rbase[s] = colw[s] != kNoElem ? ra * W + colw[s] : 0u;
+            }
+            const uint32_t n_mine = rb - ra;                     // MODE 0 / 1: rows of my slot
+
+            auto scan_rows = [&](auto esc_tag) {
+                constexpr int ESC = decltype(esc_tag)::value;   // 0: the strip has no escape, 1: values in LDS, 2: too many for LDS, look them up in the container
+                constexpr uint32_t U = 2u;                       // steps per batch of LDS reads; two batches alternate
+                // Step ts: my first column is element sbase[s] + ts * W of the strip (rows I do not have: see n_mine).
+                // A lane without a column reads the strip's first word (what it computes goes nowhere: it sits
+                // behind the row's lanes in every scan, and its store is dropped); reads of steps past the end
+                // (the batch fetched ahead) may leave the strip, which LDS tolerates.
+                auto fetch = [&](uint32_t t0, uint32_t (&raw)[U][NSEG]) {
+#pragma unroll
+                    for (uint32_t u = 0; u < U; ++u) {
+                        const uint32_t tw = (t0 + u) * W;                 // uniform
+#pragma unroll
+                        for (int s = 0; s < NSEG; ++s) raw[u][s] = lds_read(rbase[s] + tw);
+                    }
+                };
+                auto steps_of = [&](uint32_t t0, const uint32_t (&raw)[U][NSEG]) {
+#pragma unroll
+                  for (uint32_t u = 0; u < U; ++u) {
+                    const uint32_t tstep = t0 + u;
+                    if (tstep >= n_steps) break;                          // uniform
+                    int32_t carry = 0;
+                    const uint32_t tw = tstep * W;                              // uniform
+#pragma unroll
+                    for (int s = 0; s < NSEG; ++s) {
+                        // element offset inside the strip (kNoElem or beyond: no element, the store is dropped)
+                        const uint32_t off = (MODE == 2 || tstep < n_mine) ? sbase[s] + tw : kNoElem;
                         int32_t d[VEC];
                         if (VEC == 2) {
-                            const uint32_t two = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(strip) + lds_byte);
-                            d[0] = (int32_t)(int16_t)(two & 0xffffu);
-                            d[VEC - 1] = (int32_t)two >> 16;
+                            d[0] = (int32_t)(int16_t)(raw[u][s] & 0xffffu);
+                            d[VEC - 1] = (int32_t)raw[u][s] >> 16;
                         } else {
-                            d[0] = (int32_t)*reinterpret_cast<const int16_t *>(reinterpret_cast<const char *>(strip) + lds_byte);
+                            d[0] = (int32_t)raw[u][s];
                         }
-#pragma unroll
-                        for (int v = 0; v < VEC; ++v) d[v] = on ? d[v] : 0;
                         if (ESC) {
+                            const bool on = sbase[s] != kNoElem && (MODE == 2 || tstep < n_mine);
                             bool is_esc[VEC];
                             uint64_t em[VEC], any_esc = 0ull;
 #pragma unroll
                             for (int v = 0; v < VEC; ++v) {
-                                is_esc[v] = d[v] == esc_marker;
+                                is_esc[v] = on && d[v] == esc_marker;
                                 em[v] = wave_ballot(is_esc[v]);
                                 any_esc |= em[v];
                             }
                             if (any_esc) {                            // wavefront-uniform
-                                // escapes in element order: the lanes hold consecutive elements (slots in order,
-                                // columns in order), then a lane's own columns
+                                // escapes of my slot in element order: lanes, then a lane's own columns
                                 uint32_t before = 0, all = 0;
 #pragma unroll
                                 for (int v = 0; v < VEC; ++v) {
-                                    before += (uint32_t)__popcll(em[v] & lt_mask);
-                                    all += (uint32_t)__popcll(em[v]);
+                                    const uint64_t m = em[v] & slot_mask;
+                                    before += (uint32_t)__popcll(m & lt_mask);
+                                    all += (uint32_t)__popcll(m);
                                 }
                                 uint32_t pos = cur + before;
 #pragma unroll
@@ -913,51 +1252,35 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
 #pragma unroll
                         for (int v = VEC - 2; v >= 0; --v) rp[v] = (int32_t)((uint32_t)rp[v + 1] - (uint32_t)d[v + 1]);
                         float val[VEC];
-                        if (MODE == 2) {
-                            const uint32_t keep = h_row ? ~0u : 0u;          // a plane starts: its column sums start over
+                        const uint32_t keep = (MODE == 2 ? h_row : h_l) ? ~0u : 0u;     // a plane starts: its column sums start over
 #pragma unroll
-                            for (int v = 0; v < VEC; ++v) {
-                                q[s][v] = (int32_t)(((uint32_t)q[s][v] & keep) + (uint32_t)rp[v]);
-                                val[v] = (float)q[s][v] * ebx2;
-                            }
-                        } else {
-                            // column prefix across the slots of the step (rows of one plane only), on top of
-                            // what the plane had summed up when the step began
-#pragma unroll
-                            for (int v = 0; v < VEC; ++v) {
-                                int32_t cs = rp[v];
-#pragma unroll
-                                for (uint32_t lv = 0; lv < (MODE == 1 ? 1u : 6u); ++lv) {
-                                    const uint32_t dd = 1u << lv;
-                                    if (MODE == 0 && dd >= K) break;                       // uniform
-                                    const int32_t up = __builtin_amdgcn_ds_bpermute((int)src_up[lv], cs);
-                                    cs = (slot >= dd && h_lane >= dd) ? (int32_t)((uint32_t)cs + (uint32_t)up) : cs;
-                                }
-                                const int32_t qq = (int32_t)((uint32_t)cs + (h_lane > slot ? (uint32_t)q[0][v] : 0u));
-                                val[v] = (float)qq * ebx2;
-                                // the last row of the step hands its sums to every slot of the next step
-                                const uint32_t ks = (rows_left < K ? rows_left : K) - 1u;   // uniform
-                                uint32_t ln;
-                                if (MODE == 1) ln = ks * 32u + wl;
-                                else { const uint32_t rw = fdiv(ks, a.divSpr); ln = rw * 16u + (ks - rw * spr) * L + wl; }
-                                q[0][v] = __builtin_amdgcn_ds_bpermute((int)(ln * 4u), qq);
-                            }
+                        for (int v = 0; v < VEC; ++v) {
+                            q[s][v] = (int32_t)(((uint32_t)q[s][v] & keep) + (uint32_t)rp[v]);
+                            val[v] = (float)q[s][v] * ebx2;
                         }
-                        const uint32_t off_c = off > kNoElem ? kNoElem : off;
                         if (OUT == 0 && VEC == 2) {
                             u32x2_t two;
                             two.x = __float_as_uint(val[0]); two.y = __float_as_uint(val[VEC - 1]);
-                            __builtin_amdgcn_raw_buffer_store_b64(two, r_out, (int)(off_c * 4u), 0, 0);
+                            __builtin_amdgcn_raw_buffer_store_b64(two, r_out, (int)(off * 4u), 0, 0);
                         } else if (OUT == 0) {
-                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val[0]), r_out, (int)(off_c * 4u), 0, 0);
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val[0]), r_out, (int)(off * 4u), 0, 0);
                         } else if (VEC == 2) {
-                            __builtin_amdgcn_raw_buffer_store_b32(narrow16<OUT>(val[0]) | (narrow16<OUT>(val[VEC - 1]) << 16), r_out, (int)(off_c * 2u), 0, 0);
+                            __builtin_amdgcn_raw_buffer_store_b32(narrow16<OUT>(val[0]) | (narrow16<OUT>(val[VEC - 1]) << 16), r_out, (int)(off * 2u), 0, 0);
                         } else {
-                            __builtin_amdgcn_raw_buffer_store_b16((unsigned short)narrow16<OUT>(val[0]), r_out, (int)(off_c * 2u), 0, 0);
+                            __builtin_amdgcn_raw_buffer_store_b16((unsigned short)narrow16<OUT>(val[0]), r_out, (int)(off * 2u), 0, 0);
                         }
                     }
                     if (MODE == 2) { ++h_row; h_row = (h_row == H) ? 0u : h_row; }
-                    else { h_lane += k_mod; h_lane -= (h_lane >= H) ? H : 0u; }
+                    else { ++h_l; h_l = (h_l == H) ? 0u : h_l; }
+                  }
+                };
+                uint32_t ra_[U][NSEG], rb_[U][NSEG];
+                fetch(0, ra_);
+                for (uint32_t t0 = 0; t0 < n_steps; t0 += 2u * U) {
+                    fetch(t0 + U, rb_);
+                    steps_of(t0, ra_);
+                    fetch(t0 + 2u * U, ra_);
+                    steps_of(t0 + U, rb_);
                 }
             };
             if (n_esc == 0u) scan_rows(std::integral_constant<int, 0>{});
@@ -981,7 +1304,9 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
                 }
             }
             wave_lds_fence();
-            s_a = s_b;
+
+            s_a = n_have ? n_sa : e_b;
+            j += NWG;
         }
     }
 }
