@@ -978,21 +978,31 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
             bool has_verbatim = false;
             if (n_rec) {
                 r_begin = rec_lower_bound(rec, rpos, n_rec, 2u * s_a, lane);
-                const uint32_t span = 2u * (s_b - s_a);           // at most two records per element
-                const uint32_t hi = (n_rec - r_begin < span) ? n_rec : r_begin + span;
-                r_end = rec_lower_bound(rec, r_begin, hi, 2u * s_b, lane);
-                for (uint32_t base = r_begin; base < r_end; base += kWave) {
+                r_end = r_begin;
+                for (uint32_t base = r_begin; base < n_rec; base += kWave) {     // until a record beyond the strip turns up
                     const uint32_t k = base + lane;
-                    uint32_t key = 1u, val = 0;
-                    if (k < r_end) { key = rec[2 * (size_t)k]; val = rec[2 * (size_t)k + 1]; }
-                    const bool is_e = k < r_end && !(key & 1u);
+                    uint32_t key = 0xffffffffu, val = 0;
+                    if (k < n_rec) { key = rec[2 * (size_t)k]; val = rec[2 * (size_t)k + 1]; }
+                    const bool mine = key < 2u * s_b;
+                    const uint32_t n_mine_rec = (uint32_t)__popcll(wave_ballot(mine));
+                    const bool is_e = mine && !(key & 1u);
                     const uint64_t esc_mask = wave_ballot(is_e);
-                    if (wave_ballot(k < r_end && (key & 1u))) has_verbatim = true;
+                    if (wave_ballot(mine && (key & 1u))) has_verbatim = true;
                     if (is_e) {
                         const uint32_t pos = n_esc + (uint32_t)__popcll(esc_mask & lt_mask);
-                        if (pos < kFuEscEntries) esc[pos] = (int32_t)val;
+                        const uint32_t e = (key >> 1) - s_a;                     // inside the strip
+                        int32_t held = esc_marker;                               // what the strip holds for this residual
+                        if (pos < kFuEscEntries) {
+                            esc[pos] = (int32_t)val;
+                            if (c16) {
+                                // the compact table's residuals leave room in 16 bits: the place in the list goes
+                                // into the strip, so that the scan finds the value without counting escapes
+                                held = kLut16Escape - 1 - (int32_t)pos;
+                                const uint32_t rel = e + (s_a - (c0 << 6));
+                                *reinterpret_cast<int16_t *>(reinterpret_cast<char *>(strip) + (rel << 1) + ((rel >> 6) << 4)) = (int16_t)held;
+                            }
+                        }
                         if (exchange) {
-                            const uint32_t e = (key >> 1) - s_a;                 // inside the strip
                             const uint32_t r = fdiv(e, a.divW);
                             const uint32_t cw = e - r * W;
                             uint32_t ke = 0u, ls = lastseg;
@@ -1003,20 +1013,22 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
                                 if ((ke + 1u) * rps <= r) ++ke;
                                 uint32_t r0, r1; bool fr;
                                 slot_rows(ke, r0, r1, fr, ls);
-                                atomicAdd(&s_cnt[wave][ke & 63u], 1u);
+                                if (!c16) atomicAdd(&s_cnt[wave][ke & 63u], 1u);
                             }
                             if (r >= ls && (MODE != 2 || hand_on))
-                                atomicAdd(&s_carry[wave][COOP ? (ke * W + cw) & (kFuCarryW - 1u) : 0u], (int32_t)(val - (uint32_t)esc_marker));
+                                atomicAdd(&s_carry[wave][COOP ? (ke * W + cw) & (kFuCarryW - 1u) : 0u], (int32_t)(val - (uint32_t)held));
                         }
                     }
                     n_esc += (uint32_t)__popcll(esc_mask);
+                    r_end += n_mine_rec;
+                    if (n_mine_rec < (uint32_t)kWave) break;
                 }
                 rpos = r_end;
             }
             const bool esc_in_lds = n_esc <= kFuEscEntries;
             wave_lds_fence();
             uint32_t esc_base = 0;                               // escapes of the slots in front of mine
-            if (MODE != 2 && n_esc) {
+            if (MODE != 2 && n_esc && !c16) {
                 const uint32_t mine = s_cnt[wave][lane];
                 const uint32_t incl = wave_incl_scan<uint32_t>(mine);
                 wave_lds_fence();
@@ -1171,7 +1183,7 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
             const uint32_t n_mine = rb - ra;                     // MODE 0 / 1: rows of my slot
 
             auto scan_rows = [&](auto esc_tag) {
-                constexpr int ESC = decltype(esc_tag)::value;   // 0: the strip has no escape, 1: values in LDS, 2: too many for LDS, look them up in the container
+                constexpr int ESC = decltype(esc_tag)::value;   // 0: the strip has no escape; 1: compact table, escaped residuals hold their place in the list; 2: escapes counted
                 constexpr uint32_t U = 2u;                       // steps per batch of LDS reads; two batches alternate
                 // Step ts: my first column is element sbase[s] + ts * W of the strip (rows I do not have: see n_mine).
                 // A lane without a column reads the strip's first word (what it computes goes nowhere: it sits
@@ -1203,7 +1215,31 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
                         } else {
                             d[0] = (int32_t)raw[u][s];
                         }
-                        if (ESC) {
+                        // the value of an escaped residual, looked up in the container (the list in LDS did not hold it)
+                        auto from_container = [&](uint32_t elem) -> int32_t {
+                            const uint32_t key = 2u * elem;
+                            uint32_t lo = r_begin, hi = r_end;
+                            while (lo < hi) { const uint32_t mid = (lo + hi) >> 1; if (rec[2 * (size_t)mid] < key) lo = mid + 1; else hi = mid; }
+                            return (lo < r_end && rec[2 * (size_t)lo] == key) ? (int32_t)rec[2 * (size_t)lo + 1] : 0;
+                        };
+                        if (ESC == 1) {
+                            // compact table: an escaped residual holds its place in the list (or the bare marker if the list was full)
+                            const bool on = sbase[s] != kNoElem && (MODE == 2 || tstep < n_mine);
+                            bool is_esc[VEC];
+                            bool any = false;
+#pragma unroll
+                            for (int v = 0; v < VEC; ++v) { is_esc[v] = on && d[v] <= kLut16Escape; any = any || is_esc[v]; }
+                            if (wave_ballot(any)) {                    // wavefront-uniform
+#pragma unroll
+                                for (int v = 0; v < VEC; ++v) {
+                                    if (is_esc[v]) {
+                                        if (d[v] == kLut16Escape) d[v] = from_container(s_a + off + (uint32_t)v);
+                                        else d[v] = esc[(uint32_t)(kLut16Escape - 1 - d[v]) & (kFuEscEntries - 1u)];
+                                    }
+                                }
+                            }
+                        }
+                        if (ESC == 2) {
                             const bool on = sbase[s] != kNoElem && (MODE == 2 || tstep < n_mine);
                             bool is_esc[VEC];
                             uint64_t em[VEC], any_esc = 0ull;
@@ -1226,14 +1262,8 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
 #pragma unroll
                                 for (int v = 0; v < VEC; ++v) {
                                     if (is_esc[v]) {
-                                        if (ESC == 2) {
-                                            const uint32_t key = 2u * (s_a + off + (uint32_t)v);
-                                            uint32_t lo = r_begin, hi = r_end;
-                                            while (lo < hi) { const uint32_t mid = (lo + hi) >> 1; if (rec[2 * (size_t)mid] < key) lo = mid + 1; else hi = mid; }
-                                            d[v] = (lo < r_end && rec[2 * (size_t)lo] == key) ? (int32_t)rec[2 * (size_t)lo + 1] : 0;
-                                        } else {
-                                            d[v] = esc[pos < kFuEscEntries ? pos : kFuEscEntries - 1u];   // beyond: corrupt container only
-                                        }
+                                        if (!esc_in_lds) d[v] = from_container(s_a + off + (uint32_t)v);
+                                        else d[v] = esc[pos < kFuEscEntries ? pos : kFuEscEntries - 1u];   // beyond: corrupt container only
                                         ++pos;
                                     }
                                 }
@@ -1284,7 +1314,7 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
                 }
             };
             if (n_esc == 0u) scan_rows(std::integral_constant<int, 0>{});
-            else if (esc_in_lds) scan_rows(std::integral_constant<int, 1>{});
+            else if (c16) scan_rows(std::integral_constant<int, 1>{});
             else scan_rows(std::integral_constant<int, 2>{});
 
             // ---- verbatim values overwrite what was just stored ----
