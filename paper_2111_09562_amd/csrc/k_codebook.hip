@@ -687,28 +687,39 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
 
     // look-up table on the next kLutBits bits; entries carry the residual, not the symbol
     const uint32_t mx = s_maxlen;
+    // Length of the code a left-aligned bit pattern v starts with, searched in [lo, hi]: the smallest L with
+    // v below the upper bound of the codes of length L (the bounds do not decrease with L, and the longest
+    // length closes the code space); 0 if the code is longer than hi.  A handful of LDS reads.
+    auto code_length = [&](uint64_t v, uint32_t lo, uint32_t hi) -> uint32_t {
+        if (hi > mx) hi = mx;
+        if (lo > hi) return 0u;
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (mid >= mx || v < s_limit[mid]) hi = mid; else lo = mid + 1u;
+        }
+        return (lo >= mx || v < s_limit[lo]) && s_cnt[lo] ? lo : 0u;
+    };
     const int32_t radius = (int32_t)(nbins / 2u);
     const bool compact = nbins <= kLut16MaxBins;
     const bool skip_general = compact && a.compact_only && !(a.general_unless_chunk64 && s_chunk != 64u);
     for (uint32_t e = tid; e < (skip_general ? 0u : kLutSize); e += kBookBlock) {
         const uint64_t v = (uint64_t)e << (64 - kLutBits);
         uint32_t entry = 0;
-        const uint32_t top = mx < (uint32_t)kLutBits ? mx : (uint32_t)kLutBits;
-        for (uint32_t L = 1; L <= top; ++L) {
-            if (s_cnt[L] && (v < s_limit[L] || L == mx)) {
+        {
+            const uint32_t L = code_length(v, 1u, (uint32_t)kLutBits);
+            if (L) {
                 uint64_t off = (v >> (64u - L)) - s_first[L];
                 if (off >= s_cnt[L]) off = s_cnt[L] - 1u;      // only reachable with an invalid stream
                 const uint32_t sym = sorted[s_findex[L] + off];
                 const int32_t d = sym ? (int32_t)sym - radius : -32768;
                 entry = ((uint32_t)d << 8) | L;
-                break;
             }
         }
         if (entry == 0) {
             // no code of at most kLutBits bits starts here: length byte 0, and in the residual field the
             // shortest length a code with this prefix can have (where the decoder's search starts)
-            uint32_t L = (uint32_t)kLutBits + 1u;
-            while (L < mx && v >= s_limit[L]) ++L;
+            uint32_t L = code_length(v, (uint32_t)kLutBits + 1u, mx);
+            if (L == 0u) L = mx;
             entry = L << 8;
         }
         a.t.lut[e] = entry;
@@ -727,15 +738,14 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
             const uint32_t e = tid * kPer + j;
             const uint64_t v = (uint64_t)e << (64 - kLut16Bits);
             uint32_t entry = 0;
-            const uint32_t top = mx < (uint32_t)kLut16Bits ? mx : (uint32_t)kLut16Bits;
-            for (uint32_t L = 1; L <= top; ++L) {
-                if (s_cnt[L] && (v < s_limit[L] || L == mx)) {
+            {
+                const uint32_t L = code_length(v, 1u, (uint32_t)kLut16Bits);
+                if (L) {
                     uint64_t off = (v >> (64u - L)) - s_first[L];
                     if (off >= s_cnt[L]) off = s_cnt[L] - 1u;      // only reachable with an invalid stream
                     const uint32_t sym = sorted[s_findex[L] + off];
                     const int32_t d = sym ? (int32_t)sym - radius : kLut16Escape;
                     entry = (((uint32_t)d & 0xfffu) << 4) | L;
-                    break;
                 }
             }
             ent[j] = entry;
@@ -743,8 +753,8 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
             if (entry == 0) {
                 // the longest code under this prefix is the one its last bit pattern belongs to
                 const uint64_t v_hi = v | ((1ull << (64 - kLut16Bits)) - 1ull);
-                uint32_t L = (uint32_t)kLut16Bits + 1u;
-                while (L < mx && v_hi >= s_limit[L]) ++L;
+                uint32_t L = code_length(v_hi, (uint32_t)kLut16Bits + 1u, mx);
+                if (L == 0u) L = mx;
                 const uint32_t k = L - (uint32_t)kLut16Bits;
                 kbits[j] = k <= 1u ? 1u : (k <= 2u ? 2u : (k <= 4u ? 4u : 6u));
                 need += 1u << kbits[j];
@@ -779,16 +789,13 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
                 const uint32_t first = (pe >> 6) << 1;
                 if (pe != 0u && (pe & 0xfu) == 0u && x >= first && x - first < (1u << kb)) {       // (always, for an entry inside an allocated sub-table)
                     const uint64_t v = ((uint64_t)e << (64 - kLut16Bits)) | ((uint64_t)(x - first) << (64 - kLut16Bits - kb));
-                    const uint32_t top = mx < (uint32_t)kLut16Bits + kb ? mx : (uint32_t)kLut16Bits + kb;
-                    for (uint32_t L = (uint32_t)kLut16Bits + 1u; L <= top; ++L) {
-                        if (s_cnt[L] && (v < s_limit[L] || L == mx)) {
-                            uint64_t off = (v >> (64u - L)) - s_first[L];
-                            if (off >= s_cnt[L]) off = s_cnt[L] - 1u;  // only reachable with an invalid stream
-                            const uint32_t sym = sorted[s_findex[L] + off];
-                            const int32_t d = sym ? (int32_t)sym - radius : kLut16Escape;
-                            entry = (((uint32_t)d & 0xfffu) << 4) | (L - (uint32_t)kLut16Bits);
-                            break;
-                        }
+                    const uint32_t L = code_length(v, (uint32_t)kLut16Bits + 1u, (uint32_t)kLut16Bits + kb);
+                    if (L) {
+                        uint64_t off = (v >> (64u - L)) - s_first[L];
+                        if (off >= s_cnt[L]) off = s_cnt[L] - 1u;  // only reachable with an invalid stream
+                        const uint32_t sym = sorted[s_findex[L] + off];
+                        const int32_t d = sym ? (int32_t)sym - radius : kLut16Escape;
+                        entry = (((uint32_t)d & 0xfffu) << 4) | (L - (uint32_t)kLut16Bits);
                     }
                 }
             }
