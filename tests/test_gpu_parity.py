@@ -367,6 +367,45 @@ def test_which_kernels_decompress(comet, oracle):
     c.close()
 
 
+@pytest.mark.parametrize("shape", [
+    (3, 7, 200, 100),      # planes of five strips, two columns per lane: column sums handed from strip to strip and across wavefronts
+    (2, 5, 333, 97),       # odd width (one column per lane, two 64-lane segments), strips that end inside planes
+    (4, 40, 90, 44),       # 32-lane halves: two runs of rows side by side, plane starts inside a run
+    (6, 300, 40, 12),      # narrow planes: eight runs of rows side by side, several planes per run
+    (2, 2000, 5, 3),       # tiny planes: many planes per run, rows of three lanes
+    (1, 3, 1500, 128),     # the widest plane that goes this way
+    (2, 3, 300, 130),      # just beyond it: a segment per wavefront, sums stay in registers
+    (1, 2, 700, 224),      # four segments of 64 lanes... two columns per lane, planes much larger than a strip
+])
+def test_fused_decompression_strips(comet, oracle, shape):
+    """Decompression in one kernel on shapes whose planes, strips and segments do not line up: planes larger and
+    smaller than a strip, strips that end inside planes, escapes (a small alphabet at a tight bound: their
+    values come from the list in LDS, and beyond its capacity from the container) and verbatim values on
+    both sides of strip boundaries.  Against the oracle, bit for bit; fp32 and bfloat16 outputs."""
+    x = synth.relu_blur(shape, seed=sum(shape), blur=3, shift=-0.2)
+    flat = x.ravel()
+    rng = np.random.default_rng(7)
+    for i in rng.integers(0, flat.size, 40):
+        flat[i] = [np.inf, -np.inf, 3.0e9, -0.0, np.nan][i % 5]
+    ctx = comet.Context(max_elems=x.size, max_nbins=1024)
+    ctx.comet_set_chunk_syms(64)
+    for eb, nbins in [(1e-2, 1024), (2e-3, 16), (1e-3, 64)]:
+        buf = oracle.compress(x, eb, nbins, 64)
+        want = oracle.decompress(buf).ravel()
+        cont = dev(np.concatenate([buf, np.zeros((-buf.size) % 16, np.uint8)]))
+        y = torch.empty(x.size, dtype=torch.float32, device="cuda")
+        ctx.comet_decompress(cont, buf.size, shape, y)
+        ctx.comet_sync()
+        got = y.cpu().numpy()
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), (shape, eb, nbins, int(np.flatnonzero(got.view(np.uint32) != want.view(np.uint32))[0]))
+        if shape[3] <= 512:
+            y16 = torch.empty(x.size, dtype=torch.bfloat16, device="cuda")
+            ctx.comet_decompress_16(cont, buf.size, shape, y16)
+            ctx.comet_sync()
+            assert np.array_equal(y16.view(torch.int16).cpu().numpy().view(np.uint16), oracle.narrow16(want, oracle.BF16)), (shape, eb, nbins)
+    ctx.close()
+
+
 # Plane widths on both sides of every boundary between the lane mappings of the quantise and the
 # scan kernels (one or two columns per lane; several rows per step up to 32 lanes per row; 1, 2, 4, 8
 # segments of 64 lanes), odd and even, with heights that leave a ragged last step and last strip.
