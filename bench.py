@@ -25,11 +25,116 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
-# HBM bytes per mean launch of a kernel, from the rocprofv3 counter runs summarised under profiles/
-# (FETCH_SIZE + WRITE_SIZE, scaled by the same counters on a plain copy of known size); filled in by hand
-# from those summaries, None where no counter run covers the kernel
-TRAFFIC = {"k_quantize_rows": 185594479, "k_encode_count": 61144341, "k_encode_pack": 87444836,
-           "k_decode_chunks": 103274120, "k_scan_store": 201241676}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_resnet50_set_batch64.txt")
+
+
+def traffic_from_profiles():
+    """HBM bytes per mean launch of every kernel, from the rocprofv3 counter summary under profiles/
+    (FETCH_SIZE + WRITE_SIZE, scaled by the same counters on a plain copy of known size): the lines
+    `TRAFFIC <kernel> <bytes>` of that file.  Empty if the file is missing."""
+    out = {}
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                w = line.split()
+                if len(w) == 3 and w[0] == "TRAFFIC":
+                    out[w[1]] = int(w[2])
+    except OSError:
+        pass
+    return out
+
+
+def other_configs(comet, synth, torch, np, chunk_syms, reps=5):
+    """Throughput and ratio of the configurations that are not the headline workload: config 0, the VGG-16-shaped
+    set (config 2), the error-bound sweep (config 3, primary curve) and the two large tensors of config 4, each
+    alone and with one stream compressing while the other decompresses.  One context, one call at a time
+    (median of `reps`), except where config 4 overlaps two."""
+    def med(fn, sync, n=reps):
+        ts = []
+        for _ in range(n):
+            sync()
+            t = time.perf_counter()
+            fn()
+            sync()
+            ts.append(time.perf_counter() - t)
+        return sorted(ts)[len(ts) // 2]
+
+    def cell(ctx, xd, e, cont, out):
+        used = ctx.comet_compress(xd, e["eb"], e["nbins"], cont)
+        ctx.comet_decompress(cont, used, xd.shape, out)
+        ctx.comet_sync()
+        tc = med(lambda: ctx.comet_compress(xd, e["eb"], e["nbins"], cont, sync=False), torch.cuda.synchronize)
+        td = med(lambda: ctx.comet_decompress(cont, used, xd.shape, out), torch.cuda.synchronize)
+        ctx.comet_sync()
+        n = xd.numel()
+        b = used / n
+        return dict(elements=n, container_bytes=used, ratio=round(4 * n / used, 3), compress_GBps=round(4 * n / tc / 1e9, 1), decompress_GBps=round(4 * n / td / 1e9, 1),
+                    roundtrip_GBps=round(4 * n / (tc + td) / 1e9, 1),
+                    compress_frac_hbm_two_pass_floor=round((8 + b) * n / tc / 1e9 / HBM_PEAK_GBS, 4),
+                    decompress_frac_hbm_fused_floor=round((4 + b) * n / td / 1e9 / HBM_PEAK_GBS, 4))
+
+    res = {}
+    # config 0 and config 2: per set, the sums over its tensors
+    for name, entries in (("config0", synth.config0()), ("config2_vgg16_batch32", synth.config2(32))):
+        ctx = comet.Context(max(int(np.prod(e["shape"])) for e in entries), max(e["nbins"] for e in entries))
+        ctx.comet_set_chunk_syms(chunk_syms)
+        cells = []
+        for e in entries:
+            xd = torch.from_numpy(synth.make(e)).cuda()
+            cont = torch.empty(comet.comet_compress_bound(xd.shape, e["nbins"], chunk_syms), dtype=torch.uint8, device="cuda")
+            out = torch.empty_like(xd)
+            cells.append(cell(ctx, xd, e, cont, out))
+            del xd, cont, out
+        ctx.close()
+        n = sum(c["elements"] for c in cells)
+        tc = sum(4 * c["elements"] / c["compress_GBps"] for c in cells)
+        td = sum(4 * c["elements"] / c["decompress_GBps"] for c in cells)
+        used = sum(c["container_bytes"] for c in cells)
+        b = used / n
+        res[name] = dict(eb=entries[0]["eb"], nbins=entries[0]["nbins"], elements=n, ratio=round(4 * n / used, 3),
+                         compress_GBps=round(4 * n / tc, 1), decompress_GBps=round(4 * n / td, 1), roundtrip_GBps=round(4 * n / (tc + td), 1),
+                         compress_frac_hbm_two_pass_floor=round((8 + b) * n / tc / HBM_PEAK_GBS, 4),
+                         decompress_frac_hbm_fused_floor=round((4 + b) * n / td / HBM_PEAK_GBS, 4),
+                         per_layer_ratio=[c["ratio"] for c in cells])
+    # config 3: one tensor, seven error bounds with their alphabets
+    entries = synth.config3(64)
+    xd = torch.from_numpy(synth.make(entries[0])).cuda()
+    ctx = comet.Context(xd.numel(), 65536)
+    ctx.comet_set_chunk_syms(chunk_syms)
+    cont = torch.empty(comet.comet_compress_bound(xd.shape, 65536, chunk_syms), dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(xd)
+    res["config3_eb_sweep"] = [dict(eb=float(f"{e['eb']:.3g}"), nbins=e["nbins"], **{k: v for k, v in cell(ctx, xd, e, cont, out).items() if k not in ("elements", "container_bytes")})
+                               for e in entries]
+    ctx.close()
+    del xd, cont, out
+    # config 4: two large tensors, each alone, then one being compressed while the other is decompressed
+    entries = synth.config4()
+    n = int(np.prod(entries[0]["shape"]))
+    ctxs = [comet.Context(n, entries[0]["nbins"]) for _ in entries]
+    for c in ctxs:
+        c.comet_set_chunk_syms(chunk_syms)
+    sts = [torch.cuda.Stream(), torch.cuda.Stream()]
+    xds, conts, outs, used, alone = [], [], [], [], []
+    for i, e in enumerate(entries):
+        xd = torch.from_numpy(synth.make(e)).cuda()
+        cont = torch.empty(comet.comet_compress_bound(xd.shape, e["nbins"], chunk_syms), dtype=torch.uint8, device="cuda")
+        out = torch.empty_like(xd)
+        alone.append(cell(ctxs[i], xd, e, cont, out))
+        used.append(alone[-1]["container_bytes"])
+        xds.append(xd); conts.append(cont); outs.append(out)
+
+    def both():
+        ctxs[0].comet_compress(xds[0], entries[0]["eb"], entries[0]["nbins"], conts[0], stream=sts[0], sync=False)
+        ctxs[1].comet_decompress(conts[1], used[1], xds[1].shape, outs[1], stream=sts[1])
+    t_both = med(both, torch.cuda.synchronize)
+    for c, st in zip(ctxs, sts):
+        c.comet_sync(st)
+        c.close()
+    t_sum = 4 * n / alone[0]["compress_GBps"] / 1e9 + 4 * n / alone[1]["decompress_GBps"] / 1e9
+    res["config4_two_tensors"] = dict(eb=entries[0]["eb"], nbins=entries[0]["nbins"], alone=alone,
+                                      overlapped=dict(ms=round(t_both * 1e3, 3), GBps_of_input=round(8 * n / t_both / 1e9, 1),
+                                                      one_after_the_other_ms=round(t_sum * 1e3, 3)))
+    return res
 
 
 def main() -> int:
@@ -48,6 +153,7 @@ def main() -> int:
                          "(the paper's future work: hiding the codec behind the layers' compute); adds path.overlap_with_conv")
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer table to stderr")
     ap.add_argument("--no-split", action="store_true", help="skip the compress-only and decompress-only passes")
+    ap.add_argument("--no-configs", action="store_true", help="skip the other configurations (path.configs)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="first run one plain device-to-device copy of the largest layer (a kernel of known traffic "
                          "that hardware-counter runs are scaled by)")
@@ -220,13 +326,30 @@ def main() -> int:
     for c in ctxs:
         c.comet_profile_enable(False)
 
+    # the same step with every call on one stream (what a training loop that compresses a layer while the next
+    # one computes sees: the single-workgroup kernels of a layer are then on the step's critical path)
+    def step_one_stream():
+        for x, e, c in zip(xs, layers, conts):
+            ctxs[0].comet_compress(x, e["eb"], e["nbins"], c, stream=streams[0], sync=False)
+        for i in reversed(range(len(xs))):
+            ctxs[0].comet_decompress(conts[i], conts[i].numel(), xs[i].shape, outs[i], stream=streams[0])
+    step_one_stream()
+    torch.cuda.synchronize()
+    t1s = time.perf_counter()
+    for _ in range(args.steps):
+        step_one_stream()
+    torch.cuda.synchronize()
+    one_stream_s = (time.perf_counter() - t1s) / args.steps
+    ctxs[0].comet_sync(streams[0])
+
     cont_bytes = sum(sizes)
     b = cont_bytes / n_total                       # container bytes per element
     # algorithmic bytes per element of each streaming kernel (what its interface makes it read + write):
     # quantise: fp32 in, u16 code out; encode: codes in (count pass), codes in and container out (pack pass);
     # decode: container in, int16 residual out; scan + store: int16 in, fp32 out
     alg = {"k_quantize_rows": 4.0 + 2.0, "k_encode_count": 2.0, "k_encode_pack": 2.0 + b, "k_decode_chunks": b + 2.0,
-           "k_scan_store": 2.0 + 4.0}
+           "k_scan_store": 2.0 + 4.0, "k_decode_scan": b + 4.0}
+    traffic = traffic_from_profiles()
     dom = max(alg.keys(), key=lambda k: kern[k]["total_ms"])
     launches = kern[dom]["launches"]
     # every launch of a kernel handles one layer; the five layers differ in size, so
@@ -235,7 +358,7 @@ def main() -> int:
     avg_s = kern[dom]["total_ms"] / launches / 1e3
     achieved = alg_bytes_per_launch / avg_s / 1e9
     roofline = dict(bound="hbm", kernel=dom, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=TRAFFIC.get(dom),
+                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=traffic.get(dom),
                     avg_launch_us=round(avg_s * 1e6, 2), launches=launches,
                     alg_bytes_per_elem=round(alg[dom], 4),
                     note="mean over the five layers of the set; durations from HIP events recorded by the library on "
@@ -244,13 +367,17 @@ def main() -> int:
                          "kernel shares the chip, so its duration there measures the mix, not the kernel); traffic = "
                          "HBM bytes per mean launch from rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by a copy of known "
                          "size (profiles/hbm_traffic_resnet50_set_batch64.txt)")
-    # path-level figures: bytes the kernels of a path must move per element (compress: 6 + 4 + b, decompress:
-    # b + 2 + 6) and the smallest any codec could move (4 + b each way)
+    # path-level figures: bytes the kernels of a path move per element (compress: 6 + 4 + b, decompress in one
+    # kernel: b + 4), the floors of the method (two passes to compress: 8 + b; b + 4 to decompress) and the
+    # smallest any codec could move (4 + b each way)
     step_s = dt / args.steps
     path = dict(ratio=round(in_bytes / cont_bytes, 3),
                 per_layer_ratio=[round(4 * x.numel() / s, 3) for x, s in zip(xs, sizes)],
-                roundtrip_frac_hbm_kernel_bytes=round((18.0 + 2 * b) * n_total / step_s / 1e9 / HBM_PEAK_GBS, 4),
+                roundtrip_frac_hbm_kernel_bytes=round((14.0 + 2 * b) * n_total / step_s / 1e9 / HBM_PEAK_GBS, 4),
+                roundtrip_frac_hbm_method_floor=round((12.0 + 2 * b) * n_total / step_s / 1e9 / HBM_PEAK_GBS, 4),
                 roundtrip_frac_hbm_min_bytes=round((8.0 + 2 * b) * n_total / step_s / 1e9 / HBM_PEAK_GBS, 4),
+                one_stream=dict(ms_per_step=round(one_stream_s * 1e3, 4), GBps=round(in_bytes / one_stream_s / 1e9, 1),
+                                note="every call of the step on one stream, nothing overlaps"),
                 kernels={k: dict(launches=v["launches"], avg_us=round(v["avg_us"], 2)) for k, v in kern.items()},
                 # the same roofline arithmetic for every streaming kernel (mean launch, algorithmic bytes / duration)
                 kernel_frac_hbm={k: round(alg[k] * n_total / len(xs) / (kern[k]["total_ms"] / kern[k]["launches"] / 1e3) / 1e9
@@ -262,7 +389,7 @@ def main() -> int:
                     compress_with_codebook_GBps=round(in_bytes / tr / 1e9, 1),
                     bf16_roundtrip_Gelem_per_s=round(n_total / t16 / 1e9, 2), fp32_roundtrip_Gelem_per_s=round(n_total / (dt / args.steps) / 1e9, 2),
                     compress_frac_hbm_kernel_bytes=round((10.0 + b) * n_total / tc / 1e9 / HBM_PEAK_GBS, 4),
-                    decompress_frac_hbm_kernel_bytes=round((8.0 + b) * n_total / td / 1e9 / HBM_PEAK_GBS, 4),
+                    decompress_frac_hbm_kernel_bytes=round((4.0 + b) * n_total / td / 1e9 / HBM_PEAK_GBS, 4),
                     # floors of the method itself: two passes over the data to compress (8 + b bytes per element),
                     # a fused decode + reconstruction to decompress (b + 4), and what a codec with a known code book
                     # could reach (4 + b)
@@ -278,7 +405,7 @@ def main() -> int:
         t_copy = timed(copy_big)
         copy_gbs = 8.0 * xs[big].numel() / t_copy / 1e9
         path.update(copy_ceiling_GBps=round(copy_gbs, 1),
-                    roundtrip_frac_copy_ceiling_kernel_bytes=round((18.0 + 2 * b) * n_total / step_s / 1e9 / copy_gbs, 4),
+                    roundtrip_frac_copy_ceiling_kernel_bytes=round((14.0 + 2 * b) * n_total / step_s / 1e9 / copy_gbs, 4),
                     roundtrip_frac_copy_ceiling_min_bytes=round((8.0 + 2 * b) * n_total / step_s / 1e9 / copy_gbs, 4))
     prop = torch.cuda.get_device_properties(0)
     path["device"] = dict(name=prop.name, compute_units=prop.multi_processor_count, memory_GB=round(prop.total_memory / 2**30, 1),
@@ -286,6 +413,8 @@ def main() -> int:
 
     cpu = None
     if not args.no_cpu_baseline:
+        from concurrent.futures import ThreadPoolExecutor
+
         from oracle import comet_oracle as oracle
         t0 = time.perf_counter()
         bufs = [oracle.compress(x, e["eb"], e["nbins"], args.chunk_syms) for x, e in zip(xs_host, layers)]
@@ -293,10 +422,36 @@ def main() -> int:
         for bf in reversed(bufs):
             oracle.decompress(bf)
         t2 = time.perf_counter()
-        cpu = dict(value=round(in_bytes / (t2 - t0) / 1e9, 4), unit="GB/s", cores=1, kind="oracle",
-                   sample=f"the whole set once ({in_bytes / 1e6:.1f} MB): compress {t1 - t0:.1f} s, decompress {t2 - t1:.1f} s",
-                   compress_GBps=round(in_bytes / (t1 - t0) / 1e9, 4), decompress_GBps=round(in_bytes / (t2 - t1) / 1e9, 4))
         assert [len(bf) for bf in bufs] == sizes, "GPU and oracle container sizes differ"
+        for bf, c in zip(bufs, conts):                 # the containers of the last step, byte for byte
+            assert np.array_equal(c[:len(bf)].cpu().numpy(), bf), "a GPU container differs from the oracle's"
+        # secondary: every host core at once, each on a slice of the batch as a tensor of its own (throughput only:
+        # such containers differ from those of the whole tensors)
+        cores = max(1, min(os.cpu_count() or 1, 16))
+        slices = []
+        for x, e in zip(xs_host, layers):
+            per = max(1, x.shape[0] // cores)
+            slices += [(np.ascontiguousarray(x[i:i + per]), e) for i in range(0, x.shape[0], per)]
+
+        def one(job):
+            xx, e = job
+            oracle.decompress(oracle.compress(xx, e["eb"], e["nbins"], args.chunk_syms))
+        t3 = time.perf_counter()
+        with ThreadPoolExecutor(max_workers=cores) as pool:
+            list(pool.map(one, slices))
+        t4 = time.perf_counter()
+        cpu = dict(value=round(in_bytes / (t2 - t0) / 1e9, 4), unit="GB/s", cores=1, kind="oracle",
+                   sample=f"the whole set once ({in_bytes / 1e6:.1f} MB): compress {t1 - t0:.1f} s, decompress {t2 - t1:.1f} s; "
+                          "its containers equal the GPU's byte for byte",
+                   compress_GBps=round(in_bytes / (t1 - t0) / 1e9, 4), decompress_GBps=round(in_bytes / (t2 - t1) / 1e9, 4),
+                   all_cores=dict(value=round(in_bytes / (t4 - t3) / 1e9, 4), unit="GB/s", cores=cores,
+                                  note="throughput only: the same set cut into batch slices, one oracle round trip per slice, "
+                                       f"{cores} threads; containers differ from those of the whole tensors"))
+
+    if not args.no_configs:
+        del xs, outs, conts
+        torch.cuda.empty_cache()
+        path["configs"] = other_configs(comet, synth, torch, np, args.chunk_syms)
 
     if args.per_layer:
         for e, x, s in zip(layers, xs, sizes):
