@@ -265,6 +265,30 @@ int launch_quantize(comet_ctx *ctx, const void *x, comet_shape s, uint64_t n, fl
     return COMET_OK;
 }
 
+// The code book kernel, behind the sort kernels that an alphabet too large for LDS needs.  b.ctl->n_active
+// must be zero on entry (the call's control block has just been cleared).
+int launch_codebook(comet_ctx *ctx, BookArgs &b, hipStream_t st) {
+    TimedScope ts(ctx, st, COMET_KERNEL_CODEBOOK);
+    // (up to kBookBySymbolMax bins the occurring symbols mostly fit LDS, and the launches would cost more than
+    // the kernel's own sort does when they do not)
+    if (!b.given_len && b.nbins > kBookBySymbolMax) {
+        uint32_t tiles = 1;
+        while (tiles * (uint32_t)kBookBlock < b.nbins) tiles <<= 1;
+        const uint32_t total = tiles * (uint32_t)kBookBlock;          // <= kMaxBins: what the scratch arrays hold
+        uint64_t *src = b.scratch.keys, *dst = b.scratch.iw;
+        hipLaunchKernelGGL(k_book_sort_tiles, dim3(tiles), dim3(kBookBlock), 0, st, b.hist, b.nbins, src, b.ctl);
+        for (uint32_t run = (uint32_t)kBookBlock; run < total; run <<= 1) {
+            hipLaunchKernelGGL(k_book_merge, dim3(total / (uint32_t)kBookMergeBlock), dim3(kBookMergeBlock), 0, st, src, dst, run, b.ctl);
+            uint64_t *t = src; src = dst; dst = t;
+        }
+        b.scratch.keys = src; b.scratch.iw = dst;
+        b.presorted = 1u;
+    }
+    hipLaunchKernelGGL(k_codebook, dim3(1), dim3(kBookBlock), 0, st, b);
+    HIP_TRY(hipGetLastError());
+    return COMET_OK;
+}
+
 int launch_encode(comet_ctx *ctx, const uint16_t *codes, uint64_t n, uint32_t nbins, uint32_t chunk_syms,
                   hipStream_t st, uint32_t *chunk_off, uint8_t *container, uint64_t capacity,
                   uint32_t *payload, uint64_t payload_cap, uint64_t *payload_words_out, uint64_t *desc) {
@@ -523,11 +547,8 @@ int compress_impl(comet_ctx *ctx, const void *dev_in, int in_type, comet_shape s
         BookArgs b{};
         b.hist = hist; b.given_len = dev_len; b.nbins = nbins; b.len_out = out + proto.off_len; b.code_out = nullptr; b.enc = ctx->enc;
         b.scratch = ctx->book; b.ctl = &ctx->state->ctl; b.hdr = reinterpret_cast<Header *>(out); b.proto = proto; b.capacity = capacity;
-        {
-            TimedScope ts(ctx, st, COMET_KERNEL_CODEBOOK);
-            hipLaunchKernelGGL(k_codebook, dim3(1), dim3(kBookBlock), 0, st, b);
-        }
-        HIP_TRY(hipGetLastError());
+        rc = launch_codebook(ctx, b, st);
+        if (rc) return rc;
     }
     rc = launch_encode(ctx, ctx->codes, n, nbins, S, st, reinterpret_cast<uint32_t *>(out + proto.off_chunk), out, capacity,
                        nullptr, 0, nullptr, desc_e);
@@ -1007,8 +1028,8 @@ int comet_stage_codebook(comet_ctx *ctx, const uint32_t *dev_hist, uint32_t nbin
     BookArgs b{};
     b.hist = dev_hist; b.nbins = nbins; b.len_out = dev_len; b.code_out = dev_code; b.enc = ctx->enc;
     b.scratch = ctx->book; b.ctl = &ctx->state->ctl; b.hdr = nullptr; b.capacity = 0;
-    hipLaunchKernelGGL(k_codebook, dim3(1), dim3(kBookBlock), 0, st, b);
-    HIP_TRY(hipGetLastError());
+    const int rc = launch_codebook(ctx, b, st);
+    if (rc) return rc;
     hipLaunchKernelGGL(k_latch, dim3(1), dim3(1), 0, st, ctx->state);
     HIP_TRY(hipGetLastError());
     return COMET_OK;

@@ -80,6 +80,7 @@ struct BookArgs {
     uint64_t *code_out;        // u64[nbins] or null (stage output)
     uint64_t *enc;             // u64[nbins]: (code << 6) | len, 0 for unused symbols
     BookScratch scratch;
+    uint32_t presorted;        // scratch.keys holds the leaves in (frequency, symbol) order (k_book_sort_tiles, k_book_merge) if more than kBookLdsSyms symbols occur
     Control *ctl;
     // container finalisation (null header = stage call)
     Header *hdr;
@@ -87,6 +88,9 @@ struct BookArgs {
     uint64_t capacity;
 };
 __global__ void k_codebook(BookArgs a);
+constexpr int kBookMergeBlock = 256;
+__global__ void k_book_sort_tiles(const uint32_t *hist, uint32_t nbins, uint64_t *keys, Control *ctl);
+__global__ void k_book_merge(const uint64_t *src, uint64_t *dst, uint32_t run, const Control *ctl);
 
 // ---- encode -------------------------------------------------------------------
 constexpr int kEncBlock = 256;             // four wavefronts, each encodes 256 symbols per step cooperatively

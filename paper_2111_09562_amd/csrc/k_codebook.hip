@@ -4,7 +4,12 @@
 //   k_decode_tables  length table -> canonical decode tables; validates a header.
 // One workgroup each: the work is a few thousand symbols at most and sits on the
 // critical path between the two streaming kernels, so it is latency- not
-// bandwidth-bound.  Alphabets up to kBookLdsSyms live entirely in LDS.
+// bandwidth-bound.  Alphabets up to kBookLdsSyms live entirely in LDS.  Larger ones:
+//   k_book_sort_tiles, k_book_merge  the leaves in (frequency, symbol) order, by as many
+//                    workgroups as the alphabet has tiles of 1024 symbols (a merge sort:
+//                    tiles sorted in registers, then runs merged pairwise by ranking);
+//                    k_codebook then merges in global memory while many items wait and
+//                    finishes in LDS.
 //
 // Length rule (must give exactly one answer): leaves ordered by (frequency,
 // symbol); two queues; at every step the two smallest heads are merged, the leaf
@@ -192,11 +197,13 @@ __device__ inline void round_items(const uint64_t *keys, uint64_t *iw, uint32_t 
     }
 }
 
+// Rounds while more than `stop` items wait; the state is handed back.
 template <bool WAVE, typename Sync>
 __device__ inline void huffman_rounds(const uint64_t *keys, uint64_t *iw, uint32_t *leaf_parent, uint32_t *int_parent,
-                                      uint32_t m, uint32_t lane, uint32_t nlanes, Sync sync) {
-    uint32_t li = 0, ii = 0, ni = 0;
-    while ((m - li) + (ni - ii) > 1u) {
+                                      uint32_t m, uint32_t lane, uint32_t nlanes, Sync sync, uint32_t stop,
+                                      uint32_t &li, uint32_t &ii, uint32_t &ni) {
+    li = 0; ii = 0; ni = 0;
+    while ((m - li) + (ni - ii) > stop) {
         uint32_t nl, nn;
         round_control<WAVE>(keys, iw, m, li, ii, ni, &nl, &nn);
         round_items(keys, iw, leaf_parent, int_parent, li, ii, ni, nl, nn, lane, nlanes);
@@ -213,10 +220,11 @@ __device__ inline uint64_t lane_value64(uint64_t v, uint32_t src) { return lane_
 // a prefix of each), and the merged order of the items comes from a short counting loop or from
 // one bitonic merge across the lanes instead of a binary search in LDS per item.  A round with more items is shared by all
 // wavefronts through the general routines (every wavefront works out the round's counts for
-// itself).  state: three words of LDS.
+// itself).  state: three words of LDS.  n_wait: nodes that wait already, iw[0, n_wait) (a
+// construction that was begun elsewhere); iw beyond them must be zero on entry.
 __device__ inline void huffman_rounds_lds(const uint64_t *keys, uint64_t *iw, uint32_t *leaf_parent, uint32_t *int_parent,
-                                          uint32_t m, uint32_t tid, uint32_t nthreads, uint32_t *state) {
-    uint32_t li = 0, ii = 0, ni = 0;
+                                          uint32_t m, uint32_t tid, uint32_t nthreads, uint32_t *state, uint32_t n_wait = 0) {
+    uint32_t li = 0, ii = 0, ni = n_wait;
     const uint32_t lane = tid & (uint32_t)(kWave - 1);
     const uint64_t inf = ~0ull;
     while (true) {
@@ -314,9 +322,11 @@ __device__ inline void huffman_rounds_lds(const uint64_t *keys, uint64_t *iw, ui
 // Everything between the histogram and the tables, on storage that is either LDS
 // (LDS == true: the pointers are the workgroup's own __shared__ arrays, so the
 // compiler emits ds_* instructions) or global scratch for large alphabets.
+// l_keys .. l_ip: the workgroup's LDS arrays of kBookLdsSyms entries (the same pointers as keys .. int_parent when LDS).
 template <bool LDS>
 __device__ inline void codebook_body(const BookArgs &a, uint32_t m, uint64_t *keys, uint64_t *iw, uint32_t *leaf_parent,
-                                     uint32_t *int_parent, uint64_t *s_x, uint32_t *s_part, uint32_t *s_cnt,
+                                     uint32_t *int_parent, uint64_t *l_keys, uint64_t *l_iw, uint32_t *l_lp, uint32_t *l_ip,
+                                     uint64_t *s_x, uint32_t *s_part, uint32_t *s_cnt,
                                      uint64_t *s_first, uint32_t *s_findex, uint32_t *s_maxlen, uint32_t *s_wc) {
     const uint32_t tid = threadIdx.x;
     const uint32_t nbins = a.nbins;
@@ -324,7 +334,16 @@ __device__ inline void codebook_body(const BookArgs &a, uint32_t m, uint64_t *ke
     // (code book reuse: the given length takes the place of the frequency, so the keys are already
     // those of step 5 and steps 2-4 are skipped)
     const bool given = a.given_len != nullptr;
-    {
+    // presorted: the sort kernels have left the leaves in order in keys[0, m) (large alphabets built from a histogram)
+    const bool presorted = !LDS && !given && a.presorted != 0u;
+    if (presorted) {
+        for (uint32_t s = tid; s < nbins; s += kBookBlock)
+            if (a.hist[s] == 0u) {
+                a.len_out[s] = 0;
+                a.enc[s] = 0;
+                if (a.code_out) a.code_out[s] = 0;
+            }
+    } else {
         uint32_t done = 0;
         for (uint32_t base = 0; base < nbins; base += kBookBlock) {
             const uint32_t s = base + tid;
@@ -341,19 +360,21 @@ __device__ inline void codebook_body(const BookArgs &a, uint32_t m, uint64_t *ke
         }
     }
     const uint32_t m2 = next_pow2(m > 1 ? m : 2);
-    for (uint32_t i = m + tid; i < m2; i += kBookBlock) keys[i] = ~0ull;
+    if (!presorted) for (uint32_t i = m + tid; i < m2; i += kBookBlock) keys[i] = ~0ull;
     for (uint32_t i = tid; i < m; i += kBookBlock) iw[i] = 0;
     __syncthreads();
 
     const bool reg_sort = LDS && m2 <= (uint32_t)kBookBlock;
     // Canonical order without a second sort: the lengths are scattered into a by-symbol table (in the
     // sort's exchange buffer, free after step 2) and the symbols are then visited in increasing order.
-    const bool by_symbol = LDS && nbins <= (uint32_t)kBookBySymbolMax;
-    uint8_t *s_depth = reinterpret_cast<uint8_t *>(s_x);
+    // The by-symbol table of an alphabet built in global memory is the length table itself (a sort of
+    // that many keys by one workgroup would cost more than visiting every symbol).
+    const bool by_symbol = !LDS || nbins <= (uint32_t)kBookBySymbolMax;
+    uint8_t *s_depth = LDS ? reinterpret_cast<uint8_t *>(s_x) : a.len_out;
     if (given) {
         // lengths per symbol are known: count them; a length the container cannot hold spoils the count
         // of length 64, which the completeness test below then rejects
-        if (by_symbol) {
+        if (by_symbol && LDS) {
             for (uint32_t i = tid; i < nbins; i += kBookBlock) s_depth[i] = 0;
             __syncthreads();
         }
@@ -371,7 +392,7 @@ __device__ inline void codebook_body(const BookArgs &a, uint32_t m, uint64_t *ke
         key = bitonic_sort_regs(key, s_x, m2);
         if (tid < m2) keys[tid] = key;
         __syncthreads();
-    } else {
+    } else if (!presorted) {
         bitonic_sort(keys, m2);
     }
 
@@ -380,12 +401,28 @@ __device__ inline void codebook_body(const BookArgs &a, uint32_t m, uint64_t *ke
         if (LDS) {
             huffman_rounds_lds(keys, iw, leaf_parent, int_parent, m, tid, (uint32_t)kBookBlock, s_part);
         } else {
-            huffman_rounds<false>(keys, iw, leaf_parent, int_parent, m, tid, (uint32_t)kBookBlock, [] { __syncthreads(); });
+            // The first rounds merge thousands of light leaves each: in global memory, by everybody.  Most
+            // rounds come later, with few items each: once the L leaves and N nodes that wait make at most
+            // kBookLdsSyms / 2 items, they move to LDS (L + 2N - 1 nodes at the end, which fit), the rounds
+            // are finished there, and the parents go back with the offset of the first node moved.
+            uint32_t li, ii, ni;
+            huffman_rounds<false>(keys, iw, leaf_parent, int_parent, m, tid, (uint32_t)kBookBlock, [] { __syncthreads(); },
+                                  kBookLdsSyms / 2u, li, ii, ni);
+            const uint32_t L = m - li, N = ni - ii;
+            if (L + N > 1u) {
+                for (uint32_t j = tid; j < L; j += kBookBlock) l_keys[j] = keys[li + j];
+                for (uint32_t k = tid; k < kBookLdsSyms; k += kBookBlock) l_iw[k] = k < N ? iw[ii + k] : 0ull;
+                __syncthreads();
+                huffman_rounds_lds(l_keys, l_iw, l_lp, l_ip, L, tid, (uint32_t)kBookBlock, s_part, N);
+                __syncthreads();
+                for (uint32_t j = tid; j < L; j += kBookBlock) leaf_parent[li + j] = ii + l_lp[j];
+                for (uint32_t k = tid; k + 1u < L + 2u * N - 1u; k += kBookBlock) int_parent[ii + k] = ii + l_ip[k];   // (the last node is the root)
+            }
         }
     }
     __syncthreads();
 
-    if (by_symbol) {
+    if (by_symbol && LDS) {
         for (uint32_t i = tid; i < nbins; i += kBookBlock) s_depth[i] = 0;
         __syncthreads();
     }
@@ -477,6 +514,40 @@ __device__ inline void codebook_body(const BookArgs &a, uint32_t m, uint64_t *ke
     }
 }
 
+// ---------------------------------------------------------------------------
+// Leaves of a large alphabet in (frequency, symbol) order.  One key per symbol: (frequency, symbol), or
+// a key above all of those for a symbol that does not occur (each its own, so that no two keys are
+// equal).  k_book_sort_tiles: one tile of kBookBlock symbols per workgroup, sorted in registers; the
+// grid's tiles are a power of two and cover the alphabet.  It also counts the symbols that occur.
+// k_book_merge: runs of `run` keys merged pairwise; a key's place is its rank in its own run plus the
+// number of smaller keys in the other one (binary search); one key per thread.  Alphabets whose
+// occurring symbols fit LDS are built there from the histogram: the merges then have nothing to do.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBookBlock) void k_book_sort_tiles(const uint32_t *hist, uint32_t nbins, uint64_t *keys, Control *ctl) {
+    __shared__ uint64_t s_x[kBookBlock];
+    const uint32_t s = blockIdx.x * (uint32_t)kBookBlock + threadIdx.x;
+    const uint32_t f = s < nbins ? hist[s] : 0u;
+    const uint32_t cnt = (uint32_t)__syncthreads_count(f != 0u);
+    if (threadIdx.x == 0 && cnt) atomicAdd(&ctl->n_active, cnt);
+    uint64_t key = f ? (((uint64_t)f << 16) | s) : ((1ull << 63) | s);
+    key = bitonic_sort_regs(key, s_x, (uint32_t)kBookBlock);
+    keys[s] = key;
+}
+
+__global__ __launch_bounds__(kBookMergeBlock) void k_book_merge(const uint64_t *src, uint64_t *dst, uint32_t run, const Control *ctl) {
+    if (ctl->n_active <= kBookLdsSyms) return;
+    const uint32_t i = blockIdx.x * (uint32_t)kBookMergeBlock + threadIdx.x;
+    const uint64_t key = src[i];
+    const uint32_t r = i / run, own = i - r * run;           // run: a power of two
+    const uint64_t *other = src + (size_t)(r ^ 1u) * run;
+    uint32_t lo = 0, hi = run;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (other[mid] < key) lo = mid + 1; else hi = mid;
+    }
+    dst[(size_t)(r & ~1u) * run + own + lo] = key;
+}
+
 __global__ __launch_bounds__(kBookBlock) void k_codebook(BookArgs a) {
     // One workgroup on the critical path of its stream, often next to the streaming kernels of
     // other streams: its wavefronts go first whenever they are ready to issue.
@@ -504,10 +575,10 @@ __global__ __launch_bounds__(kBookBlock) void k_codebook(BookArgs a) {
         m += __syncthreads_count((s < nbins) && (a.given_len ? a.given_len[s] != 0 : a.hist[s] != 0u));
     }
     if (m <= kBookLdsSyms)
-        codebook_body<true>(a, m, s_keys, s_iw, s_lp, s_ip, s_x, s_part, s_cnt, s_first, s_findex, &s_maxlen, s_wc);
+        codebook_body<true>(a, m, s_keys, s_iw, s_lp, s_ip, s_keys, s_iw, s_lp, s_ip, s_x, s_part, s_cnt, s_first, s_findex, &s_maxlen, s_wc);
     else
-        codebook_body<false>(a, m, a.scratch.keys, a.scratch.iw, a.scratch.leaf_parent, a.scratch.int_parent, s_x, s_part,
-                             s_cnt, s_first, s_findex, &s_maxlen, s_wc);
+        codebook_body<false>(a, m, a.scratch.keys, a.scratch.iw, a.scratch.leaf_parent, a.scratch.int_parent, s_keys, s_iw, s_lp, s_ip,
+                             s_x, s_part, s_cnt, s_first, s_findex, &s_maxlen, s_wc);
 
     // ---- 7. container layout ----
     if (tid == 0) {

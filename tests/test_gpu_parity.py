@@ -158,6 +158,38 @@ def test_stage_codebook_sweep(comet, ctx, oracle):
         assert np.array_equal(codes.cpu().numpy().view(np.uint64), want_code), (nb, m, kind)
 
 
+def test_stage_codebook_large_alphabets(comet, ctx, oracle):
+    """Alphabets with more occurring symbols than fit LDS: the leaves are sorted by the tile and merge kernels
+    (alphabet sizes that are and are not a whole number of tiles, or a power of two of them), the first merge
+    rounds run in global memory and the rest in LDS, the canonical order is counted by symbol."""
+    rng = np.random.default_rng(77)
+    cases = []
+    for nb, m in ((2050, 2049), (3000, 2900), (4096, 4096), (5002, 2500), (8192, 2100), (16384, 9000), (40000, 33000),
+                  (65536, 2049), (65536, 26000), (65536, 65536), (65534, 65534)):
+        for kind in ("tail", "flat", "expo", "ones"):
+            h = np.zeros(nb, np.uint64)
+            act = rng.choice(nb, m, replace=False)
+            if kind == "tail":                 # what a fine error bound gives: a heavy centre, thousands of symbols seen a few times
+                w = np.floor(5e7 * np.exp(-np.abs(act - nb / 2.0) / (nb / 40.0))) + rng.integers(1, 4, m)
+            elif kind == "flat":
+                w = rng.integers(1, 3, m)
+            elif kind == "expo":
+                w = np.floor(np.exp(rng.uniform(0, 21, m))) + 1
+            else:
+                w = np.ones(m)
+            h[act] = w
+            cases.append((nb, m, kind, h.astype(np.uint32)))
+    for nb, m, kind, h in cases:
+        want_len = oracle.code_lengths(h)
+        want_code = oracle.canonical_codes(want_len)
+        lens = torch.empty(nb, dtype=torch.uint8, device="cuda")
+        codes = torch.empty(nb, dtype=torch.int64, device="cuda")
+        ctx.comet_stage_codebook(dev(h.view(np.int32)), nb, lens, codes)
+        ctx.comet_sync()
+        assert np.array_equal(lens.cpu().numpy(), want_len), (nb, m, kind)
+        assert np.array_equal(codes.cpu().numpy().view(np.uint64), want_code), (nb, m, kind)
+
+
 def _deep_histogram(levels, nbins):
     """Counts whose Huffman tree is a chain `levels` deep at its far end: Fibonacci numbers as long as they
     fit 32 bits, then groups of equal counts that add up to the next Fibonacci number (a group merges into
@@ -561,6 +593,17 @@ def test_compress_with_codebook_stale_table(comet, ctx, oracle, w, eb, nbins, ch
     x_new.ravel()[11] = -900.0                                    # residuals far outside the alphabet: escapes
     x_old.ravel()[5] = 1000.0                                     # ... and in the older tensor, so that its table has a code word for them
     assert _reuse_case(comet, ctx, oracle, x_old, x_new, eb, nbins, chunk) is not None
+
+
+def test_compress_with_codebook_more_lengths_than_fit_lds(comet, ctx, oracle):
+    """A given table with more than 2048 code words (its canonical codes are then counted by symbol in global memory)."""
+    x_old = synth.relu_blur((4, 8, 56, 56), seed=93, blur=3, shift=0.0)
+    x_new = synth.relu_blur((4, 8, 56, 56), seed=94, blur=3, shift=0.0)
+    x_old.ravel()[5] = 1000.0
+    x_new.ravel()[11] = -900.0
+    a, used = gpu_compress(ctx, comet, x_old, 1e-4, 8192, 64)
+    assert int(np.count_nonzero(a[comet.HEADER_BYTES: comet.HEADER_BYTES + 8192].cpu().numpy())) > 2048
+    assert _reuse_case(comet, ctx, oracle, x_old, x_new, 1e-4, 8192, 64) is not None
 
 
 def test_compress_with_codebook_own_table_is_compress(comet, ctx, oracle):
