@@ -25,7 +25,8 @@
  *
  * Pins (tests/test_oracle_*.py): two hand-computed pipelines, numpy rint /
  * cumsum / bincount identities, an independent heap Huffman cost, Kraft sums,
- * closed-form code lengths, the error-bound invariant, brute-force tie cases.
+ * closed-form code lengths, the error-bound invariant, brute-force tie cases,
+ * a hand-computed container with an elided chunk.
  * Parity unpinned: anything about real network activations (the paper's
  * Table 1 ratios) -- the datasets are not available.
  *
@@ -92,8 +93,8 @@ void oracle_constants(float eb, float *ebx2, float *r) {
  * Non-representable t gives q = 0; a failing finite element keeps its q so its
  * neighbours still predict from it.
  */
-int oracle_prequant(const float *x, uint64_t n, float eb,
-                    int32_t *q, uint8_t *is_value_outlier, uint64_t *nnz) {
+static int prequant_impl(const float *x, uint64_t n, float eb, int zero_first,
+                         int32_t *q, uint8_t *is_value_outlier, uint64_t *nnz) {
     if (!x || !q || !is_value_outlier || !valid_eb(eb)) return ORC_ERR_INVALID;
     float ebx2, r;
     oracle_constants(eb, &ebx2, &r);
@@ -101,6 +102,11 @@ int oracle_prequant(const float *x, uint64_t n, float eb,
     for (uint64_t i = 0; i < n; ++i) {
         float xi = x[i];
         if (xi != 0.0f) ++nz;               /* NaN counts as non-zero */
+        if (zero_first && fabsf(xi) <= eb) { /* the alternative of Sec. 3.4 (see below); NaN fails the comparison */
+            q[i] = 0;
+            is_value_outlier[i] = 0;
+            continue;
+        }
         float t = xi * r;
         if (!(fabsf(t) < 16777216.0f)) {    /* also true for NaN and Inf */
             q[i] = 0;
@@ -115,6 +121,26 @@ int oracle_prequant(const float *x, uint64_t n, float eb,
     }
     if (nnz) *nnz = nz;
     return ORC_OK;
+}
+
+int oracle_prequant(const float *x, uint64_t n, float eb,
+                    int32_t *q, uint8_t *is_value_outlier, uint64_t *nnz) {
+    return prequant_impl(x, n, eb, 0, q, is_value_outlier, nnz);
+}
+
+/*
+ * The alternative zero handling that Sec. 3.4 describes and turns down: every
+ * value within eb of zero is set to zero already in the first quantisation
+ * step, instead of being filtered after reconstruction.  With prequantisation
+ * on the lattice of multiples of 2eb this is the same thing: r is within half
+ * an ulp of 1/(2eb), so eb * r rounds to at most 1/2 (a tie goes to the even
+ * neighbour, 1/2 itself), multiplication is monotonic, and |x * r| <= 1/2
+ * rounds to q = 0, which is within the bound of x.  The switch therefore
+ * changes no quantised value; it exists so that this can be checked.
+ */
+int oracle_prequant_zero_first(const float *x, uint64_t n, float eb,
+                               int32_t *q, uint8_t *is_value_outlier, uint64_t *nnz) {
+    return prequant_impl(x, n, eb, 1, q, is_value_outlier, nnz);
 }
 
 /* ------------------------------------------------------------------------- */
@@ -285,8 +311,17 @@ static void put_bit(uint32_t *words, uint64_t bitpos, uint32_t bit) {
     if (bit) words[bitpos / 32u] |= (1u << (31u - (uint32_t)(bitpos % 32u)));
 }
 
-int oracle_encode(const uint16_t *codes, uint64_t n, uint32_t nbins, uint32_t chunk_syms,
-                  const uint8_t *len, const uint64_t *code,
+/*
+ * zero_chunks (container version 2): a chunk all of whose codes are the centre
+ * code nbins/2 -- residual zero everywhere, which is what a region of zeros
+ * (or of any constant) gives after prediction -- takes no words at all.  The
+ * sparsity of activations behind ReLU (Sec. 4.2, the ratio R) makes such
+ * chunks common.  A chunk with symbols in it otherwise has at least one bit, so a
+ * word count of zero is unambiguous and the chunk table needs no flag.  The
+ * histogram and the code lengths are those of all codes, elided or not.
+ */
+static int encode_impl(const uint16_t *codes, uint64_t n, uint32_t nbins, uint32_t chunk_syms,
+                  const uint8_t *len, const uint64_t *code, int zero_chunks,
                   uint32_t *chunk_off, uint64_t n_chunks_cap,
                   uint32_t *payload, uint64_t payload_cap_words, uint64_t *payload_words) {
     if (!codes || !len || !code || !chunk_off || !payload_words || chunk_syms == 0) return ORC_ERR_INVALID;
@@ -301,11 +336,16 @@ int oracle_encode(const uint16_t *codes, uint64_t n, uint32_t nbins, uint32_t ch
             if (codes[i] >= nbins || len[codes[i]] == 0) return ORC_ERR_INVALID;
             bits += len[codes[i]];
         }
+        if (zero_chunks) {
+            int all_centre = 1;
+            for (uint64_t i = lo; i < hi; ++i) if (codes[i] != nbins / 2u) all_centre = 0;
+            if (all_centre) bits = 0;
+        }
         uint64_t words = (bits + 31u) / 32u;
         if (word > 0xFFFFFFFFull) return ORC_ERR_CAPACITY;
         chunk_off[j] = (uint32_t)word;
         if (word + words > payload_cap_words) return ORC_ERR_CAPACITY;
-        if (payload) {
+        if (payload && words) {
             for (uint64_t k = 0; k < words; ++k) payload[word + k] = 0u;
             uint64_t bp = 0;
             for (uint64_t i = lo; i < hi; ++i) {
@@ -323,6 +363,20 @@ int oracle_encode(const uint16_t *codes, uint64_t n, uint32_t nbins, uint32_t ch
     return ORC_OK;
 }
 
+int oracle_encode(const uint16_t *codes, uint64_t n, uint32_t nbins, uint32_t chunk_syms,
+                  const uint8_t *len, const uint64_t *code,
+                  uint32_t *chunk_off, uint64_t n_chunks_cap,
+                  uint32_t *payload, uint64_t payload_cap_words, uint64_t *payload_words) {
+    return encode_impl(codes, n, nbins, chunk_syms, len, code, 0, chunk_off, n_chunks_cap, payload, payload_cap_words, payload_words);
+}
+
+int oracle_encode_zero_chunks(const uint16_t *codes, uint64_t n, uint32_t nbins, uint32_t chunk_syms,
+                              const uint8_t *len, const uint64_t *code,
+                              uint32_t *chunk_off, uint64_t n_chunks_cap,
+                              uint32_t *payload, uint64_t payload_cap_words, uint64_t *payload_words) {
+    return encode_impl(codes, n, nbins, chunk_syms, len, code, 1, chunk_off, n_chunks_cap, payload, payload_cap_words, payload_words);
+}
+
 /* ------------------------------------------------------------------------- */
 /* Step 7: chunk decode                                                       */
 /* ------------------------------------------------------------------------- */
@@ -331,9 +385,10 @@ int oracle_encode(const uint16_t *codes, uint64_t n, uint32_t nbins, uint32_t ch
  * first code of that length and how many symbols have it; read bits one at a
  * time, extending the candidate code, until it falls inside the range of its
  * length.  Each chunk must consume exactly its words, and its padding bits
- * must be zero.
+ * must be zero.  zero_chunks (container version 2): a chunk without words is
+ * the centre code nbins/2 throughout.
  */
-int oracle_decode(const uint8_t *len, uint32_t nbins,
+static int decode_impl(const uint8_t *len, uint32_t nbins, int zero_chunks,
                   const uint32_t *chunk_off, const uint32_t *payload, uint64_t payload_words,
                   uint64_t n, uint32_t chunk_syms, uint16_t *codes_out) {
     if (!len || !chunk_off || !codes_out || chunk_syms == 0 || nbins == 0 || nbins > 65536u) return ORC_ERR_INVALID;
@@ -374,6 +429,10 @@ int oracle_decode(const uint8_t *len, uint32_t nbins,
         uint64_t w0 = chunk_off[j];
         uint64_t w1 = (j + 1 < n_chunks) ? chunk_off[j + 1] : payload_words;
         if (w0 > w1 || w1 > payload_words) { rc = ORC_ERR_FORMAT; break; }
+        if (zero_chunks && w0 == w1) {
+            for (uint64_t i = lo; i < hi; ++i) codes_out[i] = (uint16_t)(nbins / 2u);
+            continue;
+        }
         uint64_t nbits_avail = (w1 - w0) * 32u;
         uint64_t bp = 0;
         for (uint64_t i = lo; i < hi; ++i) {
@@ -398,6 +457,18 @@ int oracle_decode(const uint8_t *len, uint32_t nbins,
     }
     free(sorted);
     return rc;
+}
+
+int oracle_decode(const uint8_t *len, uint32_t nbins,
+                  const uint32_t *chunk_off, const uint32_t *payload, uint64_t payload_words,
+                  uint64_t n, uint32_t chunk_syms, uint16_t *codes_out) {
+    return decode_impl(len, nbins, 0, chunk_off, payload, payload_words, n, chunk_syms, codes_out);
+}
+
+int oracle_decode_zero_chunks(const uint8_t *len, uint32_t nbins,
+                              const uint32_t *chunk_off, const uint32_t *payload, uint64_t payload_words,
+                              uint64_t n, uint32_t chunk_syms, uint16_t *codes_out) {
+    return decode_impl(len, nbins, 1, chunk_off, payload, payload_words, n, chunk_syms, codes_out);
 }
 
 /* ------------------------------------------------------------------------- */
@@ -543,13 +614,17 @@ static int valid_given_lengths(const uint8_t *len, uint32_t nbins) {
  * usual, so the decoder needs no change and the reconstruction is the one the
  * full pipeline gives.
  */
+#define ORC_ZERO_CHUNKS 1u   /* container version 2: all-centre chunks take no words (see encode_impl) */
+#define ORC_ZERO_FIRST 2u    /* zeros forced in the first quantisation step (see oracle_prequant_zero_first) */
+
 static int compress_impl(const float *x, uint32_t N, uint32_t C, uint32_t H, uint32_t W,
-                         float eb, uint32_t nbins, uint32_t chunk_syms, const uint8_t *given,
+                         float eb, uint32_t nbins, uint32_t chunk_syms, const uint8_t *given, uint32_t flags,
                          uint8_t *out, uint64_t capacity, uint64_t *used) {
     uint64_t n;
     if (!x || !out || !used || !valid_eb(eb) || !valid_nbins(nbins) || chunk_syms == 0 ||
         !shape_elems(N, C, H, W, &n)) return ORC_ERR_INVALID;
     if (given && !valid_given_lengths(given, nbins)) return ORC_ERR_INVALID;
+    if (flags & ~(ORC_ZERO_CHUNKS | ORC_ZERO_FIRST)) return ORC_ERR_INVALID;
     float ebx2, r;
     oracle_constants(eb, &ebx2, &r);
     uint64_t n_chunks = (n + chunk_syms - 1u) / chunk_syms;
@@ -564,7 +639,7 @@ static int compress_impl(const float *x, uint32_t N, uint32_t C, uint32_t H, uin
     uint32_t *chunk_off = (uint32_t *)malloc((size_t)n_chunks * 4u);
     if (!q || !delta || !vflag || !codes || !freq || !len || !code || !chunk_off) { rc = ORC_ERR_NOMEM; goto done; }
     uint64_t nnz = 0;
-    if ((rc = oracle_prequant(x, n, eb, q, vflag, &nnz)) != ORC_OK) goto done;
+    if ((rc = prequant_impl(x, n, eb, (flags & ORC_ZERO_FIRST) != 0, q, vflag, &nnz)) != ORC_OK) goto done;
     if ((rc = oracle_predict_code(q, N, C, H, W, nbins, codes, delta)) != ORC_OK) goto done;
     if (given) {
         memcpy(len, given, nbins);
@@ -591,12 +666,12 @@ static int compress_impl(const float *x, uint32_t N, uint32_t C, uint32_t H, uin
     uint64_t payload_cap_words = (capacity - off_payload) / 4u;
     memset(out, 0, (size_t)off_payload);
     uint64_t payload_words = 0;
-    rc = oracle_encode(codes, n, nbins, chunk_syms, len, code, chunk_off, n_chunks,
-                       (uint32_t *)(void *)(out + off_payload), payload_cap_words, &payload_words);
+    rc = encode_impl(codes, n, nbins, chunk_syms, len, code, (flags & ORC_ZERO_CHUNKS) != 0, chunk_off, n_chunks,
+                     (uint32_t *)(void *)(out + off_payload), payload_cap_words, &payload_words);
     if (rc != ORC_OK) goto done;
     uint64_t total = off_payload + 4u * payload_words;
 
-    put32(out + 0, ORC_MAGIC); put32(out + 4, 1u); put32(out + 8, 0u);
+    put32(out + 0, ORC_MAGIC); put32(out + 4, (flags & ORC_ZERO_CHUNKS) ? 2u : 1u); put32(out + 8, 0u);
     put32(out + 12, N); put32(out + 16, C); put32(out + 20, H); put32(out + 24, W);
     put32(out + 28, nbins); put32(out + 32, chunk_syms); put32(out + 36, (uint32_t)n_chunks);
     put32(out + 40, f2u(eb)); put32(out + 44, f2u(ebx2)); put32(out + 48, f2u(r));
@@ -622,7 +697,14 @@ done:
 int oracle_compress(const float *x, uint32_t N, uint32_t C, uint32_t H, uint32_t W,
                     float eb, uint32_t nbins, uint32_t chunk_syms,
                     uint8_t *out, uint64_t capacity, uint64_t *used) {
-    return compress_impl(x, N, C, H, W, eb, nbins, chunk_syms, NULL, out, capacity, used);
+    return compress_impl(x, N, C, H, W, eb, nbins, chunk_syms, NULL, 0u, out, capacity, used);
+}
+
+/* The zero-handling variants: flags is a sum of ORC_ZERO_CHUNKS (1) and ORC_ZERO_FIRST (2). */
+int oracle_compress_variant(const float *x, uint32_t N, uint32_t C, uint32_t H, uint32_t W,
+                            float eb, uint32_t nbins, uint32_t chunk_syms, uint32_t flags,
+                            uint8_t *out, uint64_t capacity, uint64_t *used) {
+    return compress_impl(x, N, C, H, W, eb, nbins, chunk_syms, NULL, flags, out, capacity, used);
 }
 
 /* Compression with the length table of an earlier compression (see compress_impl). */
@@ -630,14 +712,15 @@ int oracle_compress_with_lengths(const float *x, uint32_t N, uint32_t C, uint32_
                                  float eb, uint32_t nbins, uint32_t chunk_syms, const uint8_t *given_len,
                                  uint8_t *out, uint64_t capacity, uint64_t *used) {
     if (!given_len) return ORC_ERR_INVALID;
-    return compress_impl(x, N, C, H, W, eb, nbins, chunk_syms, given_len, out, capacity, used);
+    return compress_impl(x, N, C, H, W, eb, nbins, chunk_syms, given_len, 0u, out, capacity, used);
 }
 
 int oracle_decompress(const uint8_t *in, uint64_t bytes, float *out, uint64_t out_cap_elems,
                       uint32_t *shape_out /* N,C,H,W or NULL */) {
     if (!in || !out) return ORC_ERR_INVALID;
     if (bytes < ORC_HEADER_BYTES) return ORC_ERR_FORMAT;
-    if (get32(in + 0) != ORC_MAGIC || get32(in + 4) != 1u || get32(in + 8) != 0u) return ORC_ERR_FORMAT;
+    uint32_t version = get32(in + 4);
+    if (get32(in + 0) != ORC_MAGIC || (version != 1u && version != 2u) || get32(in + 8) != 0u) return ORC_ERR_FORMAT;
     uint32_t N = get32(in + 12), C = get32(in + 16), H = get32(in + 20), W = get32(in + 24);
     uint32_t nbins = get32(in + 28), chunk_syms = get32(in + 32), n_chunks = get32(in + 36);
     float eb = u2f(get32(in + 40));
@@ -664,7 +747,7 @@ int oracle_decompress(const uint8_t *in, uint64_t bytes, float *out, uint64_t ou
     for (uint64_t j = 0; j < n_chunks; ++j) chunk_off[j] = get32(in + off_chunk + 4u * j);
     for (uint64_t k = 0; k < 2ull * n_rec; ++k) rec[k] = get32(in + off_outlier + 4u * k);
     for (uint64_t k = 0; k < payload_words; ++k) payload[k] = get32(in + off_payload + 4u * k);
-    rc = oracle_decode(in + off_len, nbins, chunk_off, payload, payload_words, n, chunk_syms, codes);
+    rc = decode_impl(in + off_len, nbins, version == 2u, chunk_off, payload, payload_words, n, chunk_syms, codes);
     if (rc != ORC_OK) goto done;
     rc = oracle_reconstruct(codes, rec, n_rec, N, C, H, W, nbins, eb, out);
     if (rc == ORC_OK && shape_out) { shape_out[0] = N; shape_out[1] = C; shape_out[2] = H; shape_out[3] = W; }

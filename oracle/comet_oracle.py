@@ -54,6 +54,10 @@ def lib():
         L.oracle_compress_bound.argtypes = [C.c_uint32] * 6
         L.oracle_compress_bound.restype = C.c_uint64
         L.oracle_compress.argtypes = [f32p] + [C.c_uint32] * 4 + [C.c_float, C.c_uint32, C.c_uint32, u8p, C.c_uint64, u64p]
+        L.oracle_compress_variant.argtypes = [f32p] + [C.c_uint32] * 4 + [C.c_float, C.c_uint32, C.c_uint32, C.c_uint32, u8p, C.c_uint64, u64p]
+        L.oracle_prequant_zero_first.argtypes = [f32p, C.c_uint64, C.c_float, i32p, u8p, u64p]
+        L.oracle_encode_zero_chunks.argtypes = L.oracle_encode.argtypes
+        L.oracle_decode_zero_chunks.argtypes = L.oracle_decode.argtypes
         L.oracle_compress_with_lengths.argtypes = [f32p] + [C.c_uint32] * 4 + [C.c_float, C.c_uint32, C.c_uint32, u8p, u8p, C.c_uint64, u64p]
         L.oracle_decompress.argtypes = [u8p, C.c_uint64, f32p, C.c_uint64, u32p]
         L.oracle_adapt_eb.argtypes = [C.c_double, C.c_double, C.c_double, C.c_uint32, C.c_double, C.c_double, C.c_float, C.c_float, f32p]
@@ -97,12 +101,14 @@ def constants(eb: float):
     return np.float32(e2.value), np.float32(r.value)
 
 
-def prequant(x, eb: float):
+def prequant(x, eb: float, zero_first: bool = False):
+    """zero_first: the alternative of Sec. 3.4 (values within eb of zero are zeroed in this step)."""
     x = _c(x, np.float32).ravel()
     q = np.empty(x.size, np.int32)
     v = np.empty(x.size, np.uint8)
     nnz = C.c_uint64()
-    _chk(lib().oracle_prequant(_p(x, C.c_float), x.size, C.c_float(eb), _p(q, C.c_int32), _p(v, C.c_uint8), C.byref(nnz)), "oracle_prequant")
+    fn = lib().oracle_prequant_zero_first if zero_first else lib().oracle_prequant
+    _chk(fn(_p(x, C.c_float), x.size, C.c_float(eb), _p(q, C.c_int32), _p(v, C.c_uint8), C.byref(nnz)), "oracle_prequant")
     return q, v, int(nnz.value)
 
 
@@ -137,7 +143,8 @@ def canonical_codes(ln):
     return code
 
 
-def encode(codes, nbins: int, chunk_syms: int, ln, code):
+def encode(codes, nbins: int, chunk_syms: int, ln, code, zero_chunks: bool = False):
+    """zero_chunks: chunks that hold the centre code only take no words (container version 2)."""
     codes = _c(codes, np.uint16).ravel()
     ln = _c(ln, np.uint8).ravel()
     code = _c(code, np.uint64).ravel()
@@ -148,19 +155,21 @@ def encode(codes, nbins: int, chunk_syms: int, ln, code):
     cap = total_bits // 32 + n_chunks + 1
     payload = np.zeros(cap, np.uint32)
     words = C.c_uint64()
-    _chk(lib().oracle_encode(_p(codes, C.c_uint16), n, nbins, chunk_syms, _p(ln, C.c_uint8), _p(code, C.c_uint64),
-                             _p(chunk_off, C.c_uint32), n_chunks, _p(payload, C.c_uint32), cap, C.byref(words)), "oracle_encode")
+    fn = lib().oracle_encode_zero_chunks if zero_chunks else lib().oracle_encode
+    _chk(fn(_p(codes, C.c_uint16), n, nbins, chunk_syms, _p(ln, C.c_uint8), _p(code, C.c_uint64),
+            _p(chunk_off, C.c_uint32), n_chunks, _p(payload, C.c_uint32), cap, C.byref(words)), "oracle_encode")
     return chunk_off[:n_chunks].copy(), payload[: int(words.value)].copy()
 
 
-def decode(ln, chunk_off, payload, n: int, chunk_syms: int):
+def decode(ln, chunk_off, payload, n: int, chunk_syms: int, zero_chunks: bool = False):
     ln = _c(ln, np.uint8).ravel()
     chunk_off = _c(chunk_off, np.uint32).ravel()
     payload = _c(payload, np.uint32).ravel()
     out = np.empty(n, np.uint16)
     pl = payload if payload.size else np.zeros(1, np.uint32)
     co = chunk_off if chunk_off.size else np.zeros(1, np.uint32)
-    _chk(lib().oracle_decode(_p(ln, C.c_uint8), ln.size, _p(co, C.c_uint32), _p(pl, C.c_uint32), payload.size, n, chunk_syms, _p(out, C.c_uint16)), "oracle_decode")
+    fn = lib().oracle_decode_zero_chunks if zero_chunks else lib().oracle_decode
+    _chk(fn(_p(ln, C.c_uint8), ln.size, _p(co, C.c_uint32), _p(pl, C.c_uint32), payload.size, n, chunk_syms, _p(out, C.c_uint16)), "oracle_decode")
     return out
 
 
@@ -180,8 +189,12 @@ def compress_bound(shape, nbins: int, chunk_syms: int) -> int:
     return int(lib().oracle_compress_bound(n_, c_, h_, w_, nbins, chunk_syms))
 
 
-def compress(x, eb: float, nbins: int, chunk_syms: int, capacity: int | None = None) -> np.ndarray:
-    """Full pipeline; returns the container as a uint8 array of its exact size."""
+ZERO_CHUNKS = 1      # container version 2: chunks that hold the centre code only take no words
+ZERO_FIRST = 2       # the alternative of Sec. 3.4: values within eb of zero are zeroed in the first quantisation step
+
+
+def compress(x, eb: float, nbins: int, chunk_syms: int, capacity: int | None = None, flags: int = 0) -> np.ndarray:
+    """Full pipeline; returns the container as a uint8 array of its exact size.  flags: ZERO_CHUNKS | ZERO_FIRST."""
     x = _c(x, np.float32)
     assert x.ndim == 4
     n_, c_, h_, w_ = x.shape
@@ -197,7 +210,11 @@ def compress(x, eb: float, nbins: int, chunk_syms: int, capacity: int | None = N
     while True:
         out = np.empty(capacity, np.uint8)
         used = C.c_uint64()
-        rc = lib().oracle_compress(_p(x, C.c_float), n_, c_, h_, w_, C.c_float(eb), nbins, chunk_syms, _p(out, C.c_uint8), capacity, C.byref(used))
+        if flags:
+            rc = lib().oracle_compress_variant(_p(x, C.c_float), n_, c_, h_, w_, C.c_float(eb), nbins, chunk_syms, flags,
+                                               _p(out, C.c_uint8), capacity, C.byref(used))
+        else:
+            rc = lib().oracle_compress(_p(x, C.c_float), n_, c_, h_, w_, C.c_float(eb), nbins, chunk_syms, _p(out, C.c_uint8), capacity, C.byref(used))
         if rc == ERR_CAPACITY and auto and capacity < compress_bound(x.shape, nbins, chunk_syms):
             capacity = compress_bound(x.shape, nbins, chunk_syms)
             continue

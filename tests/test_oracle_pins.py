@@ -518,7 +518,7 @@ def test_capacity_and_format_errors(oracle):
     assert ei.value.code == oracle.ERR_CAPACITY
     assert oracle.compress(x, 1e-2, 1024, 128, capacity=buf.size).size == buf.size
     assert oracle.compress_bound(x.shape, 1024, 128) >= buf.size
-    for off, val in [(0, 0x58), (4, 2), (8, 1), (28, 3), (96, 0)]:
+    for off, val in [(0, 0x58), (4, 3), (8, 1), (28, 3), (96, 0)]:
         bad = buf.copy()
         bad[off] = val
         with pytest.raises(oracle.OracleError):
@@ -602,6 +602,115 @@ def test_reuse_rejects_tables_the_decoder_would_reject(oracle):
     single = np.zeros(64, np.uint8); single[0] = 1                                  # everything escapes
     buf = oracle.compress_with_lengths(x, 1e-2, 64, 64, single)
     assert np.array_equal(oracle.decompress(buf).view(np.uint32), oracle.decompress(oracle.compress(x, 1e-2, 64, 64)).view(np.uint32))
+
+
+# --------------------------------------------------------------------------
+# zero-handling variants (Sec. 3.4: the filter's alternative; Sec. 4.2: sparsity R)
+# --------------------------------------------------------------------------
+
+def test_zero_chunks_hand_case(oracle):
+    """By hand: 2 eb = 1, so q = x; one row, so d = q - q_left.  x = [0 0 0 0 | 0 1 1 0] in chunks of 4:
+    d = [0 0 0 0 | 0 1 0 -1], codes d + 4 = [4 4 4 4 | 4 5 4 3].  Counts 4: 6, 3: 1, 5: 1; the two light
+    leaves merge first, so the lengths are 4: 1, 3: 2, 5: 2 and the canonical codes 4 -> 0, 3 -> 10,
+    5 -> 11.  The first chunk holds the centre code only: no words in version 2, the word 0000... in
+    version 1.  The second reads 0 11 0 10."""
+    x = np.array([0, 0, 0, 0, 0, 1, 1, 0], np.float32).reshape(1, 1, 1, 8)
+    v1 = oracle.parse_container(oracle.compress(x, 0.5, 8, 4))
+    buf = oracle.compress(x, 0.5, 8, 4, flags=oracle.ZERO_CHUNKS)
+    v2 = oracle.parse_container(buf)
+    assert (v1["version"], v2["version"]) == (1, 2)
+    want_len = np.zeros(8, np.uint8); want_len[4], want_len[3], want_len[5] = 1, 2, 2
+    assert list(v1["len"]) == list(want_len) and list(v2["len"]) == list(want_len)
+    assert list(v1["chunk_off"]) == [0, 1] and [int(w) for w in v1["payload"]] == [0, 0b011010 << 26]
+    assert list(v2["chunk_off"]) == [0, 0] and [int(w) for w in v2["payload"]] == [0b011010 << 26]
+    assert v2["total_bytes"] == v1["total_bytes"] - 4 == buf.size
+    assert np.array_equal(oracle.decompress(buf), x)
+    # a last chunk that is short and holds the centre code only
+    x = np.array([0, 1, 1, 0, 0, 0], np.float32).reshape(1, 1, 1, 6)
+    buf = oracle.compress(x, 0.5, 8, 4, flags=oracle.ZERO_CHUNKS)
+    v2 = oracle.parse_container(buf)
+    assert list(v2["chunk_off"]) == [0, 1] and [int(w) for w in v2["payload"]] == [0b011010 << 26]
+    assert np.array_equal(oracle.decompress(buf), x)
+    # nothing but zeros: one code word, no payload at all
+    x = np.zeros((1, 2, 3, 4), np.float32)
+    v2 = oracle.parse_container(oracle.compress(x, 0.5, 8, 4, flags=oracle.ZERO_CHUNKS))
+    assert v2["payload_words"] == 0 and list(v2["chunk_off"]) == [0] * 6 and v2["len"][4] == 1
+    assert np.array_equal(oracle.decompress(oracle.compress(x, 0.5, 8, 4, flags=oracle.ZERO_CHUNKS)), x)
+
+
+@pytest.mark.parametrize("chunk", [64, 128, 256])
+@pytest.mark.parametrize("shift", [-0.2, -1.0])
+def test_zero_chunks_against_version_1(oracle, chunk, shift):
+    """Version 2 is version 1 with the words of the all-centre chunks taken out: same length table, same
+    records, the remaining words in the same order, and the same reconstruction bit for bit."""
+    x = synth.relu_blur((3, 4, 28, 28), seed=5, blur=3, shift=shift)
+    x[1, 2] = 0.0                                                 # a whole plane of zeros
+    x.ravel()[7] = np.inf                                         # a verbatim value inside a run of zeros
+    eb, nbins = 1e-2, 1024
+    a = oracle.parse_container(oracle.compress(x, eb, nbins, chunk))
+    buf = oracle.compress(x, eb, nbins, chunk, flags=oracle.ZERO_CHUNKS)
+    b = oracle.parse_container(buf)
+    q, _, _ = oracle.prequant(x, eb)
+    codes, _ = oracle.predict_code(q, x.shape, nbins)
+    n_chunks = -(-codes.size // chunk)
+    pad = np.full(n_chunks * chunk, nbins // 2, np.uint16); pad[:codes.size] = codes
+    centre_only = (pad.reshape(n_chunks, chunk) == nbins // 2).all(axis=1)
+    assert centre_only.sum() >= 2 and not centre_only.all()
+    assert np.array_equal(a["len"], b["len"]) and np.array_equal(a["records"], b["records"])
+    off_a = np.append(a["chunk_off"], a["payload_words"]).astype(np.int64)
+    words_a = np.diff(off_a)
+    words_b = np.where(centre_only, 0, words_a)
+    assert np.array_equal(b["chunk_off"], np.concatenate([[0], np.cumsum(words_b)[:-1]]))
+    assert b["payload_words"] == words_b.sum()
+    kept = np.concatenate([a["payload"][off_a[j]: off_a[j + 1]] for j in range(n_chunks) if not centre_only[j]])
+    assert np.array_equal(b["payload"], kept)
+    assert np.array_equal(oracle.decompress(buf).view(np.uint32), oracle.decompress(oracle.compress(x, eb, nbins, chunk)).view(np.uint32))
+    # a chunk without words means something in version 2 only
+    bad = buf.copy(); bad[4] = 1
+    with pytest.raises(oracle.OracleError) as ei:
+        oracle.decompress(bad)
+    assert ei.value.code == oracle.ERR_FORMAT
+    # stage level: the decoder gives the codes back
+    ln = np.asarray(b["len"], np.uint8)
+    off, payload = oracle.encode(codes, nbins, chunk, ln, oracle.canonical_codes(ln), zero_chunks=True)
+    assert np.array_equal(off, b["chunk_off"]) and np.array_equal(payload, b["payload"])
+    assert np.array_equal(oracle.decode(ln, off, payload, codes.size, chunk, zero_chunks=True), codes)
+
+
+@pytest.mark.parametrize("eb", [1e-1, 1e-2, 3e-3, 1e-4])
+def test_zero_first_is_the_filter_on_this_lattice(oracle, eb):
+    """Sec. 3.4 turns down zeroing the values within eb of zero in the first quantisation step because it
+    would spoil the prediction of the points that follow.  With prequantisation nothing is predicted from
+    reconstructed values, and a value within eb of zero rounds to the lattice point 0 anyway: on ordinary
+    data the alternative changes neither a quantised value nor a byte of the container."""
+    x = synth.relu_blur((2, 3, 40, 33), seed=9, blur=3, shift=-0.2)
+    x[0, 0, :3, :5] = [[eb * 0.999, -eb * 0.999, eb * 0.5, -eb * 0.25, eb * 1.5]] * 3     # either side of the bound
+    q0, v0, _ = oracle.prequant(x, eb)
+    q1, v1, _ = oracle.prequant(x, eb, zero_first=True)
+    assert np.array_equal(q0, q1) and np.array_equal(v0, v1)
+    a = oracle.compress(x, eb, 1024, 64)
+    b = oracle.compress(x, eb, 1024, 64, flags=oracle.ZERO_FIRST)
+    assert np.array_equal(a, b)
+    xh = oracle.decompress(b)
+    assert np.all(xh[np.abs(x) <= np.float32(eb) * np.float32(0.99)] == 0.0)
+
+
+def test_zero_first_never_differs(oracle):
+    """Why the two are the same thing, not only on ordinary data: r = fl(1 / 2eb) is within half an ulp of
+    the exact reciprocal, so eb * r is within half an ulp of 1/2 and rounds to at most 1/2 (a tie goes to
+    the even neighbour, which is 1/2 itself); multiplication is monotonic, so every |x| <= eb has
+    |x * r| <= 1/2, which rounds to q = 0, and q = 0 is never a value outlier there.  Checked at the bound
+    itself and at its neighbours for bounds across the whole range of exponents."""
+    rng = np.random.default_rng(12)
+    ebs = np.concatenate([rng.uniform(1e-3, 1e-1, 3000), np.exp2(rng.uniform(-99, 99, 3000))]).astype(np.float32)
+    for eb in ebs:
+        below = np.nextafter(eb, np.float32(0))
+        above = np.nextafter(eb, np.float32(np.inf))
+        x = np.array([eb, -eb, below, -below, above, -above, 0.0, -0.0], np.float32)
+        q0, v0, _ = oracle.prequant(x, float(eb))
+        q1, v1, _ = oracle.prequant(x, float(eb), zero_first=True)
+        assert q0[:4].tolist() == [0, 0, 0, 0] and not v0[:4].any()
+        assert np.array_equal(q0, q1) and np.array_equal(v0, v1)
 
 
 def test_expansion_case_fits_bound(oracle):
