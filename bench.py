@@ -96,6 +96,28 @@ def other_configs(comet, synth, torch, np, chunk_syms, reps=5):
                          compress_frac_hbm_two_pass_floor=round((8 + b) * n / tc / HBM_PEAK_GBS, 4),
                          decompress_frac_hbm_fused_floor=round((4 + b) * n / td / HBM_PEAK_GBS, 4),
                          per_layer_ratio=[c["ratio"] for c in cells])
+    # zero chunks (container version 2) on the headline set and on a sparser one (shift -1.0: about 85 % zeros)
+    zc = {}
+    for name, shift in (("resnet50_set_batch64", -0.2), ("resnet50_set_batch64_sparse", -1.0)):
+        entries = [dict(e, shift=shift) for e in synth.config1(64)]
+        ctx = comet.Context(max(int(np.prod(e["shape"])) for e in entries), 1024)
+        ctx.comet_set_chunk_syms(chunk_syms)
+        tot = {}
+        for e in entries:
+            xd = torch.from_numpy(synth.make(e)).cuda()
+            cont = torch.empty(comet.comet_compress_bound(xd.shape, e["nbins"], chunk_syms), dtype=torch.uint8, device="cuda")
+            out = torch.empty_like(xd)
+            for v, on in (("v1", False), ("v2", True)):
+                ctx.comet_set_zero_chunks(on)
+                r = cell(ctx, xd, e, cont, out)
+                t = tot.setdefault(v, dict(bytes=0, n=0, tc=0.0, td=0.0))
+                t["bytes"] += r["container_bytes"]; t["n"] += r["elements"]
+                t["tc"] += 4 * r["elements"] / r["compress_GBps"]; t["td"] += 4 * r["elements"] / r["decompress_GBps"]
+            del xd, cont, out
+        ctx.close()
+        zc[name] = {v: dict(ratio=round(4 * t["n"] / t["bytes"], 3), compress_GBps=round(4 * t["n"] / t["tc"], 1),
+                            decompress_GBps=round(4 * t["n"] / t["td"], 1)) for v, t in tot.items()}
+    res["zero_chunks"] = zc
     # config 3: one tensor, seven error bounds with their alphabets
     entries = synth.config3(64)
     xd = torch.from_numpy(synth.make(entries[0])).cuda()

@@ -70,6 +70,16 @@ void comet_destroy(comet_ctx *ctx);
  * 128 or 256.  Stored in the container; the decompressor reads it there. */
 int comet_set_chunk_syms(comet_ctx *ctx, uint32_t chunk_syms);
 
+/* Zero-chunk containers for subsequent comet_compress calls (off by default).
+ * Activations behind ReLU are sparse (the ratio R of Sec. 4.2): a run of zeros,
+ * like any constant run, leaves residual 0 after prediction, i.e. the centre
+ * code nbins/2.  With enable != 0 a chunk that holds nothing but that code
+ * takes no payload words at all (its entry in the chunk table equals the next
+ * one; a chunk with symbols otherwise has at least one bit), and the container
+ * says version 2 in its header; everything else, code book included, is as in
+ * version 1.  The decompressor reads the version and takes either. */
+int comet_set_zero_chunks(comet_ctx *ctx, int enable);
+
 /* Worst-case container size in bytes for a shape (every element an outlier and
  * stored verbatim); 0 if the arguments are invalid.  Realistic activations need
  * a small fraction of it; callers that pass less rely on COMET_ERR_CAPACITY,

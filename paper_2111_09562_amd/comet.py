@@ -18,7 +18,7 @@ HEADER_BYTES = 128
 DEFAULT_CHUNK_SYMS = 64
 
 EXPORTS = (
-    "comet_create", "comet_destroy", "comet_set_chunk_syms", "comet_compress_bound", "comet_compress", "comet_compress_with_codebook",
+    "comet_create", "comet_destroy", "comet_set_chunk_syms", "comet_set_zero_chunks", "comet_compress_bound", "comet_compress", "comet_compress_with_codebook",
     "comet_decompress", "comet_decompress_static", "comet_compress_16", "comet_decompress_16", "comet_sync", "comet_peek", "comet_adapt_defaults", "comet_adapt_eb", "comet_abs_mean",
     "comet_controller_init", "comet_controller_tick", "comet_controller_update",
     "comet_stage_quantize", "comet_stage_codebook", "comet_stage_encode", "comet_stage_decode",
@@ -69,6 +69,7 @@ def lib():
         L.comet_destroy.argtypes = [vp]
         L.comet_destroy.restype = None
         L.comet_set_chunk_syms.argtypes = [vp, C.c_uint32]
+        L.comet_set_zero_chunks.argtypes = [vp, C.c_int]
         L.comet_compress_bound.argtypes = [Shape, C.c_uint32, C.c_uint32]
         L.comet_compress_bound.restype = u64
         L.comet_compress.argtypes = [vp, vp, Shape, C.c_float, C.c_uint32, vp, vp, u64, C.POINTER(u64)]
@@ -223,6 +224,10 @@ class Context:
             self.close()
         except Exception:
             pass
+
+    def comet_set_zero_chunks(self, enable: bool) -> None:
+        """Containers of version 2: chunks that hold the centre code only take no payload words."""
+        _chk(lib().comet_set_zero_chunks(self._h, 1 if enable else 0), "comet_set_zero_chunks")
 
     def comet_set_chunk_syms(self, chunk_syms: int) -> None:
         _chk(lib().comet_set_chunk_syms(self._h, chunk_syms), "comet_set_chunk_syms")

@@ -65,6 +65,7 @@ struct comet_ctx {
     uint64_t max_elems = 0;
     uint32_t max_nbins = 0;
     uint32_t chunk_syms = COMET_DEFAULT_CHUNK_SYMS;
+    uint32_t zero_chunks = 0;                       // containers of version 2: chunks of nothing but centre codes take no words
     // device memory
     DevState *state = nullptr;       // latched + Control, then histogram + descriptors (zero region)
     uint8_t *zero_region = nullptr;  // == (uint8_t*)&state->ctl
@@ -294,6 +295,7 @@ int launch_encode(comet_ctx *ctx, const uint16_t *codes, uint64_t n, uint32_t nb
                   uint32_t *payload, uint64_t payload_cap, uint64_t *payload_words_out, uint64_t *desc) {
     EncodeArgs a{};
     a.codes = codes; a.n = n; a.chunk_syms = chunk_syms;
+    a.zero_pair = ctx->zero_chunks ? ((nbins / 2u) << 16) | (nbins / 2u) : 0u;
     a.n_chunks = (uint32_t)((n + chunk_syms - 1) / chunk_syms);
     a.enc = ctx->enc; a.nbins = nbins;
     a.tbl_n = nbins < kEncTableMax ? nbins : kEncTableMax;
@@ -460,6 +462,12 @@ void comet_destroy(comet_ctx *c) {
     delete c;
 }
 
+int comet_set_zero_chunks(comet_ctx *ctx, int enable) {
+    if (!ctx) return COMET_ERR_INVALID;
+    ctx->zero_chunks = enable ? 1u : 0u;
+    return COMET_OK;
+}
+
 int comet_set_chunk_syms(comet_ctx *ctx, uint32_t chunk_syms) {
     if (!ctx || !valid_chunk(chunk_syms)) return COMET_ERR_INVALID;
     ctx->chunk_syms = chunk_syms;
@@ -517,7 +525,7 @@ int compress_impl(comet_ctx *ctx, const void *dev_in, int in_type, comet_shape s
     const uint64_t tiles_e = e_grid;
 
     Header proto{};
-    proto.magic = kMagic; proto.version = 1; proto.N = s.n; proto.C = s.c; proto.H = s.h; proto.W = s.w;
+    proto.magic = kMagic; proto.version = ctx->zero_chunks ? 2u : 1u; proto.N = s.n; proto.C = s.c; proto.H = s.h; proto.W = s.w;
     proto.nbins = nbins; proto.chunk_syms = S; proto.n_chunks = (uint32_t)n_chunks;
     const float ebx2 = 2.0f * eb;
     const float r = (float)(1.0 / (double)ebx2);
@@ -914,7 +922,7 @@ int comet_peek(comet_ctx *ctx, const void *dev_in, uint64_t bytes, void *stream,
     const Header &h = *ctx->host_hdr;
     comet_shape s{h.N, h.C, h.H, h.W};
     uint64_t n;
-    if (h.magic != kMagic || h.version != 1 || h.status != 0 || !shape_elems(s, &n) || !valid_nbins(h.nbins) ||
+    if (h.magic != kMagic || (h.version != 1 && h.version != 2) || h.status != 0 || !shape_elems(s, &n) || !valid_nbins(h.nbins) ||
         h.chunk_syms == 0 || h.total_bytes > bytes || h.total_bytes != h.off_payload + 4 * h.payload_words) return COMET_ERR_FORMAT;
     info->shape = s; info->nbins = h.nbins; info->chunk_syms = h.chunk_syms; info->n_chunks = h.n_chunks;
     info->n_active = h.n_active; info->max_len = h.max_len; info->n_outlier_records = h.n_rec; info->n_value_records = h.n_vrec;
@@ -1069,6 +1077,7 @@ int comet_stage_decode(comet_ctx *ctx, const uint8_t *dev_len, uint32_t nbins, c
     ReconArgs a{};
     a.chunk_off = dev_chunk_off; a.payload = dev_payload; a.payload_words = payload_words; a.chunk_syms = chunk_syms;
     a.n_chunks = (uint32_t)((n + chunk_syms - 1) / chunk_syms); a.t = ctx->tables; a.n = n; a.codes_out = dev_codes_out; a.ctl = &ctx->state->ctl;
+    a.zero_chunks = ctx->zero_chunks;
     uint32_t grid = (a.n_chunks + kDecBlock - 1) / kDecBlock;
     const uint32_t cap = (uint32_t)ctx->num_cu * 32u;
     if (grid > cap) grid = cap;

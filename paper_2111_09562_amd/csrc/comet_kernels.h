@@ -115,6 +115,7 @@ struct EncodeArgs {
     uint64_t *desc;            // words of every segment (written by the count kernel, read by the pack kernel)
     Control *ctl;
     uint32_t *latched;         // product path: the context's persistent status word (the pack kernel seals the header); else null
+    uint32_t zero_pair;        // container version 2: (centre << 16) | centre, a chunk of nothing but centre codes takes no words; else 0
 };
 constexpr uint32_t kEncUnroll = 4;         // steps of 256 symbols a wavefront handles per iteration
 constexpr uint32_t kEncStepWordsMax = 468; // 256 code words of up to 58 bits, in 32-bit words, plus slack
@@ -199,6 +200,7 @@ struct ReconArgs {
     float *out;
     uint32_t skip_chunk64;         // 1: do nothing for a container with chunks of 64 symbols (k_decode_scan has handled it)
     uint16_t *codes_out;           // stage decode: write codes instead of reconstructing
+    uint32_t zero_chunks;          // stage decode: a chunk without words is the centre code throughout (a container says so in its version)
     Control *ctl;
 };
 template <int MODE> __global__ void k_reconstruct(ReconArgs a);   // 0 container, 1 codes from memory

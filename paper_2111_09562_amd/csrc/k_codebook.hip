@@ -644,7 +644,7 @@ __global__ __launch_bounds__(kBookBlock) void k_decode_tables(TablesArgs a) {
             const Header &e = a.expect;
             const uint64_t n = (uint64_t)e.N * e.C * e.H * e.W;
             if (a.bytes < kHeaderBytes) ok = 0;
-            if (h.magic != kMagic || h.version != 1u || h.status != 0u) ok = 0;
+            if (h.magic != kMagic || (h.version != 1u && h.version != 2u) || h.status != 0u) ok = 0;
             if (h.N != e.N || h.C != e.C || h.H != e.H || h.W != e.W) ok = 0;
             if (h.nbins < 4u || h.nbins > 65536u || (h.nbins & 1u)) ok = 0;
             s_nbins = h.nbins;

@@ -306,6 +306,7 @@ __global__ __launch_bounds__(kDsBlock) void k_decode_chunks(DsArgs a) {
     const uint32_t payload_words = (uint32_t)hdr->payload_words;
     const uint32_t S = hdr->chunk_syms;
     const uint32_t n_chunks = hdr->n_chunks;
+    const bool zero_chunks = hdr->version == 2u;
 
     const bool c16 = a.t.meta[4] != 0u;                     // the compact table exists: use it
     {
@@ -377,7 +378,20 @@ __global__ __launch_bounds__(kDsBlock) void k_decode_chunks(DsArgs a) {
         offsets_of(grp + grp_step, off_lane_next, off_end_next);
 
         // ---- decode, one lane per chunk ----
-        if (c < c_hi && n_words) {
+        // (container version 2: a chunk without words is the centre code, residual 0, throughout)
+        bool no_words = false;
+        if (zero_chunks) {
+            const uint32_t next_off = (uint32_t)__shfl_down((int)my_off, 1, kWave);
+            no_words = c < c_hi && ((c + 1u < c_hi) ? next_off : w_end) <= my_off;
+        }
+        if (no_words) {
+            const uint64_t s0 = (uint64_t)c * S;
+            const uint32_t nsym = (a.n - s0 < (uint64_t)S) ? (uint32_t)(a.n - s0) : S;
+            int16_t *dst = a.resid + s0;
+            uint32_t k = 0;
+            for (; k + 8u <= nsym; k += 8u) *reinterpret_cast<uint4 *>(dst + k) = make_uint4(0u, 0u, 0u, 0u);
+            for (; k < nsym; ++k) dst[k] = 0;
+        } else if (c < c_hi && n_words) {
             uint32_t w0 = (my_off < w_begin) ? 0u : my_off - w_begin;
             const uint64_t s0 = (uint64_t)c * S;
             const uint32_t nsym = (a.n - s0 < (uint64_t)S) ? (uint32_t)(a.n - s0) : S;
@@ -720,6 +734,7 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
     const uint32_t payload_words = (uint32_t)hdr->payload_words;
     const uint32_t n_chunks = hdr->n_chunks;
     const uint32_t n_rec = hdr->n_rec;
+    const bool zero_chunks = hdr->version == 2u;
     const float eb = __uint_as_float(hdr->eb_bits);
     const float ebx2 = __uint_as_float(hdr->ebx2_bits);
 
@@ -942,6 +957,14 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
                         const uint32_t *gsrc = payload + w_begin;
                         if (c16) run(std::true_type{}, gsrc); else run(std::false_type{}, gsrc);
                     }
+                }
+                // Container version 2: a chunk without words is residual 0 throughout.  Its lane has read
+                // the words of the chunk behind it (or past the end of the strip's, which is harmless) with
+                // the others; what it decoded is dropped.
+                if (zero_chunks && n_words) {
+                    const uint32_t next_off = (uint32_t)__shfl_down((int)my_off, 1, kWave);
+                    const uint32_t w_last = w_begin + n_words;
+                    if (((c + 1u < c1) ? next_off : w_last) <= my_off) { pa = u32x16_t{}; pb = u32x16_t{}; }
                 }
             }
             wave_lds_fence();

@@ -89,6 +89,27 @@ __device__ inline void fetch_steps(const uint16_t *codes, uint64_t n, uint32_t c
             v[u] = (st0 + u < steps) ? load4(codes, e0 + u * 256u + lane * 4u, n) : make_uint2(0, 0);
     }
 }
+// Container version 2 (sparse activations behind ReLU, COMET Sec. 4.2): which chunks of the step hold
+// nothing but the centre code and therefore take no words; true for the lanes of such a chunk.  left:
+// symbols of the step that exist (256 except at the end of the tensor; positions past the end do not count).
+template <int LPC>
+__device__ inline bool chunk_is_centre_only(uint2 v, uint32_t zero_pair, uint32_t lane, uint32_t left) {
+    bool mine = v.x == zero_pair && v.y == zero_pair;
+    if (left < 256u) {
+        const uint32_t centre = zero_pair & 0xffffu;
+        mine = true;
+#pragma unroll
+        for (uint32_t j = 0; j < 4; ++j) {
+            const uint32_t w = (j < 2) ? v.x : v.y;
+            const uint32_t c = (j & 1) ? (w >> 16) : (w & 0xffffu);
+            mine = mine && (lane * 4u + j >= left || c == centre);
+        }
+    }
+    const uint64_t all = wave_ballot(mine);
+    constexpr uint64_t grp = LPC == 64 ? ~0ull : ((1ull << (LPC & 63)) - 1ull);
+    return ((all >> ((lane / LPC) * LPC)) & grp) == grp;
+}
+
 __device__ inline uint32_t code_of(uint2 v, int j) {
     const uint32_t w = (j < 2) ? v.x : v.y;
     return (j & 1) ? (w >> 16) : (w & 0xffffu);
@@ -137,6 +158,10 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_count(EncodeArgs a) {
                 const uint32_t left = (a.n > e0) ? (uint32_t)(a.n - e0) : 0u;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) bits += (lane * 4u + (uint32_t)j < left) ? tbl.length(code_of(v[u], j)) : 0u;
+            }
+            if (a.zero_pair) {                                               // (uniform)
+                const uint32_t left = (e0 + 256u <= a.n) ? 256u : ((a.n > e0) ? (uint32_t)(a.n - e0) : 0u);
+                if (chunk_is_centre_only<LPC>(v[u], a.zero_pair, lane, left)) bits = 0;
             }
             const uint32_t incl = group_incl_scan<LPC>(bits);
             if ((lane % LPC) == LPC - 1 && c0 + g < c_hi) s_cnt[c0 + g - c_lo] = (incl + 31u) >> 5;
@@ -281,6 +306,8 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_pack(EncodeArgs a) {
                 bits += len[j];
                 acc = (acc << len[j]) | cw[j];
             }
+            // a chunk of nothing but centre codes takes no words: its lanes place a string of no bits
+            if (a.zero_pair && chunk_is_centre_only<LPC>(v[u], a.zero_pair, lane, left)) bits = 0;      // (the test on zero_pair is uniform)
             const uint32_t incl = group_incl_scan<LPC>(bits);
             // words of every chunk of the step, and where each chunk's words start inside the buffer
             uint32_t wbase = 0, total_words = 0;

@@ -121,9 +121,11 @@ __global__ __launch_bounds__(kDecBlock) void k_reconstruct(ReconArgs a) {
     uint32_t S = a.chunk_syms, n_chunks = a.n_chunks;
     int32_t radius = a.radius;
     float eb = a.eb, ebx2 = a.ebx2;
+    bool zero_chunks = false;
     LdsTables t{};
     if (MODE == 0) {
         const Header *h = reinterpret_cast<const Header *>(a.container);
+        zero_chunks = h->version == 2u;
         chunk_off = reinterpret_cast<const uint32_t *>(a.container + h->off_chunk);
         rec = reinterpret_cast<const uint32_t *>(a.container + h->off_outlier);
         payload = reinterpret_cast<const uint32_t *>(a.container + h->off_payload);
@@ -169,19 +171,21 @@ __global__ __launch_bounds__(kDecBlock) void k_reconstruct(ReconArgs a) {
                     uint64_t w1 = (c + 1u < n_chunks) ? chunk_off[c + 1u] : payload_words;
                     if (w1 > payload_words) w1 = payload_words;
                     if (w0 > w1) w0 = w1;
+                    const bool no_words = zero_chunks && w0 == w1;        // container version 2: the centre code throughout
                     BitReader br;
                     br.init(payload + w0, payload + w1);
                     const uint64_t s0 = (uint64_t)c * S;
                     uint32_t nsym = (n - s0 < S) ? (uint32_t)(n - s0) : S;
                     if (s0 + nsym > e1) nsym = (uint32_t)(e1 - s0);       // nothing past the strip is needed
                     uint32_t k = 0;
+                    if (no_words) k = s0 < e0 ? (uint32_t)(e0 - s0) : 0u;
                     for (; s0 + k < e0; ++k) (void)decode_symbol(br, t);  // symbols that belong to the previous strip
                     const uint32_t l0 = (uint32_t)(s0 + k - e0);
                     uint32_t row = fdiv(l0, a.divW);
                     uint32_t col = l0 - row * W;
                     int32_t *dst = tile + row * pitch;
                     for (; k < nsym; ++k) {
-                        const uint32_t sym = decode_symbol(br, t);
+                        const uint32_t sym = no_words ? (uint32_t)radius : decode_symbol(br, t);
                         dst[col] = sym ? (int32_t)sym - radius : 0;
                         if (++col == W) { col = 0; dst += pitch; }
                     }
@@ -308,11 +312,12 @@ __global__ __launch_bounds__(kDecBlock) void k_decode_only(ReconArgs a) {
         uint64_t w1 = (c + 1u < a.n_chunks) ? a.chunk_off[c + 1u] : a.payload_words;
         if (w1 > a.payload_words) w1 = a.payload_words;
         if (w0 > w1) w0 = w1;
+        const bool no_words = a.zero_chunks && w0 == w1;        // container version 2: the centre code throughout
         BitReader br;
         br.init(a.payload + w0, a.payload + w1);
         const uint64_t s0 = c * S;
         const uint32_t nsym = (a.n - s0 < S) ? (uint32_t)(a.n - s0) : S;
-        for (uint32_t k = 0; k < nsym; ++k) a.codes_out[s0 + k] = (uint16_t)decode_symbol(br, t);
+        for (uint32_t k = 0; k < nsym; ++k) a.codes_out[s0 + k] = no_words ? (uint16_t)t.radius : (uint16_t)decode_symbol(br, t);
     }
 }
 

@@ -595,6 +595,108 @@ def test_compress_with_codebook_stale_table(comet, ctx, oracle, w, eb, nbins, ch
     assert _reuse_case(comet, ctx, oracle, x_old, x_new, eb, nbins, chunk) is not None
 
 
+# --------------------------------------------------------------------------
+# zero chunks (container version 2)
+# --------------------------------------------------------------------------
+
+def _sparse_input(shape, seed):
+    """Mostly zeros in blobs, one plane of nothing but zeros, a verbatim value inside a run of zeros, and
+    the end of the tensor zero (a last chunk that is short and holds the centre code only)."""
+    x = synth.relu_blur(shape, seed=seed, blur=3, shift=-1.0)
+    x[0, 0] = 0.0
+    x.ravel()[7] = np.inf
+    x.ravel()[-(min(37, x.size // 2)):] = 0.0
+    return x
+
+
+@pytest.mark.parametrize("shape", [(2, 3, 56, 56), (3, 5, 7, 7), (2, 2, 28, 30), (1, 3, 33, 130), (1, 2, 20, 224), (1, 2, 9, 600),
+                                   (1, 2, 3, 8192), (1, 1, 1, 37)])
+@pytest.mark.parametrize("eb,nbins,chunk", [(1e-2, 1024, 64), (1e-3, 65536, 64), (1e-2, 1024, 128), (2e-2, 64, 256)])
+def test_zero_chunks_container_and_values(comet, ctx, oracle, shape, eb, nbins, chunk):
+    """Every compressor and decompressor kernel with chunks that take no words: chunks of 64 symbols (the
+    one-kernel decompression), of 128 and 256 (decode and scan apart), planes wider than 512 columns (the
+    general kernel); container bytes and values against the oracle's version 2."""
+    x = _sparse_input(shape, seed=500 + shape[3])
+    want = oracle.compress(x, eb, nbins, chunk, flags=oracle.ZERO_CHUNKS)
+    c = oracle.parse_container(want)
+    words = np.diff(np.append(c["chunk_off"], c["payload_words"]).astype(np.int64))
+    assert c["version"] == 2 and ((words == 0).any() or x.size < 1000)
+    ref = oracle.decompress(want).ravel().view(np.uint32)
+    ctx.comet_set_zero_chunks(True)
+    try:
+        out, used = gpu_compress(ctx, comet, x, eb, nbins, chunk)
+    finally:
+        ctx.comet_set_zero_chunks(False)
+    assert used == want.size and np.array_equal(out[:used].cpu().numpy(), want)
+    y = torch.empty(x.size, dtype=torch.float32, device="cuda")
+    ctx.comet_decompress(out, used, x.shape, y)              # (the context is back to version 1: the container says what it is)
+    ctx.comet_sync()
+    assert np.array_equal(y.cpu().numpy().view(np.uint32), ref)
+    if shape[3] <= 512:
+        for okind, tdt in ((oracle.F16, torch.float16), (oracle.BF16, torch.bfloat16)):
+            y16 = torch.empty(x.size, dtype=tdt, device="cuda")
+            ctx.comet_decompress_16(out, used, x.shape, y16)
+            ctx.comet_sync()
+            assert np.array_equal(y16.view(torch.int16).cpu().numpy().view(np.uint16), oracle.decompress_16(want, okind).ravel())
+    ctx.comet_set_chunk_syms(128)
+
+
+def test_zero_chunks_nothing_but_zeros(comet, ctx, oracle):
+    for shape, chunk in (((2, 3, 14, 14), 64), ((1, 2, 40, 100), 128), ((1, 1, 2, 700), 64)):
+        x = np.zeros(shape, np.float32)
+        want = oracle.compress(x, 1e-2, 1024, chunk, flags=oracle.ZERO_CHUNKS)
+        assert oracle.parse_container(want)["payload_words"] == 0
+        ctx.comet_set_zero_chunks(True)
+        try:
+            out, used = gpu_compress(ctx, comet, x, 1e-2, 1024, chunk)
+        finally:
+            ctx.comet_set_zero_chunks(False)
+        assert used == want.size and np.array_equal(out[:used].cpu().numpy(), want)
+        y = torch.full((x.size,), 7.0, dtype=torch.float32, device="cuda")
+        ctx.comet_decompress(out, used, shape, y)
+        ctx.comet_sync()
+        assert np.array_equal(y.cpu().numpy().view(np.uint32), np.zeros(x.size, np.uint32))
+    ctx.comet_set_chunk_syms(128)
+
+
+@pytest.mark.parametrize("chunk", [64, 100, 256])
+def test_zero_chunks_stage_encode_decode(comet, ctx, oracle, chunk):
+    rng = np.random.default_rng(chunk)
+    n, nbins = 20_000, 256
+    codes = np.full(n, nbins // 2, np.uint16)
+    busy = rng.random(n // 50) < 0.4                          # runs of 50 symbols that are not all centre
+    for k in np.flatnonzero(busy):
+        codes[50 * k: 50 * k + 50] = rng.integers(120, 137, 50)
+    hist = oracle.histogram(codes, nbins)
+    ln = oracle.code_lengths(hist)
+    cw = oracle.canonical_codes(ln)
+    want_off, want_payload = oracle.encode(codes, nbins, chunk, ln, cw, zero_chunks=True)
+    assert (np.diff(np.append(want_off, want_payload.size).astype(np.int64)) == 0).any()
+    ctx.comet_set_zero_chunks(True)
+    try:
+        if chunk != 100:                                      # the encoder takes chunks of 64, 128 and 256 symbols
+            lens_d = torch.empty(nbins, dtype=torch.uint8, device="cuda")
+            ctx.comet_stage_codebook(dev(hist.view(np.int32)), nbins, lens_d)
+            n_chunks = (n + chunk - 1) // chunk
+            off_d = torch.empty(n_chunks, dtype=torch.int32, device="cuda")
+            payload_d = torch.zeros(want_payload.size + 16, dtype=torch.int32, device="cuda")
+            pw_d = torch.zeros(1, dtype=torch.int64, device="cuda")
+            codes_d = torch.zeros(n + 16, dtype=torch.int16, device="cuda")
+            codes_d[:n] = dev(codes.view(np.int16))
+            ctx.comet_stage_encode(codes_d, n, nbins, chunk, off_d, payload_d, pw_d)
+            ctx.comet_sync()
+            assert int(pw_d.item()) == want_payload.size
+            assert np.array_equal(off_d.cpu().numpy().view(np.uint32), want_off)
+            assert np.array_equal(payload_d.cpu().numpy().view(np.uint32)[: want_payload.size], want_payload)
+        out = torch.empty(n, dtype=torch.int16, device="cuda")
+        ctx.comet_stage_decode(dev(ln), nbins, dev(want_off.view(np.int32)), dev(want_payload.view(np.int32)),
+                               want_payload.size, n, chunk, out)
+        ctx.comet_sync()
+        assert np.array_equal(out.cpu().numpy().view(np.uint16), codes)
+    finally:
+        ctx.comet_set_zero_chunks(False)
+
+
 def test_compress_with_codebook_more_lengths_than_fit_lds(comet, ctx, oracle):
     """A given table with more than 2048 code words (its canonical codes are then counted by symbol in global memory)."""
     x_old = synth.relu_blur((4, 8, 56, 56), seed=93, blur=3, shift=0.0)
