@@ -96,9 +96,11 @@ def other_configs(comet, synth, torch, np, chunk_syms, reps=5):
                          compress_frac_hbm_two_pass_floor=round((8 + b) * n / tc / HBM_PEAK_GBS, 4),
                          decompress_frac_hbm_fused_floor=round((4 + b) * n / td / HBM_PEAK_GBS, 4),
                          per_layer_ratio=[c["ratio"] for c in cells])
-    # zero chunks (container version 2) on the headline set and on a sparser one (shift -1.0: about 85 % zeros)
+    # zero chunks (container version 2) on the headline set (55 % zeros) and on sparser ones (the same recipe with the
+    # shift before the ReLU at -1.0, -2.0, -2.5: 84 %, 98 %, 99 % zeros)
     zc = {}
-    for name, shift in (("resnet50_set_batch64", -0.2), ("resnet50_set_batch64_sparse", -1.0)):
+    for name, shift in (("resnet50_set_batch64", -0.2), ("resnet50_set_batch64_zeros84", -1.0), ("resnet50_set_batch64_zeros98", -2.0),
+                        ("resnet50_set_batch64_zeros99", -2.5)):
         entries = [dict(e, shift=shift) for e in synth.config1(64)]
         ctx = comet.Context(max(int(np.prod(e["shape"])) for e in entries), 1024)
         ctx.comet_set_chunk_syms(chunk_syms)
