@@ -44,6 +44,21 @@ def traffic_from_profiles():
     return out
 
 
+def valu_issue_from_profiles():
+    """Share of the vector-ALU issue slots each kernel uses (rocprofv3 SQ counters): the lines
+    `VALU_ISSUE <kernel> <fraction>` of the counter summary under profiles/."""
+    out = {}
+    try:
+        with open(os.path.join(ROOT, "profiles", "sq_counters_resnet50_set_batch64.txt")) as f:
+            for line in f:
+                w = line.split()
+                if len(w) == 3 and w[0] == "VALU_ISSUE":
+                    out[w[1]] = float(w[2])
+    except OSError:
+        pass
+    return out
+
+
 def other_configs(comet, synth, torch, np, chunk_syms, reps=5):
     """Throughput and ratio of the configurations that are not the headline workload: config 0, the VGG-16-shaped
     set (config 2), the error-bound sweep (config 3, primary curve) and the two large tensors of config 4, each
@@ -382,7 +397,7 @@ def main() -> int:
     avg_s = kern[dom]["total_ms"] / launches / 1e3
     achieved = alg_bytes_per_launch / avg_s / 1e9
     roofline = dict(bound="hbm", kernel=dom, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=traffic.get(dom),
+                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=traffic.get(dom), valu_issue=valu_issue_from_profiles().get(dom),
                     avg_launch_us=round(avg_s * 1e6, 2), launches=launches,
                     alg_bytes_per_elem=round(alg[dom], 4),
                     note="mean over the five layers of the set; durations from HIP events recorded by the library on "
