@@ -1009,17 +1009,26 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
                     const bool mine = key < 2u * s_b;
                     const uint32_t n_mine_rec = (uint32_t)__popcll(wave_ballot(mine));
                     const bool is_e = mine && !(key & 1u);
-                    const uint64_t esc_mask = wave_ballot(is_e);
                     if (wave_ballot(mine && (key & 1u))) has_verbatim = true;
-                    if (is_e) {
+                    // Compact table: the strip holds 16-bit residuals of which the table's own take 12 bits.  An
+                    // escaped residual that fits the rest of the 16-bit range goes into the strip as it is (it
+                    // is a residual like any other from then on); only the others are listed.
+                    const bool direct = is_e && c16 && (int32_t)val > kLut16Escape && (int32_t)val < 32768;
+                    if (direct) {
+                        const uint32_t rel = (key >> 1) - (c0 << 6);
+                        *reinterpret_cast<int16_t *>(reinterpret_cast<char *>(strip) + (rel << 1) + ((rel >> 6) << 4)) = (int16_t)(int32_t)val;
+                    }
+                    const bool listed = is_e && !direct;
+                    const uint64_t esc_mask = wave_ballot(listed);
+                    if (listed) {
                         const uint32_t pos = n_esc + (uint32_t)__popcll(esc_mask & lt_mask);
                         const uint32_t e = (key >> 1) - s_a;                     // inside the strip
                         int32_t held = esc_marker;                               // what the strip holds for this residual
                         if (pos < kFuEscEntries) {
                             esc[pos] = (int32_t)val;
                             if (c16) {
-                                // the compact table's residuals leave room in 16 bits: the place in the list goes
-                                // into the strip, so that the scan finds the value without counting escapes
+                                // the place in the list goes into the strip (values below the table's escape marker
+                                // are free), so that the scan finds the value without counting escapes
                                 held = kLut16Escape - 1 - (int32_t)pos;
                                 const uint32_t rel = e + (s_a - (c0 << 6));
                                 *reinterpret_cast<int16_t *>(reinterpret_cast<char *>(strip) + (rel << 1) + ((rel >> 6) << 4)) = (int16_t)held;

@@ -595,6 +595,36 @@ def test_compress_with_codebook_stale_table(comet, ctx, oracle, w, eb, nbins, ch
     assert _reuse_case(comet, ctx, oracle, x_old, x_new, eb, nbins, chunk) is not None
 
 
+@pytest.mark.parametrize("shape", [(4, 8, 7, 7), (2, 4, 28, 28), (2, 3, 56, 56), (1, 3, 40, 112), (1, 2, 30, 224), (1, 1, 12, 500)])
+@pytest.mark.parametrize("eb,nbins", [(1e-2, 1024), (2e-2, 64), (1e-2, 4096)])
+def test_fused_decompression_escapes_of_every_size(comet, ctx, oracle, shape, eb, nbins):
+    """Escaped residuals of every kind in one tensor: those that fit the 16 bits a residual has in LDS next to
+    the table's own (kept in place), those below the table's range and those beyond 16 bits (listed), more of
+    them than the list holds in some strips, and verbatim values between them."""
+    rng = np.random.default_rng(shape[3] + nbins)
+    x = synth.relu_blur(shape, seed=900 + shape[3], blur=3, shift=-0.2)
+    flat = x.ravel()
+    k = max(8, flat.size // 25)
+    idx = rng.choice(flat.size, k, replace=False)
+    mag = np.exp(rng.uniform(np.log(0.5), np.log(5000.0), k)).astype(np.float32)       # residuals from tens to hundreds of thousands of steps
+    flat[idx] = mag * rng.choice(np.array([-1.0, 1.0], np.float32), k)
+    flat[rng.choice(flat.size, 5, replace=False)] = [np.inf, -np.inf, np.nan, 3e30, -1e-30]
+    dense = slice(flat.size // 2, flat.size // 2 + min(700, flat.size // 4))            # a run where nearly everything escapes
+    flat[dense] = rng.normal(0, 60.0, flat[dense].size).astype(np.float32)
+    want = oracle.compress(x, eb, nbins, 64)
+    rec = oracle.parse_container(want)["records"]
+    vals = rec[rec[:, 0] % 2 == 0][:, 1].view(np.int32)
+    assert (vals > 32767).any() and (vals < -2048).any() and ((vals > -2048) & (vals < 32768)).any()
+    out, used = gpu_compress(ctx, comet, x, eb, nbins, 64)
+    assert used == want.size and np.array_equal(out[:used].cpu().numpy(), want)
+    ref = oracle.decompress(want).ravel().view(np.uint32)
+    y = torch.empty(x.size, dtype=torch.float32, device="cuda")
+    ctx.comet_decompress(out, used, shape, y)
+    ctx.comet_sync()
+    assert np.array_equal(y.cpu().numpy().view(np.uint32), ref)
+    ctx.comet_set_chunk_syms(128)
+
+
 # --------------------------------------------------------------------------
 # zero chunks (container version 2)
 # --------------------------------------------------------------------------
