@@ -71,6 +71,10 @@ __device__ inline int32_t decode_long(uint64_t win, uint32_t start, uint32_t lut
 // first one, and one word of look-ahead so that no load sits on the critical
 // path.  Words are read from words[min(i, last)].  Everything is branch-free
 // except the wavefront-uniform test for a code longer than the look-up table.
+// The position runs from 1 to 32 (32: the first word is used up, the next bit is
+// the second word's first), so that the next 32 bits of the stream are always one
+// funnel shift of the two words, `alignbit(hi, lo, 32 - pos)`, whose shift count
+// the hardware takes modulo 32.
 // C16: the compact table (12 bits, u16 entries (residual << 4) | length), else the
 // general one (11 bits, u32 entries (residual << 8) | length).
 template <bool C16>
@@ -79,21 +83,26 @@ struct BitBuf {
     const uint32_t *words;
     uint32_t last;
     uint32_t hi, lo, nw;        // the word being consumed, the next one, the one after (look-ahead)
-    uint32_t pos, wp;           // bits of `hi` already consumed (0 .. 31); index of `nw`
+    uint32_t pos, wp;           // bits of `hi` already consumed (1 .. 32); index of `nw`
     __device__ inline uint32_t word(uint32_t i) const { return words[i < last ? i : last]; }
     __device__ inline void open(const uint32_t *w, uint32_t last_, uint32_t w0) {
         words = w; last = last_;
-        hi = word(w0); lo = word(w0 + 1); nw = word(w0 + 2);
-        pos = 0;
-        wp = w0 + 2;
+        hi = 0u; lo = word(w0); nw = word(w0 + 1);          // (a first word that is used up already)
+        pos = 32;
+        wp = w0 + 1;
     }
     static __device__ inline uint32_t look(const DsTables &t, uint64_t window) {
         const uint32_t idx = (uint32_t)(window >> (64 - kBits));
         return C16 ? (uint32_t)reinterpret_cast<const uint16_t *>(t.lut)[idx] : t.lut[idx];
     }
+    static __device__ inline uint32_t look32(const DsTables &t, uint32_t window) {       // window: the next 32 bits
+        const uint32_t idx = window >> (32 - kBits);
+        return C16 ? (uint32_t)reinterpret_cast<const uint16_t *>(t.lut)[idx] : t.lut[idx];
+    }
     static __device__ inline uint32_t len_of(uint32_t e) { return C16 ? (e & 0xfu) : (e & 0xffu); }
     static __device__ inline int32_t resid_of(uint32_t e) { return C16 ? ((int32_t)(e << 16) >> 20) : ((int32_t)e >> 8); }
     static __device__ inline uint32_t hint_of(uint32_t e) { return C16 ? (e >> 4) : (e >> 8); }
+    __device__ inline void advance() { hi = lo; lo = nw; ++wp; nw = word(wp); }
 
     __device__ inline int32_t next(const DsTables &t) {
         const uint64_t both = (((uint64_t)hi << 32) | lo) << pos;          // the next 64 - pos bits, left-aligned
@@ -102,23 +111,23 @@ struct BitBuf {
         int32_t d = resid_of(e);
         if (__builtin_expect(wave_ballot(L == 0u) != 0ull, 0)) {   // some lane met a code longer than the table: rare
             if (L == 0u) {
-                const uint64_t win = both | (pos ? (uint64_t)nw >> (32u - pos) : 0ull);
+                const uint64_t win = both | ((uint64_t)nw >> (32u - pos));
                 // second level: the prefix's sub-table on the next 1, 2, 4 or 6 bits; what is longer still
                 // (or has no sub-table) is searched by length
                 const bool found = second_level(t, e, win, L, d);
                 if (!found) d = decode_long(win, C16 ? 0u : hint_of(e), (uint32_t)kBits, t, &L);
                 if (pos + L >= 64u) {            // the code runs into the look-ahead word: move one word on here
-                    hi = lo; lo = nw; ++wp; nw = word(wp);
-                    pos -= 32u;
+                    advance();
+                    pos -= 32u;                  // (modulo 2^32; the sum below is in range again)
                 }
             }
         }
         pos += L;
-        // a word is used up: the next ones move in (a look-up-table code is at most kBits long)
-        const bool need = pos >= 32u;
+        // a word is used up: the next ones move in
+        const bool need = pos > 32u;
         hi = need ? lo : hi;
         lo = need ? nw : lo;
-        pos &= 31u;
+        pos -= need ? 32u : 0u;
         wp += need ? 1u : 0u;
         nw = word(wp);
         return d;
@@ -136,25 +145,25 @@ struct BitBuf {
         d = resid_of(e2);
         return true;
     }
-    // 64 bits of the stream from bit p (< 64) of the two words on: the look-ahead word fills the low end
+    // 64 bits of the stream from bit p (1 .. 63) of the two words on: the look-ahead word fills the low end
     __device__ inline uint64_t window_at(uint64_t both, uint32_t p) const {
-        return (both << p) | (p ? (((uint64_t)nw << 32) >> (64u - p)) : 0ull);
+        return (both << p) | (((uint64_t)nw << 32) >> (64u - p));
     }
-    // Two symbols packed as (second << 16) | (first & 0xffff).  Two look-up-table codes take at most
-    // 24 bits, so after the first one there are still at least kBits valid bits in the two words and
-    // the words move on only once per pair.  One wavefront-uniform test per pair: if either code of any
-    // lane is longer than the table the pair is finished by pair_with_long_codes.
+    // Two symbols packed as (second << 16) | (first & 0xffff).  The first code is looked up in the next 32
+    // bits, the second in the same bits shifted by the first one's length (a look-up-table code is at most
+    // kBits long, so 32 - kBits >= kBits of them are still there), and the words move on at most once per
+    // pair.  One wavefront-uniform test per pair: if either code of any lane is longer than the table the
+    // pair is finished by pair_with_long_codes.
     __device__ inline uint32_t next_pair(const DsTables &t) {
-        const uint64_t both = ((uint64_t)hi << 32) | lo;
-        const uint32_t e0 = look(t, both << pos);
-        const uint32_t p1 = pos + len_of(e0);
-        const uint32_t e1 = look(t, both << p1);
-        if (__builtin_expect(wave_ballot(len_of(e0) == 0u || len_of(e1) == 0u) != 0ull, 0)) return pair_with_long_codes(t, both, e0);
-        const uint32_t p2 = p1 + len_of(e1);
-        const bool need = p2 >= 32u;
+        const uint32_t top = __builtin_amdgcn_alignbit(hi, lo, 32u - pos);
+        const uint32_t e0 = look32(t, top);
+        const uint32_t e1 = look32(t, top << len_of(e0));
+        if (__builtin_expect(wave_ballot(len_of(e0) == 0u || len_of(e1) == 0u) != 0ull, 0)) return pair_with_long_codes(t, e0);
+        const uint32_t p2 = pos + len_of(e0) + len_of(e1);
+        const bool need = p2 > 32u;
         hi = need ? lo : hi;
         lo = need ? nw : lo;
-        pos = p2 & 31u;
+        pos = need ? p2 - 32u : p2;
         wp += need ? 1u : 0u;
         nw = word(wp);
         if (C16) return ((uint32_t)resid_of(e1) << 16) | ((uint32_t)resid_of(e0) & 0xffffu);
@@ -164,12 +173,13 @@ struct BitBuf {
     // second level (the lanes concerned only): up to 18 bits, so the second look-up still finds its bits in the
     // two words, and the pair may use up two words instead of one.  Only a code beyond both levels makes the
     // pair start over, one symbol at a time.
-    __device__ inline uint32_t pair_with_long_codes(const DsTables &t, uint64_t both, uint32_t e0) {
+    __device__ inline uint32_t pair_with_long_codes(const DsTables &t, uint32_t e0) {
+        const uint64_t both = ((uint64_t)hi << 32) | lo;
         uint32_t L0 = len_of(e0);
         int32_t d0 = resid_of(e0);
         bool fail = false;
         if (L0 == 0u) fail = !second_level(t, e0, window_at(both, pos), L0, d0);
-        const uint32_t p1 = pos + L0;                          // at most 31 + 18
+        const uint32_t p1 = pos + L0;                          // at most 32 + 18
         const uint32_t e1 = look(t, both << p1);
         uint32_t L1 = len_of(e1);
         int32_t d1 = resid_of(e1);
@@ -179,14 +189,14 @@ struct BitBuf {
             const uint32_t s1 = (uint32_t)next(t);
             return (s1 << 16) | s0;
         }
-        uint32_t p2 = p1 + L1;                                 // at most 31 + 36
-        const bool need = p2 >= 32u;
+        uint32_t p2 = p1 + L1;                                 // at most 32 + 36
+        const bool need = p2 > 32u;
         hi = need ? lo : hi;
         lo = need ? nw : lo;
         p2 -= need ? 32u : 0u;
         wp += need ? 1u : 0u;
         nw = word(wp);
-        if (p2 >= 32u) { hi = lo; lo = nw; p2 -= 32u; ++wp; nw = word(wp); }     // long codes may have used up a second word
+        if (p2 > 32u) { advance(); p2 -= 32u; }                 // long codes may have used up a second word
         pos = p2;
         return ((uint32_t)d1 << 16) | ((uint32_t)d0 & 0xffffu);
     }
