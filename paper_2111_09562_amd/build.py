@@ -17,11 +17,13 @@ LIB = os.path.join(HERE, "libcomet.so")
 ARCH = "gfx950"
 
 FLAGS = [
-    "-O3", "-std=c++17", f"--offload-arch={ARCH}", "-fPIC", "-shared",
+    "-O3", "-std=c++17", f"--offload-arch={ARCH}", "-fPIC",
     "-ffp-contract=off", "-fno-fast-math",            # every float op is one IEEE operation, as in the reference
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
 ]
+OBJ = os.path.join(HERE, "_build")                   # object files (not tracked)
+JOBS = 8
 
 
 def hipcc() -> str:
@@ -31,18 +33,49 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def sources():
-    return sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".h")))
+def units():
+    """The translation units: every .hip file.  No kernel calls device code of another unit, so
+    no relocatable device code is needed; the longest units come first."""
+    names = sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
+    names.sort(key=lambda f: (not f.startswith("k_decompress"), not f.startswith("k_quantize_rows")))
+    return [os.path.join(CSRC, f) for f in names]
+
+
+def headers():
+    return sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")) + \
+        [os.path.join(HERE, "..", "include", "comet.h")]
 
 
 def build(force: bool = False, verbose: bool = False) -> str:
-    newest = max(os.path.getmtime(p) for p in sources() + [os.path.join(HERE, "..", "include", "comet.h")])
-    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= newest:
-        return LIB
-    cmd = [hipcc()] + FLAGS + ["-o", LIB, os.path.join(CSRC, "libcomet.hip")]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
+    """Compile what is out of date (everything with force), several units at a time, and link."""
+    os.makedirs(OBJ, exist_ok=True)
+    newest_header = max(os.path.getmtime(p) for p in headers())
+    cc = hipcc()
+    todo, objs = [], []
+    for src in units():
+        obj = os.path.join(OBJ, os.path.basename(src)[:-4] + ".o")
+        objs.append(obj)
+        if force or not os.path.exists(obj) or os.path.getmtime(obj) < max(os.path.getmtime(src), newest_header):
+            todo.append([cc] + FLAGS + ["-c", src, "-o", obj])
+    running = []
+    def reap(block_until_below):
+        while len(running) > block_until_below:
+            proc, cmd = running.pop(0)
+            if proc.wait() != 0:
+                for other, _ in running:
+                    other.kill()
+                raise subprocess.CalledProcessError(proc.returncode, cmd)
+    for cmd in todo:
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        running.append((subprocess.Popen(cmd), cmd))
+        reap(JOBS - 1)
+    reap(0)
+    if todo or not os.path.exists(LIB) or any(os.path.getmtime(o) > os.path.getmtime(LIB) for o in objs):
+        cmd = [cc, f"--offload-arch={ARCH}", "-shared", "-fPIC", "-o", LIB] + objs
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.check_call(cmd)
     return LIB
 
 

@@ -6,6 +6,7 @@
 #include <cstdio>
 #include <cstring>
 #include <mutex>
+#include <numeric>
 #include <new>
 #include <vector>
 
@@ -181,15 +182,26 @@ void encode_geometry(const comet_ctx *ctx, uint64_t n_chunks, uint32_t *seg_chun
 // columns) with `grid` workgroups of four wavefronts, each wavefront on rows_per_wave consecutive
 // rows; otherwise the flat-tile kernel with `grid` segments of tiles.
 // vec: columns per lane of the row-walking kernel (2 if W is even and the input is 8-byte aligned).
+// chunk_align: if not 0, every run is a whole number of chunks of that many symbols (single-pass compression).
 struct QuantGeom { bool rows; uint32_t grid, rows_per_wave, rows_per_step, vec; };
-QuantGeom quantize_geometry(const comet_ctx *ctx, comet_shape s, uint64_t n, const void *x, uint32_t elem_bytes = 4);
+QuantGeom quantize_geometry(const comet_ctx *ctx, comet_shape s, uint64_t n, const void *x, uint32_t elem_bytes = 4, uint32_t chunk_align = 0);
 
-// reuse_len: code book reuse (device u8[nbins], row-walking kernel only); else null
+// Single-pass compression with a given code book: what the quantise kernel needs to encode its own codes.
+struct SinglePass {
+    const uint64_t *enc;       // encode table of the given lengths (k_codebook has run)
+    uint32_t chunk_syms, zero_pair;
+    uint32_t *chunk_off;       // chunk table of the container
+    uint32_t *run_words;       // one entry per run
+    uint32_t *work_words;      // n / 2 words
+};
+
+// reuse_len: code book reuse (device u8[nbins], row-walking kernel only, with sp); else null
 // in_type: element type of x (0 fp32, COMET_F16, COMET_BF16; the 16-bit types: row-walking kernel only, no reuse)
 int launch_quantize(comet_ctx *ctx, const void *x, comet_shape s, uint64_t n, float eb, uint32_t nbins,
                     hipStream_t st, uint16_t *codes, uint32_t *hist, uint32_t *hist_parts, uint32_t *rec, uint64_t rec_cap,
-                    uint64_t *desc, const uint8_t *reuse_len = nullptr, int in_type = 0) {
+                    uint64_t *desc, const uint8_t *reuse_len = nullptr, int in_type = 0, const SinglePass *sp = nullptr) {
     if (in_type != 0 && (reuse_len || s.w > kQuantRowsMaxW)) return COMET_ERR_INVALID;
+    if ((reuse_len != nullptr) != (sp != nullptr)) return COMET_ERR_INVALID;
     QuantArgs a{};
     a.x = x; a.n = n;
     a.divW = make_fastdiv(s.w); a.divH = make_fastdiv(s.h);
@@ -199,7 +211,7 @@ int launch_quantize(comet_ctx *ctx, const void *x, comet_shape s, uint64_t n, fl
     a.win_lo = (nbins - a.win_n) / 2u;
     a.n_tiles = (uint32_t)((n + kQuantTile - 1) / kQuantTile);
     a.codes = codes; a.hist = hist; a.rec = rec; a.rec_cap = rec_cap; a.desc = desc; a.ctl = &ctx->state->ctl;
-    const QuantGeom g = quantize_geometry(ctx, s, n, x, in_type ? 2u : 4u);
+    const QuantGeom g = quantize_geometry(ctx, s, n, x, in_type ? 2u : 4u, sp ? sp->chunk_syms : 0u);
     const uint32_t grid = g.grid;
     if (g.rows) {
         a.rows_total = (uint32_t)((uint64_t)s.n * s.c * s.h);
@@ -230,13 +242,25 @@ int launch_quantize(comet_ctx *ctx, const void *x, comet_shape s, uint64_t n, fl
             if (!reuse_len) { COMET_LAUNCH_QR_IN(VEC, NSEG, MULTI, 0); break; }                                        \
             {                                                                                                          \
                 TimedScope ts(ctx, st, COMET_KERNEL_QUANTIZE);                                                         \
-                hipLaunchKernelGGL((k_quantize_rows<VEC, NSEG, MULTI, true, true>), dim3(grid), dim3(kQuantBlock), lds_reuse, st, a); \
+                if (a.enc_n == nbins) hipLaunchKernelGGL((k_quantize_rows<VEC, NSEG, MULTI, true, true>), dim3(grid), dim3(kQuantBlock), lds_single, st, a); \
+                else hipLaunchKernelGGL((k_quantize_rows<VEC, NSEG, MULTI, false, true>), dim3(grid), dim3(kQuantBlock), lds_single, st, a);                 \
             }                                                                                                          \
             TimedScope ts(ctx, st, COMET_KERNEL_GATHER);                                                               \
             hipLaunchKernelGGL((k_gather_records<VEC, NSEG, MULTI, true>), dim3(grid), dim3(kQuantBlock), lds_reuse, st, a); \
         } while (0)
         a.reuse_len = reuse_len;
-        const size_t lds_reuse = ((size_t)nbins + 3u) & ~(size_t)3u;    // the given length table, one byte per bin
+        const size_t lds_reuse = ((size_t)nbins + 7u) & ~(size_t)7u;    // the given length table, one byte per bin
+        size_t lds_single = 0;
+        if (sp) {
+            // the kernel encodes its own codes: part of the encode table, a ring of codes and an assembly buffer per wavefront
+            a.enc = sp->enc;
+            a.enc_n = nbins < kEncTableMax ? nbins : kEncTableMax;
+            a.enc_lo = (nbins - a.enc_n) / 2u;
+            a.chunk_syms = sp->chunk_syms; a.zero_pair = sp->zero_pair;
+            a.chunk_off = sp->chunk_off; a.run_words = sp->run_words; a.work_words = sp->work_words;
+            lds_single = lds_reuse + ((size_t)a.enc_n + 1u) * 8u +
+                         (size_t)(kQuantBlock / kWave) * ((kEncRingSyms + 4u) * 2u + kEncRunBufWords * 4u);
+        }
         const uint32_t lanes_per_row = s.w / g.vec;
         if (g.vec == 2u) {
             if (lanes_per_row <= 32u) COMET_LAUNCH_QR(2, 1, true);
@@ -340,7 +364,7 @@ void encode_geometry(const comet_ctx *ctx, uint64_t n_chunks, uint32_t *seg_chun
     *n_seg = (uint32_t)((n_chunks + seg - 1) / seg);
 }
 
-QuantGeom quantize_geometry(const comet_ctx *ctx, comet_shape s, uint64_t n, const void *x, uint32_t elem_bytes) {
+QuantGeom quantize_geometry(const comet_ctx *ctx, comet_shape s, uint64_t n, const void *x, uint32_t elem_bytes, uint32_t chunk_align) {
     QuantGeom g{};
     g.vec = 1;
     if (s.w <= kQuantRowsMaxW) {
@@ -351,13 +375,20 @@ QuantGeom quantize_geometry(const comet_ctx *ctx, comet_shape s, uint64_t n, con
         const uint32_t lanes_per_row = s.w / g.vec;
         const uint32_t K = lanes_per_row <= 32u ? (uint32_t)kWave / lanes_per_row : 1u;
         g.rows_per_step = K;
+        // runs of whole steps; single-pass compression: and of whole chunks (chunk sizes are powers of two)
+        uint32_t unit = K;
+        if (chunk_align) {
+            uint32_t rows_per_chunk = chunk_align;               // rows after which a chunk boundary is a row boundary
+            for (uint32_t w = s.w; (w & 1u) == 0u && rows_per_chunk > 1u; w >>= 1) rows_per_chunk >>= 1;
+            unit = K / std::gcd(K, rows_per_chunk) * rows_per_chunk;
+        }
         // a few wavefronts per SIMD, but runs of at least 2048 elements (every run re-reads one row)
         const uint64_t want = (uint64_t)ctx->num_cu * 4u * kQuantRunsPerSimd;
         uint64_t per = (rows_total + want - 1) / want;
         const uint64_t min_rows = (2048u + s.w - 1u) / s.w;
         if (per < min_rows) per = min_rows;
-        per = (per + K - 1) / K * K;
-        if (per > rows_total) per = (rows_total + K - 1) / K * K;
+        per = (per + unit - 1) / unit * unit;
+        if (per > rows_total) per = (rows_total + unit - 1) / unit * unit;
         // a run must stay below 2^28 elements (buffer offsets): cannot be exceeded, rows_total * w < 2^31 and
         // the run count is in the thousands unless the tensor itself is small
         const uint64_t waves = (rows_total + per - 1) / per;
@@ -405,7 +436,8 @@ int comet_create(comet_ctx **out, uint64_t max_elems, uint32_t max_nbins) {
     if ((e = hipMalloc((void **)&c->stats, 8ull * (kStatsPartialMax + 1u))) != hipSuccess) return fail(COMET_ERR_NOMEM);
     c->max_runs = (uint64_t)c->num_cu * 4u * kQuantRunsPerSimd + 8u;
     if ((e = hipMalloc((void **)&c->rec_stage, c->max_runs * kQuantRecRun * 8ull)) != hipSuccess) return fail(COMET_ERR_NOMEM);
-    if ((e = hipMalloc((void **)&c->run_count, 3ull * c->max_runs * 4ull)) != hipSuccess) return fail(COMET_ERR_NOMEM);
+    // (a fourth array of one entry per run: the words of every run of the single-pass compression)
+    if ((e = hipMalloc((void **)&c->run_count, 4ull * c->max_runs * 4ull)) != hipSuccess) return fail(COMET_ERR_NOMEM);
     {
         // one blob: book scratch + decode tables
         uint64_t o = 0;
@@ -521,7 +553,7 @@ int compress_impl(comet_ctx *ctx, const void *dev_in, int in_type, comet_shape s
     const uint64_t n_chunks = (n + S - 1) / S;
     uint32_t e_seg, e_grid;
     encode_geometry(ctx, n_chunks, &e_seg, &e_grid);
-    const uint64_t tiles_q = quantize_geometry(ctx, s, n, dev_in, in_type ? 2u : 4u).grid;
+    const uint64_t tiles_q = quantize_geometry(ctx, s, n, dev_in, in_type ? 2u : 4u, dev_len ? S : 0u).grid;
     const uint64_t tiles_e = e_grid;
 
     Header proto{};
@@ -548,19 +580,40 @@ int compress_impl(comet_ctx *ctx, const void *dev_in, int in_type, comet_shape s
     uint64_t *desc_e = reinterpret_cast<uint64_t *>(ctx->zero_region + z.off_desc_e);
     uint8_t *out = static_cast<uint8_t *>(dev_out);
 
-    int rc = launch_quantize(ctx, dev_in, s, n, eb, nbins, st, ctx->codes, hist, hist_parts,
-                             reinterpret_cast<uint32_t *>(out + proto.off_outlier), (capacity - proto.off_outlier) / 8u, desc_q, dev_len, in_type);
-    if (rc) return rc;
-    {
-        BookArgs b{};
-        b.hist = hist; b.given_len = dev_len; b.nbins = nbins; b.len_out = out + proto.off_len; b.code_out = nullptr; b.enc = ctx->enc;
-        b.scratch = ctx->book; b.ctl = &ctx->state->ctl; b.hdr = reinterpret_cast<Header *>(out); b.proto = proto; b.capacity = capacity;
-        rc = launch_codebook(ctx, b, st);
-        if (rc) return rc;
+    BookArgs b{};
+    b.hist = hist; b.given_len = dev_len; b.nbins = nbins; b.len_out = out + proto.off_len; b.code_out = nullptr; b.enc = ctx->enc;
+    b.scratch = ctx->book; b.ctl = &ctx->state->ctl; b.hdr = reinterpret_cast<Header *>(out); b.proto = proto; b.capacity = capacity;
+    uint32_t *rec = reinterpret_cast<uint32_t *>(out + proto.off_outlier);
+    const uint64_t rec_cap = (capacity - proto.off_outlier) / 8u;
+    uint32_t *chunk_off = reinterpret_cast<uint32_t *>(out + proto.off_chunk);
+    int rc;
+    if (dev_len) {
+        // Single pass over the input: the code book first (header, length section, encode table), then the quantise
+        // kernel encodes its own codes into the work area, then the words of every run move to their place.
+        if ((rc = launch_codebook(ctx, b, st))) return rc;
+        const QuantGeom g = quantize_geometry(ctx, s, n, dev_in, 4u, S);
+        SinglePass sp{};
+        sp.enc = ctx->enc; sp.chunk_syms = S;
+        sp.zero_pair = ctx->zero_chunks ? ((nbins / 2u) << 16) | (nbins / 2u) : 0u;
+        sp.chunk_off = chunk_off;
+        sp.run_words = ctx->run_count + 3u * ctx->max_runs;
+        sp.work_words = reinterpret_cast<uint32_t *>(ctx->codes);
+        if ((rc = launch_quantize(ctx, dev_in, s, n, eb, nbins, st, nullptr, hist, hist_parts, rec, rec_cap, desc_q, dev_len, 0, &sp))) return rc;
+        PlaceArgs p{};
+        p.run_words = sp.run_words;
+        p.rows_per_wave = g.rows_per_wave; p.rows_total = (uint32_t)((uint64_t)s.n * s.c * s.h); p.W = s.w;
+        p.n_runs = (p.rows_total + g.rows_per_wave - 1u) / g.rows_per_wave;
+        p.chunk_syms = S; p.work_words = sp.work_words; p.container = out; p.capacity = capacity;
+        p.ctl = &ctx->state->ctl; p.latched = &ctx->state->latched;
+        constexpr uint32_t per_wg = (uint32_t)(kPlaceBlock / kWave);
+        TimedScope ts(ctx, st, COMET_KERNEL_ENCODE);
+        hipLaunchKernelGGL(k_place_payload, dim3((p.n_runs + per_wg - 1u) / per_wg), dim3(kPlaceBlock), 0, st, p);
+        HIP_TRY(hipGetLastError());
+    } else {
+        if ((rc = launch_quantize(ctx, dev_in, s, n, eb, nbins, st, ctx->codes, hist, hist_parts, rec, rec_cap, desc_q, nullptr, in_type))) return rc;
+        if ((rc = launch_codebook(ctx, b, st))) return rc;
+        if ((rc = launch_encode(ctx, ctx->codes, n, nbins, S, st, chunk_off, out, capacity, nullptr, 0, nullptr, desc_e))) return rc;
     }
-    rc = launch_encode(ctx, ctx->codes, n, nbins, S, st, reinterpret_cast<uint32_t *>(out + proto.off_chunk), out, capacity,
-                       nullptr, 0, nullptr, desc_e);
-    if (rc) return rc;
     if (bytes_out) {
         HIP_TRY(hipMemcpyAsync(ctx->host_state, ctx->state, sizeof(DevState), hipMemcpyDeviceToHost, st));
         HIP_TRY(hipStreamSynchronize(st));

@@ -30,6 +30,14 @@ struct QuantArgs {
     const uint8_t *reuse_len;  //   code book reuse (REUSE kernels): u8[nbins] code lengths; a code of length 0 becomes an escape; no histogram
     uint32_t *hist_parts;      //   hist_copies partial histograms of nbins entries, zeroed: workgroup b adds to copy b % hist_copies
     uint32_t hist_copies;      //   (k_gather_records adds them up into hist)
+    // single-pass compression (REUSE kernels): the codes are encoded by the wavefront that makes them
+    const uint64_t *enc;       //   encode table of the given lengths: (code << 6) | length per symbol
+    uint32_t enc_lo, enc_n;    //   table entries [enc_lo, enc_lo + enc_n) are cached in LDS
+    uint32_t chunk_syms;       //   64, 128 or 256; a run is a whole number of chunks
+    uint32_t zero_pair;        //   container version 2: (centre << 16) | centre, else 0
+    uint32_t *chunk_off;       //   chunk table of the container: offsets relative to the run (k_place_payload makes them absolute)
+    uint32_t *run_words;       //   words of every run
+    uint32_t *work_words;      //   work area: the words of the run that starts at element e at word e / 2
     uint16_t *codes;
     uint32_t *hist;            // u32[nbins], zeroed
     uint32_t *rec;             // (key, payload) pairs
@@ -37,6 +45,8 @@ struct QuantArgs {
     uint64_t *desc;            // chained-scan descriptors, one per segment, zeroed
     Control *ctl;
 };
+constexpr uint32_t kEncRingSyms = 2048;    // single-pass compression: codes a wavefront keeps in LDS between quantisation and encoding
+constexpr uint32_t kEncRunBufWords = 512;  //   its assembly buffer: the words of one step of 256 symbols (at most 468) and slack
 constexpr uint32_t kQuantRecLds = 3072;   // outlier records buffered in LDS per workgroup (24 KB)
 template <bool FULLWIN> __global__ void k_quantize(QuantArgs a);   // flat tiles, any plane width; FULLWIN: every bin is in the LDS window
 constexpr uint32_t kQuantRowsMaxW = 512;  // widest plane of the row-walking kernel
@@ -117,6 +127,21 @@ struct EncodeArgs {
     uint32_t *latched;         // product path: the context's persistent status word (the pack kernel seals the header); else null
     uint32_t zero_pair;        // container version 2: (centre << 16) | centre, a chunk of nothing but centre codes takes no words; else 0
 };
+// single-pass compression: the words of every run from the work area to the payload
+struct PlaceArgs {
+    const uint32_t *run_words;     // words of every run
+    uint32_t n_runs;               // runs that hold rows (the arrays have an entry for every wavefront of the grid)
+    uint32_t rows_per_wave, rows_total, W;
+    uint32_t chunk_syms;
+    const uint32_t *work_words;    // the run that starts at element e has its words from word e / 2 on
+    uint8_t *container;
+    uint64_t capacity;
+    Control *ctl;
+    uint32_t *latched;             // the context's persistent status word
+};
+constexpr int kPlaceBlock = 256;
+__global__ void k_place_payload(PlaceArgs a);
+
 constexpr uint32_t kEncUnroll = 4;         // steps of 256 symbols a wavefront handles per iteration
 constexpr uint32_t kEncStepWordsMax = 468; // 256 code words of up to 58 bits, in 32-bit words, plus slack
 constexpr uint32_t kEncBufWords = 640;     // assembly buffer of a wavefront (ordinary code books fill a fraction of it)

@@ -27,9 +27,16 @@
 //     operations in flight instead of draining them.
 // Escaped residuals (code 0) sit in the work buffer as -32768 and are replaced, in
 // element order, from the outlier records (copied to LDS once per strip).
+//
+// This file is the body of three translation units, one per output type (k_decompress_f32.hip,
+// k_decompress_f16.hip, k_decompress_bf16.hip define COMET_DEC_OUT and include it).
 #include <type_traits>
 
 #include "comet_kernels.h"
+
+#ifndef COMET_DEC_OUT
+#error "include through k_decompress_f32.hip, k_decompress_f16.hip or k_decompress_bf16.hip"
+#endif
 
 namespace comet {
 
@@ -293,6 +300,7 @@ __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes
 
 }  // namespace
 
+#if COMET_DEC_OUT == 0            // (not a template: in the fp32 unit only)
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kDsBlock) void k_decode_chunks(DsArgs a) {
     extern __shared__ uint32_t s_dyn_ds[];                  // kDsWaves x kDsStageWords: the words of 64 chunks per wavefront
@@ -417,6 +425,7 @@ __global__ __launch_bounds__(kDsBlock) void k_decode_chunks(DsArgs a) {
         wave_lds_fence();
     }
 }
+#endif
 
 // ---------------------------------------------------------------------------------------------
 // VEC: adjacent columns per lane (2 needs an even W and an output aligned to two elements: one load
@@ -1383,38 +1392,14 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
     }
 }
 
-#define COMET_INST_FUSED(OUT)                                           \
-    template __global__ void k_decode_scan<1, 0, OUT, 1>(FuArgs);       \
-    template __global__ void k_decode_scan<1, 1, OUT, 1>(FuArgs);       \
-    template __global__ void k_decode_scan<1, 2, OUT, 1>(FuArgs);       \
-    template __global__ void k_decode_scan<2, 2, OUT, 1>(FuArgs);       \
-    template __global__ void k_decode_scan<4, 2, OUT, 1>(FuArgs);       \
-    template __global__ void k_decode_scan<8, 2, OUT, 1>(FuArgs);       \
-    template __global__ void k_decode_scan<1, 0, OUT, 2>(FuArgs);       \
-    template __global__ void k_decode_scan<1, 1, OUT, 2>(FuArgs);       \
-    template __global__ void k_decode_scan<1, 2, OUT, 2>(FuArgs);       \
-    template __global__ void k_decode_scan<2, 2, OUT, 2>(FuArgs);       \
-    template __global__ void k_decode_scan<4, 2, OUT, 2>(FuArgs);
-COMET_INST_FUSED(0)
-COMET_INST_FUSED(1)
-COMET_INST_FUSED(2)
-#undef COMET_INST_FUSED
-
-#define COMET_INST_SCAN(OUT)                                            \
-    template __global__ void k_scan_store<1, 0, OUT, 1>(DsArgs);        \
-    template __global__ void k_scan_store<1, 1, OUT, 1>(DsArgs);        \
-    template __global__ void k_scan_store<1, 2, OUT, 1>(DsArgs);        \
-    template __global__ void k_scan_store<2, 2, OUT, 1>(DsArgs);        \
-    template __global__ void k_scan_store<4, 2, OUT, 1>(DsArgs);        \
-    template __global__ void k_scan_store<8, 2, OUT, 1>(DsArgs);        \
-    template __global__ void k_scan_store<1, 0, OUT, 2>(DsArgs);        \
-    template __global__ void k_scan_store<1, 1, OUT, 2>(DsArgs);        \
-    template __global__ void k_scan_store<1, 2, OUT, 2>(DsArgs);        \
-    template __global__ void k_scan_store<2, 2, OUT, 2>(DsArgs);        \
-    template __global__ void k_scan_store<4, 2, OUT, 2>(DsArgs);
-COMET_INST_SCAN(0)
-COMET_INST_SCAN(1)
-COMET_INST_SCAN(2)
-#undef COMET_INST_SCAN
+// One translation unit per output type (COMET_DEC_OUT: 0 fp32, 1 IEEE half, 2 bfloat16) instantiates the
+// kernels; they compile side by side.
+#define COMET_INST_DEC(NS, MO, VE)                                                   \
+    template __global__ void k_decode_scan<NS, MO, COMET_DEC_OUT, VE>(FuArgs);       \
+    template __global__ void k_scan_store<NS, MO, COMET_DEC_OUT, VE>(DsArgs);
+COMET_INST_DEC(1, 0, 1) COMET_INST_DEC(1, 1, 1) COMET_INST_DEC(1, 2, 1) COMET_INST_DEC(2, 2, 1)
+COMET_INST_DEC(4, 2, 1) COMET_INST_DEC(8, 2, 1) COMET_INST_DEC(1, 0, 2) COMET_INST_DEC(1, 1, 2)
+COMET_INST_DEC(1, 2, 2) COMET_INST_DEC(2, 2, 2) COMET_INST_DEC(4, 2, 2)
+#undef COMET_INST_DEC
 
 }  // namespace comet

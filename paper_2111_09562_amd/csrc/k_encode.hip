@@ -23,45 +23,11 @@
 // The encode table ((code << 6) | length per symbol) is cached in LDS for the
 // bins around the centre; other symbols are looked up in global memory.
 #include "comet_kernels.h"
+#include "comet_encode.h"
 
 namespace comet {
 
 namespace {
-
-// FULL: the whole table is in LDS.  Keeping global loads out of that variant matters: a load
-// inside the loop would make every iteration wait for the stores of the previous one.
-template <bool FULL>
-struct TableView {
-    const uint64_t *lds;
-    const uint64_t *glob;
-    uint32_t lo, n, nbins;
-    // A code outside the alphabet cannot come from the quantise kernel; it reads the zero entry
-    // that follows the cached part (length 0: the symbol contributes no bits).
-    __device__ inline uint64_t full(uint32_t code) const {
-        if (FULL) return lds[code < nbins ? code : nbins];
-        if (code >= nbins) return 0ull;
-        const uint32_t i = code - lo;
-        return (i < n) ? lds[i] : glob[code];
-    }
-    // length only
-    __device__ inline uint32_t length(uint32_t code) const {
-        if (FULL) return reinterpret_cast<const uint32_t *>(lds)[2u * (code < nbins ? code : nbins)] & 63u;
-        return (uint32_t)full(code) & 63u;
-    }
-};
-
-// inclusive prefix sum inside groups of LPC = 16, 32 or 64 adjacent lanes (DPP, no LDS)
-template <int LPC>
-__device__ inline uint32_t group_incl_scan(uint32_t v) {
-    int32_t x = (int32_t)v;
-    x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xf, 0xf, true);    // row_shr:1
-    x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xf, 0xf, true);    // row_shr:2
-    x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xf, 0xf, true);    // row_shr:4
-    x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xf, 0xf, true);    // row_shr:8
-    if (LPC >= 32) x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1, 3
-    if (LPC >= 64) x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2, 3
-    return (uint32_t)x;
-}
 
 // Four consecutive codes of this lane (symbols i0 .. i0+3) as two packed words, 0 past the end
 // (the caller masks those positions: every 16-bit value can be a code of the largest alphabet).
@@ -89,32 +55,6 @@ __device__ inline void fetch_steps(const uint16_t *codes, uint64_t n, uint32_t c
             v[u] = (st0 + u < steps) ? load4(codes, e0 + u * 256u + lane * 4u, n) : make_uint2(0, 0);
     }
 }
-// Container version 2 (sparse activations behind ReLU, COMET Sec. 4.2): which chunks of the step hold
-// nothing but the centre code and therefore take no words; true for the lanes of such a chunk.  left:
-// symbols of the step that exist (256 except at the end of the tensor; positions past the end do not count).
-template <int LPC>
-__device__ inline bool chunk_is_centre_only(uint2 v, uint32_t zero_pair, uint32_t lane, uint32_t left) {
-    bool mine = v.x == zero_pair && v.y == zero_pair;
-    if (left < 256u) {
-        const uint32_t centre = zero_pair & 0xffffu;
-        mine = true;
-#pragma unroll
-        for (uint32_t j = 0; j < 4; ++j) {
-            const uint32_t w = (j < 2) ? v.x : v.y;
-            const uint32_t c = (j & 1) ? (w >> 16) : (w & 0xffffu);
-            mine = mine && (lane * 4u + j >= left || c == centre);
-        }
-    }
-    const uint64_t all = wave_ballot(mine);
-    constexpr uint64_t grp = LPC == 64 ? ~0ull : ((1ull << (LPC & 63)) - 1ull);
-    return ((all >> ((lane / LPC) * LPC)) & grp) == grp;
-}
-
-__device__ inline uint32_t code_of(uint2 v, int j) {
-    const uint32_t w = (j < 2) ? v.x : v.y;
-    return (j & 1) ? (w >> 16) : (w & 0xffffu);
-}
-
 }  // namespace
 
 // ---------------------------------------------------------------------------
@@ -354,6 +294,87 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_pack(EncodeArgs a) {
     for (uint32_t idx = tid; idx < nc; idx += kEncBlock) a.chunk_off[c_lo + idx] = (uint32_t)(base + a.chunk_off[c_lo + idx]);
     if (overflow) atomicOr(&a.ctl->status, (uint32_t)ST_CAPACITY);
 
+}
+
+// ---------------------------------------------------------------------------
+// Single-pass compression, last step.  The quantise kernel has left the words of every run of
+// rows in a work area, with chunk offsets relative to the run, and k_gather_records the number
+// of outlier records, which decides where the payload starts.  One wavefront per run: the words
+// in front of the run are added up (the counts of all runs in front of the workgroup, by the
+// whole workgroup), the run's words are copied to their place and its chunk offsets made
+// absolute.  The wavefront of the last run seals the header.  Nothing is copied if an earlier
+// kernel of the call has raised an error.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kPlaceBlock) void k_place_payload(PlaceArgs a) {
+    constexpr int kWaves = kPlaceBlock / kWave;
+    __shared__ uint64_t s_part64[kWaves];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = (uint32_t)lane_id();
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / kWave));
+    const uint32_t run0 = blockIdx.x * kWaves, run = run0 + wave;
+
+    uint64_t sum = 0;
+    for (uint32_t i0 = 0; i0 < run0; i0 += 8u * kPlaceBlock) {            // eight loads in flight per thread
+        uint32_t v[8];
+#pragma unroll
+        for (uint32_t j = 0; j < 8; ++j) {
+            const uint32_t i = i0 + j * kPlaceBlock + tid;
+            v[j] = (i < run0) ? a.run_words[i] : 0u;
+        }
+#pragma unroll
+        for (uint32_t j = 0; j < 8; ++j) sum += v[j];
+    }
+    uint64_t base;
+    (void)block_excl_scan<uint64_t, kWaves>(sum, s_part64, base);
+    uint32_t mine = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const uint32_t c = (run0 + (uint32_t)w < a.n_runs) ? a.run_words[run0 + w] : 0u;
+        if ((uint32_t)w < wave) base += c;
+        if ((uint32_t)w == wave) mine = c;
+    }
+    if (run >= a.n_runs) return;
+
+    Header *h = reinterpret_cast<Header *>(a.container);
+    const uint64_t n_rec = a.ctl->n_rec;
+    const uint64_t rec_end = h->off_outlier + 8ull * n_rec;
+    const uint64_t off_payload = align16(rec_end);
+    const uint32_t earlier = a.ctl->status;                  // what the kernels before this one raised
+    const uint64_t pw_mine = base + mine;
+    if (run + 1u == a.n_runs && lane == 0) {
+        uint32_t stt = earlier;
+        const uint64_t total = off_payload + 4ull * pw_mine;
+        if (pw_mine > 0xffffffffull || total > a.capacity) stt |= (uint32_t)ST_CAPACITY;   // (chunk offsets are 32-bit word indices)
+        h->n_rec = (uint32_t)n_rec;
+        h->n_vrec = (uint32_t)a.ctl->n_vrec;
+        h->nnz = a.ctl->nnz;
+        h->off_payload = off_payload;
+        h->payload_words = pw_mine;
+        h->total_bytes = total;
+        h->status = stt ? 1u : 0u;
+        a.ctl->off_payload = off_payload;
+        a.ctl->payload_words = pw_mine;
+        a.ctl->total_bytes = total;
+        if (off_payload <= a.capacity)
+            for (uint64_t o = rec_end; o < off_payload; ++o) a.container[o] = 0;     // padding behind the records
+        if (stt) {
+            atomicOr(&a.ctl->status, stt);
+            atomicOr(a.latched, stt);
+        }
+    }
+    if (earlier) return;
+    const uint64_t cap_words = (a.capacity >= off_payload) ? (a.capacity - off_payload) / 4u : 0u;
+    const uint64_t row_lo = (uint64_t)run * a.rows_per_wave;
+    uint64_t row_hi = row_lo + a.rows_per_wave;
+    if (row_hi > a.rows_total) row_hi = a.rows_total;
+    const uint64_t e_lo = row_lo * a.W, e_hi = row_hi * a.W;
+    uint32_t *payload = reinterpret_cast<uint32_t *>(a.container + off_payload);
+    const uint32_t *src = a.work_words + e_lo / 2u;
+    for (uint32_t i = lane; i < mine; i += kWave)
+        if (base + i < cap_words) payload[base + i] = src[i];
+    uint32_t *chunk_off = reinterpret_cast<uint32_t *>(a.container + h->off_chunk);
+    const uint32_t c_lo = (uint32_t)(e_lo / a.chunk_syms), c_hi = (uint32_t)((e_hi + a.chunk_syms - 1u) / a.chunk_syms);
+    for (uint32_t c = c_lo + lane; c < c_hi; c += kWave) chunk_off[c] = (uint32_t)(base + chunk_off[c]);
 }
 
 #define COMET_INST_ENC(S)                                                  \

@@ -30,9 +30,17 @@
 // time writing in place).  The histogram goes the same way: LDS windows are added
 // to one of several partial histograms, which k_gather_records adds up.  Nothing
 // waits for anything inside a kernel.
+//
+// Compression with a given code book (the REUSE kernels) is a single pass over the input: the
+// lengths are known, so a wavefront encodes its own codes instead of storing them.  It keeps
+// them in a ring in LDS and, 256 at a time, packs them with the lane layout of the encode
+// kernel into a work area of its run; a run is a whole number of chunks, so no chunk is shared
+// between wavefronts.  k_place_payload moves the words of every run to their final place, which
+// depends on the sizes of all runs in front of it and on the number of outlier records.
 #include <type_traits>
 
 #include "comet_kernels.h"
+#include "comet_encode.h"
 
 namespace comet {
 
@@ -85,11 +93,13 @@ struct SweepCounts {
 // window.
 // REUSE: code book reuse.  s_len (LDS, u8[nbins]) holds the code lengths the caller brought; a code
 // whose length is 0 becomes an escape, there is no histogram, and an escape that the table has no
-// code word for raises ST_CODEBOOK.
+// code word for raises ST_CODEBOOK.  In PASS 0 the codes go to the ring of `enc` in LDS and are encoded
+// from there (tbl: the encode table; FULLWIN then says that all of it is in LDS).
 template <int VEC, int NSEG, bool MULTI, bool FULLWIN, int PASS, bool REUSE = false, int IN = 0>
 __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint32_t row_hi, uint32_t lane, uint32_t *s_hist,
                                       uint32_t hist_dummy, uint2 *s_buf, uint2 *rec_dst, uint64_t rec_cap, SweepCounts &cnt,
-                                      const uint8_t *s_len = nullptr) {
+                                      const uint8_t *s_len = nullptr, RunEncoder *enc = nullptr,
+                                      const TableView<FULLWIN> *tbl = nullptr) {
     const uint32_t W = a.divW.d, H = a.divH.d;
     const uint32_t LPR = W / (uint32_t)VEC;         // lanes per row
     const int32_t radius = a.radius;
@@ -203,6 +213,17 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
         cur += buffered;
         buffered = 0;
     };
+    uint16_t *ring_w = (PASS == 0 && REUSE) ? const_cast<uint16_t *>(enc->ring) : nullptr;
+    // single-pass compression: encode what the ring holds of the run's first `produced` symbols
+    auto drain = [&](uint32_t produced, bool final) {
+        if (PASS == 0 && REUSE) {
+            if (!final && produced - enc->consumed < 256u) return;
+            wave_lds_fence();
+            if (a.chunk_syms == 64u) enc->template drain<64, FULLWIN>(*tbl, lane, produced, final);
+            else if (a.chunk_syms == 128u) enc->template drain<128, FULLWIN>(*tbl, lane, produced, final);
+            else enc->template drain<256, FULLWIN>(*tbl, lane, produced, final);
+        }
+    };
     auto steps_of = [&](auto full_tag, uint32_t t0, float (&xb)[U][NSEG][VEC]) {
         constexpr bool FULL = decltype(full_tag)::value;
 #pragma unroll
@@ -284,7 +305,12 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
                         }
                     }
                 }
-                if (PASS == 0) {
+                if (PASS == 0 && REUSE) {
+                    // into the ring (lanes without an element write behind it)
+                    const uint32_t at = valid ? ((col[s] + soff) & (kEncRingSyms - 1u)) : kEncRingSyms;
+                    if (VEC == 2) *reinterpret_cast<uint32_t *>(ring_w + at) = code[0] | (code[VEC - 1] << 16);
+                    else ring_w[at] = (uint16_t)code[0];
+                } else if (PASS == 0) {
                     const int voff = FULL ? (int)(col[s] * 2u) : (int)((col[s] + soff) * 2u);
                     const int sof = FULL ? (int)(soff * 2u) : 0;
                     if (VEC == 2) __builtin_amdgcn_raw_buffer_store_b32(code[0] | (code[VEC - 1] << 16), r_c, voff, sof, 0);
@@ -348,14 +374,19 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
         for (; t0 < n_full; t0 += 2u * U) {
             fetch(full, t0 + U, t_max, xb);
             steps_of(full, t0, xa);
+            drain((t0 + U) * stride, false);
             fetch(full, t0 + 2u * U, t_max, xa);                // the last round re-reads the last step, unused
             steps_of(full, t0 + U, xb);
+            drain((t0 + 2u * U) * stride, false);
         }
     }
     for (; t0 < n_steps; t0 += U) {                              // fewer than two batches left
         fetch(general, t0, 0, xa);
         steps_of(general, t0, xa);
+        const uint32_t done = (t0 + U) * stride;
+        drain(done < n_el ? done : n_el, false);
     }
+    drain(n_el, true);
     flush_records();
     return cur;
 }
@@ -386,8 +417,15 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize_rows(QuantArgs a) {
     const uint32_t lane = (uint32_t)lane_id();
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / kWave));
     uint8_t *s_len = reinterpret_cast<uint8_t *>(s_dyn_qr);
+    // REUSE: behind the length table the cached part of the encode table (and a zero entry), then per
+    // wavefront the ring of codes (and the word lanes without an element write to) and the assembly buffer
+    uint64_t *s_tbl = reinterpret_cast<uint64_t *>(s_len + ((a.nbins + 7u) & ~7u));
+    uint16_t *s_ring = reinterpret_cast<uint16_t *>(s_tbl + a.enc_n + 1u) + wave * (kEncRingSyms + 4u);
+    uint32_t *s_asm = reinterpret_cast<uint32_t *>(reinterpret_cast<uint16_t *>(s_tbl + a.enc_n + 1u) + kWaves * (kEncRingSyms + 4u)) + wave * kEncRunBufWords;
     if (REUSE) {
         for (uint32_t i = tid; i < a.nbins; i += kQuantBlock) s_len[i] = a.reuse_len[i];
+        for (uint32_t i = tid; i <= a.enc_n; i += kQuantBlock) s_tbl[i] = (i < a.enc_n) ? a.enc[a.enc_lo + i] : 0ull;
+        for (uint32_t i = lane; i < kEncRunBufWords; i += kWave) s_asm[i] = 0;
     } else {
         for (uint32_t i = tid; i < (a.win_n << a.hist_shift); i += kQuantBlock) s_hist[i] = 0;
     }
@@ -398,9 +436,24 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize_rows(QuantArgs a) {
     run_rows(a, run, &row_lo, &row_hi);
     SweepCounts cnt;
     uint32_t my_records = 0;
+    RunEncoder enc;
+    TableView<FULLWIN> tbl{s_tbl, a.enc, a.enc_lo, a.enc_n, a.nbins};
+    if (REUSE) {
+        const uint32_t e_lo = row_lo * a.divW.d, n_el = (row_hi - row_lo) * a.divW.d;    // a whole number of chunks, but for the last run
+        enc.ring = s_ring; enc.buf = s_asm;
+        enc.words = a.work_words + e_lo / 2u; enc.cap_words = n_el / 2u;
+        enc.chunk_off = a.chunk_off + e_lo / a.chunk_syms;
+        enc.zero_pair = a.zero_pair;
+    }
     if (row_hi > row_lo)
         my_records = sweep_rows<VEC, NSEG, MULTI, FULLWIN, 0, REUSE, IN>(a, row_lo, row_hi, lane, s_hist, (a.win_n << a.hist_shift) + tid, s_recbuf[wave],
-                                                                 reinterpret_cast<uint2 *>(a.stage) + (size_t)run * kQuantRecRun, kQuantRecRun, cnt, s_len);
+                                                                 reinterpret_cast<uint2 *>(a.stage) + (size_t)run * kQuantRecRun, kQuantRecRun, cnt, s_len,
+                                                                 REUSE ? &enc : nullptr, REUSE ? &tbl : nullptr);
+    if (REUSE) {
+        if (lane == 0) a.run_words[run] = enc.wrun;
+        // a run that needs more than 16 bits per symbol does not fit its work area: the table does not suit this tensor
+        if (wave_ballot(enc.overflow) && lane == 0) atomicOr(&a.ctl->status, (uint32_t)ST_CODEBOOK);
+    }
     // results: record count per run; records, non-zero inputs and verbatim records per workgroup (summed
     // up by the gather kernel; thousands of atomics on one counter would cost more than the sweep)
     const uint32_t nnz_wave = wave_sum<uint32_t>(cnt.nnz_lane);
@@ -531,6 +584,7 @@ __global__ __launch_bounds__(kQuantBlock) void k_gather_records(QuantArgs a) {
     template __global__ void k_quantize_rows<VEC, NSEG, MULTI, true, false, 0>(QuantArgs);       \
     template __global__ void k_quantize_rows<VEC, NSEG, MULTI, false, false, 0>(QuantArgs);      \
     template __global__ void k_quantize_rows<VEC, NSEG, MULTI, true, true, 0>(QuantArgs);        \
+    template __global__ void k_quantize_rows<VEC, NSEG, MULTI, false, true, 0>(QuantArgs);       \
     template __global__ void k_gather_records<VEC, NSEG, MULTI, false, 0>(QuantArgs);            \
     template __global__ void k_gather_records<VEC, NSEG, MULTI, true, 0>(QuantArgs);             \
     COMET_INST_QR16(VEC, NSEG, MULTI, 1)                                                         \
