@@ -104,7 +104,8 @@ int comet_compress(comet_ctx *ctx, const float *dev_in, comet_shape shape, float
 /* Compress with the code book of an earlier compression of the same layer.  COMET refreshes a
  * layer's statistics only every W iterations because they change slowly (Sec. 3.1); the same holds
  * for the layer's histogram, so the histogram and the Huffman construction (Sec. 4.1) can be skipped
- * between refreshes.  dev_len: device pointer to u8[nbins] code lengths (the length section of an
+ * between refreshes; with the code words known beforehand the tensor is read once, every part of it
+ * quantised and encoded by the same wavefront.  dev_len: device pointer to u8[nbins] code lengths (the length section of an
  * earlier container of the same nbins starts COMET_HEADER_BYTES into it); it must stay valid and
  * unchanged until the call has completed and may lie inside another container, not inside dev_out.
  * The lengths must form a complete prefix code (or one symbol of length 1), none above 57.  A
@@ -112,9 +113,11 @@ int comet_compress(comet_ctx *ctx, const float *dev_in, comet_shape shape, float
  * alphabet (escape symbol + outlier record); the container carries the table, so it decompresses
  * with comet_decompress to exactly the values comet_compress would give.  Everything else as
  * comet_compress.  Limits: nbins <= 8192 and planes of at most 512 columns (COMET_ERR_INVALID
- * otherwise).  A table that is no such code, or that lacks a code word for the escape symbol when
- * the tensor needs one, raises COMET_ERR_CODEBOOK (device-side: returned here if bytes_out is
- * given, else by comet_sync); the caller then compresses in full. */
+ * otherwise).  A table that is no such code, that lacks a code word for the escape symbol when
+ * the tensor needs one, or that spends more than 16 bits per symbol on some run of rows (about
+ * 2048 elements or more: the encoded run does not fit its share of the workspace; such a table
+ * expands the data) raises COMET_ERR_CODEBOOK (device-side: returned here if bytes_out is given,
+ * else by comet_sync); the caller then compresses in full. */
 int comet_compress_with_codebook(comet_ctx *ctx, const float *dev_in, comet_shape shape, float eb, uint32_t nbins,
                                  const uint8_t *dev_len, void *stream, void *dev_out, uint64_t capacity,
                                  uint64_t *bytes_out);

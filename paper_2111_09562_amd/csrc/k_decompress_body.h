@@ -703,7 +703,7 @@ __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
 // elements lie inside 64 consecutive chunks (about 4032 elements).  A wavefront takes a strip:
 //   1. the words of the strip's chunks come global -> LDS with coalesced loads;
 //   2. every lane decodes one chunk, 64 symbols, into 32 registers (pairs of int16 residuals);
-//   3. the lanes write their registers to the same LDS region, one row of kFuPitch words per chunk
+//   3. the lanes write their registers to the same LDS region, element after element
 //      (the words are no longer needed: the two uses share the memory);
 //   4. the lanes turn into columns and walk the strip's rows out of LDS: row prefix by a DPP scan,
 //      column prefix in a register per column, * 2eb, store.  Rows that take at most 32 lanes are
@@ -1002,9 +1002,11 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
                 pf_have = true;
             }
 
-            // ---- 3. registers -> LDS, one row of kFuPitch words per chunk ----
+            // ---- 3. registers -> LDS, element after element: 32 words per chunk.  (The 16-byte writes of the 64 lanes
+            // fall into the same banks, which costs a few hundred cycles per strip; a padded row per chunk would avoid
+            // that, and cost every later read of the strip four instructions for its address instead of one.) ----
             {
-                uint4 *row = reinterpret_cast<uint4 *>(strip + lane * kFuPitch);
+                uint4 *row = reinterpret_cast<uint4 *>(strip + lane * 32u);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     row[i] = make_uint4(pa[4 * i], pa[4 * i + 1], pa[4 * i + 2], pa[4 * i + 3]);
@@ -1035,7 +1037,7 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
                     const bool direct = is_e && c16 && (int32_t)val > kLut16Escape && (int32_t)val < 32768;
                     if (direct) {
                         const uint32_t rel = (key >> 1) - (c0 << 6);
-                        *reinterpret_cast<int16_t *>(reinterpret_cast<char *>(strip) + (rel << 1) + ((rel >> 6) << 4)) = (int16_t)(int32_t)val;
+                        *reinterpret_cast<int16_t *>(reinterpret_cast<char *>(strip) + (rel << 1)) = (int16_t)(int32_t)val;
                     }
                     const bool listed = is_e && !direct;
                     const uint64_t esc_mask = wave_ballot(listed);
@@ -1050,7 +1052,7 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
                                 // are free), so that the scan finds the value without counting escapes
                                 held = kLut16Escape - 1 - (int32_t)pos;
                                 const uint32_t rel = e + (s_a - (c0 << 6));
-                                *reinterpret_cast<int16_t *>(reinterpret_cast<char *>(strip) + (rel << 1) + ((rel >> 6) << 4)) = (int16_t)held;
+                                *reinterpret_cast<int16_t *>(reinterpret_cast<char *>(strip) + (rel << 1)) = (int16_t)held;
                             }
                         }
                         if (exchange) {
@@ -1089,8 +1091,8 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
             }
 
             const uint32_t rel0 = s_a - (c0 << 6);               // the strip's first element inside its chunks
-            // a strip's element `off` in LDS: ((rel0 + off) / 64) * kFuPitch * 4 + ((rel0 + off) % 64) * 2 bytes
-            auto lds_of = [&](uint32_t off) { const uint32_t rel = off + rel0; return (rel << 1) + ((rel >> 6) << 4); };
+            // a strip's element `off` in LDS: byte 2 * (rel0 + off) of the strip's region
+            auto lds_of = [&](uint32_t off) { return (off + rel0) << 1; };
             auto lds_read = [&](uint32_t off) -> uint32_t {      // VEC == 2: two residuals; else one (sign-extended)
                 const char *p = reinterpret_cast<const char *>(strip) + lds_of(off);
                 if (VEC == 2) return *reinterpret_cast<const uint32_t *>(p);

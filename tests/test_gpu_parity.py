@@ -776,6 +776,68 @@ def test_compress_with_codebook_errors(comet, ctx, oracle):
     assert ei.value.code == comet.ERR_INVALID
 
 
+def test_compress_with_codebook_zero_chunks(comet, ctx, oracle):
+    """Container version 2 from the single-pass compressor: with the tensor's own table it is the oracle's version 2."""
+    x = synth.relu_blur((2, 8, 56, 56), seed=95, blur=3, shift=-0.2)
+    x[1, 2:6] = 0.0                                              # whole planes of zeros: chunks of nothing but the centre code
+    want = oracle.compress(x, 1e-2, 1024, 64, flags=oracle.ZERO_CHUNKS)
+    a, used_a = gpu_compress(ctx, comet, x, 1e-2, 1024, 64)
+    table = a[comet.HEADER_BYTES: comet.HEADER_BYTES + 1024]
+    b = torch.empty_like(a)
+    ctx.comet_set_zero_chunks(True)
+    try:
+        used_b = ctx.comet_compress_with_codebook(dev(x), 1e-2, 1024, table, b)
+    finally:
+        ctx.comet_set_zero_chunks(False)
+    assert used_b == want.size and used_b < used_a
+    assert np.array_equal(b[:used_b].cpu().numpy(), want)
+
+
+def test_compress_with_codebook_table_that_expands_the_data(comet, ctx, oracle):
+    """The single-pass compressor gives a run of rows 16 bits per symbol of work space.  A table that needs more
+    (here: 20 bits for the centre code of a tensor of zeros) is refused with the error that tells the caller to
+    compress in full, as for a missing escape code; the oracle, which has no such limit, encodes it.  With zero
+    chunks the same tensor takes no words at all and goes through."""
+    nbins = 64
+    lens = np.zeros(nbins, np.uint8)
+    lens[nbins // 2] = 20; lens[0] = 20                           # centre and escape: 20 bits each
+    lens[1:20] = np.arange(1, 20, dtype=np.uint8)                 # 2^-1 + ... + 2^-19 + 2 * 2^-20 = 1
+    x = np.zeros((1, 4, 32, 32), np.float32)
+    oracle.compress_with_lengths(x, 1e-2, nbins, 64, lens)        # valid for the oracle
+    out = torch.empty(comet.comet_compress_bound(x.shape, nbins, 64), dtype=torch.uint8, device="cuda")
+    ctx.comet_set_chunk_syms(64)
+    with pytest.raises(comet.CometError) as ei:
+        ctx.comet_compress_with_codebook(dev(x), 1e-2, nbins, dev(lens), out)
+    assert ei.value.code == comet.ERR_CODEBOOK
+    ctx.comet_set_zero_chunks(True)
+    try:
+        used = ctx.comet_compress_with_codebook(dev(x), 1e-2, nbins, dev(lens), out)
+    finally:
+        ctx.comet_set_zero_chunks(False)
+    y = torch.full((x.size,), 7.0, dtype=torch.float32, device="cuda")
+    ctx.comet_decompress(out, used, x.shape, y)
+    ctx.comet_sync()
+    assert not y.any()
+    # the context still works afterwards
+    used = ctx.comet_compress(dev(x), 1e-2, nbins, out)
+    assert np.array_equal(out[:used].cpu().numpy(), oracle.compress(x, 1e-2, nbins, 64))
+
+
+def test_compress_with_codebook_capacity(comet, ctx, oracle):
+    """A container buffer that is too small for the payload: the kernel that moves the words to their place reports it."""
+    x = synth.relu_blur((2, 8, 56, 56), seed=96, blur=3, shift=-0.2)
+    a, used = gpu_compress(ctx, comet, x, 1e-2, 1024, 64)
+    table = a[comet.HEADER_BYTES: comet.HEADER_BYTES + 1024].clone()
+    small = torch.zeros((used - 4096) // 16 * 16 + 64, dtype=torch.uint8, device="cuda")
+    guard = small[-64:]                                          # not part of the capacity handed over: must stay untouched
+    with pytest.raises(comet.CometError) as ei:
+        ctx.comet_compress_with_codebook(dev(x), 1e-2, 1024, table, small[:-64])
+    assert ei.value.code == comet.ERR_CAPACITY
+    assert not guard.any()
+    b = torch.empty_like(a)
+    assert ctx.comet_compress_with_codebook(dev(x), 1e-2, 1024, table, b) == used and torch.equal(a[:used], b[:used])
+
+
 def test_abs_mean(comet, ctx, oracle):
     """The controller's statistic.  Tolerance: both sides add non-negative fp64 terms, the oracle in index
     order, the GPU in a fixed tree; each addition is within 2^-53 relative, so the two sums differ by at
