@@ -77,12 +77,13 @@ __device__ inline uint32_t code_of(uint2 v, int j) {
 // of the run (positions relative to the run, like the chunk offsets it writes); a small kernel
 // moves them to their place once the sizes of all runs and the record count are known.
 // ---------------------------------------------------------------------------------------------
+constexpr uint32_t kEncOob = 0x80000000u;       // byte offset beyond every buffer
 struct RunEncoder {
     const uint16_t *ring;       // LDS: kEncRingSyms codes, element e of the run at e % kEncRingSyms
     uint32_t *buf;              // LDS: assembly buffer of one step, kEncRunBufWords words, zero between steps
-    uint32_t *words;            // global: the run's words
-    uint32_t cap_words;         //   and how many fit
-    uint32_t *chunk_off;        // global: chunk table entry of the run's first chunk
+    __amdgpu_buffer_rsrc_t r_words;   // global: the run's words (as many as fit)
+    uint32_t cap_words;
+    __amdgpu_buffer_rsrc_t r_chunk;   // global: the chunk table entries of the run's chunks
     uint32_t zero_pair;         // container version 2: (centre << 16) | centre, else 0
     uint32_t consumed = 0;      // symbols encoded so far (a multiple of 256 until the run's last step)
     uint32_t wrun = 0;          // words written so far
@@ -117,7 +118,10 @@ struct RunEncoder {
             if ((uint32_t)k == g) wbase = total_words;
             total_words += wk;
         }
-        if ((lane % LPC) == 0u && g * (uint32_t)S < left) chunk_off[consumed / (uint32_t)S + g] = wrun + wbase;
+        // (buffer stores that every lane issues, with an offset out of range where there is nothing to store: a
+        // store inside a branch would make the quantise loop around this wait for all its loads at every turn)
+        __builtin_amdgcn_raw_buffer_store_b32(wrun + wbase, r_chunk,
+                                              ((lane % LPC) == 0u && g * (uint32_t)S < left) ? (int)((consumed / (uint32_t)S + g) * 4u) : (int)kEncOob, 0, 0);
         uint32_t p = wbase * 32u + incl - bits;
         auto place = [&](uint64_t t, uint32_t L, uint32_t at) {
             const uint32_t sh = at & 31u, w = at >> 5;
@@ -137,12 +141,23 @@ struct RunEncoder {
             }
         }
         wave_lds_fence();
-        for (uint32_t k = lane; k < total_words; k += kWave) {
+        // the step's words leave: 128 of them (16 bits per symbol) with two stores of every lane, the rare rest in a loop;
+        // what lies beyond the run's work area is dropped by the buffer's range check
+#pragma unroll
+        for (uint32_t k0 = 0; k0 < 2u * kWave; k0 += kWave) {
+            const uint32_t k = k0 + lane;
             const uint32_t word = buf[k];
             buf[k] = 0;
-            if (wrun + k < cap_words) words[wrun + k] = word;
-            else overflow = true;
+            __builtin_amdgcn_raw_buffer_store_b32(word, r_words, k < total_words ? (int)((wrun + k) * 4u) : (int)kEncOob, 0, 0);
         }
+        if (__builtin_expect(total_words > 2u * kWave, 0)) {
+            for (uint32_t k = 2u * kWave + lane; k < total_words; k += kWave) {
+                const uint32_t word = buf[k];
+                buf[k] = 0;
+                __builtin_amdgcn_raw_buffer_store_b32(word, r_words, (int)((wrun + k) * 4u), 0, 0);
+            }
+        }
+        if (wrun + total_words > cap_words) overflow = true;
         wave_lds_fence();
         wrun += total_words;
         consumed += left;
@@ -152,6 +167,7 @@ struct RunEncoder {
     // the end of the run (final) the rest.
     template <int S, bool FULLTBL>
     __device__ inline void drain(const TableView<FULLTBL> &tbl, uint32_t lane, uint32_t produced, bool final) {
+
         while (produced - consumed >= 256u) step<S, FULLTBL>(tbl, lane, 256u);
         if (final && consumed < produced) step<S, FULLTBL>(tbl, lane, produced - consumed);
     }

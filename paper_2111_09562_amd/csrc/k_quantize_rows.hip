@@ -441,8 +441,9 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize_rows(QuantArgs a) {
     if (REUSE) {
         const uint32_t e_lo = row_lo * a.divW.d, n_el = (row_hi - row_lo) * a.divW.d;    // a whole number of chunks, but for the last run
         enc.ring = s_ring; enc.buf = s_asm;
-        enc.words = a.work_words + e_lo / 2u; enc.cap_words = n_el / 2u;
-        enc.chunk_off = a.chunk_off + e_lo / a.chunk_syms;
+        enc.cap_words = n_el / 2u;
+        enc.r_words = rows_rsrc(a.work_words + e_lo / 2u, enc.cap_words * 4u);
+        enc.r_chunk = rows_rsrc(a.chunk_off + e_lo / a.chunk_syms, (n_el + a.chunk_syms - 1u) / a.chunk_syms * 4u);
         enc.zero_pair = a.zero_pair;
     }
     if (row_hi > row_lo)
