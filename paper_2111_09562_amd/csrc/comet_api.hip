@@ -383,7 +383,9 @@ QuantGeom quantize_geometry(const comet_ctx *ctx, comet_shape s, uint64_t n, con
             unit = K / std::gcd(K, rows_per_chunk) * rows_per_chunk;
         }
         // a few wavefronts per SIMD, but runs of at least 2048 elements (every run re-reads one row)
-        const uint64_t want = (uint64_t)ctx->num_cu * 4u * kQuantRunsPerSimd;
+        // (single-pass compression: the encoder's ring and tables in LDS leave room for four workgroups per compute
+        // unit, and a run that has to wait for a place would make the launch take two rounds)
+        const uint64_t want = (uint64_t)ctx->num_cu * 4u * (chunk_align ? kQuantRunsPerSimdSingle : kQuantRunsPerSimd);
         uint64_t per = (rows_total + want - 1) / want;
         const uint64_t min_rows = (2048u + s.w - 1u) / s.w;
         if (per < min_rows) per = min_rows;

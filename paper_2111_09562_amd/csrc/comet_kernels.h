@@ -53,6 +53,7 @@ constexpr uint32_t kQuantRowsMaxW = 512;  // widest plane of the row-walking ker
 constexpr uint32_t kQuantRecRun = 768;    // outlier records staged per run (one run of rows per wavefront)
 constexpr uint32_t kQuantRecLds2 = 256;   // records a wavefront buffers in LDS before it writes them to the staging area in bulk
 constexpr uint32_t kQuantRunsPerSimd = 5; // runs the launch aims at, per SIMD
+constexpr uint32_t kQuantRunsPerSimdSingle = 4;   //   ... of the single-pass compression (all of them resident at once)
 constexpr uint32_t kQuantHistCopiesMax = 32;        // partial histograms the workgroups spread their flushes over
 constexpr uint32_t kQuantHistPartsWords = 65536;    // all copies together have at most this many entries
 // VEC adjacent columns per lane (2 needs an even W and 8-byte aligned input), NSEG segments of 64 lanes per row,
