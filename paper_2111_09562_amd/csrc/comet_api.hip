@@ -258,7 +258,7 @@ int launch_quantize(comet_ctx *ctx, const void *x, comet_shape s, uint64_t n, fl
             a.enc_lo = (nbins - a.enc_n) / 2u;
             a.chunk_syms = sp->chunk_syms; a.zero_pair = sp->zero_pair;
             a.chunk_off = sp->chunk_off; a.run_words = sp->run_words; a.work_words = sp->work_words;
-            lds_single = lds_reuse + ((size_t)a.enc_n + 1u) * 8u +
+            lds_single = (a.enc_n == nbins ? 0u : lds_reuse) + ((size_t)a.enc_n + 1u) * 8u +
                          (size_t)(kQuantBlock / kWave) * ((kEncRingSyms + 4u) * 2u + kEncRunBufWords * 4u);
         }
         const uint32_t lanes_per_row = s.w / g.vec;

@@ -46,7 +46,7 @@ struct QuantArgs {
     Control *ctl;
 };
 constexpr uint32_t kEncRingSyms = 1024;    // single-pass compression: codes a wavefront keeps in LDS between quantisation and encoding (a batch of at most 512, and less than 256 not yet encoded)
-constexpr uint32_t kEncRunBufWords = 512;  //   its assembly buffer: the words of one step of 256 symbols (at most 468) and slack
+constexpr uint32_t kEncRunBufWords = 476;  //   its assembly buffer: the words of one step of 256 symbols (at most 456 of code words of 57 bits, two more touched) and slack
 constexpr uint32_t kQuantRecLds = 3072;   // outlier records buffered in LDS per workgroup (24 KB)
 template <bool FULLWIN> __global__ void k_quantize(QuantArgs a);   // flat tiles, any plane width; FULLWIN: every bin is in the LDS window
 constexpr uint32_t kQuantRowsMaxW = 512;  // widest plane of the row-walking kernel

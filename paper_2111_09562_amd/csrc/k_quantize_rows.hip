@@ -214,6 +214,13 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
         buffered = 0;
     };
     uint16_t *ring_w = (PASS == 0 && REUSE) ? const_cast<uint16_t *>(enc->ring) : nullptr;
+    // REUSE: does the given table have a code word for this code?  From the length table; the single-pass sweep with
+    // the whole encode table in LDS reads that instead (an entry is 0 for a symbol without a code word), which saves
+    // the length table's LDS.
+    auto has_code = [&](uint32_t c) -> bool {
+        if (PASS == 0 && REUSE && FULLWIN) return reinterpret_cast<const uint32_t *>(tbl->lds)[2u * c] != 0u;
+        return s_len[c] != 0;
+    };
     // single-pass compression: encode what the ring holds of the run's first `produced` symbols
     auto drain = [&](uint32_t produced, bool final) {
         if (PASS == 0 && REUSE) {
@@ -280,7 +287,7 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
                     d[v] = (int32_t)((uint32_t)rd[v] - (uint32_t)up[v]);
                     const uint32_t c = (uint32_t)d[v] + (uint32_t)radius;
                     inr[v] = (c - 1u) < code_span;
-                    if (REUSE) inr[v] = inr[v] && s_len[inr[v] ? c : 0u] != 0;    // no code word in the given table: an escape
+                    if (REUSE) inr[v] = inr[v] && has_code(inr[v] ? c : 0u);      // no code word in the given table: an escape
                     code[v] = inr[v] ? c : 0u;
                     // error-bound filter: |x - y| in fp32 is within one rounding of the exact error
                     const float err = fabsf(x[v] - qf[v] * a.ebx2);
@@ -324,7 +331,7 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
                         uint64_t any_e = 0ull;
 #pragma unroll
                         for (int v = 0; v < VEC; ++v) any_e |= em[v];
-                        if (any_e != 0ull && s_len[0] == 0 && lane == 0) atomicOr(&a.ctl->status, (uint32_t)ST_CODEBOOK);
+                        if (any_e != 0ull && !has_code(0u) && lane == 0) atomicOr(&a.ctl->status, (uint32_t)ST_CODEBOOK);
                     }
                     uint64_t vm[VEC];
                     bool verb[VEC];
@@ -417,13 +424,22 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize_rows(QuantArgs a) {
     const uint32_t lane = (uint32_t)lane_id();
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / kWave));
     uint8_t *s_len = reinterpret_cast<uint8_t *>(s_dyn_qr);
+    if (REUSE && (a.ctl->status & (uint32_t)ST_CODEBOOK)) {
+        // k_codebook has refused the given table (the same for every thread): nothing is encoded with it, and the
+        // kernels behind this one find no records and no words
+        if (lane == 0) { a.run_count[blockIdx.x * kWaves + wave] = 0; a.run_words[blockIdx.x * kWaves + wave] = 0; }
+        if (tid < 3u) a.run_count[gridDim.x * kWaves + tid * gridDim.x + blockIdx.x] = 0;
+        return;
+    }
     // REUSE: behind the length table the cached part of the encode table (and a zero entry), then per
     // wavefront the ring of codes (and the word lanes without an element write to) and the assembly buffer
-    uint64_t *s_tbl = reinterpret_cast<uint64_t *>(s_len + ((a.nbins + 7u) & ~7u));
+    // (no length table if the whole encode table is there: FULLWIN)
+    uint64_t *s_tbl = reinterpret_cast<uint64_t *>(s_len + (FULLWIN ? 0u : ((a.nbins + 7u) & ~7u)));
     uint16_t *s_ring = reinterpret_cast<uint16_t *>(s_tbl + a.enc_n + 1u) + wave * (kEncRingSyms + 4u);
     uint32_t *s_asm = reinterpret_cast<uint32_t *>(reinterpret_cast<uint16_t *>(s_tbl + a.enc_n + 1u) + kWaves * (kEncRingSyms + 4u)) + wave * kEncRunBufWords;
     if (REUSE) {
-        for (uint32_t i = tid; i < a.nbins; i += kQuantBlock) s_len[i] = a.reuse_len[i];
+        if (!FULLWIN)
+            for (uint32_t i = tid; i < a.nbins; i += kQuantBlock) s_len[i] = a.reuse_len[i];
         for (uint32_t i = tid; i <= a.enc_n; i += kQuantBlock) s_tbl[i] = (i < a.enc_n) ? a.enc[a.enc_lo + i] : 0ull;
         for (uint32_t i = lane; i < kEncRunBufWords; i += kWave) s_asm[i] = 0;
     } else {
