@@ -184,7 +184,8 @@ void encode_geometry(const comet_ctx *ctx, uint64_t n_chunks, uint32_t *seg_chun
 // vec: columns per lane of the row-walking kernel (2 if W is even and the input is 8-byte aligned).
 // chunk_align: if not 0, every run is a whole number of chunks of that many symbols (single-pass compression).
 struct QuantGeom { bool rows; uint32_t grid, rows_per_wave, rows_per_step, vec; };
-QuantGeom quantize_geometry(const comet_ctx *ctx, comet_shape s, uint64_t n, const void *x, uint32_t elem_bytes = 4, uint32_t chunk_align = 0);
+// nbins: the alphabet (its histogram window decides how many workgroups a compute unit holds at once).
+QuantGeom quantize_geometry(const comet_ctx *ctx, comet_shape s, uint64_t n, const void *x, uint32_t nbins, uint32_t elem_bytes = 4, uint32_t chunk_align = 0);
 
 // Single-pass compression with a given code book: what the quantise kernel needs to encode its own codes.
 struct SinglePass {
@@ -211,7 +212,7 @@ int launch_quantize(comet_ctx *ctx, const void *x, comet_shape s, uint64_t n, fl
     a.win_lo = (nbins - a.win_n) / 2u;
     a.n_tiles = (uint32_t)((n + kQuantTile - 1) / kQuantTile);
     a.codes = codes; a.hist = hist; a.rec = rec; a.rec_cap = rec_cap; a.desc = desc; a.ctl = &ctx->state->ctl;
-    const QuantGeom g = quantize_geometry(ctx, s, n, x, in_type ? 2u : 4u, sp ? sp->chunk_syms : 0u);
+    const QuantGeom g = quantize_geometry(ctx, s, n, x, nbins, in_type ? 2u : 4u, sp ? sp->chunk_syms : 0u);
     const uint32_t grid = g.grid;
     if (g.rows) {
         a.rows_total = (uint32_t)((uint64_t)s.n * s.c * s.h);
@@ -364,7 +365,7 @@ void encode_geometry(const comet_ctx *ctx, uint64_t n_chunks, uint32_t *seg_chun
     *n_seg = (uint32_t)((n_chunks + seg - 1) / seg);
 }
 
-QuantGeom quantize_geometry(const comet_ctx *ctx, comet_shape s, uint64_t n, const void *x, uint32_t elem_bytes, uint32_t chunk_align) {
+QuantGeom quantize_geometry(const comet_ctx *ctx, comet_shape s, uint64_t n, const void *x, uint32_t nbins, uint32_t elem_bytes, uint32_t chunk_align) {
     QuantGeom g{};
     g.vec = 1;
     if (s.w <= kQuantRowsMaxW) {
@@ -383,9 +384,18 @@ QuantGeom quantize_geometry(const comet_ctx *ctx, comet_shape s, uint64_t n, con
             unit = K / std::gcd(K, rows_per_chunk) * rows_per_chunk;
         }
         // a few wavefronts per SIMD, but runs of at least 2048 elements (every run re-reads one row)
-        // (single-pass compression: the encoder's ring and tables in LDS leave room for four workgroups per compute
-        // unit, and a run that has to wait for a place would make the launch take two rounds)
-        const uint64_t want = (uint64_t)ctx->num_cu * 4u * (chunk_align ? kQuantRunsPerSimdSingle : kQuantRunsPerSimd);
+        // All runs should be resident at once: a run that has to wait for a place makes the launch take two rounds.
+        // A workgroup is one wavefront per SIMD; how many a compute unit holds follows from the LDS they need (the
+        // histogram window of a large alphabet leaves room for three; the encoder's ring and tables of the single-pass
+        // compression for four).
+        uint32_t runs_per_simd = chunk_align ? kQuantRunsPerSimdSingle : kQuantRunsPerSimd;
+        if (!chunk_align) {
+            const uint32_t win_n = nbins < kHistWindowMax ? nbins : kHistWindowMax;
+            const size_t lds = (((size_t)win_n << (win_n <= 2048u ? 2u : 0u)) + kQuantBlock) * 4u + kQuantStaticLds;
+            const uint32_t fit = (uint32_t)(kLdsPerCu / lds);
+            if (fit < runs_per_simd) runs_per_simd = fit ? fit : 1u;
+        }
+        const uint64_t want = (uint64_t)ctx->num_cu * 4u * runs_per_simd;
         uint64_t per = (rows_total + want - 1) / want;
         const uint64_t min_rows = (2048u + s.w - 1u) / s.w;
         if (per < min_rows) per = min_rows;
@@ -555,7 +565,7 @@ int compress_impl(comet_ctx *ctx, const void *dev_in, int in_type, comet_shape s
     const uint64_t n_chunks = (n + S - 1) / S;
     uint32_t e_seg, e_grid;
     encode_geometry(ctx, n_chunks, &e_seg, &e_grid);
-    const uint64_t tiles_q = quantize_geometry(ctx, s, n, dev_in, in_type ? 2u : 4u, dev_len ? S : 0u).grid;
+    const uint64_t tiles_q = quantize_geometry(ctx, s, n, dev_in, nbins, in_type ? 2u : 4u, dev_len ? S : 0u).grid;
     const uint64_t tiles_e = e_grid;
 
     Header proto{};
@@ -593,7 +603,7 @@ int compress_impl(comet_ctx *ctx, const void *dev_in, int in_type, comet_shape s
         // Single pass over the input: the code book first (header, length section, encode table), then the quantise
         // kernel encodes its own codes into the work area, then the words of every run move to their place.
         if ((rc = launch_codebook(ctx, b, st))) return rc;
-        const QuantGeom g = quantize_geometry(ctx, s, n, dev_in, 4u, S);
+        const QuantGeom g = quantize_geometry(ctx, s, n, dev_in, nbins, 4u, S);
         SinglePass sp{};
         sp.enc = ctx->enc; sp.chunk_syms = S;
         sp.zero_pair = ctx->zero_chunks ? ((nbins / 2u) << 16) | (nbins / 2u) : 0u;
@@ -1069,7 +1079,7 @@ int comet_stage_quantize(comet_ctx *ctx, const float *dev_in, comet_shape s, flo
         ((uintptr_t)dev_codes & 7u) || ((uintptr_t)dev_records & 7u)) return COMET_ERR_INVALID;
     if (n > ctx->max_elems) return COMET_ERR_NOMEM;
     hipStream_t st = (hipStream_t)stream;
-    const uint64_t tiles_q = quantize_geometry(ctx, s, n, dev_in).grid;
+    const uint64_t tiles_q = quantize_geometry(ctx, s, n, dev_in, nbins).grid;
     const ZeroLayout z = zero_layout(0, nbins, tiles_q, 1);
     if (z.bytes > ctx->zero_cap) return COMET_ERR_NOMEM;
     HIP_TRY(hipMemsetAsync(ctx->zero_region, 0, z.bytes, st));
