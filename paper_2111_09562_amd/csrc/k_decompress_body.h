@@ -84,14 +84,16 @@ __device__ inline int32_t decode_long(uint64_t win, uint32_t start, uint32_t lut
 // the hardware takes modulo 32.
 // C16: the compact table (12 bits, u16 entries (residual << 4) | length), else the
 // general one (11 bits, u32 entries (residual << 8) | length).
-template <bool C16>
+// STAGED: the words lie in the wavefront's LDS region, where a read past the last word is harmless (it stays inside
+// the workgroup's LDS or returns nothing) and needs no clamp.
+template <bool C16, bool STAGED = false>
 struct BitBuf {
     static constexpr int kBits = C16 ? kLut16Bits : kLutBits;
     const uint32_t *words;
     uint32_t last;
     uint32_t hi, lo, nw;        // the word being consumed, the next one, the one after (look-ahead)
     uint32_t pos, wp;           // bits of `hi` already consumed (1 .. 32); index of `nw`
-    __device__ inline uint32_t word(uint32_t i) const { return words[i < last ? i : last]; }
+    __device__ inline uint32_t word(uint32_t i) const { return STAGED ? words[i] : words[i < last ? i : last]; }
     __device__ inline void open(const uint32_t *w, uint32_t last_, uint32_t w0) {
         words = w; last = last_;
         hi = 0u; lo = word(w0); nw = word(w0 + 1);          // (a first word that is used up already)
@@ -173,7 +175,13 @@ struct BitBuf {
         pos = need ? p2 - 32u : p2;
         wp += need ? 1u : 0u;
         nw = word(wp);
-        if (C16) return ((uint32_t)resid_of(e1) << 16) | ((uint32_t)resid_of(e0) & 0xffffu);
+        if (C16) {
+            // the two entries side by side, then both residuals moved down over their lengths at once
+            typedef short s16x2 __attribute__((ext_vector_type(2)));
+            s16x2 two = __builtin_bit_cast(s16x2, __builtin_amdgcn_perm(e1, e0, 0x05040100u));
+            two >>= (short)4;
+            return __builtin_bit_cast(uint32_t, two);
+        }
         return __builtin_amdgcn_perm(e1, e0, 0x06050201u);      // bytes 1, 2 of each entry: the two residuals
     }
     // The same pair when some lane has a code longer than the table.  Such a code is resolved through the
@@ -955,8 +963,8 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
                 w0 = w0 < last ? w0 : last;
                 // (one call per address space of the words, so that the reader's loads are LDS or global
                 // instructions, not generic ones)
-                auto run = [&](auto c16_tag, auto wsrc) {
-                    BitBuf<decltype(c16_tag)::value> bb;
+                auto run = [&](auto c16_tag, auto staged_tag, auto wsrc) {
+                    BitBuf<decltype(c16_tag)::value, decltype(staged_tag)::value> bb;
                     bb.open(wsrc, last, w0);
 #pragma nounroll
                     for (uint32_t j4 = 0; j4 < 4u; ++j4) {
@@ -971,10 +979,10 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
                 };
                 if (c < c1 && n_words) {
                     if (all_staged) {
-                        if (c16) run(std::true_type{}, strip); else run(std::false_type{}, strip);
+                        if (c16) run(std::true_type{}, std::true_type{}, strip); else run(std::false_type{}, std::true_type{}, strip);
                     } else {
                         const uint32_t *gsrc = payload + w_begin;
-                        if (c16) run(std::true_type{}, gsrc); else run(std::false_type{}, gsrc);
+                        if (c16) run(std::true_type{}, std::false_type{}, gsrc); else run(std::false_type{}, std::false_type{}, gsrc);
                     }
                 }
                 // Container version 2: a chunk without words is residual 0 throughout.  Its lane has read
@@ -1123,8 +1131,10 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
                         const uint32_t r = (MODE == 2 ? r_first : ra) + ts;   // my row inside the strip
 #pragma unroll
                         for (int s = 0; s < NSEG; ++s) {
-                            const bool on = colw[s] != kNoElem && r >= lastseg_l && r < rb;
-                            const uint32_t raw = lds_read(on ? r * W + colw[s] : 0u);
+                            // (one slot: the loop's bounds are the rows that count, and what a lane without a column
+                            // adds up is dropped behind the loop)
+                            const bool on = MODE == 2 ? true : (colw[s] != kNoElem && r >= lastseg_l && r < rb);
+                            const uint32_t raw = lds_read((MODE == 2 ? colw[s] != kNoElem : on) ? r * W + colw[s] : 0u);
                             if (VEC == 2) {
                                 dsum[s][0] += on ? (int32_t)(int16_t)(raw & 0xffffu) : 0;
                                 dsum[s][VEC - 1] += on ? (int32_t)raw >> 16 : 0;
@@ -1132,6 +1142,12 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
                                 dsum[s][0] += on ? (int32_t)raw : 0;
                             }
                         }
+                    }
+                    if (MODE == 2) {
+#pragma unroll
+                        for (int s = 0; s < NSEG; ++s)
+#pragma unroll
+                            for (int v = 0; v < VEC; ++v) dsum[s][v] = colw[s] != kNoElem ? dsum[s][v] : 0;
                     }
                     // prefix over the columns, on top of the escapes' share
                     int32_t carry = 0;
