@@ -1130,16 +1130,18 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
                     for (int s = 0; s < NSEG; ++s)
 #pragma unroll
                         for (int v = 0; v < VEC; ++v) dsum[s][v] = 0;
+                    // (MODE 0 / 1: a slot's last plane starts in its last H rows at the earliest, so every slot walks up
+                    // from its own last row, H rows at most)
                     const uint32_t r_first = MODE == 2 ? lastseg : 0u;       // MODE 2: uniform
-                    const uint32_t r_count = MODE == 2 ? rows - lastseg : rps;
+                    const uint32_t r_count = MODE == 2 ? rows - lastseg : (rps < H ? rps : H);
 #pragma unroll 4
                     for (uint32_t ts = 0; ts < r_count; ++ts) {
-                        const uint32_t r = (MODE == 2 ? r_first : ra) + ts;   // my row inside the strip
+                        const uint32_t r = MODE == 2 ? r_first + ts : rb - 1u - ts;   // my row inside the strip
 #pragma unroll
                         for (int s = 0; s < NSEG; ++s) {
                             // (one slot: the loop's bounds are the rows that count, and what a lane without a column
                             // adds up is dropped behind the loop)
-                            const bool on = MODE == 2 ? true : (colw[s] != kNoElem && r >= lastseg_l && r < rb);
+                            const bool on = MODE == 2 ? true : (colw[s] != kNoElem && ts < rb - ra && r >= lastseg_l);
                             const uint32_t raw = lds_read((MODE == 2 ? colw[s] != kNoElem : on) ? r * W + colw[s] : 0u);
                             if (VEC == 2) {
                                 dsum[s][0] += on ? (int32_t)(int16_t)(raw & 0xffffu) : 0;
@@ -1199,6 +1201,32 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
                     }
                     wave_lds_fence();                             // all sums read: the area may take the hand-over
                 }
+                // What I hand on is my last plane's column sums down to my last row.  If that plane starts inside my
+                // strip it does not depend on what I receive, and goes out before I wait: otherwise every strip of the
+                // segment would wait for the one before it to have waited.
+                auto hand_over = [&](const int32_t (&qq)[NSEG][VEC]) {
+                    const bool last_slot = MODE == 2 || (rb == rows && rb > ra);
+#pragma unroll
+                    for (int s = 0; s < NSEG; ++s)
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v)
+                            if (colw[s] != kNoElem && last_slot)
+                                s_carry[wave][COOP ? (colw[s] + (uint32_t)v) & (kFuCarryW - 1u) : 0u] = (int32_t)((uint32_t)tcol[s][v] + (fresh_l ? 0u : (uint32_t)qq[s][v]));
+                    wave_lds_fence();
+                    if (lane == 0) __hip_atomic_store(&s_ready[wave], j + 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    published = j + 1u;
+                };
+                const bool early = hand_on && fresh;
+                if (early) {
+                    // (a slot whose last plane started in an earlier slot of this strip has met that slot on its way back:
+                    // its sums above are those of the slots in between)
+                    int32_t q0[NSEG][VEC];
+#pragma unroll
+                    for (int s = 0; s < NSEG; ++s)
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) q0[s][v] = (MODE == 2 || ha == 0u) ? 0 : acc[v];
+                    hand_over(q0);
+                }
                 // what the strip received
                 int32_t cin[NSEG][VEC];
 #pragma unroll
@@ -1222,20 +1250,8 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
                         if (MODE == 2) q[s][v] = cin[s][v];
                         else q[s][v] = ha != 0u ? (int32_t)((uint32_t)acc[v] + (reached ? 0u : (uint32_t)cin[s][v])) : 0;
                     }
-                if (hand_on) {
-                    const bool last_slot = MODE == 2 || (rb == rows && rb > ra);
-#pragma unroll
-                    for (int s = 0; s < NSEG; ++s)
-#pragma unroll
-                        for (int v = 0; v < VEC; ++v)
-                            if (colw[s] != kNoElem && last_slot)
-                                s_carry[wave][COOP ? (colw[s] + (uint32_t)v) & (kFuCarryW - 1u) : 0u] = (int32_t)((uint32_t)tcol[s][v] + (fresh_l ? 0u : (uint32_t)q[s][v]));
-                    wave_lds_fence();
-                    if (lane == 0) __hip_atomic_store(&s_ready[wave], j + 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
-                    published = j + 1u;
-                } else {
-                    published = 0u;
-                }
+                if (hand_on && !early) hand_over(q);
+                if (!hand_on) published = 0u;
             }
 
             // ---- 4. scan the rows out of LDS ----

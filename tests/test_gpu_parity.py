@@ -405,6 +405,9 @@ def test_which_kernels_decompress(comet, oracle):
     (4, 40, 90, 44),       # 32-lane halves: two runs of rows side by side, plane starts inside a run
     (6, 300, 40, 12),      # narrow planes: eight runs of rows side by side, several planes per run
     (2, 2000, 5, 3),       # tiny planes: many planes per run, rows of three lanes
+    (8, 4000, 7, 7),       # ... strips whose rows do not divide evenly among the eight runs (a shorter last run), two strips per segment
+    (3, 500, 14, 14),      # ... the same with two columns per lane
+    (5, 700, 7, 7),        # ... and with a single short strip
     (1, 3, 1500, 128),     # the widest plane that goes this way
     (2, 3, 300, 130),      # just beyond it: a segment per wavefront, sums stay in registers
     (1, 2, 700, 224),      # four segments of 64 lanes... two columns per lane, planes much larger than a strip
