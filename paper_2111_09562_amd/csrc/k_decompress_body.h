@@ -1032,7 +1032,7 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
                 // (my strip before this one ended at rpos and this one starts a few strips later: its first record is
                 // nearly always among the next few thousand, which two rounds of probes find; else all that is left is searched)
                 {
-                    const uint32_t near = (n_rec - rpos > 65u * 64u) ? rpos + 65u * 64u : n_rec;
+                    const uint32_t near = (j != gw && n_rec - rpos > 65u * 64u) ? rpos + 65u * 64u : n_rec;     // (my first strip: anywhere)
                     r_begin = rec_lower_bound(rec, rpos, near, 2u * s_a, lane);
                     if (r_begin == near && near < n_rec) r_begin = rec_lower_bound(rec, near, n_rec, 2u * s_a, lane);
                 }
