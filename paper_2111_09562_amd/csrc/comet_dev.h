@@ -38,6 +38,8 @@ struct Control {
     uint64_t total_bytes;
     uint32_t n_active;
     uint32_t max_len;
+    uint32_t enc_in_window;  // k_codebook: every symbol with a code word, but for the escape symbol, lies in the part of the encode table the encoders cache in LDS
+    uint32_t pad_;
 };
 
 // Orders the LDS accesses of the lanes of one wavefront (writes before, reads after).  Only the

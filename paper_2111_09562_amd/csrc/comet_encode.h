@@ -8,24 +8,32 @@ namespace comet {
 
 namespace {
 
-// FULL: the whole table is in LDS.  Keeping global loads out of that variant matters: a load
-// inside the loop would make every iteration wait for the stores of the previous one.
-template <bool FULL>
+// The encode table as the encoders see it.  TM 1 (or true): the whole table is in LDS.  Keeping global loads out
+// of that variant matters: a load inside the loop would make every iteration wait for the stores of the previous
+// one.  TM 0 (or false): the entries [lo, lo + n) are in LDS, the others are looked up in global memory.  TM 2: as
+// TM 0, but every symbol that has a code word lies in [lo, lo + n), but for the escape symbol 0, whose entry is kept
+// behind the cached ones (k_codebook says whether that holds: Control::enc_in_window); again no global loads.
+template <int TM>
 struct TableView {
     const uint64_t *lds;
     const uint64_t *glob;
     uint32_t lo, n, nbins;
-    // A code outside the alphabet cannot come from the quantise kernel; it reads the zero entry
-    // that follows the cached part (length 0: the symbol contributes no bits).
+    // A code outside the alphabet cannot come from the quantise kernel; it reads the entry that follows the
+    // cached part: zero (length 0: the symbol contributes no bits), in TM 2 the escape symbol's.
+    __device__ inline uint32_t index(uint32_t code) const {
+        if (TM == 1) return code < nbins ? code : nbins;
+        const uint32_t i = code - lo;                 // (TM 2; a code below lo wraps to a large number)
+        return i < n ? i : n;
+    }
     __device__ inline uint64_t full(uint32_t code) const {
-        if (FULL) return lds[code < nbins ? code : nbins];
+        if (TM != 0) return lds[index(code)];
         if (code >= nbins) return 0ull;
         const uint32_t i = code - lo;
         return (i < n) ? lds[i] : glob[code];
     }
     // length only
     __device__ inline uint32_t length(uint32_t code) const {
-        if (FULL) return reinterpret_cast<const uint32_t *>(lds)[2u * (code < nbins ? code : nbins)] & 63u;
+        if (TM != 0) return reinterpret_cast<const uint32_t *>(lds)[2u * index(code)] & 63u;
         return (uint32_t)full(code) & 63u;
     }
 };

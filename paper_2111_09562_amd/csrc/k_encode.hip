@@ -70,8 +70,8 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_count(EncodeArgs a) {
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = (uint32_t)lane_id();
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / kWave));   // a scalar: what derives from it stays scalar
-    for (uint32_t i = tid; i <= a.tbl_n; i += kEncBlock) s_tbl[i] = (i < a.tbl_n) ? a.enc[a.tbl_lo + i] : 0ull;
-    TableView<FULLTBL> tbl{s_tbl, a.enc, a.tbl_lo, a.tbl_n, a.nbins};
+    // (behind the cached entries: a zero entry, or the escape symbol's if part of the table is cached)
+    for (uint32_t i = tid; i <= a.tbl_n; i += kEncBlock) s_tbl[i] = (i < a.tbl_n) ? a.enc[a.tbl_lo + i] : (FULLTBL ? 0ull : a.enc[0]);
     __syncthreads();
 
     const uint32_t seg = blockIdx.x;
@@ -81,6 +81,8 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_count(EncodeArgs a) {
     const uint32_t steps = (nc + CPS - 1u) / CPS;
     const uint32_t g = lane / LPC;                   // my chunk inside a step
 
+    // The loop over the steps, once per way of looking a code up (the choice is the same for every thread).
+    auto sweep = [&](auto tbl) {
     // kEncUnroll steps per iteration, their loads issued together
     for (uint32_t st0 = wave * kEncUnroll; st0 < steps; st0 += (kEncBlock / kWave) * kEncUnroll) {
         uint2 v[kEncUnroll];
@@ -107,6 +109,10 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_count(EncodeArgs a) {
             if ((lane % LPC) == LPC - 1 && c0 + g < c_hi) s_cnt[c0 + g - c_lo] = (incl + 31u) >> 5;
         }
     }
+    };
+    if (FULLTBL) sweep(TableView<1>{s_tbl, a.enc, a.tbl_lo, a.tbl_n, a.nbins});
+    else if (a.ctl->enc_in_window) sweep(TableView<2>{s_tbl, a.enc, a.tbl_lo, a.tbl_n, a.nbins});
+    else sweep(TableView<0>{s_tbl, a.enc, a.tbl_lo, a.tbl_n, a.nbins});
     __syncthreads();
 
     // counts -> segment-relative exclusive offsets, kEncBlock consecutive chunks at a time
@@ -135,8 +141,7 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_pack(EncodeArgs a) {
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = (uint32_t)lane_id();
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / kWave));   // a scalar: what derives from it stays scalar
-    for (uint32_t i = tid; i <= a.tbl_n; i += kEncBlock) s_tbl[i] = (i < a.tbl_n) ? a.enc[a.tbl_lo + i] : 0ull;
-    TableView<FULLTBL> tbl{s_tbl, a.enc, a.tbl_lo, a.tbl_n, a.nbins};
+    for (uint32_t i = tid; i <= a.tbl_n; i += kEncBlock) s_tbl[i] = (i < a.tbl_n) ? a.enc[a.tbl_lo + i] : (FULLTBL ? 0ull : a.enc[0]);
     uint32_t *buf = s_buf + wave * kEncBufWords;
     for (uint32_t i = lane; i < kEncBufWords; i += kWave) buf[i] = 0;
 
@@ -215,6 +220,8 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_pack(EncodeArgs a) {
         wave_lds_fence();
     };
     constexpr uint32_t kStride = (kEncBlock / kWave) * kEncUnroll;
+    // The loop over the steps, once per way of looking a code up (the choice is the same for every thread).
+    auto sweep = [&](auto tbl) {
     uint32_t st0 = wave * kEncUnroll;
     uint2 v_next[kEncUnroll];
     uint32_t off_next = 0;
@@ -288,6 +295,10 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_pack(EncodeArgs a) {
         }
         flush(off0, wpos);
     }
+    };
+    if (FULLTBL) sweep(TableView<1>{s_tbl, a.enc, a.tbl_lo, a.tbl_n, a.nbins});
+    else if (a.ctl->enc_in_window) sweep(TableView<2>{s_tbl, a.enc, a.tbl_lo, a.tbl_n, a.nbins});
+    else sweep(TableView<0>{s_tbl, a.enc, a.tbl_lo, a.tbl_n, a.nbins});
     // chunk offsets become absolute (every wavefront has consumed the relative ones of its steps
     // only after this barrier)
     __syncthreads();
