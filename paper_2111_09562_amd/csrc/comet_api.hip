@@ -224,8 +224,8 @@ int launch_quantize(comet_ctx *ctx, const void *x, comet_shape s, uint64_t n, fl
         a.hist_parts = hist_parts;
         a.hist_copies = hist_copies(nbins);
         a.hist_shift = a.win_n <= 2048u ? 2u : 0u;            // four copies while they fit 32 KB
-        const size_t lds = (((size_t)a.win_n << a.hist_shift) + kQuantBlock) * 4u;
         const bool full = a.win_n == nbins;
+        const size_t lds = (((size_t)a.win_n << a.hist_shift) + kQuantBlock) * 4u + (full ? 0u : (size_t)(kQuantBlock / kWave) * kQuantOowList * 2u);
 #define COMET_LAUNCH_QR_IN(VEC, NSEG, MULTI, IN)                                                                       \
         do {                                                                                                           \
             {                                                                                                          \
@@ -391,7 +391,8 @@ QuantGeom quantize_geometry(const comet_ctx *ctx, comet_shape s, uint64_t n, con
         uint32_t runs_per_simd = chunk_align ? kQuantRunsPerSimdSingle : kQuantRunsPerSimd;
         if (!chunk_align) {
             const uint32_t win_n = nbins < kHistWindowMax ? nbins : kHistWindowMax;
-            const size_t lds = (((size_t)win_n << (win_n <= 2048u ? 2u : 0u)) + kQuantBlock) * 4u + kQuantStaticLds;
+            const size_t lds = (((size_t)win_n << (win_n <= 2048u ? 2u : 0u)) + kQuantBlock) * 4u + kQuantStaticLds +
+                               (win_n < nbins ? (size_t)(kQuantBlock / kWave) * kQuantOowList * 2u : 0u);
             const uint32_t fit = (uint32_t)(kLdsPerCu / lds);
             if (fit < runs_per_simd) runs_per_simd = fit ? fit : 1u;
         }

@@ -53,6 +53,7 @@ constexpr uint32_t kQuantRowsMaxW = 512;  // widest plane of the row-walking ker
 constexpr uint32_t kQuantRecRun = 768;    // outlier records staged per run (one run of rows per wavefront)
 constexpr uint32_t kQuantRecLds2 = 256;   // records a wavefront buffers in LDS before it writes them to the staging area in bulk
 constexpr uint32_t kQuantRunsPerSimd = 5; // runs the launch aims at, per SIMD
+constexpr uint32_t kQuantOowList = 512;   // codes outside the LDS histogram window a wavefront lists before it adds them to the global histogram
 constexpr uint32_t kQuantStaticLds = 8448; // static LDS of k_quantize_rows (the record buffers of its four wavefronts and a few words), rounded up
 constexpr uint32_t kLdsPerCu = 160u * 1024u;
 constexpr uint32_t kQuantRunsPerSimdSingle = 4;   //   ... of the single-pass compression (all of them resident at once)

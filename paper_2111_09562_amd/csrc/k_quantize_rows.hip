@@ -80,8 +80,10 @@ template <int IN> __device__ inline float load_elem(const void *x, size_t i) {
 
 struct SweepCounts {
     uint32_t nnz_lane = 0;      // per lane: non-zero inputs
-    uint32_t oow_lane = 0;      // per lane: codes counted straight into the global histogram
+    uint32_t oow = 0;           // wavefront-uniform: codes outside the LDS window (counted in the global histogram)
     uint32_t vrec = 0;          // wavefront-uniform: verbatim records
+    uint16_t *oow_list = nullptr;   // LDS, kQuantOowList entries of this wavefront: such codes on their way to the global histogram
+    uint32_t oow_held = 0;      // wavefront-uniform: entries of the list in use
 };
 
 // One sweep of a wavefront over rows [row_lo, row_hi).  PASS 0: everything (codes, histogram,
@@ -213,6 +215,12 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
         cur += buffered;
         buffered = 0;
     };
+    auto flush_oow = [&]() {                                     // the listed codes -> global histogram
+        wave_lds_fence();
+        for (uint32_t i = lane; i < cnt.oow_held; i += kWave) atomicAdd(&a.hist[cnt.oow_list[i]], 1u);
+        wave_lds_fence();
+        cnt.oow_held = 0;
+    };
     uint16_t *ring_w = (PASS == 0 && REUSE) ? const_cast<uint16_t *>(enc->ring) : nullptr;
     // REUSE: does the given table have a code word for this code?  From the length table; the single-pass sweep with
     // the whole encode table in LDS reads that instead (an entry is 0 for a symbol without a code word), which saves
@@ -308,7 +316,18 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
                             const uint32_t bin = code[v] - a.win_lo;
                             const bool inwin = bin < a.win_n;
                             atomicAdd(&s_hist[(count && inwin) ? (bin << a.hist_shift) + hist_sub : hist_dummy], 1u);
-                            if (count && !inwin) { atomicAdd(&a.hist[code[v]], 1u); ++cnt.oow_lane; }
+                            // A code outside the window goes to a list in LDS and from there, in bulk, to the global
+                            // histogram: an atomic on global memory in this loop would make every step wait for all
+                            // loads in flight.
+                            const uint64_t om = wave_ballot(count && !inwin);
+                            if (om != 0ull) {                   // uniform
+                                const uint32_t n_new = (uint32_t)__popcll(om);
+                                if (cnt.oow_held + n_new > kQuantOowList) flush_oow();
+                                if (count && !inwin)
+                                    cnt.oow_list[cnt.oow_held + __builtin_amdgcn_mbcnt_hi((uint32_t)(om >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)om, 0u))] = (uint16_t)code[v];
+                                cnt.oow_held += n_new;
+                                cnt.oow += n_new;
+                            }
                         }
                     }
                 }
@@ -395,6 +414,7 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
     }
     drain(n_el, true);
     flush_records();
+    if (PASS == 0 && !REUSE && !FULLWIN && cnt.oow_held) flush_oow();
     return cur;
 }
 
@@ -451,6 +471,8 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize_rows(QuantArgs a) {
     uint32_t row_lo, row_hi;
     run_rows(a, run, &row_lo, &row_hi);
     SweepCounts cnt;
+    // (a window that does not hold every bin: behind it and the threads' dummy words, a list per wavefront)
+    if (!REUSE && !FULLWIN) cnt.oow_list = reinterpret_cast<uint16_t *>(s_hist + (a.win_n << a.hist_shift) + kQuantBlock) + wave * kQuantOowList;
     uint32_t my_records = 0;
     RunEncoder enc;
     TableView<FULLWIN> tbl{s_tbl, a.enc, a.enc_lo, a.enc_n, a.nbins};
@@ -493,7 +515,7 @@ __global__ __launch_bounds__(kQuantBlock) void k_quantize_rows(QuantArgs a) {
     }
     if (REUSE) return;                              // no histogram (uniform: every thread has passed the barrier above)
     uint32_t *part = a.hist_parts + (size_t)(blockIdx.x % a.hist_copies) * a.nbins;
-    uint64_t counted = FULLWIN ? 0ull : (uint64_t)cnt.oow_lane;
+    uint64_t counted = (FULLWIN || lane != 0u) ? 0ull : (uint64_t)cnt.oow;
     for (uint32_t i = tid; i < a.win_n; i += kQuantBlock) {
         uint32_t v = 0;
         for (uint32_t k = 0; k < (1u << a.hist_shift); ++k) v += s_hist[(i << a.hist_shift) + k];
