@@ -22,6 +22,8 @@
 // header: the payload size it computes decides everything the header still lacks.
 // The encode table ((code << 6) | length per symbol) is cached in LDS for the
 // bins around the centre; other symbols are looked up in global memory.
+#include <type_traits>
+
 #include "comet_kernels.h"
 #include "comet_encode.h"
 
@@ -220,8 +222,10 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_pack(EncodeArgs a) {
         wave_lds_fence();
     };
     constexpr uint32_t kStride = (kEncBlock / kWave) * kEncUnroll;
-    // The loop over the steps, once per way of looking a code up (the choice is the same for every thread).
-    auto sweep = [&](auto tbl) {
+    // The loop over the steps, once per way of looking a code up (the choice is the same for every thread), and once
+    // more for the tensor's last segment: everywhere else every step has its 256 symbols, and the loop tests nothing.
+    auto sweep = [&](auto tbl, auto tail_tag) {
+    constexpr bool TAIL = decltype(tail_tag)::value;
     uint32_t st0 = wave * kEncUnroll;
     uint2 v_next[kEncUnroll];
     uint32_t off_next = 0;
@@ -236,15 +240,18 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_pack(EncodeArgs a) {
 #pragma unroll
         for (uint32_t u = 0; u < kEncUnroll; ++u) {
             if (st0 + u >= steps) break;
-            const uint64_t e0 = (uint64_t)(c_lo + (st0 + u) * CPS) * S;    // first symbol of the step (uniform)
-            const uint32_t left = (e0 + 256u <= a.n) ? 256u : ((a.n > e0) ? (uint32_t)(a.n - e0) : 0u);
+            uint32_t left = 256u;
+            if (TAIL) {
+                const uint64_t e0 = (uint64_t)(c_lo + (st0 + u) * CPS) * S;    // first symbol of the step (uniform)
+                left = (e0 + 256u <= a.n) ? 256u : ((a.n > e0) ? (uint32_t)(a.n - e0) : 0u);
+            }
             uint64_t cw[4];
             uint32_t len[4], bits = 0;
             uint64_t acc = 0;                                // my code words one after the other (if they fit 64 bits)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 uint64_t e = tbl.full(code_of(v[u], j));
-                if (__builtin_expect(left < 256u, 0)) {      // wavefront-uniform; only the last step of the tensor
+                if (TAIL && __builtin_expect(left < 256u, 0)) {      // wavefront-uniform; only the last step of the tensor
                     asm volatile("" ::: "memory");           // keep this a branch: as selects it would cost every step
                     e = (lane * 4u + (uint32_t)j < left) ? e : 0ull;
                 }
@@ -296,9 +303,13 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_pack(EncodeArgs a) {
         flush(off0, wpos);
     }
     };
-    if (FULLTBL) sweep(TableView<1>{s_tbl, a.enc, a.tbl_lo, a.tbl_n, a.nbins});
-    else if (a.ctl->enc_in_window) sweep(TableView<2>{s_tbl, a.enc, a.tbl_lo, a.tbl_n, a.nbins});
-    else sweep(TableView<0>{s_tbl, a.enc, a.tbl_lo, a.tbl_n, a.nbins});
+    const bool whole = (uint64_t)c_hi * S <= a.n;              // every chunk of my segment has all its symbols
+    auto sweep_with = [&](auto tbl) {
+        if (whole) sweep(tbl, std::false_type{}); else sweep(tbl, std::true_type{});
+    };
+    if (FULLTBL) sweep_with(TableView<1>{s_tbl, a.enc, a.tbl_lo, a.tbl_n, a.nbins});
+    else if (a.ctl->enc_in_window) sweep_with(TableView<2>{s_tbl, a.enc, a.tbl_lo, a.tbl_n, a.nbins});
+    else sweep_with(TableView<0>{s_tbl, a.enc, a.tbl_lo, a.tbl_n, a.nbins});
     // chunk offsets become absolute (every wavefront has consumed the relative ones of its steps
     // only after this barrier)
     __syncthreads();
