@@ -783,9 +783,9 @@ int decompress_impl(const DecompWs &ws, const void *dev_in, uint64_t bytes, come
         f.out = dev_out; f.ctl = &ws.state->ctl;
         const int mode = lpr <= 16u ? 0 : (lpr <= 32u ? 1 : 2);
         const int nseg = lpr <= 64u ? 1 : (lpr <= 128u ? 2 : (lpr <= 256u ? 4 : 8));
-        // planes of at most kFuCarryW columns: one segment of planes per workgroup, its strips dealt to all its
+        // planes of at most 128 lanes per row: one segment of planes per workgroup, its strips dealt to all its
         // wavefronts; wider planes: units of whole planes per wavefront
-        const bool coop = nseg == 1 || (nseg == 2 && vec == 1u);
+        const bool coop = nseg <= 2;
         FusedGeom fg = fused_geometry(ws.num_cu, s);
         if (coop) {
             const uint64_t planes = (uint64_t)s.n * s.c;

@@ -268,10 +268,10 @@ template <int NSEG, int MODE, int OUT = 0, int VEC = 1> __global__ void k_scan_s
 constexpr int kFuWaves = 16;                          // wavefronts per workgroup, each working on its own; one workgroup per CU
 constexpr int kFuBlock = kFuWaves * kWave;
 constexpr uint32_t kFuStripWords = 64u * 32u;         // a strip's residuals, element after element (64 chunks of 64 int16); before that, the words of its chunks
-constexpr uint32_t kFuEscEntries = 64u;               // values of a strip's escaped residuals kept in LDS
+constexpr uint32_t kFuEscEntries = 32u;               // values of a strip's escaped residuals kept in LDS
 constexpr uint32_t kFuRegionWords = kFuStripWords + kFuEscEntries;
 constexpr uint32_t kFuPrefetch = 20u;                 // words per lane (of a strip's chunks) loaded while the strip before is scanned
-constexpr uint32_t kFuCarryW = 128u;                  // widest plane whose strips are dealt to all wavefronts of a workgroup (column sums handed on through LDS)
+constexpr uint32_t kFuCarryW = 128u;                  // widest plane whose strips are dealt to all wavefronts of a workgroup (column sums handed on through LDS), one column per lane; twice that with two
 
 struct FuArgs {
     const uint8_t *container;

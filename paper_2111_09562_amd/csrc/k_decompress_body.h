@@ -735,7 +735,8 @@ __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
 template <int NSEG, int MODE, int OUT, int VEC>
 __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
     constexpr uint32_t OS = OUT ? 2u : 4u;                   // bytes per output element
-    constexpr bool COOP = NSEG == 1 || (NSEG == 2 && VEC == 1);     // planes of at most kFuCarryW columns
+    constexpr bool COOP = NSEG <= 2;                                // planes of at most 128 lanes per row
+    constexpr uint32_t CW = (NSEG == 2 && VEC == 2) ? 2u * kFuCarryW : kFuCarryW;   // columns of the widest of them
     constexpr uint32_t NWG = COOP ? (uint32_t)kFuWaves : 1u;        // wavefronts that share a segment
     extern __shared__ uint32_t s_dyn_ds[];                  // per wavefront: strip (kFuStripWords), escape values (kFuEscEntries)
     __shared__ uint32_t s_lut[kLutSize];
@@ -743,7 +744,7 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
     __shared__ uint64_t s_limit[65];
     __shared__ uint64_t s_first[65];
     __shared__ uint32_t s_findex[65];
-    __shared__ int32_t s_carry[COOP ? kFuWaves : 1][COOP ? kFuCarryW : 1];   // column sums a strip hands to the next one
+    __shared__ int32_t s_carry[COOP ? kFuWaves : 1][COOP ? CW : 1];   // column sums a strip hands to the next one
     __shared__ uint32_t s_ready[kFuWaves], s_acked[kFuWaves];               // strip number + 1 of the slot's content / of its last reader
     __shared__ uint32_t s_cnt[(MODE != 2) ? kFuWaves : 1][64];                // MODE 0 / 1: escapes per slot of lanes
 
@@ -948,7 +949,7 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
             // my exchange area: free once the reader of what I handed on last has taken it; cleared for the escapes' share
             if (exchange) {
                 if (published) wait_for(&s_acked[wave], published);
-                for (uint32_t i = lane; i < kFuCarryW; i += kWave) s_carry[wave][COOP ? i : 0u] = 0;
+                for (uint32_t i = lane; i < CW; i += kWave) s_carry[wave][COOP ? i : 0u] = 0;
                 if (MODE != 2) s_cnt[wave][lane] = 0u;
             }
             wave_lds_fence();
@@ -1083,7 +1084,7 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
                                 if (!c16) atomicAdd(&s_cnt[wave][ke & 63u], 1u);
                             }
                             if (r >= ls && (MODE != 2 || hand_on))
-                                atomicAdd(&s_carry[wave][COOP ? (ke * W + cw) & (kFuCarryW - 1u) : 0u], (int32_t)(val - (uint32_t)held));
+                                atomicAdd(&s_carry[wave][COOP ? (ke * W + cw) & (CW - 1u) : 0u], (int32_t)(val - (uint32_t)held));
                         }
                     }
                     n_esc += (uint32_t)__popcll(esc_mask);
@@ -1164,7 +1165,7 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
                         int32_t dd[VEC];
 #pragma unroll
                         for (int v = 0; v < VEC; ++v)
-                            dd[v] = colw[s] != kNoElem ? (int32_t)((uint32_t)dsum[s][v] + (uint32_t)s_carry[wave][COOP ? (slot * W + colw[s] + (uint32_t)v) & (kFuCarryW - 1u) : 0u]) : 0;
+                            dd[v] = colw[s] != kNoElem ? (int32_t)((uint32_t)dsum[s][v] + (uint32_t)s_carry[wave][COOP ? (slot * W + colw[s] + (uint32_t)v) & (CW - 1u) : 0u]) : 0;
                         int32_t mine = dd[0];
 #pragma unroll
                         for (int v = 1; v < VEC; ++v) mine = (int32_t)((uint32_t)mine + (uint32_t)dd[v]);
@@ -1185,7 +1186,7 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
                 if (MODE != 2) {
 #pragma unroll
                     for (int v = 0; v < VEC; ++v)
-                        if (colw[0] != kNoElem) s_carry[wave][COOP ? (slot * W + colw[0] + (uint32_t)v) & (kFuCarryW - 1u) : 0u] = tcol[0][v];
+                        if (colw[0] != kNoElem) s_carry[wave][COOP ? (slot * W + colw[0] + (uint32_t)v) & (CW - 1u) : 0u] = tcol[0][v];
                     wave_lds_fence();
                     for (uint32_t dd = 1; dd < K; ++dd) {         // slots in front of mine, nearest first
                         const bool take = slot >= dd && !reached && colw[0] != kNoElem;
@@ -1194,7 +1195,7 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
                         slot_rows(kk, r0, r1, fr, ls);
 #pragma unroll
                         for (int v = 0; v < VEC; ++v) {
-                            const int32_t tv = s_carry[wave][COOP ? (kk * W + (take ? colw[0] : 0u) + (uint32_t)v) & (kFuCarryW - 1u) : 0u];
+                            const int32_t tv = s_carry[wave][COOP ? (kk * W + (take ? colw[0] : 0u) + (uint32_t)v) & (CW - 1u) : 0u];
                             acc[v] = take ? (int32_t)((uint32_t)acc[v] + (uint32_t)tv) : acc[v];
                         }
                         reached = reached || (take && fr);
@@ -1211,7 +1212,7 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
 #pragma unroll
                         for (int v = 0; v < VEC; ++v)
                             if (colw[s] != kNoElem && last_slot)
-                                s_carry[wave][COOP ? (colw[s] + (uint32_t)v) & (kFuCarryW - 1u) : 0u] = (int32_t)((uint32_t)tcol[s][v] + (fresh_l ? 0u : (uint32_t)qq[s][v]));
+                                s_carry[wave][COOP ? (colw[s] + (uint32_t)v) & (CW - 1u) : 0u] = (int32_t)((uint32_t)tcol[s][v] + (fresh_l ? 0u : (uint32_t)qq[s][v]));
                     wave_lds_fence();
                     if (lane == 0) __hip_atomic_store(&s_ready[wave], j + 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
                     published = j + 1u;
@@ -1238,7 +1239,7 @@ __global__ __launch_bounds__(kFuBlock) void k_decode_scan(FuArgs a) {
 #pragma unroll
                     for (int s = 0; s < NSEG; ++s)
 #pragma unroll
-                        for (int v = 0; v < VEC; ++v) cin[s][v] = colw[s] != kNoElem ? s_carry[prev_w][COOP ? (colw[s] + (uint32_t)v) & (kFuCarryW - 1u) : 0u] : 0;
+                        for (int v = 0; v < VEC; ++v) cin[s][v] = colw[s] != kNoElem ? s_carry[prev_w][COOP ? (colw[s] + (uint32_t)v) & (CW - 1u) : 0u] : 0;
                     wave_lds_fence();
                     if (lane == 0) __hip_atomic_store(&s_acked[prev_w], j, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
                 }

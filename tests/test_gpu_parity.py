@@ -409,7 +409,10 @@ def test_which_kernels_decompress(comet, oracle):
     (3, 500, 14, 14),      # ... the same with two columns per lane
     (5, 700, 7, 7),        # ... and with a single short strip
     (1, 3, 1500, 128),     # the widest plane that goes this way
-    (2, 3, 300, 130),      # just beyond it: a segment per wavefront, sums stay in registers
+    (2, 3, 300, 130),      # just beyond it with two columns per lane: two segments of 64 lanes, still dealt to all wavefronts
+    (3, 5, 60, 256),       # the widest plane that goes this way with two columns per lane
+    (2, 3, 150, 129),      # one column per lane beyond 128 columns: a segment per wavefront, sums stay in registers
+    (1, 2, 200, 258),      # the same with two columns per lane
     (1, 2, 700, 224),      # four segments of 64 lanes... two columns per lane, planes much larger than a strip
 ])
 def test_fused_decompression_strips(comet, oracle, shape):
