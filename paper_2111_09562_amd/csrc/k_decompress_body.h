@@ -720,8 +720,8 @@ __global__ __launch_bounds__(kDsBlock) void k_scan_store(DsArgs a) {
 //      handed from step to step through the lanes of the last row.
 // A strip need not end at a plane boundary: the column sums restart wherever a plane starts.
 //
-// Who takes which strip.  Planes of at most 128 columns (COOP): one segment per workgroup, its strips
-// dealt to the twelve wavefronts in turn, so the work divides evenly whatever the plane size.  A strip
+// Who takes which strip.  Planes of at most 128 lanes per row (COOP: 128 columns, 256 with two columns per lane):
+// one segment per workgroup, its strips dealt to the sixteen wavefronts in turn, so the work divides evenly whatever the plane size.  A strip
 // that starts inside a plane needs that plane's column sums over the rows above: every strip adds up
 // the residuals of its last (unfinished) plane column by column, which after a prefix over the
 // columns is what the strip contributes, adds what it received itself if the plane started earlier,
