@@ -356,7 +356,7 @@ int launch_encode(comet_ctx *ctx, const uint16_t *codes, uint64_t n, uint32_t nb
 
 void encode_geometry(const comet_ctx *ctx, uint64_t n_chunks, uint32_t *seg_chunks, uint32_t *n_seg) {
     // one segment of consecutive chunks per workgroup: about as many segments as workgroups fit the chip
-    const uint64_t want = (uint64_t)ctx->num_cu * 8u;
+    const uint64_t want = (uint64_t)ctx->num_cu * 6u;
     uint64_t seg = (n_chunks + want - 1) / want;
     seg = (seg + 3u) & ~(uint64_t)3u;
     if (seg < 4u) seg = 4u;
