@@ -438,7 +438,7 @@ int comet_create(comet_ctx **out, uint64_t max_elems, uint32_t max_nbins) {
     // scan descriptors: one per segment of the quantise / encode kernels (worst case over chunk sizes)
     const uint64_t tiles_q = (uint64_t)c->num_cu * 16u + 16u;
     const uint64_t tiles_e = (uint64_t)c->num_cu * 8u + max_elems / 64u / kEncSegChunksMax + 16u;
-    const ZeroLayout z = zero_layout(kMaxBins, kMaxBins, tiles_q, tiles_e);   // the partial histograms take 256 KB whatever the alphabet
+    const ZeroLayout z = zero_layout(kMaxBins, kMaxBins, tiles_q, tiles_e);   // the partial histograms take up to 2 MB
     c->zero_cap = z.bytes;
     const uint64_t state_bytes = offsetof(DevState, ctl) + z.bytes;
     if ((e = hipMalloc((void **)&c->state, state_bytes)) != hipSuccess) return fail(COMET_ERR_NOMEM);

@@ -58,7 +58,7 @@ constexpr uint32_t kQuantStaticLds = 8448; // static LDS of k_quantize_rows (the
 constexpr uint32_t kLdsPerCu = 160u * 1024u;
 constexpr uint32_t kQuantRunsPerSimdSingle = 4;   //   ... of the single-pass compression (all of them resident at once)
 constexpr uint32_t kQuantHistCopiesMax = 32;        // partial histograms the workgroups spread their flushes over
-constexpr uint32_t kQuantHistPartsWords = 65536;    // all copies together have at most this many entries
+constexpr uint32_t kQuantHistPartsWords = 8u * 65536u;    // all copies together have at most this many entries (2 MB: eight copies of the largest alphabet)
 // VEC adjacent columns per lane (2 needs an even W and 8-byte aligned input), NSEG segments of 64 lanes per row,
 // MULTI: several rows per step
 // REUSE: code book reuse: escapes follow the given length table, no histogram (FULLWIN is then true and unused)

@@ -217,7 +217,10 @@ __device__ inline uint32_t sweep_rows(const QuantArgs &a, uint32_t row_lo, uint3
     };
     auto flush_oow = [&]() {                                     // the listed codes -> global histogram
         wave_lds_fence();
-        for (uint32_t i = lane; i < cnt.oow_held; i += kWave) atomicAdd(&a.hist[cnt.oow_list[i]], 1u);
+        // (into the workgroup's partial histogram: the codes just outside the window are few and frequent, and all
+        // workgroups adding to one copy of them queue up on a handful of cache lines)
+        uint32_t *part = a.hist_parts + (size_t)(blockIdx.x % a.hist_copies) * a.nbins;
+        for (uint32_t i = lane; i < cnt.oow_held; i += kWave) atomicAdd(&part[cnt.oow_list[i]], 1u);
         wave_lds_fence();
         cnt.oow_held = 0;
     };
