@@ -427,18 +427,41 @@ __device__ inline void codebook_body(const BookArgs &a, uint32_t m, uint64_t *ke
         __syncthreads();
     }
     // ---- 4. depth of every leaf: walk to the root (node m-2) ----
-    for (uint32_t i = tid; i < m; i += kBookBlock) {
-        const uint32_t sym = (uint32_t)(keys[i] & 0xffffu);
-        uint32_t depth = 1;
-        if (m >= 2) {
-            uint32_t p = leaf_parent[i];
-            const uint32_t root = m - 2;
-            while (p != root && depth < 66u) { p = int_parent[p]; ++depth; }
+    // (four leaves per thread at a time: a walk is a chain of dependent loads, in global memory for a large
+    // alphabet, and four chains wait side by side)
+    constexpr uint32_t kWalks = 4;
+    for (uint32_t i0 = tid; i0 < m; i0 += kWalks * kBookBlock) {
+        uint32_t p[kWalks], depth[kWalks];
+        const uint32_t root = m >= 2 ? m - 2 : 0u;
+#pragma unroll
+        for (uint32_t k = 0; k < kWalks; ++k) {
+            const uint32_t i = i0 + k * kBookBlock;
+            depth[k] = 1;
+            p[k] = (m >= 2 && i < m) ? leaf_parent[i] : root;
         }
-        keys[i] = ((uint64_t)depth << 16) | sym;     // re-keyed for the canonical order
-        atomicAdd(&s_cnt[depth > 64 ? 64 : depth], 1u);
-        atomicMax(s_maxlen, depth);
-        if (by_symbol) s_depth[sym] = (uint8_t)(depth > 64 ? 64 : depth);
+        bool more = true;
+        while (more) {
+            more = false;
+#pragma unroll
+            for (uint32_t k = 0; k < kWalks; ++k) {
+                const bool go = p[k] != root && depth[k] < 66u;
+                const uint32_t q = go ? int_parent[p[k]] : root;
+                p[k] = go ? q : p[k];
+                depth[k] += go ? 1u : 0u;
+                more = more || go;
+            }
+        }
+#pragma unroll
+        for (uint32_t k = 0; k < kWalks; ++k) {
+            const uint32_t i = i0 + k * kBookBlock;
+            if (i < m) {
+                const uint32_t sym = (uint32_t)(keys[i] & 0xffffu);
+                keys[i] = ((uint64_t)depth[k] << 16) | sym;     // re-keyed for the canonical order
+                atomicAdd(&s_cnt[depth[k] > 64 ? 64 : depth[k]], 1u);
+                atomicMax(s_maxlen, depth[k]);
+                if (by_symbol) s_depth[sym] = (uint8_t)(depth[k] > 64 ? 64 : depth[k]);
+            }
+        }
     }
     __syncthreads();
     }   // !given
