@@ -156,9 +156,31 @@ __device__ inline uint32_t count_below_wave(const uint64_t *arr, uint32_t begin,
     return cnt;
 }
 
+// The same count by a whole workgroup of kBookBlock threads (every thread must call; arrays in global memory):
+// every thread probes one entry per step, kBookBlock entries evenly spread over what is left of the range, so
+// two steps (two memory round trips) settle a range of a million entries, where the galloping search of one
+// thread takes two dependent loads per bit of the answer.
+__device__ inline uint32_t count_below_block(const uint64_t *arr, uint32_t begin, uint32_t end, uint64_t t, int shift) {
+    uint32_t lo = begin, hi = end;                   // the first entry above t lies in [lo, hi]
+    while (true) {
+        const uint32_t n = hi - lo;
+        if (n == 0u) return lo - begin;
+        const uint32_t stride = (n + (uint32_t)kBookBlock - 1u) / (uint32_t)kBookBlock;
+        const uint32_t p = lo + (threadIdx.x + 1u) * stride - 1u;         // my probe: the last entry of my piece
+        const bool ok = p < hi && (arr[p] >> shift) <= t;                 // (the probes that pass are the first ones)
+        const uint32_t c = (uint32_t)__syncthreads_count(ok ? 1 : 0);
+        const uint32_t new_lo = lo + c * stride;
+        if (stride == 1u) return new_lo - begin;
+        const uint32_t next_probe = new_lo + stride - 1u;                 // the first probe that failed, or beyond the range
+        hi = next_probe < hi ? next_probe : hi;
+        lo = new_lo;
+    }
+}
+
 // One round, control part: how many leaves (nl) and internal nodes (nn) are merged now.  Uniform
-// over the callers; WAVE: the counts are taken by a whole wavefront probing 64 entries per step.
-template <bool WAVE>
+// over the callers; WAVE: the counts are taken by a whole wavefront probing 64 entries per step;
+// BLOCK: by the whole workgroup (every thread of it calls).
+template <bool WAVE, bool BLOCK = false>
 __device__ inline void round_control(const uint64_t *keys, const uint64_t *iw, uint32_t m, uint32_t li, uint32_t ii, uint32_t ni,
                                      uint32_t *nl_out, uint32_t *nn_out) {
     const uint64_t inf = ~0ull;
@@ -168,8 +190,8 @@ __device__ inline void round_control(const uint64_t *keys, const uint64_t *iw, u
     if (a0 <= b0) { s0 = a0; s1 = (a1 <= b0) ? a1 : b0; }
     else { s0 = b0; s1 = (a0 <= b1) ? a0 : b1; }
     const uint64_t t = s0 + s1;
-    uint32_t nl = WAVE ? count_below_wave(keys, li, m, t, 16) : count_below(keys, li, m, t, 16, false);
-    uint32_t nn = WAVE ? count_below_wave(iw, ii, ni, t, 0) : count_below(iw, ii, ni, t, 0, false);
+    uint32_t nl = BLOCK ? count_below_block(keys, li, m, t, 16) : (WAVE ? count_below_wave(keys, li, m, t, 16) : count_below(keys, li, m, t, 16, false));
+    uint32_t nn = BLOCK ? count_below_block(iw, ii, ni, t, 0) : (WAVE ? count_below_wave(iw, ii, ni, t, 0) : count_below(iw, ii, ni, t, 0, false));
     if ((nl + nn) & 1u) {
         const uint64_t la = nl ? keys[li + nl - 1] >> 16 : 0, lb = nn ? iw[ii + nn - 1] : 0;
         if (nn && (!nl || la <= lb)) --nn; else --nl;
@@ -178,8 +200,42 @@ __device__ inline void round_control(const uint64_t *keys, const uint64_t *iw, u
 }
 
 // One round, the items: lane `lane` of `nlanes` takes every nlanes-th of the nl + nn items.
+// ITEMS: items a lane works on side by side (arrays in global memory: every item is a chain of dependent loads).
+template <uint32_t ITEMS = 1>
 __device__ inline void round_items(const uint64_t *keys, uint64_t *iw, uint32_t *leaf_parent, uint32_t *int_parent,
                                    uint32_t li, uint32_t ii, uint32_t ni, uint32_t nl, uint32_t nn, uint32_t lane, uint32_t nlanes) {
+    if (ITEMS > 1) {
+        for (uint32_t idx0 = lane; idx0 < nl + nn; idx0 += ITEMS * nlanes) {
+            uint64_t w[ITEMS];
+            bool on[ITEMS], leaf[ITEMS];
+            // the item's weight, then its rank among the items of the other kind (both loops: ITEMS loads in flight)
+#pragma unroll
+            for (uint32_t k = 0; k < ITEMS; ++k) {
+                const uint32_t idx = idx0 + k * nlanes;
+                on[k] = idx < nl + nn;
+                leaf[k] = idx < nl;
+                w[k] = !on[k] ? 0ull : (leaf[k] ? keys[li + idx] >> 16 : iw[ii + (idx - nl)]);
+            }
+            uint32_t rank[ITEMS];
+#pragma unroll
+            for (uint32_t k = 0; k < ITEMS; ++k) {
+                const uint32_t idx = idx0 + k * nlanes;
+                rank[k] = 0;
+                if (on[k]) rank[k] = leaf[k] ? idx + count_below(iw, ii, ii + nn, w[k], 0, true)
+                                             : (idx - nl) + count_below(keys, li, li + nl, w[k], 16, false);
+            }
+#pragma unroll
+            for (uint32_t k = 0; k < ITEMS; ++k) {
+                const uint32_t idx = idx0 + k * nlanes;
+                if (on[k]) {
+                    if (leaf[k]) leaf_parent[li + idx] = ni + (rank[k] >> 1);
+                    else int_parent[ii + (idx - nl)] = ni + (rank[k] >> 1);
+                    atomicAdd(reinterpret_cast<unsigned long long *>(&iw[ni + (rank[k] >> 1)]), (unsigned long long)w[k]);
+                }
+            }
+        }
+        return;
+    }
     for (uint32_t idx = lane; idx < nl + nn; idx += nlanes) {
         uint64_t w;
         uint32_t rank;
@@ -205,8 +261,8 @@ __device__ inline void huffman_rounds(const uint64_t *keys, uint64_t *iw, uint32
     li = 0; ii = 0; ni = 0;
     while ((m - li) + (ni - ii) > stop) {
         uint32_t nl, nn;
-        round_control<WAVE>(keys, iw, m, li, ii, ni, &nl, &nn);
-        round_items(keys, iw, leaf_parent, int_parent, li, ii, ni, nl, nn, lane, nlanes);
+        round_control<WAVE, !WAVE>(keys, iw, m, li, ii, ni, &nl, &nn);     // (not WAVE: the whole workgroup is here)
+        round_items<WAVE ? 1u : 4u>(keys, iw, leaf_parent, int_parent, li, ii, ni, nl, nn, lane, nlanes);
         sync();
         li += nl; ii += nn; ni += (nl + nn) >> 1;
     }
