@@ -319,6 +319,7 @@ int launch_encode(comet_ctx *ctx, const uint16_t *codes, uint64_t n, uint32_t nb
                   hipStream_t st, uint32_t *chunk_off, uint8_t *container, uint64_t capacity,
                   uint32_t *payload, uint64_t payload_cap, uint64_t *payload_words_out, uint64_t *desc) {
     EncodeArgs a{};
+    a.len8 = container ? container + kHeaderBytes : nullptr;      // the length section k_codebook has written
     a.codes = codes; a.n = n; a.chunk_syms = chunk_syms;
     a.zero_pair = ctx->zero_chunks ? ((nbins / 2u) << 16) | (nbins / 2u) : 0u;
     a.n_chunks = (uint32_t)((n + chunk_syms - 1) / chunk_syms);
@@ -328,7 +329,11 @@ int launch_encode(comet_ctx *ctx, const uint16_t *codes, uint64_t n, uint32_t nb
     uint32_t seg, grid;
     encode_geometry(ctx, a.n_chunks, &seg, &grid);
     a.seg_chunks = seg;
-    const size_t lds_count = ((size_t)a.tbl_n + 1u) * 8u + (size_t)seg * 4u;       // table, a zero entry, word counts
+    // table and a zero entry (or, for a large alphabet, the lengths of enc_len_window() symbols: whichever is larger), word counts
+    const size_t lenw = enc_len_window(nbins) + 8u;
+    const size_t tbl_bytes = ((size_t)a.tbl_n + 1u) * 8u;
+    a.tbl_room = (uint32_t)((a.tbl_n < nbins && lenw > tbl_bytes ? lenw : tbl_bytes) + 7u) & ~7u;
+    const size_t lds_count = (size_t)a.tbl_room + (size_t)seg * 4u;
     const size_t lds_pack = ((size_t)a.tbl_n + 1u) * 8u + (size_t)(kEncBlock / kWave) * kEncBufWords * 4u;
     a.chunk_off = chunk_off; a.container = container; a.capacity = capacity;
     a.payload = payload; a.payload_cap_words = payload_cap; a.payload_words_out = payload_words_out;

@@ -39,7 +39,7 @@ struct Control {
     uint32_t n_active;
     uint32_t max_len;
     uint32_t enc_in_window;  // k_codebook: every symbol with a code word, but for the escape symbol, lies in the part of the encode table the encoders cache in LDS
-    uint32_t pad_;
+    uint32_t len_in_window;  // k_codebook: ... in the (wider) part whose lengths the count kernel caches
 };
 
 // Orders the LDS accesses of the lanes of one wavefront (writes before, reads after).  Only the

@@ -38,6 +38,18 @@ struct TableView {
     }
 };
 
+// The code lengths alone, one byte each, of the symbols [lo, lo + n) in LDS; behind them the escape symbol's.  For the
+// count kernel when every symbol that occurs lies in that range (Control::len_in_window): eight times the symbols of the
+// encode table's cached part in the same LDS, and no look-up in global memory.
+struct LengthView {
+    const uint8_t *lds;
+    uint32_t lo, n;
+    __device__ inline uint32_t length(uint32_t code) const {
+        const uint32_t i = code - lo;                 // (a code below lo wraps to a large number)
+        return lds[i < n ? i : n];
+    }
+};
+
 // inclusive prefix sum inside groups of LPC = 16, 32 or 64 adjacent lanes (DPP, no LDS)
 template <int LPC>
 __device__ inline uint32_t group_incl_scan(uint32_t v) {

@@ -109,6 +109,10 @@ __global__ void k_book_merge(const uint64_t *src, uint64_t *dst, uint32_t run, c
 // ---- encode -------------------------------------------------------------------
 constexpr int kEncBlock = 256;             // four wavefronts, each encodes 256 symbols per step cooperatively
 constexpr uint32_t kEncTableMax = 2048;    // table entries cached in LDS
+// Code lengths (one byte each) the count kernel caches in LDS instead of part of the encode table, if every symbol that
+// occurs lies among them: 16384 around the centre (the room of the table's cached part), 32768 for the largest alphabets
+// (whose symbols spread wider; twice the LDS, which costs the smaller ones more than it gains them).
+__host__ __device__ inline uint32_t enc_len_window(uint32_t nbins) { return nbins <= 16384u ? nbins : (nbins <= 32768u ? 16384u : 32768u); }
 constexpr uint32_t kEncSegChunksMax = 4096;   // chunks per workgroup segment (their word counts live in LDS)
 
 struct EncodeArgs {
@@ -118,8 +122,10 @@ struct EncodeArgs {
     uint32_t n_chunks;
     uint32_t seg_chunks;       // chunks per segment (one segment per workgroup)
     const uint64_t *enc;
+    const uint8_t *len8;       // device u8[nbins]: the code lengths alone (the container's length section), or null
     uint32_t nbins;
     uint32_t tbl_lo, tbl_n;    // table entries [tbl_lo, tbl_lo + tbl_n) are cached in LDS
+    uint32_t tbl_room;         // count kernel: bytes of LDS in front of the word counts (the table, or the lengths of a large alphabet)
     uint32_t *chunk_off;
     uint8_t *container;        // product path: payload position comes from ctl->off_payload
     uint64_t capacity;

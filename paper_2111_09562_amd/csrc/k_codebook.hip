@@ -652,14 +652,16 @@ __global__ __launch_bounds__(kBookBlock) void k_codebook(BookArgs a) {
     // (and: does every symbol that occurs, but for the escape symbol, lie in the part of the encode table that the
     // encoders keep in LDS?)
     const uint32_t win_n = nbins < kEncTableMax ? nbins : kEncTableMax, win_lo = (nbins - win_n) / 2u;
+    const uint32_t lenw_n = enc_len_window(nbins), lenw_lo = (nbins - lenw_n) / 2u;
     int outside = 0;
     for (uint32_t base = 0; base < nbins; base += kBookBlock) {
         const uint32_t s = base + tid;
         const bool occurs = (s < nbins) && (a.given_len ? a.given_len[s] != 0 : a.hist[s] != 0u);
         m += __syncthreads_count(occurs);
         outside |= (occurs && s != 0u && s - win_lo >= win_n) ? 1 : 0;
+        outside |= (occurs && s != 0u && s - lenw_lo >= lenw_n) ? 2 : 0;
     }
-    outside = __syncthreads_or(outside);
+    outside = (__syncthreads_or(outside & 1) ? 1 : 0) | (__syncthreads_or(outside & 2) ? 2 : 0);
     if (m <= kBookLdsSyms)
         codebook_body<true>(a, m, s_keys, s_iw, s_lp, s_ip, s_keys, s_iw, s_lp, s_ip, s_x, s_part, s_cnt, s_first, s_findex, &s_maxlen, s_wc);
     else
@@ -670,7 +672,8 @@ __global__ __launch_bounds__(kBookBlock) void k_codebook(BookArgs a) {
     if (tid == 0) {
         a.ctl->n_active = m;
         a.ctl->max_len = s_maxlen;
-        a.ctl->enc_in_window = outside ? 0u : 1u;
+        a.ctl->enc_in_window = (outside & 1) ? 0u : 1u;
+        a.ctl->len_in_window = (outside & 2) ? 0u : 1u;
         if (a.hdr) {
             Header h = a.proto;
             h.n_active = m;

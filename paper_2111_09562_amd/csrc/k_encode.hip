@@ -66,14 +66,23 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_count(EncodeArgs a) {
     constexpr int CPS = 256 / S;                     // chunks per wavefront step
     extern __shared__ uint64_t s_dyn_enc[];
     uint64_t *s_tbl = s_dyn_enc;                                                // a.tbl_n entries and a zero entry
-    uint32_t *s_cnt = reinterpret_cast<uint32_t *>(s_dyn_enc + a.tbl_n + 1u);   // a.seg_chunks word counts
+    uint32_t *s_cnt = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(s_dyn_enc) + a.tbl_room);   // a.seg_chunks word counts
     __shared__ uint32_t s_part32[kEncBlock / kWave];
 
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = (uint32_t)lane_id();
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / kWave));   // a scalar: what derives from it stays scalar
     // (behind the cached entries: a zero entry, or the escape symbol's if part of the table is cached)
-    for (uint32_t i = tid; i <= a.tbl_n; i += kEncBlock) s_tbl[i] = (i < a.tbl_n) ? a.enc[a.tbl_lo + i] : (FULLTBL ? 0ull : a.enc[0]);
+    // Part of the table cached, symbols that occur outside it, but all of them inside the wider range of lengths
+    // alone: those are cached instead (in the room of the entries; the launch has made it large enough for either).
+    const bool lengths_only = !FULLTBL && a.len8 && a.tbl_n == kEncTableMax && !a.ctl->enc_in_window && a.ctl->len_in_window;
+    const uint32_t lenw_n = enc_len_window(a.nbins), lenw_lo = (a.nbins - lenw_n) / 2u;
+    if (lengths_only) {
+        uint8_t *s_len8 = reinterpret_cast<uint8_t *>(s_tbl);
+        for (uint32_t i = tid; i <= lenw_n; i += kEncBlock) s_len8[i] = (i < lenw_n) ? a.len8[lenw_lo + i] : a.len8[0];
+    } else {
+        for (uint32_t i = tid; i <= a.tbl_n; i += kEncBlock) s_tbl[i] = (i < a.tbl_n) ? a.enc[a.tbl_lo + i] : (FULLTBL ? 0ull : a.enc[0]);
+    }
     __syncthreads();
 
     const uint32_t seg = blockIdx.x;
@@ -114,6 +123,7 @@ __global__ __launch_bounds__(kEncBlock) void k_encode_count(EncodeArgs a) {
     };
     if (FULLTBL) sweep(TableView<1>{s_tbl, a.enc, a.tbl_lo, a.tbl_n, a.nbins});
     else if (a.ctl->enc_in_window) sweep(TableView<2>{s_tbl, a.enc, a.tbl_lo, a.tbl_n, a.nbins});
+    else if (lengths_only) sweep(LengthView{reinterpret_cast<const uint8_t *>(s_tbl), lenw_lo, lenw_n});
     else sweep(TableView<0>{s_tbl, a.enc, a.tbl_lo, a.tbl_n, a.nbins});
     __syncthreads();
 
